@@ -1,0 +1,221 @@
+"""CPU oracle: an unfused fp64 interpreter for fusion patterns.
+
+TEST INFRASTRUCTURE ONLY.  This file is the reference the HIP path is checked
+against.  It may be imported by tests/, by the smoke entry and by the bench's
+cpu_baseline leg, and by nothing else; it shares no code with the HIP path and
+never imports it.
+
+What it computes
+----------------
+The paper's method (kernel fusion without shape values, Sections 2 and 4.3)
+reaches *exactly* the result of running the ops of a pattern one after the
+other; fusion changes where intermediates live, not what they are.  The oracle
+is therefore that plain definition written out: it walks the op list in order,
+one op at a time, and materialises every intermediate as a full numpy array in
+float64.  Broadcasts are made explicit (a real, tiled copy), reductions are
+numpy reductions over one axis.  There is no blocking, fusion or reordering.
+
+The paper names ops only by example (Add, Sub, Mul, Transpose, Slice, Pad,
+Broadcast, Split; Sections 4.1, 4.2.1, 4.3) and gives them their HLO meaning;
+the op set here is the element-wise / broadcast / cast / select / reduce family
+with those standard meanings:
+
+* unary, binary, compare  : numpy ufuncs on float64 (int64 for integer values)
+* rsqrt = 1/sqrt, rcp = 1/x, sigmoid = 1/(1+exp(-x)), erf = the error function
+* cast to a float type    : identity (values are not rounded to the storage type;
+                            the comparator that uses the oracle absorbs the final
+                            rounding); cast to an integer type truncates toward zero;
+                            cast to bool is ``x != 0``
+* select(p, a, b)         : a where p != 0, else b
+* broadcast               : HLO broadcast_in_dim
+* reduce_{sum,max,min}    : over exactly one axis, the axis is dropped
+* reduce_argmax           : lowest index among the maxima, int64
+* dim_size                : the runtime size of a symbolic dimension, as a scalar
+
+Inputs stored as f16 / bf16 are converted to float64 by the caller (every such
+value is exactly representable); the oracle itself only sees numpy arrays.
+"""
+from __future__ import annotations
+
+from typing import Dict, List, Sequence, Tuple
+
+import numpy as np
+from scipy import special as _sp
+
+
+class OracleError(ValueError):
+    pass
+
+
+_FLOAT = ("f32", "f16", "bf16")
+_INT = ("i32", "i64")
+
+
+def _as_dtype(x: np.ndarray, dtype: str) -> np.ndarray:
+    """Value conversion performed by a ``cast`` op (see module docstring)."""
+    if dtype in _FLOAT:
+        return x.astype(np.float64)
+    if dtype in _INT:
+        return np.trunc(x.astype(np.float64)).astype(np.int64)
+    if dtype == "bool":
+        return x != 0
+    raise OracleError(f"unknown dtype {dtype}")
+
+
+def _broadcast_in_dim(x: np.ndarray, out_shape: Tuple[int, ...], axis_map: Sequence[int]) -> np.ndarray:
+    if len(axis_map) != x.ndim:
+        raise OracleError("broadcast: axis_map length != operand rank")
+    if any(b <= a for a, b in zip(axis_map, axis_map[1:])):
+        raise OracleError("broadcast: axis_map must be strictly increasing")
+    shape = [1] * len(out_shape)
+    for k, a in enumerate(axis_map):
+        if x.shape[k] != out_shape[a] and x.shape[k] != 1:
+            raise OracleError("broadcast: operand dim neither equal to result dim nor 1")
+        shape[a] = x.shape[k]
+    # explicit tiling: a real copy of the operand repeated along the new axes
+    return np.broadcast_to(x.reshape(shape), out_shape).copy()
+
+
+_UNARY = {
+    "neg": lambda x: -x,
+    "abs": np.abs,
+    "exp": np.exp,
+    "log": np.log,
+    "tanh": np.tanh,
+    "sqrt": np.sqrt,
+    "rsqrt": lambda x: 1.0 / np.sqrt(x),
+    "rcp": lambda x: 1.0 / x,
+    "sigmoid": lambda x: 1.0 / (1.0 + np.exp(-x)),
+    "erf": _sp.erf,
+}
+
+
+def _int_div(a, b):
+    # C-style truncating division for integer values
+    q = np.abs(a) // np.abs(b)
+    return np.where((a < 0) != (b < 0), -q, q)
+
+
+_BINARY = {
+    "add": np.add,
+    "sub": np.subtract,
+    "mul": np.multiply,
+    "div": lambda a, b: _int_div(a, b) if a.dtype.kind == "i" else a / b,
+    "max": np.maximum,
+    "min": np.minimum,
+    "pow": np.power,
+}
+
+_COMPARE = {
+    "lt": np.less, "le": np.less_equal, "gt": np.greater,
+    "ge": np.greater_equal, "eq": np.equal, "ne": np.not_equal,
+}
+
+
+def _same_shape(*xs: np.ndarray) -> None:
+    """Element-wise ops take operands of one shape (or rank-0 scalars): numpy's
+    implicit broadcasting between two non-scalar shapes is not part of the op set."""
+    shapes = {x.shape for x in xs if x.ndim > 0}
+    if len(shapes) > 1:
+        raise OracleError(f"element-wise operands differ in shape: {sorted(shapes)}")
+
+
+def _common(a: np.ndarray, b: np.ndarray):
+    """Bring two operands to one numeric kind (bool < int64 < float64)."""
+    _same_shape(a, b)
+    if a.dtype == b.dtype:
+        return a, b
+    if a.dtype.kind == "f" or b.dtype.kind == "f":
+        return a.astype(np.float64), b.astype(np.float64)
+    return a.astype(np.int64), b.astype(np.int64)
+
+
+def run(pattern, dims: Sequence[int], inputs: Sequence[np.ndarray]):
+    """Evaluate ``pattern`` at runtime sizes ``dims`` on ``inputs``.
+
+    ``inputs[k]`` is the array for the k-th ``param`` op.  Returns
+    ``(outputs, values)``: the list of output arrays in ``output``-op order and
+    the dict op-index -> materialised value for *every* op (all intermediates).
+    Every op's result shape is checked against the shape the pattern declares
+    for it at these ``dims``; a mismatch raises OracleError.
+    """
+    with np.errstate(over="ignore", under="ignore", invalid="ignore", divide="ignore"):
+        return _run(pattern, dims, inputs)
+
+
+def _run(pattern, dims, inputs):
+    dims = [int(d) for d in dims]
+    if len(dims) != pattern.n_dims:
+        raise OracleError(f"expected {pattern.n_dims} runtime dims, got {len(dims)}")
+    vals: Dict[int, np.ndarray] = {}
+    outs: List[np.ndarray] = []
+    next_param = 0
+    for idx, op in enumerate(pattern.ops):
+        want = tuple(dims[d] if d >= 0 else -d for d in op.dims)
+        oc = op.opcode
+        if oc == "param":
+            x = np.asarray(inputs[next_param])
+            next_param += 1
+            if op.dtype in _FLOAT:
+                v = x.astype(np.float64)
+            elif op.dtype in _INT:
+                v = x.astype(np.int64)
+            else:
+                v = x != 0
+            if v.shape != want:
+                raise OracleError(f"param {idx}: got shape {v.shape}, pattern says {want}")
+        elif oc == "const":
+            v = _as_dtype(np.asarray(op.fconst, dtype=np.float64), op.dtype)
+        elif oc == "dim_size":
+            v = _as_dtype(np.asarray(float(dims[op.axis_map[0]])), op.dtype)
+        elif oc in _UNARY:
+            v = _UNARY[oc](vals[op.ins[0]])
+        elif oc in _BINARY:
+            a, b = _common(vals[op.ins[0]], vals[op.ins[1]])
+            v = _BINARY[oc](a, b)
+        elif oc in _COMPARE:
+            a, b = _common(vals[op.ins[0]], vals[op.ins[1]])
+            v = _COMPARE[oc](a, b)
+        elif oc == "select":
+            a, b = _common(vals[op.ins[1]], vals[op.ins[2]])
+            _same_shape(vals[op.ins[0]], a, b)
+            v = np.where(vals[op.ins[0]] != 0, a, b)
+        elif oc == "cast":
+            v = _as_dtype(vals[op.ins[0]], op.dtype)
+        elif oc == "broadcast":
+            v = _broadcast_in_dim(vals[op.ins[0]], want, op.axis_map)
+        elif oc in ("reduce_sum", "reduce_max", "reduce_min", "reduce_argmax"):
+            x = vals[op.ins[0]]
+            ax = op.axis_map[0]
+            if not 0 <= ax < x.ndim:
+                raise OracleError(f"op {idx}: reduce axis {ax} out of range")
+            if x.shape[ax] == 0:
+                raise OracleError(f"op {idx}: reduction over an empty axis")
+            if oc == "reduce_sum":
+                v = np.sum(x, axis=ax)
+            elif oc == "reduce_max":
+                v = np.max(x, axis=ax)
+            elif oc == "reduce_min":
+                v = np.min(x, axis=ax)
+            else:
+                v = np.argmax(x, axis=ax).astype(np.int64)  # first occurrence
+        elif oc == "output":
+            v = vals[op.ins[0]]
+            outs.append(v)
+        else:
+            raise OracleError(f"op {idx}: unknown opcode {oc}")
+        v = np.asarray(v)
+        if v.ndim > 0 or len(want) > 0:
+            # rank-0 operands act as scalars inside element-wise ops; anything
+            # else must come out with exactly the declared shape
+            if v.shape != want:
+                if v.ndim == 0:
+                    v = np.full(want, v)
+                else:
+                    raise OracleError(f"op {idx} ({oc}): result shape {v.shape}, pattern says {want}")
+        vals[idx] = v
+    return outs, vals
+
+
+def run_outputs(pattern, dims, inputs):
+    return run(pattern, dims, inputs)[0]

@@ -1,0 +1,381 @@
+"""Pins for the CPU oracle: what the mathematics fixes, independent of the oracle.
+
+Every check compares the oracle with something that is not the oracle:
+Python-scalar loops over ``math`` functions, ``math.fsum`` brute force, explicit
+np.tile / np.repeat constructions, closed forms and invariants, and library
+special cases (torch / scipy in float64).  The paper prints no worked numeric
+example for its kernels, so there are no printed values to match.
+"""
+import itertools
+import math
+
+import numpy as np
+import pytest
+import scipy.special
+import torch
+
+from oracle import OracleError, run
+from workloads import PatternBuilder
+from workloads.configs import (c0_pattern, c1_pattern, c2_pattern, c3_pattern, c4_pattern,
+                               c1_inputs, c4_inputs)
+
+rng = np.random.default_rng(7)
+
+
+def _single(opcode, *arrays, dtype="f32"):
+    """Pattern applying one element-wise op to same-shape rank-1 params."""
+    pb = PatternBuilder()
+    n = pb.dim()
+    ps = [pb.param(dtype, [n]) for _ in arrays]
+    pb.output(pb.op(opcode, *ps))
+    return run(pb.build(), [len(arrays[0])], list(arrays))[0][0]
+
+
+# ---------------------------------------------------------------- per-op pins
+UNARY_REF = {
+    "neg": lambda v: -v, "abs": abs, "exp": math.exp, "log": math.log, "tanh": math.tanh,
+    "sqrt": math.sqrt, "rsqrt": lambda v: 1.0 / math.sqrt(v), "rcp": lambda v: 1.0 / v,
+    "sigmoid": lambda v: 1.0 / (1.0 + math.exp(-v)), "erf": math.erf,
+}
+
+
+@pytest.mark.parametrize("opcode", sorted(UNARY_REF))
+def test_unary_matches_python_math(opcode):
+    x = rng.uniform(0.1, 3.0, 17) if opcode in ("log", "sqrt", "rsqrt", "rcp") else rng.normal(0, 2, 17)
+    got = _single(opcode, x)
+    ref = np.array([UNARY_REF[opcode](float(v)) for v in x])
+    np.testing.assert_allclose(got, ref, rtol=1e-14, atol=0)
+
+
+BINARY_REF = {
+    "add": lambda a, b: a + b, "sub": lambda a, b: a - b, "mul": lambda a, b: a * b,
+    "div": lambda a, b: a / b, "max": max, "min": min, "pow": lambda a, b: a ** b,
+}
+
+
+@pytest.mark.parametrize("opcode", sorted(BINARY_REF))
+def test_binary_matches_python_scalars_and_operand_order(opcode):
+    a = rng.uniform(0.5, 3.0, 13)
+    b = rng.uniform(0.5, 3.0, 13)
+    got = _single(opcode, a, b)
+    ref = np.array([BINARY_REF[opcode](float(u), float(v)) for u, v in zip(a, b)])
+    np.testing.assert_allclose(got, ref, rtol=1e-15, atol=0)
+    if opcode in ("sub", "div", "pow"):          # a swapped operand must show
+        assert not np.allclose(got, np.array([BINARY_REF[opcode](float(v), float(u)) for u, v in zip(a, b)]))
+
+
+@pytest.mark.parametrize("opcode,fn", [("lt", lambda a, b: a < b), ("le", lambda a, b: a <= b),
+                                       ("gt", lambda a, b: a > b), ("ge", lambda a, b: a >= b),
+                                       ("eq", lambda a, b: a == b), ("ne", lambda a, b: a != b)])
+def test_compare(opcode, fn):
+    a = np.array([1.0, 2.0, 3.0, -1.0, 0.0])
+    b = np.array([2.0, 2.0, 1.0, -1.0, -0.0])
+    got = _single(opcode, a, b)
+    assert got.dtype == np.bool_
+    assert got.tolist() == [fn(float(u), float(v)) for u, v in zip(a, b)]
+
+
+def test_select_orientation_and_nonzero_predicate():
+    pb = PatternBuilder()
+    n = pb.dim()
+    p = pb.param("bool", [n])
+    a = pb.param("f32", [n])
+    b = pb.param("f32", [n])
+    pb.output(pb.op("select", p, a, b))
+    out = run(pb.build(), [4], [np.array([1, 0, 7, 0], dtype=np.uint8),
+                                np.array([10., 11., 12., 13.]), np.array([20., 21., 22., 23.])])[0][0]
+    assert out.tolist() == [10., 21., 12., 23.]      # true (any nonzero) picks the first value
+
+
+def test_cast_rules():
+    pb = PatternBuilder()
+    n = pb.dim()
+    x = pb.param("f32", [n])
+    pb.output(pb.cast(x, "i32"))
+    pb.output(pb.cast(x, "bf16"))
+    pb.output(pb.cast(x, "bool"))
+    xs = np.array([-1.7, -0.2, 0.0, 0.9, 2.5, 1.0 + 2.0 ** -20])
+    i, f, b = run(pb.build(), [6], [xs])[0]
+    assert i.tolist() == [-1, 0, 0, 0, 2, 1] and i.dtype == np.int64   # truncation toward zero
+    assert np.array_equal(f, xs)                                         # float casts do not round
+    assert b.tolist() == [True, True, False, True, True, True]
+
+
+def test_const_and_dim_size_scalars():
+    pb = PatternBuilder()
+    t, h = pb.dims(2)
+    x = pb.param("f32", [t, h])
+    y = pb.op("add", pb.op("mul", x, pb.const(3.0)), pb.dim_size(h))
+    z = pb.op("sub", pb.dim_size(t), y, dims=[t, h])
+    pb.output(z)
+    xs = rng.normal(size=(3, 5))
+    out = run(pb.build(), [3, 5], [xs])[0][0]
+    np.testing.assert_allclose(out, 3.0 - (xs * 3.0 + 5.0), rtol=1e-15)
+
+
+# ---------------------------------------------------------------- broadcast
+def test_broadcast_equals_explicit_tiling():
+    pb = PatternBuilder()
+    a, b, c = pb.dims(3)
+    v_b = pb.param("f32", [b])
+    v_ac = pb.param("f32", [a, c])
+    v_a1c = pb.param("f32", [a, pb.static(1), c])
+    pb.output(pb.broadcast(v_b, [a, b, c], [1]))
+    pb.output(pb.broadcast(v_ac, [a, b, c], [0, 2]))
+    pb.output(pb.broadcast(v_a1c, [a, b, c], [0, 1, 2]))
+    A, B, C = 2, 3, 4
+    xb = rng.normal(size=B)
+    xac = rng.normal(size=(A, C))
+    xa1c = rng.normal(size=(A, 1, C))
+    o1, o2, o3 = run(pb.build(), [A, B, C], [xb, xac, xa1c])[0]
+    assert np.array_equal(o1, np.tile(xb.reshape(1, B, 1), (A, 1, C)))
+    assert np.array_equal(o2, np.repeat(xac[:, None, :], B, axis=1))
+    assert np.array_equal(o3, np.repeat(xa1c, B, axis=1))
+    # element-by-element definition
+    for i, j, k in itertools.product(range(A), range(B), range(C)):
+        assert o1[i, j, k] == xb[j] and o2[i, j, k] == xac[i, k] and o3[i, j, k] == xa1c[i, 0, k]
+
+
+def test_broadcast_rejects_mismatch_and_implicit_numpy_broadcast():
+    pb = PatternBuilder()
+    a, b = pb.dims(2)
+    x = pb.param("f32", [a])
+    pb.output(pb.broadcast(x, [a, b], [1]))       # maps axis of size a onto axis of size b
+    with pytest.raises(OracleError):
+        run(pb.build(), [2, 3], [np.zeros(2)])
+    pb = PatternBuilder()
+    a, b = pb.dims(2)
+    x = pb.param("f32", [a, b])
+    y = pb.param("f32", [b])
+    pb.output(pb.op("add", x, y))                 # no explicit broadcast: not allowed
+    with pytest.raises(OracleError):
+        run(pb.build(), [2, 3], [np.zeros((2, 3)), np.zeros(3)])
+
+
+# ---------------------------------------------------------------- reductions
+@pytest.mark.parametrize("axis", [0, 1, 2])
+def test_reductions_equal_brute_force(axis):
+    shape = (3, 4, 5)
+    x = rng.normal(size=shape)
+    pb = PatternBuilder()
+    d = pb.dims(3)
+    p = pb.param("f32", d)
+    for kind in ("sum", "max", "min", "argmax"):
+        pb.output(pb.reduce(kind, p, axis))
+    s, mx, mn, am = run(pb.build(), shape, [x])[0]
+    rest = [r for k, r in enumerate(shape) if k != axis]
+    assert s.shape == tuple(rest)
+    for idx in itertools.product(*[range(r) for r in rest]):
+        sl = list(idx)
+        sl.insert(axis, slice(None))
+        line = [float(v) for v in x[tuple(sl)]]
+        assert abs(s[idx] - math.fsum(line)) <= 1e-15 * sum(abs(v) for v in line)
+        assert mx[idx] == max(line) and mn[idx] == min(line)
+        assert am[idx] == line.index(max(line))
+
+
+def test_reduce_size_one_and_empty_axis():
+    pb = PatternBuilder()
+    d = pb.dims(2)
+    p = pb.param("f32", d)
+    pb.output(pb.reduce("sum", p, 1))
+    x = rng.normal(size=(4, 1))
+    assert np.array_equal(run(pb.build(), [4, 1], [x])[0][0], x[:, 0])
+    with pytest.raises(OracleError):
+        run(pb.build(), [4, 0], [np.zeros((4, 0))])
+    assert run(pb.build(), [0, 3], [np.zeros((0, 3))])[0][0].shape == (0,)
+
+
+def test_argmax_planted_maxima_and_ties():
+    pb = PatternBuilder()
+    d = pb.dims(2)
+    p = pb.param("f32", d)
+    pb.output(pb.reduce("argmax", p, 1))
+    x = rng.normal(size=(6, 9))
+    want = [3, 0, 8, 5, 5, 1]
+    for r, c in enumerate(want):
+        x[r, c] = 10.0
+    x[3, 7] = 10.0      # tie after the planted one: lowest index wins
+    x[4, 2] = 10.0      # tie before the planted one
+    want[4] = 2
+    got = run(pb.build(), [6, 9], [x])[0][0]
+    assert got.dtype == np.int64 and got.tolist() == want
+    assert got.tolist() == np.argmax(x, axis=1).tolist()
+
+
+# ---------------------------------------------------------------- C0 GELU
+def _c0(x, b, r):
+    return run(c0_pattern(), list(x.shape), [x, b, r])[0][0]
+
+
+def test_c0_gelu_closed_forms():
+    H = 5
+    zero = np.zeros(H)
+    u = rng.normal(0, 2, size=(4, H))
+    g = _c0(u, zero, np.zeros_like(u))
+    gm = _c0(-u, zero, np.zeros_like(u))
+    np.testing.assert_allclose(g - gm, u, rtol=0, atol=1e-15)      # tanh is odd => g(u) - g(-u) = u
+    assert _c0(np.zeros((1, H)), zero, np.zeros((1, H))).tolist() == [[0.0] * H]
+    big = np.full((1, H), 12.0)
+    np.testing.assert_allclose(_c0(big, zero, np.zeros((1, H))), big, rtol=1e-15)
+    assert np.all(np.abs(_c0(-big, zero, np.zeros((1, H)))) < 1e-15)
+
+
+def test_c0_matches_scalar_loop_and_torch():
+    T, H = 3, 7
+    x = rng.normal(size=(T, H))
+    b = rng.normal(0, 0.02, size=H)
+    r = rng.normal(size=(T, H))
+    got = _c0(x, b, r)
+    for t in range(T):
+        for h in range(H):
+            u = x[t, h] + b[h]
+            ref = 0.5 * u * (1.0 + math.tanh(math.sqrt(2.0 / math.pi) * (u + 0.044715 * u ** 3))) + r[t, h]
+            assert abs(got[t, h] - ref) < 1e-14
+    ref = torch.nn.functional.gelu(torch.from_numpy(x + b), approximate="tanh").numpy() + r
+    np.testing.assert_allclose(got, ref, rtol=0, atol=1e-14)
+
+
+# ---------------------------------------------------------------- C1 softmax
+def _c1(x, mask):
+    B, NH, S, _ = x.shape
+    return run(c1_pattern(), [B, NH, S], [x, mask])[0][0]
+
+
+def test_c1_rows_sum_to_one_and_shift_invariance():
+    x, mask = [t.double().numpy() for t in c1_inputs([2, 3, 11], seed=5)]
+    y = _c1(x, mask)
+    np.testing.assert_allclose(y.sum(-1), 1.0, rtol=0, atol=1e-12)
+    shift = rng.normal(size=(2, 3, 11, 1)) * 8.0          # x*0.125 shifts by a per-row constant
+    np.testing.assert_allclose(_c1(x + shift, mask), y, rtol=1e-12, atol=1e-15)
+
+
+def test_c1_constant_row_and_masked_equals_textbook_softmax_of_valid_slice():
+    B, NH, S = 2, 2, 9
+    lens = [4, 9]
+    mask = np.zeros((B, 1, 1, S))
+    for b, L in enumerate(lens):
+        mask[b, 0, 0, L:] = -1.0e4
+    y = _c1(np.full((B, NH, S, S), 0.37), mask)
+    for b, L in enumerate(lens):
+        np.testing.assert_allclose(y[b, :, :, :L], 1.0 / L, rtol=1e-15)
+        assert np.all(y[b, :, :, L:] == 0.0)               # exp(-1e4) underflows to exactly 0
+    x = rng.normal(size=(B, NH, S, S))
+    y = _c1(x, mask)
+    for b, L in enumerate(lens):
+        ref = scipy.special.softmax(x[b, :, :, :L] * 0.125, axis=-1)
+        np.testing.assert_allclose(y[b, :, :, :L], ref, rtol=1e-14, atol=0)
+        ref_t = torch.softmax(torch.from_numpy(x[b, :, :, :L] * 0.125), dim=-1).numpy()
+        np.testing.assert_allclose(y[b, :, :, :L], ref_t, rtol=1e-14, atol=0)
+
+
+# ---------------------------------------------------------------- C2 LayerNorm
+def test_c2_pre_affine_moments_and_torch_special_case():
+    T, H = 5, 33
+    pat = c2_pattern()
+    x = rng.normal(size=(T, H))
+    r = rng.normal(size=(T, H))
+    b = rng.normal(size=H)
+    gamma = rng.normal(1, 0.1, size=H)
+    beta = rng.normal(0, 0.1, size=H)
+    outs, vals = run(pat, [T, H], [x, r, b, gamma, beta])
+    # the normalised value n is the operand of the first multiply by broadcast(gamma)
+    n = None
+    for i, op in enumerate(pat.ops):
+        if op.opcode == "mul" and pat.ops[op.ins[1]].opcode == "broadcast" and pat.ops[op.ins[0]].opcode == "mul":
+            n = vals[op.ins[0]]
+    assert n is not None
+    v = x + r + b
+    var = v.var(axis=1)                                  # population variance
+    np.testing.assert_allclose(n.mean(axis=1), 0.0, atol=1e-14)
+    np.testing.assert_allclose(n.var(axis=1), var / (var + 1e-5), rtol=1e-12)
+    np.testing.assert_allclose(n.var(axis=1), 1.0, atol=1e-4)
+    ref = torch.nn.functional.layer_norm(torch.from_numpy(v), (H,), torch.from_numpy(gamma),
+                                         torch.from_numpy(beta), eps=1e-5).numpy()
+    np.testing.assert_allclose(outs[0], ref, rtol=1e-12, atol=1e-13)
+    # gamma = 1, beta = 0, r = b = 0 reduces to the library's plain layer_norm
+    o = run(pat, [T, H], [x, np.zeros((T, H)), np.zeros(H), np.ones(H), np.zeros(H)])[0][0]
+    ref = torch.nn.functional.layer_norm(torch.from_numpy(x), (H,), eps=1e-5).numpy()
+    np.testing.assert_allclose(o, ref, rtol=1e-12, atol=1e-13)
+
+
+def test_c2_constant_row_gives_beta():
+    T, H = 2, 8
+    beta = rng.normal(size=H)
+    o = run(c2_pattern(), [T, H], [np.full((T, H), 0.75), np.zeros((T, H)), np.zeros(H),
+                                   rng.normal(1, 0.1, size=H), beta])[0][0]
+    np.testing.assert_allclose(o, np.tile(beta, (T, 1)), rtol=0, atol=1e-15)
+
+
+# ---------------------------------------------------------------- C3 column reduction
+def test_c3_invariants():
+    pat = c3_pattern()
+    T, C = 37, 6
+    x = rng.uniform(-1, 1, size=(T, C))
+    s, mean, y = run(pat, [T, C], [x])[0]
+    for c in range(C):
+        assert abs(s[c] - math.fsum(float(v) for v in x[:, c])) < 1e-14
+        assert abs(mean[c] - math.fsum(float(v) for v in x[:, c]) / T) < 1e-15
+    np.testing.assert_allclose(y.sum(axis=0), 0.0, atol=1e-9 * T)
+    np.testing.assert_allclose(y, x - x.mean(axis=0, keepdims=True), atol=1e-15)
+    s, mean, y = run(pat, [T, C], [np.ones((T, C))])[0]
+    assert np.all(s == T) and np.all(mean == 1.0) and np.all(y == 0.0)
+    x1 = rng.uniform(-1, 1, size=(1, C))
+    s, mean, y = run(pat, [1, C], [x1])[0]
+    assert np.array_equal(s, x1[0]) and np.array_equal(mean, x1[0]) and np.all(y == 0.0)
+
+
+# ---------------------------------------------------------------- C4 mixed chain
+def _c4(x, mask, bH, cT):
+    T, H = x.shape
+    return run(c4_pattern(), [T, H], [x, mask, bH, cT])
+
+
+def _c4_named(pat, vals):
+    """Pick p (the div), q (the select), s (the row sum), w (rsqrt) out of the intermediates."""
+    named = {}
+    for i, op in enumerate(pat.ops):
+        if op.opcode == "div":
+            named["p"] = vals[i]
+        elif op.opcode == "select":
+            named["q"] = vals[i]
+        elif op.opcode == "reduce_sum":
+            named["s"] = vals[i]
+        elif op.opcode == "rsqrt":
+            named["w"] = vals[i]
+        elif op.opcode == "cast" and op.dtype == "f32":
+            named["x32"] = vals[i]
+    return named
+
+
+def test_c4_invariants():
+    pat = c4_pattern()
+    T, H = 6, 19
+    x, mask, bH, cT = [t.double().numpy() for t in c4_inputs([T, H], seed=3)]
+    mask[0, :] = 0
+    outs, vals = _c4(x, mask, bH, cT)
+    nm = _c4_named(pat, vals)
+    p, q, s, w, x32 = nm["p"], nm["q"], nm["s"], nm["w"], nm["x32"]
+    np.testing.assert_allclose(p.sum(axis=1), 1.0, atol=1e-12)
+    np.testing.assert_allclose(q.sum(axis=1), 1.0 - (p * (mask != 0)).sum(axis=1), atol=1e-12)
+    assert np.all(s >= 1.0) and np.all(s <= H)            # the max term contributes exp(0) = 1
+    np.testing.assert_allclose(w, s ** -0.5, rtol=1e-15)
+    y32 = outs[0]
+    np.testing.assert_allclose(y32 - x32 * w[:, None], q, atol=1e-14)
+    assert np.all(q[mask != 0] == 0.0)                    # true => zeroed
+    np.testing.assert_allclose(y32[mask != 0], (x32 * w[:, None])[mask != 0], rtol=1e-15)
+    # p, q do not depend on the per-row shift cT
+    outs2, vals2 = _c4(x, mask, bH, cT + rng.normal(size=(T, 1)))
+    np.testing.assert_allclose(_c4_named(pat, vals2)["p"], p, rtol=1e-11, atol=1e-16)
+    # mask all false, bH = 0: p is the textbook softmax of x
+    outs3, vals3 = _c4(x, np.zeros_like(mask), np.zeros(H), cT)
+    np.testing.assert_allclose(_c4_named(pat, vals3)["p"], scipy.special.softmax(x, axis=1), rtol=1e-12)
+    # and the whole chain against a direct transcription with scalar loops on one row
+    t = 2
+    b = [x[t, h] + bH[h] + cT[t, 0] for h in range(H)]
+    m = max(b)
+    e = [math.exp(v - m) for v in b]
+    ssum = math.fsum(e)
+    for h in range(H):
+        qh = 0.0 if mask[t, h] else e[h] / ssum
+        assert abs(y32[t, h] - (qh + x[t, h] / math.sqrt(ssum))) < 1e-14
