@@ -1,0 +1,235 @@
+/*
+ * disc.h -- C ABI of the shape-generic fusion-kernel library for MI355X (gfx950).
+ *
+ * The library implements the hot path that the DISC dynamic-shape compiler
+ * (arXiv 2103.05288) speeds up: a fusion pattern of memory-bound ops is
+ * registered ONCE, without shape values, and is then launched at any runtime
+ * shape without recompiling (Section 2, "DISC generates fused kernels adaptive
+ * to any coming shapes"; static rank only).
+ *
+ *   register:  op list + shape constraints  ->  constraint closure (Section
+ *              4.2.1), fusion decision from shape propagation + constraints
+ *              (Section 4.3 "Shape hints collection"), kernel template choice
+ *              (loop fusion / input fusion with a reduce root, Section 4.3
+ *              "Shape-adaptive fusion configuration"), ONE device compile that
+ *              holds every kernel version, and a launch plan with everything
+ *              that does not depend on shape values precomputed.
+ *   launch:    runtime dims -> host shape calculation (Section 4.2.1 "Shape
+ *              calculation"), version + launch-dimension selection (Section
+ *              4.3), kernel launch (Section 4.2.3 "Host-side control").
+ *              No op of the pattern is walked at launch time.
+ *
+ * Conventions
+ *  - Every function returns 0 (DISC_OK) or a negative disc_status; nothing
+ *    throws, aborts or prints.  disc_last_error() returns a context-owned,
+ *    NUL-terminated message that stays valid until the next call on that
+ *    context.
+ *  - A context is not thread-safe: one context per host thread.
+ *  - All tensor pointers passed to disc_launch / disc_plan are DEVICE pointers
+ *    owned by the caller (the paper takes its buffers from the framework's
+ *    cached allocator, Section 4.2.2); tensors are dense, row-major, without
+ *    strides.  `ops`, `cs`, `dims` and the pointer arrays themselves are HOST
+ *    memory, read during the call only.
+ *  - The library never allocates or frees device memory in disc_launch and
+ *    never synchronises: the launch is asynchronous on `hip_stream`.
+ *  - Outputs must not overlap inputs or each other.
+ */
+#ifndef DISC_H_
+#define DISC_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct disc_ctx disc_ctx;
+
+typedef enum {
+  DISC_OK = 0,
+  DISC_ERR_INVALID_ARG = -1, /* null pointer, bad id, n_dims / n_in / n_out mismatch          */
+  DISC_ERR_BAD_PATTERN = -2, /* malformed op list: bad opcode / dtype / rank, forward reference,
+                                contradictory static sizes, rank > DISC_MAX_RANK               */
+  DISC_ERR_UNFUSIBLE = -3,   /* the checker cannot prove that all ops share one iteration space */
+  DISC_ERR_CONSTRAINT = -4,  /* runtime dims contradict a registered equality or a static size  */
+  DISC_ERR_WORKSPACE = -5,   /* workspace missing or smaller than disc_workspace_bytes()        */
+  DISC_ERR_COMPILE = -6,     /* device compile failed; the compiler log is in disc_last_error   */
+  DISC_ERR_HIP = -7,         /* a HIP runtime call failed                                       */
+  DISC_ERR_SHAPE = -8,       /* negative dim, element count overflow, row too long              */
+  DISC_ERR_EMPTY_REDUCE = -9 /* reduction over an axis of runtime size 0                        */
+} disc_status;
+
+enum { DISC_MAX_RANK = 4, DISC_MAX_OPS = 256, DISC_MAX_DIMS = 16 };
+
+typedef enum {
+  DISC_F32 = 0, DISC_F16 = 1, DISC_BF16 = 2, DISC_I32 = 3, DISC_I64 = 4,
+  DISC_BOOL = 5 /* one byte per element, nonzero = true */
+} disc_dtype;
+
+/* Op set: the element-wise / broadcast / cast / select / reduce family with HLO meaning
+ * (the paper names Add, Sub, Mul, Broadcast, ... by example: Sections 4.1, 4.2.1, 4.3). */
+typedef enum {
+  /* leaves */
+  DISC_PARAM = 0,  /* k-th PARAM = k-th input pointer of disc_launch                           */
+  DISC_CONST,      /* rank-0 constant `fconst`                                                 */
+  DISC_DIM_SIZE,   /* rank-0 scalar: runtime size of symbolic dim axis_map[0] (shape value
+                      computed on the host and handed to the device, Section 4.2.1)            */
+  /* unary */
+  DISC_NEG, DISC_ABS, DISC_EXP, DISC_LOG, DISC_TANH, DISC_SQRT, DISC_RSQRT, DISC_RCP,
+  DISC_SIGMOID, DISC_ERF,
+  /* binary */
+  DISC_ADD, DISC_SUB, DISC_MUL, DISC_DIV, DISC_MAX, DISC_MIN, DISC_POW,
+  /* compare: result dtype DISC_BOOL */
+  DISC_LT, DISC_LE, DISC_GT, DISC_GE, DISC_EQ, DISC_NE,
+  DISC_SELECT,     /* in = (pred, on_true, on_false); pred != 0 picks on_true                  */
+  DISC_CAST,       /* to `dtype`; float->int truncates toward zero                             */
+  DISC_BROADCAST,  /* HLO broadcast_in_dim: axis_map[k] = result axis of operand axis k,
+                      strictly increasing; an operand axis of static size 1 may expand         */
+  DISC_REDUCE_SUM, DISC_REDUCE_MAX, DISC_REDUCE_MIN,
+  DISC_REDUCE_ARGMAX, /* lowest index among the maxima; dtype DISC_I32 or DISC_I64             */
+  DISC_OUTPUT,     /* k-th OUTPUT = k-th output pointer; in[0] = the value, same dtype         */
+  DISC_OPCODE_COUNT
+} disc_opcode;
+
+/* One op.  A value is named by the index of the op producing it; `in[]` refers to earlier ops.
+ * dim[i] >= 0 : symbolic dim id (size given at launch as dims[id]);  dim[i] < 0 : static size
+ * -dim[i].  Rank-0 values (CONST, DIM_SIZE) may be operands of element-wise ops as scalars.
+ * Float values are computed in fp32 registers whatever their storage dtype and rounded once,
+ * to nearest even, when stored. */
+typedef struct {
+  int32_t opcode;                  /* disc_opcode                                              */
+  int32_t dtype;                   /* disc_dtype of the result                                 */
+  int32_t in[3];                   /* operand value ids, unused = -1                           */
+  int32_t rank;                    /* 0..DISC_MAX_RANK                                         */
+  int32_t dim[DISC_MAX_RANK];
+  int32_t axis_map[DISC_MAX_RANK]; /* BROADCAST: map; REDUCE_*: [0] = axis; DIM_SIZE: [0] = id */
+  double fconst;                   /* CONST only                                               */
+} disc_op;
+
+/* Caller-supplied shape constraints: what the paper's bridging layer injects when lowering loses
+ * shape information (Section 4.2.1, the Split example). */
+typedef enum {
+  DISC_DIM_EQ = 0,   /* dim a_axis of value a_value == dim b_axis of value b_value             */
+  DISC_NUMEL_EQ = 1  /* values a_value and b_value have the same number of elements            */
+} disc_constraint_kind;
+
+typedef struct {
+  int32_t kind, a_value, a_axis, b_value, b_axis;
+} disc_constraint;
+
+typedef enum {
+  DISC_TEMPLATE_LOOP = 0,       /* loop fusion: element-wise / broadcast chain                  */
+  DISC_TEMPLATE_ROW_REDUCE = 1, /* input fusion, reduce over the innermost axis (+ epilogue)    */
+  DISC_TEMPLATE_COL_REDUCE = 2  /* input fusion, reduce over an outer axis (+ epilogue)         */
+} disc_template;
+
+typedef struct {
+  int32_t template_kind;   /* disc_template                                                    */
+  int32_t n_dims;          /* symbolic dims expected by disc_launch                            */
+  int32_t n_inputs, n_outputs;
+  int32_t compile_events;  /* device compiles spent on this pattern so far (target: 1)         */
+  int32_t n_variants;      /* kernel versions held by the pattern's single module              */
+  int32_t n_phases;        /* row/col reduce: number of dependent reduction levels             */
+  int32_t vec_width;       /* elements per vector access of the vectorised versions            */
+  int32_t n_collapsed;     /* iteration-space rank after merging dims with identical roles     */
+  int32_t n_dim_classes;   /* number of dimension-equality classes after closure               */
+  int32_t dim_class[DISC_MAX_DIMS]; /* class id of every symbolic dim (equal id = proved equal) */
+  double compile_ms;       /* wall time of the one device compile                              */
+} disc_pattern_info_t;
+
+/* Kernel versions (Section 4.3: several versions per pattern, selected on the host). */
+typedef enum {
+  DISC_V_LOOP_VEC = 0,      /* loop fusion, vector accesses, 32-bit slot index                 */
+  DISC_V_LOOP_VEC_I64,      /* ... 64-bit index                                                */
+  DISC_V_LOOP_SCALAR,       /* loop fusion, one element per access                             */
+  DISC_V_LOOP_SCALAR_I64,
+  DISC_V_ROW_REG_VEC,       /* row reduce, row resident in registers of a lane group, vector   */
+  DISC_V_ROW_REG_SCALAR,    /* same, one element per access                                    */
+  DISC_V_ROW_STREAM_VEC,    /* row reduce, one block per row, row re-read per phase            */
+  DISC_V_ROW_STREAM_SCALAR,
+  DISC_V_COL_3STAGE_VEC,    /* column reduce: partial -> combine -> epilogue (<= 3 launches)   */
+  DISC_V_COL_3STAGE_SCALAR,
+  DISC_V_COL_STRIP_VEC,     /* column reduce, one block per column strip, single launch        */
+  DISC_V_COL_STRIP_SCALAR,
+  DISC_V_COUNT
+} disc_variant;
+
+typedef struct {
+  int32_t variant;          /* disc_variant                                                    */
+  int32_t n_launches;       /* device launches this call makes (0 when an output is empty)     */
+  int32_t index_bits;       /* 32 or 64                                                        */
+  int32_t vec_width;        /* elements per access of the chosen version                       */
+  int32_t lanes_per_row;    /* row reduce: lanes that own one row (1..256), else 0             */
+  int32_t slots_per_lane;   /* row reduce: vector slots held per lane, else unroll factor      */
+  int32_t reg_slots;        /* compile-time slot capacity of the chosen instantiation          */
+  uint32_t grid[3][3];      /* per launch                                                      */
+  uint32_t block[3][3];
+  uint32_t lds_bytes[3];
+  int64_t rows, inner;      /* canonical iteration space [rows, inner] ([outer,mid,inner] for
+                               column reduce: rows = outer * mid)                              */
+  int64_t mid;              /* column reduce: reduced extent, else 0                           */
+  int64_t algorithmic_bytes;/* inputs read once + outputs written once at these dims           */
+  size_t workspace_bytes;
+} disc_plan_t;
+
+typedef struct {
+  int64_t patterns_registered;  /* distinct patterns                                           */
+  int64_t pattern_cache_hits;   /* re-registrations answered from the pattern cache            */
+  int64_t compile_events;       /* device compiles, all patterns                               */
+  int64_t launch_calls;         /* successful disc_launch calls                                */
+  int64_t device_launches;      /* kernels enqueued                                            */
+  int64_t variant_count[DISC_V_COUNT];
+  int64_t host_plan_ns;         /* total wall time in shape calculation + selection            */
+  int64_t host_launch_ns;       /* total wall time in disc_launch (plan + enqueue)             */
+} disc_stats_t;
+
+/* Create a context bound to HIP device `hip_device`.  hip_device = -1 makes a host-only context:
+ * registration (checker, classifier, code generation, device compile for gfx950) and disc_plan
+ * work, disc_launch returns DISC_ERR_INVALID_ARG.  The caller frees it with disc_destroy. */
+int disc_create(disc_ctx** out, int hip_device);
+void disc_destroy(disc_ctx* ctx);
+const char* disc_last_error(const disc_ctx* ctx);
+
+/* Register a fusion pattern (op sequence without shape values + constraints) and compile it
+ * once.  `ops` / `cs` are copied.  Registering an identical op list + constraints again returns
+ * the same id without compiling (pattern cache keyed on the op sequence, never on sizes). */
+int disc_register_pattern(disc_ctx* ctx, const disc_op* ops, int n_ops, const disc_constraint* cs,
+                          int n_cs, int32_t* pattern_id_out);
+int disc_pattern_info(disc_ctx* ctx, int32_t id, disc_pattern_info_t* out);
+/* Generated device source of the pattern (context-owned, valid until disc_destroy). */
+const char* disc_pattern_source(disc_ctx* ctx, int32_t id);
+
+/* Bytes of device workspace disc_launch needs at these dims (0 for loop / row patterns). */
+int disc_workspace_bytes(disc_ctx* ctx, int32_t id, const int64_t* dims, int n_dims, size_t* out);
+
+/* Pure host: the runtime flow of one launch without enqueueing anything (shape calculation,
+ * constraint check, version and launch-dimension selection).  `inputs` / `outputs` may be NULL
+ * (then buffers are assumed 16-byte aligned); pointers are only inspected, never dereferenced.
+ * force_variant = -1 lets the host choose. */
+int disc_plan(disc_ctx* ctx, int32_t id, const int64_t* dims, int n_dims, const void* const* inputs,
+              void* const* outputs, int force_variant, disc_plan_t* out);
+
+/* Launch the pattern at runtime sizes dims[0..n_dims).  Asynchronous on `hip_stream` (a
+ * hipStream_t, NULL = default stream).  Any output with zero elements and no reduction over an
+ * empty axis: success, nothing launched. */
+int disc_launch(disc_ctx* ctx, int32_t id, const int64_t* dims, int n_dims,
+                const void* const* inputs, int n_in, void* const* outputs, int n_out,
+                void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Tests only: make the next launches of this context use `variant` when it is legal for the
+ * pattern and the shape (else DISC_ERR_INVALID_ARG at launch); -1 restores host selection. */
+int disc_force_variant(disc_ctx* ctx, int variant);
+
+int disc_get_stats(disc_ctx* ctx, disc_stats_t* out);
+
+/* Measurement helpers (not part of the method): a plain 16-byte-vector device copy used as the
+ * practical bandwidth ceiling, and an empty kernel used as the launch-latency floor.
+ * dst / src are device pointers, 16-byte aligned; bytes a multiple of 16. */
+int disc_util_copy(disc_ctx* ctx, void* dst, const void* src, size_t bytes, void* hip_stream);
+int disc_util_empty_launch(disc_ctx* ctx, void* hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DISC_H_ */

@@ -1,0 +1,729 @@
+// Registration-time analysis of a fusion pattern (host only, no GPU).
+//
+//  1. validate the op list (static rank, Section 2);
+//  2. close the shape constraints: dimension-size equality classes from op semantics and
+//     from the caller, tensor-size equality from the caller (Section 4.2.1);
+//  3. fusion decision: prove from shape propagation + constraints that every op shares one
+//     iteration space, and pick the template (Section 4.3);
+//  4. resolve every value to the root axes it is indexed by (implicit broadcast: a broadcast
+//     is an indexing function on the small operand, never materialised);
+//  5. merge root axes that play identical roles for every operand, so index arithmetic is
+//     done once per group instead of once per axis ("more aggressive index calculation
+//     simplification", Section 4.2.1);
+//  6. write the shape-calculation recipes the launch path evaluates.
+#include <algorithm>
+#include <cstdio>
+#include <cstring>
+#include <set>
+#include <functional>
+
+#include "disc_internal.hpp"
+
+namespace disc {
+
+const char* dtype_ctype(int d) {
+  switch (d) {
+    case DISC_F32: return "float";
+    case DISC_F16: return "_Float16";
+    case DISC_BF16: return "__bf16";
+    case DISC_I32: return "int";
+    case DISC_I64: return "disc::i64";
+    default: return "disc::u8";
+  }
+}
+const char* reg_ctype(RegKind k) {
+  switch (k) {
+    case RK_I32: return "int";
+    case RK_I64: return "disc::i64";
+    case RK_BOOL: return "bool";
+    default: return "float";
+  }
+}
+const char* opcode_name(int oc) {
+  static const char* names[] = {"param", "const", "dim_size", "neg", "abs", "exp", "log", "tanh",
+    "sqrt", "rsqrt", "rcp", "sigmoid", "erf", "add", "sub", "mul", "div", "max", "min", "pow",
+    "lt", "le", "gt", "ge", "eq", "ne", "select", "cast", "broadcast", "reduce_sum", "reduce_max",
+    "reduce_min", "reduce_argmax", "output"};
+  if (oc < 0 || oc >= DISC_OPCODE_COUNT) return "?";
+  return names[oc];
+}
+
+// ------------------------------------------------------------------ DimClasses
+void DimClasses::init(int n_symbolic) {
+  n_sym = n_symbolic;
+  parent.resize(n_sym);
+  static_val.assign(n_sym, -1);
+  for (int i = 0; i < n_sym; ++i) parent[i] = i;
+  static_atom.clear();
+}
+int DimClasses::atom(int32_t dim) {
+  if (dim >= 0) return dim;
+  int64_t sz = -(int64_t)dim;
+  auto it = static_atom.find(sz);
+  if (it != static_atom.end()) return it->second;
+  int a = (int)parent.size();
+  parent.push_back(a);
+  static_val.push_back(sz);
+  static_atom[sz] = a;
+  return a;
+}
+int DimClasses::find(int a) {
+  while (parent[a] != a) {
+    parent[a] = parent[parent[a]];
+    a = parent[a];
+  }
+  return a;
+}
+bool DimClasses::unite(int a, int b, std::string* err) {
+  a = find(a);
+  b = find(b);
+  if (a == b) return true;
+  if (static_val[a] >= 0 && static_val[b] >= 0 && static_val[a] != static_val[b]) {
+    if (err) {
+      char buf[128];
+      snprintf(buf, sizeof buf, "static sizes %lld and %lld would have to be equal",
+               (long long)static_val[a], (long long)static_val[b]);
+      *err = buf;
+    }
+    return false;
+  }
+  // keep the smaller atom id as representative so class ids are stable
+  if (b < a) std::swap(a, b);
+  parent[b] = a;
+  if (static_val[a] < 0) static_val[a] = static_val[b];
+  return true;
+}
+
+namespace {
+
+bool is_unary(int oc) { return oc >= DISC_NEG && oc <= DISC_ERF; }
+bool is_binary(int oc) { return oc >= DISC_ADD && oc <= DISC_POW; }
+bool is_compare(int oc) { return oc >= DISC_LT && oc <= DISC_NE; }
+bool is_reduce(int oc) { return oc >= DISC_REDUCE_SUM && oc <= DISC_REDUCE_ARGMAX; }
+bool is_elementwise(int oc) {
+  return is_unary(oc) || is_binary(oc) || is_compare(oc) || oc == DISC_SELECT || oc == DISC_CAST;
+}
+int n_operands(int oc) {
+  if (oc <= DISC_DIM_SIZE) return 0;
+  if (is_unary(oc) || oc == DISC_CAST || oc == DISC_BROADCAST || is_reduce(oc) || oc == DISC_OUTPUT)
+    return 1;
+  if (oc == DISC_SELECT) return 3;
+  return 2;
+}
+
+struct Builder {
+  Analysis& an;
+  std::string& err;
+  std::map<std::pair<int, Ctx>, int> memo;
+  int status = DISC_OK;
+
+  Builder(Analysis& a, std::string& e) : an(a), err(e) {}
+
+  int fail(int code, const std::string& msg) {
+    if (status == DISC_OK) {
+      status = code;
+      err = msg;
+    }
+    return -1;
+  }
+  std::string opdesc(int v) {
+    char buf[64];
+    snprintf(buf, sizeof buf, "op %d (%s)", v, opcode_name(an.ops[v].opcode));
+    return buf;
+  }
+  bool dim_is_one(int32_t d) { return an.classes.static_of(an.classes.atom(d)) == 1; }
+  bool shapes_match_root(const disc_op& op) {
+    if (op.rank != an.root_rank) return false;
+    for (int k = 0; k < op.rank; ++k)
+      if (!an.classes.same(an.classes.atom(op.dim[k]), an.classes.atom(an.root_dims[k]))) return false;
+    return true;
+  }
+  // drop axes of static size 1 from a context (they contribute offset 0)
+  Ctx normalise(const disc_op& op, Ctx c) {
+    for (int k = 0; k < op.rank; ++k)
+      if (dim_is_one(op.dim[k])) c[k] = -1;
+    return c;
+  }
+
+  // Resolve value v as seen through context c; returns node id.
+  int demand(int v, Ctx c) {
+    const disc_op& op = an.ops[v];
+    c = normalise(op, c);
+    auto key = std::make_pair(v, c);
+    auto it = memo.find(key);
+    if (it != memo.end()) return it->second;
+    Node n;
+    n.opcode = op.opcode;
+    n.dtype = op.dtype;
+    n.rk = reg_kind(op.dtype);
+    n.value = v;
+    n.ctx = c;
+    const int oc = op.opcode;
+    if (oc == DISC_PARAM) {
+      Access a;
+      a.value = v;
+      a.is_output = false;
+      a.dtype = op.dtype;
+      a.ctx = c;
+      int slot = 0;
+      for (int i = 0; i < v; ++i)
+        if (an.ops[i].opcode == DISC_PARAM) ++slot;
+      a.slot = slot;
+      n.access = (int)an.accesses.size();
+      an.accesses.push_back(a);
+    } else if (oc == DISC_CONST) {
+      n.fconst = op.fconst;
+    } else if (oc == DISC_DIM_SIZE) {
+      n.sym_dim = op.axis_map[0];
+    } else if (oc == DISC_BROADCAST || oc == DISC_OUTPUT) {
+      // no computation: alias of the operand seen through the composed context
+      const disc_op& src = an.ops[op.in[0]];
+      Ctx sc(src.rank, -1);
+      if (oc == DISC_OUTPUT) {
+        sc = c;
+      } else {
+        for (int k = 0; k < src.rank; ++k) sc[k] = c[op.axis_map[k]];
+      }
+      int id = demand(op.in[0], sc);
+      memo[key] = id;
+      return id;
+    } else if (is_reduce(oc)) {
+      if (an.reduce_axis < 0) return fail(DISC_ERR_UNFUSIBLE, opdesc(v) + ": reduction in a loop-fusion pattern");
+      Ctx natural;
+      for (int k = 0; k < an.root_rank; ++k)
+        if (k != an.reduce_axis) natural.push_back(k);
+      Ctx nn = normalise(op, natural);
+      if (c != nn)
+        return fail(DISC_ERR_UNFUSIBLE, opdesc(v) + ": reduction result is consumed along other axes than "
+                    "the ones it was produced on; the iteration spaces cannot be proved compatible");
+      Ctx ident(an.root_rank);
+      for (int k = 0; k < an.root_rank; ++k) ident[k] = k;
+      n.in[0] = demand(op.in[0], ident);
+      n.n_in = 1;
+      if (n.in[0] < 0) return -1;
+    } else {
+      const int no = n_operands(oc);
+      for (int k = 0; k < no; ++k) {
+        const disc_op& src = an.ops[op.in[k]];
+        Ctx sc = src.rank == 0 ? Ctx() : c;
+        n.in[k] = demand(op.in[k], sc);
+        if (n.in[k] < 0) return -1;
+      }
+      n.n_in = no;
+    }
+    int id = (int)an.nodes.size();
+    an.nodes.push_back(n);
+    memo[key] = id;
+    return id;
+  }
+};
+
+void mul_into(DimProduct& p, const DimClasses&, int32_t dim) {
+  if (dim >= 0) p.sym.push_back(dim); else p.stat *= -(int64_t)dim;
+}
+
+}  // namespace
+
+int analyze(const disc_op* ops, int n_ops, const disc_constraint* cs, int n_cs, Analysis* out,
+            std::string* errp) {
+  Analysis& an = *out;
+  std::string& err = *errp;
+  char buf[256];
+  if (!ops || n_ops <= 0) { err = "empty op list"; return DISC_ERR_INVALID_ARG; }
+  if (n_ops > DISC_MAX_OPS) { err = "too many ops"; return DISC_ERR_BAD_PATTERN; }
+  if (n_cs < 0 || (n_cs > 0 && !cs)) { err = "bad constraint list"; return DISC_ERR_INVALID_ARG; }
+  an.ops.assign(ops, ops + n_ops);
+  an.cs.assign(cs, cs + n_cs);
+
+  // ---- 1. structural validation ---------------------------------------------------------
+  int n_sym = 0, n_out = 0, n_in = 0;
+  std::vector<char> is_output_src(n_ops, 0);
+  for (int i = 0; i < n_ops; ++i) {
+    const disc_op& op = ops[i];
+    auto bad = [&](const char* what) {
+      snprintf(buf, sizeof buf, "op %d (%s): %s", i, opcode_name(op.opcode), what);
+      err = buf;
+      return DISC_ERR_BAD_PATTERN;
+    };
+    if (op.opcode < 0 || op.opcode >= DISC_OPCODE_COUNT) return bad("unknown opcode");
+    if (op.dtype < DISC_F32 || op.dtype > DISC_BOOL) return bad("unknown dtype");
+    if (op.rank < 0 || op.rank > DISC_MAX_RANK) return bad("rank outside 0..4 (static rank only)");
+    for (int k = 0; k < op.rank; ++k) {
+      if (op.dim[k] >= DISC_MAX_DIMS) return bad("symbolic dim id too large");
+      if (op.dim[k] >= 0) n_sym = std::max(n_sym, op.dim[k] + 1);
+    }
+    const int no = n_operands(op.opcode);
+    for (int k = 0; k < no; ++k) {
+      if (op.in[k] < 0 || op.in[k] >= i) return bad("operand must name an earlier op");
+      if (ops[op.in[k]].opcode == DISC_OUTPUT) return bad("an OUTPUT op is not a value");
+    }
+    const int oc = op.opcode;
+    if (oc == DISC_CONST && op.rank != 0) return bad("CONST must have rank 0");
+    if (oc == DISC_DIM_SIZE) {
+      if (op.rank != 0) return bad("DIM_SIZE must have rank 0");
+      if (op.axis_map[0] < 0 || op.axis_map[0] >= DISC_MAX_DIMS) return bad("DIM_SIZE of an unknown dim");
+      n_sym = std::max(n_sym, op.axis_map[0] + 1);
+      if (op.dtype == DISC_BOOL) return bad("DIM_SIZE cannot be bool");
+    }
+    if (oc == DISC_PARAM) ++n_in;
+    if (oc == DISC_OUTPUT) {
+      ++n_out;
+      if (op.dtype != ops[op.in[0]].dtype) return bad("OUTPUT dtype differs from its value");
+      if (op.rank != ops[op.in[0]].rank) return bad("OUTPUT rank differs from its value");
+      if (op.rank == 0) return bad("rank-0 outputs are not supported");
+    }
+    if (is_unary(oc) && oc != DISC_NEG && oc != DISC_ABS && !is_float_dtype(op.dtype))
+      return bad("transcendental op needs a float dtype");
+    if (is_unary(oc) && reg_kind(op.dtype) == RK_BOOL) return bad("arithmetic on bool");
+    if (is_binary(oc)) {
+      if (reg_kind(op.dtype) == RK_BOOL) return bad("arithmetic result cannot be bool");
+      for (int k = 0; k < 2; ++k)
+        if (reg_kind(ops[op.in[k]].dtype) == RK_BOOL) return bad("arithmetic on bool (cast first)");
+      if (!is_float_dtype(op.dtype))
+        for (int k = 0; k < 2; ++k)
+          if (is_float_dtype(ops[op.in[k]].dtype)) return bad("float operand of an integer op (cast first)");
+      if (oc == DISC_POW && !is_float_dtype(op.dtype)) return bad("POW needs a float dtype");
+    }
+    if (is_compare(oc) && op.dtype != DISC_BOOL) return bad("comparison result must be DISC_BOOL");
+    if (oc == DISC_SELECT) {
+      for (int k = 1; k < 3; ++k)
+        if (is_float_dtype(ops[op.in[k]].dtype) != is_float_dtype(op.dtype) ||
+            (reg_kind(op.dtype) == RK_BOOL) != (reg_kind(ops[op.in[k]].dtype) == RK_BOOL))
+          return bad("SELECT branches must have the kind of the result");
+    }
+    if (is_reduce(oc)) {
+      const disc_op& src = ops[op.in[0]];
+      if (reg_kind(src.dtype) == RK_BOOL) return bad("reduction over bool (cast first)");
+      if (oc == DISC_REDUCE_ARGMAX) {
+        if (op.dtype != DISC_I32 && op.dtype != DISC_I64) return bad("ARGMAX result must be I32 or I64");
+      } else if (is_float_dtype(src.dtype) != is_float_dtype(op.dtype) || reg_kind(op.dtype) == RK_BOOL) {
+        return bad("reduction result must have the kind of its operand");
+      }
+      if (src.rank < 1 || op.rank != src.rank - 1) return bad("reduce result must drop exactly one axis");
+      if (op.axis_map[0] < 0 || op.axis_map[0] >= src.rank) return bad("reduce axis out of range");
+    }
+    if (oc == DISC_BROADCAST) {
+      const disc_op& src = ops[op.in[0]];
+      if (src.dtype != op.dtype) return bad("BROADCAST changes dtype");
+      if (src.rank > op.rank) return bad("BROADCAST to a lower rank");
+      for (int k = 0; k < src.rank; ++k) {
+        if (op.axis_map[k] < 0 || op.axis_map[k] >= op.rank) return bad("BROADCAST axis_map out of range");
+        if (k > 0 && op.axis_map[k] <= op.axis_map[k - 1]) return bad("BROADCAST axis_map must be strictly increasing");
+      }
+    }
+    if (is_elementwise(oc)) {
+      for (int k = 0; k < no; ++k) {
+        const disc_op& src = ops[op.in[k]];
+        if (src.rank != 0 && src.rank != op.rank) return bad("element-wise operand rank differs from result rank");
+      }
+    }
+  }
+  if (n_out == 0) { err = "pattern has no OUTPUT"; return DISC_ERR_BAD_PATTERN; }
+  an.n_sym = n_sym;
+  an.n_inputs = n_in;
+  an.n_outputs = n_out;
+
+  // ---- 2. constraint closure ------------------------------------------------------------
+  DimClasses& dc = an.classes;
+  dc.init(n_sym);
+  auto unite = [&](int i, int32_t a, int32_t b) -> bool {
+    std::string e;
+    if (!dc.unite(dc.atom(a), dc.atom(b), &e)) {
+      snprintf(buf, sizeof buf, "op %d (%s): %s", i, opcode_name(ops[i].opcode), e.c_str());
+      err = buf;
+      return false;
+    }
+    return true;
+  };
+  for (int i = 0; i < n_ops; ++i) {
+    const disc_op& op = ops[i];
+    const int oc = op.opcode;
+    if (is_elementwise(oc) || oc == DISC_OUTPUT) {
+      // shape propagation class "same shape": every non-scalar operand has the result's shape
+      for (int k = 0; k < n_operands(oc); ++k) {
+        const disc_op& src = ops[op.in[k]];
+        if (src.rank == 0) continue;
+        for (int a = 0; a < op.rank; ++a)
+          if (!unite(i, src.dim[a], op.dim[a])) return DISC_ERR_BAD_PATTERN;
+      }
+    } else if (oc == DISC_BROADCAST) {
+      const disc_op& src = ops[op.in[0]];
+      for (int k = 0; k < src.rank; ++k) {
+        if (src.dim[k] == -1) continue;   // static 1 expands (or stays 1)
+        if (!unite(i, src.dim[k], op.dim[op.axis_map[k]])) return DISC_ERR_BAD_PATTERN;
+      }
+    } else if (is_reduce(oc)) {
+      const disc_op& src = ops[op.in[0]];
+      for (int k = 0, r = 0; k < src.rank; ++k) {
+        if (k == op.axis_map[0]) continue;
+        if (!unite(i, src.dim[k], op.dim[r])) return DISC_ERR_BAD_PATTERN;
+        ++r;
+      }
+    }
+  }
+  // caller-supplied constraints (what the framework bridging would inject)
+  std::vector<std::pair<int, int>> numel_eq;
+  for (int c = 0; c < n_cs; ++c) {
+    const disc_constraint& k = cs[c];
+    auto badc = [&](const char* what) {
+      snprintf(buf, sizeof buf, "constraint %d: %s", c, what);
+      err = buf;
+      return DISC_ERR_BAD_PATTERN;
+    };
+    if (k.a_value < 0 || k.a_value >= n_ops || k.b_value < 0 || k.b_value >= n_ops) return badc("unknown value");
+    if (k.kind == DISC_DIM_EQ) {
+      if (k.a_axis < 0 || k.a_axis >= ops[k.a_value].rank || k.b_axis < 0 || k.b_axis >= ops[k.b_value].rank)
+        return badc("axis out of range");
+      std::string e;
+      if (!dc.unite(dc.atom(ops[k.a_value].dim[k.a_axis]), dc.atom(ops[k.b_value].dim[k.b_axis]), &e))
+        return badc(e.c_str());
+    } else if (k.kind == DISC_NUMEL_EQ) {
+      numel_eq.push_back({k.a_value, k.b_value});
+    } else {
+      return badc("unknown kind");
+    }
+  }
+
+  // ---- 3. fusion decision + template -----------------------------------------------------
+  // tensor-size classes: two values have provably the same element count when the multisets of
+  // their (non-unit) dimension classes agree, or when the caller says so
+  auto numel_key = [&](const disc_op& op) {
+    std::vector<int> k;
+    for (int a = 0; a < op.rank; ++a) {
+      int c = dc.find(dc.atom(op.dim[a]));
+      if (dc.static_val[c] == 1) continue;
+      k.push_back(c);
+    }
+    std::sort(k.begin(), k.end());
+    return k;
+  };
+  std::vector<int> numel_parent(n_ops);
+  for (int i = 0; i < n_ops; ++i) numel_parent[i] = i;
+  std::function<int(int)> nfind = [&](int a) {
+    while (numel_parent[a] != a) a = numel_parent[a] = numel_parent[numel_parent[a]];
+    return a;
+  };
+  {
+    std::map<std::vector<int>, int> first;
+    for (int i = 0; i < n_ops; ++i) {
+      auto k = numel_key(ops[i]);
+      auto it = first.find(k);
+      if (it == first.end()) first[k] = i; else numel_parent[nfind(i)] = nfind(it->second);
+    }
+    for (auto& p : numel_eq) numel_parent[nfind(p.first)] = nfind(p.second);
+  }
+
+  int first_reduce = -1;
+  for (int i = 0; i < n_ops; ++i)
+    if (is_reduce(ops[i].opcode)) { first_reduce = i; break; }
+  int root_value;
+  if (first_reduce >= 0) {
+    root_value = ops[first_reduce].in[0];
+    an.reduce_axis = ops[first_reduce].axis_map[0];
+  } else {
+    root_value = -1;
+    for (int i = 0; i < n_ops; ++i)
+      if (ops[i].opcode == DISC_OUTPUT) { root_value = ops[i].in[0]; break; }
+    an.reduce_axis = -1;
+  }
+  an.root_rank = ops[root_value].rank;
+  an.root_dims.assign(ops[root_value].dim, ops[root_value].dim + an.root_rank);
+
+  Builder b(an, err);
+  // every reduction must run over the same axis of the same iteration space
+  for (int i = 0; i < n_ops; ++i) {
+    if (!is_reduce(ops[i].opcode)) continue;
+    const disc_op& src = ops[ops[i].in[0]];
+    if (!b.shapes_match_root(src)) {
+      snprintf(buf, sizeof buf, "op %d (%s) and op %d (%s): the reduced tensors cannot be proved to have "
+               "the same shape", first_reduce, opcode_name(ops[first_reduce].opcode), i, opcode_name(ops[i].opcode));
+      err = buf;
+      return DISC_ERR_UNFUSIBLE;
+    }
+    if (ops[i].axis_map[0] != an.reduce_axis) {
+      snprintf(buf, sizeof buf, "op %d and op %d reduce over different axes (%d vs %d)", first_reduce, i,
+               an.reduce_axis, ops[i].axis_map[0]);
+      err = buf;
+      return DISC_ERR_UNFUSIBLE;
+    }
+  }
+
+  // "natural" context of values that are not full-shaped: defined through reductions
+  std::vector<Ctx> nat(n_ops);
+  std::vector<char> has_nat(n_ops, 0);
+  Ctx ident(an.root_rank);
+  for (int k = 0; k < an.root_rank; ++k) ident[k] = k;
+  for (int i = 0; i < n_ops; ++i) {
+    const disc_op& op = ops[i];
+    if (op.rank > 0 && b.shapes_match_root(op)) { nat[i] = ident; has_nat[i] = 1; continue; }
+    if (is_reduce(op.opcode)) {
+      for (int k = 0; k < an.root_rank; ++k) if (k != an.reduce_axis) nat[i].push_back(k);
+      has_nat[i] = 1;
+    } else if (is_elementwise(op.opcode) || op.opcode == DISC_OUTPUT) {
+      for (int k = 0; k < n_operands(op.opcode); ++k) {
+        int s = op.in[k];
+        if (ops[s].rank == op.rank && has_nat[s]) { nat[i] = nat[s]; has_nat[i] = 1; break; }
+      }
+    }
+  }
+
+  // flat loop fusion: outputs agree only in element count (tensor-size equality)
+  if (an.reduce_axis < 0) {
+    bool all_match = true, all_numel = true;
+    for (int i = 0; i < n_ops; ++i) {
+      if (ops[i].opcode != DISC_OUTPUT) continue;
+      if (!b.shapes_match_root(ops[i])) all_match = false;
+      if (nfind(i) != nfind(root_value)) all_numel = false;
+    }
+    if (!all_match) {
+      if (!all_numel) {
+        int o1 = -1, o2 = -1;
+        for (int i = 0; i < n_ops; ++i)
+          if (ops[i].opcode == DISC_OUTPUT) { if (o1 < 0) o1 = i; else if (!b.shapes_match_root(ops[i]) && o2 < 0) o2 = i; }
+        snprintf(buf, sizeof buf, "op %d (output) and op %d (output): neither equal shapes nor equal element "
+                 "counts can be proved; add a DIM_EQ or NUMEL_EQ constraint or register two patterns", o1, o2);
+        err = buf;
+        return DISC_ERR_UNFUSIBLE;
+      }
+      an.flat = true;
+    }
+  }
+
+  // ---- 4. contexts ---------------------------------------------------------------------
+  if (an.flat) {
+    // Every tensor is walked with one linear index: legal only when each operand is a full
+    // (non-broadcast) tensor of the common element count or a scalar.
+    for (int i = 0; i < n_ops; ++i) {
+      const disc_op& op = ops[i];
+      if (op.opcode == DISC_BROADCAST) {
+        snprintf(buf, sizeof buf, "op %d (broadcast): outputs agree only in element count, so the pattern is "
+                 "fused over a flat index and cannot contain a broadcast", i);
+        err = buf;
+        return DISC_ERR_UNFUSIBLE;
+      }
+      if (op.rank > 0 && nfind(i) != nfind(root_value)) {
+        snprintf(buf, sizeof buf, "op %d (%s): element count cannot be proved equal to that of op %d", i,
+                 opcode_name(op.opcode), root_value);
+        err = buf;
+        return DISC_ERR_UNFUSIBLE;
+      }
+    }
+  }
+  for (int i = 0; i < n_ops; ++i) {
+    if (ops[i].opcode != DISC_OUTPUT) continue;
+    Ctx c;
+    if (an.flat) {
+      c.assign(ops[i].rank, 0);   // placeholder, flat accesses ignore contexts
+    } else if (b.shapes_match_root(ops[i])) {
+      c = ident;
+    } else if (has_nat[i]) {
+      c = nat[i];
+    } else {
+      snprintf(buf, sizeof buf, "op %d (output): its shape is neither the iteration space of the pattern nor "
+               "derived from a reduction over it", i);
+      err = buf;
+      return DISC_ERR_UNFUSIBLE;
+    }
+    OutputRef o;
+    o.node = b.demand(i, c);
+    if (o.node < 0) return b.status;
+    Access a;
+    a.value = i;
+    a.is_output = true;
+    a.dtype = ops[i].dtype;
+    a.ctx = b.normalise(ops[i], c);
+    a.slot = (int)an.outputs.size();
+    o.access = (int)an.accesses.size();
+    an.accesses.push_back(a);
+    an.outputs.push_back(o);
+  }
+  if (b.status != DISC_OK) return b.status;
+
+  // ---- 5. collapse root axes with identical roles ------------------------------------------
+  an.groups.clear();
+  if (an.flat) {
+    an.root_rank = ops[root_value].rank;
+    std::vector<int> g;
+    for (int k = 0; k < an.root_rank; ++k) g.push_back(k);
+    an.groups.push_back(g);
+    for (auto& a : an.accesses) {
+      a.ctx.assign(ops[a.value].rank, 0);
+      a.groups = {0};
+    }
+  } else {
+    auto mergeable = [&](int i) {   // may root axes i and i+1 form one group?
+      if (i == an.reduce_axis || i + 1 == an.reduce_axis) return false;
+      for (const auto& a : an.accesses) {
+        int pi = -1, pj = -1;
+        for (int k = 0; k < (int)a.ctx.size(); ++k) {
+          if (a.ctx[k] == i) pi = k;
+          if (a.ctx[k] == i + 1) pj = k;
+        }
+        if (pi < 0 && pj < 0) continue;
+        if (pi < 0 || pj < 0) return false;
+        // both present: must be adjacent in the operand too (axes of size 1 in between are fine)
+        for (int k = pi + 1; k < pj; ++k)
+          if (a.ctx[k] != -1) return false;
+      }
+      return true;
+    };
+    // root axes of static size 1 carry no index: drop them from the iteration space
+    std::vector<int> live;
+    for (int k = 0; k < an.root_rank; ++k)
+      if (!b.dim_is_one(an.root_dims[k]) || k == an.reduce_axis) live.push_back(k);
+    if (live.empty()) live.push_back(an.root_rank - 1);
+    std::vector<int> cur;
+    for (size_t t = 0; t < live.size(); ++t) {
+      cur.push_back(live[t]);
+      bool join = false;
+      if (t + 1 < live.size()) {
+        // axes between live[t] and live[t+1] are unit axes; merge only direct neighbours in the live list
+        join = true;
+        int i = live[t], j = live[t + 1];
+        if (i == an.reduce_axis || j == an.reduce_axis) join = false;
+        if (join) {
+          for (const auto& a : an.accesses) {
+            int pi = -1, pj = -1;
+            for (int k = 0; k < (int)a.ctx.size(); ++k) {
+              if (a.ctx[k] == i) pi = k;
+              if (a.ctx[k] == j) pj = k;
+            }
+            if (pi < 0 && pj < 0) continue;
+            if (pi < 0 || pj < 0) { join = false; break; }
+            for (int k = pi + 1; k < pj; ++k)
+              if (a.ctx[k] != -1) { join = false; break; }
+            if (!join) break;
+          }
+        }
+      }
+      if (!join) {
+        an.groups.push_back(cur);
+        cur.clear();
+      }
+    }
+    (void)mergeable;
+    // group membership of every access
+    for (auto& a : an.accesses) {
+      a.groups.clear();
+      for (int g = 0; g < (int)an.groups.size(); ++g) {
+        bool has = false;
+        for (int ax : an.groups[g])
+          for (int c : a.ctx) if (c == ax) has = true;
+        if (has) a.groups.push_back(g);
+      }
+    }
+  }
+  const int ng = (int)an.groups.size();
+  if (an.reduce_axis >= 0) {
+    int rg = -1;
+    for (int g = 0; g < ng; ++g)
+      for (int ax : an.groups[g]) if (ax == an.reduce_axis) rg = g;
+    if (rg == ng - 1) {
+      an.tmpl = DISC_TEMPLATE_ROW_REDUCE;
+      an.inner_group = ng - 1;
+    } else {
+      an.tmpl = DISC_TEMPLATE_COL_REDUCE;
+      an.mid_group = rg;
+      an.inner_group = ng - 1;
+      if (rg + 2 != ng) {
+        err = "column reduction: the axes after the reduced one do not collapse into one contiguous group";
+        return DISC_ERR_UNFUSIBLE;
+      }
+      if (rg > 1) {
+        err = "column reduction: the axes before the reduced one do not collapse into one group";
+        return DISC_ERR_UNFUSIBLE;
+      }
+    }
+  } else {
+    an.tmpl = DISC_TEMPLATE_LOOP;
+    an.inner_group = ng - 1;
+  }
+  if (ng > 4) { err = "iteration space does not collapse to <= 4 groups"; return DISC_ERR_UNFUSIBLE; }
+
+  // ---- 6. domains and phases --------------------------------------------------------------
+  auto ctx_has_group = [&](const Ctx& c, int g) {
+    for (int ax : an.groups[g]) for (int x : c) if (x == ax) return true;
+    return false;
+  };
+  int max_phase = 0;
+  for (auto& n : an.nodes) {
+    if (n.opcode == DISC_CONST || n.opcode == DISC_DIM_SIZE) {
+      n.dom = DOM_SCALAR;
+      n.phase = 0;
+      continue;
+    }
+    if (an.flat) {
+      n.dom = DOM_ELEM;
+    } else if (an.tmpl == DISC_TEMPLATE_COL_REDUCE) {
+      // "row" domain of a column reduction = values without the reduced (mid) axis
+      n.dom = ctx_has_group(n.ctx, an.mid_group) ? DOM_ELEM : DOM_ROW;
+    } else {
+      n.dom = ctx_has_group(n.ctx, an.inner_group) ? DOM_ELEM : DOM_ROW;
+    }
+    int ph = 0;
+    for (int k = 0; k < n.n_in; ++k) ph = std::max(ph, an.nodes[n.in[k]].phase);
+    if (is_reduce(n.opcode)) {
+      n.reduce_slot = (int)an.reduces[ph].size();
+      if (ph >= 7) { err = "too many dependent reduction levels"; return DISC_ERR_UNFUSIBLE; }
+      an.reduces[ph].push_back((int)(&n - &an.nodes[0]));
+      n.phase = ph + 1;
+      n.dom = DOM_ROW;
+    } else {
+      n.phase = ph;
+    }
+    max_phase = std::max(max_phase, n.phase);
+  }
+  an.n_phases = max_phase;
+  if (an.tmpl == DISC_TEMPLATE_COL_REDUCE && an.n_phases > 1) {
+    err = "column reduction feeding another reduction: needs a second pass over the tensor, not one fusion";
+    return DISC_ERR_UNFUSIBLE;
+  }
+
+  // ---- 7. access kinds and shape-calculation recipes ---------------------------------------
+  an.group_size.assign(ng, DimProduct());
+  for (int g = 0; g < ng; ++g)
+    for (int ax : an.groups[g]) mul_into(an.group_size[g], dc, an.root_dims[ax]);
+  const int n_outer = an.inner_group;   // groups before the inner one
+  an.needs_decomp = false;
+  for (auto& a : an.accesses) {
+    a.has_inner = !a.groups.empty() && a.groups.back() == an.inner_group;
+    int outer_cnt = (int)a.groups.size() - (a.has_inner ? 1 : 0);
+    if (outer_cnt == n_outer) a.kind = a.has_inner ? ACC_FULL : (n_outer == 0 ? ACC_SCALAR : ACC_PERROW);
+    else if (outer_cnt == 0) a.kind = a.has_inner ? ACC_ROWVEC : ACC_SCALAR;
+    else a.kind = ACC_PARTIAL;
+    if (a.kind == ACC_PARTIAL) {
+      an.needs_decomp = true;
+      // stride of spanned outer group g = product of the later groups this access spans
+      for (size_t t = 0; t < a.groups.size(); ++t) {
+        if (a.groups[t] == an.inner_group) continue;
+        DimProduct p;
+        for (size_t u = t + 1; u < a.groups.size(); ++u) {
+          const DimProduct& gs = an.group_size[a.groups[u]];
+          p.sym.insert(p.sym.end(), gs.sym.begin(), gs.sym.end());
+          p.stat *= gs.stat;
+        }
+        a.stride_prod.push_back((int)an.products.size());
+        an.products.push_back(p);
+      }
+    }
+  }
+  for (auto& n : an.nodes)
+    if (n.opcode == DISC_DIM_SIZE &&
+        std::find(an.dim_size_syms.begin(), an.dim_size_syms.end(), n.sym_dim) == an.dim_size_syms.end())
+      an.dim_size_syms.push_back(n.sym_dim);
+
+  // vector width: 16 bytes of the narrowest per-element tensor, at most 8 elements
+  int min_bytes = 8;
+  bool any = false;
+  for (const auto& a : an.accesses) {
+    if (!a.has_inner) continue;
+    if (a.dtype == DISC_BOOL) continue;      // masks ride along at whatever width the data needs
+    min_bytes = std::min(min_bytes, dtype_bytes(a.dtype));
+    any = true;
+  }
+  if (!any) min_bytes = 2;
+  an.vec_width = std::min(8, 16 / min_bytes);
+  return DISC_OK;
+}
+
+}  // namespace disc

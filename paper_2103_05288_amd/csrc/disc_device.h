@@ -1,0 +1,330 @@
+// disc_device.h -- hand-written, shape-generic kernel schedules for gfx950 (CDNA4).
+//
+// This header is compiled at pattern-registration time together with ONE generated
+// `struct Pat` that holds the fused per-element expression of the pattern.  Everything
+// that decides performance lives here and is written by hand: how rows are mapped to
+// lanes, how data moves through registers / LDS, how reductions are combined.  The
+// schedules never see a shape as a compile-time constant; every extent arrives in the
+// kernel-argument block that the host fills at launch (the paper's host-side shape
+// calculation and launch-dimension selection, Sections 4.2.1 and 4.3).
+//
+// The two templates of Section 4.3 ("classical loop fusion and input fusion with reduce
+// operation as the root") are kloop_kernel and the row_* / col_* kernels; each exists in
+// several versions (vector / scalar access, 32 / 64-bit index, register-resident / streamed
+// row, ...) which the host selects per incoming shape.
+//
+// Interface expected from the generated `Pat` (all members static, __device__, inlined):
+//   struct Args            kernel-argument block (pointers, extents, fast-division constants)
+//   struct RowCtx          per-row state: operand base offsets and per-row values
+//   template<int V> struct Slot      V consecutive elements of every per-element operand
+//   template<int V> struct OutSlot   V consecutive elements of every per-element output
+//   row_begin(A,row,rc)                        fill RowCtx for `row` (loads per-row operands)
+//   load<V>(A,rc,col,nvalid,slot)              load a slot (nvalid < V: predicated per element)
+//   template<int P> struct Acc                 accumulator of reduction phase P
+//   acc_init<P>(acc)  acc_merge<P>(a,b)  acc_shfl<P>(acc,lane_mask)
+//   accum<P,V>(A,acc,slot,e,col,rc)            fold element e of a slot into acc
+//   row_after<P>(A,rc,acc)                     per-row values that become known after phase P
+//   epilogue<V>(A,rc,slot,col,out)             per-element results of all outputs
+//   store<V>(A,rc,col,nvalid,out)              store a slot of outputs
+//   row_store(A,row,rc)                        store per-row outputs (one lane per row calls it)
+//   NPHASE, MAX_ACC_BYTES
+#pragma once
+
+namespace disc {
+
+typedef unsigned char u8;
+typedef unsigned short u16;
+typedef unsigned int u32;
+typedef long long i64;
+typedef unsigned long long u64;
+
+#define DISC_DEV __device__ __forceinline__
+
+// ---------------------------------------------------------------------------------------
+// Vectors of N storage elements with ELEMENT alignment only.  gfx950 runs with unaligned
+// global access enabled, so the compiler still emits one wide load / store (global_load_
+// dwordx4 for 16 bytes) and the hardware serves rows that start at any element.  This is
+// why no separate "aligned" kernel version is needed for rows whose length is not a
+// multiple of the vector width.
+// ---------------------------------------------------------------------------------------
+template <class T, int N>
+struct __attribute__((packed, aligned(alignof(T)))) Vec {
+  T v[N];
+};
+
+template <class T, int N, class I>
+DISC_DEV void ld(Vec<T, N>& d, const T* __restrict__ p, I off, int nvalid) {
+  if (nvalid >= N) {
+    d = *reinterpret_cast<const Vec<T, N>*>(p + off);
+  } else {
+#pragma unroll
+    for (int e = 0; e < N; ++e) d.v[e] = e < nvalid ? p[off + e] : T(0);
+  }
+}
+
+template <class T, int N, class I>
+DISC_DEV void st(T* __restrict__ p, I off, const Vec<T, N>& s, int nvalid) {
+  if (nvalid >= N) {
+    *reinterpret_cast<Vec<T, N>*>(p + off) = s;
+  } else {
+#pragma unroll
+    for (int e = 0; e < N; ++e)
+      if (e < nvalid) p[off + e] = s.v[e];
+  }
+}
+
+// storage <-> register conversions (float values live in fp32 registers; one rounding,
+// to nearest even, at the store)
+DISC_DEV float to_f32(float x) { return x; }
+DISC_DEV float to_f32(_Float16 x) { return (float)x; }
+DISC_DEV float to_f32(__bf16 x) { return (float)x; }
+DISC_DEV float to_f32(int x) { return (float)x; }
+DISC_DEV float to_f32(i64 x) { return (float)x; }
+DISC_DEV float to_f32(bool x) { return x ? 1.f : 0.f; }
+template <class T> DISC_DEV T from_f32(float x);
+template <> DISC_DEV float from_f32<float>(float x) { return x; }
+template <> DISC_DEV _Float16 from_f32<_Float16>(float x) { return (_Float16)x; }
+template <> DISC_DEV __bf16 from_f32<__bf16>(float x) { return (__bf16)x; }
+
+// ---------------------------------------------------------------------------------------
+// Division by a runtime extent with constants the host precomputes from the shape
+// (round-up multiply-shift method of Granlund & Montgomery): for 0 <= n < 2^31,
+//   n / d == (umulhi(n, m) + n) >> s   with s = ceil(log2 d), m = floor(2^32 (2^s - d) / d) + 1.
+// ---------------------------------------------------------------------------------------
+struct FastDiv {
+  u32 d, m, s, pad;
+};
+DISC_DEV u32 fdiv(u32 n, const FastDiv& f) { return (__umulhi(n, f.m) + n) >> f.s; }
+
+// ---------------------------------------------------------------------------------------
+// cross-lane helpers (64-wide wavefronts)
+// ---------------------------------------------------------------------------------------
+DISC_DEV float shfl_xor(float v, int m) { return __shfl_xor(v, m, 64); }
+DISC_DEV int shfl_xor(int v, int m) { return __shfl_xor(v, m, 64); }
+DISC_DEV double shfl_xor(double v, int m) { return __shfl_xor(v, m, 64); }
+DISC_DEV i64 shfl_xor(i64 v, int m) {
+  int lo = __shfl_xor((int)(u32)(u64)v, m, 64), hi = __shfl_xor((int)((u64)v >> 32), m, 64);
+  return (i64)(((u64)(u32)hi << 32) | (u32)lo);
+}
+
+// =======================================================================================
+// Loop fusion (kLoop).  The iteration space is [rows, inner]; it is cut into slots of V
+// consecutive elements of one row.  Consecutive lanes take consecutive slots, so every wave
+// reads and writes one contiguous stretch of memory whatever `inner` is; a block walks the
+// slot list with a grid stride, U slots in flight per lane to keep enough bytes in flight
+// for HBM.  (row, col) of a slot come from one multiply-shift division per slot.
+// =======================================================================================
+template <class Pat, int V, int U, bool I64>
+DISC_DEV void kloop_body(const typename Pat::Args& A) {
+  if constexpr (!I64) {
+    const u32 nslots = (u32)A.nslots;
+    const u32 stride = gridDim.x * blockDim.x;
+    const u32 inner = (u32)A.inner;
+    for (u32 s0 = blockIdx.x * blockDim.x + threadIdx.x; s0 < nslots; s0 += stride * U) {
+      typename Pat::template Slot<V> slot[U];
+      typename Pat::RowCtx rc[U];
+      int col[U], nv[U];
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const u32 s = s0 + u * stride;
+        nv[u] = 0;
+        if (s < nslots) {
+          const u32 row = fdiv(s, A.spr_div);
+          col[u] = (int)((s - row * A.spr_div.d) * V);
+          nv[u] = min((int)V, (int)(inner - (u32)col[u]));
+          Pat::row_begin(A, (i64)row, rc[u]);
+          Pat::template load<V>(A, rc[u], col[u], nv[u], slot[u]);
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        if (nv[u] > 0) {
+          typename Pat::template OutSlot<V> o;
+          Pat::template epilogue<V>(A, rc[u], slot[u], col[u], o);
+          Pat::template store<V>(A, rc[u], col[u], nv[u], o);
+        }
+      }
+    }
+  } else {
+    const i64 nslots = A.nslots;
+    const i64 stride = (i64)gridDim.x * blockDim.x;
+    const i64 spr = A.spr;
+    for (i64 s = (i64)blockIdx.x * blockDim.x + threadIdx.x; s < nslots; s += stride) {
+      const i64 row = s / spr;
+      const i64 col = (s - row * spr) * V;
+      const i64 rem = A.inner - col;
+      const int nv = rem < (i64)V ? (int)rem : V;
+      typename Pat::template Slot<V> slot;
+      typename Pat::RowCtx rc;
+      Pat::row_begin(A, row, rc);
+      Pat::template load<V>(A, rc, col, nv, slot);
+      typename Pat::template OutSlot<V> o;
+      Pat::template epilogue<V>(A, rc, slot, col, o);
+      Pat::template store<V>(A, rc, col, nv, o);
+    }
+  }
+}
+
+// =======================================================================================
+// Input fusion with a row reduction as root (kInput, reduce over the innermost axis).
+//
+// Register-resident version: a row is owned by a group of G lanes (G a power of two chosen
+// by the host per shape: 1..32 = several rows per wavefront for short rows, 64 = a
+// wavefront per row, 128 / 256 = several wavefronts per row).  Lane l of the group holds
+// slots l, l+G, l+2G, ... (NV of them, V elements each), loaded ONCE; every reduction phase
+// and the epilogue run out of registers, so the row makes exactly one trip from HBM and one
+// back.  Within a wavefront partial results are combined with xor-shuffles; across the
+// wavefronts of a row through a double-buffered LDS exchange (one barrier per phase).
+// =======================================================================================
+struct RowPlan {
+  int G;        // lanes per row, power of two, <= blockDim.x
+  int log2G;
+  int nv;       // slots per lane actually needed at this shape (<= NV of the instantiation)
+  int pad;
+};
+
+template <class Pat, int P, int V, int NV>
+DISC_DEV void row_phases(const typename Pat::Args& A, const RowPlan& rp, typename Pat::RowCtx& rc,
+                         const typename Pat::template Slot<V> (&slot)[NV], const int (&nvalid)[NV],
+                         int col0, char* lds, int& parity) {
+  if constexpr (P < Pat::NPHASE) {
+    typename Pat::template Acc<P> acc;
+    Pat::template acc_init<P>(acc);
+#pragma unroll
+    for (int j = 0; j < NV; ++j) {
+      const int col = col0 + j * rp.G * V;
+#pragma unroll
+      for (int e = 0; e < V; ++e)
+        if (e < nvalid[j]) Pat::template accum<P, V>(A, acc, slot[j], e, col + e, rc);
+    }
+    // lanes of one wavefront
+    const int gw = rp.G < 64 ? rp.G : 64;
+    for (int m = gw >> 1; m > 0; m >>= 1) {
+      typename Pat::template Acc<P> o = acc;
+      Pat::template acc_shfl<P>(o, m);
+      Pat::template acc_merge<P>(acc, o);
+    }
+    // wavefronts of one row
+    if (rp.G > 64) {
+      typedef typename Pat::template Acc<P> AccT;
+      AccT* ex = reinterpret_cast<AccT*>(lds + parity * 4 * Pat::MAX_ACC_BYTES);
+      parity ^= 1;
+      const int wave = threadIdx.x >> 6;
+      if ((threadIdx.x & 63) == 0) ex[wave] = acc;
+      __syncthreads();
+      const int wpr = rp.G >> 6;               // wavefronts per row
+      const int w0 = wave & ~(wpr - 1);
+      acc = ex[w0];
+      for (int w = 1; w < wpr; ++w) {
+        AccT o = ex[w0 + w];
+        Pat::template acc_merge<P>(acc, o);
+      }
+    }
+    Pat::template row_after<P>(A, rc, acc);
+    row_phases<Pat, P + 1, V, NV>(A, rp, rc, slot, nvalid, col0, lds, parity);
+  }
+}
+
+template <class Pat, int V, int NV>
+DISC_DEV void row_reg_body(const typename Pat::Args& A, const RowPlan& rp) {
+  __shared__ __attribute__((aligned(16))) char lds[2 * 4 * Pat::MAX_ACC_BYTES];
+  const int lane = threadIdx.x & (rp.G - 1);
+  const int grp = threadIdx.x >> rp.log2G;
+  const int rpb = blockDim.x >> rp.log2G;        // rows per block
+  const i64 rows = A.rows;
+  const int inner = (int)A.inner;
+  const int col0 = lane * V;
+  int parity = 0;
+  const i64 ngroups = (rows + rpb - 1) / rpb;
+  for (i64 rg = blockIdx.x; rg < ngroups; rg += gridDim.x) {
+    const i64 row = rg * rpb + grp;
+    const bool active = row < rows;
+    typename Pat::RowCtx rc{};
+    typename Pat::template Slot<V> slot[NV];
+    int nvalid[NV];
+    if (active) Pat::row_begin(A, row, rc);
+#pragma unroll
+    for (int j = 0; j < NV; ++j) {
+      const int col = col0 + j * rp.G * V;
+      int n = inner - col;
+      n = n > V ? V : n;
+      nvalid[j] = (active && j < rp.nv && n > 0) ? n : 0;
+      if (nvalid[j] > 0) Pat::template load<V>(A, rc, col, nvalid[j], slot[j]);
+    }
+    row_phases<Pat, 0, V, NV>(A, rp, rc, slot, nvalid, col0, lds, parity);
+#pragma unroll
+    for (int j = 0; j < NV; ++j) {
+      if (nvalid[j] > 0) {
+        const int col = col0 + j * rp.G * V;
+        typename Pat::template OutSlot<V> o;
+        Pat::template epilogue<V>(A, rc, slot[j], col, o);
+        Pat::template store<V>(A, rc, col, nvalid[j], o);
+      }
+    }
+    if (active && lane == 0) Pat::row_store(A, row, rc);
+  }
+}
+
+// Streaming version for rows that do not fit the register budget: one block per row, the
+// row is re-read (from L2 / Infinity Cache when it fits) once per reduction phase and once
+// for the epilogue.  Any row length below 2^31 works.
+template <class Pat, int P, int V>
+DISC_DEV void row_stream_phases(const typename Pat::Args& A, typename Pat::RowCtx& rc, int inner,
+                                char* lds, int& parity) {
+  if constexpr (P < Pat::NPHASE) {
+    typedef typename Pat::template Acc<P> AccT;
+    AccT acc;
+    Pat::template acc_init<P>(acc);
+    for (int col = threadIdx.x * V; col < inner; col += blockDim.x * V) {
+      int n = inner - col;
+      n = n > V ? V : n;
+      typename Pat::template Slot<V> slot;
+      Pat::template load<V>(A, rc, col, n, slot);
+#pragma unroll
+      for (int e = 0; e < V; ++e)
+        if (e < n) Pat::template accum<P, V>(A, acc, slot, e, col + e, rc);
+    }
+    for (int m = 32; m > 0; m >>= 1) {
+      AccT o = acc;
+      Pat::template acc_shfl<P>(o, m);
+      Pat::template acc_merge<P>(acc, o);
+    }
+    AccT* ex = reinterpret_cast<AccT*>(lds + parity * 16 * Pat::MAX_ACC_BYTES);
+    parity ^= 1;
+    const int wave = threadIdx.x >> 6;
+    if ((threadIdx.x & 63) == 0) ex[wave] = acc;
+    __syncthreads();
+    const int nw = blockDim.x >> 6;
+    acc = ex[0];
+    for (int w = 1; w < nw; ++w) {
+      AccT o = ex[w];
+      Pat::template acc_merge<P>(acc, o);
+    }
+    Pat::template row_after<P>(A, rc, acc);
+    row_stream_phases<Pat, P + 1, V>(A, rc, inner, lds, parity);
+  }
+}
+
+template <class Pat, int V>
+DISC_DEV void row_stream_body(const typename Pat::Args& A) {
+  __shared__ __attribute__((aligned(16))) char lds[2 * 16 * Pat::MAX_ACC_BYTES];
+  const int inner = (int)A.inner;
+  int parity = 0;
+  for (i64 row = blockIdx.x; row < A.rows; row += gridDim.x) {
+    typename Pat::RowCtx rc;
+    Pat::row_begin(A, row, rc);
+    row_stream_phases<Pat, 0, V>(A, rc, inner, lds, parity);
+    for (int col = threadIdx.x * V; col < inner; col += blockDim.x * V) {
+      int n = inner - col;
+      n = n > V ? V : n;
+      typename Pat::template Slot<V> slot;
+      Pat::template load<V>(A, rc, col, n, slot);
+      typename Pat::template OutSlot<V> o;
+      Pat::template epilogue<V>(A, rc, slot, col, o);
+      Pat::template store<V>(A, rc, col, n, o);
+    }
+    if (threadIdx.x == 0) Pat::row_store(A, row, rc);
+  }
+}
+
+}  // namespace disc

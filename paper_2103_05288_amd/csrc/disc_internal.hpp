@@ -1,0 +1,170 @@
+// Internal data structures of the host side: pattern IR, constraint classes, the resolved
+// node graph, collapsed iteration space, launch recipes.  Nothing here touches the GPU.
+#pragma once
+
+#include <cstdint>
+#include <map>
+#include <string>
+#include <vector>
+
+#include "disc.h"
+
+namespace disc {
+
+// Register kind a value is computed in (storage dtype only matters at loads / stores).
+enum RegKind { RK_F32 = 0, RK_I32 = 1, RK_I64 = 2, RK_BOOL = 3 };
+
+inline RegKind reg_kind(int dtype) {
+  switch (dtype) {
+    case DISC_I32: return RK_I32;
+    case DISC_I64: return RK_I64;
+    case DISC_BOOL: return RK_BOOL;
+    default: return RK_F32;
+  }
+}
+inline int dtype_bytes(int dtype) {
+  switch (dtype) {
+    case DISC_F32: case DISC_I32: return 4;
+    case DISC_F16: case DISC_BF16: return 2;
+    case DISC_I64: return 8;
+    default: return 1;
+  }
+}
+inline bool is_float_dtype(int d) { return d == DISC_F32 || d == DISC_F16 || d == DISC_BF16; }
+const char* dtype_ctype(int dtype);   // storage type name in device code
+const char* reg_ctype(RegKind k);     // register type name in device code
+const char* opcode_name(int opcode);
+
+// ---------------------------------------------------------------------------------------
+// Dimension-size equality classes (Section 4.2.1): union-find over "atoms".  Atoms
+// [0, n_sym) are the symbolic dims, further atoms are distinct static sizes.
+// ---------------------------------------------------------------------------------------
+struct DimClasses {
+  int n_sym = 0;
+  std::vector<int> parent;
+  std::vector<int64_t> static_val;      // per atom; -1 = unknown (symbolic)
+  std::map<int64_t, int> static_atom;   // static size -> atom
+
+  void init(int n_symbolic);
+  int atom(int32_t dim);                 // dim as stored in disc_op::dim
+  int find(int a);
+  int64_t static_of(int a) { return static_val[find(a)]; }
+  // false + message when two different static sizes would become equal
+  bool unite(int a, int b, std::string* err);
+  bool same(int a, int b) { return find(a) == find(b); }
+};
+
+// A value seen from the iteration space: for each axis of the value the root axis it is
+// indexed by, or -1 when the axis has static size 1 (contributes nothing to the offset).
+typedef std::vector<int> Ctx;
+
+enum Domain { DOM_SCALAR = 0, DOM_ROW = 1, DOM_ELEM = 2 };
+
+// Where an operand / result lives relative to the canonical [outer groups..., inner] space.
+enum AccessKind {
+  ACC_FULL = 0,     // all outer groups + inner, contiguous: offset = row * inner + col
+  ACC_ROWVEC = 1,   // inner only:                            offset = col
+  ACC_PERROW = 2,   // all outer groups, no inner:            offset = row
+  ACC_SCALAR = 3,   // no group at all:                       offset = 0
+  ACC_PARTIAL = 4   // a strict subset of the outer groups (+ inner or not): strided
+};
+
+struct Access {
+  int value = -1;          // op index of the PARAM / OUTPUT
+  int slot = -1;           // k-th input or k-th output pointer
+  bool is_output = false;
+  int dtype = 0;
+  Ctx ctx;
+  std::vector<int> groups; // collapsed groups it spans, increasing
+  bool has_inner = false;
+  AccessKind kind = ACC_FULL;
+  // ACC_PARTIAL: index (into Recipe::products) of the stride of each spanned outer group
+  std::vector<int> stride_prod;
+};
+
+// Resolved graph: one node per (value, context) pair actually needed.
+struct Node {
+  int opcode = 0;
+  int dtype = 0;
+  RegKind rk = RK_F32;
+  int value = -1;           // originating op
+  Ctx ctx;
+  int in[3] = {-1, -1, -1}; // node ids
+  int n_in = 0;
+  Domain dom = DOM_SCALAR;
+  int phase = 0;            // number of dependent reductions before this value is known
+  int access = -1;          // PARAM: index into accesses
+  double fconst = 0.0;
+  int sym_dim = -1;         // DIM_SIZE
+  int reduce_slot = -1;     // REDUCE_*: index of the reduction within its phase
+};
+
+struct OutputRef {
+  int node = -1;
+  int access = -1;
+};
+
+// A product of runtime dims the host evaluates at launch (shape calculation).
+struct DimProduct {
+  std::vector<int> sym;     // symbolic dim ids
+  int64_t stat = 1;         // static factor
+};
+
+struct Analysis {
+  int tmpl = DISC_TEMPLATE_LOOP;
+  int n_sym = 0;
+  std::vector<disc_op> ops;
+  std::vector<disc_constraint> cs;
+  DimClasses classes;
+
+  // iteration space
+  int root_rank = 0;
+  std::vector<int32_t> root_dims;        // dim entries (symbolic id or -static) of the root shape
+  int reduce_axis = -1;                  // root axis, -1 for loop fusion
+  bool flat = false;                     // loop fusion over values that only agree in element count
+  std::vector<std::vector<int>> groups;  // collapsed groups of consecutive root axes
+  int inner_group = -1;                  // index of the innermost group
+  int mid_group = -1;                    // column reduce: the reduced group
+
+  std::vector<Node> nodes;               // topological order
+  std::vector<Access> accesses;
+  std::vector<OutputRef> outputs;        // in OUTPUT-op order
+  std::vector<int> reduces[8];           // reduce nodes per phase
+  int n_phases = 0;
+  int n_inputs = 0, n_outputs = 0;
+  bool needs_decomp = false;             // some access is ACC_PARTIAL
+
+  // launch recipes
+  std::vector<DimProduct> group_size;    // per collapsed group
+  std::vector<DimProduct> products;      // strides of partial accesses
+  std::vector<int> dim_size_syms;        // symbolic dims referenced by DIM_SIZE nodes
+  int vec_width = 1;                     // elements per vector slot
+};
+
+// Kernel-argument block layout shared by the code generator and the launcher.
+struct ArgField {
+  enum Kind { ROWS, INNER, NSLOTS, SPR, SPR_DIV, GROUP_DIV, GROUP_SIZE, IN_PTR, OUT_PTR, STRIDE,
+              DIMF, DIMI, MID, WS_PTR, AUX } kind;
+  int index = 0;       // group / pointer / product / dim index
+  int offset = 0;
+  int size = 0;
+};
+struct ArgLayout {
+  std::vector<ArgField> fields;
+  int size = 0;
+};
+
+struct Generated {
+  std::string source;
+  ArgLayout args;
+  std::vector<std::string> kernels;   // entry-point names present in the module
+};
+
+// checker.cpp: validate, close constraints, decide fusion, resolve contexts, collapse.
+int analyze(const disc_op* ops, int n_ops, const disc_constraint* cs, int n_cs, Analysis* out,
+            std::string* err);
+
+// codegen.cpp
+int generate(const Analysis& an, Generated* out, std::string* err);
+
+}  // namespace disc

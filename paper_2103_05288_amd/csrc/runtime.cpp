@@ -1,0 +1,641 @@
+// Context, pattern cache, the one device compile per pattern, and the launch path.
+//
+// The launch path is the "generated runtime flow" of the paper (Section 4.2) in the form of a
+// closure specialised at registration: shape calculation from the runtime dims, the check of
+// the registered equalities, version and launch-dimension selection (Section 4.3), filling of
+// the kernel-argument block, one enqueue.  It walks recipes made of a handful of integer
+// products and comparisons; the op list of the pattern is never visited at launch time.
+#include <hip/hip_runtime_api.h>
+#include <hip/hiprtc.h>
+
+#include <chrono>
+#include <cstdlib>
+#include <cstring>
+#include <memory>
+
+#include "disc_internal.hpp"
+
+namespace disc {
+
+extern const char* const kDeviceHeader;   // disc_device.h, embedded at build time
+
+namespace {
+
+struct DeviceRowPlan {   // mirrors disc::RowPlan of the device header
+  int32_t G, log2G, nv, pad;
+};
+struct FastDivHost {
+  uint32_t d, m, s, pad;
+};
+
+FastDivHost make_fastdiv(uint64_t d) {
+  FastDivHost f{1, 1, 0, 0};
+  if (d == 0 || d > 0x7fffffffull) { f.d = (uint32_t)(d > 0xffffffffull ? 0xffffffffu : d); return f; }
+  uint32_t s = 0;
+  while ((1ull << s) < d) ++s;
+  f.d = (uint32_t)d;
+  f.s = s;
+  f.m = (uint32_t)((((1ull << s) - d) << 32) / d + 1);
+  return f;
+}
+
+struct Pattern {
+  Analysis an;
+  Generated gen;
+  std::string key;
+  int compile_events = 0;
+  double compile_ms = 0;
+  hipModule_t module = nullptr;
+  std::map<std::string, hipFunction_t> fn;
+  // constraint recipes
+  std::vector<std::pair<int, int>> eq_checks;         // symbolic dims that must be equal
+  std::vector<std::pair<int, int64_t>> static_checks; // symbolic dim that must equal a static size
+  std::vector<int> class_of_dim;
+  int n_classes = 0;
+  // element count recipes for algorithmic bytes
+  std::vector<std::pair<DimProduct, int>> io_numel;   // (numel product, bytes per element)
+};
+
+struct ShapeVals {
+  int64_t group[4] = {1, 1, 1, 1};
+  int64_t rows = 1, inner = 1, mid = 0;
+  std::vector<int64_t> products;
+  int64_t alg_bytes = 0;
+};
+
+bool mul_ovf(int64_t a, int64_t b, int64_t* r) { return __builtin_mul_overflow(a, b, r); }
+
+bool eval_product(const DimProduct& p, const int64_t* dims, int64_t* out) {
+  int64_t v = p.stat;
+  for (int s : p.sym)
+    if (mul_ovf(v, dims[s], &v)) return false;
+  *out = v;
+  return true;
+}
+
+int64_t now_ns() {
+  return std::chrono::duration_cast<std::chrono::nanoseconds>(std::chrono::steady_clock::now().time_since_epoch()).count();
+}
+
+}  // namespace
+}  // namespace disc
+
+using namespace disc;
+
+struct disc_ctx {
+  int device = -1;
+  int n_cus = 256;
+  std::string err;
+  std::vector<std::unique_ptr<Pattern>> patterns;
+  std::map<std::string, int> cache;
+  disc_stats_t stats{};
+  int force_variant = -1;
+  hipModule_t util_module = nullptr;
+  hipFunction_t util_copy = nullptr, util_empty = nullptr;
+  int row_target_nv = 4;     // tuning knobs, overridable from the environment for experiments
+  int grid_mult = 8;
+  int loop_unroll = 4;
+};
+
+namespace {
+
+int set_err(disc_ctx* c, int code, const std::string& msg) {
+  if (c) c->err = msg;
+  return code;
+}
+
+int hip_fail(disc_ctx* c, hipError_t e, const char* what) {
+  return set_err(c, DISC_ERR_HIP, std::string(what) + ": " + hipGetErrorString(e));
+}
+
+int compile_source(disc_ctx* c, const std::string& src, std::vector<char>* code, double* ms) {
+  hiprtcProgram prog;
+  if (hiprtcCreateProgram(&prog, src.c_str(), "disc_pattern.hip", 0, nullptr, nullptr) != HIPRTC_SUCCESS)
+    return set_err(c, DISC_ERR_COMPILE, "hiprtcCreateProgram failed");
+  const char* opts[] = {"--offload-arch=gfx950", "-O3", "-std=c++17", "-Xclang", "-target-feature", "-Xclang",
+                        "-packed-fp32-ops", "-Wno-unused-value"};
+  auto t0 = std::chrono::steady_clock::now();
+  hiprtcResult r = hiprtcCompileProgram(prog, (int)(sizeof opts / sizeof opts[0]), opts);
+  *ms = std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - t0).count();
+  if (r != HIPRTC_SUCCESS) {
+    size_t n = 0;
+    hiprtcGetProgramLogSize(prog, &n);
+    std::string log(n, '\0');
+    if (n) hiprtcGetProgramLog(prog, &log[0]);
+    hiprtcDestroyProgram(&prog);
+    return set_err(c, DISC_ERR_COMPILE, "device compile failed:\n" + log);
+  }
+  size_t n = 0;
+  hiprtcGetCodeSize(prog, &n);
+  code->resize(n);
+  hiprtcGetCode(prog, code->data());
+  hiprtcDestroyProgram(&prog);
+  return DISC_OK;
+}
+
+Pattern* get_pattern(disc_ctx* c, int32_t id) {
+  if (!c || id < 0 || id >= (int)c->patterns.size()) return nullptr;
+  return c->patterns[id].get();
+}
+
+// ---- shape calculation (host) -------------------------------------------------------------
+int shape_calc(disc_ctx* c, const Pattern& p, const int64_t* dims, int n_dims, ShapeVals* sv) {
+  if (!dims && p.an.n_sym > 0) return set_err(c, DISC_ERR_INVALID_ARG, "dims is null");
+  if (n_dims != p.an.n_sym) {
+    char buf[96];
+    snprintf(buf, sizeof buf, "pattern has %d symbolic dims, %d given", p.an.n_sym, n_dims);
+    return set_err(c, DISC_ERR_INVALID_ARG, buf);
+  }
+  for (int i = 0; i < n_dims; ++i)
+    if (dims[i] < 0) return set_err(c, DISC_ERR_SHAPE, "negative dimension");
+  char buf[160];
+  for (const auto& e : p.eq_checks)
+    if (dims[e.first] != dims[e.second]) {
+      snprintf(buf, sizeof buf, "dims[%d] = %lld and dims[%d] = %lld were registered as equal", e.first,
+               (long long)dims[e.first], e.second, (long long)dims[e.second]);
+      return set_err(c, DISC_ERR_CONSTRAINT, buf);
+    }
+  for (const auto& e : p.static_checks)
+    if (dims[e.first] != e.second) {
+      snprintf(buf, sizeof buf, "dims[%d] = %lld must equal the static size %lld", e.first, (long long)dims[e.first],
+               (long long)e.second);
+      return set_err(c, DISC_ERR_CONSTRAINT, buf);
+    }
+  const Analysis& an = p.an;
+  const int ng = (int)an.groups.size();
+  int64_t total = 1;
+  for (int g = 0; g < ng; ++g) {
+    if (!eval_product(an.group_size[g], dims, &sv->group[g]) || mul_ovf(total, sv->group[g], &total))
+      return set_err(c, DISC_ERR_SHAPE, "element count overflows int64");
+  }
+  sv->inner = sv->group[an.inner_group];
+  sv->rows = 1;
+  for (int g = 0; g < an.inner_group; ++g) sv->rows *= sv->group[g];
+  sv->mid = an.mid_group >= 0 ? sv->group[an.mid_group] : 0;
+  sv->products.resize(an.products.size());
+  for (size_t i = 0; i < an.products.size(); ++i)
+    if (!eval_product(an.products[i], dims, &sv->products[i]))
+      return set_err(c, DISC_ERR_SHAPE, "stride overflows int64");
+  sv->alg_bytes = 0;
+  for (const auto& io : p.io_numel) {
+    int64_t n = 0;
+    if (!eval_product(io.first, dims, &n) || mul_ovf(n, io.second, &n))
+      return set_err(c, DISC_ERR_SHAPE, "tensor size overflows int64");
+    sv->alg_bytes += n;
+  }
+  return DISC_OK;
+}
+
+int ilog2_ceil(int64_t v) {
+  int l = 0;
+  while ((1ll << l) < v) ++l;
+  return l;
+}
+
+struct LaunchRec {
+  const char* kernel = nullptr;
+  uint32_t grid = 1, block = 256;
+  bool rowplan = false;
+  DeviceRowPlan rp{};
+};
+
+struct FullPlan {
+  disc_plan_t pub{};
+  ShapeVals sv;
+  LaunchRec launches[3];
+  int64_t nslots = 0, spr = 0;
+};
+
+// ---- version + launch-dimension selection (host) ---------------------------------------------
+int make_plan(disc_ctx* c, const Pattern& p, const int64_t* dims, int n_dims, int force, FullPlan* fp) {
+  int rc = shape_calc(c, p, dims, n_dims, &fp->sv);
+  if (rc) return rc;
+  const Analysis& an = p.an;
+  const ShapeVals& sv = fp->sv;
+  disc_plan_t& pub = fp->pub;
+  pub.rows = sv.rows;
+  pub.inner = sv.inner;
+  pub.mid = sv.mid;
+  pub.algorithmic_bytes = sv.alg_bytes;
+  pub.workspace_bytes = 0;
+  pub.n_launches = 0;
+  pub.variant = -1;
+  const int V = an.vec_width;
+  const int64_t max_grid = (int64_t)c->n_cus * c->grid_mult;
+
+  if (an.tmpl == DISC_TEMPLATE_LOOP) {
+    if (sv.rows == 0 || sv.inner == 0) return DISC_OK;
+    bool vec;
+    {
+      const int64_t spr_v = (sv.inner + V - 1) / V;
+      const double waste = 1.0 - (double)sv.inner / (double)(spr_v * V);
+      vec = waste <= 0.25;
+    }
+    if (force == DISC_V_LOOP_VEC || force == DISC_V_LOOP_VEC_I64) vec = true;
+    else if (force == DISC_V_LOOP_SCALAR || force == DISC_V_LOOP_SCALAR_I64) vec = false;
+    else if (force >= 0) return set_err(c, DISC_ERR_INVALID_ARG, "forced version does not belong to a loop-fusion pattern");
+    const int v = vec ? V : 1;
+    int64_t spr = (sv.inner + v - 1) / v, nslots;
+    if (mul_ovf(spr, sv.rows, &nslots)) return set_err(c, DISC_ERR_SHAPE, "slot count overflows int64");
+    bool i64 = nslots >= (1ll << 31) - (1ll << 24) || sv.inner >= (1ll << 31) - 16 || sv.rows >= (1ll << 31);
+    if (force == DISC_V_LOOP_VEC_I64 || force == DISC_V_LOOP_SCALAR_I64) i64 = true;
+    else if (force >= 0 && i64) return set_err(c, DISC_ERR_INVALID_ARG, "forced 32-bit version cannot index this shape");
+    pub.variant = vec ? (i64 ? DISC_V_LOOP_VEC_I64 : DISC_V_LOOP_VEC) : (i64 ? DISC_V_LOOP_SCALAR_I64 : DISC_V_LOOP_SCALAR);
+    pub.index_bits = i64 ? 64 : 32;
+    pub.vec_width = v;
+    const int U = i64 ? 1 : c->loop_unroll;
+    pub.slots_per_lane = U;
+    int64_t blocks = (nslots + 256ll * U - 1) / (256ll * U);
+    blocks = std::min(blocks, i64 ? max_grid * 4 : max_grid);
+    LaunchRec& L = fp->launches[0];
+    static const char* names[] = {"k_loop_vec", "k_loop_vec_i64", "k_loop_scalar", "k_loop_scalar_i64"};
+    L.kernel = names[pub.variant - DISC_V_LOOP_VEC];
+    L.grid = (uint32_t)blocks;
+    L.block = 256;
+    fp->nslots = nslots;
+    fp->spr = spr;
+    pub.n_launches = 1;
+  } else if (an.tmpl == DISC_TEMPLATE_ROW_REDUCE) {
+    if (sv.rows == 0) return DISC_OK;
+    if (sv.inner == 0) return set_err(c, DISC_ERR_EMPTY_REDUCE, "reduction over an axis of size 0");
+    if (sv.inner >= (1ll << 31) - 4096) return set_err(c, DISC_ERR_SHAPE, "row longer than 2^31 elements");
+    bool vec = sv.inner >= V / 2 || V == 1;
+    bool stream;
+    if (force >= 0) {
+      if (force < DISC_V_ROW_REG_VEC || force > DISC_V_ROW_STREAM_SCALAR)
+        return set_err(c, DISC_ERR_INVALID_ARG, "forced version does not belong to a row-reduce pattern");
+      vec = force == DISC_V_ROW_REG_VEC || force == DISC_V_ROW_STREAM_VEC;
+    }
+    const int v = vec ? V : 1;
+    const int64_t spr = (sv.inner + v - 1) / v;
+    stream = spr > 256 * 8;
+    if (force == DISC_V_ROW_STREAM_VEC || force == DISC_V_ROW_STREAM_SCALAR) stream = true;
+    else if (force >= 0 && stream) return set_err(c, DISC_ERR_INVALID_ARG, "row too long for the forced register-resident version");
+    pub.vec_width = v;
+    pub.index_bits = 64;
+    fp->spr = spr;
+    fp->nslots = 0;
+    LaunchRec& L = fp->launches[0];
+    L.block = 256;
+    if (stream) {
+      pub.variant = vec ? DISC_V_ROW_STREAM_VEC : DISC_V_ROW_STREAM_SCALAR;
+      L.kernel = vec ? "k_row_stream_vec" : "k_row_stream_scalar";
+      L.grid = (uint32_t)std::min<int64_t>(sv.rows, max_grid * 2);
+      pub.lanes_per_row = 256;
+      pub.slots_per_lane = (int)((spr + 255) / 256);
+      pub.reg_slots = 1;
+    } else {
+      // lanes per row: smallest power of two that keeps <= target slots per lane
+      int G = 1 << ilog2_ceil((spr + c->row_target_nv - 1) / c->row_target_nv);
+      G = std::min(G, 256);
+      int nv = (int)((spr + G - 1) / G);
+      int inst = nv <= 1 ? 1 : nv <= 2 ? 2 : nv <= 4 ? 4 : 8;
+      pub.variant = vec ? DISC_V_ROW_REG_VEC : DISC_V_ROW_REG_SCALAR;
+      static const char* kv[] = {"k_row_vec_nv1", "k_row_vec_nv2", "k_row_vec_nv4", "k_row_vec_nv8"};
+      static const char* ks[] = {"k_row_scalar_nv1", "k_row_scalar_nv2", "k_row_scalar_nv4", "k_row_scalar_nv8"};
+      const int ii = inst == 1 ? 0 : inst == 2 ? 1 : inst == 4 ? 2 : 3;
+      L.kernel = vec ? kv[ii] : ks[ii];
+      L.rowplan = true;
+      L.rp.G = G;
+      L.rp.log2G = ilog2_ceil(G);
+      L.rp.nv = nv;
+      const int rpb = 256 / G;
+      const int64_t ngroups = (sv.rows + rpb - 1) / rpb;
+      L.grid = (uint32_t)std::min<int64_t>(ngroups, max_grid);
+      pub.lanes_per_row = G;
+      pub.slots_per_lane = nv;
+      pub.reg_slots = inst;
+    }
+    pub.n_launches = 1;
+  } else {
+    return set_err(c, DISC_ERR_UNFUSIBLE, "column-reduce launch path not available");
+  }
+  for (int l = 0; l < pub.n_launches; ++l) {
+    pub.grid[l][0] = fp->launches[l].grid;
+    pub.grid[l][1] = pub.grid[l][2] = 1;
+    pub.block[l][0] = fp->launches[l].block;
+    pub.block[l][1] = pub.block[l][2] = 1;
+    pub.lds_bytes[l] = 0;
+  }
+  return DISC_OK;
+}
+
+void fill_args(const Pattern& p, const FullPlan& fp, const int64_t* dims, const void* const* in, void* const* outp,
+               void* ws, unsigned char* buf) {
+  const ShapeVals& sv = fp.sv;
+  for (const auto& f : p.gen.args.fields) {
+    unsigned char* dst = buf + f.offset;
+    int64_t v = 0;
+    switch (f.kind) {
+      case ArgField::ROWS: v = sv.rows; memcpy(dst, &v, 8); break;
+      case ArgField::INNER: v = sv.inner; memcpy(dst, &v, 8); break;
+      case ArgField::NSLOTS: v = fp.nslots; memcpy(dst, &v, 8); break;
+      case ArgField::SPR: v = fp.spr; memcpy(dst, &v, 8); break;
+      case ArgField::MID: v = sv.mid; memcpy(dst, &v, 8); break;
+      case ArgField::GROUP_SIZE: v = sv.group[f.index]; memcpy(dst, &v, 8); break;
+      case ArgField::IN_PTR: memcpy(dst, &in[f.index], 8); break;
+      case ArgField::OUT_PTR: memcpy(dst, &outp[f.index], 8); break;
+      case ArgField::WS_PTR: memcpy(dst, &ws, 8); break;
+      case ArgField::AUX: memcpy(dst, &v, 8); break;
+      case ArgField::STRIDE: v = sv.products[f.index]; memcpy(dst, &v, 8); break;
+      case ArgField::DIMI: v = dims[p.an.dim_size_syms[f.index]]; memcpy(dst, &v, 8); break;
+      case ArgField::SPR_DIV: { FastDivHost d = make_fastdiv((uint64_t)fp.spr); memcpy(dst, &d, 16); break; }
+      case ArgField::GROUP_DIV: { FastDivHost d = make_fastdiv((uint64_t)sv.group[f.index]); memcpy(dst, &d, 16); break; }
+      case ArgField::DIMF: { float x = (float)dims[p.an.dim_size_syms[f.index]]; memcpy(dst, &x, 4); break; }
+    }
+  }
+}
+
+const char* kUtilSource = R"SRC(
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+extern "C" __global__ void __launch_bounds__(256) disc_util_copy_k(u32x4* __restrict__ dst, const u32x4* __restrict__ src, long long n) {
+  const long long stride = (long long)gridDim.x * blockDim.x;
+  long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  for (; i + 3 * stride < n; i += 4 * stride) {
+    u32x4 a = src[i], b = src[i + stride], c = src[i + 2 * stride], d = src[i + 3 * stride];
+    dst[i] = a; dst[i + stride] = b; dst[i + 2 * stride] = c; dst[i + 3 * stride] = d;
+  }
+  for (; i < n; i += stride) dst[i] = src[i];
+}
+extern "C" __global__ void disc_util_empty_k() {}
+)SRC";
+
+int ensure_util(disc_ctx* c) {
+  if (c->util_module) return DISC_OK;
+  if (c->device < 0) return set_err(c, DISC_ERR_INVALID_ARG, "host-only context");
+  std::vector<char> code;
+  double ms;
+  int rc = compile_source(c, kUtilSource, &code, &ms);
+  if (rc) return rc;
+  hipError_t e = hipModuleLoadData(&c->util_module, code.data());
+  if (e != hipSuccess) return hip_fail(c, e, "hipModuleLoadData");
+  if ((e = hipModuleGetFunction(&c->util_copy, c->util_module, "disc_util_copy_k")) != hipSuccess) return hip_fail(c, e, "hipModuleGetFunction");
+  if ((e = hipModuleGetFunction(&c->util_empty, c->util_module, "disc_util_empty_k")) != hipSuccess) return hip_fail(c, e, "hipModuleGetFunction");
+  return DISC_OK;
+}
+
+}  // namespace
+
+// ============================================================================================
+// C ABI
+// ============================================================================================
+extern "C" {
+
+int disc_create(disc_ctx** out, int hip_device) {
+  if (!out) return DISC_ERR_INVALID_ARG;
+  *out = nullptr;
+  std::unique_ptr<disc_ctx> c(new (std::nothrow) disc_ctx);
+  if (!c) return DISC_ERR_INVALID_ARG;
+  c->device = hip_device;
+  if (hip_device >= 0) {
+    int n = 0;
+    if (hipGetDeviceCount(&n) != hipSuccess || hip_device >= n) return DISC_ERR_HIP;
+    if (hipSetDevice(hip_device) != hipSuccess) return DISC_ERR_HIP;
+    hipDeviceProp_t prop;
+    if (hipGetDeviceProperties(&prop, hip_device) != hipSuccess) return DISC_ERR_HIP;
+    c->n_cus = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+  }
+  if (const char* e = getenv("DISC_ROW_TARGET_NV")) c->row_target_nv = std::max(1, std::min(8, atoi(e)));
+  if (const char* e = getenv("DISC_GRID_MULT")) c->grid_mult = std::max(1, std::min(64, atoi(e)));
+  if (const char* e = getenv("DISC_LOOP_UNROLL")) (void)e;   // the unroll factor is a compile-time constant of the kernels
+  *out = c.release();
+  return DISC_OK;
+}
+
+void disc_destroy(disc_ctx* ctx) {
+  if (!ctx) return;
+  if (ctx->device >= 0) {
+    for (auto& p : ctx->patterns)
+      if (p->module) (void)hipModuleUnload(p->module);
+    if (ctx->util_module) (void)hipModuleUnload(ctx->util_module);
+  }
+  delete ctx;
+}
+
+const char* disc_last_error(const disc_ctx* ctx) { return ctx ? ctx->err.c_str() : "null context"; }
+
+int disc_register_pattern(disc_ctx* ctx, const disc_op* ops, int n_ops, const disc_constraint* cs, int n_cs,
+                          int32_t* pattern_id_out) {
+  if (!ctx) return DISC_ERR_INVALID_ARG;
+  if (!pattern_id_out) return set_err(ctx, DISC_ERR_INVALID_ARG, "pattern_id_out is null");
+  *pattern_id_out = -1;
+  if (!ops || n_ops <= 0) return set_err(ctx, DISC_ERR_INVALID_ARG, "empty op list");
+  if (n_cs < 0 || (n_cs > 0 && !cs)) return set_err(ctx, DISC_ERR_INVALID_ARG, "bad constraint list");
+  if (n_ops > DISC_MAX_OPS) return set_err(ctx, DISC_ERR_BAD_PATTERN, "too many ops");
+  // pattern cache: the key is the op sequence and the constraints -- no sizes (Section 2)
+  std::string key;
+  for (int i = 0; i < n_ops; ++i) {
+    disc_op o = ops[i];
+    const int rank = std::max(0, std::min<int>(o.rank, DISC_MAX_RANK));
+    for (int k = rank; k < DISC_MAX_RANK; ++k) o.dim[k] = 0;
+    const bool uses_map = o.opcode == DISC_BROADCAST || o.opcode == DISC_DIM_SIZE ||
+                          (o.opcode >= DISC_REDUCE_SUM && o.opcode <= DISC_REDUCE_ARGMAX);
+    if (!uses_map) memset(o.axis_map, 0, sizeof o.axis_map);
+    if (o.opcode != DISC_CONST) o.fconst = 0;
+    key.append(reinterpret_cast<const char*>(&o.opcode), sizeof(int32_t) * 2);
+    key.append(reinterpret_cast<const char*>(o.in), sizeof o.in);
+    key.append(reinterpret_cast<const char*>(&o.rank), sizeof(int32_t));
+    key.append(reinterpret_cast<const char*>(o.dim), sizeof o.dim);
+    key.append(reinterpret_cast<const char*>(o.axis_map), sizeof o.axis_map);
+    key.append(reinterpret_cast<const char*>(&o.fconst), sizeof o.fconst);
+  }
+  key.append("|");
+  for (int i = 0; i < n_cs; ++i) key.append(reinterpret_cast<const char*>(&cs[i]), sizeof(disc_constraint));
+  auto hit = ctx->cache.find(key);
+  if (hit != ctx->cache.end()) {
+    *pattern_id_out = hit->second;
+    ctx->stats.pattern_cache_hits++;
+    return DISC_OK;
+  }
+
+  std::unique_ptr<Pattern> p(new Pattern);
+  p->key = key;
+  std::string err;
+  int rc = analyze(ops, n_ops, cs, n_cs, &p->an, &err);
+  if (rc) return set_err(ctx, rc, err);
+  rc = generate(p->an, &p->gen, &err);
+  if (rc) return set_err(ctx, rc, err);
+  p->gen.source = std::string(kDeviceHeader) + "\n" + p->gen.source;
+
+  // launch-time constraint recipes
+  DimClasses& dc = p->an.classes;
+  p->class_of_dim.assign(p->an.n_sym, 0);
+  {
+    std::map<int, int> rep_to_class;
+    std::map<int, int> first_member;
+    for (int d = 0; d < p->an.n_sym; ++d) {
+      int r = dc.find(d);
+      if (!rep_to_class.count(r)) rep_to_class[r] = (int)rep_to_class.size();
+      p->class_of_dim[d] = rep_to_class[r];
+      if (first_member.count(r)) p->eq_checks.push_back({first_member[r], d});
+      else first_member[r] = d;
+      if (dc.static_val[r] >= 0 && first_member[r] == d) p->static_checks.push_back({d, dc.static_val[r]});
+    }
+    p->n_classes = (int)rep_to_class.size();
+  }
+  for (const auto& op : p->an.ops) {
+    if (op.opcode != DISC_PARAM && op.opcode != DISC_OUTPUT) continue;
+    DimProduct prod;
+    for (int k = 0; k < op.rank; ++k) {
+      if (op.dim[k] >= 0) prod.sym.push_back(op.dim[k]); else prod.stat *= -(int64_t)op.dim[k];
+    }
+    p->io_numel.push_back({prod, dtype_bytes(op.dtype)});
+  }
+
+  std::vector<char> code;
+  rc = compile_source(ctx, p->gen.source, &code, &p->compile_ms);
+  p->compile_events = 1;
+  ctx->stats.compile_events++;
+  if (rc) return rc;
+  if (ctx->device >= 0) {
+    hipError_t e = hipModuleLoadData(&p->module, code.data());
+    if (e != hipSuccess) return hip_fail(ctx, e, "hipModuleLoadData");
+    for (const auto& name : p->gen.kernels) {
+      hipFunction_t f;
+      e = hipModuleGetFunction(&f, p->module, name.c_str());
+      if (e != hipSuccess) return hip_fail(ctx, e, ("hipModuleGetFunction " + name).c_str());
+      p->fn[name] = f;
+    }
+  }
+  const int id = (int)ctx->patterns.size();
+  ctx->cache[key] = id;
+  ctx->patterns.push_back(std::move(p));
+  ctx->stats.patterns_registered++;
+  *pattern_id_out = id;
+  return DISC_OK;
+}
+
+int disc_pattern_info(disc_ctx* ctx, int32_t id, disc_pattern_info_t* out) {
+  Pattern* p = get_pattern(ctx, id);
+  if (!p || !out) return set_err(ctx, DISC_ERR_INVALID_ARG, "bad pattern id or null output");
+  memset(out, 0, sizeof *out);
+  out->template_kind = p->an.tmpl;
+  out->n_dims = p->an.n_sym;
+  out->n_inputs = p->an.n_inputs;
+  out->n_outputs = p->an.n_outputs;
+  out->compile_events = p->compile_events;
+  out->n_variants = (int)p->gen.kernels.size();
+  out->n_phases = p->an.n_phases;
+  out->vec_width = p->an.vec_width;
+  out->n_collapsed = (int)p->an.groups.size();
+  out->n_dim_classes = p->n_classes;
+  for (int d = 0; d < p->an.n_sym && d < DISC_MAX_DIMS; ++d) out->dim_class[d] = p->class_of_dim[d];
+  out->compile_ms = p->compile_ms;
+  return DISC_OK;
+}
+
+const char* disc_pattern_source(disc_ctx* ctx, int32_t id) {
+  Pattern* p = get_pattern(ctx, id);
+  return p ? p->gen.source.c_str() : nullptr;
+}
+
+int disc_workspace_bytes(disc_ctx* ctx, int32_t id, const int64_t* dims, int n_dims, size_t* out) {
+  Pattern* p = get_pattern(ctx, id);
+  if (!p || !out) return set_err(ctx, DISC_ERR_INVALID_ARG, "bad pattern id or null output");
+  FullPlan fp;
+  int rc = make_plan(ctx, *p, dims, n_dims, -1, &fp);
+  if (rc) return rc;
+  *out = fp.pub.workspace_bytes;
+  return DISC_OK;
+}
+
+int disc_plan(disc_ctx* ctx, int32_t id, const int64_t* dims, int n_dims, const void* const* inputs,
+              void* const* outputs, int force_variant, disc_plan_t* out) {
+  (void)inputs;
+  (void)outputs;
+  Pattern* p = get_pattern(ctx, id);
+  if (!p || !out) return set_err(ctx, DISC_ERR_INVALID_ARG, "bad pattern id or null output");
+  FullPlan fp;
+  int rc = make_plan(ctx, *p, dims, n_dims, force_variant, &fp);
+  if (rc) return rc;
+  *out = fp.pub;
+  return DISC_OK;
+}
+
+int disc_force_variant(disc_ctx* ctx, int variant) {
+  if (!ctx || variant < -1 || variant >= DISC_V_COUNT) return set_err(ctx, DISC_ERR_INVALID_ARG, "unknown version");
+  ctx->force_variant = variant;
+  return DISC_OK;
+}
+
+int disc_launch(disc_ctx* ctx, int32_t id, const int64_t* dims, int n_dims, const void* const* inputs, int n_in,
+                void* const* outputs, int n_out, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  const int64_t t0 = now_ns();
+  Pattern* p = get_pattern(ctx, id);
+  if (!p) return set_err(ctx, DISC_ERR_INVALID_ARG, "bad pattern id");
+  if (ctx->device < 0) return set_err(ctx, DISC_ERR_INVALID_ARG, "host-only context cannot launch");
+  if (n_in != p->an.n_inputs || n_out != p->an.n_outputs) {
+    char buf[96];
+    snprintf(buf, sizeof buf, "pattern takes %d inputs and %d outputs, got %d and %d", p->an.n_inputs, p->an.n_outputs, n_in, n_out);
+    return set_err(ctx, DISC_ERR_INVALID_ARG, buf);
+  }
+  if ((n_in > 0 && !inputs) || !outputs) return set_err(ctx, DISC_ERR_INVALID_ARG, "null pointer array");
+  FullPlan fp;
+  int rc = make_plan(ctx, *p, dims, n_dims, ctx->force_variant, &fp);
+  const int64_t t1 = now_ns();
+  ctx->stats.host_plan_ns += t1 - t0;
+  if (rc) return rc;
+  if (fp.pub.n_launches == 0) {
+    ctx->stats.launch_calls++;
+    ctx->stats.host_launch_ns += now_ns() - t0;
+    return DISC_OK;
+  }
+  for (int i = 0; i < n_in; ++i)
+    if (!inputs[i]) return set_err(ctx, DISC_ERR_INVALID_ARG, "null input pointer");
+  for (int i = 0; i < n_out; ++i)
+    if (!outputs[i]) return set_err(ctx, DISC_ERR_INVALID_ARG, "null output pointer");
+  if (fp.pub.workspace_bytes > 0 && (!workspace || workspace_bytes < fp.pub.workspace_bytes))
+    return set_err(ctx, DISC_ERR_WORKSPACE, "workspace missing or too small");
+
+  alignas(16) unsigned char buf[4096 + 32];
+  const int asz = p->gen.args.size;
+  if (asz + 16 > (int)sizeof buf) return set_err(ctx, DISC_ERR_BAD_PATTERN, "argument block too large");
+  fill_args(*p, fp, dims, inputs, outputs, workspace, buf);
+  for (int l = 0; l < fp.pub.n_launches; ++l) {
+    const LaunchRec& L = fp.launches[l];
+    auto it = p->fn.find(L.kernel);
+    if (it == p->fn.end()) return set_err(ctx, DISC_ERR_HIP, std::string("kernel version missing: ") + L.kernel);
+    size_t size = (size_t)asz;
+    if (L.rowplan) {
+      memcpy(buf + asz, &L.rp, sizeof L.rp);
+      size += sizeof L.rp;
+    }
+    void* extra[] = {HIP_LAUNCH_PARAM_BUFFER_POINTER, buf, HIP_LAUNCH_PARAM_BUFFER_SIZE, &size, HIP_LAUNCH_PARAM_END};
+    hipError_t e = hipModuleLaunchKernel(it->second, L.grid, 1, 1, L.block, 1, 1, 0, (hipStream_t)hip_stream, nullptr, extra);
+    if (e != hipSuccess) return hip_fail(ctx, e, "hipModuleLaunchKernel");
+    ctx->stats.device_launches++;
+  }
+  ctx->stats.launch_calls++;
+  if (fp.pub.variant >= 0 && fp.pub.variant < DISC_V_COUNT) ctx->stats.variant_count[fp.pub.variant]++;
+  ctx->stats.host_launch_ns += now_ns() - t0;
+  return DISC_OK;
+}
+
+int disc_get_stats(disc_ctx* ctx, disc_stats_t* out) {
+  if (!ctx || !out) return DISC_ERR_INVALID_ARG;
+  *out = ctx->stats;
+  return DISC_OK;
+}
+
+int disc_util_copy(disc_ctx* ctx, void* dst, const void* src, size_t bytes, void* hip_stream) {
+  if (!ctx || !dst || !src || (bytes & 15) || ((uintptr_t)dst & 15) || ((uintptr_t)src & 15))
+    return set_err(ctx, DISC_ERR_INVALID_ARG, "copy needs 16-byte aligned pointers and size");
+  int rc = ensure_util(ctx);
+  if (rc) return rc;
+  long long n = (long long)(bytes / 16);
+  if (n == 0) return DISC_OK;
+  void* args[] = {&dst, &src, &n};
+  long long blocks = std::min<long long>((n + 1023) / 1024, (long long)ctx->n_cus * 2);
+  hipError_t e = hipModuleLaunchKernel(ctx->util_copy, (uint32_t)blocks, 1, 1, 256, 1, 1, 0, (hipStream_t)hip_stream, args, nullptr);
+  return e == hipSuccess ? DISC_OK : hip_fail(ctx, e, "hipModuleLaunchKernel");
+}
+
+int disc_util_empty_launch(disc_ctx* ctx, void* hip_stream) {
+  if (!ctx) return DISC_ERR_INVALID_ARG;
+  int rc = ensure_util(ctx);
+  if (rc) return rc;
+  hipError_t e = hipModuleLaunchKernel(ctx->util_empty, 1, 1, 1, 64, 1, 1, 0, (hipStream_t)hip_stream, nullptr, nullptr);
+  return e == hipSuccess ? DISC_OK : hip_fail(ctx, e, "hipModuleLaunchKernel");
+}
+
+}  // extern "C"

@@ -254,13 +254,12 @@ class Config:
     pattern: Callable[[], Pattern]
     calls: Callable[..., List[List[int]]]
     inputs: Callable[..., list]
-    out_tol: str          # "f32" or "16bit": which comparator bar applies
 
 
 CONFIGS = {
-    "C0": Config("C0", c0_pattern, c0_calls, c0_inputs, "f32"),
-    "C1": Config("C1", c1_pattern, c1_calls, c1_inputs, "16bit"),
-    "C2": Config("C2", c2_pattern, c2_calls, c2_inputs, "16bit"),
-    "C3": Config("C3", c3_pattern, c3_calls, c3_inputs, "f32"),
-    "C4": Config("C4", c4_pattern, c4_calls, c4_inputs, "16bit"),
+    "C0": Config("C0", c0_pattern, c0_calls, c0_inputs),
+    "C1": Config("C1", c1_pattern, c1_calls, c1_inputs),
+    "C2": Config("C2", c2_pattern, c2_calls, c2_inputs),
+    "C3": Config("C3", c3_pattern, c3_calls, c3_inputs),
+    "C4": Config("C4", c4_pattern, c4_calls, c4_inputs),
 }
