@@ -1,0 +1,330 @@
+#!/usr/bin/env python3
+"""Benchmark of the shape-generic fusion kernels on one MI355X.
+
+One "step" = one pass of the whole hot path over the five benchmark configurations' dynamic-shape
+sweeps (C0 8 calls, C1 32, C2 48, C3 200, C4 1000; every call a different runtime shape, every
+pattern compiled once).  Inputs are resident in HBM before the timed region starts.
+
+  value = algorithmic bytes of one step / wall time of one step            (GB/s)
+
+Algorithmic bytes = every input read once + every output written once.  The JSON line also carries
+the roofline of the dominant kernel (the C4 row-reduce version that moves the most bytes), a CPU
+baseline (the unfused fp64 oracle timed on a bounded sample of the same workload) and per-config
+detail.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+from concurrent.futures import ThreadPoolExecutor
+
+import numpy as np
+import torch
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+from workloads.configs import CONFIGS, TORCH_DTYPE, algorithmic_bytes  # noqa: E402
+
+PEAK_HBM_GBPS = 8000.0
+
+
+def _fill_normal(buf: torch.Tensor, seed: int, chunk: int = 1 << 27):
+    g = torch.Generator(device=buf.device)
+    g.manual_seed(seed)
+    flat = buf.view(-1)
+    for a in range(0, flat.numel(), chunk):
+        b = min(flat.numel(), a + chunk)
+        tmp = torch.empty(b - a, dtype=torch.float32, device=buf.device)
+        tmp.normal_(0.0, 1.0, generator=g)
+        flat[a:b] = tmp.to(buf.dtype)
+        del tmp
+
+
+class Arena:
+    """A flat pre-filled device buffer; tensors for a call are views at a rotating offset so that
+    consecutive calls do not re-read what the previous call left in cache."""
+
+    def __init__(self, numel: int, dtype, device, fill, seed):
+        self.buf = torch.empty(numel, dtype=dtype, device=device)
+        self.pos = 0
+        self.align = 256 // self.buf.element_size()
+        if fill == "normal":
+            _fill_normal(self.buf, seed)
+        elif fill == "uniform":
+            g = torch.Generator(device=device)
+            g.manual_seed(seed)
+            self.buf.uniform_(-1.0, 1.0, generator=g)
+        elif fill == "mask":
+            g = torch.Generator(device=device)
+            g.manual_seed(seed)
+            chunk = 1 << 28
+            for a in range(0, numel, chunk):
+                b = min(numel, a + chunk)
+                self.buf[a:b] = (torch.rand(b - a, device=device, generator=g) < 0.1).to(dtype)
+
+    def take(self, shape):
+        n = int(np.prod(shape))
+        if self.pos + n > self.buf.numel():
+            self.pos = 0
+        v = self.buf[self.pos:self.pos + n].view(*shape)
+        self.pos += (n + self.align - 1) // self.align * self.align
+        return v
+
+
+class Sweep:
+    """All calls of one configuration with their device tensors bound."""
+
+    def __init__(self, name, ctx, device):
+        self.name = name
+        self.cfg = CONFIGS[name]
+        self.pattern = self.cfg.pattern()
+        self.handle = ctx.register(self.pattern)
+        self.calls = self.cfg.calls()
+        self.bytes = [algorithmic_bytes(self.pattern, d) for d in self.calls]
+        self.bound = []          # (dims, inputs, outputs, workspace)
+        self.device = device
+        self._bind(ctx)
+
+    def _bind(self, ctx):
+        dev = self.device
+        pat = self.pattern
+        in_shapes = lambda d: [pat.shape_of(i, d) for i in pat.params]
+        out_shapes = lambda d: [pat.shape_of(i, d) for i in pat.outputs]
+        n_in, n_out = len(pat.params), len(pat.outputs)
+        # one arena per tensor slot, sized for twice the largest call (so the offset can rotate)
+        max_in = [max(int(np.prod(in_shapes(d)[k])) for d in self.calls) for k in range(n_in)]
+        max_out = [max(int(np.prod(out_shapes(d)[k])) for d in self.calls) for k in range(n_out)]
+        sum_in = [sum(int(np.prod(in_shapes(d)[k])) for d in self.calls) for k in range(n_in)]
+        arenas_in = []
+        for k, pi in enumerate(pat.params):
+            dt = TORCH_DTYPE[pat.ops[pi].dtype]
+            numel = min(sum_in[k] + 4096 * len(self.calls), 2 * max_in[k] + 4096)
+            fill = "mask" if pat.ops[pi].dtype == "bool" else ("uniform" if self.name == "C3" else "normal")
+            arenas_in.append(Arena(numel, dt, dev, fill, seed=1000 + 17 * k + 101 * int(self.name[1:])))
+        arenas_out = [Arena(2 * max_out[k] + 4096, TORCH_DTYPE[pat.ops[oi].dtype], dev, None, 0)
+                      for k, oi in enumerate(pat.outputs)]
+        ws_need = max(ctx.workspace_bytes(self.handle.id, d) for d in self.calls)
+        self.workspace = torch.empty(max(ws_need, 256), dtype=torch.uint8, device=dev)
+        rng = np.random.default_rng(4242)
+        for d in self.calls:
+            ins = [arenas_in[k].take(s) for k, s in enumerate(in_shapes(d))]
+            if self.name == "C1":
+                # real key-padding mask (0 / -1e4) from per-batch valid lengths
+                B, NH, S = d
+                lens = torch.from_numpy(rng.integers(1, S + 1, size=B)).to(dev)
+                keys = torch.arange(S, device=dev).view(1, 1, 1, S)
+                ins[1] = torch.where(keys < lens.view(B, 1, 1, 1), 0.0, -1.0e4).to(torch.float16).contiguous()
+            if self.name == "C0":
+                ins[1] = ins[1] * 0.02
+            if self.name == "C2":
+                ins[3] = (ins[3].float() * 0.1 + 1.0).to(ins[3].dtype)
+                ins[4] = (ins[4].float() * 0.1).to(ins[4].dtype)
+            outs = [arenas_out[k].take(s) for k, s in enumerate(out_shapes(d))]
+            self.bound.append((d, ins, outs))
+
+    def run_all(self):
+        h, ws = self.handle, self.workspace
+        for d, ins, outs in self.bound:
+            h.launch(d, ins, outs, workspace=ws)
+
+    def run_one(self, i):
+        d, ins, outs = self.bound[i]
+        self.handle.launch(d, ins, outs, workspace=self.workspace)
+
+
+def time_events(fn, stream=None):
+    a = torch.cuda.Event(enable_timing=True)
+    b = torch.cuda.Event(enable_timing=True)
+    a.record()
+    fn()
+    b.record()
+    b.synchronize()
+    return a.elapsed_time(b) * 1e-3
+
+
+def cpu_baseline(sweeps, budget_s=20.0):
+    """Oracle (as it stands) on a bounded sample of the sweep: calls in sweep order, smallest
+    element counts first skipped none, until the time budget is used; row-independent patterns
+    are evaluated in row chunks on a thread pool (numpy releases the GIL inside ufuncs)."""
+    from oracle import run as oracle_run
+    cores = min(os.cpu_count() or 1, 16)
+    pool = ThreadPoolExecutor(max_workers=cores)
+    total_bytes, total_s, n_calls = 0, 0.0, 0
+    per_cfg_budget = budget_s / len(sweeps)
+    detail = {}
+    for sw in sweeps:
+        pat = sw.pattern
+        used, b, n = 0.0, 0, 0
+        order = np.argsort([int(np.prod(d)) for d in sw.calls])      # small shapes first: bounded work
+        for i in order:
+            d, ins, _ = sw.bound[i]
+            if sw.bytes[i] > (1 << 26):
+                continue
+            host = [t.cpu() for t in ins]
+            host = [t.to(torch.float64).numpy() if t.dtype.is_floating_point else t.numpy() for t in host]
+            t0 = time.perf_counter()
+            rows = d[0]
+            row_split = sw.name in ("C0", "C2", "C4") and rows >= 2 * cores
+            if row_split:
+                # rows are independent: same results as one call, evaluated chunk by chunk
+                bounds = np.linspace(0, rows, cores + 1).astype(int)
+                def work(k):
+                    lo, hi = bounds[k], bounds[k + 1]
+                    if hi <= lo:
+                        return None
+                    # slice the operands whose leading axis is the row dim (symbolic dim 0)
+                    sub = [h[lo:hi] if (len(pat.ops[pi].dims) >= 1 and pat.ops[pi].dims[0] == 0) else h
+                           for h, pi in zip(host, pat.params)]
+                    return oracle_run(pat, [hi - lo] + list(d[1:]), sub)[0]
+                list(pool.map(work, range(cores)))
+            else:
+                oracle_run(pat, d, host)
+            dt = time.perf_counter() - t0
+            used += dt
+            b += sw.bytes[i]
+            n += 1
+            if used > per_cfg_budget:
+                break
+        detail[sw.name] = {"calls": n, "seconds": round(used, 3), "GBps": round(b / used / 1e9, 4) if used > 0 else None}
+        total_bytes += b
+        total_s += used
+        n_calls += n
+    pool.shutdown()
+    return {"value": round(total_bytes / total_s / 1e9, 4), "unit": "GB/s", "cores": cores, "kind": "oracle",
+            "sample": f"{n_calls} smallest-first calls of the C0-C4 sweeps (<= 64 MiB each), ~{budget_s:.0f} s of CPU work; "
+                      "C0/C2/C4 row-chunked over a thread pool, C1/C3 one numpy call",
+            "per_config": detail}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--configs", default="C0,C1,C2,C3,C4")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-budget", type=float, default=20.0)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
+        sys.exit(3)
+
+    from paper_2103_05288_amd import Context
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    ctx = Context(0)
+    names = [n for n in args.configs.split(",") if n]
+    t_setup = time.perf_counter()
+    sweeps = [Sweep(n, ctx, dev) for n in names]
+    torch.cuda.synchronize()
+    setup_s = time.perf_counter() - t_setup
+
+    def step():
+        for sw in sweeps:
+            sw.run_all()
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    step_bytes = sum(sum(sw.bytes) for sw in sweeps)
+    ms_per_step = wall / args.steps * 1e3
+    value = step_bytes / (wall / args.steps) / 1e9
+
+    # ---- per-config and per-call device times (HIP events on the launch stream), after the timed region
+    per_cfg = {}
+    dominant = None
+    for sw in sweeps:
+        sw.run_all()
+        torch.cuda.synchronize()
+        t_cfg = min(time_events(sw.run_all) for _ in range(3))
+        per_call = []
+        for i in range(len(sw.calls)):
+            per_call.append(min(time_events(lambda: sw.run_one(i)) for _ in range(2)))
+        plans = [sw.handle.plan(d) for d in sw.calls]
+        by_kernel = {}
+        for i, pl in enumerate(plans):
+            key = f"{pl['variant_name']}/slots{pl['reg_slots']}" if pl["reg_slots"] else pl["variant_name"]
+            e = by_kernel.setdefault(key, {"launches": 0, "bytes": 0, "seconds": 0.0})
+            e["launches"] += 1
+            e["bytes"] += sw.bytes[i]
+            e["seconds"] += per_call[i]
+        long_rows = [i for i, pl in enumerate(plans) if pl["inner"] >= 1024]
+        big = [i for i in range(len(sw.calls)) if sw.bytes[i] >= (32 << 20)]
+        gb = lambda idx: (sum(sw.bytes[i] for i in idx) / max(1e-12, sum(per_call[i] for i in idx)) / 1e9) if idx else None
+        per_cfg[sw.name] = {
+            "calls": len(sw.calls), "bytes": sum(sw.bytes), "sweep_ms": round(t_cfg * 1e3, 4),
+            "GBps_sweep": round(sum(sw.bytes) / t_cfg / 1e9, 1),
+            "GBps_sum_of_calls": round(gb(list(range(len(sw.calls)))), 1),
+            "GBps_rows_ge_1024": None if gb(long_rows) is None else round(gb(long_rows), 1),
+            "GBps_calls_ge_32MiB": None if gb(big) is None else round(gb(big), 1),
+            "median_call_us": round(float(np.median(per_call)) * 1e6, 2),
+            "compile_events": sw.handle.ctx.pattern_info(sw.handle.id)["compile_events"],
+            "compile_ms": round(sw.handle.info["compile_ms"], 1),
+            "kernels": {k: {"launches": v["launches"], "GBps": round(v["bytes"] / v["seconds"] / 1e9, 1),
+                            "avg_us": round(v["seconds"] / v["launches"] * 1e6, 2)} for k, v in by_kernel.items()},
+        }
+        if sw.name == "C4" or dominant is None:
+            k, v = max(by_kernel.items(), key=lambda kv: kv[1]["bytes"])
+            dominant = (sw.name, k, v)
+
+    # ---- practical ceiling (plain 16-byte copy, 1 GiB) and launch floor
+    n_copy = 1 << 30
+    src = torch.empty(n_copy, dtype=torch.uint8, device=dev)
+    dst = torch.empty(n_copy, dtype=torch.uint8, device=dev)
+    src.zero_()
+    ctx.util_copy(dst, src, n_copy)
+    torch.cuda.synchronize()
+    t_copy = min(time_events(lambda: [ctx.util_copy(dst, src, n_copy) for _ in range(10)]) for _ in range(3)) / 10
+    copy_gbps = 2 * n_copy / t_copy / 1e9
+    del src, dst
+    ctx.util_empty_launch()
+    torch.cuda.synchronize()
+    t_empty = time_events(lambda: [ctx.util_empty_launch() for _ in range(1000)]) / 1000
+    st = ctx.stats()
+    host_us = st["host_launch_ns"] / max(1, st["launch_calls"]) / 1e3
+    plan_us = st["host_plan_ns"] / max(1, st["launch_calls"]) / 1e3
+
+    dom_name, dom_kernel, dom = dominant
+    achieved = dom["bytes"] / dom["seconds"] / 1e9
+    roofline = {"bound": "hbm", "kernel": f"{dom_name}:{dom_kernel}", "achieved": round(achieved, 1), "peak": PEAK_HBM_GBPS,
+                "unit": "GB/s", "frac": round(achieved / PEAK_HBM_GBPS, 4), "traffic": None,
+                "launches": dom["launches"], "avg_launch_us": round(dom["seconds"] / dom["launches"] * 1e6, 2),
+                "bytes_per_launch": int(dom["bytes"] / dom["launches"]),
+                "frac_of_copy_ceiling": round(achieved / copy_gbps, 4)}
+
+    out = {
+        "metric": "effective HBM GB/s over the dynamic-shape sweep (C0-C4), one compile per pattern",
+        "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 3), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32 arithmetic (f32 / f16 / bf16 storage, f64 column sums)", "data": "synthetic",
+        "config": {"workload": "+".join(names) + " dynamic-shape sweeps: " +
+                   ", ".join(f"{sw.name} {len(sw.calls)} calls" for sw in sweeps),
+                   "bytes_per_step": step_bytes, "calls_per_step": sum(len(sw.calls) for sw in sweeps)},
+        "pct_of_peak": round(100 * value / PEAK_HBM_GBPS, 2),
+        "roofline": roofline,
+        "copy_ceiling_GBps": round(copy_gbps, 1),
+        "empty_launch_us": round(t_empty * 1e6, 2),
+        "host_launch_us_per_call": round(host_us, 2), "host_plan_us_per_call": round(plan_us, 3),
+        "kernels_compiled_per_pattern": {sw.name: per_cfg[sw.name]["compile_events"] for sw in sweeps},
+        "per_config": per_cfg,
+        "setup_s": round(setup_s, 1),
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(sweeps, args.cpu_budget)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

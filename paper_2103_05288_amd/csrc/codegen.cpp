@@ -142,22 +142,29 @@ struct Gen {
     return fmt("(%s)(%s)", dtype_ctype(dtype), x.c_str());
   }
 
-  // Emits straight-line code computing nodes inside one device function.  `elem_ok` says
-  // whether per-element values may be computed here (slot `s`, element `e` in scope);
-  // per-row values are read from `rc` unless `row_define` lists them as being defined here.
+  // Where a piece of generated code runs; decides where each kind of value is read from.
+  enum Mode {
+    M_ELEM,        // row / loop templates, per element: slot `s`, element `e`, per-row values in `rc`
+    M_ROWLOCAL,    // row / loop templates, per row: row_begin / row_after compute per-row values
+    M_COL_ACCUM,   // column reduce stage 1, per element: values without the reduced axis are inlined
+    M_COL_FINISH,  // column reduce stage 2, per (outer, column): scalars `o`, `c`, accumulator `acc`
+    M_COL_EPI      // column reduce stage 3, per element: reduce results arrive in the slot
+  };
+
+  // Emits straight-line code computing nodes inside one device function.
   struct Fn {
     Gen& g;
     std::ostringstream body;
     std::map<int, std::string> names;
-    bool elem_ok;
-    bool row_local;     // compute per-row values locally instead of reading rc (row_begin / row_after)
-    Fn(Gen& gg, bool e, bool rl) : g(gg), elem_ok(e), row_local(rl) {}
+    Mode mode;
+    Fn(Gen& gg, Mode m) : g(gg), mode(m) {}
 
     std::string val(int id) {
       auto it = names.find(id);
       if (it != names.end()) return it->second;
       const Node& n = g.an.nodes[id];
       std::string r;
+      const bool col = mode == M_COL_ACCUM || mode == M_COL_FINISH || mode == M_COL_EPI;
       if (n.opcode == DISC_CONST) {
         if (n.rk == RK_F32) r = float_lit(n.fconst);
         else if (n.rk == RK_BOOL) r = n.fconst != 0 ? "true" : "false";
@@ -165,13 +172,23 @@ struct Gen {
       } else if (n.opcode == DISC_DIM_SIZE) {
         if (n.rk == RK_F32) r = fmt("A.dimf%d", g.dim_index(n.sym_dim));
         else r = fmt("(%s)A.dimi%d", reg_ctype(n.rk), g.dim_index(n.sym_dim));
-      } else if (n.dom == DOM_ROW && !row_local) {
-        r = fmt("rc.r%d", id);
       } else if (n.opcode == DISC_PARAM) {
         const Access& a = g.an.accesses[n.access];
-        if (n.dom == DOM_ELEM) r = from_storage(fmt("s.a%d.v[e]", n.access), a.dtype);
-        else r = fmt("rc.r%d", id);   // loaded by row_begin
+        if (mode == M_COL_FINISH) {
+          // a scalar load at (outer index o, column c); the operand has no reduced axis here
+          std::string off = a.has_inner ? (a.groups.size() > 1 ? "o * A.inner + c" : "c")
+                                        : (a.groups.empty() ? "0" : "o");
+          r = from_storage(fmt("A.p%d[%s]", a.slot, off.c_str()), a.dtype);
+        } else if (a.has_inner) {
+          r = from_storage(fmt("s.a%d.v[e]", n.access), a.dtype);
+        } else {
+          r = fmt("rc.r%d", id);   // loaded by row_begin
+        }
       } else if (g.is_reduce(n.opcode)) {
+        if (mode == M_COL_FINISH) r = g.acc_value(n, "acc");
+        else if (mode == M_COL_EPI) r = fmt("s.red%d.v[e]", n.reduce_slot);
+        else r = fmt("rc.r%d", id);
+      } else if (!col && n.dom == DOM_ROW && mode == M_ELEM) {
         r = fmt("rc.r%d", id);
       } else {
         r = fmt("t%d", id);
@@ -217,6 +234,23 @@ struct Gen {
     }
   };
 
+  bool col_tmpl() const { return an.tmpl == DISC_TEMPLATE_COL_REDUCE; }
+  // accumulator C type of a reduction: long column sums of fp32 data run in fp64 (values near
+  // zero must still meet the absolute part of the fp32 tolerance after cancellation)
+  std::string acc_ctype(const Node& n) const {
+    RegKind ok = an.nodes[n.in[0]].rk;
+    if (col_tmpl() && n.opcode == DISC_REDUCE_SUM && ok == RK_F32) return "double";
+    return reg_ctype(ok);
+  }
+  // reduce result as a register value of the node's kind, read from accumulator `acc`
+  std::string acc_value(const Node& n, const std::string& acc) const {
+    RegKind ok = an.nodes[n.in[0]].rk;
+    if (n.opcode == DISC_REDUCE_ARGMAX) return convert(acc + "." + acci(n.reduce_slot), RK_I32, n.rk);
+    std::string f = acc + "." + accf(n.reduce_slot);
+    if (acc_ctype(n) == "double") f = "(float)" + f;
+    return convert(f, ok, n.rk);
+  }
+
   std::string row_fields() {
     std::ostringstream o;
     for (size_t i = 0; i < an.accesses.size(); ++i) {
@@ -226,13 +260,15 @@ struct Gen {
     }
     for (size_t i = 0; i < an.nodes.size(); ++i) {
       const Node& n = an.nodes[i];
-      if (n.dom == DOM_ROW) o << "    " << reg_ctype(n.rk) << " r" << i << ";\n";
+      const bool perrow_param = n.opcode == DISC_PARAM && !an.accesses[n.access].has_inner;
+      if ((!col_tmpl() && n.dom == DOM_ROW) || perrow_param) o << "    " << reg_ctype(n.rk) << " r" << i << ";\n";
     }
+    if (col_tmpl()) o << "    disc::i64 ob;\n";   // offset of this row's outer slice in the reduce-result planes
     o << "    int unused_;\n";
     return o.str();
   }
 
-  // offset expression of a per-row (no inner) access for row `row`
+  // offset expression of an access without the inner group, for row `row`
   std::string perrow_offset(const Access& a, size_t idx) {
     switch (a.kind) {
       case ACC_PERROW: return "row";
@@ -244,7 +280,8 @@ struct Gen {
   void emit_row_begin() {
     os << "  static DISC_DEV void row_begin(const Args& A, disc::i64 row, RowCtx& rc) {\n";
     const int n_outer = an.inner_group;
-    if (an.needs_decomp) {
+    const bool decomp = an.needs_decomp || (col_tmpl() && an.mid_group == 1);
+    if (decomp) {
       os << "    disc::i64 ig[4] = {0, 0, 0, 0};\n";
       os << "    if (A.rows < 2147483648LL) {\n      disc::u32 t = (disc::u32)row;\n";
       for (int g = n_outer - 1; g >= 1; --g)
@@ -254,6 +291,7 @@ struct Gen {
         os << fmt("      { disc::i64 q = t / A.gs%d; ig[%d] = t - q * A.gs%d; t = q; }\n", g, g, g);
       os << "      ig[0] = t;\n    }\n";
     }
+    if (col_tmpl()) os << (an.mid_group == 1 ? "    rc.ob = ig[0] * A.inner;\n" : "    rc.ob = 0;\n");
     for (size_t i = 0; i < an.accesses.size(); ++i) {
       const Access& a = an.accesses[i];
       if (a.kind == ACC_PARTIAL) {
@@ -270,16 +308,16 @@ struct Gen {
         os << "    rc.b" << i << " = row * A.inner;\n";
       }
     }
-    Fn fn(*this, false, true);
+    Fn fn(*this, M_ROWLOCAL);
     for (size_t i = 0; i < an.nodes.size(); ++i) {
       const Node& n = an.nodes[i];
-      if (n.dom != DOM_ROW || n.phase != 0) continue;
       if (n.opcode == DISC_PARAM) {
         const Access& a = an.accesses[n.access];
+        if (a.has_inner) continue;
         std::string off = perrow_offset(a, n.access);
         fn.body << "    rc.r" << i << " = " << from_storage(fmt("A.p%d[%s]", a.slot, off.c_str()), a.dtype) << ";\n";
         fn.names[(int)i] = fmt("rc.r%zu", i);
-      } else {
+      } else if (!col_tmpl() && n.dom == DOM_ROW && n.phase == 0) {
         std::string v = fn.val((int)i);
         fn.body << "    rc.r" << i << " = " << v << ";\n";
         fn.names[(int)i] = fmt("rc.r%zu", i);
@@ -289,19 +327,49 @@ struct Gen {
     os << "    (void)A; (void)row; (void)rc;\n  }\n";
   }
 
-  void emit_slots() {
+  // Which operand accesses a stage needs in its slot: all of them, or only those reachable from
+  // the values the stage computes (keeps the epilogue of a column reduce from loading operands
+  // that only feed the reduction).
+  std::vector<char> accesses_needed(const std::vector<int>& roots, bool stop_at_reduce) {
+    std::vector<char> need(an.accesses.size(), 0), seen(an.nodes.size(), 0);
+    std::vector<int> stack(roots);
+    while (!stack.empty()) {
+      int id = stack.back();
+      stack.pop_back();
+      if (seen[id]) continue;
+      seen[id] = 1;
+      const Node& n = an.nodes[id];
+      if (n.opcode == DISC_PARAM) need[n.access] = 1;
+      if (stop_at_reduce && is_reduce(n.opcode)) continue;
+      for (int k = 0; k < n.n_in; ++k) stack.push_back(n.in[k]);
+    }
+    return need;
+  }
+
+  void emit_slots(const std::vector<char>& need, bool with_red) {
     os << "  template <int V> struct Slot {\n";
     for (size_t i = 0; i < an.accesses.size(); ++i) {
       const Access& a = an.accesses[i];
-      if (!a.is_output && a.has_inner) os << "    disc::Vec<" << dtype_ctype(a.dtype) << ", V> a" << i << ";\n";
+      if (!a.is_output && a.has_inner && need[i]) os << "    disc::Vec<" << dtype_ctype(a.dtype) << ", V> a" << i << ";\n";
     }
+    if (with_red)
+      for (int id : an.reduces[0])
+        os << "    disc::Vec<" << reg_ctype(an.nodes[id].rk) << ", V> red" << an.nodes[id].reduce_slot << ";\n";
     os << "    int unused_;\n  };\n";
     os << "  template <int V> struct OutSlot {\n";
     for (size_t i = 0; i < an.accesses.size(); ++i) {
       const Access& a = an.accesses[i];
-      if (a.is_output && a.has_inner) os << "    disc::Vec<" << dtype_ctype(a.dtype) << ", V> o" << a.slot << ";\n";
+      if (a.is_output && a.has_inner && elem_output(a)) os << "    disc::Vec<" << dtype_ctype(a.dtype) << ", V> o" << a.slot << ";\n";
     }
     os << "    int unused_;\n  };\n";
+  }
+
+  // outputs written per element by the epilogue (column reduce: only those that keep the reduced axis)
+  bool elem_output(const Access& a) const {
+    if (!a.has_inner) return false;
+    if (!col_tmpl()) return true;
+    for (int g : a.groups) if (g == an.mid_group) return true;
+    return false;
   }
 
   std::string elem_base(const Access& a, size_t i) {
@@ -309,18 +377,27 @@ struct Gen {
     return fmt("rc.b%zu + col", i);
   }
 
-  void emit_load_store() {
+  void emit_load_store(const std::vector<char>& need, bool with_red) {
     os << "  template <int V, class C> static DISC_DEV void load(const Args& A, const RowCtx& rc, C col, int nvalid, Slot<V>& s) {\n";
     for (size_t i = 0; i < an.accesses.size(); ++i) {
       const Access& a = an.accesses[i];
-      if (a.is_output || !a.has_inner) continue;
+      if (a.is_output || !a.has_inner || !need[i]) continue;
       os << "    disc::ld(s.a" << i << ", A.p" << a.slot << ", " << elem_base(a, i) << ", nvalid);\n";
+    }
+    if (with_red) {
+      int k = 0;
+      for (int id : an.reduces[0]) {
+        const Node& n = an.nodes[id];
+        os << "    disc::ld(s.red" << n.reduce_slot << ", reinterpret_cast<const " << reg_ctype(n.rk)
+           << "*>(reinterpret_cast<const char*>(A.ws1) + " << k << " * A.aux1), rc.ob + col, nvalid);\n";
+        ++k;
+      }
     }
     os << "    (void)A; (void)rc; (void)col; (void)nvalid; (void)s;\n  }\n";
     os << "  template <int V, class C> static DISC_DEV void store(const Args& A, const RowCtx& rc, C col, int nvalid, const OutSlot<V>& o) {\n";
     for (size_t i = 0; i < an.accesses.size(); ++i) {
       const Access& a = an.accesses[i];
-      if (!a.is_output || !a.has_inner) continue;
+      if (!a.is_output || !elem_output(a)) continue;
       os << "    disc::st(A.o" << a.slot << ", " << elem_base(a, i) << ", o.o" << a.slot << ", nvalid);\n";
     }
     os << "    (void)A; (void)rc; (void)col; (void)nvalid; (void)o;\n  }\n";
@@ -337,9 +414,9 @@ struct Gen {
       int bytes = 0;
       for (int id : an.reduces[p]) {
         const Node& n = an.nodes[id];
-        RegKind ok = an.nodes[n.in[0]].rk;
-        os << "  " << reg_ctype(ok) << " " << accf(n.reduce_slot) << ";\n";
-        bytes += ok == RK_I64 ? 8 : 4;
+        const std::string ct = acc_ctype(n);
+        os << "  " << ct << " " << accf(n.reduce_slot) << ";\n";
+        bytes += (ct == "double" || ct == "disc::i64") ? 8 : 4;
         if (n.opcode == DISC_REDUCE_ARGMAX) { os << "  int " << acci(n.reduce_slot) << ";\n"; bytes += 4; }
       }
       os << "};\n";
@@ -355,7 +432,7 @@ struct Gen {
   std::string identity(const Node& n) {
     RegKind ok = an.nodes[n.in[0]].rk;
     switch (n.opcode) {
-      case DISC_REDUCE_SUM: return ok == RK_F32 ? "0.0f" : "0";
+      case DISC_REDUCE_SUM: return acc_ctype(n) == "double" ? "0.0" : ok == RK_F32 ? "0.0f" : "0";
       case DISC_REDUCE_MIN: return ok == RK_F32 ? "__builtin_inff()" : ok == RK_I64 ? "9223372036854775807LL" : "2147483647";
       default: return ok == RK_F32 ? "(-__builtin_inff())" : ok == RK_I64 ? "(-9223372036854775807LL - 1)" : "(-2147483647 - 1)";
     }
@@ -413,11 +490,11 @@ struct Gen {
       os << "    }\n";
     }
     os << "    (void)a; (void)m;\n  }\n";
-    // accumulate one element
+    // accumulate one element; `col` is the index along the reduced axis (for argmax)
     os << "  template <int P, int V> static DISC_DEV void accum(const Args& A, Acc<P>& acc, const Slot<V>& s, int e, int col, const RowCtx& rc) {\n";
     for (int p = 0; p < an.n_phases; ++p) {
       os << "    if constexpr (P == " << p << ") {\n";
-      Fn fn(*this, true, false);
+      Fn fn(*this, col_tmpl() ? M_COL_ACCUM : M_ELEM);
       std::ostringstream tail;
       for (int id : an.reduces[p]) {
         const Node& n = an.nodes[id];
@@ -441,17 +518,15 @@ struct Gen {
       os << fn.body.str() << tail.str() << "    }\n";
     }
     os << "    (void)A; (void)acc; (void)s; (void)e; (void)col; (void)rc;\n  }\n";
+    if (col_tmpl()) return;
     // per-row values known after phase P
     os << "  template <int P> static DISC_DEV void row_after(const Args& A, RowCtx& rc, const Acc<P>& acc) {\n";
     for (int p = 0; p < an.n_phases; ++p) {
       os << "    if constexpr (P == " << p << ") {\n";
-      Fn fn(*this, false, true);
+      Fn fn(*this, M_ROWLOCAL);
       for (int id : an.reduces[p]) {
         const Node& n = an.nodes[id];
-        RegKind ok = an.nodes[n.in[0]].rk;
-        std::string src = n.opcode == DISC_REDUCE_ARGMAX ? "acc." + acci(n.reduce_slot) : "acc." + accf(n.reduce_slot);
-        RegKind sk = n.opcode == DISC_REDUCE_ARGMAX ? RK_I32 : ok;
-        fn.body << "    rc.r" << id << " = " << convert(src, sk, n.rk) << ";\n";
+        fn.body << "    rc.r" << id << " = " << acc_value(n, "acc") << ";\n";
       }
       // earlier per-row values are read back from rc
       for (size_t i = 0; i < an.nodes.size(); ++i) {
@@ -471,30 +546,83 @@ struct Gen {
     os << "    (void)A; (void)rc; (void)acc;\n  }\n";
   }
 
-  void emit_epilogue() {
+  void emit_epilogue(Mode mode) {
     os << "  template <int V, class C> static DISC_DEV void epilogue(const Args& A, const RowCtx& rc, const Slot<V>& s, C col, OutSlot<V>& o) {\n";
     os << "#pragma unroll\n    for (int e = 0; e < V; ++e) {\n";
-    Fn fn(*this, true, false);
+    Fn fn(*this, mode);
     std::ostringstream tail;
     for (const auto& out : an.outputs) {
       const Access& a = an.accesses[out.access];
-      if (!a.has_inner) continue;
+      if (!elem_output(a)) continue;
       const Node& n = an.nodes[out.node];
       tail << "    o.o" << a.slot << ".v[e] = " << to_storage(fn.val(out.node), n.rk, a.dtype) << ";\n";
     }
     os << fn.body.str() << tail.str();
     os << "    }\n    (void)A; (void)rc; (void)s; (void)col; (void)o;\n  }\n";
     os << "  static DISC_DEV void row_store(const Args& A, disc::i64 row, const RowCtx& rc) {\n";
-    for (const auto& out : an.outputs) {
-      const Access& a = an.accesses[out.access];
-      if (a.has_inner) continue;
-      const Node& n = an.nodes[out.node];
-      std::string off = a.kind == ACC_PERROW ? "row" : a.kind == ACC_SCALAR ? "0" : fmt("rc.b%d", out.access);
-      Fn fn2(*this, false, false);
-      os << "    A.o" << a.slot << "[" << off << "] = " << to_storage(fn2.val(out.node), n.rk, a.dtype) << ";\n";
+    if (!col_tmpl()) {
+      for (const auto& out : an.outputs) {
+        const Access& a = an.accesses[out.access];
+        if (a.has_inner) continue;
+        const Node& n = an.nodes[out.node];
+        std::string off = a.kind == ACC_PERROW ? "row" : a.kind == ACC_SCALAR ? "0" : fmt("rc.b%d", out.access);
+        Fn fn2(*this, M_ELEM);
+        os << "    A.o" << a.slot << "[" << off << "] = " << to_storage(fn2.val(out.node), n.rk, a.dtype) << ";\n";
+      }
     }
     os << "    (void)A; (void)row; (void)rc;\n  }\n";
   }
+
+  // ---- column reduce: partial-accumulator planes and the finish step -------------------------
+  // Workspace ws0 holds one 8-byte cell per (accumulator field, outer, chunk, column); ws1 holds
+  // the final reduce results, one plane per reduction, typed as the reduce result's register kind.
+  void emit_col_extras() {
+    os << "  static DISC_DEV void acc_st(const Args& A, disc::i64 idx, const Acc<0>& a) {\n";
+    int k = 0;
+    auto cell = [&](const std::string& ct, const std::string& field, bool store) {
+      std::string wide = (ct == "float" || ct == "double") ? "double" : "disc::i64";
+      if (store) os << "    reinterpret_cast<" << wide << "*>(A.ws0)[" << k << " * A.aux0 + idx] = (" << wide << ")a." << field << ";\n";
+      else os << "    a." << field << " = (" << ct << ")reinterpret_cast<const " << wide << "*>(A.ws0)[" << k << " * A.aux0 + idx];\n";
+      ++k;
+    };
+    for (int id : an.reduces[0]) {
+      const Node& n = an.nodes[id];
+      cell(acc_ctype(n), accf(n.reduce_slot), true);
+      if (n.opcode == DISC_REDUCE_ARGMAX) cell("int", acci(n.reduce_slot), true);
+    }
+    os << "    (void)A; (void)idx; (void)a;\n  }\n";
+    n_acc_cells = k;
+    k = 0;
+    os << "  static DISC_DEV void acc_ld(const Args& A, disc::i64 idx, Acc<0>& a) {\n";
+    for (int id : an.reduces[0]) {
+      const Node& n = an.nodes[id];
+      cell(acc_ctype(n), accf(n.reduce_slot), false);
+      if (n.opcode == DISC_REDUCE_ARGMAX) cell("int", acci(n.reduce_slot), false);
+    }
+    os << "    (void)A; (void)idx; (void)a;\n  }\n";
+    // finish: one (outer index o, column c); writes the reduce-result planes and every output that
+    // has lost the reduced axis
+    os << "  static DISC_DEV void col_finish(const Args& A, disc::i64 o, disc::i64 c, const Acc<0>& acc) {\n";
+    Fn fn(*this, M_COL_FINISH);
+    std::ostringstream tail;
+    k = 0;
+    for (int id : an.reduces[0]) {
+      const Node& n = an.nodes[id];
+      tail << "    reinterpret_cast<" << reg_ctype(n.rk) << "*>(reinterpret_cast<char*>(A.ws1) + " << k
+           << " * A.aux1)[o * A.inner + c] = " << fn.val(id) << ";\n";
+      ++k;
+    }
+    for (const auto& out : an.outputs) {
+      const Access& a = an.accesses[out.access];
+      if (elem_output(a)) continue;
+      const Node& n = an.nodes[out.node];
+      std::string off = a.groups.size() > 1 ? "o * A.inner + c" : "c";
+      tail << "    A.o" << a.slot << "[" << off << "] = " << to_storage(fn.val(out.node), n.rk, a.dtype) << ";\n";
+    }
+    os << fn.body.str() << tail.str();
+    os << "    (void)A; (void)o; (void)c; (void)acc;\n  }\n";
+  }
+  int n_acc_cells = 0;
 
   void emit_args() {
     os << "  struct Args {\n";
@@ -504,52 +632,106 @@ struct Gen {
 
   void emit_kernels(Generated* out) {
     const int V = an.vec_width;
-    auto k = [&](const std::string& name, const std::string& body, bool rowplan) {
+    auto k = [&](const std::string& name, const std::string& body, const char* plan) {
       os << "extern \"C\" __global__ void __launch_bounds__(256) " << name << "(Pat::Args A"
-         << (rowplan ? ", disc::RowPlan rp" : "") << ") { " << body << " }\n";
+         << (plan ? std::string(", disc::") + plan + " rp" : std::string()) << ") { " << body << " }\n";
       out->kernels.push_back(name);
     };
     if (an.tmpl == DISC_TEMPLATE_LOOP) {
-      k("k_loop_vec", fmt("disc::kloop_body<Pat, %d, 4, false>(A);", V), false);
-      k("k_loop_vec_i64", fmt("disc::kloop_body<Pat, %d, 1, true>(A);", V), false);
-      k("k_loop_scalar", "disc::kloop_body<Pat, 1, 4, false>(A);", false);
-      k("k_loop_scalar_i64", "disc::kloop_body<Pat, 1, 1, true>(A);", false);
+      k("k_loop_vec", fmt("disc::kloop_body<Pat, %d, 4, false>(A);", V), nullptr);
+      k("k_loop_vec_i64", fmt("disc::kloop_body<Pat, %d, 1, true>(A);", V), nullptr);
+      k("k_loop_scalar", "disc::kloop_body<Pat, 1, 4, false>(A);", nullptr);
+      k("k_loop_scalar_i64", "disc::kloop_body<Pat, 1, 1, true>(A);", nullptr);
     } else if (an.tmpl == DISC_TEMPLATE_ROW_REDUCE) {
       for (int nv : {1, 2, 4, 8}) {
-        k(fmt("k_row_vec_nv%d", nv), fmt("disc::row_reg_body<Pat, %d, %d>(A, rp);", V, nv), true);
-        k(fmt("k_row_scalar_nv%d", nv), fmt("disc::row_reg_body<Pat, 1, %d>(A, rp);", nv), true);
+        k(fmt("k_row_vec_nv%d", nv), fmt("disc::row_reg_body<Pat, %d, %d>(A, rp);", V, nv), "RowPlan");
+        k(fmt("k_row_scalar_nv%d", nv), fmt("disc::row_reg_body<Pat, 1, %d>(A, rp);", nv), "RowPlan");
       }
-      k("k_row_stream_vec", fmt("disc::row_stream_body<Pat, %d>(A);", V), false);
-      k("k_row_stream_scalar", "disc::row_stream_body<Pat, 1>(A);", false);
+      k("k_row_stream_vec", fmt("disc::row_stream_body<Pat, %d>(A);", V), nullptr);
+      k("k_row_stream_scalar", "disc::row_stream_body<Pat, 1>(A);", nullptr);
+    } else {
+      k("k_col_partial_vec", fmt("disc::col_partial_body<Pat, %d>(A, rp);", V), "ColPlan");
+      k("k_col_partial_scalar", "disc::col_partial_body<Pat, 1>(A, rp);", "ColPlan");
+      k("k_col_finish", "disc::col_finish_body<Pat>(A, rp);", "ColPlan");
+      if (has_elem_outputs()) {
+        k("k_col_epi_vec", fmt("disc::kloop_body<PatE, %d, 4, false>(A);", V), nullptr);
+        k("k_col_epi_vec_i64", fmt("disc::kloop_body<PatE, %d, 1, true>(A);", V), nullptr);
+        k("k_col_epi_scalar", "disc::kloop_body<PatE, 1, 4, false>(A);", nullptr);
+        k("k_col_epi_scalar_i64", "disc::kloop_body<PatE, 1, 1, true>(A);", nullptr);
+      }
     }
   }
 
+  bool has_elem_outputs() const {
+    for (const auto& out : an.outputs)
+      if (elem_output(an.accesses[out.access])) return true;
+    return false;
+  }
+
   int run(Generated* out, std::string* err) {
-    if (an.tmpl == DISC_TEMPLATE_COL_REDUCE) {
-      *err = "column-reduction code generation is not available in this build";
-      return DISC_ERR_UNFUSIBLE;
+    if (col_tmpl()) {
+      for (const auto& a : an.accesses) {
+        if (a.kind == ACC_PARTIAL && a.has_inner) {
+          // [outer, inner] operands are addressed through rc.b like any strided operand: fine
+        }
+      }
     }
+    (void)err;
     build_layout();
     os << "// generated: one fused pattern, every kernel version\n";
     emit_acc_types();
+    std::vector<char> all(an.accesses.size(), 1);
     os << "struct Pat {\n";
     os << "  static constexpr int NPHASE = " << an.n_phases << ";\n";
     os << "  static constexpr int MAX_ACC_BYTES = " << acc_bytes << ";\n";
     os << "  template <int P> using Acc = typename PatAccSel<P>::type;\n";
     emit_args();
     os << "  struct RowCtx {\n" << row_fields() << "  };\n";
-    emit_slots();
-    emit_row_begin();
-    emit_load_store();
-    emit_acc_fns();
-    emit_epilogue();
-    os << "};\n";
+    if (!col_tmpl()) {
+      emit_slots(all, false);
+      emit_row_begin();
+      emit_load_store(all, false);
+      emit_acc_fns();
+      emit_epilogue(M_ELEM);
+      os << "};\n";
+    } else {
+      // stage 1 + 2: operands that feed the reductions
+      std::vector<int> roots;
+      for (int id : an.reduces[0]) roots.push_back(an.nodes[id].in[0]);
+      std::vector<char> need1 = accesses_needed(roots, true);
+      emit_slots(need1, false);
+      emit_row_begin();
+      emit_load_store(need1, false);
+      emit_acc_fns();
+      emit_col_extras();
+      os << "  static constexpr int N_ACC_CELLS = " << n_acc_cells << ";\n";
+      os << "};\n";
+      if (has_elem_outputs()) {
+        // stage 3: the epilogue as a loop fusion that reads the reduce results as column vectors
+        std::vector<int> eroots;
+        for (const auto& o2 : an.outputs)
+          if (elem_output(an.accesses[o2.access])) eroots.push_back(o2.node);
+        std::vector<char> need3 = accesses_needed(eroots, true);
+        os << "struct PatE {\n";
+        os << "  static constexpr int NPHASE = 0;\n  static constexpr int MAX_ACC_BYTES = 8;\n";
+        os << "  template <int P> using Acc = int;\n";
+        os << "  typedef Pat::Args Args;\n  typedef Pat::RowCtx RowCtx;\n";
+        emit_slots(need3, true);
+        os << "  static DISC_DEV void row_begin(const Args& A, disc::i64 row, RowCtx& rc) { Pat::row_begin(A, row, rc); }\n";
+        emit_load_store(need3, true);
+        emit_epilogue(M_COL_EPI);
+        os << "};\n";
+      }
+    }
     os << "static_assert(sizeof(Pat::Args) == " << layout.size << ", \"argument block layout\");\n";
     for (const auto& f : layout.fields)
       os << "static_assert(__builtin_offsetof(Pat::Args, " << field_name(f) << ") == " << f.offset << ", \"argument block layout\");\n";
     emit_kernels(out);
     out->source = os.str();
     out->args = layout;
+    out->n_acc_cells = n_acc_cells;
+    out->n_red_planes = col_tmpl() ? (int)an.reduces[0].size() : 0;
+    out->has_epilogue = col_tmpl() ? has_elem_outputs() : true;
     return DISC_OK;
   }
 };

@@ -327,4 +327,112 @@ DISC_DEV void row_stream_body(const typename Pat::Args& A) {
   }
 }
 
+// =======================================================================================
+// Input fusion with a column reduction as root (reduce over an outer axis).  Canonical
+// space [outer, mid, inner], `mid` reduced.  Three stages, no atomics, so results are
+// bit-identical from run to run:
+//   1. col_partial: the reduced axis is cut into chunks; a block owns one chunk of one column
+//      tile.  Lanes run along `inner` (coalesced, V elements each), the block's row-lanes
+//      stride over the rows of the chunk with four rows in flight; every lane keeps V column
+//      accumulators (fp64 for fp32 sums).  The row-lanes of a column are combined through an
+//      LDS transpose in fixed order and one partial per (chunk, column) goes to the workspace.
+//   2. col_finish:  per column, partials are merged in fixed order; values and outputs that
+//      no longer have the reduced axis (sum, mean, ...) are produced here.
+//   3. the epilogue is a loop fusion (kloop_body) that reads the reduce results as column
+//      vectors -- the tensor is read a second time, from Infinity Cache when it fits.
+// =======================================================================================
+struct ColPlan {
+  int GC;          // lanes along inner per block, power of two <= 64
+  int log2GC;
+  int nchunk;      // chunks of the reduced axis
+  int pad;
+  i64 chunk_rows;  // rows per chunk
+  i64 outer;
+};
+
+template <class Pat, int V>
+DISC_DEV void col_partial_body(const typename Pat::Args& A, const ColPlan& cp) {
+  typedef typename Pat::template Acc<0> AccT;
+  __shared__ AccT lds[256 * V];
+  const int tx = threadIdx.x & (cp.GC - 1);
+  const int ty = threadIdx.x >> cp.log2GC;
+  const int TY = blockDim.x >> cp.log2GC;
+  const i64 col = ((i64)blockIdx.x * cp.GC + tx) * V;
+  const i64 rem = A.inner - col;
+  const int nvalid = rem <= 0 ? 0 : (rem < (i64)V ? (int)rem : V);
+  const i64 chunk = blockIdx.y;
+  const i64 m0 = chunk * cp.chunk_rows;
+  const i64 m1 = m0 + cp.chunk_rows < A.mid ? m0 + cp.chunk_rows : A.mid;
+  for (i64 o = blockIdx.z; o < cp.outer; o += gridDim.z) {
+    AccT acc[V];
+#pragma unroll
+    for (int e = 0; e < V; ++e) Pat::template acc_init<0>(acc[e]);
+    if (nvalid > 0) {
+      i64 m = m0 + ty;
+      for (; m + 3 * TY < m1; m += 4 * TY) {
+        typename Pat::template Slot<V> s[4];
+        typename Pat::RowCtx rc[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          Pat::row_begin(A, o * A.mid + m + u * TY, rc[u]);
+          Pat::template load<V>(A, rc[u], col, nvalid, s[u]);
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+#pragma unroll
+          for (int e = 0; e < V; ++e)
+            if (e < nvalid) Pat::template accum<0, V>(A, acc[e], s[u], e, (int)(m + u * TY), rc[u]);
+      }
+      for (; m < m1; m += TY) {
+        typename Pat::template Slot<V> s;
+        typename Pat::RowCtx rc;
+        Pat::row_begin(A, o * A.mid + m, rc);
+        Pat::template load<V>(A, rc, col, nvalid, s);
+#pragma unroll
+        for (int e = 0; e < V; ++e)
+          if (e < nvalid) Pat::template accum<0, V>(A, acc[e], s, e, (int)m, rc);
+      }
+    }
+#pragma unroll
+    for (int e = 0; e < V; ++e) lds[(ty * cp.GC + tx) * V + e] = acc[e];
+    __syncthreads();
+    if (ty == 0 && nvalid > 0) {
+      for (int t = 1; t < TY; ++t)
+#pragma unroll
+        for (int e = 0; e < V; ++e) Pat::template acc_merge<0>(acc[e], lds[(t * cp.GC + tx) * V + e]);
+#pragma unroll
+      for (int e = 0; e < V; ++e)
+        if (e < nvalid) Pat::acc_st(A, (o * cp.nchunk + chunk) * A.inner + col + e, acc[e]);
+    }
+    __syncthreads();
+  }
+}
+
+template <class Pat>
+DISC_DEV void col_finish_body(const typename Pat::Args& A, const ColPlan& cp) {
+  typedef typename Pat::template Acc<0> AccT;
+  __shared__ AccT lds[256];
+  const int tx = threadIdx.x & 63;
+  const int g = threadIdx.x >> 6;
+  const i64 c = (i64)blockIdx.x * 64 + tx;
+  for (i64 o = blockIdx.y; o < cp.outer; o += gridDim.y) {
+    AccT acc;
+    Pat::template acc_init<0>(acc);
+    if (c < A.inner) {
+      for (int j = g; j < cp.nchunk; j += 4) {
+        AccT t;
+        Pat::acc_ld(A, (o * cp.nchunk + j) * A.inner + c, t);
+        Pat::template acc_merge<0>(acc, t);
+      }
+    }
+    lds[g * 64 + tx] = acc;
+    __syncthreads();
+    if (g == 0 && c < A.inner) {
+      for (int t = 1; t < 4; ++t) Pat::template acc_merge<0>(acc, lds[t * 64 + tx]);
+      Pat::col_finish(A, o, c, acc);
+    }
+    __syncthreads();
+  }
+}
+
 }  // namespace disc

@@ -158,6 +158,9 @@ struct Generated {
   std::string source;
   ArgLayout args;
   std::vector<std::string> kernels;   // entry-point names present in the module
+  int n_acc_cells = 0;                // column reduce: 8-byte cells per partial accumulator
+  int n_red_planes = 0;               // column reduce: reduce-result planes in the workspace
+  bool has_epilogue = true;           // column reduce: some output keeps the reduced axis
 };
 
 // checker.cpp: validate, close constraints, decide fusion, resolve contexts, collapse.

@@ -24,6 +24,10 @@ namespace {
 struct DeviceRowPlan {   // mirrors disc::RowPlan of the device header
   int32_t G, log2G, nv, pad;
 };
+struct DeviceColPlan {   // mirrors disc::ColPlan of the device header
+  int32_t GC, log2GC, nchunk, pad;
+  int64_t chunk_rows, outer;
+};
 struct FastDivHost {
   uint32_t d, m, s, pad;
 };
@@ -194,9 +198,11 @@ int ilog2_ceil(int64_t v) {
 
 struct LaunchRec {
   const char* kernel = nullptr;
-  uint32_t grid = 1, block = 256;
-  bool rowplan = false;
+  uint32_t grid[3] = {1, 1, 1};
+  uint32_t block = 256;
+  int plan_kind = 0;         // 0 none, 1 RowPlan, 2 ColPlan
   DeviceRowPlan rp{};
+  DeviceColPlan cp{};
 };
 
 struct FullPlan {
@@ -204,7 +210,43 @@ struct FullPlan {
   ShapeVals sv;
   LaunchRec launches[3];
   int64_t nslots = 0, spr = 0;
+  int64_t aux[4] = {0, 0, 0, 0};
+  size_t ws_off[2] = {0, 0};
 };
+
+// Loop-fusion launch geometry for an iteration space [rows, inner]; shared by loop patterns and
+// by the epilogue stage of column reduces.  want_vec / want_i64: -1 = let the shape decide.
+int plan_loop(disc_ctx* c, int64_t rows, int64_t inner, int V, int want_vec, int want_i64, const char* const names[4],
+              FullPlan* fp, LaunchRec* L, bool* vec_out, bool* i64_out) {
+  bool vec;
+  {
+    const int64_t spr_v = (inner + V - 1) / V;
+    const double waste = 1.0 - (double)inner / (double)(spr_v * V);
+    vec = waste <= 0.25;
+  }
+  if (want_vec >= 0) vec = want_vec != 0;
+  const int v = vec ? V : 1;
+  int64_t spr = (inner + v - 1) / v, nslots;
+  if (mul_ovf(spr, rows, &nslots)) return set_err(c, DISC_ERR_SHAPE, "slot count overflows int64");
+  bool i64 = nslots >= (1ll << 31) - (1ll << 24) || inner >= (1ll << 31) - 16 || rows >= (1ll << 31);
+  if (want_i64 == 1) i64 = true;
+  else if (want_i64 == 0 && i64) return set_err(c, DISC_ERR_INVALID_ARG, "forced 32-bit version cannot index this shape");
+  const int U = i64 ? 1 : c->loop_unroll;
+  const int64_t max_grid = (int64_t)c->n_cus * c->grid_mult;
+  int64_t blocks = (nslots + 256ll * U - 1) / (256ll * U);
+  blocks = std::min(blocks, i64 ? max_grid * 4 : max_grid);
+  L->kernel = names[(vec ? 0 : 2) + (i64 ? 1 : 0)];
+  L->grid[0] = (uint32_t)blocks;
+  L->block = 256;
+  fp->nslots = nslots;
+  fp->spr = spr;
+  fp->pub.index_bits = i64 ? 64 : 32;
+  fp->pub.vec_width = v;
+  fp->pub.slots_per_lane = U;
+  *vec_out = vec;
+  *i64_out = i64;
+  return DISC_OK;
+}
 
 // ---- version + launch-dimension selection (host) ---------------------------------------------
 int make_plan(disc_ctx* c, const Pattern& p, const int64_t* dims, int n_dims, int force, FullPlan* fp) {
@@ -225,35 +267,18 @@ int make_plan(disc_ctx* c, const Pattern& p, const int64_t* dims, int n_dims, in
 
   if (an.tmpl == DISC_TEMPLATE_LOOP) {
     if (sv.rows == 0 || sv.inner == 0) return DISC_OK;
-    bool vec;
-    {
-      const int64_t spr_v = (sv.inner + V - 1) / V;
-      const double waste = 1.0 - (double)sv.inner / (double)(spr_v * V);
-      vec = waste <= 0.25;
+    int want_vec = -1, want_i64 = -1;
+    if (force >= 0) {
+      if (force > DISC_V_LOOP_SCALAR_I64)
+        return set_err(c, DISC_ERR_INVALID_ARG, "forced version does not belong to a loop-fusion pattern");
+      want_vec = force == DISC_V_LOOP_VEC || force == DISC_V_LOOP_VEC_I64;
+      want_i64 = force == DISC_V_LOOP_VEC_I64 || force == DISC_V_LOOP_SCALAR_I64;
     }
-    if (force == DISC_V_LOOP_VEC || force == DISC_V_LOOP_VEC_I64) vec = true;
-    else if (force == DISC_V_LOOP_SCALAR || force == DISC_V_LOOP_SCALAR_I64) vec = false;
-    else if (force >= 0) return set_err(c, DISC_ERR_INVALID_ARG, "forced version does not belong to a loop-fusion pattern");
-    const int v = vec ? V : 1;
-    int64_t spr = (sv.inner + v - 1) / v, nslots;
-    if (mul_ovf(spr, sv.rows, &nslots)) return set_err(c, DISC_ERR_SHAPE, "slot count overflows int64");
-    bool i64 = nslots >= (1ll << 31) - (1ll << 24) || sv.inner >= (1ll << 31) - 16 || sv.rows >= (1ll << 31);
-    if (force == DISC_V_LOOP_VEC_I64 || force == DISC_V_LOOP_SCALAR_I64) i64 = true;
-    else if (force >= 0 && i64) return set_err(c, DISC_ERR_INVALID_ARG, "forced 32-bit version cannot index this shape");
+    static const char* const names[] = {"k_loop_vec", "k_loop_vec_i64", "k_loop_scalar", "k_loop_scalar_i64"};
+    bool vec, i64;
+    rc = plan_loop(c, sv.rows, sv.inner, V, want_vec, want_i64, names, fp, &fp->launches[0], &vec, &i64);
+    if (rc) return rc;
     pub.variant = vec ? (i64 ? DISC_V_LOOP_VEC_I64 : DISC_V_LOOP_VEC) : (i64 ? DISC_V_LOOP_SCALAR_I64 : DISC_V_LOOP_SCALAR);
-    pub.index_bits = i64 ? 64 : 32;
-    pub.vec_width = v;
-    const int U = i64 ? 1 : c->loop_unroll;
-    pub.slots_per_lane = U;
-    int64_t blocks = (nslots + 256ll * U - 1) / (256ll * U);
-    blocks = std::min(blocks, i64 ? max_grid * 4 : max_grid);
-    LaunchRec& L = fp->launches[0];
-    static const char* names[] = {"k_loop_vec", "k_loop_vec_i64", "k_loop_scalar", "k_loop_scalar_i64"};
-    L.kernel = names[pub.variant - DISC_V_LOOP_VEC];
-    L.grid = (uint32_t)blocks;
-    L.block = 256;
-    fp->nslots = nslots;
-    fp->spr = spr;
     pub.n_launches = 1;
   } else if (an.tmpl == DISC_TEMPLATE_ROW_REDUCE) {
     if (sv.rows == 0) return DISC_OK;
@@ -280,7 +305,7 @@ int make_plan(disc_ctx* c, const Pattern& p, const int64_t* dims, int n_dims, in
     if (stream) {
       pub.variant = vec ? DISC_V_ROW_STREAM_VEC : DISC_V_ROW_STREAM_SCALAR;
       L.kernel = vec ? "k_row_stream_vec" : "k_row_stream_scalar";
-      L.grid = (uint32_t)std::min<int64_t>(sv.rows, max_grid * 2);
+      L.grid[0] = (uint32_t)std::min<int64_t>(sv.rows, max_grid * 2);
       pub.lanes_per_row = 256;
       pub.slots_per_lane = (int)((spr + 255) / 256);
       pub.reg_slots = 1;
@@ -295,24 +320,87 @@ int make_plan(disc_ctx* c, const Pattern& p, const int64_t* dims, int n_dims, in
       static const char* ks[] = {"k_row_scalar_nv1", "k_row_scalar_nv2", "k_row_scalar_nv4", "k_row_scalar_nv8"};
       const int ii = inst == 1 ? 0 : inst == 2 ? 1 : inst == 4 ? 2 : 3;
       L.kernel = vec ? kv[ii] : ks[ii];
-      L.rowplan = true;
+      L.plan_kind = 1;
       L.rp.G = G;
       L.rp.log2G = ilog2_ceil(G);
       L.rp.nv = nv;
       const int rpb = 256 / G;
       const int64_t ngroups = (sv.rows + rpb - 1) / rpb;
-      L.grid = (uint32_t)std::min<int64_t>(ngroups, max_grid);
+      L.grid[0] = (uint32_t)std::min<int64_t>(ngroups, max_grid);
       pub.lanes_per_row = G;
       pub.slots_per_lane = nv;
       pub.reg_slots = inst;
     }
     pub.n_launches = 1;
   } else {
-    return set_err(c, DISC_ERR_UNFUSIBLE, "column-reduce launch path not available");
+    // column reduce: canonical [outer, mid, inner], rows = outer * mid
+    const int64_t outer = an.mid_group == 1 ? sv.group[0] : 1;
+    const int64_t mid = sv.mid, inner = sv.inner;
+    if (outer == 0 || inner == 0) return DISC_OK;
+    if (mid == 0) return set_err(c, DISC_ERR_EMPTY_REDUCE, "reduction over an axis of size 0");
+    if (mid >= (1ll << 31) - 1) return set_err(c, DISC_ERR_SHAPE, "reduced axis longer than 2^31");
+    int want_vec = -1;
+    if (force >= 0) {
+      if (force != DISC_V_COL_3STAGE_VEC && force != DISC_V_COL_3STAGE_SCALAR)
+        return set_err(c, DISC_ERR_INVALID_ARG, "forced version does not belong to a column-reduce pattern");
+      want_vec = force == DISC_V_COL_3STAGE_VEC;
+    }
+    bool vec;
+    {
+      const int64_t spr_v = (inner + V - 1) / V;
+      vec = 1.0 - (double)inner / (double)(spr_v * V) <= 0.25;
+      if (want_vec >= 0) vec = want_vec != 0;
+    }
+    const int v = vec ? V : 1;
+    const int64_t spr = (inner + v - 1) / v;
+    int GC = 1 << ilog2_ceil(std::min<int64_t>(spr, 64));
+    const int TY = 256 / GC;
+    const int64_t col_tiles = (spr + GC - 1) / GC;
+    // chunks of the reduced axis: enough blocks to fill the chip, at least 4 rows per row-lane
+    int64_t target_blocks = (int64_t)c->n_cus * 4;
+    int64_t nchunk = (target_blocks + col_tiles * outer - 1) / (col_tiles * outer);
+    const int64_t max_chunks = std::max<int64_t>(1, mid / (4ll * TY));
+    nchunk = std::max<int64_t>(1, std::min<int64_t>(std::min<int64_t>(nchunk, max_chunks), 1024));
+    const int64_t chunk_rows = (mid + nchunk - 1) / nchunk;
+    nchunk = (mid + chunk_rows - 1) / chunk_rows;
+    DeviceColPlan cp{GC, ilog2_ceil(GC), (int32_t)nchunk, 0, chunk_rows, outer};
+    int64_t cells, red_bytes;
+    if (mul_ovf(outer * nchunk, inner, &cells) || mul_ovf(cells, (int64_t)p.gen.n_acc_cells * 8, &red_bytes))
+      return set_err(c, DISC_ERR_SHAPE, "workspace size overflows int64");
+    fp->aux[0] = cells;                 // cells per accumulator-field plane
+    fp->aux[1] = outer * inner * 8;     // bytes per reduce-result plane
+    fp->ws_off[0] = 0;
+    fp->ws_off[1] = ((size_t)red_bytes + 255) / 256 * 256;
+    pub.workspace_bytes = fp->ws_off[1] + (size_t)p.gen.n_red_planes * (size_t)fp->aux[1];
+    pub.variant = vec ? DISC_V_COL_3STAGE_VEC : DISC_V_COL_3STAGE_SCALAR;
+    pub.lanes_per_row = GC;
+    LaunchRec& L0 = fp->launches[0];
+    L0.kernel = vec ? "k_col_partial_vec" : "k_col_partial_scalar";
+    L0.grid[0] = (uint32_t)col_tiles;
+    L0.grid[1] = (uint32_t)nchunk;
+    L0.grid[2] = (uint32_t)std::min<int64_t>(outer, 65535);
+    L0.plan_kind = 2;
+    L0.cp = cp;
+    LaunchRec& L1 = fp->launches[1];
+    L1.kernel = "k_col_finish";
+    L1.grid[0] = (uint32_t)((inner + 63) / 64);
+    L1.grid[1] = (uint32_t)std::min<int64_t>(outer, 65535);
+    L1.plan_kind = 2;
+    L1.cp = cp;
+    pub.n_launches = 2;
+    if (p.gen.has_epilogue) {
+      static const char* const names[] = {"k_col_epi_vec", "k_col_epi_vec_i64", "k_col_epi_scalar", "k_col_epi_scalar_i64"};
+      bool v2, i64;
+      rc = plan_loop(c, sv.rows, inner, V, vec ? 1 : 0, -1, names, fp, &fp->launches[2], &v2, &i64);
+      if (rc) return rc;
+      pub.n_launches = 3;
+    } else {
+      pub.vec_width = v;
+      pub.index_bits = 64;
+    }
   }
   for (int l = 0; l < pub.n_launches; ++l) {
-    pub.grid[l][0] = fp->launches[l].grid;
-    pub.grid[l][1] = pub.grid[l][2] = 1;
+    for (int k = 0; k < 3; ++k) pub.grid[l][k] = fp->launches[l].grid[k];
     pub.block[l][0] = fp->launches[l].block;
     pub.block[l][1] = pub.block[l][2] = 1;
     pub.lds_bytes[l] = 0;
@@ -335,8 +423,8 @@ void fill_args(const Pattern& p, const FullPlan& fp, const int64_t* dims, const 
       case ArgField::GROUP_SIZE: v = sv.group[f.index]; memcpy(dst, &v, 8); break;
       case ArgField::IN_PTR: memcpy(dst, &in[f.index], 8); break;
       case ArgField::OUT_PTR: memcpy(dst, &outp[f.index], 8); break;
-      case ArgField::WS_PTR: memcpy(dst, &ws, 8); break;
-      case ArgField::AUX: memcpy(dst, &v, 8); break;
+      case ArgField::WS_PTR: { void* w = ws ? (char*)ws + fp.ws_off[f.index] : nullptr; memcpy(dst, &w, 8); break; }
+      case ArgField::AUX: v = fp.aux[f.index]; memcpy(dst, &v, 8); break;
       case ArgField::STRIDE: v = sv.products[f.index]; memcpy(dst, &v, 8); break;
       case ArgField::DIMI: v = dims[p.an.dim_size_syms[f.index]]; memcpy(dst, &v, 8); break;
       case ArgField::SPR_DIV: { FastDivHost d = make_fastdiv((uint64_t)fp.spr); memcpy(dst, &d, 16); break; }
@@ -589,19 +677,23 @@ int disc_launch(disc_ctx* ctx, int32_t id, const int64_t* dims, int n_dims, cons
 
   alignas(16) unsigned char buf[4096 + 32];
   const int asz = p->gen.args.size;
-  if (asz + 16 > (int)sizeof buf) return set_err(ctx, DISC_ERR_BAD_PATTERN, "argument block too large");
+  if (asz + 48 > (int)sizeof buf) return set_err(ctx, DISC_ERR_BAD_PATTERN, "argument block too large");
   fill_args(*p, fp, dims, inputs, outputs, workspace, buf);
   for (int l = 0; l < fp.pub.n_launches; ++l) {
     const LaunchRec& L = fp.launches[l];
     auto it = p->fn.find(L.kernel);
     if (it == p->fn.end()) return set_err(ctx, DISC_ERR_HIP, std::string("kernel version missing: ") + L.kernel);
     size_t size = (size_t)asz;
-    if (L.rowplan) {
+    if (L.plan_kind == 1) {
       memcpy(buf + asz, &L.rp, sizeof L.rp);
       size += sizeof L.rp;
+    } else if (L.plan_kind == 2) {
+      memcpy(buf + asz, &L.cp, sizeof L.cp);
+      size += sizeof L.cp;
     }
     void* extra[] = {HIP_LAUNCH_PARAM_BUFFER_POINTER, buf, HIP_LAUNCH_PARAM_BUFFER_SIZE, &size, HIP_LAUNCH_PARAM_END};
-    hipError_t e = hipModuleLaunchKernel(it->second, L.grid, 1, 1, L.block, 1, 1, 0, (hipStream_t)hip_stream, nullptr, extra);
+    hipError_t e = hipModuleLaunchKernel(it->second, L.grid[0], L.grid[1], L.grid[2], L.block, 1, 1, 0,
+                                         (hipStream_t)hip_stream, nullptr, extra);
     if (e != hipSuccess) return hip_fail(ctx, e, "hipModuleLaunchKernel");
     ctx->stats.device_launches++;
   }

@@ -39,11 +39,12 @@ SMALL = {
     "C0": [[1, 768], [7, 768], [300, 768], [33, 5], [5, 1], [129, 771]],
     "C1": [[2, 3, 16], [2, 3, 17], [1, 2, 64], [2, 1, 131], [1, 1, 512], [1, 1, 1]],
     "C2": [[5, 768], [64, 1024], [3, 4096], [17, 100], [9, 3], [2, 9000]],
+    "C3": [[1, 1024], [100, 1024], [5000, 1024], [37, 100], [300, 7], [64, 3000], [2, 1]],
     "C4": [[1, 64], [37, 64], [100, 777], [3, 8192], [1000, 65], [5, 9], [2, 20000]],
 }
 
 
-@pytest.mark.parametrize("cfg_name", ["C0", "C1", "C2", "C4"])
+@pytest.mark.parametrize("cfg_name", ["C0", "C1", "C2", "C3", "C4"])
 def test_small_shapes_one_compile(ctx, cfg_name):
     h = None
     for i, dims in enumerate(SMALL[cfg_name]):
