@@ -3,10 +3,22 @@
 // hand-written schedules of disc_device.h are instantiated with.  All kernel versions of a
 // pattern come out of this one translation unit, so a pattern costs exactly one device
 // compile whatever shapes it later runs at (Section 2 / Section 4.3 of the paper).
+//
+// Decisions taken here, per pattern and independent of any shape value:
+//  * which operands stream from HBM and are loaded up front into the slot (tensors that span
+//    the whole iteration space) and which are small, cached operands loaded where they are
+//    used (row vectors, row-group operands): keeps registers free across reduction phases;
+//  * which intermediate values are carried in registers from one reduction phase to the next
+//    and which are recomputed from the raw slot (a cast or one add is cheaper than 8 registers);
+//  * division by a per-row value becomes a multiplication by a reciprocal computed once per row;
+//    per-element transcendental ops use the hardware approximations (1 ulp exp2 / log2 / rcp /
+//    rsq), per-row and per-column scalar math stays IEEE-correct.
 #include <cmath>
 #include <cstdarg>
-#include <map>
 #include <cstdio>
+#include <functional>
+#include <map>
+#include <set>
 #include <sstream>
 
 #include "disc_internal.hpp"
@@ -31,18 +43,35 @@ std::string float_lit(double v) {
   char buf[64];
   snprintf(buf, sizeof buf, "%.9gf", (double)f);
   std::string s = buf;
-  if (s.find('.') == std::string::npos && s.find('e') == std::string::npos && s.find("inf") == std::string::npos)
-    s.insert(s.size() - 1, ".0");
+  if (s.find('.') == std::string::npos && s.find('e') == std::string::npos) s.insert(s.size() - 1, ".0");
   return s;
+}
+
+bool heavy_op(int oc) {
+  switch (oc) {
+    case DISC_EXP: case DISC_LOG: case DISC_TANH: case DISC_SQRT: case DISC_RSQRT: case DISC_RCP:
+    case DISC_SIGMOID: case DISC_ERF: case DISC_DIV: case DISC_POW: return true;
+    default: return false;
+  }
 }
 
 struct Gen {
   const Analysis& an;
   ArgLayout layout;
   std::ostringstream os;
+  int acc_bytes = 8;
+  int n_acc_cells = 0;
+  // row template: values carried in registers across phases, and the function that makes them
+  std::set<int> keep_nodes;
+  std::map<int, int> produced_phase;
+  std::set<int> need_rinv;     // per-row values whose reciprocal is precomputed
   explicit Gen(const Analysis& a) : an(a) {}
 
-  bool is_reduce(int oc) const { return oc >= DISC_REDUCE_SUM && oc <= DISC_REDUCE_ARGMAX; }
+  static bool is_reduce(int oc) { return oc >= DISC_REDUCE_SUM && oc <= DISC_REDUCE_ARGMAX; }
+  bool col_tmpl() const { return an.tmpl == DISC_TEMPLATE_COL_REDUCE; }
+  bool row_tmpl() const { return an.tmpl == DISC_TEMPLATE_ROW_REDUCE; }
+  // small cached operands of a row reduce are loaded at their point of use, not into the slot
+  bool late(const Access& a) const { return row_tmpl() && !a.is_output && a.has_inner && a.kind != ACC_FULL; }
 
   // ---- kernel-argument block ------------------------------------------------------------
   void add_field(ArgField::Kind k, int index, int size) {
@@ -72,48 +101,45 @@ struct Gen {
     for (size_t i = 0; i < an.dim_size_syms.size(); ++i) add_field(ArgField::DIMF, (int)i, 4);
     if (layout.size % 8) layout.size += 8 - layout.size % 8;
   }
-  std::string field_decl(const ArgField& f) const {
+  int io_dtype(int opcode, int index) const {
+    int k = 0;
+    for (const auto& op : an.ops)
+      if (op.opcode == opcode && k++ == index) return op.dtype;
+    return DISC_F32;
+  }
+  std::string field_name(const ArgField& f) const {
     switch (f.kind) {
-      case ArgField::ROWS: return "disc::i64 rows;";
-      case ArgField::INNER: return "disc::i64 inner;";
-      case ArgField::NSLOTS: return "disc::i64 nslots;";
-      case ArgField::SPR: return "disc::i64 spr;";
-      case ArgField::MID: return "disc::i64 mid;";
-      case ArgField::GROUP_SIZE: return fmt("disc::i64 gs%d;", f.index);
-      case ArgField::IN_PTR: {
-        int dt = DISC_F32;
-        int k = 0;
-        for (const auto& op : an.ops)
-          if (op.opcode == DISC_PARAM && k++ == f.index) dt = op.dtype;
-        return fmt("const %s* __restrict__ p%d;", dtype_ctype(dt), f.index);
-      }
-      case ArgField::OUT_PTR: {
-        int dt = DISC_F32;
-        int k = 0;
-        for (const auto& op : an.ops)
-          if (op.opcode == DISC_OUTPUT && k++ == f.index) dt = op.dtype;
-        return fmt("%s* __restrict__ o%d;", dtype_ctype(dt), f.index);
-      }
-      case ArgField::WS_PTR: return fmt("void* ws%d;", f.index);
-      case ArgField::AUX: return fmt("disc::i64 aux%d;", f.index);
-      case ArgField::STRIDE: return fmt("disc::i64 st%d;", f.index);
-      case ArgField::DIMI: return fmt("disc::i64 dimi%d;", f.index);
-      case ArgField::SPR_DIV: return "disc::FastDiv spr_div;";
-      case ArgField::GROUP_DIV: return fmt("disc::FastDiv gd%d;", f.index);
-      case ArgField::DIMF: return fmt("float dimf%d;", f.index);
+      case ArgField::ROWS: return "rows";
+      case ArgField::INNER: return "inner";
+      case ArgField::NSLOTS: return "nslots";
+      case ArgField::SPR: return "spr";
+      case ArgField::MID: return "mid";
+      case ArgField::GROUP_SIZE: return fmt("gs%d", f.index);
+      case ArgField::IN_PTR: return fmt("p%d", f.index);
+      case ArgField::OUT_PTR: return fmt("o%d", f.index);
+      case ArgField::WS_PTR: return fmt("ws%d", f.index);
+      case ArgField::AUX: return fmt("aux%d", f.index);
+      case ArgField::STRIDE: return fmt("st%d", f.index);
+      case ArgField::DIMI: return fmt("dimi%d", f.index);
+      case ArgField::SPR_DIV: return "spr_div";
+      case ArgField::GROUP_DIV: return fmt("gd%d", f.index);
+      case ArgField::DIMF: return fmt("dimf%d", f.index);
     }
     return "";
   }
-  std::string field_name(const ArgField& f) const {
-    std::string d = field_decl(f);
-    size_t e = d.rfind(';');
-    size_t b = d.find_last_of(" *_", e);   // crude but all names end the declaration
-    (void)b;
-    size_t sp = d.find_last_of(' ', e);
-    return d.substr(sp + 1, e - sp - 1);
+  std::string field_decl(const ArgField& f) const {
+    const std::string n = field_name(f);
+    switch (f.kind) {
+      case ArgField::IN_PTR: return fmt("const %s* __restrict__ %s;", dtype_ctype(io_dtype(DISC_PARAM, f.index)), n.c_str());
+      case ArgField::OUT_PTR: return fmt("%s* __restrict__ %s;", dtype_ctype(io_dtype(DISC_OUTPUT, f.index)), n.c_str());
+      case ArgField::WS_PTR: return "void* " + n + ";";
+      case ArgField::SPR_DIV: case ArgField::GROUP_DIV: return "disc::FastDiv " + n + ";";
+      case ArgField::DIMF: return "float " + n + ";";
+      default: return "disc::i64 " + n + ";";
+    }
   }
 
-  // ---- expression emission ---------------------------------------------------------------
+  // ---- conversions -------------------------------------------------------------------------
   int dim_index(int sym) const {
     for (size_t i = 0; i < an.dim_size_syms.size(); ++i)
       if (an.dim_size_syms[i] == sym) return (int)i;
@@ -142,6 +168,25 @@ struct Gen {
     return fmt("(%s)(%s)", dtype_ctype(dtype), x.c_str());
   }
 
+  // accumulator field names of reduce `slot` in a phase
+  static std::string accf(int slot) { return fmt("f%d", slot); }
+  static std::string acci(int slot) { return fmt("i%d", slot); }
+  // accumulator C type of a reduction: long column sums of fp32 data run in fp64 (values near
+  // zero must still meet the absolute part of the fp32 tolerance after cancellation)
+  std::string acc_ctype(const Node& n) const {
+    RegKind ok = an.nodes[n.in[0]].rk;
+    if (col_tmpl() && n.opcode == DISC_REDUCE_SUM && ok == RK_F32) return "double";
+    return reg_ctype(ok);
+  }
+  // reduce result as a register value of the node's kind, read from accumulator `acc`
+  std::string acc_value(const Node& n, const std::string& acc) const {
+    RegKind ok = an.nodes[n.in[0]].rk;
+    if (n.opcode == DISC_REDUCE_ARGMAX) return convert(acc + "." + acci(n.reduce_slot), RK_I32, n.rk);
+    std::string f = acc + "." + accf(n.reduce_slot);
+    if (acc_ctype(n) == "double") f = "(float)" + f;
+    return convert(f, ok, n.rk);
+  }
+
   // Where a piece of generated code runs; decides where each kind of value is read from.
   enum Mode {
     M_ELEM,        // row / loop templates, per element: slot `s`, element `e`, per-row values in `rc`
@@ -157,7 +202,11 @@ struct Gen {
     std::ostringstream body;
     std::map<int, std::string> names;
     Mode mode;
+    int P = 0;            // M_ELEM: index of the phase function being emitted (n_phases = epilogue)
+    bool keep = false;    // M_ELEM: values may be read from / written to the Keep registers
+    std::set<int> late_used;
     Fn(Gen& gg, Mode m) : g(gg), mode(m) {}
+    bool fast() const { return mode == M_ELEM || mode == M_COL_ACCUM || mode == M_COL_EPI; }
 
     std::string val(int id) {
       auto it = names.find(id);
@@ -180,20 +229,29 @@ struct Gen {
                                         : (a.groups.empty() ? "0" : "o");
           r = from_storage(fmt("A.p%d[%s]", a.slot, off.c_str()), a.dtype);
         } else if (a.has_inner) {
-          r = from_storage(fmt("s.a%d.v[e]", n.access), a.dtype);
+          if (g.late(a)) {
+            late_used.insert(n.access);
+            r = from_storage(fmt("l%d.v[e]", n.access), a.dtype);
+          } else {
+            r = from_storage(fmt("s.a%d.v[e]", n.access), a.dtype);
+          }
         } else {
           r = fmt("rc.r%d", id);   // loaded by row_begin
         }
-      } else if (g.is_reduce(n.opcode)) {
+      } else if (is_reduce(n.opcode)) {
         if (mode == M_COL_FINISH) r = g.acc_value(n, "acc");
         else if (mode == M_COL_EPI) r = fmt("s.red%d.v[e]", n.reduce_slot);
         else r = fmt("rc.r%d", id);
       } else if (!col && n.dom == DOM_ROW && mode == M_ELEM) {
         r = fmt("rc.r%d", id);
+      } else if (mode == M_ELEM && keep && g.keep_nodes.count(id) && g.produced_phase[id] < P) {
+        r = fmt("k.k%d[e]", id);
       } else {
         r = fmt("t%d", id);
         const std::string rhs = expr(n);   // emits the operands first
-        body << "    const " << reg_ctype(n.rk) << " " << r << " = " << rhs << ";\n";
+        body << "        const " << reg_ctype(n.rk) << " " << r << " = " << rhs << ";\n";
+        if (mode == M_ELEM && keep && g.keep_nodes.count(id) && g.produced_phase[id] == P)
+          body << "        k.k" << id << "[e] = " << r << ";\n";
       }
       names[id] = r;
       return r;
@@ -202,21 +260,28 @@ struct Gen {
     std::string expr(const Node& n) {
       const RegKind k = n.rk;
       auto a = [&](int i) { return as(n.in[i], k); };
+      const bool f = fast();
       switch (n.opcode) {
         case DISC_NEG: return "-" + a(0);
         case DISC_ABS: return k == RK_F32 ? "fabsf(" + a(0) + ")" : "(" + a(0) + " < 0 ? -" + a(0) + " : " + a(0) + ")";
-        case DISC_EXP: return "expf(" + a(0) + ")";
-        case DISC_LOG: return "logf(" + a(0) + ")";
-        case DISC_TANH: return "tanhf(" + a(0) + ")";
-        case DISC_SQRT: return "sqrtf(" + a(0) + ")";
-        case DISC_RSQRT: return "rsqrtf(" + a(0) + ")";
-        case DISC_RCP: return "(1.0f / " + a(0) + ")";
-        case DISC_SIGMOID: return "(1.0f / (1.0f + expf(-" + a(0) + ")))";
+        case DISC_EXP: return (f ? "disc::fast_exp(" : "expf(") + a(0) + ")";
+        case DISC_LOG: return (f ? "disc::fast_log(" : "logf(") + a(0) + ")";
+        case DISC_TANH: return (f ? "disc::fast_tanh(" : "tanhf(") + a(0) + ")";
+        case DISC_SQRT: return (f ? "disc::fast_sqrt(" : "sqrtf(") + a(0) + ")";
+        case DISC_RSQRT: return (f ? "disc::fast_rsqrt(" : "rsqrtf(") + a(0) + ")";
+        case DISC_RCP: return f ? "disc::fast_rcp(" + a(0) + ")" : "(1.0f / " + a(0) + ")";
+        case DISC_SIGMOID: return f ? "disc::fast_sigmoid(" + a(0) + ")" : "(1.0f / (1.0f + expf(-" + a(0) + ")))";
         case DISC_ERF: return "erff(" + a(0) + ")";
         case DISC_ADD: return a(0) + " + " + a(1);
         case DISC_SUB: return a(0) + " - " + a(1);
         case DISC_MUL: return a(0) + " * " + a(1);
-        case DISC_DIV: return a(0) + " / " + a(1);
+        case DISC_DIV: {
+          if (k != RK_F32 || !f) return a(0) + " / " + a(1);
+          const Node& d = g.an.nodes[n.in[1]];
+          if (mode == M_ELEM && g.need_rinv.count(n.in[1])) return a(0) + " * " + fmt("rc.q%d", n.in[1]);
+          if (d.dom == DOM_SCALAR) return a(0) + " * (1.0f / " + a(1) + ")";
+          return a(0) + " * disc::fast_rcp(" + a(1) + ")";
+        }
         case DISC_MAX: return k == RK_F32 ? "fmaxf(" + a(0) + ", " + a(1) + ")" : "(" + a(0) + " > " + a(1) + " ? " + a(0) + " : " + a(1) + ")";
         case DISC_MIN: return k == RK_F32 ? "fminf(" + a(0) + ", " + a(1) + ")" : "(" + a(0) + " < " + a(1) + " ? " + a(0) + " : " + a(1) + ")";
         case DISC_POW: return "powf(" + a(0) + ", " + a(1) + ")";
@@ -234,23 +299,67 @@ struct Gen {
     }
   };
 
-  bool col_tmpl() const { return an.tmpl == DISC_TEMPLATE_COL_REDUCE; }
-  // accumulator C type of a reduction: long column sums of fp32 data run in fp64 (values near
-  // zero must still meet the absolute part of the fp32 tolerance after cancellation)
-  std::string acc_ctype(const Node& n) const {
-    RegKind ok = an.nodes[n.in[0]].rk;
-    if (col_tmpl() && n.opcode == DISC_REDUCE_SUM && ok == RK_F32) return "double";
-    return reg_ctype(ok);
+  // ---- planning of cross-phase registers (row template) -----------------------------------------
+  std::vector<int> phase_roots(int P) const {
+    std::vector<int> r;
+    if (P < an.n_phases) {
+      for (int id : an.reduces[P]) r.push_back(an.nodes[id].in[0]);
+    } else {
+      for (const auto& out : an.outputs)
+        if (elem_output(an.accesses[out.access])) r.push_back(out.node);
+    }
+    return r;
   }
-  // reduce result as a register value of the node's kind, read from accumulator `acc`
-  std::string acc_value(const Node& n, const std::string& acc) const {
-    RegKind ok = an.nodes[n.in[0]].rk;
-    if (n.opcode == DISC_REDUCE_ARGMAX) return convert(acc + "." + acci(n.reduce_slot), RK_I32, n.rk);
-    std::string f = acc + "." + accf(n.reduce_slot);
-    if (acc_ctype(n) == "double") f = "(float)" + f;
-    return convert(f, ok, n.rk);
+  double recompute_cost(int id, int P, std::map<int, double>& memo) const {
+    auto it = memo.find(id);
+    if (it != memo.end()) return it->second;
+    const Node& n = an.nodes[id];
+    double c;
+    if (n.dom != DOM_ELEM) c = 0;
+    else if (n.opcode == DISC_PARAM) c = late(an.accesses[n.access]) ? 1e9 : 0;
+    else if (keep_nodes.count(id) && produced_phase.at(id) < P) c = 0;
+    else {
+      c = heavy_op(n.opcode) ? 4 : 1;
+      for (int k = 0; k < n.n_in; ++k) c += recompute_cost(n.in[k], P, memo);
+    }
+    memo[id] = c;
+    return c;
+  }
+  void plan_keeps() {
+    keep_nodes.clear();
+    produced_phase.clear();
+    if (!row_tmpl()) return;
+    for (int P = 0; P <= an.n_phases; ++P) {
+      std::set<int> seen;
+      std::function<void(int)> visit = [&](int id) {
+        const Node& n = an.nodes[id];
+        if (n.dom != DOM_ELEM || n.opcode == DISC_PARAM || seen.count(id)) return;
+        seen.insert(id);
+        auto pp = produced_phase.find(id);
+        if (pp != produced_phase.end() && pp->second < P) {
+          std::map<int, double> memo;
+          if (keep_nodes.count(id) || recompute_cost(id, P, memo) > 2.0) {
+            keep_nodes.insert(id);
+            return;
+          }
+        }
+        if (pp == produced_phase.end()) produced_phase[id] = P;
+        for (int k = 0; k < n.n_in; ++k) visit(n.in[k]);
+      };
+      for (int r : phase_roots(P)) visit(r);
+    }
+  }
+  void plan_rinv() {
+    need_rinv.clear();
+    if (col_tmpl()) return;
+    for (const Node& n : an.nodes)
+      if (n.opcode == DISC_DIV && n.rk == RK_F32 && n.dom == DOM_ELEM) {
+        const Node& d = an.nodes[n.in[1]];
+        if (d.dom == DOM_ROW && d.rk == RK_F32) need_rinv.insert(n.in[1]);
+      }
   }
 
+  // ---- per-row context -------------------------------------------------------------------------
   std::string row_fields() {
     std::ostringstream o;
     for (size_t i = 0; i < an.accesses.size(); ++i) {
@@ -262,10 +371,16 @@ struct Gen {
       const Node& n = an.nodes[i];
       const bool perrow_param = n.opcode == DISC_PARAM && !an.accesses[n.access].has_inner;
       if ((!col_tmpl() && n.dom == DOM_ROW) || perrow_param) o << "    " << reg_ctype(n.rk) << " r" << i << ";\n";
+      if (need_rinv.count((int)i)) o << "    float q" << i << ";\n";
     }
     if (col_tmpl()) o << "    disc::i64 ob;\n";   // offset of this row's outer slice in the reduce-result planes
     o << "    int unused_;\n";
     return o.str();
+  }
+  void assign_row(Fn& fn, size_t i, const std::string& v) {
+    fn.body << "    rc.r" << i << " = " << v << ";\n";
+    if (need_rinv.count((int)i)) fn.body << "    rc.q" << i << " = 1.0f / rc.r" << i << ";\n";
+    fn.names[(int)i] = fmt("rc.r%zu", i);
   }
 
   // offset expression of an access without the inner group, for row `row`
@@ -315,21 +430,17 @@ struct Gen {
         const Access& a = an.accesses[n.access];
         if (a.has_inner) continue;
         std::string off = perrow_offset(a, n.access);
-        fn.body << "    rc.r" << i << " = " << from_storage(fmt("A.p%d[%s]", a.slot, off.c_str()), a.dtype) << ";\n";
-        fn.names[(int)i] = fmt("rc.r%zu", i);
+        assign_row(fn, i, from_storage(fmt("A.p%d[%s]", a.slot, off.c_str()), a.dtype));
       } else if (!col_tmpl() && n.dom == DOM_ROW && n.phase == 0) {
         std::string v = fn.val((int)i);
-        fn.body << "    rc.r" << i << " = " << v << ";\n";
-        fn.names[(int)i] = fmt("rc.r%zu", i);
+        assign_row(fn, i, v);
       }
     }
     os << fn.body.str();
     os << "    (void)A; (void)row; (void)rc;\n  }\n";
   }
 
-  // Which operand accesses a stage needs in its slot: all of them, or only those reachable from
-  // the values the stage computes (keeps the epilogue of a column reduce from loading operands
-  // that only feed the reduction).
+  // Which operand accesses a stage needs: those reachable from the values the stage computes.
   std::vector<char> accesses_needed(const std::vector<int>& roots, bool stop_at_reduce) {
     std::vector<char> need(an.accesses.size(), 0), seen(an.nodes.size(), 0);
     std::vector<int> stack(roots);
@@ -346,30 +457,35 @@ struct Gen {
     return need;
   }
 
-  void emit_slots(const std::vector<char>& need, bool with_red) {
-    os << "  template <int V> struct Slot {\n";
-    for (size_t i = 0; i < an.accesses.size(); ++i) {
-      const Access& a = an.accesses[i];
-      if (!a.is_output && a.has_inner && need[i]) os << "    disc::Vec<" << dtype_ctype(a.dtype) << ", V> a" << i << ";\n";
-    }
-    if (with_red)
-      for (int id : an.reduces[0])
-        os << "    disc::Vec<" << reg_ctype(an.nodes[id].rk) << ", V> red" << an.nodes[id].reduce_slot << ";\n";
-    os << "    int unused_;\n  };\n";
-    os << "  template <int V> struct OutSlot {\n";
-    for (size_t i = 0; i < an.accesses.size(); ++i) {
-      const Access& a = an.accesses[i];
-      if (a.is_output && a.has_inner && elem_output(a)) os << "    disc::Vec<" << dtype_ctype(a.dtype) << ", V> o" << a.slot << ";\n";
-    }
-    os << "    int unused_;\n  };\n";
-  }
-
   // outputs written per element by the epilogue (column reduce: only those that keep the reduced axis)
   bool elem_output(const Access& a) const {
     if (!a.has_inner) return false;
     if (!col_tmpl()) return true;
     for (int g : a.groups) if (g == an.mid_group) return true;
     return false;
+  }
+
+  void emit_slots(const std::vector<char>& need, bool with_red, bool with_keep) {
+    os << "  template <int V> struct Slot {\n";
+    for (size_t i = 0; i < an.accesses.size(); ++i) {
+      const Access& a = an.accesses[i];
+      if (!a.is_output && a.has_inner && need[i] && !late(a)) os << "    disc::Vec<" << dtype_ctype(a.dtype) << ", V> a" << i << ";\n";
+    }
+    if (with_red)
+      for (int id : an.reduces[0])
+        os << "    disc::Vec<" << reg_ctype(an.nodes[id].rk) << ", V> red" << an.nodes[id].reduce_slot << ";\n";
+    os << "    int unused_;\n  };\n";
+    os << "  template <int V> struct Keep {\n";
+    if (with_keep)
+      for (int id : keep_nodes)   // native vectors: always registers, never a stack array
+        os << "    typename disc::Vec<" << reg_ctype(an.nodes[id].rk) << ", V>::vec_t k" << id << ";\n";
+    os << "    int unused_;\n  };\n";
+    os << "  template <int V> struct OutSlot {\n";
+    for (size_t i = 0; i < an.accesses.size(); ++i) {
+      const Access& a = an.accesses[i];
+      if (a.is_output && elem_output(a)) os << "    disc::Vec<" << dtype_ctype(a.dtype) << ", V> o" << a.slot << ";\n";
+    }
+    os << "    int unused_;\n  };\n";
   }
 
   std::string elem_base(const Access& a, size_t i) {
@@ -381,7 +497,7 @@ struct Gen {
     os << "  template <int V, class C> static DISC_DEV void load(const Args& A, const RowCtx& rc, C col, int nvalid, Slot<V>& s) {\n";
     for (size_t i = 0; i < an.accesses.size(); ++i) {
       const Access& a = an.accesses[i];
-      if (a.is_output || !a.has_inner || !need[i]) continue;
+      if (a.is_output || !a.has_inner || !need[i] || late(a)) continue;
       os << "    disc::ld(s.a" << i << ", A.p" << a.slot << ", " << elem_base(a, i) << ", nvalid);\n";
     }
     if (with_red) {
@@ -403,10 +519,6 @@ struct Gen {
     os << "    (void)A; (void)rc; (void)col; (void)nvalid; (void)o;\n  }\n";
   }
 
-  // accumulator field names of reduce `slot` in a phase
-  static std::string accf(int slot) { return fmt("f%d", slot); }
-  static std::string acci(int slot) { return fmt("i%d", slot); }
-
   void emit_acc_types() {
     int max_bytes = 8;
     for (int p = 0; p < an.n_phases; ++p) {
@@ -427,7 +539,6 @@ struct Gen {
       os << "template <> struct PatAccSel<" << p << "> { typedef PatAcc" << p << " type; };\n";
     acc_bytes = max_bytes;
   }
-  int acc_bytes = 8;
 
   std::string identity(const Node& n) {
     RegKind ok = an.nodes[n.in[0]].rk;
@@ -438,8 +549,22 @@ struct Gen {
     }
   }
 
-  void emit_acc_fns() {
-    // init
+  // statement folding value `x` of one element into accumulator field(s) of reduce node n
+  std::string fold_stmt(const Node& n, const std::string& x, const std::string& idx) {
+    RegKind ok = an.nodes[n.in[0]].rk;
+    std::string f = "acc." + accf(n.reduce_slot), i = "acc." + acci(n.reduce_slot);
+    switch (n.opcode) {
+      case DISC_REDUCE_SUM: return f + " += " + x + ";";
+      case DISC_REDUCE_MAX:
+        return ok == RK_F32 ? f + " = fmaxf(" + f + ", " + x + ");" : f + " = " + f + " > " + x + " ? " + f + " : " + x + ";";
+      case DISC_REDUCE_MIN:
+        return ok == RK_F32 ? f + " = fminf(" + f + ", " + x + ");" : f + " = " + f + " < " + x + " ? " + f + " : " + x + ";";
+      default:
+        return "if (" + x + " > " + f + ") { " + f + " = " + x + "; " + i + " = " + idx + "; }";
+    }
+  }
+
+  void emit_acc_basic() {
     os << "  template <int P> static DISC_DEV void acc_init(Acc<P>& a) {\n";
     for (int p = 0; p < an.n_phases; ++p) {
       os << "    if constexpr (P == " << p << ") {\n";
@@ -451,7 +576,6 @@ struct Gen {
       os << "    }\n";
     }
     os << "    (void)a;\n  }\n";
-    // merge
     os << "  template <int P> static DISC_DEV void acc_merge(Acc<P>& a, const Acc<P>& b) {\n";
     for (int p = 0; p < an.n_phases; ++p) {
       os << "    if constexpr (P == " << p << ") {\n";
@@ -477,88 +601,121 @@ struct Gen {
       os << "    }\n";
     }
     os << "    (void)a; (void)b;\n  }\n";
-    // shuffle
-    os << "  template <int P> static DISC_DEV void acc_shfl(Acc<P>& a, int m) {\n";
+    os << "  template <int P, int S> static DISC_DEV void acc_xchg(Acc<P>& a) {\n";
     for (int p = 0; p < an.n_phases; ++p) {
       os << "    if constexpr (P == " << p << ") {\n";
       for (int id : an.reduces[p]) {
         const Node& n = an.nodes[id];
-        os << "      a." << accf(n.reduce_slot) << " = disc::shfl_xor(a." << accf(n.reduce_slot) << ", m);\n";
+        os << "      a." << accf(n.reduce_slot) << " = disc::lane_xchg<S>(a." << accf(n.reduce_slot) << ");\n";
         if (n.opcode == DISC_REDUCE_ARGMAX)
-          os << "      a." << acci(n.reduce_slot) << " = disc::shfl_xor(a." << acci(n.reduce_slot) << ", m);\n";
+          os << "      a." << acci(n.reduce_slot) << " = disc::lane_xchg<S>(a." << acci(n.reduce_slot) << ");\n";
       }
       os << "    }\n";
     }
-    os << "    (void)a; (void)m;\n  }\n";
-    // accumulate one element; `col` is the index along the reduced axis (for argmax)
-    os << "  template <int P, int V> static DISC_DEV void accum(const Args& A, Acc<P>& acc, const Slot<V>& s, int e, int col, const RowCtx& rc) {\n";
+    os << "    (void)a;\n  }\n";
+  }
+
+  void emit_late_loads(std::ostream& o, const Fn& fn, const char* ind) {
+    for (int ai : fn.late_used) {
+      const Access& a = an.accesses[ai];
+      o << ind << "disc::Vec<" << dtype_ctype(a.dtype) << ", V> l" << ai << ";\n";
+      o << ind << "disc::ld(l" << ai << ", A.p" << a.slot << ", " << elem_base(a, ai) << ", nvalid);\n";
+    }
+  }
+
+  // one flavour (with or without cross-phase registers) of reduction phase p, slot granularity
+  void emit_phase_flavour(int p, bool keep) {
+    Fn fn(*this, M_ELEM);
+    fn.P = p;
+    fn.keep = keep;
+    std::string tail, tail_pred;
+    for (int id : an.reduces[p]) {
+      const Node& n = an.nodes[id];
+      const std::string x = fn.val(n.in[0]);
+      const std::string st = fold_stmt(n, x, "col + e");
+      tail += "        " + st + "\n";
+      tail_pred += "        if (e < nvalid) { " + st + " }\n";
+    }
+    emit_late_loads(os, fn, "      ");
+    os << "      if (nvalid >= V) {\n#pragma unroll\n      for (int e = 0; e < V; ++e) {\n" << fn.body.str() << tail << "      }\n";
+    os << "      } else {\n#pragma unroll\n      for (int e = 0; e < V; ++e) {\n" << fn.body.str() << tail_pred << "      }\n      }\n";
+  }
+
+  void emit_row_phase_fns() {
+    os << "  template <int P, int V, bool KEEP> static DISC_DEV void phase(const Args& A, Acc<P>& acc, const Slot<V>& s, Keep<V>& k, int nvalid, int col, const RowCtx& rc) {\n";
     for (int p = 0; p < an.n_phases; ++p) {
       os << "    if constexpr (P == " << p << ") {\n";
-      Fn fn(*this, col_tmpl() ? M_COL_ACCUM : M_ELEM);
-      std::ostringstream tail;
-      for (int id : an.reduces[p]) {
-        const Node& n = an.nodes[id];
-        RegKind ok = an.nodes[n.in[0]].rk;
-        std::string x = fn.val(n.in[0]);
-        std::string f = "acc." + accf(n.reduce_slot), i = "acc." + acci(n.reduce_slot);
-        switch (n.opcode) {
-          case DISC_REDUCE_SUM: tail << "    " << f << " += " << x << ";\n"; break;
-          case DISC_REDUCE_MAX:
-            if (ok == RK_F32) tail << "    " << f << " = fmaxf(" << f << ", " << x << ");\n";
-            else tail << "    " << f << " = " << f << " > " << x << " ? " << f << " : " << x << ";\n";
-            break;
-          case DISC_REDUCE_MIN:
-            if (ok == RK_F32) tail << "    " << f << " = fminf(" << f << ", " << x << ");\n";
-            else tail << "    " << f << " = " << f << " < " << x << " ? " << f << " : " << x << ";\n";
-            break;
-          default:
-            tail << "    if (" << x << " > " << f << ") { " << f << " = " << x << "; " << i << " = col; }\n";
-        }
-      }
-      os << fn.body.str() << tail.str() << "    }\n";
+      os << "      if constexpr (KEEP) {\n";
+      emit_phase_flavour(p, true);
+      os << "      } else {\n";
+      emit_phase_flavour(p, false);
+      os << "      }\n    }\n";
     }
-    os << "    (void)A; (void)acc; (void)s; (void)e; (void)col; (void)rc;\n  }\n";
-    if (col_tmpl()) return;
+    os << "    (void)A; (void)acc; (void)s; (void)k; (void)nvalid; (void)col; (void)rc;\n  }\n";
     // per-row values known after phase P
     os << "  template <int P> static DISC_DEV void row_after(const Args& A, RowCtx& rc, const Acc<P>& acc) {\n";
     for (int p = 0; p < an.n_phases; ++p) {
       os << "    if constexpr (P == " << p << ") {\n";
       Fn fn(*this, M_ROWLOCAL);
-      for (int id : an.reduces[p]) {
-        const Node& n = an.nodes[id];
-        fn.body << "    rc.r" << id << " = " << acc_value(n, "acc") << ";\n";
-      }
       // earlier per-row values are read back from rc
       for (size_t i = 0; i < an.nodes.size(); ++i) {
         const Node& n = an.nodes[i];
         if (n.dom != DOM_ROW) continue;
-        if (n.phase <= p || is_reduce(n.opcode)) fn.names[(int)i] = fmt("rc.r%zu", i);
+        if (n.phase <= p && !(is_reduce(n.opcode) && n.phase == p + 1)) fn.names[(int)i] = fmt("rc.r%zu", i);
       }
+      for (int id : an.reduces[p]) assign_row(fn, id, acc_value(an.nodes[id], "acc"));
       for (size_t i = 0; i < an.nodes.size(); ++i) {
         const Node& n = an.nodes[i];
         if (n.dom != DOM_ROW || n.phase != p + 1 || is_reduce(n.opcode)) continue;
         std::string v = fn.val((int)i);
-        fn.body << "    rc.r" << i << " = " << v << ";\n";
-        fn.names[(int)i] = fmt("rc.r%zu", i);
+        assign_row(fn, i, v);
       }
       os << fn.body.str() << "    }\n";
     }
     os << "    (void)A; (void)rc; (void)acc;\n  }\n";
   }
 
-  void emit_epilogue(Mode mode) {
-    os << "  template <int V, class C> static DISC_DEV void epilogue(const Args& A, const RowCtx& rc, const Slot<V>& s, C col, OutSlot<V>& o) {\n";
-    os << "#pragma unroll\n    for (int e = 0; e < V; ++e) {\n";
-    Fn fn(*this, mode);
-    std::ostringstream tail;
-    for (const auto& out : an.outputs) {
-      const Access& a = an.accesses[out.access];
-      if (!elem_output(a)) continue;
-      const Node& n = an.nodes[out.node];
-      tail << "    o.o" << a.slot << ".v[e] = " << to_storage(fn.val(out.node), n.rk, a.dtype) << ";\n";
+  // column reduce stage 1: element granularity (one accumulator per column element)
+  void emit_col_accum() {
+    os << "  template <int P, int V> static DISC_DEV void accum(const Args& A, Acc<P>& acc, const Slot<V>& s, int e, int col, const RowCtx& rc) {\n";
+    Fn fn(*this, M_COL_ACCUM);
+    std::string tail;
+    for (int id : an.reduces[0]) {
+      const Node& n = an.nodes[id];
+      tail += "        " + fold_stmt(n, fn.val(n.in[0]), "col") + "\n";
     }
-    os << fn.body.str() << tail.str();
-    os << "    }\n    (void)A; (void)rc; (void)s; (void)col; (void)o;\n  }\n";
+    os << fn.body.str() << tail;
+    os << "    (void)A; (void)acc; (void)s; (void)e; (void)col; (void)rc;\n  }\n";
+  }
+
+  void emit_epilogue(Mode mode) {
+    os << "  template <int V, bool KEEP, class C> static DISC_DEV void epilogue(const Args& A, const RowCtx& rc, const Slot<V>& s, const Keep<V>& k, C col, int nvalid, OutSlot<V>& o) {\n";
+    auto flavour = [&](bool keep) {
+      Fn fn(*this, mode);
+      fn.P = an.n_phases;
+      fn.keep = keep;
+      std::ostringstream tail;
+      for (const auto& out : an.outputs) {
+        const Access& a = an.accesses[out.access];
+        if (!elem_output(a)) continue;
+        const Node& n = an.nodes[out.node];
+        tail << "        o.o" << a.slot << ".v[e] = " << to_storage(fn.val(out.node), n.rk, a.dtype) << ";\n";
+      }
+      emit_late_loads(os, fn, "      ");
+      os << "#pragma unroll\n      for (int e = 0; e < V; ++e) {\n" << fn.body.str() << tail.str() << "      }\n";
+    };
+    if (row_tmpl() && mode == M_ELEM) {
+      os << "    if constexpr (KEEP) {\n";
+      flavour(true);
+      os << "    } else {\n";
+      flavour(false);
+      os << "    }\n";
+    } else {
+      os << "    {\n";
+      flavour(false);
+      os << "    }\n";
+    }
+    os << "    (void)A; (void)rc; (void)s; (void)k; (void)col; (void)nvalid; (void)o;\n  }\n";
     os << "  static DISC_DEV void row_store(const Args& A, disc::i64 row, const RowCtx& rc) {\n";
     if (!col_tmpl()) {
       for (const auto& out : an.outputs) {
@@ -577,7 +734,6 @@ struct Gen {
   // Workspace ws0 holds one 8-byte cell per (accumulator field, outer, chunk, column); ws1 holds
   // the final reduce results, one plane per reduction, typed as the reduce result's register kind.
   void emit_col_extras() {
-    os << "  static DISC_DEV void acc_st(const Args& A, disc::i64 idx, const Acc<0>& a) {\n";
     int k = 0;
     auto cell = [&](const std::string& ct, const std::string& field, bool store) {
       std::string wide = (ct == "float" || ct == "double") ? "double" : "disc::i64";
@@ -585,6 +741,7 @@ struct Gen {
       else os << "    a." << field << " = (" << ct << ")reinterpret_cast<const " << wide << "*>(A.ws0)[" << k << " * A.aux0 + idx];\n";
       ++k;
     };
+    os << "  static DISC_DEV void acc_st(const Args& A, disc::i64 idx, const Acc<0>& a) {\n";
     for (int id : an.reduces[0]) {
       const Node& n = an.nodes[id];
       cell(acc_ctype(n), accf(n.reduce_slot), true);
@@ -622,7 +779,6 @@ struct Gen {
     os << fn.body.str() << tail.str();
     os << "    (void)A; (void)o; (void)c; (void)acc;\n  }\n";
   }
-  int n_acc_cells = 0;
 
   void emit_args() {
     os << "  struct Args {\n";
@@ -630,10 +786,17 @@ struct Gen {
     os << "  };\n";
   }
 
+  bool has_elem_outputs() const {
+    for (const auto& out : an.outputs)
+      if (elem_output(an.accesses[out.access])) return true;
+    return false;
+  }
+
   void emit_kernels(Generated* out) {
     const int V = an.vec_width;
+    int min_blocks = 1;   // per-CU resident blocks the register allocator must leave room for
     auto k = [&](const std::string& name, const std::string& body, const char* plan) {
-      os << "extern \"C\" __global__ void __launch_bounds__(256) " << name << "(Pat::Args A"
+      os << "extern \"C\" __global__ void __launch_bounds__(256, " << min_blocks << ") " << name << "(Pat::Args A"
          << (plan ? std::string(", disc::") + plan + " rp" : std::string()) << ") { " << body << " }\n";
       out->kernels.push_back(name);
     };
@@ -644,9 +807,11 @@ struct Gen {
       k("k_loop_scalar_i64", "disc::kloop_body<Pat, 1, 1, true>(A);", nullptr);
     } else if (an.tmpl == DISC_TEMPLATE_ROW_REDUCE) {
       for (int nv : {1, 2, 4, 8}) {
+        min_blocks = 1;   // natural allocation: capping registers here only produced spills
         k(fmt("k_row_vec_nv%d", nv), fmt("disc::row_reg_body<Pat, %d, %d>(A, rp);", V, nv), "RowPlan");
         k(fmt("k_row_scalar_nv%d", nv), fmt("disc::row_reg_body<Pat, 1, %d>(A, rp);", nv), "RowPlan");
       }
+      min_blocks = 1;
       k("k_row_stream_vec", fmt("disc::row_stream_body<Pat, %d>(A);", V), nullptr);
       k("k_row_stream_scalar", "disc::row_stream_body<Pat, 1>(A);", nullptr);
     } else {
@@ -662,22 +827,11 @@ struct Gen {
     }
   }
 
-  bool has_elem_outputs() const {
-    for (const auto& out : an.outputs)
-      if (elem_output(an.accesses[out.access])) return true;
-    return false;
-  }
-
   int run(Generated* out, std::string* err) {
-    if (col_tmpl()) {
-      for (const auto& a : an.accesses) {
-        if (a.kind == ACC_PARTIAL && a.has_inner) {
-          // [outer, inner] operands are addressed through rc.b like any strided operand: fine
-        }
-      }
-    }
     (void)err;
     build_layout();
+    plan_keeps();
+    plan_rinv();
     os << "// generated: one fused pattern, every kernel version\n";
     emit_acc_types();
     std::vector<char> all(an.accesses.size(), 1);
@@ -688,10 +842,11 @@ struct Gen {
     emit_args();
     os << "  struct RowCtx {\n" << row_fields() << "  };\n";
     if (!col_tmpl()) {
-      emit_slots(all, false);
+      emit_slots(all, false, true);
       emit_row_begin();
       emit_load_store(all, false);
-      emit_acc_fns();
+      emit_acc_basic();
+      if (row_tmpl()) emit_row_phase_fns();
       emit_epilogue(M_ELEM);
       os << "};\n";
     } else {
@@ -699,10 +854,11 @@ struct Gen {
       std::vector<int> roots;
       for (int id : an.reduces[0]) roots.push_back(an.nodes[id].in[0]);
       std::vector<char> need1 = accesses_needed(roots, true);
-      emit_slots(need1, false);
+      emit_slots(need1, false, false);
       emit_row_begin();
       emit_load_store(need1, false);
-      emit_acc_fns();
+      emit_acc_basic();
+      emit_col_accum();
       emit_col_extras();
       os << "  static constexpr int N_ACC_CELLS = " << n_acc_cells << ";\n";
       os << "};\n";
@@ -716,7 +872,7 @@ struct Gen {
         os << "  static constexpr int NPHASE = 0;\n  static constexpr int MAX_ACC_BYTES = 8;\n";
         os << "  template <int P> using Acc = int;\n";
         os << "  typedef Pat::Args Args;\n  typedef Pat::RowCtx RowCtx;\n";
-        emit_slots(need3, true);
+        emit_slots(need3, true, false);
         os << "  static DISC_DEV void row_begin(const Args& A, disc::i64 row, RowCtx& rc) { Pat::row_begin(A, row, rc); }\n";
         emit_load_store(need3, true);
         emit_epilogue(M_COL_EPI);

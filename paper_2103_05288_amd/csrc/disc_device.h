@@ -21,10 +21,13 @@
 //   row_begin(A,row,rc)                        fill RowCtx for `row` (loads per-row operands)
 //   load<V>(A,rc,col,nvalid,slot)              load a slot (nvalid < V: predicated per element)
 //   template<int P> struct Acc                 accumulator of reduction phase P
-//   acc_init<P>(acc)  acc_merge<P>(a,b)  acc_shfl<P>(acc,lane_mask)
-//   accum<P,V>(A,acc,slot,e,col,rc)            fold element e of a slot into acc
+//   acc_init<P>(acc)  acc_merge<P>(a,b)  acc_xchg<P,S>(acc)   (S: lane_xchg step)
+//   template<int V> struct Keep                per-element values carried between phases
+//   phase<P,V,KEEP>(A,acc,slot,keep,nvalid,col,rc)   fold one slot into acc (row reduce);
+//                                              KEEP=false recomputes instead of using `keep`
+//   accum<P,V>(A,acc,slot,e,col,rc)            fold element e of a slot into acc (column reduce)
 //   row_after<P>(A,rc,acc)                     per-row values that become known after phase P
-//   epilogue<V>(A,rc,slot,col,out)             per-element results of all outputs
+//   epilogue<V,KEEP>(A,rc,slot,keep,col,nvalid,out)  per-element results of all outputs
 //   store<V>(A,rc,col,nvalid,out)              store a slot of outputs
 //   row_store(A,row,rc)                        store per-row outputs (one lane per row calls it)
 //   NPHASE, MAX_ACC_BYTES
@@ -41,21 +44,24 @@ typedef unsigned long long u64;
 #define DISC_DEV __device__ __forceinline__
 
 // ---------------------------------------------------------------------------------------
-// Vectors of N storage elements with ELEMENT alignment only.  gfx950 runs with unaligned
-// global access enabled, so the compiler still emits one wide load / store (global_load_
-// dwordx4 for 16 bytes) and the hardware serves rows that start at any element.  This is
-// why no separate "aligned" kernel version is needed for rows whose length is not a
-// multiple of the vector width.
+// Vectors of N storage elements, loaded and stored with ELEMENT alignment only.  gfx950
+// runs with unaligned global access enabled, so the compiler still emits one wide access
+// (global_load_dwordx4 for 16 bytes) and the hardware serves rows that start at any element.
+// This is why no separate "aligned" kernel version is needed for rows whose length is not a
+// multiple of the vector width.  The payload is a native vector value (never a byte copy
+// into a struct), so it always lives in registers.
 // ---------------------------------------------------------------------------------------
 template <class T, int N>
-struct __attribute__((packed, aligned(alignof(T)))) Vec {
-  T v[N];
+struct Vec {
+  typedef T vec_t __attribute__((ext_vector_type(N)));
+  typedef vec_t unaligned_t __attribute__((aligned(alignof(T))));
+  vec_t v;
 };
 
 template <class T, int N, class I>
 DISC_DEV void ld(Vec<T, N>& d, const T* __restrict__ p, I off, int nvalid) {
   if (nvalid >= N) {
-    d = *reinterpret_cast<const Vec<T, N>*>(p + off);
+    d.v = *reinterpret_cast<const typename Vec<T, N>::unaligned_t*>(p + off);
   } else {
 #pragma unroll
     for (int e = 0; e < N; ++e) d.v[e] = e < nvalid ? p[off + e] : T(0);
@@ -65,7 +71,7 @@ DISC_DEV void ld(Vec<T, N>& d, const T* __restrict__ p, I off, int nvalid) {
 template <class T, int N, class I>
 DISC_DEV void st(T* __restrict__ p, I off, const Vec<T, N>& s, int nvalid) {
   if (nvalid >= N) {
-    *reinterpret_cast<Vec<T, N>*>(p + off) = s;
+    *reinterpret_cast<typename Vec<T, N>::unaligned_t*>(p + off) = s.v;
   } else {
 #pragma unroll
     for (int e = 0; e < N; ++e)
@@ -86,6 +92,18 @@ template <> DISC_DEV float from_f32<float>(float x) { return x; }
 template <> DISC_DEV _Float16 from_f32<_Float16>(float x) { return (_Float16)x; }
 template <> DISC_DEV __bf16 from_f32<__bf16>(float x) { return (__bf16)x; }
 
+// Per-element transcendental math on the hardware approximation units (about 1 ulp each):
+// the fused kernels have roughly 40 VALU lane-operations per element to spend before they stop
+// being HBM-bound, which IEEE-correct expf / division would use up several times over.
+DISC_DEV float fast_rcp(float x) { return __builtin_amdgcn_rcpf(x); }
+DISC_DEV float fast_rsqrt(float x) { return __builtin_amdgcn_rsqf(x); }
+DISC_DEV float fast_sqrt(float x) { return __builtin_amdgcn_sqrtf(x); }
+DISC_DEV float fast_exp(float x) { return __builtin_amdgcn_exp2f(x * 1.44269504088896341f); }
+DISC_DEV float fast_log(float x) { return __builtin_amdgcn_logf(x) * 0.693147180559945309f; }
+DISC_DEV float fast_sigmoid(float x) { return fast_rcp(1.0f + fast_exp(-x)); }
+// tanh(x) = 1 - 2 / (exp(2x) + 1): exact limits at +-inf, absolute error ~1e-7 everywhere
+DISC_DEV float fast_tanh(float x) { return 1.0f - 2.0f * fast_rcp(fast_exp(2.0f * x) + 1.0f); }
+
 // ---------------------------------------------------------------------------------------
 // Division by a runtime extent with constants the host precomputes from the shape
 // (round-up multiply-shift method of Granlund & Montgomery): for 0 <= n < 2^31,
@@ -97,14 +115,55 @@ struct FastDiv {
 DISC_DEV u32 fdiv(u32 n, const FastDiv& f) { return (__umulhi(n, f.m) + n) >> f.s; }
 
 // ---------------------------------------------------------------------------------------
-// cross-lane helpers (64-wide wavefronts)
+// Cross-lane exchange inside a 64-wide wavefront, all on the VALU (no LDS crossbar):
+// lane_xchg<S>(v) returns v of a partner lane such that combining a value with its partner
+// for S = 1, 2, 4, 8, 16, 32 in turn leaves every lane of each aligned 2S-lane group with
+// the combination of the whole group.  S = 1, 2: DPP quad permutes; S = 4, 8: DPP mirror
+// within 8 / 16 lanes (after the quad steps every quad is uniform, so mirroring pairs the
+// right quads); S = 16, 32: gfx950's permlane16 / permlane32 swaps, called with both operands
+// equal, which hand back the partner row / half as the second result.
 // ---------------------------------------------------------------------------------------
-DISC_DEV float shfl_xor(float v, int m) { return __shfl_xor(v, m, 64); }
-DISC_DEV int shfl_xor(int v, int m) { return __shfl_xor(v, m, 64); }
-DISC_DEV double shfl_xor(double v, int m) { return __shfl_xor(v, m, 64); }
-DISC_DEV i64 shfl_xor(i64 v, int m) {
-  int lo = __shfl_xor((int)(u32)(u64)v, m, 64), hi = __shfl_xor((int)((u64)v >> 32), m, 64);
-  return (i64)(((u64)(u32)hi << 32) | (u32)lo);
+template <int S>
+DISC_DEV u32 lane_xchg_u32(u32 v) {
+  if constexpr (S == 1) return (u32)__builtin_amdgcn_update_dpp(0, (int)v, 0xB1, 0xf, 0xf, true);        // quad_perm [1,0,3,2]
+  else if constexpr (S == 2) return (u32)__builtin_amdgcn_update_dpp(0, (int)v, 0x4E, 0xf, 0xf, true);   // quad_perm [2,3,0,1]
+  else if constexpr (S == 4) return (u32)__builtin_amdgcn_update_dpp(0, (int)v, 0x141, 0xf, 0xf, true);  // row_half_mirror
+  else if constexpr (S == 8) return (u32)__builtin_amdgcn_update_dpp(0, (int)v, 0x140, 0xf, 0xf, true);  // row_mirror
+  else if constexpr (S == 16) {
+    auto r = __builtin_amdgcn_permlane16_swap(v, v, false, false);
+    const bool odd_row = (threadIdx.x >> 4) & 1;
+    return odd_row ? r[0] : r[1];
+  } else {
+    auto r = __builtin_amdgcn_permlane32_swap(v, v, false, false);
+    const bool upper = (threadIdx.x >> 5) & 1;
+    return upper ? r[0] : r[1];
+  }
+}
+template <int S> DISC_DEV float lane_xchg(float v) { return __builtin_bit_cast(float, lane_xchg_u32<S>(__builtin_bit_cast(u32, v))); }
+template <int S> DISC_DEV int lane_xchg(int v) { return (int)lane_xchg_u32<S>((u32)v); }
+template <int S> DISC_DEV i64 lane_xchg(i64 v) {
+  const u32 lo = lane_xchg_u32<S>((u32)(u64)v), hi = lane_xchg_u32<S>((u32)((u64)v >> 32));
+  return (i64)(((u64)hi << 32) | lo);
+}
+template <int S> DISC_DEV double lane_xchg(double v) { return __builtin_bit_cast(double, lane_xchg<S>(__builtin_bit_cast(i64, v))); }
+
+// all-reduce of an accumulator over aligned groups of G lanes (G a power of two, <= 64)
+template <class Pat, int P, int S>
+DISC_DEV void group_step(typename Pat::template Acc<P>& acc, int G) {
+  if (G > S) {
+    typename Pat::template Acc<P> o = acc;
+    Pat::template acc_xchg<P, S>(o);
+    Pat::template acc_merge<P>(acc, o);
+  }
+}
+template <class Pat, int P>
+DISC_DEV void group_allreduce(typename Pat::template Acc<P>& acc, int G) {
+  group_step<Pat, P, 1>(acc, G);
+  group_step<Pat, P, 2>(acc, G);
+  group_step<Pat, P, 4>(acc, G);
+  group_step<Pat, P, 8>(acc, G);
+  group_step<Pat, P, 16>(acc, G);
+  group_step<Pat, P, 32>(acc, G);
 }
 
 // =======================================================================================
@@ -140,7 +199,8 @@ DISC_DEV void kloop_body(const typename Pat::Args& A) {
       for (int u = 0; u < U; ++u) {
         if (nv[u] > 0) {
           typename Pat::template OutSlot<V> o;
-          Pat::template epilogue<V>(A, rc[u], slot[u], col[u], o);
+          typename Pat::template Keep<V> kp;
+          Pat::template epilogue<V, false>(A, rc[u], slot[u], kp, col[u], nv[u], o);
           Pat::template store<V>(A, rc[u], col[u], nv[u], o);
         }
       }
@@ -159,7 +219,8 @@ DISC_DEV void kloop_body(const typename Pat::Args& A) {
       Pat::row_begin(A, row, rc);
       Pat::template load<V>(A, rc, col, nv, slot);
       typename Pat::template OutSlot<V> o;
-      Pat::template epilogue<V>(A, rc, slot, col, o);
+      typename Pat::template Keep<V> kp;
+      Pat::template epilogue<V, false>(A, rc, slot, kp, col, nv, o);
       Pat::template store<V>(A, rc, col, nv, o);
     }
   }
@@ -185,7 +246,8 @@ struct RowPlan {
 
 template <class Pat, int P, int V, int NV>
 DISC_DEV void row_phases(const typename Pat::Args& A, const RowPlan& rp, typename Pat::RowCtx& rc,
-                         const typename Pat::template Slot<V> (&slot)[NV], const int (&nvalid)[NV],
+                         const typename Pat::template Slot<V> (&slot)[NV],
+                         typename Pat::template Keep<V> (&keep)[NV], const int (&nvalid)[NV],
                          int col0, char* lds, int& parity) {
   if constexpr (P < Pat::NPHASE) {
     typename Pat::template Acc<P> acc;
@@ -193,17 +255,10 @@ DISC_DEV void row_phases(const typename Pat::Args& A, const RowPlan& rp, typenam
 #pragma unroll
     for (int j = 0; j < NV; ++j) {
       const int col = col0 + j * rp.G * V;
-#pragma unroll
-      for (int e = 0; e < V; ++e)
-        if (e < nvalid[j]) Pat::template accum<P, V>(A, acc, slot[j], e, col + e, rc);
+      if (nvalid[j] > 0) Pat::template phase<P, V, true>(A, acc, slot[j], keep[j], nvalid[j], col, rc);
     }
     // lanes of one wavefront
-    const int gw = rp.G < 64 ? rp.G : 64;
-    for (int m = gw >> 1; m > 0; m >>= 1) {
-      typename Pat::template Acc<P> o = acc;
-      Pat::template acc_shfl<P>(o, m);
-      Pat::template acc_merge<P>(acc, o);
-    }
+    group_allreduce<Pat, P>(acc, rp.G < 64 ? rp.G : 64);
     // wavefronts of one row
     if (rp.G > 64) {
       typedef typename Pat::template Acc<P> AccT;
@@ -221,7 +276,7 @@ DISC_DEV void row_phases(const typename Pat::Args& A, const RowPlan& rp, typenam
       }
     }
     Pat::template row_after<P>(A, rc, acc);
-    row_phases<Pat, P + 1, V, NV>(A, rp, rc, slot, nvalid, col0, lds, parity);
+    row_phases<Pat, P + 1, V, NV>(A, rp, rc, slot, keep, nvalid, col0, lds, parity);
   }
 }
 
@@ -241,6 +296,7 @@ DISC_DEV void row_reg_body(const typename Pat::Args& A, const RowPlan& rp) {
     const bool active = row < rows;
     typename Pat::RowCtx rc{};
     typename Pat::template Slot<V> slot[NV];
+    typename Pat::template Keep<V> keep[NV];
     int nvalid[NV];
     if (active) Pat::row_begin(A, row, rc);
 #pragma unroll
@@ -251,13 +307,13 @@ DISC_DEV void row_reg_body(const typename Pat::Args& A, const RowPlan& rp) {
       nvalid[j] = (active && j < rp.nv && n > 0) ? n : 0;
       if (nvalid[j] > 0) Pat::template load<V>(A, rc, col, nvalid[j], slot[j]);
     }
-    row_phases<Pat, 0, V, NV>(A, rp, rc, slot, nvalid, col0, lds, parity);
+    row_phases<Pat, 0, V, NV>(A, rp, rc, slot, keep, nvalid, col0, lds, parity);
 #pragma unroll
     for (int j = 0; j < NV; ++j) {
       if (nvalid[j] > 0) {
         const int col = col0 + j * rp.G * V;
         typename Pat::template OutSlot<V> o;
-        Pat::template epilogue<V>(A, rc, slot[j], col, o);
+        Pat::template epilogue<V, true>(A, rc, slot[j], keep[j], col, nvalid[j], o);
         Pat::template store<V>(A, rc, col, nvalid[j], o);
       }
     }
@@ -280,15 +336,10 @@ DISC_DEV void row_stream_phases(const typename Pat::Args& A, typename Pat::RowCt
       n = n > V ? V : n;
       typename Pat::template Slot<V> slot;
       Pat::template load<V>(A, rc, col, n, slot);
-#pragma unroll
-      for (int e = 0; e < V; ++e)
-        if (e < n) Pat::template accum<P, V>(A, acc, slot, e, col + e, rc);
+      typename Pat::template Keep<V> kp;
+      Pat::template phase<P, V, false>(A, acc, slot, kp, n, col, rc);
     }
-    for (int m = 32; m > 0; m >>= 1) {
-      AccT o = acc;
-      Pat::template acc_shfl<P>(o, m);
-      Pat::template acc_merge<P>(acc, o);
-    }
+    group_allreduce<Pat, P>(acc, 64);
     AccT* ex = reinterpret_cast<AccT*>(lds + parity * 16 * Pat::MAX_ACC_BYTES);
     parity ^= 1;
     const int wave = threadIdx.x >> 6;
@@ -320,7 +371,8 @@ DISC_DEV void row_stream_body(const typename Pat::Args& A) {
       typename Pat::template Slot<V> slot;
       Pat::template load<V>(A, rc, col, n, slot);
       typename Pat::template OutSlot<V> o;
-      Pat::template epilogue<V>(A, rc, slot, col, o);
+      typename Pat::template Keep<V> kp;
+      Pat::template epilogue<V, false>(A, rc, slot, kp, col, n, o);
       Pat::template store<V>(A, rc, col, n, o);
     }
     if (threadIdx.x == 0) Pat::row_store(A, row, rc);

@@ -117,7 +117,9 @@ int compile_source(disc_ctx* c, const std::string& src, std::vector<char>* code,
   if (hiprtcCreateProgram(&prog, src.c_str(), "disc_pattern.hip", 0, nullptr, nullptr) != HIPRTC_SUCCESS)
     return set_err(c, DISC_ERR_COMPILE, "hiprtcCreateProgram failed");
   const char* opts[] = {"--offload-arch=gfx950", "-O3", "-std=c++17", "-Xclang", "-target-feature", "-Xclang",
-                        "-packed-fp32-ops", "-Wno-unused-value"};
+                        "-packed-fp32-ops", "-Wno-unused-value",
+                        // the fused expressions are scalar per element on purpose: no packed-fp32 pairs
+                        "-fno-slp-vectorize", "-fno-vectorize"};
   auto t0 = std::chrono::steady_clock::now();
   hiprtcResult r = hiprtcCompileProgram(prog, (int)(sizeof opts / sizeof opts[0]), opts);
   *ms = std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - t0).count();
