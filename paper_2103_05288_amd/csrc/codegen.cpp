@@ -498,7 +498,8 @@ struct Gen {
     for (size_t i = 0; i < an.accesses.size(); ++i) {
       const Access& a = an.accesses[i];
       if (a.is_output || !a.has_inner || !need[i] || late(a)) continue;
-      os << "    disc::ld(s.a" << i << ", A.p" << a.slot << ", " << elem_base(a, i) << ", nvalid);\n";
+      os << "    disc::ld(s.a" << i << ", A.p" << a.slot << ", " << elem_base(a, i) << ", nvalid"
+         << (a.kind == ACC_FULL ? fmt(", rc.b%zu + col + V <= A.rows * A.inner", i) : std::string()) << ");\n";
     }
     if (with_red) {
       int k = 0;

@@ -58,9 +58,13 @@ struct Vec {
   vec_t v;
 };
 
+// `whole_ok`: all N elements lie inside the tensor even though only `nvalid` of them belong to
+// this row (the rest are the head of the next row).  Then the wide load is still taken and the
+// caller ignores the surplus elements; only the last slot of the whole tensor is read element
+// by element.  This keeps ragged rows on the wide-load path.
 template <class T, int N, class I>
-DISC_DEV void ld(Vec<T, N>& d, const T* __restrict__ p, I off, int nvalid) {
-  if (nvalid >= N) {
+DISC_DEV void ld(Vec<T, N>& d, const T* __restrict__ p, I off, int nvalid, bool whole_ok = false) {
+  if (nvalid >= N || whole_ok) {
     d.v = *reinterpret_cast<const typename Vec<T, N>::unaligned_t*>(p + off);
   } else {
 #pragma unroll

@@ -623,7 +623,7 @@ int disc_workspace_bytes(disc_ctx* ctx, int32_t id, const int64_t* dims, int n_d
   Pattern* p = get_pattern(ctx, id);
   if (!p || !out) return set_err(ctx, DISC_ERR_INVALID_ARG, "bad pattern id or null output");
   FullPlan fp;
-  int rc = make_plan(ctx, *p, dims, n_dims, -1, &fp);
+  int rc = make_plan(ctx, *p, dims, n_dims, ctx->force_variant, &fp);   // same selection disc_launch will make
   if (rc) return rc;
   *out = fp.pub.workspace_bytes;
   return DISC_OK;

@@ -1,0 +1,272 @@
+"""Host-side logic through the C ABI, no GPU needed: exports, checker, fusion decision, planner,
+error paths.  A host-only context (device -1) still runs the whole registration path including
+the one device compile for gfx950 (hipRTC cross-compiles without a GPU)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2103_05288_amd import Context, DiscError, VARIANTS, lib_path, load_library
+from workloads import PatternBuilder
+from workloads.configs import CONFIGS, algorithmic_bytes
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+V = {n: i for i, n in enumerate(VARIANTS)}
+
+
+@pytest.fixture(scope="module")
+def ctx():
+    c = Context(-1)
+    yield c
+    c.close()
+
+
+@pytest.fixture(scope="module")
+def handles(ctx):
+    return {n: ctx.register(cfg.pattern()) for n, cfg in CONFIGS.items()}
+
+
+def expect(code, fn, *a, **k):
+    with pytest.raises(DiscError) as e:
+        fn(*a, **k)
+    assert e.value.status == code, (e.value.status, e.value.message)
+    return e.value.message
+
+
+# ------------------------------------------------------------------ boundary
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "disc.h")).read()
+    body = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(disc_[a-z_]+)\s*\(", body))
+    assert {"disc_create", "disc_register_pattern", "disc_launch", "disc_plan"} <= declared
+    lib = ctypes.CDLL(lib_path())
+    for name in sorted(declared):
+        assert hasattr(lib, name), f"{name} declared in disc.h but not exported"
+    assert load_library() is not None
+
+
+def test_one_compile_per_pattern_and_pattern_cache(ctx, handles):
+    kinds = {n: h.info["template"] for n, h in handles.items()}
+    assert kinds == {"C0": "loop", "C1": "row_reduce", "C2": "row_reduce", "C3": "col_reduce", "C4": "row_reduce"}
+    before = ctx.stats()
+    for n, cfg in CONFIGS.items():
+        again = ctx.register(cfg.pattern())          # same op sequence: answered from the cache
+        assert again.id == handles[n].id
+        assert again.info["compile_events"] == 1
+    after = ctx.stats()
+    assert after["compile_events"] == before["compile_events"]
+    assert after["pattern_cache_hits"] == before["pattern_cache_hits"] + len(CONFIGS)
+    # planning at many shapes never compiles
+    for t in (1, 7, 1000, 99999):
+        handles["C4"].plan([t, 333])
+    assert ctx.stats()["compile_events"] == after["compile_events"]
+
+
+def test_generated_source_is_exposed(handles):
+    src = handles["C4"].source
+    assert "struct Pat" in src and "k_row_vec_nv4" in src and "row_reg_body" in src
+
+
+# ------------------------------------------------------------------ constraint closure
+def test_dim_classes_from_op_semantics(ctx, handles):
+    assert handles["C1"].info["n_dim_classes"] == 3
+    # Add: operands and result have the same shape -> symbolic dims get merged
+    pb = PatternBuilder()
+    d = pb.dims(6)
+    x = pb.param("f32", [d[0], d[1]])
+    r = pb.param("f32", [d[2], d[3]])
+    pb.output(pb.op("add", x, r, dims=[d[4], d[5]]))
+    h = ctx.register(pb.build())
+    cls = h.info["dim_class"]
+    assert cls[0] == cls[2] == cls[4] and cls[1] == cls[3] == cls[5] and cls[0] != cls[1]
+    assert h.plan([5, 7, 5, 7, 5, 7])["n_launches"] == 1
+    msg = expect("CONSTRAINT", h.plan, [5, 7, 6, 7, 5, 7])
+    assert "registered as equal" in msg
+
+
+def test_static_sizes(ctx):
+    pb = PatternBuilder()
+    t = pb.dim()
+    x = pb.param("f32", [t, pb.static(3)])
+    y = pb.param("f32", [t, pb.static(4)])
+    pb.output(pb.op("add", x, y))
+    assert "static sizes" in expect("BAD_PATTERN", ctx.register, pb.build())
+    pb = PatternBuilder()
+    t, h = pb.dims(2)
+    x = pb.param("f32", [t, h])
+    y = pb.param("f32", [t, pb.static(16)])
+    pb.output(pb.op("add", x, y))
+    hd = ctx.register(pb.build())
+    assert hd.plan([9, 16])["n_launches"] == 1
+    assert "static size" in expect("CONSTRAINT", hd.plan, [9, 17])
+
+
+def _two_chains(constraint=None):
+    """Two element-wise chains on tensors whose shapes are unrelated in the op list (what is left
+    of a framework Split after lowering): fusible only with an injected constraint."""
+    pb = PatternBuilder()
+    a, b, c, d = pb.dims(4)
+    x = pb.param("f32", [a, b])
+    z = pb.param("f32", [c, d])
+    o1 = pb.output(pb.op("exp", x))
+    o2 = pb.output(pb.op("neg", z))
+    if constraint == "dim":
+        pb.dim_eq(x, 0, z, 0)
+        pb.dim_eq(x, 1, z, 1)
+    elif constraint == "numel":
+        pb.numel_eq(x, z)
+    return pb.build(), (o1, o2)
+
+
+def test_caller_constraints_enable_fusion(ctx):
+    msg = expect("UNFUSIBLE", ctx.register, _two_chains()[0])
+    assert "DIM_EQ" in msg and "NUMEL_EQ" in msg
+    h = ctx.register(_two_chains("dim")[0])
+    assert h.info["template"] == "loop" and h.info["n_outputs"] == 2 and h.info["n_dim_classes"] == 2
+    assert h.info["n_collapsed"] == 1                      # [a,b] collapses to one flat group
+    expect("CONSTRAINT", h.plan, [4, 5, 4, 6])
+    hn = ctx.register(_two_chains("numel")[0])             # tensor-size equality: fused over a flat index
+    assert hn.info["template"] == "loop" and hn.info["n_collapsed"] == 1
+    assert hn.plan([4, 6, 3, 8])["inner"] == 24
+
+
+# ------------------------------------------------------------------ fusion decision
+def test_unfusible_patterns(ctx):
+    # reductions over different axes
+    pb = PatternBuilder()
+    t, h = pb.dims(2)
+    x = pb.param("f32", [t, h])
+    pb.output(pb.reduce("sum", x, 0))
+    pb.output(pb.reduce("sum", x, 1))
+    assert "different axes" in expect("UNFUSIBLE", ctx.register, pb.build())
+    # a row result consumed along the other axis of a square iteration space
+    pb = PatternBuilder()
+    n = pb.dim()
+    x = pb.param("f32", [n, n])
+    m = pb.reduce("max", x, 1)
+    pb.output(pb.op("sub", x, pb.broadcast(m, [n, n], [1])))
+    assert "other axes" in expect("UNFUSIBLE", ctx.register, pb.build())
+    # a column reduction feeding a second reduction needs another pass over the tensor
+    pb = PatternBuilder()
+    t, h = pb.dims(2)
+    x = pb.param("f32", [t, h])
+    mean = pb.op("div", pb.reduce("sum", x, 0), pb.dim_size(t))
+    d = pb.op("sub", x, pb.broadcast(mean, [t, h], [1]))
+    pb.output(pb.reduce("sum", pb.op("mul", d, d), 0))
+    assert "second pass" in expect("UNFUSIBLE", ctx.register, pb.build())
+
+
+def test_broadcast_contexts_and_collapse(ctx, handles):
+    # C1: [B, NH, S, S] with a [B,1,1,S] mask collapses to [B] x [NH*S] x [S]
+    assert handles["C1"].info["n_collapsed"] == 3
+    p = handles["C1"].plan([8, 12, 100])
+    assert p["rows"] == 8 * 12 * 100 and p["inner"] == 100
+    # outer sum x[i] + y[j]: one operand per axis, nothing collapses
+    pb = PatternBuilder()
+    n, m = pb.dims(2)
+    x = pb.param("f32", [n])
+    y = pb.param("f32", [m])
+    pb.output(pb.op("add", pb.broadcast(x, [n, m], [0]), pb.broadcast(y, [n, m], [1])))
+    h = ctx.register(pb.build())
+    assert h.info["n_collapsed"] == 2
+    # a pure element-wise rank-4 pattern collapses to one flat dim
+    pb = PatternBuilder()
+    d = pb.dims(4)
+    x = pb.param("bf16", d)
+    pb.output(pb.cast(pb.op("tanh", pb.cast(x, "f32")), "bf16"))
+    h = ctx.register(pb.build())
+    assert h.info["n_collapsed"] == 1 and h.plan([2, 3, 4, 5])["inner"] == 120
+
+
+@pytest.mark.parametrize("case", ["forward_ref", "rank5", "bool_arith", "no_output", "bad_axis", "bcast_order",
+                                  "argmax_dtype", "output_dtype"])
+def test_bad_patterns(ctx, case):
+    from workloads.pattern import Op, Pattern
+    p = Pattern(n_dims=2)
+    if case == "forward_ref":
+        p.ops = [Op("param", "f32", (), (0,)), Op("neg", "f32", (2,), (0,)), Op("output", "f32", (1,), (0,))]
+    elif case == "rank5":
+        lib = load_library()
+        from paper_2103_05288_amd.binding import disc_op, disc_constraint
+        ops = (disc_op * 1)()
+        ops[0].opcode, ops[0].dtype, ops[0].rank = 0, 0, 5
+        pid = ctypes.c_int32()
+        rc = lib.disc_register_pattern(ctx.h, ops, 1, (disc_constraint * 1)(), 0, ctypes.byref(pid))
+        assert rc == -2 and b"static rank" in lib.disc_last_error(ctx.h)
+        return
+    elif case == "bool_arith":
+        p.ops = [Op("param", "bool", (), (0,)), Op("add", "f32", (0, 0), (0,)), Op("output", "f32", (1,), (0,))]
+    elif case == "no_output":
+        p.ops = [Op("param", "f32", (), (0,))]
+    elif case == "bad_axis":
+        p.ops = [Op("param", "f32", (), (0, 1)), Op("reduce_sum", "f32", (0,), (0,), (2,)), Op("output", "f32", (1,), (0,))]
+    elif case == "bcast_order":
+        p.ops = [Op("param", "f32", (), (0, 1)), Op("broadcast", "f32", (0,), (0, 1), (1, 0)), Op("output", "f32", (1,), (0, 1))]
+    elif case == "argmax_dtype":
+        p.ops = [Op("param", "f32", (), (0, 1)), Op("reduce_argmax", "f32", (0,), (0,), (1,)), Op("output", "f32", (1,), (0,))]
+    elif case == "output_dtype":
+        p.ops = [Op("param", "f32", (), (0,)), Op("output", "bf16", (0,), (0,))]
+    expect("BAD_PATTERN", ctx.register, p)
+
+
+# ------------------------------------------------------------------ runtime flow (planner)
+def test_row_schedule_selection(handles):
+    h = handles["C4"]
+    short = h.plan([1000, 64])
+    assert short["variant_name"] == "row_reg_vec" and short["lanes_per_row"] < 64      # several rows per wavefront
+    mid = h.plan([1000, 1024])
+    assert mid["variant_name"] == "row_reg_vec" and mid["n_launches"] == 1
+    long_ = h.plan([100, 8192])
+    assert long_["variant_name"] == "row_reg_vec" and long_["lanes_per_row"] == 256     # wavefronts cooperate via LDS
+    assert long_["lanes_per_row"] * long_["slots_per_lane"] * long_["vec_width"] >= 8192
+    huge = h.plan([10, 100000])
+    assert huge["variant_name"] == "row_stream_vec"                                    # does not fit registers
+    for p in (short, mid, long_, huge):
+        assert p["grid"][0][0] >= 1 and p["block"][0][0] == 256
+    assert h.plan([7, 3])["vec_width"] in (1, 8)
+    forced = h.plan([1000, 1024], V["row_reg_scalar"])
+    assert forced["vec_width"] == 1 and forced["variant_name"] == "row_reg_scalar"
+    expect("INVALID_ARG", h.plan, [1000, 1024], V["loop_vec"])
+    expect("INVALID_ARG", h.plan, [10, 100000], V["row_reg_vec"])
+
+
+def test_loop_and_index_width_selection(ctx, handles):
+    h = handles["C0"]
+    p = h.plan([300, 768])
+    assert p["variant_name"] == "loop_vec" and p["index_bits"] == 32 and p["vec_width"] == 4
+    assert p["algorithmic_bytes"] == algorithmic_bytes(CONFIGS["C0"].pattern(), [300, 768])
+    assert h.plan([300, 5])["variant_name"] == "loop_scalar"      # padding a 5-wide row to 8 wastes too much
+    pb = PatternBuilder()
+    n = pb.dim()
+    x = pb.param("bf16", [n])
+    pb.output(pb.cast(pb.op("neg", pb.cast(x, "f32")), "bf16"))
+    big = ctx.register(pb.build())
+    assert big.plan([1 << 20])["index_bits"] == 32
+    assert big.plan([1 << 35])["index_bits"] == 64
+    expect("INVALID_ARG", big.plan, [1 << 35], V["loop_vec"])
+
+
+def test_col_reduce_plan_and_workspace(ctx, handles):
+    h = handles["C3"]
+    p = h.plan([65536, 1024])
+    assert p["variant_name"] == "col_3stage_vec" and p["n_launches"] == 3 and p["mid"] == 65536
+    assert p["workspace_bytes"] > 0 and ctx.workspace_bytes(h.id, [65536, 1024]) == p["workspace_bytes"]
+    assert p["grid"][0][1] > 1                                    # the reduced axis is cut into chunks
+    assert h.plan([1, 1024])["grid"][0][1] == 1
+    assert ctx.workspace_bytes(handles["C4"].id, [10, 10]) == 0
+
+
+def test_degenerate_shapes_and_errors(ctx, handles):
+    assert handles["C0"].plan([0, 768])["n_launches"] == 0
+    assert handles["C4"].plan([0, 64])["n_launches"] == 0
+    expect("EMPTY_REDUCE", handles["C4"].plan, [5, 0])
+    expect("EMPTY_REDUCE", handles["C3"].plan, [0, 1024])
+    assert handles["C3"].plan([5, 0])["n_launches"] == 0
+    expect("SHAPE", handles["C0"].plan, [-1, 768])
+    expect("SHAPE", handles["C0"].plan, [1 << 40, 1 << 40])
+    expect("INVALID_ARG", handles["C0"].plan, [1, 2, 3])
+    expect("INVALID_ARG", ctx.plan, 12345, [1, 2])
+    expect("INVALID_ARG", ctx.force_variant, 99)
+    # a host-only context cannot launch
+    expect("INVALID_ARG", handles["C0"].launch, [1, 768], [1, 2, 3], [4], stream=0)
