@@ -166,6 +166,7 @@ typedef struct {
   uint32_t grid[3][3];      /* per launch                                                      */
   uint32_t block[3][3];
   uint32_t lds_bytes[3];
+  char kernel[3][48];       /* entry-point symbol of each launch, as a profiler shows it        */
   int64_t rows, inner;      /* canonical iteration space [rows, inner] ([outer,mid,inner] for
                                column reduce: rows = outer * mid)                              */
   int64_t mid;              /* column reduce: reduced extent, else 0                           */

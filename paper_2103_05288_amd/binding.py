@@ -48,7 +48,7 @@ class disc_plan_t(C.Structure):
     _fields_ = [("variant", C.c_int32), ("n_launches", C.c_int32), ("index_bits", C.c_int32),
                 ("vec_width", C.c_int32), ("lanes_per_row", C.c_int32), ("slots_per_lane", C.c_int32),
                 ("reg_slots", C.c_int32), ("grid", (C.c_uint32 * 3) * 3), ("block", (C.c_uint32 * 3) * 3),
-                ("lds_bytes", C.c_uint32 * 3), ("rows", C.c_int64), ("inner", C.c_int64), ("mid", C.c_int64),
+                ("lds_bytes", C.c_uint32 * 3), ("kernel", (C.c_char * 48) * 3), ("rows", C.c_int64), ("inner", C.c_int64), ("mid", C.c_int64),
                 ("algorithmic_bytes", C.c_int64), ("workspace_bytes", C.c_size_t)]
 
 
@@ -209,7 +209,8 @@ class Context:
         arr, n = self._dims(dims)
         p = disc_plan_t()
         self._check(self.lib.disc_plan(self.h, pid, arr, n, None, None, int(force_variant), C.byref(p)))
-        d = {k: getattr(p, k) for k, _ in p._fields_ if k not in ("grid", "block", "lds_bytes")}
+        d = {k: getattr(p, k) for k, _ in p._fields_ if k not in ("grid", "block", "lds_bytes", "kernel")}
+        d["kernels"] = [bytes(p.kernel[i]).split(b"\0")[0].decode() for i in range(p.n_launches)]
         d["grid"] = [list(g) for g in p.grid][: p.n_launches]
         d["block"] = [list(b) for b in p.block][: p.n_launches]
         d["lds_bytes"] = list(p.lds_bytes)[: p.n_launches]

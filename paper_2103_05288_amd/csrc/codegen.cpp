@@ -374,6 +374,7 @@ struct Gen {
       if (need_rinv.count((int)i)) o << "    float q" << i << ";\n";
     }
     if (col_tmpl()) o << "    disc::i64 ob;\n";   // offset of this row's outer slice in the reduce-result planes
+    o << "    const char* sl;\n";                 // staged row vectors in LDS (row reduce), or null
     o << "    int unused_;\n";
     return o.str();
   }
@@ -616,11 +617,51 @@ struct Gen {
     os << "    (void)a;\n  }\n";
   }
 
+  // row-vector operands of a row reduce that can be staged in LDS, in access order
+  std::vector<int> staged_accesses() const {
+    std::vector<int> r;
+    if (!row_tmpl()) return r;
+    for (size_t i = 0; i < an.accesses.size(); ++i)
+      if (late(an.accesses[i]) && an.accesses[i].kind == ACC_ROWVEC) r.push_back((int)i);
+    return r;
+  }
+  int staged_index(int access) const {
+    std::vector<int> st = staged_accesses();
+    for (size_t k = 0; k < st.size(); ++k)
+      if (st[k] == access) return (int)k;
+    return -1;
+  }
+  // byte offset of staged operand k: operands are laid out one after the other, each
+  // (inner + V) elements long, rounded up to 16 bytes
+  void emit_stage_fns() {
+    std::vector<int> st = staged_accesses();
+    os << "  static constexpr int N_STAGED = " << st.size() << ";\n";
+    os << "  template <int V> static DISC_DEV int stage_offset(const Args& A, int k) {\n    int off = 0;\n";
+    for (size_t k = 0; k < st.size(); ++k)
+      os << "    if (k > " << k << ") off += (((int)A.inner + V) * " << dtype_bytes(an.accesses[st[k]].dtype) << " + 15) & ~15;\n";
+    os << "    (void)A; (void)k;\n    return off;\n  }\n";
+    os << "  template <int V> static DISC_DEV void stage(const Args& A, char* lds, int tid, int nthreads) {\n";
+    for (size_t k = 0; k < st.size(); ++k) {
+      const Access& a = an.accesses[st[k]];
+      os << "    {\n      " << dtype_ctype(a.dtype) << "* dst = reinterpret_cast<" << dtype_ctype(a.dtype)
+         << "*>(lds + stage_offset<V>(A, " << k << "));\n";
+      os << "      const int n = (int)A.inner;\n";
+      os << "      disc::stage_copy<V>(dst, A.p" << a.slot << ", n, tid, nthreads);\n    }\n";
+    }
+    os << "    (void)A; (void)lds; (void)tid; (void)nthreads;\n  }\n";
+  }
+
   void emit_late_loads(std::ostream& o, const Fn& fn, const char* ind) {
     for (int ai : fn.late_used) {
       const Access& a = an.accesses[ai];
       o << ind << "disc::Vec<" << dtype_ctype(a.dtype) << ", V> l" << ai << ";\n";
-      o << ind << "disc::ld(l" << ai << ", A.p" << a.slot << ", " << elem_base(a, ai) << ", nvalid);\n";
+      const int st = staged_index(ai);
+      if (st >= 0) {
+        o << ind << "if (rc.sl) disc::ld_lds(l" << ai << ", rc.sl, stage_offset<V>(A, " << st << "), (int)col);\n";
+        o << ind << "else disc::ld(l" << ai << ", A.p" << a.slot << ", " << elem_base(a, ai) << ", nvalid);\n";
+      } else {
+        o << ind << "disc::ld(l" << ai << ", A.p" << a.slot << ", " << elem_base(a, ai) << ", nvalid);\n";
+      }
     }
   }
 
@@ -638,7 +679,10 @@ struct Gen {
       tail_pred += "        if (e < nvalid) { " + st + " }\n";
     }
     emit_late_loads(os, fn, "      ");
-    os << "      if (nvalid >= V) {\n#pragma unroll\n      for (int e = 0; e < V; ++e) {\n" << fn.body.str() << tail << "      }\n";
+    // wave-uniform choice: the unpredicated body only when every lane of the wavefront has a
+    // full slot; otherwise the whole wavefront takes the predicated body once (a per-lane branch
+    // would make wavefronts with one ragged lane execute both bodies)
+    os << "      if (disc::wave_all(nvalid >= V)) {\n#pragma unroll\n      for (int e = 0; e < V; ++e) {\n" << fn.body.str() << tail << "      }\n";
     os << "      } else {\n#pragma unroll\n      for (int e = 0; e < V; ++e) {\n" << fn.body.str() << tail_pred << "      }\n      }\n";
   }
 
@@ -797,7 +841,7 @@ struct Gen {
     const int V = an.vec_width;
     int min_blocks = 1;   // per-CU resident blocks the register allocator must leave room for
     auto k = [&](const std::string& name, const std::string& body, const char* plan) {
-      os << "extern \"C\" __global__ void __launch_bounds__(256, " << min_blocks << ") " << name << "(Pat::Args A"
+      os << "extern \"C\" __global__ void __launch_bounds__(256, " << min_blocks << ") " << out->prefix << name << "(Pat::Args A"
          << (plan ? std::string(", disc::") + plan + " rp" : std::string()) << ") { " << body << " }\n";
       out->kernels.push_back(name);
     };
@@ -847,7 +891,10 @@ struct Gen {
       emit_row_begin();
       emit_load_store(all, false);
       emit_acc_basic();
-      if (row_tmpl()) emit_row_phase_fns();
+      if (row_tmpl()) {
+        emit_stage_fns();
+        emit_row_phase_fns();
+      }
       emit_epilogue(M_ELEM);
       os << "};\n";
     } else {
@@ -889,13 +936,16 @@ struct Gen {
     out->n_acc_cells = n_acc_cells;
     out->n_red_planes = col_tmpl() ? (int)an.reduces[0].size() : 0;
     out->has_epilogue = col_tmpl() ? has_elem_outputs() : true;
+    out->staged_elem_bytes.clear();
+    for (int ai : staged_accesses()) out->staged_elem_bytes.push_back(dtype_bytes(an.accesses[ai].dtype));
     return DISC_OK;
   }
 };
 
 }  // namespace
 
-int generate(const Analysis& an, Generated* out, std::string* err) {
+int generate(const Analysis& an, const std::string& prefix, Generated* out, std::string* err) {
+  out->prefix = prefix;
   Gen g(an);
   return g.run(out, err);
 }

@@ -151,6 +151,9 @@ template <int S> DISC_DEV i64 lane_xchg(i64 v) {
 }
 template <int S> DISC_DEV double lane_xchg(double v) { return __builtin_bit_cast(double, lane_xchg<S>(__builtin_bit_cast(i64, v))); }
 
+// true when the predicate holds in every active lane of the wavefront (scalar result)
+DISC_DEV bool wave_all(bool p) { return __builtin_amdgcn_ballot_w64(!p) == 0; }
+
 // all-reduce of an accumulator over aligned groups of G lanes (G a power of two, <= 64)
 template <class Pat, int P, int S>
 DISC_DEV void group_step(typename Pat::template Acc<P>& acc, int G) {
@@ -245,8 +248,30 @@ struct RowPlan {
   int G;        // lanes per row, power of two, <= blockDim.x
   int log2G;
   int nv;       // slots per lane actually needed at this shape (<= NV of the instantiation)
-  int pad;
+  int stage;    // 1: row-vector operands are staged once per block in dynamic LDS
 };
+
+// Row-vector operands (bias, gamma, beta, ...) are the same for every row a block processes:
+// when the host grants the LDS, each block copies them once into dynamic LDS, padded with V
+// zero elements, and every slot reads them from there with one aligned LDS vector read --
+// no per-slot trip through the vector memory pipeline and no ragged-tail path for them.
+extern __shared__ __attribute__((aligned(16))) char disc_stage_lds[];
+
+// cooperative copy of n elements (+ pad zero elements) into LDS: 16-byte pieces, then the tail
+template <int PAD, class T>
+DISC_DEV void stage_copy(T* dst, const T* __restrict__ src, int n, int tid, int nthreads) {
+  constexpr int E = 16 / (int)sizeof(T);
+  const int nvec = n / E;
+  for (int i = tid; i < nvec; i += nthreads)
+    reinterpret_cast<typename Vec<T, E>::vec_t*>(dst)[i] =
+        *reinterpret_cast<const typename Vec<T, E>::unaligned_t*>(src + (i64)i * E);
+  for (int i = nvec * E + tid; i < n + PAD; i += nthreads) dst[i] = i < n ? src[i] : T(0);
+}
+
+template <class T, int N>
+DISC_DEV void ld_lds(Vec<T, N>& d, const char* base, int byte_off, int col) {
+  d.v = *reinterpret_cast<const typename Vec<T, N>::vec_t*>(base + byte_off + col * (int)sizeof(T));
+}
 
 template <class Pat, int P, int V, int NV>
 DISC_DEV void row_phases(const typename Pat::Args& A, const RowPlan& rp, typename Pat::RowCtx& rc,
@@ -295,6 +320,12 @@ DISC_DEV void row_reg_body(const typename Pat::Args& A, const RowPlan& rp) {
   const int col0 = lane * V;
   int parity = 0;
   const i64 ngroups = (rows + rpb - 1) / rpb;
+  const char* staged = nullptr;
+  if (rp.stage) {
+    Pat::template stage<V>(A, disc_stage_lds, threadIdx.x, blockDim.x);
+    __syncthreads();
+    staged = disc_stage_lds;
+  }
   for (i64 rg = blockIdx.x; rg < ngroups; rg += gridDim.x) {
     const i64 row = rg * rpb + grp;
     const bool active = row < rows;
@@ -303,6 +334,7 @@ DISC_DEV void row_reg_body(const typename Pat::Args& A, const RowPlan& rp) {
     typename Pat::template Keep<V> keep[NV];
     int nvalid[NV];
     if (active) Pat::row_begin(A, row, rc);
+    rc.sl = staged;
 #pragma unroll
     for (int j = 0; j < NV; ++j) {
       const int col = col0 + j * rp.G * V;
@@ -368,6 +400,7 @@ DISC_DEV void row_stream_body(const typename Pat::Args& A) {
   for (i64 row = blockIdx.x; row < A.rows; row += gridDim.x) {
     typename Pat::RowCtx rc;
     Pat::row_begin(A, row, rc);
+    rc.sl = nullptr;
     row_stream_phases<Pat, 0, V>(A, rc, inner, lds, parity);
     for (int col = threadIdx.x * V; col < inner; col += blockDim.x * V) {
       int n = inner - col;

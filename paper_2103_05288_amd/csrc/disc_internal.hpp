@@ -157,10 +157,12 @@ struct ArgLayout {
 struct Generated {
   std::string source;
   ArgLayout args;
-  std::vector<std::string> kernels;   // entry-point names present in the module
+  std::string prefix;                 // per-pattern prefix of the entry-point symbols (profilers tell patterns apart)
+  std::vector<std::string> kernels;   // entry-point names present in the module, without the prefix
   int n_acc_cells = 0;                // column reduce: 8-byte cells per partial accumulator
   int n_red_planes = 0;               // column reduce: reduce-result planes in the workspace
   bool has_epilogue = true;           // column reduce: some output keeps the reduced axis
+  std::vector<int> staged_elem_bytes; // row reduce: element size of each row vector that can be staged in LDS
 };
 
 // checker.cpp: validate, close constraints, decide fusion, resolve contexts, collapse.
@@ -168,6 +170,6 @@ int analyze(const disc_op* ops, int n_ops, const disc_constraint* cs, int n_cs, 
             std::string* err);
 
 // codegen.cpp
-int generate(const Analysis& an, Generated* out, std::string* err);
+int generate(const Analysis& an, const std::string& prefix, Generated* out, std::string* err);
 
 }  // namespace disc

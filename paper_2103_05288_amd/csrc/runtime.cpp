@@ -99,6 +99,7 @@ struct disc_ctx {
   int row_target_nv = 4;     // tuning knobs, overridable from the environment for experiments
   int grid_mult = 8;
   int loop_unroll = 4;
+  int row_stage = 1;
 };
 
 namespace {
@@ -203,6 +204,7 @@ struct LaunchRec {
   uint32_t grid[3] = {1, 1, 1};
   uint32_t block = 256;
   int plan_kind = 0;         // 0 none, 1 RowPlan, 2 ColPlan
+  uint32_t dyn_lds = 0;      // dynamic LDS bytes
   DeviceRowPlan rp{};
   DeviceColPlan cp{};
 };
@@ -326,6 +328,14 @@ int make_plan(disc_ctx* c, const Pattern& p, const int64_t* dims, int n_dims, in
       L.rp.G = G;
       L.rp.log2G = ilog2_ceil(G);
       L.rp.nv = nv;
+      // stage row vectors in LDS when they fit a modest budget (keeps >= 3 blocks per CU resident)
+      {
+        int64_t bytes = 0;
+        for (int eb : p.gen.staged_elem_bytes) bytes += ((sv.inner + v) * eb + 15) & ~15ll;
+        const bool stage = c->row_stage && bytes > 0 && bytes <= 48 * 1024;
+        L.rp.pad = stage ? 1 : 0;
+        L.dyn_lds = stage ? (uint32_t)bytes : 0;
+      }
       const int rpb = 256 / G;
       const int64_t ngroups = (sv.rows + rpb - 1) / rpb;
       L.grid[0] = (uint32_t)std::min<int64_t>(ngroups, max_grid);
@@ -405,7 +415,8 @@ int make_plan(disc_ctx* c, const Pattern& p, const int64_t* dims, int n_dims, in
     for (int k = 0; k < 3; ++k) pub.grid[l][k] = fp->launches[l].grid[k];
     pub.block[l][0] = fp->launches[l].block;
     pub.block[l][1] = pub.block[l][2] = 1;
-    pub.lds_bytes[l] = 0;
+    pub.lds_bytes[l] = fp->launches[l].dyn_lds;
+    snprintf(pub.kernel[l], sizeof pub.kernel[l], "%s%s", p.gen.prefix.c_str(), fp->launches[l].kernel);
   }
   return DISC_OK;
 }
@@ -486,6 +497,7 @@ int disc_create(disc_ctx** out, int hip_device) {
     c->n_cus = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
   }
   if (const char* e = getenv("DISC_ROW_TARGET_NV")) c->row_target_nv = std::max(1, std::min(8, atoi(e)));
+  if (const char* e = getenv("DISC_ROW_STAGE")) c->row_stage = atoi(e) != 0;
   if (const char* e = getenv("DISC_GRID_MULT")) c->grid_mult = std::max(1, std::min(64, atoi(e)));
   if (const char* e = getenv("DISC_LOOP_UNROLL")) (void)e;   // the unroll factor is a compile-time constant of the kernels
   *out = c.release();
@@ -543,7 +555,7 @@ int disc_register_pattern(disc_ctx* ctx, const disc_op* ops, int n_ops, const di
   std::string err;
   int rc = analyze(ops, n_ops, cs, n_cs, &p->an, &err);
   if (rc) return set_err(ctx, rc, err);
-  rc = generate(p->an, &p->gen, &err);
+  rc = generate(p->an, "disc_p" + std::to_string(ctx->patterns.size()) + "_", &p->gen, &err);
   if (rc) return set_err(ctx, rc, err);
   p->gen.source = std::string(kDeviceHeader) + "\n" + p->gen.source;
 
@@ -582,7 +594,7 @@ int disc_register_pattern(disc_ctx* ctx, const disc_op* ops, int n_ops, const di
     if (e != hipSuccess) return hip_fail(ctx, e, "hipModuleLoadData");
     for (const auto& name : p->gen.kernels) {
       hipFunction_t f;
-      e = hipModuleGetFunction(&f, p->module, name.c_str());
+      e = hipModuleGetFunction(&f, p->module, (p->gen.prefix + name).c_str());
       if (e != hipSuccess) return hip_fail(ctx, e, ("hipModuleGetFunction " + name).c_str());
       p->fn[name] = f;
     }
@@ -694,7 +706,7 @@ int disc_launch(disc_ctx* ctx, int32_t id, const int64_t* dims, int n_dims, cons
       size += sizeof L.cp;
     }
     void* extra[] = {HIP_LAUNCH_PARAM_BUFFER_POINTER, buf, HIP_LAUNCH_PARAM_BUFFER_SIZE, &size, HIP_LAUNCH_PARAM_END};
-    hipError_t e = hipModuleLaunchKernel(it->second, L.grid[0], L.grid[1], L.grid[2], L.block, 1, 1, 0,
+    hipError_t e = hipModuleLaunchKernel(it->second, L.grid[0], L.grid[1], L.grid[2], L.block, 1, 1, L.dyn_lds,
                                          (hipStream_t)hip_stream, nullptr, extra);
     if (e != hipSuccess) return hip_fail(ctx, e, "hipModuleLaunchKernel");
     ctx->stats.device_launches++;
