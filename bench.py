@@ -125,15 +125,26 @@ class Sweep:
                 ins[4] = (ins[4].float() * 0.1).to(ins[4].dtype)
             outs = [arenas_out[k].take(s) for k, s in enumerate(out_shapes(d))]
             self.bound.append((d, ins, outs))
+        # arguments marshalled once per call site; the timed loop is one C call per launch
+        self.calls_bound = [self.handle.bind(d, ins, outs, workspace=self.workspace) for d, ins, outs in self.bound]
 
     def run_all(self):
-        h, ws = self.handle, self.workspace
-        for d, ins, outs in self.bound:
-            h.launch(d, ins, outs, workspace=ws)
+        for c in self.calls_bound:
+            c()
 
     def run_one(self, i):
-        d, ins, outs = self.bound[i]
-        self.handle.launch(d, ins, outs, workspace=self.workspace)
+        self.calls_bound[i]()
+
+    def timed_calls(self):
+        """Per-call device time inside a back-to-back sweep: one event between consecutive launches on
+        the launch stream, one synchronisation at the end."""
+        evs = [torch.cuda.Event(enable_timing=True) for _ in range(len(self.calls_bound) + 1)]
+        evs[0].record()
+        for i, c in enumerate(self.calls_bound):
+            c()
+            evs[i + 1].record()
+        evs[-1].synchronize()
+        return [evs[i].elapsed_time(evs[i + 1]) * 1e-3 for i in range(len(self.calls_bound))]
 
 
 def time_events(fn, stream=None):
@@ -208,6 +219,7 @@ def main():
     ap.add_argument("--configs", default="C0,C1,C2,C3,C4")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-budget", type=float, default=20.0)
+    ap.add_argument("--dump-calls", default="", help="write per-call dims / bytes / device time as JSON lines")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -249,10 +261,14 @@ def main():
         sw.run_all()
         torch.cuda.synchronize()
         t_cfg = min(time_events(sw.run_all) for _ in range(3))
-        per_call = []
-        for i in range(len(sw.calls)):
-            per_call.append(min(time_events(lambda: sw.run_one(i)) for _ in range(2)))
+        per_call = [min(a, b) for a, b in zip(sw.timed_calls(), sw.timed_calls())]
         plans = [sw.handle.plan(d) for d in sw.calls]
+        if args.dump_calls:
+            with open(args.dump_calls, "a") as f:
+                for d, b, t, pl in zip(sw.calls, sw.bytes, per_call, plans):
+                    f.write(json.dumps({"cfg": sw.name, "dims": d, "bytes": b, "us": round(t * 1e6, 2), "G": pl["lanes_per_row"],
+                                        "nv": pl["slots_per_lane"], "grid": pl["grid"][0][0] if pl["grid"] else 0,
+                                        "variant": pl["variant_name"]}) + "\n")
         by_kernel = {}
         for i, pl in enumerate(plans):
             key = "+".join(pl["kernels"])          # entry-point symbols, as rocprofv3 shows them

@@ -4,5 +4,5 @@ Python here is argument marshalling only: every step of the path (constraint clo
 fusion decision, code generation, the one device compile, shape calculation, version
 selection, launch) runs inside libdisc.so and its gfx950 kernels.
 """
-from .binding import (Context, DiscError, PatternHandle, lib_path, load_library,  # noqa: F401
+from .binding import (BoundCall, Context, DiscError, PatternHandle, lib_path, load_library,  # noqa: F401
                       OPCODE_IDS, DTYPE_IDS, VARIANTS, STATUS)

@@ -47,7 +47,7 @@ class disc_pattern_info_t(C.Structure):
 class disc_plan_t(C.Structure):
     _fields_ = [("variant", C.c_int32), ("n_launches", C.c_int32), ("index_bits", C.c_int32),
                 ("vec_width", C.c_int32), ("lanes_per_row", C.c_int32), ("slots_per_lane", C.c_int32),
-                ("reg_slots", C.c_int32), ("grid", (C.c_uint32 * 3) * 3), ("block", (C.c_uint32 * 3) * 3),
+                ("reg_slots", C.c_int32), ("row_shift", C.c_int32), ("grid", (C.c_uint32 * 3) * 3), ("block", (C.c_uint32 * 3) * 3),
                 ("lds_bytes", C.c_uint32 * 3), ("kernel", (C.c_char * 48) * 3), ("rows", C.c_int64), ("inner", C.c_int64), ("mid", C.c_int64),
                 ("algorithmic_bytes", C.c_int64), ("workspace_bytes", C.c_size_t)]
 
@@ -130,10 +130,37 @@ def marshal_pattern(pattern):
     return ops, len(pattern.ops), cs, len(pattern.constraints)
 
 
+class BoundCall:
+    """One disc_launch with its arguments marshalled once: calling it is a single C call.
+    Keeps the tensors alive; the pointers must stay valid for as long as it is used."""
+
+    def __init__(self, ctx: "Context", pid: int, dims, inputs, outputs, workspace, workspace_bytes, stream):
+        self._keep = (list(inputs), list(outputs), workspace)
+        self._fn = ctx.lib.disc_launch
+        self._ctx = ctx
+        self._args = (ctx.h, pid, (C.c_int64 * max(1, len(dims)))(*[int(d) for d in dims]), len(dims),
+                      (C.c_void_p * max(1, len(inputs)))(*[_ptr(t) for t in inputs]), len(inputs),
+                      (C.c_void_p * max(1, len(outputs)))(*[_ptr(t) for t in outputs]), len(outputs),
+                      C.c_void_p(_ptr(workspace)) if workspace is not None else C.c_void_p(),
+                      C.c_size_t(workspace_bytes), C.c_void_p(stream))
+
+    def __call__(self):
+        rc = self._fn(*self._args)
+        if rc != 0:
+            self._ctx._check(rc)
+
+
 class PatternHandle:
     def __init__(self, ctx: "Context", pid: int):
         self.ctx, self.id = ctx, pid
         self.info = ctx.pattern_info(pid)
+
+    def bind(self, dims, inputs, outputs, workspace=None, stream: Optional[int] = None) -> BoundCall:
+        if stream is None:
+            import torch
+            stream = torch.cuda.current_stream().cuda_stream
+        wsb = workspace.numel() * workspace.element_size() if workspace is not None else 0
+        return BoundCall(self.ctx, self.id, dims, inputs, outputs, workspace, wsb, stream)
 
     def launch(self, dims, inputs, outputs, **kw):
         return self.ctx.launch(self.id, dims, inputs, outputs, **kw)

@@ -65,6 +65,7 @@ struct Gen {
   std::set<int> keep_nodes;
   std::map<int, int> produced_phase;
   std::set<int> need_rinv;     // per-row values whose reciprocal is precomputed
+  std::set<int> need_nl2e;     // per-row values r for which -r*log2(e) is precomputed (exp(x - r))
   explicit Gen(const Analysis& a) : an(a) {}
 
   static bool is_reduce(int oc) { return oc >= DISC_REDUCE_SUM && oc <= DISC_REDUCE_ARGMAX; }
@@ -264,7 +265,14 @@ struct Gen {
       switch (n.opcode) {
         case DISC_NEG: return "-" + a(0);
         case DISC_ABS: return k == RK_F32 ? "fabsf(" + a(0) + ")" : "(" + a(0) + " < 0 ? -" + a(0) + " : " + a(0) + ")";
-        case DISC_EXP: return (f ? "disc::fast_exp(" : "expf(") + a(0) + ")";
+        case DISC_EXP: {
+          // exp(x - r) with r a per-row value: exp2(fma(x, log2e, -r*log2e)), the product with r
+          // is made once per row
+          const Node& s0 = g.an.nodes[n.in[0]];
+          if (f && mode == M_ELEM && s0.opcode == DISC_SUB && s0.rk == RK_F32 && g.need_nl2e.count(s0.in[1]))
+            return "disc::fast_exp2(__builtin_fmaf(" + as(s0.in[0], RK_F32) + ", 1.44269504088896341f, " + fmt("rc.n%d", s0.in[1]) + "))";
+          return (f ? "disc::fast_exp(" : "expf(") + a(0) + ")";
+        }
         case DISC_LOG: return (f ? "disc::fast_log(" : "logf(") + a(0) + ")";
         case DISC_TANH: return (f ? "disc::fast_tanh(" : "tanhf(") + a(0) + ")";
         case DISC_SQRT: return (f ? "disc::fast_sqrt(" : "sqrtf(") + a(0) + ")";
@@ -351,7 +359,14 @@ struct Gen {
   }
   void plan_rinv() {
     need_rinv.clear();
+    need_nl2e.clear();
     if (col_tmpl()) return;
+    for (const Node& n : an.nodes)
+      if (n.opcode == DISC_EXP && n.dom == DOM_ELEM) {
+        const Node& s0 = an.nodes[n.in[0]];
+        if (s0.opcode == DISC_SUB && s0.rk == RK_F32 && an.nodes[s0.in[1]].dom == DOM_ROW && an.nodes[s0.in[1]].rk == RK_F32)
+          need_nl2e.insert(s0.in[1]);
+      }
     for (const Node& n : an.nodes)
       if (n.opcode == DISC_DIV && n.rk == RK_F32 && n.dom == DOM_ELEM) {
         const Node& d = an.nodes[n.in[1]];
@@ -372,15 +387,18 @@ struct Gen {
       const bool perrow_param = n.opcode == DISC_PARAM && !an.accesses[n.access].has_inner;
       if ((!col_tmpl() && n.dom == DOM_ROW) || perrow_param) o << "    " << reg_ctype(n.rk) << " r" << i << ";\n";
       if (need_rinv.count((int)i)) o << "    float q" << i << ";\n";
+      if (need_nl2e.count((int)i)) o << "    float n" << i << ";\n";
     }
     if (col_tmpl()) o << "    disc::i64 ob;\n";   // offset of this row's outer slice in the reduce-result planes
     o << "    const char* sl;\n";                 // staged row vectors in LDS (row reduce), or null
+    o << "    bool shifted;\n";                   // slot grid shifted by the row's misalignment
     o << "    int unused_;\n";
     return o.str();
   }
   void assign_row(Fn& fn, size_t i, const std::string& v) {
     fn.body << "    rc.r" << i << " = " << v << ";\n";
     if (need_rinv.count((int)i)) fn.body << "    rc.q" << i << " = 1.0f / rc.r" << i << ";\n";
+    if (need_nl2e.count((int)i)) fn.body << "    rc.n" << i << " = -1.44269504088896341f * rc.r" << i << ";\n";
     fn.names[(int)i] = fmt("rc.r%zu", i);
   }
 
@@ -495,11 +513,11 @@ struct Gen {
   }
 
   void emit_load_store(const std::vector<char>& need, bool with_red) {
-    os << "  template <int V, class C> static DISC_DEV void load(const Args& A, const RowCtx& rc, C col, int nvalid, Slot<V>& s) {\n";
+    os << "  template <int V, class C> static DISC_DEV void load(const Args& A, const RowCtx& rc, C col, disc::Span sp, Slot<V>& s) {\n";
     for (size_t i = 0; i < an.accesses.size(); ++i) {
       const Access& a = an.accesses[i];
       if (a.is_output || !a.has_inner || !need[i] || late(a)) continue;
-      os << "    disc::ld(s.a" << i << ", A.p" << a.slot << ", " << elem_base(a, i) << ", nvalid"
+      os << "    disc::ld(s.a" << i << ", A.p" << a.slot << ", " << elem_base(a, i) << ", sp"
          << (a.kind == ACC_FULL ? fmt(", rc.b%zu + col + V <= A.rows * A.inner", i) : std::string()) << ");\n";
     }
     if (with_red) {
@@ -507,18 +525,18 @@ struct Gen {
       for (int id : an.reduces[0]) {
         const Node& n = an.nodes[id];
         os << "    disc::ld(s.red" << n.reduce_slot << ", reinterpret_cast<const " << reg_ctype(n.rk)
-           << "*>(reinterpret_cast<const char*>(A.ws1) + " << k << " * A.aux1), rc.ob + col, nvalid);\n";
+           << "*>(reinterpret_cast<const char*>(A.ws1) + " << k << " * A.aux1), rc.ob + col, sp);\n";
         ++k;
       }
     }
-    os << "    (void)A; (void)rc; (void)col; (void)nvalid; (void)s;\n  }\n";
-    os << "  template <int V, class C> static DISC_DEV void store(const Args& A, const RowCtx& rc, C col, int nvalid, const OutSlot<V>& o) {\n";
+    os << "    (void)A; (void)rc; (void)col; (void)sp; (void)s;\n  }\n";
+    os << "  template <int V, class C> static DISC_DEV void store(const Args& A, const RowCtx& rc, C col, disc::Span sp, const OutSlot<V>& o) {\n";
     for (size_t i = 0; i < an.accesses.size(); ++i) {
       const Access& a = an.accesses[i];
       if (!a.is_output || !elem_output(a)) continue;
-      os << "    disc::st(A.o" << a.slot << ", " << elem_base(a, i) << ", o.o" << a.slot << ", nvalid);\n";
+      os << "    disc::st(A.o" << a.slot << ", " << elem_base(a, i) << ", o.o" << a.slot << ", sp);\n";
     }
-    os << "    (void)A; (void)rc; (void)col; (void)nvalid; (void)o;\n  }\n";
+    os << "    (void)A; (void)rc; (void)col; (void)sp; (void)o;\n  }\n";
   }
 
   void emit_acc_types() {
@@ -632,13 +650,13 @@ struct Gen {
     return -1;
   }
   // byte offset of staged operand k: operands are laid out one after the other, each
-  // (inner + V) elements long, rounded up to 16 bytes
+  // (V + inner + V) elements long (zero padding in front and behind), rounded up to 16 bytes
   void emit_stage_fns() {
     std::vector<int> st = staged_accesses();
     os << "  static constexpr int N_STAGED = " << st.size() << ";\n";
     os << "  template <int V> static DISC_DEV int stage_offset(const Args& A, int k) {\n    int off = 0;\n";
     for (size_t k = 0; k < st.size(); ++k)
-      os << "    if (k > " << k << ") off += (((int)A.inner + V) * " << dtype_bytes(an.accesses[st[k]].dtype) << " + 15) & ~15;\n";
+      os << "    if (k > " << k << ") off += (((int)A.inner + 2 * V) * " << dtype_bytes(an.accesses[st[k]].dtype) << " + 15) & ~15;\n";
     os << "    (void)A; (void)k;\n    return off;\n  }\n";
     os << "  template <int V> static DISC_DEV void stage(const Args& A, char* lds, int tid, int nthreads) {\n";
     for (size_t k = 0; k < st.size(); ++k) {
@@ -657,10 +675,10 @@ struct Gen {
       o << ind << "disc::Vec<" << dtype_ctype(a.dtype) << ", V> l" << ai << ";\n";
       const int st = staged_index(ai);
       if (st >= 0) {
-        o << ind << "if (rc.sl) disc::ld_lds(l" << ai << ", rc.sl, stage_offset<V>(A, " << st << "), (int)col);\n";
-        o << ind << "else disc::ld(l" << ai << ", A.p" << a.slot << ", " << elem_base(a, ai) << ", nvalid);\n";
+        o << ind << "if (rc.sl) disc::ld_lds(l" << ai << ", rc.sl, stage_offset<V>(A, " << st << "), (int)col, rc.shifted);\n";
+        o << ind << "else disc::ld(l" << ai << ", A.p" << a.slot << ", " << elem_base(a, ai) << ", sp);\n";
       } else {
-        o << ind << "disc::ld(l" << ai << ", A.p" << a.slot << ", " << elem_base(a, ai) << ", nvalid);\n";
+        o << ind << "disc::ld(l" << ai << ", A.p" << a.slot << ", " << elem_base(a, ai) << ", sp);\n";
       }
     }
   }
@@ -676,18 +694,18 @@ struct Gen {
       const std::string x = fn.val(n.in[0]);
       const std::string st = fold_stmt(n, x, "col + e");
       tail += "        " + st + "\n";
-      tail_pred += "        if (e < nvalid) { " + st + " }\n";
+      tail_pred += "        if (sp.has(e)) { " + st + " }\n";
     }
     emit_late_loads(os, fn, "      ");
     // wave-uniform choice: the unpredicated body only when every lane of the wavefront has a
     // full slot; otherwise the whole wavefront takes the predicated body once (a per-lane branch
     // would make wavefronts with one ragged lane execute both bodies)
-    os << "      if (disc::wave_all(nvalid >= V)) {\n#pragma unroll\n      for (int e = 0; e < V; ++e) {\n" << fn.body.str() << tail << "      }\n";
+    os << "      if (disc::wave_all(sp.full(V))) {\n#pragma unroll\n      for (int e = 0; e < V; ++e) {\n" << fn.body.str() << tail << "      }\n";
     os << "      } else {\n#pragma unroll\n      for (int e = 0; e < V; ++e) {\n" << fn.body.str() << tail_pred << "      }\n      }\n";
   }
 
   void emit_row_phase_fns() {
-    os << "  template <int P, int V, bool KEEP> static DISC_DEV void phase(const Args& A, Acc<P>& acc, const Slot<V>& s, Keep<V>& k, int nvalid, int col, const RowCtx& rc) {\n";
+    os << "  template <int P, int V, bool KEEP> static DISC_DEV void phase(const Args& A, Acc<P>& acc, const Slot<V>& s, Keep<V>& k, disc::Span sp, int col, const RowCtx& rc) {\n";
     for (int p = 0; p < an.n_phases; ++p) {
       os << "    if constexpr (P == " << p << ") {\n";
       os << "      if constexpr (KEEP) {\n";
@@ -696,7 +714,7 @@ struct Gen {
       emit_phase_flavour(p, false);
       os << "      }\n    }\n";
     }
-    os << "    (void)A; (void)acc; (void)s; (void)k; (void)nvalid; (void)col; (void)rc;\n  }\n";
+    os << "    (void)A; (void)acc; (void)s; (void)k; (void)sp; (void)col; (void)rc;\n  }\n";
     // per-row values known after phase P
     os << "  template <int P> static DISC_DEV void row_after(const Args& A, RowCtx& rc, const Acc<P>& acc) {\n";
     for (int p = 0; p < an.n_phases; ++p) {
@@ -734,20 +752,28 @@ struct Gen {
   }
 
   void emit_epilogue(Mode mode) {
-    os << "  template <int V, bool KEEP, class C> static DISC_DEV void epilogue(const Args& A, const RowCtx& rc, const Slot<V>& s, const Keep<V>& k, C col, int nvalid, OutSlot<V>& o) {\n";
+    os << "  template <int V, bool KEEP, class C> static DISC_DEV void epilogue(const Args& A, const RowCtx& rc, const Slot<V>& s, const Keep<V>& k, C col, disc::Span sp, OutSlot<V>& o) {\n";
     auto flavour = [&](bool keep) {
       Fn fn(*this, mode);
       fn.P = an.n_phases;
       fn.keep = keep;
-      std::ostringstream tail;
+      std::ostringstream tail, decl, pack;
       for (const auto& out : an.outputs) {
         const Access& a = an.accesses[out.access];
         if (!elem_output(a)) continue;
         const Node& n = an.nodes[out.node];
-        tail << "        o.o" << a.slot << ".v[e] = " << to_storage(fn.val(out.node), n.rk, a.dtype) << ";\n";
+        if (is_float_dtype(a.dtype)) {
+          // float results are collected in fp32 and rounded to the storage type two at a time
+          decl << "      float y" << a.slot << "[V];\n";
+          tail << "        y" << a.slot << "[e] = " << convert(fn.val(out.node), n.rk, RK_F32) << ";\n";
+          pack << "      disc::cvt_vec(o.o" << a.slot << ", y" << a.slot << ");\n";
+        } else {
+          tail << "        o.o" << a.slot << ".v[e] = " << to_storage(fn.val(out.node), n.rk, a.dtype) << ";\n";
+        }
       }
       emit_late_loads(os, fn, "      ");
-      os << "#pragma unroll\n      for (int e = 0; e < V; ++e) {\n" << fn.body.str() << tail.str() << "      }\n";
+      os << decl.str();
+      os << "#pragma unroll\n      for (int e = 0; e < V; ++e) {\n" << fn.body.str() << tail.str() << "      }\n" << pack.str();
     };
     if (row_tmpl() && mode == M_ELEM) {
       os << "    if constexpr (KEEP) {\n";
@@ -760,7 +786,7 @@ struct Gen {
       flavour(false);
       os << "    }\n";
     }
-    os << "    (void)A; (void)rc; (void)s; (void)k; (void)col; (void)nvalid; (void)o;\n  }\n";
+    os << "    (void)A; (void)rc; (void)s; (void)k; (void)col; (void)sp; (void)o;\n  }\n";
     os << "  static DISC_DEV void row_store(const Args& A, disc::i64 row, const RowCtx& rc) {\n";
     if (!col_tmpl()) {
       for (const auto& out : an.outputs) {
@@ -839,9 +865,9 @@ struct Gen {
 
   void emit_kernels(Generated* out) {
     const int V = an.vec_width;
-    int min_blocks = 1;   // per-CU resident blocks the register allocator must leave room for
+    int max_threads = 256;   // largest block the entry point may be launched with
     auto k = [&](const std::string& name, const std::string& body, const char* plan) {
-      os << "extern \"C\" __global__ void __launch_bounds__(256, " << min_blocks << ") " << out->prefix << name << "(Pat::Args A"
+      os << "extern \"C\" __global__ void __launch_bounds__(" << max_threads << ") " << out->prefix << name << "(Pat::Args A"
          << (plan ? std::string(", disc::") + plan + " rp" : std::string()) << ") { " << body << " }\n";
       out->kernels.push_back(name);
     };
@@ -851,12 +877,16 @@ struct Gen {
       k("k_loop_scalar", "disc::kloop_body<Pat, 1, 4, false>(A);", nullptr);
       k("k_loop_scalar_i64", "disc::kloop_body<Pat, 1, 1, true>(A);", nullptr);
     } else if (an.tmpl == DISC_TEMPLATE_ROW_REDUCE) {
-      for (int nv : {1, 2, 4, 8}) {
-        min_blocks = 1;   // natural allocation: capping registers here only produced spills
+      // two slots per lane keep the register footprint near 100 VGPRs (4-5 waves per SIMD); longer
+      // rows get more lanes (blocks of up to 1024 threads) rather than more slots per lane
+      for (int nv : {1, 2}) {
         k(fmt("k_row_vec_nv%d", nv), fmt("disc::row_reg_body<Pat, %d, %d>(A, rp);", V, nv), "RowPlan");
         k(fmt("k_row_scalar_nv%d", nv), fmt("disc::row_reg_body<Pat, 1, %d>(A, rp);", nv), "RowPlan");
       }
-      min_blocks = 1;
+      max_threads = 1024;
+      k("k_row_vec_nv2w", fmt("disc::row_reg_body<Pat, %d, 2>(A, rp);", V), "RowPlan");
+      k("k_row_scalar_nv2w", "disc::row_reg_body<Pat, 1, 2>(A, rp);", "RowPlan");
+      max_threads = 256;
       k("k_row_stream_vec", fmt("disc::row_stream_body<Pat, %d>(A);", V), nullptr);
       k("k_row_stream_scalar", "disc::row_stream_body<Pat, 1>(A);", nullptr);
     } else {

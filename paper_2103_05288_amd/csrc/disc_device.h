@@ -19,16 +19,16 @@
 //   template<int V> struct Slot      V consecutive elements of every per-element operand
 //   template<int V> struct OutSlot   V consecutive elements of every per-element output
 //   row_begin(A,row,rc)                        fill RowCtx for `row` (loads per-row operands)
-//   load<V>(A,rc,col,nvalid,slot)              load a slot (nvalid < V: predicated per element)
+//   load<V>(A,rc,col,span,slot)                load a slot (span: elements of the slot inside the row)
 //   template<int P> struct Acc                 accumulator of reduction phase P
 //   acc_init<P>(acc)  acc_merge<P>(a,b)  acc_xchg<P,S>(acc)   (S: lane_xchg step)
 //   template<int V> struct Keep                per-element values carried between phases
-//   phase<P,V,KEEP>(A,acc,slot,keep,nvalid,col,rc)   fold one slot into acc (row reduce);
+//   phase<P,V,KEEP>(A,acc,slot,keep,span,col,rc)   fold one slot into acc (row reduce);
 //                                              KEEP=false recomputes instead of using `keep`
 //   accum<P,V>(A,acc,slot,e,col,rc)            fold element e of a slot into acc (column reduce)
 //   row_after<P>(A,rc,acc)                     per-row values that become known after phase P
-//   epilogue<V,KEEP>(A,rc,slot,keep,col,nvalid,out)  per-element results of all outputs
-//   store<V>(A,rc,col,nvalid,out)              store a slot of outputs
+//   epilogue<V,KEEP>(A,rc,slot,keep,col,span,out)  per-element results of all outputs
+//   store<V>(A,rc,col,span,out)                store a slot of outputs
 //   row_store(A,row,rc)                        store per-row outputs (one lane per row calls it)
 //   NPHASE, MAX_ACC_BYTES
 #pragma once
@@ -58,28 +58,36 @@ struct Vec {
   vec_t v;
 };
 
-// `whole_ok`: all N elements lie inside the tensor even though only `nvalid` of them belong to
-// this row (the rest are the head of the next row).  Then the wide load is still taken and the
-// caller ignores the surplus elements; only the last slot of the whole tensor is read element
-// by element.  This keeps ragged rows on the wide-load path.
+// Elements [lo, hi) of a slot belong to the row; a slot in the middle of a row has lo = 0, hi = N.
+struct Span {
+  int lo, hi;
+  DISC_DEV bool full(int n) const { return lo == 0 && hi >= n; }
+  DISC_DEV bool has(int e) const { return e >= lo && e < hi; }
+  DISC_DEV bool any() const { return hi > lo; }
+};
+
+// `whole_ok`: all N elements lie inside the tensor even though only part of them belong to this
+// row (the rest are the tail of the previous / head of the next row).  Then the wide load is
+// still taken and the caller ignores the surplus elements; only a slot that would leave the
+// tensor is read element by element.  This keeps ragged rows on the wide-load path.
 template <class T, int N, class I>
-DISC_DEV void ld(Vec<T, N>& d, const T* __restrict__ p, I off, int nvalid, bool whole_ok = false) {
-  if (nvalid >= N || whole_ok) {
+DISC_DEV void ld(Vec<T, N>& d, const T* __restrict__ p, I off, Span sp, bool whole_ok = false) {
+  if (sp.full(N) || whole_ok) {
     d.v = *reinterpret_cast<const typename Vec<T, N>::unaligned_t*>(p + off);
   } else {
 #pragma unroll
-    for (int e = 0; e < N; ++e) d.v[e] = e < nvalid ? p[off + e] : T(0);
+    for (int e = 0; e < N; ++e) d.v[e] = sp.has(e) ? p[off + e] : T(0);
   }
 }
 
 template <class T, int N, class I>
-DISC_DEV void st(T* __restrict__ p, I off, const Vec<T, N>& s, int nvalid) {
-  if (nvalid >= N) {
+DISC_DEV void st(T* __restrict__ p, I off, const Vec<T, N>& s, Span sp) {
+  if (sp.full(N)) {
     *reinterpret_cast<typename Vec<T, N>::unaligned_t*>(p + off) = s.v;
   } else {
 #pragma unroll
     for (int e = 0; e < N; ++e)
-      if (e < nvalid) p[off + e] = s.v[e];
+      if (sp.has(e)) p[off + e] = s.v[e];
   }
 }
 
@@ -96,12 +104,33 @@ template <> DISC_DEV float from_f32<float>(float x) { return x; }
 template <> DISC_DEV _Float16 from_f32<_Float16>(float x) { return (_Float16)x; }
 template <> DISC_DEV __bf16 from_f32<__bf16>(float x) { return (__bf16)x; }
 
+// fp32 results -> storage vector, two elements per conversion where the type has a packed
+// convert (v_cvt_pk_bf16_f32 on gfx950 rounds to nearest even and delivers the packed pair)
+template <class T, int N>
+DISC_DEV void cvt_vec(Vec<T, N>& d, const float (&y)[N]) {
+  if constexpr (N % 2 == 0 && sizeof(T) == 2) {
+    typedef float f2 __attribute__((ext_vector_type(2)));
+    typedef T t2 __attribute__((ext_vector_type(2)));
+#pragma unroll
+    for (int e = 0; e < N; e += 2) {
+      const f2 p = {y[e], y[e + 1]};
+      const t2 q = __builtin_convertvector(p, t2);
+      d.v[e] = q[0];
+      d.v[e + 1] = q[1];
+    }
+  } else {
+#pragma unroll
+    for (int e = 0; e < N; ++e) d.v[e] = from_f32<T>(y[e]);
+  }
+}
+
 // Per-element transcendental math on the hardware approximation units (about 1 ulp each):
 // the fused kernels have roughly 40 VALU lane-operations per element to spend before they stop
 // being HBM-bound, which IEEE-correct expf / division would use up several times over.
 DISC_DEV float fast_rcp(float x) { return __builtin_amdgcn_rcpf(x); }
 DISC_DEV float fast_rsqrt(float x) { return __builtin_amdgcn_rsqf(x); }
 DISC_DEV float fast_sqrt(float x) { return __builtin_amdgcn_sqrtf(x); }
+DISC_DEV float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 DISC_DEV float fast_exp(float x) { return __builtin_amdgcn_exp2f(x * 1.44269504088896341f); }
 DISC_DEV float fast_log(float x) { return __builtin_amdgcn_logf(x) * 0.693147180559945309f; }
 DISC_DEV float fast_sigmoid(float x) { return fast_rcp(1.0f + fast_exp(-x)); }
@@ -199,7 +228,7 @@ DISC_DEV void kloop_body(const typename Pat::Args& A) {
           col[u] = (int)((s - row * A.spr_div.d) * V);
           nv[u] = min((int)V, (int)(inner - (u32)col[u]));
           Pat::row_begin(A, (i64)row, rc[u]);
-          Pat::template load<V>(A, rc[u], col[u], nv[u], slot[u]);
+          Pat::template load<V>(A, rc[u], col[u], Span{0, nv[u]}, slot[u]);
         }
       }
 #pragma unroll
@@ -207,8 +236,8 @@ DISC_DEV void kloop_body(const typename Pat::Args& A) {
         if (nv[u] > 0) {
           typename Pat::template OutSlot<V> o;
           typename Pat::template Keep<V> kp;
-          Pat::template epilogue<V, false>(A, rc[u], slot[u], kp, col[u], nv[u], o);
-          Pat::template store<V>(A, rc[u], col[u], nv[u], o);
+          Pat::template epilogue<V, false>(A, rc[u], slot[u], kp, col[u], Span{0, nv[u]}, o);
+          Pat::template store<V>(A, rc[u], col[u], Span{0, nv[u]}, o);
         }
       }
     }
@@ -224,11 +253,11 @@ DISC_DEV void kloop_body(const typename Pat::Args& A) {
       typename Pat::template Slot<V> slot;
       typename Pat::RowCtx rc;
       Pat::row_begin(A, row, rc);
-      Pat::template load<V>(A, rc, col, nv, slot);
+      Pat::template load<V>(A, rc, col, Span{0, nv}, slot);
       typename Pat::template OutSlot<V> o;
       typename Pat::template Keep<V> kp;
-      Pat::template epilogue<V, false>(A, rc, slot, kp, col, nv, o);
-      Pat::template store<V>(A, rc, col, nv, o);
+      Pat::template epilogue<V, false>(A, rc, slot, kp, col, Span{0, nv}, o);
+      Pat::template store<V>(A, rc, col, Span{0, nv}, o);
     }
   }
 }
@@ -238,7 +267,7 @@ DISC_DEV void kloop_body(const typename Pat::Args& A) {
 //
 // Register-resident version: a row is owned by a group of G lanes (G a power of two chosen
 // by the host per shape: 1..32 = several rows per wavefront for short rows, 64 = a
-// wavefront per row, 128 / 256 = several wavefronts per row).  Lane l of the group holds
+// wavefront per row, 128 .. 1024 = several wavefronts per row, the block grows with G).  Lane l of the group holds
 // slots l, l+G, l+2G, ... (NV of them, V elements each), loaded ONCE; every reduction phase
 // and the epilogue run out of registers, so the row makes exactly one trip from HBM and one
 // back.  Within a wavefront partial results are combined with xor-shuffles; across the
@@ -248,7 +277,9 @@ struct RowPlan {
   int G;        // lanes per row, power of two, <= blockDim.x
   int log2G;
   int nv;       // slots per lane actually needed at this shape (<= NV of the instantiation)
-  int stage;    // 1: row-vector operands are staged once per block in dynamic LDS
+  int flags;    // bit 0: row-vector operands are staged once per block in dynamic LDS
+                // bit 1: the slot grid of every row is shifted so that full-size operands are
+                //        accessed at their natural vector alignment (rows of ragged length)
 };
 
 // Row-vector operands (bias, gamma, beta, ...) are the same for every row a block processes:
@@ -261,22 +292,29 @@ extern __shared__ __attribute__((aligned(16))) char disc_stage_lds[];
 template <int PAD, class T>
 DISC_DEV void stage_copy(T* dst, const T* __restrict__ src, int n, int tid, int nthreads) {
   constexpr int E = 16 / (int)sizeof(T);
+  static_assert(PAD * sizeof(T) % 16 == 0 || PAD < E, "front pad keeps 16-byte pieces aligned");
+  if (tid < PAD) dst[tid] = T(0);
+  dst += PAD;
   const int nvec = n / E;
   for (int i = tid; i < nvec; i += nthreads)
-    reinterpret_cast<typename Vec<T, E>::vec_t*>(dst)[i] =
+    reinterpret_cast<typename Vec<T, E>::unaligned_t*>(dst)[i] =
         *reinterpret_cast<const typename Vec<T, E>::unaligned_t*>(src + (i64)i * E);
   for (int i = nvec * E + tid; i < n + PAD; i += nthreads) dst[i] = i < n ? src[i] : T(0);
 }
 
+// each staged operand is stored as [N zeros | inner elements | N zeros]; `col` may be negative
+// (down to -N+1) when the slot grid is shifted, and is then not a multiple of N
 template <class T, int N>
-DISC_DEV void ld_lds(Vec<T, N>& d, const char* base, int byte_off, int col) {
-  d.v = *reinterpret_cast<const typename Vec<T, N>::vec_t*>(base + byte_off + col * (int)sizeof(T));
+DISC_DEV void ld_lds(Vec<T, N>& d, const char* base, int byte_off, int col, bool shifted) {
+  const char* p = base + byte_off + (col + N) * (int)sizeof(T);
+  if (shifted) d.v = *reinterpret_cast<const typename Vec<T, N>::unaligned_t*>(p);
+  else d.v = *reinterpret_cast<const typename Vec<T, N>::vec_t*>(p);
 }
 
 template <class Pat, int P, int V, int NV>
 DISC_DEV void row_phases(const typename Pat::Args& A, const RowPlan& rp, typename Pat::RowCtx& rc,
                          const typename Pat::template Slot<V> (&slot)[NV],
-                         typename Pat::template Keep<V> (&keep)[NV], const int (&nvalid)[NV],
+                         typename Pat::template Keep<V> (&keep)[NV], const Span (&span)[NV],
                          int col0, char* lds, int& parity) {
   if constexpr (P < Pat::NPHASE) {
     typename Pat::template Acc<P> acc;
@@ -284,14 +322,14 @@ DISC_DEV void row_phases(const typename Pat::Args& A, const RowPlan& rp, typenam
 #pragma unroll
     for (int j = 0; j < NV; ++j) {
       const int col = col0 + j * rp.G * V;
-      if (nvalid[j] > 0) Pat::template phase<P, V, true>(A, acc, slot[j], keep[j], nvalid[j], col, rc);
+      if (span[j].any()) Pat::template phase<P, V, true>(A, acc, slot[j], keep[j], span[j], col, rc);
     }
     // lanes of one wavefront
     group_allreduce<Pat, P>(acc, rp.G < 64 ? rp.G : 64);
     // wavefronts of one row
     if (rp.G > 64) {
       typedef typename Pat::template Acc<P> AccT;
-      AccT* ex = reinterpret_cast<AccT*>(lds + parity * 4 * Pat::MAX_ACC_BYTES);
+      AccT* ex = reinterpret_cast<AccT*>(lds + parity * 16 * Pat::MAX_ACC_BYTES);
       parity ^= 1;
       const int wave = threadIdx.x >> 6;
       if ((threadIdx.x & 63) == 0) ex[wave] = acc;
@@ -305,23 +343,23 @@ DISC_DEV void row_phases(const typename Pat::Args& A, const RowPlan& rp, typenam
       }
     }
     Pat::template row_after<P>(A, rc, acc);
-    row_phases<Pat, P + 1, V, NV>(A, rp, rc, slot, keep, nvalid, col0, lds, parity);
+    row_phases<Pat, P + 1, V, NV>(A, rp, rc, slot, keep, span, col0, lds, parity);
   }
 }
 
 template <class Pat, int V, int NV>
 DISC_DEV void row_reg_body(const typename Pat::Args& A, const RowPlan& rp) {
-  __shared__ __attribute__((aligned(16))) char lds[2 * 4 * Pat::MAX_ACC_BYTES];
+  __shared__ __attribute__((aligned(16))) char lds[2 * 16 * Pat::MAX_ACC_BYTES];
   const int lane = threadIdx.x & (rp.G - 1);
   const int grp = threadIdx.x >> rp.log2G;
   const int rpb = blockDim.x >> rp.log2G;        // rows per block
   const i64 rows = A.rows;
   const int inner = (int)A.inner;
-  const int col0 = lane * V;
   int parity = 0;
   const i64 ngroups = (rows + rpb - 1) / rpb;
   const char* staged = nullptr;
-  if (rp.stage) {
+  const bool shift = (rp.flags & 2) != 0;
+  if (rp.flags & 1) {
     Pat::template stage<V>(A, disc_stage_lds, threadIdx.x, blockDim.x);
     __syncthreads();
     staged = disc_stage_lds;
@@ -332,25 +370,30 @@ DISC_DEV void row_reg_body(const typename Pat::Args& A, const RowPlan& rp) {
     typename Pat::RowCtx rc{};
     typename Pat::template Slot<V> slot[NV];
     typename Pat::template Keep<V> keep[NV];
-    int nvalid[NV];
+    Span span[NV];
     if (active) Pat::row_begin(A, row, rc);
     rc.sl = staged;
+    rc.shifted = shift;
+    // shifted grid: slot k of the row starts `head` elements before column k*V, where head is the
+    // misalignment of the row start, so every slot of a full-size operand is naturally aligned
+    const int head = shift ? (int)((row * A.inner) & (i64)(V - 1)) : 0;
+    const int col0 = lane * V - head;
 #pragma unroll
     for (int j = 0; j < NV; ++j) {
       const int col = col0 + j * rp.G * V;
-      int n = inner - col;
-      n = n > V ? V : n;
-      nvalid[j] = (active && j < rp.nv && n > 0) ? n : 0;
-      if (nvalid[j] > 0) Pat::template load<V>(A, rc, col, nvalid[j], slot[j]);
+      const int hi = inner - col > V ? V : inner - col;
+      const int lo = col < 0 ? -col : 0;
+      span[j] = (active && j < rp.nv && hi > lo) ? Span{lo, hi} : Span{0, 0};
+      if (span[j].any()) Pat::template load<V>(A, rc, col, span[j], slot[j]);
     }
-    row_phases<Pat, 0, V, NV>(A, rp, rc, slot, keep, nvalid, col0, lds, parity);
+    row_phases<Pat, 0, V, NV>(A, rp, rc, slot, keep, span, col0, lds, parity);
 #pragma unroll
     for (int j = 0; j < NV; ++j) {
-      if (nvalid[j] > 0) {
+      if (span[j].any()) {
         const int col = col0 + j * rp.G * V;
         typename Pat::template OutSlot<V> o;
-        Pat::template epilogue<V, true>(A, rc, slot[j], keep[j], col, nvalid[j], o);
-        Pat::template store<V>(A, rc, col, nvalid[j], o);
+        Pat::template epilogue<V, true>(A, rc, slot[j], keep[j], col, span[j], o);
+        Pat::template store<V>(A, rc, col, span[j], o);
       }
     }
     if (active && lane == 0) Pat::row_store(A, row, rc);
@@ -371,9 +414,9 @@ DISC_DEV void row_stream_phases(const typename Pat::Args& A, typename Pat::RowCt
       int n = inner - col;
       n = n > V ? V : n;
       typename Pat::template Slot<V> slot;
-      Pat::template load<V>(A, rc, col, n, slot);
+      Pat::template load<V>(A, rc, col, Span{0, n}, slot);
       typename Pat::template Keep<V> kp;
-      Pat::template phase<P, V, false>(A, acc, slot, kp, n, col, rc);
+      Pat::template phase<P, V, false>(A, acc, slot, kp, Span{0, n}, col, rc);
     }
     group_allreduce<Pat, P>(acc, 64);
     AccT* ex = reinterpret_cast<AccT*>(lds + parity * 16 * Pat::MAX_ACC_BYTES);
@@ -401,16 +444,17 @@ DISC_DEV void row_stream_body(const typename Pat::Args& A) {
     typename Pat::RowCtx rc;
     Pat::row_begin(A, row, rc);
     rc.sl = nullptr;
+    rc.shifted = false;
     row_stream_phases<Pat, 0, V>(A, rc, inner, lds, parity);
     for (int col = threadIdx.x * V; col < inner; col += blockDim.x * V) {
       int n = inner - col;
       n = n > V ? V : n;
       typename Pat::template Slot<V> slot;
-      Pat::template load<V>(A, rc, col, n, slot);
+      Pat::template load<V>(A, rc, col, Span{0, n}, slot);
       typename Pat::template OutSlot<V> o;
       typename Pat::template Keep<V> kp;
-      Pat::template epilogue<V, false>(A, rc, slot, kp, col, n, o);
-      Pat::template store<V>(A, rc, col, n, o);
+      Pat::template epilogue<V, false>(A, rc, slot, kp, col, Span{0, n}, o);
+      Pat::template store<V>(A, rc, col, Span{0, n}, o);
     }
     if (threadIdx.x == 0) Pat::row_store(A, row, rc);
   }
@@ -464,7 +508,7 @@ DISC_DEV void col_partial_body(const typename Pat::Args& A, const ColPlan& cp) {
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
           Pat::row_begin(A, o * A.mid + m + u * TY, rc[u]);
-          Pat::template load<V>(A, rc[u], col, nvalid, s[u]);
+          Pat::template load<V>(A, rc[u], col, Span{0, nvalid}, s[u]);
         }
 #pragma unroll
         for (int u = 0; u < 4; ++u)
@@ -476,7 +520,7 @@ DISC_DEV void col_partial_body(const typename Pat::Args& A, const ColPlan& cp) {
         typename Pat::template Slot<V> s;
         typename Pat::RowCtx rc;
         Pat::row_begin(A, o * A.mid + m, rc);
-        Pat::template load<V>(A, rc, col, nvalid, s);
+        Pat::template load<V>(A, rc, col, Span{0, nvalid}, s);
 #pragma unroll
         for (int e = 0; e < V; ++e)
           if (e < nvalid) Pat::template accum<0, V>(A, acc[e], s, e, (int)m, rc);

@@ -96,10 +96,11 @@ struct disc_ctx {
   int force_variant = -1;
   hipModule_t util_module = nullptr;
   hipFunction_t util_copy = nullptr, util_empty = nullptr;
-  int row_target_nv = 4;     // tuning knobs, overridable from the environment for experiments
+  int row_target_nv = 2;     // tuning knobs, overridable from the environment for experiments
   int grid_mult = 8;
   int loop_unroll = 4;
   int row_stage = 1;
+  int row_shift = 0;   // measured slower: a shifted grid makes the first and last slot of every row partial
 };
 
 namespace {
@@ -253,7 +254,8 @@ int plan_loop(disc_ctx* c, int64_t rows, int64_t inner, int V, int want_vec, int
 }
 
 // ---- version + launch-dimension selection (host) ---------------------------------------------
-int make_plan(disc_ctx* c, const Pattern& p, const int64_t* dims, int n_dims, int force, FullPlan* fp) {
+int make_plan(disc_ctx* c, const Pattern& p, const int64_t* dims, int n_dims, int force, const void* const* inputs,
+              void* const* outputs, FullPlan* fp) {
   int rc = shape_calc(c, p, dims, n_dims, &fp->sv);
   if (rc) return rc;
   const Analysis& an = p.an;
@@ -296,10 +298,24 @@ int make_plan(disc_ctx* c, const Pattern& p, const int64_t* dims, int n_dims, in
       vec = force == DISC_V_ROW_REG_VEC || force == DISC_V_ROW_STREAM_VEC;
     }
     const int v = vec ? V : 1;
-    const int64_t spr = (sv.inner + v - 1) / v;
-    stream = spr > 256 * 8;
+    // Rows whose length is not a multiple of the vector width start at changing alignments.
+    // When every full-size operand's base address is vector-aligned the kernel shifts the slot
+    // grid of each row by the row's misalignment so that all wide accesses stay naturally
+    // aligned; a row then needs up to one slot more.
+    bool shift = false;
+    if (v > 1 && sv.inner % v != 0 && c->row_shift) {
+      shift = true;
+      for (const auto& a : an.accesses) {
+        if (a.kind != ACC_FULL || !a.has_inner) continue;
+        const void* ptr = a.is_output ? (outputs ? outputs[a.slot] : nullptr) : (inputs ? inputs[a.slot] : nullptr);
+        if (ptr && ((uintptr_t)ptr % (uintptr_t)(v * dtype_bytes(a.dtype))) != 0) shift = false;
+      }
+    }
+    const int64_t spr = shift ? (sv.inner + 2 * v - 2) / v : (sv.inner + v - 1) / v;
+    stream = spr > 1024 * 2;
     if (force == DISC_V_ROW_STREAM_VEC || force == DISC_V_ROW_STREAM_SCALAR) stream = true;
     else if (force >= 0 && stream) return set_err(c, DISC_ERR_INVALID_ARG, "row too long for the forced register-resident version");
+    if (stream) shift = false;
     pub.vec_width = v;
     pub.index_bits = 64;
     fp->spr = spr;
@@ -315,14 +331,17 @@ int make_plan(disc_ctx* c, const Pattern& p, const int64_t* dims, int n_dims, in
       pub.reg_slots = 1;
     } else {
       // lanes per row: smallest power of two that keeps <= target slots per lane
-      int G = 1 << ilog2_ceil((spr + c->row_target_nv - 1) / c->row_target_nv);
-      G = std::min(G, 256);
+      const int target = std::max(1, std::min(2, c->row_target_nv));
+      int G = 1 << ilog2_ceil((spr + target - 1) / target);
+      G = std::min(G, 1024);
       int nv = (int)((spr + G - 1) / G);
-      int inst = nv <= 1 ? 1 : nv <= 2 ? 2 : nv <= 4 ? 4 : 8;
+      int inst = nv <= 1 ? 1 : 2;
       pub.variant = vec ? DISC_V_ROW_REG_VEC : DISC_V_ROW_REG_SCALAR;
-      static const char* kv[] = {"k_row_vec_nv1", "k_row_vec_nv2", "k_row_vec_nv4", "k_row_vec_nv8"};
-      static const char* ks[] = {"k_row_scalar_nv1", "k_row_scalar_nv2", "k_row_scalar_nv4", "k_row_scalar_nv8"};
-      const int ii = inst == 1 ? 0 : inst == 2 ? 1 : inst == 4 ? 2 : 3;
+      static const char* kv[] = {"k_row_vec_nv1", "k_row_vec_nv2", "k_row_vec_nv2w"};
+      static const char* ks[] = {"k_row_scalar_nv1", "k_row_scalar_nv2", "k_row_scalar_nv2w"};
+      const int ii = G > 256 ? 2 : inst - 1;
+      if (G > 256) inst = 2;
+      L.block = (uint32_t)std::max(256, G);
       L.kernel = vec ? kv[ii] : ks[ii];
       L.plan_kind = 1;
       L.rp.G = G;
@@ -331,17 +350,18 @@ int make_plan(disc_ctx* c, const Pattern& p, const int64_t* dims, int n_dims, in
       // stage row vectors in LDS when they fit a modest budget (keeps >= 3 blocks per CU resident)
       {
         int64_t bytes = 0;
-        for (int eb : p.gen.staged_elem_bytes) bytes += ((sv.inner + v) * eb + 15) & ~15ll;
+        for (int eb : p.gen.staged_elem_bytes) bytes += ((sv.inner + 2 * v) * eb + 15) & ~15ll;
         const bool stage = c->row_stage && bytes > 0 && bytes <= 48 * 1024;
-        L.rp.pad = stage ? 1 : 0;
+        L.rp.pad = (stage ? 1 : 0) | (shift ? 2 : 0);
         L.dyn_lds = stage ? (uint32_t)bytes : 0;
       }
-      const int rpb = 256 / G;
+      const int rpb = (int)L.block / G;
       const int64_t ngroups = (sv.rows + rpb - 1) / rpb;
-      L.grid[0] = (uint32_t)std::min<int64_t>(ngroups, max_grid);
+      L.grid[0] = (uint32_t)std::min<int64_t>(ngroups, std::max<int64_t>(c->n_cus, max_grid * 256 / L.block));
       pub.lanes_per_row = G;
       pub.slots_per_lane = nv;
       pub.reg_slots = inst;
+      pub.row_shift = shift ? 1 : 0;
     }
     pub.n_launches = 1;
   } else {
@@ -498,6 +518,7 @@ int disc_create(disc_ctx** out, int hip_device) {
   }
   if (const char* e = getenv("DISC_ROW_TARGET_NV")) c->row_target_nv = std::max(1, std::min(8, atoi(e)));
   if (const char* e = getenv("DISC_ROW_STAGE")) c->row_stage = atoi(e) != 0;
+  if (const char* e = getenv("DISC_ROW_SHIFT")) c->row_shift = atoi(e) != 0;
   if (const char* e = getenv("DISC_GRID_MULT")) c->grid_mult = std::max(1, std::min(64, atoi(e)));
   if (const char* e = getenv("DISC_LOOP_UNROLL")) (void)e;   // the unroll factor is a compile-time constant of the kernels
   *out = c.release();
@@ -635,7 +656,7 @@ int disc_workspace_bytes(disc_ctx* ctx, int32_t id, const int64_t* dims, int n_d
   Pattern* p = get_pattern(ctx, id);
   if (!p || !out) return set_err(ctx, DISC_ERR_INVALID_ARG, "bad pattern id or null output");
   FullPlan fp;
-  int rc = make_plan(ctx, *p, dims, n_dims, ctx->force_variant, &fp);   // same selection disc_launch will make
+  int rc = make_plan(ctx, *p, dims, n_dims, ctx->force_variant, nullptr, nullptr, &fp);   // same selection disc_launch will make
   if (rc) return rc;
   *out = fp.pub.workspace_bytes;
   return DISC_OK;
@@ -643,12 +664,10 @@ int disc_workspace_bytes(disc_ctx* ctx, int32_t id, const int64_t* dims, int n_d
 
 int disc_plan(disc_ctx* ctx, int32_t id, const int64_t* dims, int n_dims, const void* const* inputs,
               void* const* outputs, int force_variant, disc_plan_t* out) {
-  (void)inputs;
-  (void)outputs;
   Pattern* p = get_pattern(ctx, id);
   if (!p || !out) return set_err(ctx, DISC_ERR_INVALID_ARG, "bad pattern id or null output");
   FullPlan fp;
-  int rc = make_plan(ctx, *p, dims, n_dims, force_variant, &fp);
+  int rc = make_plan(ctx, *p, dims, n_dims, force_variant, inputs, outputs, &fp);
   if (rc) return rc;
   *out = fp.pub;
   return DISC_OK;
@@ -673,7 +692,7 @@ int disc_launch(disc_ctx* ctx, int32_t id, const int64_t* dims, int n_dims, cons
   }
   if ((n_in > 0 && !inputs) || !outputs) return set_err(ctx, DISC_ERR_INVALID_ARG, "null pointer array");
   FullPlan fp;
-  int rc = make_plan(ctx, *p, dims, n_dims, ctx->force_variant, &fp);
+  int rc = make_plan(ctx, *p, dims, n_dims, ctx->force_variant, inputs, outputs, &fp);
   const int64_t t1 = now_ns();
   ctx->stats.host_plan_ns += t1 - t0;
   if (rc) return rc;

@@ -65,7 +65,7 @@ def test_one_compile_per_pattern_and_pattern_cache(ctx, handles):
 
 def test_generated_source_is_exposed(handles):
     src = handles["C4"].source
-    assert "struct Pat" in src and "k_row_vec_nv4" in src and "row_reg_body" in src
+    assert "struct Pat" in src and "k_row_vec_nv2w" in src and "row_reg_body" in src
 
 
 # ------------------------------------------------------------------ constraint closure
@@ -218,11 +218,12 @@ def test_row_schedule_selection(handles):
     mid = h.plan([1000, 1024])
     assert mid["variant_name"] == "row_reg_vec" and mid["n_launches"] == 1
     long_ = h.plan([100, 8192])
-    assert long_["variant_name"] == "row_reg_vec" and long_["lanes_per_row"] == 256     # wavefronts cooperate via LDS
+    assert long_["variant_name"] == "row_reg_vec" and long_["lanes_per_row"] == 512     # wavefronts cooperate via LDS
+    assert long_["block"][0][0] == 512 and long_["slots_per_lane"] == 2
     assert long_["lanes_per_row"] * long_["slots_per_lane"] * long_["vec_width"] >= 8192
     huge = h.plan([10, 100000])
     assert huge["variant_name"] == "row_stream_vec"                                    # does not fit registers
-    for p in (short, mid, long_, huge):
+    for p in (short, mid, huge):
         assert p["grid"][0][0] >= 1 and p["block"][0][0] == 256
     assert h.plan([7, 3])["vec_width"] in (1, 8)
     forced = h.plan([1000, 1024], V["row_reg_scalar"])
