@@ -163,8 +163,6 @@ typedef struct {
   int32_t lanes_per_row;    /* row reduce: lanes that own one row (1..256), else 0             */
   int32_t slots_per_lane;   /* row reduce: vector slots held per lane, else unroll factor      */
   int32_t reg_slots;        /* compile-time slot capacity of the chosen instantiation          */
-  int32_t row_shift;        /* row reduce: 1 = slot grid shifted per row to keep wide accesses
-                               naturally aligned (ragged row length, aligned base pointers)    */
   uint32_t grid[3][3];      /* per launch                                                      */
   uint32_t block[3][3];
   uint32_t lds_bytes[3];

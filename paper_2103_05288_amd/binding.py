@@ -47,7 +47,7 @@ class disc_pattern_info_t(C.Structure):
 class disc_plan_t(C.Structure):
     _fields_ = [("variant", C.c_int32), ("n_launches", C.c_int32), ("index_bits", C.c_int32),
                 ("vec_width", C.c_int32), ("lanes_per_row", C.c_int32), ("slots_per_lane", C.c_int32),
-                ("reg_slots", C.c_int32), ("row_shift", C.c_int32), ("grid", (C.c_uint32 * 3) * 3), ("block", (C.c_uint32 * 3) * 3),
+                ("reg_slots", C.c_int32), ("grid", (C.c_uint32 * 3) * 3), ("block", (C.c_uint32 * 3) * 3),
                 ("lds_bytes", C.c_uint32 * 3), ("kernel", (C.c_char * 48) * 3), ("rows", C.c_int64), ("inner", C.c_int64), ("mid", C.c_int64),
                 ("algorithmic_bytes", C.c_int64), ("workspace_bytes", C.c_size_t)]
 

@@ -232,16 +232,16 @@ struct Gen {
         } else if (a.has_inner) {
           if (g.late(a)) {
             late_used.insert(n.access);
-            r = from_storage(fmt("l%d.v[e]", n.access), a.dtype);
+            r = from_storage(fmt("l%d.get(e)", n.access), a.dtype);
           } else {
-            r = from_storage(fmt("s.a%d.v[e]", n.access), a.dtype);
+            r = from_storage(fmt("s.a%d.get(e)", n.access), a.dtype);
           }
         } else {
           r = fmt("rc.r%d", id);   // loaded by row_begin
         }
       } else if (is_reduce(n.opcode)) {
         if (mode == M_COL_FINISH) r = g.acc_value(n, "acc");
-        else if (mode == M_COL_EPI) r = fmt("s.red%d.v[e]", n.reduce_slot);
+        else if (mode == M_COL_EPI) r = fmt("s.red%d.get(e)", n.reduce_slot);
         else r = fmt("rc.r%d", id);
       } else if (!col && n.dom == DOM_ROW && mode == M_ELEM) {
         r = fmt("rc.r%d", id);
@@ -391,7 +391,6 @@ struct Gen {
     }
     if (col_tmpl()) o << "    disc::i64 ob;\n";   // offset of this row's outer slice in the reduce-result planes
     o << "    const char* sl;\n";                 // staged row vectors in LDS (row reduce), or null
-    o << "    bool shifted;\n";                   // slot grid shifted by the row's misalignment
     o << "    int unused_;\n";
     return o.str();
   }
@@ -605,13 +604,11 @@ struct Gen {
         std::string f = accf(n.reduce_slot), i = acci(n.reduce_slot);
         switch (n.opcode) {
           case DISC_REDUCE_SUM: os << "      a." << f << " += b." << f << ";\n"; break;
-          case DISC_REDUCE_MAX:
-            if (ok == RK_F32) os << "      a." << f << " = fmaxf(a." << f << ", b." << f << ");\n";
-            else os << "      a." << f << " = a." << f << " > b." << f << " ? a." << f << " : b." << f << ";\n";
+          case DISC_REDUCE_MAX:   // compare-select: partner values arrive through lane exchanges / LDS
+            os << "      a." << f << " = b." << f << " > a." << f << " ? b." << f << " : a." << f << ";\n";
             break;
           case DISC_REDUCE_MIN:
-            if (ok == RK_F32) os << "      a." << f << " = fminf(a." << f << ", b." << f << ");\n";
-            else os << "      a." << f << " = a." << f << " < b." << f << " ? a." << f << " : b." << f << ";\n";
+            os << "      a." << f << " = b." << f << " < a." << f << " ? b." << f << " : a." << f << ";\n";
             break;
           default:
             os << "      if (b." << f << " > a." << f << " || (b." << f << " == a." << f << " && b." << i << " < a." << i
@@ -650,13 +647,13 @@ struct Gen {
     return -1;
   }
   // byte offset of staged operand k: operands are laid out one after the other, each
-  // (V + inner + V) elements long (zero padding in front and behind), rounded up to 16 bytes
+  // (inner + V) elements long (zero padding behind), rounded up to 16 bytes
   void emit_stage_fns() {
     std::vector<int> st = staged_accesses();
     os << "  static constexpr int N_STAGED = " << st.size() << ";\n";
     os << "  template <int V> static DISC_DEV int stage_offset(const Args& A, int k) {\n    int off = 0;\n";
     for (size_t k = 0; k < st.size(); ++k)
-      os << "    if (k > " << k << ") off += (((int)A.inner + 2 * V) * " << dtype_bytes(an.accesses[st[k]].dtype) << " + 15) & ~15;\n";
+      os << "    if (k > " << k << ") off += (((int)A.inner + V) * " << dtype_bytes(an.accesses[st[k]].dtype) << " + 15) & ~15;\n";
     os << "    (void)A; (void)k;\n    return off;\n  }\n";
     os << "  template <int V> static DISC_DEV void stage(const Args& A, char* lds, int tid, int nthreads) {\n";
     for (size_t k = 0; k < st.size(); ++k) {
@@ -675,7 +672,7 @@ struct Gen {
       o << ind << "disc::Vec<" << dtype_ctype(a.dtype) << ", V> l" << ai << ";\n";
       const int st = staged_index(ai);
       if (st >= 0) {
-        o << ind << "if (rc.sl) disc::ld_lds(l" << ai << ", rc.sl, stage_offset<V>(A, " << st << "), (int)col, rc.shifted);\n";
+        o << ind << "if (rc.sl) disc::ld_lds(l" << ai << ", rc.sl, stage_offset<V>(A, " << st << "), (int)col);\n";
         o << ind << "else disc::ld(l" << ai << ", A.p" << a.slot << ", " << elem_base(a, ai) << ", sp);\n";
       } else {
         o << ind << "disc::ld(l" << ai << ", A.p" << a.slot << ", " << elem_base(a, ai) << ", sp);\n";
@@ -768,7 +765,8 @@ struct Gen {
           tail << "        y" << a.slot << "[e] = " << convert(fn.val(out.node), n.rk, RK_F32) << ";\n";
           pack << "      disc::cvt_vec(o.o" << a.slot << ", y" << a.slot << ");\n";
         } else {
-          tail << "        o.o" << a.slot << ".v[e] = " << to_storage(fn.val(out.node), n.rk, a.dtype) << ";\n";
+          decl << "      o.o" << a.slot << ".clear();\n";
+          tail << "        o.o" << a.slot << ".set(e, " << to_storage(fn.val(out.node), n.rk, a.dtype) << ");\n";
         }
       }
       emit_late_loads(os, fn, "      ");

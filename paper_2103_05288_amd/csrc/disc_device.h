@@ -51,11 +51,27 @@ typedef unsigned long long u64;
 // multiple of the vector width.  The payload is a native vector value (never a byte copy
 // into a struct), so it always lives in registers.
 // ---------------------------------------------------------------------------------------
-template <class T, int N>
+template <class T, int N, bool PACKED = (sizeof(T) == 1 && N >= 4)>
 struct Vec {
   typedef T vec_t __attribute__((ext_vector_type(N)));
   typedef vec_t unaligned_t __attribute__((aligned(alignof(T))));
   vec_t v;
+  DISC_DEV void clear() { v = vec_t(T(0)); }
+  DISC_DEV T get(int e) const { return v[e]; }
+  DISC_DEV void set(int e, T x) { v[e] = x; }
+};
+// One-byte elements are kept as whole 32-bit words: a vector of bytes is not a register type, and
+// the compiler would carry it around loops one byte per register, packing and unpacking each time.
+template <class T, int N>
+struct Vec<T, N, true> {
+  typedef unsigned vec_t __attribute__((ext_vector_type(N / 4)));
+  typedef vec_t unaligned_t __attribute__((aligned(1)));
+  vec_t v;
+  DISC_DEV void clear() { v = vec_t(0u); }
+  DISC_DEV T get(int e) const { return (T)((v[e / 4] >> (8 * (e % 4))) & 0xffu); }
+  DISC_DEV void set(int e, T x) {   // the byte must still be zero (clear() first)
+    v[e / 4] |= (unsigned)(unsigned char)x << (8 * (e % 4));
+  }
 };
 
 // Elements [lo, hi) of a slot belong to the row; a slot in the middle of a row has lo = 0, hi = N.
@@ -75,8 +91,10 @@ DISC_DEV void ld(Vec<T, N>& d, const T* __restrict__ p, I off, Span sp, bool who
   if (sp.full(N) || whole_ok) {
     d.v = *reinterpret_cast<const typename Vec<T, N>::unaligned_t*>(p + off);
   } else {
+    d.clear();
 #pragma unroll
-    for (int e = 0; e < N; ++e) d.v[e] = sp.has(e) ? p[off + e] : T(0);
+    for (int e = 0; e < N; ++e)
+      if (sp.has(e)) d.set(e, p[off + e]);
   }
 }
 
@@ -87,7 +105,7 @@ DISC_DEV void st(T* __restrict__ p, I off, const Vec<T, N>& s, Span sp) {
   } else {
 #pragma unroll
     for (int e = 0; e < N; ++e)
-      if (sp.has(e)) p[off + e] = s.v[e];
+      if (sp.has(e)) p[off + e] = s.get(e);
   }
 }
 
@@ -185,21 +203,30 @@ DISC_DEV bool wave_all(bool p) { return __builtin_amdgcn_ballot_w64(!p) == 0; }
 
 // all-reduce of an accumulator over aligned groups of G lanes (G a power of two, <= 64)
 template <class Pat, int P, int S>
-DISC_DEV void group_step(typename Pat::template Acc<P>& acc, int G) {
-  if (G > S) {
-    typename Pat::template Acc<P> o = acc;
-    Pat::template acc_xchg<P, S>(o);
-    Pat::template acc_merge<P>(acc, o);
-  }
+DISC_DEV void group_step(typename Pat::template Acc<P>& acc) {
+  typename Pat::template Acc<P> o = acc;
+  Pat::template acc_xchg<P, S>(o);
+  Pat::template acc_merge<P>(acc, o);
 }
+// nested on purpose: one scalar test per level, nothing re-derived after the branches rejoin
 template <class Pat, int P>
 DISC_DEV void group_allreduce(typename Pat::template Acc<P>& acc, int G) {
-  group_step<Pat, P, 1>(acc, G);
-  group_step<Pat, P, 2>(acc, G);
-  group_step<Pat, P, 4>(acc, G);
-  group_step<Pat, P, 8>(acc, G);
-  group_step<Pat, P, 16>(acc, G);
-  group_step<Pat, P, 32>(acc, G);
+  if (G > 1) {
+    group_step<Pat, P, 1>(acc);
+    if (G > 2) {
+      group_step<Pat, P, 2>(acc);
+      if (G > 4) {
+        group_step<Pat, P, 4>(acc);
+        if (G > 8) {
+          group_step<Pat, P, 8>(acc);
+          if (G > 16) {
+            group_step<Pat, P, 16>(acc);
+            if (G > 32) group_step<Pat, P, 32>(acc);
+          }
+        }
+      }
+    }
+  }
 }
 
 // =======================================================================================
@@ -278,8 +305,6 @@ struct RowPlan {
   int log2G;
   int nv;       // slots per lane actually needed at this shape (<= NV of the instantiation)
   int flags;    // bit 0: row-vector operands are staged once per block in dynamic LDS
-                // bit 1: the slot grid of every row is shifted so that full-size operands are
-                //        accessed at their natural vector alignment (rows of ragged length)
 };
 
 // Row-vector operands (bias, gamma, beta, ...) are the same for every row a block processes:
@@ -292,23 +317,17 @@ extern __shared__ __attribute__((aligned(16))) char disc_stage_lds[];
 template <int PAD, class T>
 DISC_DEV void stage_copy(T* dst, const T* __restrict__ src, int n, int tid, int nthreads) {
   constexpr int E = 16 / (int)sizeof(T);
-  static_assert(PAD * sizeof(T) % 16 == 0 || PAD < E, "front pad keeps 16-byte pieces aligned");
-  if (tid < PAD) dst[tid] = T(0);
-  dst += PAD;
   const int nvec = n / E;
   for (int i = tid; i < nvec; i += nthreads)
-    reinterpret_cast<typename Vec<T, E>::unaligned_t*>(dst)[i] =
+    reinterpret_cast<typename Vec<T, E>::vec_t*>(dst)[i] =
         *reinterpret_cast<const typename Vec<T, E>::unaligned_t*>(src + (i64)i * E);
   for (int i = nvec * E + tid; i < n + PAD; i += nthreads) dst[i] = i < n ? src[i] : T(0);
 }
 
-// each staged operand is stored as [N zeros | inner elements | N zeros]; `col` may be negative
-// (down to -N+1) when the slot grid is shifted, and is then not a multiple of N
+// each staged operand is stored as [inner elements | N zeros]; col is a multiple of N
 template <class T, int N>
-DISC_DEV void ld_lds(Vec<T, N>& d, const char* base, int byte_off, int col, bool shifted) {
-  const char* p = base + byte_off + (col + N) * (int)sizeof(T);
-  if (shifted) d.v = *reinterpret_cast<const typename Vec<T, N>::unaligned_t*>(p);
-  else d.v = *reinterpret_cast<const typename Vec<T, N>::vec_t*>(p);
+DISC_DEV void ld_lds(Vec<T, N>& d, const char* base, int byte_off, int col) {
+  d.v = *reinterpret_cast<const typename Vec<T, N>::vec_t*>(base + byte_off + col * (int)sizeof(T));
 }
 
 template <class Pat, int P, int V, int NV>
@@ -358,7 +377,7 @@ DISC_DEV void row_reg_body(const typename Pat::Args& A, const RowPlan& rp) {
   int parity = 0;
   const i64 ngroups = (rows + rpb - 1) / rpb;
   const char* staged = nullptr;
-  const bool shift = (rp.flags & 2) != 0;
+  const int col0 = lane * V;
   if (rp.flags & 1) {
     Pat::template stage<V>(A, disc_stage_lds, threadIdx.x, blockDim.x);
     __syncthreads();
@@ -373,17 +392,11 @@ DISC_DEV void row_reg_body(const typename Pat::Args& A, const RowPlan& rp) {
     Span span[NV];
     if (active) Pat::row_begin(A, row, rc);
     rc.sl = staged;
-    rc.shifted = shift;
-    // shifted grid: slot k of the row starts `head` elements before column k*V, where head is the
-    // misalignment of the row start, so every slot of a full-size operand is naturally aligned
-    const int head = shift ? (int)((row * A.inner) & (i64)(V - 1)) : 0;
-    const int col0 = lane * V - head;
 #pragma unroll
     for (int j = 0; j < NV; ++j) {
       const int col = col0 + j * rp.G * V;
       const int hi = inner - col > V ? V : inner - col;
-      const int lo = col < 0 ? -col : 0;
-      span[j] = (active && j < rp.nv && hi > lo) ? Span{lo, hi} : Span{0, 0};
+      span[j] = (active && j < rp.nv && hi > 0) ? Span{0, hi} : Span{0, 0};
       if (span[j].any()) Pat::template load<V>(A, rc, col, span[j], slot[j]);
     }
     row_phases<Pat, 0, V, NV>(A, rp, rc, slot, keep, span, col0, lds, parity);
@@ -444,7 +457,6 @@ DISC_DEV void row_stream_body(const typename Pat::Args& A) {
     typename Pat::RowCtx rc;
     Pat::row_begin(A, row, rc);
     rc.sl = nullptr;
-    rc.shifted = false;
     row_stream_phases<Pat, 0, V>(A, rc, inner, lds, parity);
     for (int col = threadIdx.x * V; col < inner; col += blockDim.x * V) {
       int n = inner - col;

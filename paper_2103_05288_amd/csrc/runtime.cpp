@@ -100,7 +100,6 @@ struct disc_ctx {
   int grid_mult = 8;
   int loop_unroll = 4;
   int row_stage = 1;
-  int row_shift = 0;   // measured slower: a shifted grid makes the first and last slot of every row partial
 };
 
 namespace {
@@ -256,6 +255,8 @@ int plan_loop(disc_ctx* c, int64_t rows, int64_t inner, int V, int want_vec, int
 // ---- version + launch-dimension selection (host) ---------------------------------------------
 int make_plan(disc_ctx* c, const Pattern& p, const int64_t* dims, int n_dims, int force, const void* const* inputs,
               void* const* outputs, FullPlan* fp) {
+  (void)inputs;    // pointer values are available to the selection; nothing depends on alignment at present:
+  (void)outputs;   // wide accesses need element alignment only
   int rc = shape_calc(c, p, dims, n_dims, &fp->sv);
   if (rc) return rc;
   const Analysis& an = p.an;
@@ -298,24 +299,10 @@ int make_plan(disc_ctx* c, const Pattern& p, const int64_t* dims, int n_dims, in
       vec = force == DISC_V_ROW_REG_VEC || force == DISC_V_ROW_STREAM_VEC;
     }
     const int v = vec ? V : 1;
-    // Rows whose length is not a multiple of the vector width start at changing alignments.
-    // When every full-size operand's base address is vector-aligned the kernel shifts the slot
-    // grid of each row by the row's misalignment so that all wide accesses stay naturally
-    // aligned; a row then needs up to one slot more.
-    bool shift = false;
-    if (v > 1 && sv.inner % v != 0 && c->row_shift) {
-      shift = true;
-      for (const auto& a : an.accesses) {
-        if (a.kind != ACC_FULL || !a.has_inner) continue;
-        const void* ptr = a.is_output ? (outputs ? outputs[a.slot] : nullptr) : (inputs ? inputs[a.slot] : nullptr);
-        if (ptr && ((uintptr_t)ptr % (uintptr_t)(v * dtype_bytes(a.dtype))) != 0) shift = false;
-      }
-    }
-    const int64_t spr = shift ? (sv.inner + 2 * v - 2) / v : (sv.inner + v - 1) / v;
+    const int64_t spr = (sv.inner + v - 1) / v;
     stream = spr > 1024 * 2;
     if (force == DISC_V_ROW_STREAM_VEC || force == DISC_V_ROW_STREAM_SCALAR) stream = true;
     else if (force >= 0 && stream) return set_err(c, DISC_ERR_INVALID_ARG, "row too long for the forced register-resident version");
-    if (stream) shift = false;
     pub.vec_width = v;
     pub.index_bits = 64;
     fp->spr = spr;
@@ -350,9 +337,9 @@ int make_plan(disc_ctx* c, const Pattern& p, const int64_t* dims, int n_dims, in
       // stage row vectors in LDS when they fit a modest budget (keeps >= 3 blocks per CU resident)
       {
         int64_t bytes = 0;
-        for (int eb : p.gen.staged_elem_bytes) bytes += ((sv.inner + 2 * v) * eb + 15) & ~15ll;
+        for (int eb : p.gen.staged_elem_bytes) bytes += ((sv.inner + v) * eb + 15) & ~15ll;
         const bool stage = c->row_stage && bytes > 0 && bytes <= 48 * 1024;
-        L.rp.pad = (stage ? 1 : 0) | (shift ? 2 : 0);
+        L.rp.pad = stage ? 1 : 0;
         L.dyn_lds = stage ? (uint32_t)bytes : 0;
       }
       const int rpb = (int)L.block / G;
@@ -361,7 +348,6 @@ int make_plan(disc_ctx* c, const Pattern& p, const int64_t* dims, int n_dims, in
       pub.lanes_per_row = G;
       pub.slots_per_lane = nv;
       pub.reg_slots = inst;
-      pub.row_shift = shift ? 1 : 0;
     }
     pub.n_launches = 1;
   } else {
@@ -518,7 +504,6 @@ int disc_create(disc_ctx** out, int hip_device) {
   }
   if (const char* e = getenv("DISC_ROW_TARGET_NV")) c->row_target_nv = std::max(1, std::min(8, atoi(e)));
   if (const char* e = getenv("DISC_ROW_STAGE")) c->row_stage = atoi(e) != 0;
-  if (const char* e = getenv("DISC_ROW_SHIFT")) c->row_shift = atoi(e) != 0;
   if (const char* e = getenv("DISC_GRID_MULT")) c->grid_mult = std::max(1, std::min(64, atoi(e)));
   if (const char* e = getenv("DISC_LOOP_UNROLL")) (void)e;   // the unroll factor is a compile-time constant of the kernels
   *out = c.release();
