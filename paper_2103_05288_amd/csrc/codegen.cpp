@@ -691,7 +691,10 @@ struct Gen {
       const std::string x = fn.val(n.in[0]);
       const std::string st = fold_stmt(n, x, "col + e");
       tail += "        " + st + "\n";
-      tail_pred += "        if (sp.has(e)) { " + st + " }\n";
+      // elements outside the row contribute the identity; selecting the value (not the update)
+      // keeps the accumulation itself the same instruction sequence as in the full body
+      if (n.opcode == DISC_REDUCE_ARGMAX) tail_pred += "        if (sp.has(e)) { " + st + " }\n";
+      else tail_pred += "        " + fold_stmt(n, "(sp.has(e) ? " + x + " : " + identity(n) + ")", "col + e") + "\n";
     }
     emit_late_loads(os, fn, "      ");
     // wave-uniform choice: the unpredicated body only when every lane of the wavefront has a

@@ -74,13 +74,60 @@ struct Vec<T, N, true> {
   }
 };
 
-// Elements [lo, hi) of a slot belong to the row; a slot in the middle of a row has lo = 0, hi = N.
+// The first n elements of a slot belong to the row (n = N everywhere but at the end of a row).
+// The per-element tests are evaluated once, where the span is made, so that every reduction
+// phase and the epilogue of a ragged slot reuse them instead of comparing again.
 struct Span {
-  int lo, hi;
-  DISC_DEV bool full(int n) const { return lo == 0 && hi >= n; }
-  DISC_DEV bool has(int e) const { return e >= lo && e < hi; }
-  DISC_DEV bool any() const { return hi > lo; }
+  int n;
+  bool ok[16];
+  static DISC_DEV Span upto(int n) {
+    Span s;
+    s.n = n;
+#pragma unroll
+    for (int e = 0; e < 16; ++e) s.ok[e] = e < n;
+    return s;
+  }
+  DISC_DEV bool full(int N) const { return n >= N; }
+#ifdef EXP_SPAN_INLINE
+  DISC_DEV bool has(int e) const { return e < n; }
+#else
+  DISC_DEV bool has(int e) const { return ok[e]; }
+#endif
+  DISC_DEV bool any() const { return n > 0; }
 };
+
+// A ragged slot (n < N elements) moves as the power-of-two pieces of n's binary expansion: the
+// piece of width W covers [(q-1)W, qW) when n / W == q is odd.  Every lane of a launch has the
+// same ragged length, so a wavefront issues at most log2(N) narrow accesses per ragged slot.
+template <int W, class T, int N, class I>
+DISC_DEV void ld_pieces(Vec<T, N>& d, const T* __restrict__ p, I off, int n) {
+  if constexpr (W >= 1) {
+#pragma unroll
+    for (int q = 1; q * W < N; q += 2)
+      if (n / W == q) {
+        Vec<T, W> piece;
+        piece.v = *reinterpret_cast<const typename Vec<T, W>::unaligned_t*>(p + off + (q - 1) * W);
+#pragma unroll
+        for (int i = 0; i < W; ++i) d.set((q - 1) * W + i, piece.get(i));
+      }
+    ld_pieces<W / 2>(d, p, off, n);
+  }
+}
+template <int W, class T, int N, class I>
+DISC_DEV void st_pieces(T* __restrict__ p, I off, const Vec<T, N>& s, int n) {
+  if constexpr (W >= 1) {
+#pragma unroll
+    for (int q = 1; q * W < N; q += 2)
+      if (n / W == q) {
+        Vec<T, W> piece;
+        piece.clear();
+#pragma unroll
+        for (int i = 0; i < W; ++i) piece.set(i, s.get((q - 1) * W + i));
+        *reinterpret_cast<typename Vec<T, W>::unaligned_t*>(p + off + (q - 1) * W) = piece.v;
+      }
+    st_pieces<W / 2>(p, off, s, n);
+  }
+}
 
 // `whole_ok`: all N elements lie inside the tensor even though only part of them belong to this
 // row (the rest are the tail of the previous / head of the next row).  Then the wide load is
@@ -92,9 +139,20 @@ DISC_DEV void ld(Vec<T, N>& d, const T* __restrict__ p, I off, Span sp, bool who
     d.v = *reinterpret_cast<const typename Vec<T, N>::unaligned_t*>(p + off);
   } else {
     d.clear();
+#ifdef EXP_LD_ELEM
 #pragma unroll
     for (int e = 0; e < N; ++e)
       if (sp.has(e)) d.set(e, p[off + e]);
+#else
+    ld_pieces<N / 2>(d, p, off, sp.n);
+#endif
+    // s_waitcnt vmcnt(0): the pieces are complete before the branches rejoin.  Otherwise the
+    // compiler has to assume a piece may still be in flight into d's registers and makes the
+    // wide load above wait for every earlier load of the wavefront -- on the path where no
+    // lane took this branch at all, serialising the loads of full slots.
+#ifndef EXP_NO_WAIT
+    __builtin_amdgcn_s_waitcnt(0x0F70);
+#endif
   }
 }
 
@@ -103,9 +161,13 @@ DISC_DEV void st(T* __restrict__ p, I off, const Vec<T, N>& s, Span sp) {
   if (sp.full(N)) {
     *reinterpret_cast<typename Vec<T, N>::unaligned_t*>(p + off) = s.v;
   } else {
+#ifdef EXP_ST_ELEM
 #pragma unroll
     for (int e = 0; e < N; ++e)
       if (sp.has(e)) p[off + e] = s.get(e);
+#else
+    st_pieces<N / 2>(p, off, s, sp.n);
+#endif
   }
 }
 
@@ -255,7 +317,7 @@ DISC_DEV void kloop_body(const typename Pat::Args& A) {
           col[u] = (int)((s - row * A.spr_div.d) * V);
           nv[u] = min((int)V, (int)(inner - (u32)col[u]));
           Pat::row_begin(A, (i64)row, rc[u]);
-          Pat::template load<V>(A, rc[u], col[u], Span{0, nv[u]}, slot[u]);
+          Pat::template load<V>(A, rc[u], col[u], Span::upto(nv[u]), slot[u]);
         }
       }
 #pragma unroll
@@ -263,8 +325,8 @@ DISC_DEV void kloop_body(const typename Pat::Args& A) {
         if (nv[u] > 0) {
           typename Pat::template OutSlot<V> o;
           typename Pat::template Keep<V> kp;
-          Pat::template epilogue<V, false>(A, rc[u], slot[u], kp, col[u], Span{0, nv[u]}, o);
-          Pat::template store<V>(A, rc[u], col[u], Span{0, nv[u]}, o);
+          Pat::template epilogue<V, false>(A, rc[u], slot[u], kp, col[u], Span::upto(nv[u]), o);
+          Pat::template store<V>(A, rc[u], col[u], Span::upto(nv[u]), o);
         }
       }
     }
@@ -280,11 +342,11 @@ DISC_DEV void kloop_body(const typename Pat::Args& A) {
       typename Pat::template Slot<V> slot;
       typename Pat::RowCtx rc;
       Pat::row_begin(A, row, rc);
-      Pat::template load<V>(A, rc, col, Span{0, nv}, slot);
+      Pat::template load<V>(A, rc, col, Span::upto(nv), slot);
       typename Pat::template OutSlot<V> o;
       typename Pat::template Keep<V> kp;
-      Pat::template epilogue<V, false>(A, rc, slot, kp, col, Span{0, nv}, o);
-      Pat::template store<V>(A, rc, col, Span{0, nv}, o);
+      Pat::template epilogue<V, false>(A, rc, slot, kp, col, Span::upto(nv), o);
+      Pat::template store<V>(A, rc, col, Span::upto(nv), o);
     }
   }
 }
@@ -292,17 +354,17 @@ DISC_DEV void kloop_body(const typename Pat::Args& A) {
 // =======================================================================================
 // Input fusion with a row reduction as root (kInput, reduce over the innermost axis).
 //
-// Register-resident version: a row is owned by a group of G lanes (G a power of two chosen
-// by the host per shape: 1..32 = several rows per wavefront for short rows, 64 = a
-// wavefront per row, 128 .. 1024 = several wavefronts per row, the block grows with G).  Lane l of the group holds
+// Register-resident version: a row is owned by a group of G lanes chosen by the host per shape:
+// a power of two 1..32 = several rows per wavefront for short rows, 64 = a wavefront per row,
+// any multiple of 64 up to 1024 = a block of G/64 wavefronts per row.  Lane l of the group holds
 // slots l, l+G, l+2G, ... (NV of them, V elements each), loaded ONCE; every reduction phase
 // and the epilogue run out of registers, so the row makes exactly one trip from HBM and one
 // back.  Within a wavefront partial results are combined with xor-shuffles; across the
 // wavefronts of a row through a double-buffered LDS exchange (one barrier per phase).
 // =======================================================================================
 struct RowPlan {
-  int G;        // lanes per row, power of two, <= blockDim.x
-  int log2G;
+  int G;        // lanes per row: a power of two <= 64, or a multiple of 64 equal to blockDim.x
+  int log2G;    // meaningful for G <= 64
   int nv;       // slots per lane actually needed at this shape (<= NV of the instantiation)
   int flags;    // bit 0: row-vector operands are staged once per block in dynamic LDS
 };
@@ -353,11 +415,10 @@ DISC_DEV void row_phases(const typename Pat::Args& A, const RowPlan& rp, typenam
       const int wave = threadIdx.x >> 6;
       if ((threadIdx.x & 63) == 0) ex[wave] = acc;
       __syncthreads();
-      const int wpr = rp.G >> 6;               // wavefronts per row
-      const int w0 = wave & ~(wpr - 1);
-      acc = ex[w0];
+      const int wpr = rp.G >> 6;               // wavefronts per row = wavefronts per block
+      acc = ex[0];
       for (int w = 1; w < wpr; ++w) {
-        AccT o = ex[w0 + w];
+        AccT o = ex[w];
         Pat::template acc_merge<P>(acc, o);
       }
     }
@@ -369,9 +430,11 @@ DISC_DEV void row_phases(const typename Pat::Args& A, const RowPlan& rp, typenam
 template <class Pat, int V, int NV>
 DISC_DEV void row_reg_body(const typename Pat::Args& A, const RowPlan& rp) {
   __shared__ __attribute__((aligned(16))) char lds[2 * 16 * Pat::MAX_ACC_BYTES];
-  const int lane = threadIdx.x & (rp.G - 1);
-  const int grp = threadIdx.x >> rp.log2G;
-  const int rpb = blockDim.x >> rp.log2G;        // rows per block
+  // G <= 64: a power of two, several rows per block; G > 64: a multiple of 64, the block is the row
+  const bool multi = rp.G > 64;
+  const int lane = multi ? (int)threadIdx.x : (int)threadIdx.x & (rp.G - 1);
+  const int grp = multi ? 0 : (int)threadIdx.x >> rp.log2G;
+  const int rpb = multi ? 1 : (int)blockDim.x >> rp.log2G;        // rows per block
   const i64 rows = A.rows;
   const int inner = (int)A.inner;
   int parity = 0;
@@ -396,7 +459,7 @@ DISC_DEV void row_reg_body(const typename Pat::Args& A, const RowPlan& rp) {
     for (int j = 0; j < NV; ++j) {
       const int col = col0 + j * rp.G * V;
       const int hi = inner - col > V ? V : inner - col;
-      span[j] = (active && j < rp.nv && hi > 0) ? Span{0, hi} : Span{0, 0};
+      span[j] = Span::upto((active && j < rp.nv && hi > 0) ? hi : 0);
       if (span[j].any()) Pat::template load<V>(A, rc, col, span[j], slot[j]);
     }
     row_phases<Pat, 0, V, NV>(A, rp, rc, slot, keep, span, col0, lds, parity);
@@ -427,9 +490,9 @@ DISC_DEV void row_stream_phases(const typename Pat::Args& A, typename Pat::RowCt
       int n = inner - col;
       n = n > V ? V : n;
       typename Pat::template Slot<V> slot;
-      Pat::template load<V>(A, rc, col, Span{0, n}, slot);
+      Pat::template load<V>(A, rc, col, Span::upto(n), slot);
       typename Pat::template Keep<V> kp;
-      Pat::template phase<P, V, false>(A, acc, slot, kp, Span{0, n}, col, rc);
+      Pat::template phase<P, V, false>(A, acc, slot, kp, Span::upto(n), col, rc);
     }
     group_allreduce<Pat, P>(acc, 64);
     AccT* ex = reinterpret_cast<AccT*>(lds + parity * 16 * Pat::MAX_ACC_BYTES);
@@ -462,11 +525,11 @@ DISC_DEV void row_stream_body(const typename Pat::Args& A) {
       int n = inner - col;
       n = n > V ? V : n;
       typename Pat::template Slot<V> slot;
-      Pat::template load<V>(A, rc, col, Span{0, n}, slot);
+      Pat::template load<V>(A, rc, col, Span::upto(n), slot);
       typename Pat::template OutSlot<V> o;
       typename Pat::template Keep<V> kp;
-      Pat::template epilogue<V, false>(A, rc, slot, kp, col, Span{0, n}, o);
-      Pat::template store<V>(A, rc, col, Span{0, n}, o);
+      Pat::template epilogue<V, false>(A, rc, slot, kp, col, Span::upto(n), o);
+      Pat::template store<V>(A, rc, col, Span::upto(n), o);
     }
     if (threadIdx.x == 0) Pat::row_store(A, row, rc);
   }
@@ -520,7 +583,7 @@ DISC_DEV void col_partial_body(const typename Pat::Args& A, const ColPlan& cp) {
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
           Pat::row_begin(A, o * A.mid + m + u * TY, rc[u]);
-          Pat::template load<V>(A, rc[u], col, Span{0, nvalid}, s[u]);
+          Pat::template load<V>(A, rc[u], col, Span::upto(nvalid), s[u]);
         }
 #pragma unroll
         for (int u = 0; u < 4; ++u)
@@ -532,7 +595,7 @@ DISC_DEV void col_partial_body(const typename Pat::Args& A, const ColPlan& cp) {
         typename Pat::template Slot<V> s;
         typename Pat::RowCtx rc;
         Pat::row_begin(A, o * A.mid + m, rc);
-        Pat::template load<V>(A, rc, col, Span{0, nvalid}, s);
+        Pat::template load<V>(A, rc, col, Span::upto(nvalid), s);
 #pragma unroll
         for (int e = 0; e < V; ++e)
           if (e < nvalid) Pat::template accum<0, V>(A, acc[e], s, e, (int)m, rc);

@@ -12,6 +12,7 @@
 #include <cstdlib>
 #include <cstring>
 #include <memory>
+#include <sstream>
 
 #include "disc_internal.hpp"
 
@@ -51,6 +52,7 @@ struct Pattern {
   double compile_ms = 0;
   hipModule_t module = nullptr;
   std::map<std::string, hipFunction_t> fn;
+  mutable std::map<std::string, int> resident;        // (kernel, block, LDS) -> blocks resident per CU
   // constraint recipes
   std::vector<std::pair<int, int>> eq_checks;         // symbolic dims that must be equal
   std::vector<std::pair<int, int64_t>> static_checks; // symbolic dim that must equal a static size
@@ -98,6 +100,7 @@ struct disc_ctx {
   hipFunction_t util_copy = nullptr, util_empty = nullptr;
   int row_target_nv = 2;     // tuning knobs, overridable from the environment for experiments
   int grid_mult = 8;
+  int row_rounds = 2;        // row kernels: grid = this many rounds of resident blocks
   int loop_unroll = 4;
   int row_stage = 1;
 };
@@ -117,12 +120,19 @@ int compile_source(disc_ctx* c, const std::string& src, std::vector<char>* code,
   hiprtcProgram prog;
   if (hiprtcCreateProgram(&prog, src.c_str(), "disc_pattern.hip", 0, nullptr, nullptr) != HIPRTC_SUCCESS)
     return set_err(c, DISC_ERR_COMPILE, "hiprtcCreateProgram failed");
-  const char* opts[] = {"--offload-arch=gfx950", "-O3", "-std=c++17", "-Xclang", "-target-feature", "-Xclang",
-                        "-packed-fp32-ops", "-Wno-unused-value",
-                        // the fused expressions are scalar per element on purpose: no packed-fp32 pairs
-                        "-fno-slp-vectorize", "-fno-vectorize"};
+  std::vector<const char*> opts = {"--offload-arch=gfx950", "-O3", "-std=c++17", "-Xclang", "-target-feature", "-Xclang",
+                                   "-packed-fp32-ops", "-Wno-unused-value",
+                                   // the fused expressions are scalar per element on purpose: no packed-fp32 pairs
+                                   "-fno-slp-vectorize", "-fno-vectorize"};
+  // extra device-compiler options for experiments (space separated), e.g. -D switches
+  std::vector<std::string> extra;
+  if (const char* e = getenv("DISC_DEVICE_FLAGS")) {
+    std::istringstream is(e);
+    for (std::string w; is >> w;) extra.push_back(w);
+    for (const auto& w : extra) opts.push_back(w.c_str());
+  }
   auto t0 = std::chrono::steady_clock::now();
-  hiprtcResult r = hiprtcCompileProgram(prog, (int)(sizeof opts / sizeof opts[0]), opts);
+  hiprtcResult r = hiprtcCompileProgram(prog, (int)opts.size(), opts.data());
   *ms = std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - t0).count();
   if (r != HIPRTC_SUCCESS) {
     size_t n = 0;
@@ -252,6 +262,11 @@ int plan_loop(disc_ctx* c, int64_t rows, int64_t inner, int V, int want_vec, int
   return DISC_OK;
 }
 
+// Blocks of a kernel that one CU holds at a given block size and dynamic LDS size, as the
+// runtime computes it from the compiled kernel's register and LDS use (asked once per
+// combination).  Without a device: an estimate from a 16-wavefront budget.
+int resident_blocks(const disc_ctx* c, const Pattern& p, const char* kernel, uint32_t block, uint32_t dyn_lds);
+
 // ---- version + launch-dimension selection (host) ---------------------------------------------
 int make_plan(disc_ctx* c, const Pattern& p, const int64_t* dims, int n_dims, int force, const void* const* inputs,
               void* const* outputs, FullPlan* fp) {
@@ -317,7 +332,9 @@ int make_plan(disc_ctx* c, const Pattern& p, const int64_t* dims, int n_dims, in
       pub.slots_per_lane = (int)((spr + 255) / 256);
       pub.reg_slots = 1;
     } else {
-      // lanes per row: smallest power of two that keeps <= target slots per lane
+      // lanes per row: smallest power of two that keeps <= target slots per lane.  (Wavefronts of
+      // a block that hold no slot of the row skip the arithmetic, so rounding G up costs little;
+      // blocks of 6 or 12 wavefronts were measured slower: they load the four SIMDs unevenly.)
       const int target = std::max(1, std::min(2, c->row_target_nv));
       int G = 1 << ilog2_ceil((spr + target - 1) / target);
       G = std::min(G, 1024);
@@ -328,7 +345,7 @@ int make_plan(disc_ctx* c, const Pattern& p, const int64_t* dims, int n_dims, in
       static const char* ks[] = {"k_row_scalar_nv1", "k_row_scalar_nv2", "k_row_scalar_nv2w"};
       const int ii = G > 256 ? 2 : inst - 1;
       if (G > 256) inst = 2;
-      L.block = (uint32_t)std::max(256, G);
+      L.block = G > 64 ? (uint32_t)G : 256u;
       L.kernel = vec ? kv[ii] : ks[ii];
       L.plan_kind = 1;
       L.rp.G = G;
@@ -342,9 +359,13 @@ int make_plan(disc_ctx* c, const Pattern& p, const int64_t* dims, int n_dims, in
         L.rp.pad = stage ? 1 : 0;
         L.dyn_lds = stage ? (uint32_t)bytes : 0;
       }
+      // grid-stride over row groups with a whole number of rounds of the blocks the chip holds at
+      // once.  One round would do for balance, but blocks that all start together stay in step
+      // (every CU loads, then every CU computes); later rounds start staggered and overlap
       const int rpb = (int)L.block / G;
       const int64_t ngroups = (sv.rows + rpb - 1) / rpb;
-      L.grid[0] = (uint32_t)std::min<int64_t>(ngroups, std::max<int64_t>(c->n_cus, max_grid * 256 / L.block));
+      const int64_t held = (int64_t)c->n_cus * resident_blocks(c, p, L.kernel, L.block, L.dyn_lds);
+      L.grid[0] = (uint32_t)std::min<int64_t>(ngroups, held * c->row_rounds);
       pub.lanes_per_row = G;
       pub.slots_per_lane = nv;
       pub.reg_slots = inst;
@@ -427,6 +448,22 @@ int make_plan(disc_ctx* c, const Pattern& p, const int64_t* dims, int n_dims, in
   return DISC_OK;
 }
 
+int resident_blocks(const disc_ctx* c, const Pattern& p, const char* kernel, uint32_t block, uint32_t dyn_lds) {
+  const int estimate = std::max(1, 16 / (int)((block + 63) / 64));
+  if (c->device < 0) return estimate;
+  char key[96];
+  snprintf(key, sizeof key, "%s/%u/%u", kernel, block, dyn_lds);
+  auto it = p.resident.find(key);
+  if (it != p.resident.end()) return it->second;
+  int nb = 0;
+  auto f = p.fn.find(kernel);
+  if (f == p.fn.end() ||
+      hipModuleOccupancyMaxActiveBlocksPerMultiprocessor(&nb, f->second, (int)block, dyn_lds) != hipSuccess || nb < 1)
+    nb = estimate;
+  p.resident[key] = nb;
+  return nb;
+}
+
 void fill_args(const Pattern& p, const FullPlan& fp, const int64_t* dims, const void* const* in, void* const* outp,
                void* ws, unsigned char* buf) {
   const ShapeVals& sv = fp.sv;
@@ -504,6 +541,7 @@ int disc_create(disc_ctx** out, int hip_device) {
   }
   if (const char* e = getenv("DISC_ROW_TARGET_NV")) c->row_target_nv = std::max(1, std::min(8, atoi(e)));
   if (const char* e = getenv("DISC_ROW_STAGE")) c->row_stage = atoi(e) != 0;
+  if (const char* e = getenv("DISC_ROW_ROUNDS")) c->row_rounds = std::max(1, atoi(e));
   if (const char* e = getenv("DISC_GRID_MULT")) c->grid_mult = std::max(1, std::min(64, atoi(e)));
   if (const char* e = getenv("DISC_LOOP_UNROLL")) (void)e;   // the unroll factor is a compile-time constant of the kernels
   *out = c.release();
