@@ -356,17 +356,19 @@ DISC_DEV void kloop_body(const typename Pat::Args& A) {
 //
 // Register-resident version: a row is owned by a group of G lanes chosen by the host per shape:
 // a power of two 1..32 = several rows per wavefront for short rows, 64 = a wavefront per row,
-// any multiple of 64 up to 1024 = a block of G/64 wavefronts per row.  Lane l of the group holds
+// a multiple of 64 up to 1024 = G/64 wavefronts per row (the host picks block sizes whose
+// wavefront count is a multiple of four, so the four SIMDs of a CU get equal shares).  Lane l of the group holds
 // slots l, l+G, l+2G, ... (NV of them, V elements each), loaded ONCE; every reduction phase
 // and the epilogue run out of registers, so the row makes exactly one trip from HBM and one
 // back.  Within a wavefront partial results are combined with xor-shuffles; across the
 // wavefronts of a row through a double-buffered LDS exchange (one barrier per phase).
 // =======================================================================================
 struct RowPlan {
-  int G;        // lanes per row: a power of two <= 64, or a multiple of 64 equal to blockDim.x
+  int G;        // lanes per row: a power of two <= 64, or a multiple of 64 (whole wavefronts)
   int log2G;    // meaningful for G <= 64
   int nv;       // slots per lane actually needed at this shape (<= NV of the instantiation)
   int flags;    // bit 0: row-vector operands are staged once per block in dynamic LDS
+  int rpb;      // rows per block = blockDim.x / G
 };
 
 // Row-vector operands (bias, gamma, beta, ...) are the same for every row a block processes:
@@ -392,11 +394,13 @@ DISC_DEV void ld_lds(Vec<T, N>& d, const char* base, int byte_off, int col) {
   d.v = *reinterpret_cast<const typename Vec<T, N>::vec_t*>(base + byte_off + col * (int)sizeof(T));
 }
 
-template <class Pat, int P, int V, int NV>
+// `after_first` runs once, after the slots have been folded into the accumulator of phase 0 and
+// before the lanes combine: the place where the caller issues the loads of the next row.
+template <class Pat, int P, int V, int NV, class Hook>
 DISC_DEV void row_phases(const typename Pat::Args& A, const RowPlan& rp, typename Pat::RowCtx& rc,
                          const typename Pat::template Slot<V> (&slot)[NV],
                          typename Pat::template Keep<V> (&keep)[NV], const Span (&span)[NV],
-                         int col0, char* lds, int& parity) {
+                         int col0, char* lds, int& parity, Hook& after_first) {
   if constexpr (P < Pat::NPHASE) {
     typename Pat::template Acc<P> acc;
     Pat::template acc_init<P>(acc);
@@ -405,6 +409,7 @@ DISC_DEV void row_phases(const typename Pat::Args& A, const RowPlan& rp, typenam
       const int col = col0 + j * rp.G * V;
       if (span[j].any()) Pat::template phase<P, V, true>(A, acc, slot[j], keep[j], span[j], col, rc);
     }
+    if constexpr (P == 0) after_first();
     // lanes of one wavefront
     group_allreduce<Pat, P>(acc, rp.G < 64 ? rp.G : 64);
     // wavefronts of one row
@@ -415,26 +420,26 @@ DISC_DEV void row_phases(const typename Pat::Args& A, const RowPlan& rp, typenam
       const int wave = threadIdx.x >> 6;
       if ((threadIdx.x & 63) == 0) ex[wave] = acc;
       __syncthreads();
-      const int wpr = rp.G >> 6;               // wavefronts per row = wavefronts per block
-      acc = ex[0];
+      const int wpr = rp.G >> 6;               // wavefronts per row
+      const int w0 = (wave / wpr) * wpr;       // first wavefront of this row
+      acc = ex[w0];
       for (int w = 1; w < wpr; ++w) {
-        AccT o = ex[w];
+        AccT o = ex[w0 + w];
         Pat::template acc_merge<P>(acc, o);
       }
     }
     Pat::template row_after<P>(A, rc, acc);
-    row_phases<Pat, P + 1, V, NV>(A, rp, rc, slot, keep, span, col0, lds, parity);
+    row_phases<Pat, P + 1, V, NV>(A, rp, rc, slot, keep, span, col0, lds, parity, after_first);
   }
 }
 
 template <class Pat, int V, int NV>
 DISC_DEV void row_reg_body(const typename Pat::Args& A, const RowPlan& rp) {
   __shared__ __attribute__((aligned(16))) char lds[2 * 16 * Pat::MAX_ACC_BYTES];
-  // G <= 64: a power of two, several rows per block; G > 64: a multiple of 64, the block is the row
-  const bool multi = rp.G > 64;
-  const int lane = multi ? (int)threadIdx.x : (int)threadIdx.x & (rp.G - 1);
-  const int grp = multi ? 0 : (int)threadIdx.x >> rp.log2G;
-  const int rpb = multi ? 1 : (int)blockDim.x >> rp.log2G;        // rows per block
+  // G <= 64: a power of two; G > 64: a multiple of 64
+  const int grp = rp.G <= 64 ? (int)threadIdx.x >> rp.log2G : ((int)threadIdx.x >> 6) / (rp.G >> 6);
+  const int lane = (int)threadIdx.x - grp * rp.G;
+  const int rpb = rp.rpb;
   const i64 rows = A.rows;
   const int inner = (int)A.inner;
   int parity = 0;
@@ -446,33 +451,62 @@ DISC_DEV void row_reg_body(const typename Pat::Args& A, const RowPlan& rp) {
     __syncthreads();
     staged = disc_stage_lds;
   }
-  for (i64 rg = blockIdx.x; rg < ngroups; rg += gridDim.x) {
-    const i64 row = rg * rpb + grp;
-    const bool active = row < rows;
-    typename Pat::RowCtx rc{};
-    typename Pat::template Slot<V> slot[NV];
-    typename Pat::template Keep<V> keep[NV];
-    Span span[NV];
-    if (active) Pat::row_begin(A, row, rc);
+  // The spans depend on the lane only.  A group past the last row (last block, several rows per
+  // block) works on the last row again and stores nothing, so that no branch depends on it.
+  Span span[NV];
+#pragma unroll
+  for (int j = 0; j < NV; ++j) {
+    const int col = col0 + j * rp.G * V;
+    const int hi = inner - col > V ? V : inner - col;
+    span[j] = Span::upto((j < rp.nv && hi > 0) ? hi : 0);
+  }
+  // Software pipeline over the rows of a block: the loads of the next row are issued as soon as
+  // the first reduction phase has consumed the current row's slots (every load issued so far
+  // has landed by then, so no wait in the rest of the iteration touches the new loads); they
+  // complete behind the lane reductions, the later phases, the epilogue and the stores.
+  typename Pat::RowCtx rc{};
+  typename Pat::template Slot<V> slot[NV];
+  i64 rg = blockIdx.x;
+  if (rg < ngroups) {
+    const i64 row = rg * rpb + grp < rows ? rg * rpb + grp : rows - 1;
+    Pat::row_begin(A, row, rc);
     rc.sl = staged;
 #pragma unroll
-    for (int j = 0; j < NV; ++j) {
-      const int col = col0 + j * rp.G * V;
-      const int hi = inner - col > V ? V : inner - col;
-      span[j] = Span::upto((active && j < rp.nv && hi > 0) ? hi : 0);
-      if (span[j].any()) Pat::template load<V>(A, rc, col, span[j], slot[j]);
-    }
-    row_phases<Pat, 0, V, NV>(A, rp, rc, slot, keep, span, col0, lds, parity);
+    for (int j = 0; j < NV; ++j)
+      if (span[j].any()) Pat::template load<V>(A, rc, col0 + j * rp.G * V, span[j], slot[j]);
+  }
+  while (rg < ngroups) {
+    const i64 row = rg * rpb + grp;
+    const bool active = row < rows;
+    const i64 rgn = rg + gridDim.x;
+    typename Pat::RowCtx rcn{};
+    typename Pat::template Slot<V> nxt[NV];
+    auto prefetch = [&]() {
+      if (rgn < ngroups) {
+        const i64 rown = rgn * rpb + grp < rows ? rgn * rpb + grp : rows - 1;
+        Pat::row_begin(A, rown, rcn);
+        rcn.sl = staged;
+#pragma unroll
+        for (int j = 0; j < NV; ++j)
+          if (span[j].any()) Pat::template load<V>(A, rcn, col0 + j * rp.G * V, span[j], nxt[j]);
+      }
+    };
+    typename Pat::template Keep<V> keep[NV];
+    row_phases<Pat, 0, V, NV>(A, rp, rc, slot, keep, span, col0, lds, parity, prefetch);
 #pragma unroll
     for (int j = 0; j < NV; ++j) {
       if (span[j].any()) {
         const int col = col0 + j * rp.G * V;
         typename Pat::template OutSlot<V> o;
         Pat::template epilogue<V, true>(A, rc, slot[j], keep[j], col, span[j], o);
-        Pat::template store<V>(A, rc, col, span[j], o);
+        if (active) Pat::template store<V>(A, rc, col, span[j], o);
       }
     }
     if (active && lane == 0) Pat::row_store(A, row, rc);
+    rg = rgn;
+    rc = rcn;
+#pragma unroll
+    for (int j = 0; j < NV; ++j) slot[j] = nxt[j];
   }
 }
 

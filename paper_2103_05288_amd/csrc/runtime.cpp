@@ -23,7 +23,7 @@ extern const char* const kDeviceHeader;   // disc_device.h, embedded at build ti
 namespace {
 
 struct DeviceRowPlan {   // mirrors disc::RowPlan of the device header
-  int32_t G, log2G, nv, pad;
+  int32_t G, log2G, nv, pad, rpb;
 };
 struct DeviceColPlan {   // mirrors disc::ColPlan of the device header
   int32_t GC, log2GC, nchunk, pad;
@@ -100,7 +100,7 @@ struct disc_ctx {
   hipFunction_t util_copy = nullptr, util_empty = nullptr;
   int row_target_nv = 2;     // tuning knobs, overridable from the environment for experiments
   int grid_mult = 8;
-  int row_rounds = 2;        // row kernels: grid = this many rounds of resident blocks
+  int row_rounds = 1;        // row kernels: grid = this many rounds of resident blocks
   int loop_unroll = 4;
   int row_stage = 1;
 };
@@ -332,25 +332,37 @@ int make_plan(disc_ctx* c, const Pattern& p, const int64_t* dims, int n_dims, in
       pub.slots_per_lane = (int)((spr + 255) / 256);
       pub.reg_slots = 1;
     } else {
-      // lanes per row: smallest power of two that keeps <= target slots per lane.  (Wavefronts of
-      // a block that hold no slot of the row skip the arithmetic, so rounding G up costs little;
-      // blocks of 6 or 12 wavefronts were measured slower: they load the four SIMDs unevenly.)
-      const int target = std::max(1, std::min(2, c->row_target_nv));
-      int G = 1 << ilog2_ceil((spr + target - 1) / target);
-      G = std::min(G, 1024);
-      int nv = (int)((spr + G - 1) / G);
+      // Lanes per row G and slots per lane nv (<= 2): the pair with the least capacity G * nv that
+      // holds the row, two slots per lane on a tie.  G is a power of two.  The kernels accept any
+      // multiple of 64 above a wavefront, but the finer steps measured slower: 6-wavefront blocks
+      // load the four SIMDs of a CU unevenly (-25 %), 12-wavefront blocks (192 x 4 rows, 384 x 2)
+      // leave a CU with one resident block (-10 %), and one slot per lane on more lanes loses to two
+      // slots on fewer.  Wavefronts that hold no slot of the row skip the arithmetic anyway.
+      struct Shape { int G, block; };
+      static const Shape shapes[] = {{1, 256},  {2, 256},  {4, 256},   {8, 256},   {16, 256},  {32, 256},
+                                     {64, 256}, {128, 256}, {256, 256}, {512, 512}, {1024, 1024}};
+      const int max_nv = std::max(1, std::min(2, c->row_target_nv));
+      int G = 1024, nv = 2, block = 1024;
+      int64_t best_cap = -1;
+      for (const Shape& s : shapes)
+        for (int k = max_nv; k >= 1; --k) {
+          const int64_t cap = (int64_t)s.G * k;
+          if (cap >= spr && (best_cap < 0 || cap < best_cap)) { best_cap = cap; G = s.G; nv = k; block = s.block; }
+        }
+      nv = (int)((spr + G - 1) / G);
       int inst = nv <= 1 ? 1 : 2;
       pub.variant = vec ? DISC_V_ROW_REG_VEC : DISC_V_ROW_REG_SCALAR;
       static const char* kv[] = {"k_row_vec_nv1", "k_row_vec_nv2", "k_row_vec_nv2w"};
       static const char* ks[] = {"k_row_scalar_nv1", "k_row_scalar_nv2", "k_row_scalar_nv2w"};
-      const int ii = G > 256 ? 2 : inst - 1;
-      if (G > 256) inst = 2;
-      L.block = G > 64 ? (uint32_t)G : 256u;
+      const int ii = block > 256 ? 2 : inst - 1;
+      if (block > 256) inst = 2;
+      L.block = (uint32_t)block;
       L.kernel = vec ? kv[ii] : ks[ii];
       L.plan_kind = 1;
       L.rp.G = G;
       L.rp.log2G = ilog2_ceil(G);
       L.rp.nv = nv;
+      L.rp.rpb = block / G;
       // stage row vectors in LDS when they fit a modest budget (keeps >= 3 blocks per CU resident)
       {
         int64_t bytes = 0;
@@ -359,9 +371,8 @@ int make_plan(disc_ctx* c, const Pattern& p, const int64_t* dims, int n_dims, in
         L.rp.pad = stage ? 1 : 0;
         L.dyn_lds = stage ? (uint32_t)bytes : 0;
       }
-      // grid-stride over row groups with a whole number of rounds of the blocks the chip holds at
-      // once.  One round would do for balance, but blocks that all start together stay in step
-      // (every CU loads, then every CU computes); later rounds start staggered and overlap
+      // grid-stride over row groups with exactly the blocks the chip holds at once (a larger grid
+      // leaves a partly filled last round of blocks; two and more rounds measured slower)
       const int rpb = (int)L.block / G;
       const int64_t ngroups = (sv.rows + rpb - 1) / rpb;
       const int64_t held = (int64_t)c->n_cus * resident_blocks(c, p, L.kernel, L.block, L.dyn_lds);
