@@ -672,7 +672,9 @@ struct Gen {
       o << ind << "disc::Vec<" << dtype_ctype(a.dtype) << ", V> l" << ai << ";\n";
       const int st = staged_index(ai);
       if (st >= 0) {
-        o << ind << "if (rc.sl) disc::ld_lds(l" << ai << ", rc.sl, stage_offset<V>(A, " << st << "), (int)col);\n";
+        // a compile-time choice: behind a run-time branch the wait for the operand would cover both
+        // the LDS and the global counter, and so also the row loads that are in flight for later
+        o << ind << "if constexpr (STAGED) disc::ld_lds(l" << ai << ", rc.sl, stage_offset<V>(A, " << st << "), (int)col);\n";
         o << ind << "else disc::ld(l" << ai << ", A.p" << a.slot << ", " << elem_base(a, ai) << ", sp);\n";
       } else {
         o << ind << "disc::ld(l" << ai << ", A.p" << a.slot << ", " << elem_base(a, ai) << ", sp);\n";
@@ -867,10 +869,18 @@ struct Gen {
   void emit_kernels(Generated* out) {
     const int V = an.vec_width;
     int max_threads = 256;   // largest block the entry point may be launched with
-    auto k = [&](const std::string& name, const std::string& body, const char* plan) {
-      os << "extern \"C\" __global__ void __launch_bounds__(" << max_threads << ") " << out->prefix << name << "(Pat::Args A"
-         << (plan ? std::string(", disc::") + plan + " rp" : std::string()) << ") { " << body << " }\n";
+    auto k = [&](const std::string& name, const std::string& body, const char* plan, const char* pat = "Pat") {
+      os << "extern \"C\" __global__ void __launch_bounds__(" << max_threads << ") " << (max_threads > 256 ? "DISC_WIDE_ATTR " : "")
+         << out->prefix << name << "(" << pat
+         << "::Args A" << (plan ? std::string(", disc::") + plan + " rp" : std::string()) << ") { " << body << " }\n";
       out->kernels.push_back(name);
+    };
+    // register-resident row kernels come in a second version (suffix _s) that reads the
+    // row-vector operands from their LDS copy
+    const bool staged = !staged_accesses().empty();
+    auto krow = [&](const std::string& name, int v, int nv) {
+      k(name, fmt("disc::row_reg_body<Pat, %d, %d>(A, rp);", v, nv), "RowPlan");
+      if (staged) k(name + "_s", fmt("disc::row_reg_body<PatT<true>, %d, %d>(A, rp);", v, nv), "RowPlan", "PatT<true>");
     };
     if (an.tmpl == DISC_TEMPLATE_LOOP) {
       k("k_loop_vec", fmt("disc::kloop_body<Pat, %d, 4, false>(A);", V), nullptr);
@@ -881,12 +891,12 @@ struct Gen {
       // two slots per lane keep the register footprint near 100 VGPRs (4-5 waves per SIMD); longer
       // rows get more lanes (blocks of up to 1024 threads) rather than more slots per lane
       for (int nv : {1, 2}) {
-        k(fmt("k_row_vec_nv%d", nv), fmt("disc::row_reg_body<Pat, %d, %d>(A, rp);", V, nv), "RowPlan");
-        k(fmt("k_row_scalar_nv%d", nv), fmt("disc::row_reg_body<Pat, 1, %d>(A, rp);", nv), "RowPlan");
+        krow(fmt("k_row_vec_nv%d", nv), V, nv);
+        krow(fmt("k_row_scalar_nv%d", nv), 1, nv);
       }
       max_threads = 1024;
-      k("k_row_vec_nv2w", fmt("disc::row_reg_body<Pat, %d, 2>(A, rp);", V), "RowPlan");
-      k("k_row_scalar_nv2w", "disc::row_reg_body<Pat, 1, 2>(A, rp);", "RowPlan");
+      krow("k_row_vec_nv2w", V, 2);
+      krow("k_row_scalar_nv2w", 1, 2);
       max_threads = 256;
       k("k_row_stream_vec", fmt("disc::row_stream_body<Pat, %d>(A);", V), nullptr);
       k("k_row_stream_scalar", "disc::row_stream_body<Pat, 1>(A);", nullptr);
@@ -911,7 +921,9 @@ struct Gen {
     os << "// generated: one fused pattern, every kernel version\n";
     emit_acc_types();
     std::vector<char> all(an.accesses.size(), 1);
-    os << "struct Pat {\n";
+    const bool staged_versions = !staged_accesses().empty();
+    if (staged_versions) os << "template <bool ST> struct PatT {\n  static constexpr bool STAGED = ST;\n";
+    else os << "struct Pat {\n  static constexpr bool STAGED = false;\n";
     os << "  static constexpr int NPHASE = " << an.n_phases << ";\n";
     os << "  static constexpr int MAX_ACC_BYTES = " << acc_bytes << ";\n";
     os << "  template <int P> using Acc = typename PatAccSel<P>::type;\n";
@@ -928,6 +940,7 @@ struct Gen {
       }
       emit_epilogue(M_ELEM);
       os << "};\n";
+      if (staged_versions) os << "typedef PatT<false> Pat;\n";
     } else {
       // stage 1 + 2: operands that feed the reductions
       std::vector<int> roots;

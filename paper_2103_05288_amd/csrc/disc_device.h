@@ -33,6 +33,9 @@
 //   NPHASE, MAX_ACC_BYTES
 #pragma once
 
+#ifndef DISC_WIDE_ATTR
+#define DISC_WIDE_ATTR
+#endif
 namespace disc {
 
 typedef unsigned char u8;
@@ -367,7 +370,7 @@ struct RowPlan {
   int G;        // lanes per row: a power of two <= 64, or a multiple of 64 (whole wavefronts)
   int log2G;    // meaningful for G <= 64
   int nv;       // slots per lane actually needed at this shape (<= NV of the instantiation)
-  int flags;    // bit 0: row-vector operands are staged once per block in dynamic LDS
+  int flags;    // bit 0: the launched kernel is the version that stages row-vector operands in LDS
   int rpb;      // rows per block = blockDim.x / G
 };
 
@@ -409,7 +412,9 @@ DISC_DEV void row_phases(const typename Pat::Args& A, const RowPlan& rp, typenam
       const int col = col0 + j * rp.G * V;
       if (span[j].any()) Pat::template phase<P, V, true>(A, acc, slot[j], keep[j], span[j], col, rc);
     }
+#ifndef EXP_PREFETCH_LATE
     if constexpr (P == 0) after_first();
+#endif
     // lanes of one wavefront
     group_allreduce<Pat, P>(acc, rp.G < 64 ? rp.G : 64);
     // wavefronts of one row
@@ -422,13 +427,23 @@ DISC_DEV void row_phases(const typename Pat::Args& A, const RowPlan& rp, typenam
       __syncthreads();
       const int wpr = rp.G >> 6;               // wavefronts per row
       const int w0 = (wave / wpr) * wpr;       // first wavefront of this row
-      acc = ex[w0];
-      for (int w = 1; w < wpr; ++w) {
-        AccT o = ex[w0 + w];
-        Pat::template acc_merge<P>(acc, o);
+      if ((wpr & (wpr - 1)) == 0) {
+        // every lane fetches one partial (lane i the one of wavefront i mod wpr) and the lanes
+        // combine them with the butterfly: one LDS read instead of a chain of wpr dependent ones
+        acc = ex[w0 + ((int)threadIdx.x & (wpr - 1))];
+        group_allreduce<Pat, P>(acc, wpr);
+      } else {
+        acc = ex[w0];
+        for (int w = 1; w < wpr; ++w) {
+          AccT o = ex[w0 + w];
+          Pat::template acc_merge<P>(acc, o);
+        }
       }
     }
     Pat::template row_after<P>(A, rc, acc);
+#ifdef EXP_PREFETCH_LATE
+    if constexpr (P == Pat::NPHASE - 1) after_first();
+#endif
     row_phases<Pat, P + 1, V, NV>(A, rp, rc, slot, keep, span, col0, lds, parity, after_first);
   }
 }
@@ -445,21 +460,38 @@ DISC_DEV void row_reg_body(const typename Pat::Args& A, const RowPlan& rp) {
   int parity = 0;
   const i64 ngroups = (rows + rpb - 1) / rpb;
   const char* staged = nullptr;
-  const int col0 = lane * V;
-  if (rp.flags & 1) {
+  if constexpr (Pat::STAGED) {
     Pat::template stage<V>(A, disc_stage_lds, threadIdx.x, blockDim.x);
     __syncthreads();
     staged = disc_stage_lds;
   }
-  // The spans depend on the lane only.  A group past the last row (last block, several rows per
-  // block) works on the last row again and stores nothing, so that no branch depends on it.
-  Span span[NV];
+  // A group past the last row (last block, several rows per block) works on the last row again
+  // and stores nothing, so that no branch depends on it.
+  //
+  // Rows of several wavefronts: the wavefront that gets the ragged extra slots of a row does up
+  // to twice the work of the others, and it would always be the first one -- on the same SIMD
+  // of the CU for every row.  The slot grid is therefore turned by one wavefront from row to
+  // row (lane l takes the columns of lane l + rot), which spreads the extra work evenly.
+#ifdef EXP_NO_ROT
+  const int wpr = 1;
+#else
+  const int wpr = rp.G > 64 ? rp.G >> 6 : 1;
+#endif
+  int rot = wpr > 1 ? (int)(blockIdx.x % (unsigned)wpr) * 64 : 0;
+  int col0 = lane * V;
+  int nvalid[NV];
+  auto place = [&](int r, int& c0, int (&n)[NV]) {
+    int l = lane + r;
+    if (l >= rp.G) l -= rp.G;
+    c0 = l * V;
 #pragma unroll
-  for (int j = 0; j < NV; ++j) {
-    const int col = col0 + j * rp.G * V;
-    const int hi = inner - col > V ? V : inner - col;
-    span[j] = Span::upto((j < rp.nv && hi > 0) ? hi : 0);
-  }
+    for (int j = 0; j < NV; ++j) {
+      const int col = c0 + j * rp.G * V;
+      const int hi = inner - col > V ? V : inner - col;
+      n[j] = (j < rp.nv && hi > 0) ? hi : 0;
+    }
+  };
+  place(rot, col0, nvalid);
   // Software pipeline over the rows of a block: the loads of the next row are issued as soon as
   // the first reduction phase has consumed the current row's slots (every load issued so far
   // has landed by then, so no wait in the rest of the iteration touches the new loads); they
@@ -473,23 +505,45 @@ DISC_DEV void row_reg_body(const typename Pat::Args& A, const RowPlan& rp) {
     rc.sl = staged;
 #pragma unroll
     for (int j = 0; j < NV; ++j)
-      if (span[j].any()) Pat::template load<V>(A, rc, col0 + j * rp.G * V, span[j], slot[j]);
+      if (nvalid[j] > 0) Pat::template load<V>(A, rc, col0 + j * rp.G * V, Span::upto(nvalid[j]), slot[j]);
   }
   while (rg < ngroups) {
+    // the per-element tests of the spans are made here, once per row: carried around the loop
+    // they would stop being lane masks in scalar registers
+    Span span[NV];
+#pragma unroll
+    for (int j = 0; j < NV; ++j) span[j] = Span::upto(nvalid[j]);
     const i64 row = rg * rpb + grp;
     const bool active = row < rows;
     const i64 rgn = rg + gridDim.x;
     typename Pat::RowCtx rcn{};
     typename Pat::template Slot<V> nxt[NV];
+    int col0n = col0;
+    int nvalidn[NV];
+#pragma unroll
+    for (int j = 0; j < NV; ++j) nvalidn[j] = nvalid[j];
     auto prefetch = [&]() {
       if (rgn < ngroups) {
+        if (wpr > 1) {
+          rot = rot + 64 < rp.G ? rot + 64 : 0;
+          place(rot, col0n, nvalidn);
+        }
         const i64 rown = rgn * rpb + grp < rows ? rgn * rpb + grp : rows - 1;
         Pat::row_begin(A, rown, rcn);
         rcn.sl = staged;
 #pragma unroll
         for (int j = 0; j < NV; ++j)
-          if (span[j].any()) Pat::template load<V>(A, rcn, col0 + j * rp.G * V, span[j], nxt[j]);
+          if (nvalidn[j] > 0) {
+            Span sn;            // the loads look at the element count only
+            sn.n = nvalidn[j];
+            Pat::template load<V>(A, rcn, col0n + j * rp.G * V, sn, nxt[j]);
+          }
       }
+      // keep the loads here: without a fence the compiler is free to sink them below the
+      // stores of this row (to save registers), which undoes the pipeline
+#ifndef EXP_NO_FENCE
+      asm volatile("" ::: "memory");
+#endif
     };
     typename Pat::template Keep<V> keep[NV];
     row_phases<Pat, 0, V, NV>(A, rp, rc, slot, keep, span, col0, lds, parity, prefetch);
@@ -507,6 +561,11 @@ DISC_DEV void row_reg_body(const typename Pat::Args& A, const RowPlan& rp) {
     rc = rcn;
 #pragma unroll
     for (int j = 0; j < NV; ++j) slot[j] = nxt[j];
+    if (wpr > 1) {
+      col0 = col0n;
+#pragma unroll
+      for (int j = 0; j < NV; ++j) nvalid[j] = nvalidn[j];
+    }
   }
 }
 

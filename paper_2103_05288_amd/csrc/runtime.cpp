@@ -100,7 +100,7 @@ struct disc_ctx {
   hipFunction_t util_copy = nullptr, util_empty = nullptr;
   int row_target_nv = 2;     // tuning knobs, overridable from the environment for experiments
   int grid_mult = 8;
-  int row_rounds = 1;        // row kernels: grid = this many rounds of resident blocks
+  int row_rounds = 0;        // row kernels: grid = this many rounds of resident blocks (0: by block size)
   int loop_unroll = 4;
   int row_stage = 1;
 };
@@ -370,13 +370,21 @@ int make_plan(disc_ctx* c, const Pattern& p, const int64_t* dims, int n_dims, in
         const bool stage = c->row_stage && bytes > 0 && bytes <= 48 * 1024;
         L.rp.pad = stage ? 1 : 0;
         L.dyn_lds = stage ? (uint32_t)bytes : 0;
+        if (stage) {
+          static const char* kvs[] = {"k_row_vec_nv1_s", "k_row_vec_nv2_s", "k_row_vec_nv2w_s"};
+          static const char* kss[] = {"k_row_scalar_nv1_s", "k_row_scalar_nv2_s", "k_row_scalar_nv2w_s"};
+          L.kernel = vec ? kvs[ii] : kss[ii];
+        }
       }
-      // grid-stride over row groups with exactly the blocks the chip holds at once (a larger grid
-      // leaves a partly filled last round of blocks; two and more rounds measured slower)
+      // grid-stride over row groups: a small whole number of rounds of the blocks the chip holds
+      // at once.  Measured: blocks of one wavefront-quad do best with three rounds (the hardware
+      // does not fill every CU to the computed residency in the first round; later blocks even
+      // that out), the wide blocks with one (each new block pays an unpipelined first row)
       const int rpb = (int)L.block / G;
       const int64_t ngroups = (sv.rows + rpb - 1) / rpb;
       const int64_t held = (int64_t)c->n_cus * resident_blocks(c, p, L.kernel, L.block, L.dyn_lds);
-      L.grid[0] = (uint32_t)std::min<int64_t>(ngroups, held * c->row_rounds);
+      const int rounds = c->row_rounds > 0 ? c->row_rounds : (L.block > 256 ? 1 : 3);
+      L.grid[0] = (uint32_t)std::min<int64_t>(ngroups, held * rounds);
       pub.lanes_per_row = G;
       pub.slots_per_lane = nv;
       pub.reg_slots = inst;
@@ -552,7 +560,7 @@ int disc_create(disc_ctx** out, int hip_device) {
   }
   if (const char* e = getenv("DISC_ROW_TARGET_NV")) c->row_target_nv = std::max(1, std::min(8, atoi(e)));
   if (const char* e = getenv("DISC_ROW_STAGE")) c->row_stage = atoi(e) != 0;
-  if (const char* e = getenv("DISC_ROW_ROUNDS")) c->row_rounds = std::max(1, atoi(e));
+  if (const char* e = getenv("DISC_ROW_ROUNDS")) c->row_rounds = std::max(0, atoi(e));
   if (const char* e = getenv("DISC_GRID_MULT")) c->grid_mult = std::max(1, std::min(64, atoi(e)));
   if (const char* e = getenv("DISC_LOOP_UNROLL")) (void)e;   // the unroll factor is a compile-time constant of the kernels
   *out = c.release();
