@@ -889,13 +889,17 @@ struct Gen {
       k("k_loop_scalar_i64", "disc::kloop_body<Pat, 1, 1, true>(A);", nullptr);
     } else if (an.tmpl == DISC_TEMPLATE_ROW_REDUCE) {
       // two slots per lane keep the register footprint near 100 VGPRs (4-5 waves per SIMD); longer
-      // rows get more lanes (blocks of up to 1024 threads) rather than more slots per lane
+      // rows get more lanes (blocks of up to 1024 threads) rather than more slots per lane.  The
+      // three-slot versions exist for the row lengths that would leave a third of the lanes of the
+      // next power of two without work
       for (int nv : {1, 2}) {
         krow(fmt("k_row_vec_nv%d", nv), V, nv);
         krow(fmt("k_row_scalar_nv%d", nv), 1, nv);
       }
+      krow("k_row_vec_nv3", V, 3);
       max_threads = 1024;
       krow("k_row_vec_nv2w", V, 2);
+      krow("k_row_vec_nv3w", V, 3);
       krow("k_row_scalar_nv2w", 1, 2);
       max_threads = 256;
       k("k_row_stream_vec", fmt("disc::row_stream_body<Pat, %d>(A);", V), nullptr);

@@ -98,7 +98,7 @@ struct disc_ctx {
   int force_variant = -1;
   hipModule_t util_module = nullptr;
   hipFunction_t util_copy = nullptr, util_empty = nullptr;
-  int row_target_nv = 2;     // tuning knobs, overridable from the environment for experiments
+  int row_target_nv = 3;     // tuning knobs, overridable from the environment for experiments
   int grid_mult = 8;
   int row_rounds = 0;        // row kernels: grid = this many rounds of resident blocks (0: by block size)
   int loop_unroll = 4;
@@ -315,7 +315,7 @@ int make_plan(disc_ctx* c, const Pattern& p, const int64_t* dims, int n_dims, in
     }
     const int v = vec ? V : 1;
     const int64_t spr = (sv.inner + v - 1) / v;
-    stream = spr > 1024 * 2;
+    stream = spr > 1024 * (vec ? 3 : 2);
     if (force == DISC_V_ROW_STREAM_VEC || force == DISC_V_ROW_STREAM_SCALAR) stream = true;
     else if (force >= 0 && stream) return set_err(c, DISC_ERR_INVALID_ARG, "row too long for the forced register-resident version");
     pub.vec_width = v;
@@ -341,7 +341,7 @@ int make_plan(disc_ctx* c, const Pattern& p, const int64_t* dims, int n_dims, in
       struct Shape { int G, block; };
       static const Shape shapes[] = {{1, 256},  {2, 256},  {4, 256},   {8, 256},   {16, 256},  {32, 256},
                                      {64, 256}, {128, 256}, {256, 256}, {512, 512}, {1024, 1024}};
-      const int max_nv = std::max(1, std::min(2, c->row_target_nv));
+      const int max_nv = std::max(1, std::min(vec ? 3 : 2, c->row_target_nv));   // three slots: wide versions only
       int G = 1024, nv = 2, block = 1024;
       int64_t best_cap = -1;
       for (const Shape& s : shapes)
@@ -350,14 +350,9 @@ int make_plan(disc_ctx* c, const Pattern& p, const int64_t* dims, int n_dims, in
           if (cap >= spr && (best_cap < 0 || cap < best_cap)) { best_cap = cap; G = s.G; nv = k; block = s.block; }
         }
       nv = (int)((spr + G - 1) / G);
-      int inst = nv <= 1 ? 1 : 2;
+      int inst = std::max(nv, block > 256 ? 2 : 1);   // instantiated slots per lane (blocks above 256: 2 or 3)
       pub.variant = vec ? DISC_V_ROW_REG_VEC : DISC_V_ROW_REG_SCALAR;
-      static const char* kv[] = {"k_row_vec_nv1", "k_row_vec_nv2", "k_row_vec_nv2w"};
-      static const char* ks[] = {"k_row_scalar_nv1", "k_row_scalar_nv2", "k_row_scalar_nv2w"};
-      const int ii = block > 256 ? 2 : inst - 1;
-      if (block > 256) inst = 2;
       L.block = (uint32_t)block;
-      L.kernel = vec ? kv[ii] : ks[ii];
       L.plan_kind = 1;
       L.rp.G = G;
       L.rp.log2G = ilog2_ceil(G);
@@ -370,11 +365,17 @@ int make_plan(disc_ctx* c, const Pattern& p, const int64_t* dims, int n_dims, in
         const bool stage = c->row_stage && bytes > 0 && bytes <= 48 * 1024;
         L.rp.pad = stage ? 1 : 0;
         L.dyn_lds = stage ? (uint32_t)bytes : 0;
-        if (stage) {
-          static const char* kvs[] = {"k_row_vec_nv1_s", "k_row_vec_nv2_s", "k_row_vec_nv2w_s"};
-          static const char* kss[] = {"k_row_scalar_nv1_s", "k_row_scalar_nv2_s", "k_row_scalar_nv2w_s"};
-          L.kernel = vec ? kvs[ii] : kss[ii];
-        }
+        // k_row_{vec|scalar}_nv{1|2|3}[w][_s]: w = block above 256 threads, _s = staged version
+        static const std::vector<std::string> names = [] {
+          std::vector<std::string> t;
+          for (int vs = 0; vs < 2; ++vs)
+            for (int n = 1; n <= 3; ++n)
+              for (int w = 0; w < 2; ++w)
+                for (int s = 0; s < 2; ++s)
+                  t.push_back(std::string("k_row_") + (vs ? "scalar" : "vec") + "_nv" + std::to_string(n) + (w ? "w" : "") + (s ? "_s" : ""));
+          return t;
+        }();
+        L.kernel = names[(((vec ? 0 : 1) * 3 + (inst - 1)) * 2 + (block > 256 ? 1 : 0)) * 2 + (stage ? 1 : 0)].c_str();
       }
       // grid-stride over row groups: a small whole number of rounds of the blocks the chip holds
       // at once.  Measured: blocks of one wavefront-quad do best with three rounds (the hardware
