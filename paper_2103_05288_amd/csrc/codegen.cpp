@@ -870,17 +870,16 @@ struct Gen {
     const int V = an.vec_width;
     int max_threads = 256;   // largest block the entry point may be launched with
     auto k = [&](const std::string& name, const std::string& body, const char* plan, const char* pat = "Pat") {
-      os << "extern \"C\" __global__ void __launch_bounds__(" << max_threads << ") " << (max_threads > 256 ? "DISC_WIDE_ATTR " : "")
-         << out->prefix << name << "(" << pat
+      os << "extern \"C\" __global__ void __launch_bounds__(" << max_threads << ") " << out->prefix << name << "(" << pat
          << "::Args A" << (plan ? std::string(", disc::") + plan + " rp" : std::string()) << ") { " << body << " }\n";
       out->kernels.push_back(name);
     };
-    // register-resident row kernels come in a second version (suffix _s) that reads the
-    // row-vector operands from their LDS copy
+    // the wide register-resident row kernels come in a second version (suffix _s) that reads
+    // the row-vector operands from their LDS copy
     const bool staged = !staged_accesses().empty();
     auto krow = [&](const std::string& name, int v, int nv) {
       k(name, fmt("disc::row_reg_body<Pat, %d, %d>(A, rp);", v, nv), "RowPlan");
-      if (staged) k(name + "_s", fmt("disc::row_reg_body<PatT<true>, %d, %d>(A, rp);", v, nv), "RowPlan", "PatT<true>");
+      if (staged && v > 1) k(name + "_s", fmt("disc::row_reg_body<PatT<true>, %d, %d>(A, rp);", v, nv), "RowPlan", "PatT<true>");
     };
     if (an.tmpl == DISC_TEMPLATE_LOOP) {
       k("k_loop_vec", fmt("disc::kloop_body<Pat, %d, 4, false>(A);", V), nullptr);

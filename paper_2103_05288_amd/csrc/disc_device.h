@@ -33,9 +33,6 @@
 //   NPHASE, MAX_ACC_BYTES
 #pragma once
 
-#ifndef DISC_WIDE_ATTR
-#define DISC_WIDE_ATTR
-#endif
 namespace disc {
 
 typedef unsigned char u8;
@@ -91,11 +88,7 @@ struct Span {
     return s;
   }
   DISC_DEV bool full(int N) const { return n >= N; }
-#ifdef EXP_SPAN_INLINE
-  DISC_DEV bool has(int e) const { return e < n; }
-#else
   DISC_DEV bool has(int e) const { return ok[e]; }
-#endif
   DISC_DEV bool any() const { return n > 0; }
 };
 
@@ -142,20 +135,12 @@ DISC_DEV void ld(Vec<T, N>& d, const T* __restrict__ p, I off, Span sp, bool who
     d.v = *reinterpret_cast<const typename Vec<T, N>::unaligned_t*>(p + off);
   } else {
     d.clear();
-#ifdef EXP_LD_ELEM
-#pragma unroll
-    for (int e = 0; e < N; ++e)
-      if (sp.has(e)) d.set(e, p[off + e]);
-#else
     ld_pieces<N / 2>(d, p, off, sp.n);
-#endif
     // s_waitcnt vmcnt(0): the pieces are complete before the branches rejoin.  Otherwise the
     // compiler has to assume a piece may still be in flight into d's registers and makes the
     // wide load above wait for every earlier load of the wavefront -- on the path where no
     // lane took this branch at all, serialising the loads of full slots.
-#ifndef EXP_NO_WAIT
     __builtin_amdgcn_s_waitcnt(0x0F70);
-#endif
   }
 }
 
@@ -164,13 +149,7 @@ DISC_DEV void st(T* __restrict__ p, I off, const Vec<T, N>& s, Span sp) {
   if (sp.full(N)) {
     *reinterpret_cast<typename Vec<T, N>::unaligned_t*>(p + off) = s.v;
   } else {
-#ifdef EXP_ST_ELEM
-#pragma unroll
-    for (int e = 0; e < N; ++e)
-      if (sp.has(e)) p[off + e] = s.get(e);
-#else
     st_pieces<N / 2>(p, off, s, sp.n);
-#endif
   }
 }
 
@@ -412,9 +391,7 @@ DISC_DEV void row_phases(const typename Pat::Args& A, const RowPlan& rp, typenam
       const int col = col0 + j * rp.G * V;
       if (span[j].any()) Pat::template phase<P, V, true>(A, acc, slot[j], keep[j], span[j], col, rc);
     }
-#ifndef EXP_PREFETCH_LATE
     if constexpr (P == 0) after_first();
-#endif
     // lanes of one wavefront
     group_allreduce<Pat, P>(acc, rp.G < 64 ? rp.G : 64);
     // wavefronts of one row
@@ -441,9 +418,6 @@ DISC_DEV void row_phases(const typename Pat::Args& A, const RowPlan& rp, typenam
       }
     }
     Pat::template row_after<P>(A, rc, acc);
-#ifdef EXP_PREFETCH_LATE
-    if constexpr (P == Pat::NPHASE - 1) after_first();
-#endif
     row_phases<Pat, P + 1, V, NV>(A, rp, rc, slot, keep, span, col0, lds, parity, after_first);
   }
 }
@@ -472,11 +446,7 @@ DISC_DEV void row_reg_body(const typename Pat::Args& A, const RowPlan& rp) {
   // to twice the work of the others, and it would always be the first one -- on the same SIMD
   // of the CU for every row.  The slot grid is therefore turned by one wavefront from row to
   // row (lane l takes the columns of lane l + rot), which spreads the extra work evenly.
-#ifdef EXP_NO_ROT
-  const int wpr = 1;
-#else
   const int wpr = rp.G > 64 ? rp.G >> 6 : 1;
-#endif
   int rot = wpr > 1 ? (int)(blockIdx.x % (unsigned)wpr) * 64 : 0;
   int col0 = lane * V;
   int nvalid[NV];
@@ -541,9 +511,7 @@ DISC_DEV void row_reg_body(const typename Pat::Args& A, const RowPlan& rp) {
       }
       // keep the loads here: without a fence the compiler is free to sink them below the
       // stores of this row (to save registers), which undoes the pipeline
-#ifndef EXP_NO_FENCE
       asm volatile("" ::: "memory");
-#endif
     };
     typename Pat::template Keep<V> keep[NV];
     row_phases<Pat, 0, V, NV>(A, rp, rc, slot, keep, span, col0, lds, parity, prefetch);

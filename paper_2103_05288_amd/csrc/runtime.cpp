@@ -362,7 +362,7 @@ int make_plan(disc_ctx* c, const Pattern& p, const int64_t* dims, int n_dims, in
       {
         int64_t bytes = 0;
         for (int eb : p.gen.staged_elem_bytes) bytes += ((sv.inner + v) * eb + 15) & ~15ll;
-        const bool stage = c->row_stage && bytes > 0 && bytes <= 48 * 1024;
+        const bool stage = vec && V > 1 && c->row_stage && bytes > 0 && bytes <= 48 * 1024;
         L.rp.pad = stage ? 1 : 0;
         L.dyn_lds = stage ? (uint32_t)bytes : 0;
         // k_row_{vec|scalar}_nv{1|2|3}[w][_s]: w = block above 256 threads, _s = staged version

@@ -232,6 +232,32 @@ def test_row_schedule_selection(handles):
     expect("INVALID_ARG", h.plan, [10, 100000], V["row_reg_vec"])
 
 
+def test_row_schedule_capacity_steps(handles):
+    """Lanes per row x slots per lane: the least capacity among {2, 3} x power of two that holds the
+    row; blocks above 256 threads only for the two longest classes; staged kernel versions (_s) as
+    long as the row vectors fit the LDS budget."""
+    h = handles["C4"]                     # bf16, 8 elements per slot
+    cases = {                             # H -> (lanes per row, slots per lane, block)
+        64: (4, 2, 256), 65: (4, 3, 256), 97: (8, 2, 256), 512: (32, 2, 256), 513: (32, 3, 256),
+        1024: (64, 2, 256), 1100: (64, 3, 256), 1537: (128, 2, 256), 3000: (128, 3, 256),
+        4096: (256, 2, 256), 5739: (256, 3, 256), 6145: (512, 2, 512), 8192: (512, 2, 512),
+        8200: (512, 3, 512), 12289: (1024, 2, 1024), 16385: (1024, 3, 1024), 24576: (1024, 3, 1024),
+    }
+    for H, (G, nv, block) in cases.items():
+        p = h.plan([50, H])
+        assert (p["lanes_per_row"], p["slots_per_lane"], p["block"][0][0]) == (G, nv, block), (H, p)
+        assert G * nv * 8 >= H
+        want = "k_row_vec_nv%d%s" % (max(nv, 2 if block > 256 else 1), "w" if block > 256 else "")
+        assert p["kernels"][0].endswith(want + "_s") or p["kernels"][0].endswith(want), (H, p["kernels"])
+    assert h.plan([50, 24577])["variant_name"] == "row_stream_vec"
+    # C4 stages a float32 row vector: 4 bytes x H must fit 48 KiB
+    assert h.plan([50, 8192])["kernels"][0].endswith("_s") and h.plan([50, 8192])["lds_bytes"][0] >= 4 * 8192
+    assert not h.plan([50, 16385])["kernels"][0].endswith("_s") and h.plan([50, 16385])["lds_bytes"][0] == 0
+    # scalar versions: at most two slots per lane, never staged
+    p = h.plan([50, 100], V["row_reg_scalar"])
+    assert p["slots_per_lane"] <= 2 and not p["kernels"][0].endswith("_s")
+
+
 def test_loop_and_index_width_selection(ctx, handles):
     h = handles["C0"]
     p = h.plan([300, 768])

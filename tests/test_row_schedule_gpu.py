@@ -1,0 +1,125 @@
+"""GPU parity over the row-reduce schedules: every class of (lanes per row, slots per lane), ragged
+tails of every length, row counts that leave the last block partly filled, rows of several
+wavefronts whose slot grid turns from row to row, the staged (LDS) and unstaged kernel versions,
+and the streaming version behind the longest register-resident class."""
+import os
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import run as oracle_run
+from workloads import PatternBuilder
+from workloads.configs import CONFIGS
+from tests.util import assert_close, run_gpu, to_oracle_input
+
+pytestmark = pytest.mark.gpu
+
+# row lengths chosen around the capacity steps 2 * 2^k and 3 * 2^k slots of 8 elements, plus ragged
+# tails 1..7 past a slot boundary
+ROW_LENGTHS = [1, 3, 7, 8, 9, 15, 17, 31, 33, 47, 63, 65, 97, 100, 127, 129, 191, 200, 255, 257, 385, 511, 513, 770,
+               1023, 1025, 1100, 1537, 2047, 2049, 3000, 3073, 4097, 5739, 6145, 8191, 8193, 12289, 16386, 20003,
+               24576, 24577]
+
+
+@pytest.fixture(scope="module")
+def ctx():
+    from paper_2103_05288_amd import Context
+    c = Context(0)
+    yield c
+    c.close()
+
+
+def check(ctx, cfg_name, dims, seed, handle=None):
+    cfg = CONFIGS[cfg_name]
+    pat = cfg.pattern()
+    h = handle or ctx.register(pat)
+    ins = cfg.inputs(dims, seed=seed)
+    got = run_gpu(h, pat, dims, ins)
+    want = oracle_run(pat, dims, [to_oracle_input(t) for t in ins])[0]
+    plan = h.plan(dims)
+    for k, (g, w) in enumerate(zip(got, want)):
+        assert_close(g, w, f"{cfg_name} dims={dims} out{k} G={plan['lanes_per_row']} nv={plan['slots_per_lane']} "
+                           f"kernel={plan['kernels'][0]}")
+    return plan
+
+
+@pytest.mark.parametrize("cfg_name", ["C2", "C4"])
+def test_every_capacity_class_and_tail(ctx, cfg_name):
+    h = ctx.register(CONFIGS[cfg_name].pattern())
+    seen = set()
+    for i, H in enumerate(ROW_LENGTHS):
+        T = 1 + (i * 5) % 23            # 1 .. 23 rows: every residue of rows per block shows up
+        plan = check(ctx, cfg_name, [T, H], seed=100 + i, handle=h)
+        seen.add((plan["variant_name"], plan["lanes_per_row"], plan["slots_per_lane"]))
+    lanes = {g for v, g, n in seen if v == "row_reg_vec"}
+    assert {4, 8, 16, 32, 64, 128, 256, 512, 1024} <= lanes
+    assert {n for v, g, n in seen if v == "row_reg_vec"} >= {1, 2, 3}
+    assert any(v == "row_stream_vec" for v, g, n in seen)
+
+
+@pytest.mark.parametrize("cfg_name", ["C2", "C4"])
+def test_many_rows_per_block_and_turning_grid(monkeypatch, cfg_name):
+    """Enough rows that blocks walk several of them (the software pipeline runs past its first row)
+    and, for rows of several wavefronts, the slot grid keeps turning.  One round of resident blocks
+    keeps the row counts this needs small."""
+    from paper_2103_05288_amd import Context
+    monkeypatch.setenv("DISC_ROW_ROUNDS", "1")
+    c = Context(0)
+    try:
+        h = c.register(CONFIGS[cfg_name].pattern())
+        for H, T in [(127, 70001), (1100, 9001), (2047, 6000), (3001, 5003), (5739, 6007), (8190, 4500), (20003, 700)]:
+            plan = check(c, cfg_name, [T, H], seed=H, handle=h)
+            rows_per_block = plan["block"][0][0] // plan["lanes_per_row"]
+            assert T > plan["grid"][0][0] * rows_per_block, (H, T, plan["grid"], rows_per_block)
+    finally:
+        c.close()
+
+
+def test_unstaged_versions(monkeypatch):
+    """The same shapes with LDS staging switched off: the kernel versions that read row vectors from
+    global memory in every slot."""
+    from paper_2103_05288_amd import Context
+    monkeypatch.setenv("DISC_ROW_STAGE", "0")
+    c = Context(0)
+    try:
+        for cfg_name in ("C2", "C4"):
+            h = c.register(CONFIGS[cfg_name].pattern())
+            for H, T in [(9, 40), (127, 300), (1100, 77), (3001, 2003), (8190, 600), (20003, 40)]:
+                plan = check(c, cfg_name, [T, H], seed=H + 1, handle=h)
+                assert not plan["kernels"][0].endswith("_s") and plan["lds_bytes"][0] == 0
+    finally:
+        c.close()
+
+
+def test_ragged_pieces_every_storage_width(ctx):
+    """One pattern with 1-, 2- and 4-byte operands and outputs of each width, so the ragged tail of a
+    row moves through the power-of-two pieces of every vector type; the last row ends the tensors, so
+    its tail cannot be over-read."""
+    pb = PatternBuilder("widths")
+    T, H = pb.dims(2)
+    a = pb.param("bf16", [T, H])
+    b = pb.param("f32", [T, H])
+    m = pb.param("bool", [T, H])
+    a32 = pb.cast(a, "f32")
+    s = pb.reduce("max", pb.op("mul", a32, b), 1)      # a max: no accumulated rounding to cancel against
+    y = pb.op("select", m, b, pb.op("add", a32, pb.broadcast(s, [T, H], [0])), dims=[T, H])
+    pb.output(y)                                        # f32
+    pb.output(pb.cast(y, "f16"))                        # 2 bytes
+    pb.output(pb.op("gt", y, pb.const(0.0), dims=[T, H]))   # bool, 1 byte
+    pat = pb.build()
+    h = ctx.register(pat)
+    rng = np.random.default_rng(5)
+    for H_ in list(range(1, 18)) + [63, 127, 129, 250, 1001, 4099]:
+        for T_ in (1, 5):
+            ins = [torch.from_numpy(rng.standard_normal((T_, H_)).astype(np.float32)).to(torch.bfloat16),
+                   torch.from_numpy(rng.standard_normal((T_, H_)).astype(np.float32)),
+                   torch.from_numpy((rng.random((T_, H_)) < 0.3).astype(np.uint8))]
+            got = run_gpu(h, pat, [T_, H_], ins)
+            want = oracle_run(pat, [T_, H_], [to_oracle_input(t) for t in ins])[0]
+            # the comparison output flips where y is within rounding of zero: compare it only away from 0
+            y64 = np.asarray(want[0])
+            safe = np.abs(y64) > 1e-4
+            assert_close(got[0], want[0], f"widths f32 dims={[T_, H_]}")
+            assert_close(got[1], want[1], f"widths f16 dims={[T_, H_]}")
+            assert np.array_equal(got[2].numpy()[safe] != 0, np.asarray(want[2])[safe] != 0), [T_, H_]
