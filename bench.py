@@ -319,7 +319,8 @@ def main():
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "traffic.json")
     if os.path.exists(tpath):
-        traffic = json.load(open(tpath)).get(dom_kernel)
+        rec = json.load(open(tpath)).get(dom_kernel)
+        traffic = rec["bytes_per_launch"] if rec else None
     roofline = {"bound": "hbm", "kernel": f"{dom_name}:{dom_kernel}", "achieved": round(achieved, 1), "peak": PEAK_HBM_GBPS,
                 "unit": "GB/s", "frac": round(achieved / PEAK_HBM_GBPS, 4), "traffic": traffic,
                 "launches": dom["launches"], "avg_launch_us": round(dom["seconds"] / dom["launches"] * 1e6, 2),
