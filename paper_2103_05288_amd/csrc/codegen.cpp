@@ -878,8 +878,13 @@ struct Gen {
     // the row-vector operands from their LDS copy
     const bool staged = !staged_accesses().empty();
     auto krow = [&](const std::string& name, int v, int nv) {
-      k(name, fmt("disc::row_reg_body<Pat, %d, %d>(A, rp);", v, nv), "RowPlan");
-      if (staged && v > 1) k(name + "_s", fmt("disc::row_reg_body<PatT<true>, %d, %d>(A, rp);", v, nv), "RowPlan", "PatT<true>");
+      // the two-slot version for blocks above 256 threads runs without the software pipeline: the
+      // registers it saves let a CU hold three 8-wavefront blocks instead of two (+10 % measured);
+      // with three slots the residency is the same either way and the pipeline wins
+      const char* pipe = max_threads > 256 && nv == 2 ? "false" : "true";
+      k(name, fmt("disc::row_reg_body<Pat, %d, %d, %s>(A, rp);", v, nv, pipe), "RowPlan");
+      if (staged && v > 1)
+        k(name + "_s", fmt("disc::row_reg_body<PatT<true>, %d, %d, %s>(A, rp);", v, nv, pipe), "RowPlan", "PatT<true>");
     };
     if (an.tmpl == DISC_TEMPLATE_LOOP) {
       k("k_loop_vec", fmt("disc::kloop_body<Pat, %d, 4, false>(A);", V), nullptr);

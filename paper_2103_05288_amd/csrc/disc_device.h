@@ -422,7 +422,7 @@ DISC_DEV void row_phases(const typename Pat::Args& A, const RowPlan& rp, typenam
   }
 }
 
-template <class Pat, int V, int NV>
+template <class Pat, int V, int NV, bool PIPE = true>
 DISC_DEV void row_reg_body(const typename Pat::Args& A, const RowPlan& rp) {
   __shared__ __attribute__((aligned(16))) char lds[2 * 16 * Pat::MAX_ACC_BYTES];
   // G <= 64: a power of two; G > 64: a multiple of 64
@@ -469,15 +469,17 @@ DISC_DEV void row_reg_body(const typename Pat::Args& A, const RowPlan& rp) {
   typename Pat::RowCtx rc{};
   typename Pat::template Slot<V> slot[NV];
   i64 rg = blockIdx.x;
-  if (rg < ngroups) {
+  auto load_row = [&]() {
     const i64 row = rg * rpb + grp < rows ? rg * rpb + grp : rows - 1;
     Pat::row_begin(A, row, rc);
     rc.sl = staged;
 #pragma unroll
     for (int j = 0; j < NV; ++j)
       if (nvalid[j] > 0) Pat::template load<V>(A, rc, col0 + j * rp.G * V, Span::upto(nvalid[j]), slot[j]);
-  }
+  };
+  if (PIPE && rg < ngroups) load_row();
   while (rg < ngroups) {
+    if constexpr (!PIPE) load_row();
     // the per-element tests of the spans are made here, once per row: carried around the loop
     // they would stop being lane masks in scalar registers
     Span span[NV];
@@ -493,7 +495,7 @@ DISC_DEV void row_reg_body(const typename Pat::Args& A, const RowPlan& rp) {
 #pragma unroll
     for (int j = 0; j < NV; ++j) nvalidn[j] = nvalid[j];
     auto prefetch = [&]() {
-      if (rgn < ngroups) {
+      if (PIPE && rgn < ngroups) {
         if (wpr > 1) {
           rot = rot + 64 < rp.G ? rot + 64 : 0;
           place(rot, col0n, nvalidn);
@@ -526,13 +528,18 @@ DISC_DEV void row_reg_body(const typename Pat::Args& A, const RowPlan& rp) {
     }
     if (active && lane == 0) Pat::row_store(A, row, rc);
     rg = rgn;
-    rc = rcn;
+    if constexpr (PIPE) {
+      rc = rcn;
 #pragma unroll
-    for (int j = 0; j < NV; ++j) slot[j] = nxt[j];
-    if (wpr > 1) {
-      col0 = col0n;
+      for (int j = 0; j < NV; ++j) slot[j] = nxt[j];
+      if (wpr > 1) {
+        col0 = col0n;
 #pragma unroll
-      for (int j = 0; j < NV; ++j) nvalid[j] = nvalidn[j];
+        for (int j = 0; j < NV; ++j) nvalid[j] = nvalidn[j];
+      }
+    } else if (wpr > 1) {
+      rot = rot + 64 < rp.G ? rot + 64 : 0;
+      place(rot, col0, nvalid);
     }
   }
 }
