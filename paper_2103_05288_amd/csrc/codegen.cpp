@@ -912,6 +912,9 @@ struct Gen {
       k("k_col_partial_vec", fmt("disc::col_partial_body<Pat, %d>(A, rp);", V), "ColPlan");
       k("k_col_partial_scalar", "disc::col_partial_body<Pat, 1>(A, rp);", "ColPlan");
       k("k_col_finish", "disc::col_finish_body<Pat>(A, rp);", "ColPlan");
+      const char* epi = has_elem_outputs() ? "PatE" : "void";
+      k("k_col_strip_vec", fmt("disc::col_strip_body<Pat, %s, %d>(A, rp);", epi, V), "ColPlan");
+      k("k_col_strip_scalar", fmt("disc::col_strip_body<Pat, %s, 1>(A, rp);", epi), "ColPlan");
       if (has_elem_outputs()) {
         k("k_col_epi_vec", fmt("disc::kloop_body<PatE, %d, 4, false>(A);", V), nullptr);
         k("k_col_epi_vec_i64", fmt("disc::kloop_body<PatE, %d, 1, true>(A);", V), nullptr);

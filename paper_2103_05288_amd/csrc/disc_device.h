@@ -626,6 +626,40 @@ struct ColPlan {
   i64 outer;
 };
 
+// V column accumulators of one lane over rows [m0 + ty, m1) with stride TY of outer slice o,
+// four rows in flight
+template <class Pat, int V>
+DISC_DEV void col_accumulate(const typename Pat::Args& A, i64 o, i64 col, int nvalid, i64 m0, i64 m1, int ty, int TY,
+                             typename Pat::template Acc<0> (&acc)[V]) {
+#pragma unroll
+  for (int e = 0; e < V; ++e) Pat::template acc_init<0>(acc[e]);
+  if (nvalid <= 0) return;
+  i64 m = m0 + ty;
+  for (; m + 3 * TY < m1; m += 4 * TY) {
+    typename Pat::template Slot<V> s[4];
+    typename Pat::RowCtx rc[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      Pat::row_begin(A, o * A.mid + m + u * TY, rc[u]);
+      Pat::template load<V>(A, rc[u], col, Span::upto(nvalid), s[u]);
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+#pragma unroll
+      for (int e = 0; e < V; ++e)
+        if (e < nvalid) Pat::template accum<0, V>(A, acc[e], s[u], e, (int)(m + u * TY), rc[u]);
+  }
+  for (; m < m1; m += TY) {
+    typename Pat::template Slot<V> s;
+    typename Pat::RowCtx rc;
+    Pat::row_begin(A, o * A.mid + m, rc);
+    Pat::template load<V>(A, rc, col, Span::upto(nvalid), s);
+#pragma unroll
+    for (int e = 0; e < V; ++e)
+      if (e < nvalid) Pat::template accum<0, V>(A, acc[e], s, e, (int)m, rc);
+  }
+}
+
 template <class Pat, int V>
 DISC_DEV void col_partial_body(const typename Pat::Args& A, const ColPlan& cp) {
   typedef typename Pat::template Acc<0> AccT;
@@ -641,34 +675,7 @@ DISC_DEV void col_partial_body(const typename Pat::Args& A, const ColPlan& cp) {
   const i64 m1 = m0 + cp.chunk_rows < A.mid ? m0 + cp.chunk_rows : A.mid;
   for (i64 o = blockIdx.z; o < cp.outer; o += gridDim.z) {
     AccT acc[V];
-#pragma unroll
-    for (int e = 0; e < V; ++e) Pat::template acc_init<0>(acc[e]);
-    if (nvalid > 0) {
-      i64 m = m0 + ty;
-      for (; m + 3 * TY < m1; m += 4 * TY) {
-        typename Pat::template Slot<V> s[4];
-        typename Pat::RowCtx rc[4];
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-          Pat::row_begin(A, o * A.mid + m + u * TY, rc[u]);
-          Pat::template load<V>(A, rc[u], col, Span::upto(nvalid), s[u]);
-        }
-#pragma unroll
-        for (int u = 0; u < 4; ++u)
-#pragma unroll
-          for (int e = 0; e < V; ++e)
-            if (e < nvalid) Pat::template accum<0, V>(A, acc[e], s[u], e, (int)(m + u * TY), rc[u]);
-      }
-      for (; m < m1; m += TY) {
-        typename Pat::template Slot<V> s;
-        typename Pat::RowCtx rc;
-        Pat::row_begin(A, o * A.mid + m, rc);
-        Pat::template load<V>(A, rc, col, Span::upto(nvalid), s);
-#pragma unroll
-        for (int e = 0; e < V; ++e)
-          if (e < nvalid) Pat::template accum<0, V>(A, acc[e], s, e, (int)m, rc);
-      }
-    }
+    col_accumulate<Pat, V>(A, o, col, nvalid, m0, m1, ty, TY, acc);
 #pragma unroll
     for (int e = 0; e < V; ++e) lds[(ty * cp.GC + tx) * V + e] = acc[e];
     __syncthreads();
@@ -679,6 +686,57 @@ DISC_DEV void col_partial_body(const typename Pat::Args& A, const ColPlan& cp) {
 #pragma unroll
       for (int e = 0; e < V; ++e)
         if (e < nvalid) Pat::acc_st(A, (o * cp.nchunk + chunk) * A.inner + col + e, acc[e]);
+    }
+    __syncthreads();
+  }
+}
+
+// Single-launch version for small problems, where three launches cost more than the work: a
+// block owns a strip of GC * V columns and ALL rows of it.  It reduces the strip (same lane
+// layout and fixed merge order as above), finishes its columns itself, and then -- when the
+// pattern has per-element outputs -- walks the strip a second time for the epilogue, reading the
+// tensor from cache and the reduce results it has just written (fence + barrier in between;
+// no other block reads them).  PatE = void: no epilogue.
+template <class Pat, class PatE, int V>
+DISC_DEV void col_strip_body(const typename Pat::Args& A, const ColPlan& cp) {
+  typedef typename Pat::template Acc<0> AccT;
+  __shared__ AccT lds[256 * V];
+  const int tx = threadIdx.x & (cp.GC - 1);
+  const int ty = threadIdx.x >> cp.log2GC;
+  const int TY = blockDim.x >> cp.log2GC;
+  const i64 col = ((i64)blockIdx.x * cp.GC + tx) * V;
+  const i64 rem = A.inner - col;
+  const int nvalid = rem <= 0 ? 0 : (rem < (i64)V ? (int)rem : V);
+  for (i64 o = blockIdx.y; o < cp.outer; o += gridDim.y) {
+    AccT acc[V];
+    col_accumulate<Pat, V>(A, o, col, nvalid, 0, A.mid, ty, TY, acc);
+#pragma unroll
+    for (int e = 0; e < V; ++e) lds[(ty * cp.GC + tx) * V + e] = acc[e];
+    __syncthreads();
+    if (ty == 0 && nvalid > 0) {
+      for (int t = 1; t < TY; ++t)
+#pragma unroll
+        for (int e = 0; e < V; ++e) Pat::template acc_merge<0>(acc[e], lds[(t * cp.GC + tx) * V + e]);
+#pragma unroll
+      for (int e = 0; e < V; ++e)
+        if (e < nvalid) Pat::col_finish(A, o, col + e, acc[e]);
+    }
+    if constexpr (!__is_same(PatE, void)) {
+      __threadfence();
+      __syncthreads();
+      if (nvalid > 0) {
+        const Span sp = Span::upto(nvalid);
+        for (i64 m = ty; m < A.mid; m += TY) {
+          typename PatE::RowCtx rc;
+          PatE::row_begin(A, o * A.mid + m, rc);
+          typename PatE::template Slot<V> slot;
+          PatE::template load<V>(A, rc, col, sp, slot);
+          typename PatE::template OutSlot<V> out;
+          typename PatE::template Keep<V> kp;
+          PatE::template epilogue<V, false>(A, rc, slot, kp, col, sp, out);
+          PatE::template store<V>(A, rc, col, sp, out);
+        }
+      }
     }
     __syncthreads();
   }

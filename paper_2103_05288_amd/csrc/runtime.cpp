@@ -398,11 +398,12 @@ int make_plan(disc_ctx* c, const Pattern& p, const int64_t* dims, int n_dims, in
     if (outer == 0 || inner == 0) return DISC_OK;
     if (mid == 0) return set_err(c, DISC_ERR_EMPTY_REDUCE, "reduction over an axis of size 0");
     if (mid >= (1ll << 31) - 1) return set_err(c, DISC_ERR_SHAPE, "reduced axis longer than 2^31");
-    int want_vec = -1;
+    int want_vec = -1, want_strip = -1;
     if (force >= 0) {
-      if (force != DISC_V_COL_3STAGE_VEC && force != DISC_V_COL_3STAGE_SCALAR)
+      if (force < DISC_V_COL_3STAGE_VEC || force > DISC_V_COL_STRIP_SCALAR)
         return set_err(c, DISC_ERR_INVALID_ARG, "forced version does not belong to a column-reduce pattern");
-      want_vec = force == DISC_V_COL_3STAGE_VEC;
+      want_vec = force == DISC_V_COL_3STAGE_VEC || force == DISC_V_COL_STRIP_VEC;
+      want_strip = force == DISC_V_COL_STRIP_VEC || force == DISC_V_COL_STRIP_SCALAR;
     }
     bool vec;
     {
@@ -412,6 +413,42 @@ int make_plan(disc_ctx* c, const Pattern& p, const int64_t* dims, int n_dims, in
     }
     const int v = vec ? V : 1;
     const int64_t spr = (inner + v - 1) / v;
+    // Small problems: one launch, a block per strip of columns (reduce, finish and epilogue in the
+    // same kernel).  Three launches cost ~12 us whatever the size; below about a million elements
+    // that is more than the work.
+    int64_t total;
+    const bool small = !mul_ovf(outer * mid, inner, &total) && total <= (1ll << 20);
+    const bool strip = want_strip >= 0 ? want_strip != 0 : small;
+    if (strip) {
+      // strips of >= 32 bytes per row keep the accesses coalesced; narrower strips = more blocks
+      int GC = 1;
+      while (GC < 64 && (GC * (vec ? 16 : 4) < 32 || spr / (GC * 2) >= 64)) GC *= 2;
+      GC = std::min<int>(GC, 1 << ilog2_ceil(std::min<int64_t>(spr, 64)));
+      const int64_t col_tiles = (spr + GC - 1) / GC;
+      DeviceColPlan cp{GC, ilog2_ceil(GC), 1, 0, mid, outer};
+      fp->aux[0] = 0;
+      fp->aux[1] = outer * inner * 8;
+      fp->ws_off[0] = 0;
+      fp->ws_off[1] = 0;
+      pub.workspace_bytes = (size_t)p.gen.n_red_planes * (size_t)fp->aux[1];
+      pub.variant = vec ? DISC_V_COL_STRIP_VEC : DISC_V_COL_STRIP_SCALAR;
+      pub.lanes_per_row = GC;
+      pub.vec_width = v;
+      pub.index_bits = 64;
+      LaunchRec& L0 = fp->launches[0];
+      L0.kernel = vec ? "k_col_strip_vec" : "k_col_strip_scalar";
+      L0.grid[0] = (uint32_t)col_tiles;
+      L0.grid[1] = (uint32_t)std::min<int64_t>(outer, 65535);
+      L0.plan_kind = 2;
+      L0.cp = cp;
+      pub.n_launches = 1;
+      for (int k2 = 0; k2 < 3; ++k2) pub.grid[0][k2] = L0.grid[k2];
+      pub.block[0][0] = L0.block;
+      pub.block[0][1] = pub.block[0][2] = 1;
+      pub.lds_bytes[0] = 0;
+      snprintf(pub.kernel[0], sizeof pub.kernel[0], "%s%s", p.gen.prefix.c_str(), L0.kernel);
+      return DISC_OK;
+    }
     int GC = 1 << ilog2_ceil(std::min<int64_t>(spr, 64));
     const int TY = 256 / GC;
     const int64_t col_tiles = (spr + GC - 1) / GC;

@@ -45,7 +45,7 @@ FORCED = {
     "C0": (["loop_vec", "loop_vec_i64", "loop_scalar", "loop_scalar_i64"], [[37, 768], [5, 13]]),
     "C1": (["row_reg_vec", "row_reg_scalar", "row_stream_vec", "row_stream_scalar"], [[2, 3, 77], [1, 2, 256]]),
     "C2": (["row_reg_vec", "row_reg_scalar", "row_stream_vec", "row_stream_scalar"], [[33, 768], [9, 1021]]),
-    "C3": (["col_3stage_vec", "col_3stage_scalar"], [[700, 1024], [129, 37]]),
+    "C3": (["col_3stage_vec", "col_3stage_scalar", "col_strip_vec", "col_strip_scalar"], [[700, 1024], [129, 37], [3, 1024]]),
     "C4": (["row_reg_vec", "row_reg_scalar", "row_stream_vec", "row_stream_scalar"], [[41, 1000], [7, 2040]]),
 }
 
@@ -168,7 +168,8 @@ def test_column_argmax_and_minmax(ctx):
         x = rng.normal(size=(T, C)).astype(np.float32)
         x[rng.integers(0, T, size=C), np.arange(C)] = 7.0
         x[rng.integers(0, T, size=C), np.arange(C)] = 7.0
-        compare(ctx, pat, [T, C], [torch.from_numpy(x)], "col argmax", handle=hd)
+        for v in (None, "col_3stage_vec", "col_strip_vec", "col_strip_scalar"):
+            compare(ctx, pat, [T, C], [torch.from_numpy(x)], "col argmax", force=v, handle=hd)
 
 
 # ---------------------------------------------------------------- generic patterns
@@ -219,7 +220,9 @@ def test_outer_sum_and_rank3_column_reduce(ctx):
     hd = ctx.register(pat)
     assert hd.info["template"] == "col_reduce"
     for B, T, C in ((1, 1, 1), (3, 50, 17), (2, 700, 256), (70, 9, 8)):
-        compare(ctx, pat, [B, T, C], [torch.randn(B, T, C, generator=g), torch.randn(C, generator=g)], "rank3 col", handle=hd)
+        ins = [torch.randn(B, T, C, generator=g), torch.randn(C, generator=g)]
+        for v in (None, "col_3stage_vec", "col_3stage_scalar", "col_strip_vec", "col_strip_scalar"):
+            compare(ctx, pat, [B, T, C], ins, "rank3 col", force=v, handle=hd)
 
 
 def test_row_outputs_and_logsumexp(ctx):
@@ -275,8 +278,14 @@ def test_launch_errors_and_stats(ctx):
     torch.cuda.synchronize()
     after = ctx.stats()
     assert after["launch_calls"] == before["launch_calls"] + 1
-    assert after["device_launches"] == before["device_launches"] + 3
+    assert after["device_launches"] == before["device_launches"] + 1      # small: the single-launch version
     assert after["compile_events"] == before["compile_events"]
+    big = [5000, 300]
+    ins_b = [t.cuda() for t in cfg.inputs(big, seed=2)]
+    h.launch(big, ins_b, alloc_outputs(pat, big, "cuda"),
+             workspace=torch.empty(ctx.workspace_bytes(h.id, big), dtype=torch.uint8, device="cuda"))
+    torch.cuda.synchronize()
+    assert ctx.stats()["device_launches"] == after["device_launches"] + 3   # partial, finish, epilogue
     # zero rows: success, nothing launched
     c0 = CONFIGS["C0"]
     p0 = c0.pattern()

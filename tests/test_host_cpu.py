@@ -280,8 +280,20 @@ def test_col_reduce_plan_and_workspace(ctx, handles):
     assert p["variant_name"] == "col_3stage_vec" and p["n_launches"] == 3 and p["mid"] == 65536
     assert p["workspace_bytes"] > 0 and ctx.workspace_bytes(h.id, [65536, 1024]) == p["workspace_bytes"]
     assert p["grid"][0][1] > 1                                    # the reduced axis is cut into chunks
-    assert h.plan([1, 1024])["grid"][0][1] == 1
+    assert h.plan([1, 1024], V["col_3stage_vec"])["grid"][0][1] == 1
     assert ctx.workspace_bytes(handles["C4"].id, [10, 10]) == 0
+    # up to about a million elements: one launch, a block per strip of columns; the workspace then
+    # holds the reduce results only
+    s = h.plan([512, 1024])
+    assert s["variant_name"] == "col_strip_vec" and s["n_launches"] == 1 and s["kernels"][0].endswith("k_col_strip_vec")
+    assert s["grid"][0][0] * s["lanes_per_row"] * s["vec_width"] >= 1024 and s["grid"][0][0] >= 32
+    assert 0 < s["workspace_bytes"] < p["workspace_bytes"]
+    assert h.plan([1025, 1024])["variant_name"] == "col_3stage_vec"
+    assert h.plan([7, 5])["variant_name"] == "col_strip_scalar"
+    forced = h.plan([300, 1024], V["col_3stage_scalar"])
+    assert forced["variant_name"] == "col_3stage_scalar" and forced["n_launches"] == 3
+    assert h.plan([70000, 1024], V["col_strip_vec"])["n_launches"] == 1
+    expect("INVALID_ARG", h.plan, [300, 1024], V["row_reg_vec"])
 
 
 def test_degenerate_shapes_and_errors(ctx, handles):
