@@ -157,6 +157,53 @@ def time_events(fn, stream=None):
     return a.elapsed_time(b) * 1e-3
 
 
+# Hot shapes for the gap-to-static comparison (Section 5.3 of the paper: shape-generic kernels reach
+# 85 % of static-shape ones on average): the same pattern registered shape-generic and compiled for
+# the one shape (extents and launch plan as compile-time constants, only that shape's kernel version).
+GAP_SHAPES = {
+    "C0": [[512, 768]],
+    "C1": [[8, 12, 384], [8, 12, 505]],
+    "C2": [[16384, 1024], [4096, 4096], [9000, 768]],
+    "C3": [[65536, 1024], [300, 1024]],
+    "C4": [[65536, 2048], [46773, 5739], [200000, 127], [16384, 8192]],
+}
+
+
+def gap_to_static(ctx, names, dev):
+    from workloads.configs import CONFIGS, TORCH_DTYPE, algorithmic_bytes
+    rows = []
+    for name in names:
+        cfg = CONFIGS[name]
+        pat = cfg.pattern()
+        generic = ctx.register(pat)                      # cache hit: registered by the sweep already
+        for dims in GAP_SHAPES.get(name, []):
+            ins = cfg.inputs(dims, seed=77, device=dev)
+            outs_g = [torch.empty(pat.shape_of(o, dims), dtype=TORCH_DTYPE[pat.ops[o].dtype], device=dev) for o in pat.outputs]
+            outs_s = [torch.empty_like(o) for o in outs_g]
+            ws = torch.empty(max(16, ctx.workspace_bytes(generic.id, dims)), dtype=torch.uint8, device=dev)
+            static = ctx.register_static(pat, dims)
+            cg = generic.bind(dims, ins, outs_g, workspace=ws)
+            cs = static.bind(dims, ins, outs_s, workspace=ws)
+
+            def rate(call):
+                call()
+                torch.cuda.synchronize()
+                t = min(time_events(lambda: [call() for _ in range(10)]) for _ in range(3)) / 10
+                return algorithmic_bytes(pat, dims) / t / 1e9
+            g, s = rate(cg), rate(cs)
+            diff = max(float((a.double() - b.double()).abs().max()) if a.numel() else 0.0 for a, b in zip(outs_g, outs_s))
+            rows.append({"cfg": name, "dims": dims, "generic_GBps": round(g, 1), "static_GBps": round(s, 1),
+                         "generic_over_static": round(g / s, 4), "static_compile_ms": round(static.info["compile_ms"], 1),
+                         "max_abs_diff_outputs": diff, "kernel": generic.plan(dims)["kernels"][0]})
+            del ins, outs_g, outs_s, ws
+    ratios = [r["generic_over_static"] for r in rows]
+    return {"shapes": rows, "mean_generic_over_static": round(float(np.mean(ratios)), 4) if ratios else None,
+            "min": min(ratios) if ratios else None, "max": max(ratios) if ratios else None,
+            "static_compiles": len(rows),
+            "note": "static = the same op list compiled for that one shape (a module per shape); generic = the one "
+                    "shape-generic module used by the whole sweep"}
+
+
 def cpu_baseline(sweeps, budget_s=20.0):
     """Oracle (as it stands) on a bounded sample of the sweep: calls in sweep order, smallest
     element counts first skipped none, until the time budget is used; row-independent patterns
@@ -218,6 +265,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--configs", default="C0,C1,C2,C3,C4")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-gap-to-static", action="store_true")
     ap.add_argument("--cpu-budget", type=float, default=20.0)
     ap.add_argument("--dump-calls", default="", help="write per-call dims / bytes / device time as JSON lines")
     args = ap.parse_args()
@@ -309,8 +357,18 @@ def main():
     torch.cuda.synchronize()
     t_empty = time_events(lambda: [ctx.util_empty_launch() for _ in range(1000)]) / 1000
     st = ctx.stats()
-    host_us = st["host_launch_ns"] / max(1, st["launch_calls"]) / 1e3
+    host_us = st["host_launch_ns"] / max(1, st["launch_calls"]) / 1e3     # includes waiting for queue space
     plan_us = st["host_plan_ns"] / max(1, st["launch_calls"]) / 1e3
+    # the same with an empty queue: a tiny call of the first sweep, synchronised every 32 launches
+    sw0 = sweeps[0]
+    small = min(range(len(sw0.calls)), key=lambda i: sw0.bytes[i])
+    s0 = ctx.stats()
+    for i in range(2048):
+        sw0.calls_bound[small]()
+        if i % 32 == 31:
+            torch.cuda.synchronize()
+    s1 = ctx.stats()
+    host_idle_us = (s1["host_launch_ns"] - s0["host_launch_ns"]) / 2048 / 1e3
 
     dom_name, dom_kernel, dom = dominant
     achieved = dom["bytes"] / dom["seconds"] / 1e9
@@ -339,11 +397,14 @@ def main():
         "roofline": roofline,
         "copy_ceiling_GBps": round(copy_gbps, 1),
         "empty_launch_us": round(t_empty * 1e6, 2),
-        "host_launch_us_per_call": round(host_us, 2), "host_plan_us_per_call": round(plan_us, 3),
+        "host_launch_us_per_call": round(host_idle_us, 2), "host_plan_us_per_call": round(plan_us, 3),
+        "host_launch_us_per_call_queue_full": round(host_us, 2),
         "kernels_compiled_per_pattern": {sw.name: per_cfg[sw.name]["compile_events"] for sw in sweeps},
         "per_config": per_cfg,
         "setup_s": round(setup_s, 1),
     }
+    if not args.no_gap_to_static:
+        out["gap_to_static"] = gap_to_static(ctx, names, dev)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(sweeps, args.cpu_budget)
     print(json.dumps(out))

@@ -197,6 +197,16 @@ const char* disc_last_error(const disc_ctx* ctx);
  * the same id without compiling (pattern cache keyed on the op sequence, never on sizes). */
 int disc_register_pattern(disc_ctx* ctx, const disc_op* ops, int n_ops, const disc_constraint* cs,
                           int n_cs, int32_t* pattern_id_out);
+/* The same pattern compiled for ONE shape, the way a static-shape compiler would (Section 1 and
+ * Section 5.3: the recompile-per-shape alternative, and the gap of the shape-generic kernels to
+ * it).  `dims` (host, n_dims values, copied) are planned with the same host rules as any launch;
+ * the module then holds only the kernel versions that plan launches, with every extent, stride,
+ * division constant and launch-plan member a compile-time constant.  The result is a pattern of
+ * its own (one per shape, cached on op sequence + constraints + dims): disc_plan / disc_launch
+ * with any other dims return DISC_ERR_SHAPE, forcing a version returns DISC_ERR_INVALID_ARG.
+ * disc_pattern_info(...).compile_ms is the per-shape compile cost. */
+int disc_register_pattern_static(disc_ctx* ctx, const disc_op* ops, int n_ops, const disc_constraint* cs,
+                                 int n_cs, const int64_t* dims, int n_dims, int32_t* pattern_id_out);
 int disc_pattern_info(disc_ctx* ctx, int32_t id, disc_pattern_info_t* out);
 /* Generated device source of the pattern (context-owned, valid until disc_destroy). */
 const char* disc_pattern_source(disc_ctx* ctx, int32_t id);

@@ -67,7 +67,8 @@ class DiscError(RuntimeError):
         self.message = message
 
 
-EXPORTS = ("disc_create", "disc_destroy", "disc_last_error", "disc_register_pattern", "disc_pattern_info",
+EXPORTS = ("disc_create", "disc_destroy", "disc_last_error", "disc_register_pattern", "disc_register_pattern_static",
+           "disc_pattern_info",
            "disc_pattern_source", "disc_workspace_bytes", "disc_plan", "disc_launch", "disc_force_variant",
            "disc_get_stats", "disc_util_copy", "disc_util_empty_launch")
 
@@ -95,6 +96,8 @@ def load_library():
     lib.disc_last_error.argtypes = [vp]
     lib.disc_last_error.restype = C.c_char_p
     lib.disc_register_pattern.argtypes = [vp, C.POINTER(disc_op), C.c_int, C.POINTER(disc_constraint), C.c_int, i32p]
+    lib.disc_register_pattern_static.argtypes = [vp, C.POINTER(disc_op), C.c_int, C.POINTER(disc_constraint), C.c_int,
+                                                 i64p, C.c_int, i32p]
     lib.disc_pattern_info.argtypes = [vp, C.c_int32, C.POINTER(disc_pattern_info_t)]
     lib.disc_pattern_source.argtypes = [vp, C.c_int32]
     lib.disc_pattern_source.restype = C.c_char_p
@@ -207,6 +210,14 @@ class Context:
         ops, n_ops, cs, n_cs = marshal_pattern(pattern)
         pid = C.c_int32(-1)
         self._check(self.lib.disc_register_pattern(self.h, ops, n_ops, cs, n_cs, C.byref(pid)))
+        return PatternHandle(self, pid.value)
+
+    def register_static(self, pattern, dims) -> PatternHandle:
+        """The pattern compiled for this one shape only (single-shape module)."""
+        ops, n_ops, cs, n_cs = marshal_pattern(pattern)
+        arr, n = self._dims(dims)
+        pid = C.c_int32(-1)
+        self._check(self.lib.disc_register_pattern_static(self.h, ops, n_ops, cs, n_cs, arr, n, C.byref(pid)))
         return PatternHandle(self, pid.value)
 
     def pattern_info(self, pid: int) -> dict:

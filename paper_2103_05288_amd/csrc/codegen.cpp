@@ -13,6 +13,7 @@
 //  * division by a per-row value becomes a multiplication by a reciprocal computed once per row;
 //    per-element transcendental ops use the hardware approximations (1 ulp exp2 / log2 / rcp /
 //    rsq), per-row and per-column scalar math stays IEEE-correct.
+#include <algorithm>
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
@@ -66,6 +67,7 @@ struct Gen {
   std::map<int, int> produced_phase;
   std::set<int> need_rinv;     // per-row values whose reciprocal is precomputed
   std::set<int> need_nl2e;     // per-row values r for which -r*log2(e) is precomputed (exp(x - r))
+  const GenOptions* opt = nullptr;
   explicit Gen(const Analysis& a) : an(a) {}
 
   static bool is_reduce(int oc) { return oc >= DISC_REDUCE_SUM && oc <= DISC_REDUCE_ARGMAX; }
@@ -869,9 +871,15 @@ struct Gen {
   void emit_kernels(Generated* out) {
     const int V = an.vec_width;
     int max_threads = 256;   // largest block the entry point may be launched with
+    // DISC_STATIC_ARGS / DISC_STATIC_PLAN expand to nothing in the shape-generic module; the
+    // single-shape module defines them to overwrite every extent with its constant
     auto k = [&](const std::string& name, const std::string& body, const char* plan, const char* pat = "Pat") {
+      if (opt && !opt->only_kernels.empty() &&
+          std::find(opt->only_kernels.begin(), opt->only_kernels.end(), name) == opt->only_kernels.end())
+        return;
       os << "extern \"C\" __global__ void __launch_bounds__(" << max_threads << ") " << out->prefix << name << "(" << pat
-         << "::Args A" << (plan ? std::string(", disc::") + plan + " rp" : std::string()) << ") { " << body << " }\n";
+         << "::Args A" << (plan ? std::string(", disc::") + plan + " rp" : std::string()) << ") { DISC_STATIC_ARGS(A) "
+         << (plan ? "DISC_STATIC_PLAN(rp) " : "") << body << " }\n";
       out->kernels.push_back(name);
     };
     // the wide register-resident row kernels come in a second version (suffix _s) that reads
@@ -988,6 +996,8 @@ struct Gen {
     emit_kernels(out);
     out->source = os.str();
     out->args = layout;
+    out->field_names.clear();
+    for (const auto& f : layout.fields) out->field_names.push_back(field_name(f));
     out->n_acc_cells = n_acc_cells;
     out->n_red_planes = col_tmpl() ? (int)an.reduces[0].size() : 0;
     out->has_epilogue = col_tmpl() ? has_elem_outputs() : true;
@@ -999,9 +1009,10 @@ struct Gen {
 
 }  // namespace
 
-int generate(const Analysis& an, const std::string& prefix, Generated* out, std::string* err) {
+int generate(const Analysis& an, const std::string& prefix, Generated* out, std::string* err, const GenOptions* opt) {
   out->prefix = prefix;
   Gen g(an);
+  g.opt = opt;
   return g.run(out, err);
 }
 

@@ -33,6 +33,13 @@
 //   NPHASE, MAX_ACC_BYTES
 #pragma once
 
+// A module specialised for one shape defines these before this header: they assign the shape's
+// constants to the by-value kernel arguments, and the compiler folds them through the kernel.
+#ifndef DISC_STATIC_ARGS
+#define DISC_STATIC_ARGS(A)
+#define DISC_STATIC_PLAN(rp)
+#endif
+
 namespace disc {
 
 typedef unsigned char u8;

@@ -163,6 +163,12 @@ struct Generated {
   int n_red_planes = 0;               // column reduce: reduce-result planes in the workspace
   bool has_epilogue = true;           // column reduce: some output keeps the reduced axis
   std::vector<int> staged_elem_bytes; // row reduce: element size of each row vector that can be staged in LDS
+  std::vector<std::string> field_names;   // member name of each args.fields entry in Pat::Args
+};
+
+// Optional restriction of the generated module: only the named entry points (without prefix).
+struct GenOptions {
+  std::vector<std::string> only_kernels;
 };
 
 // checker.cpp: validate, close constraints, decide fusion, resolve contexts, collapse.
@@ -170,6 +176,7 @@ int analyze(const disc_op* ops, int n_ops, const disc_constraint* cs, int n_cs, 
             std::string* err);
 
 // codegen.cpp
-int generate(const Analysis& an, const std::string& prefix, Generated* out, std::string* err);
+int generate(const Analysis& an, const std::string& prefix, Generated* out, std::string* err,
+             const GenOptions* opt = nullptr);
 
 }  // namespace disc

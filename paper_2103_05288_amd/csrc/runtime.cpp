@@ -53,6 +53,8 @@ struct Pattern {
   hipModule_t module = nullptr;
   std::map<std::string, hipFunction_t> fn;
   mutable std::map<std::string, int> resident;        // (kernel, block, LDS) -> blocks resident per CU
+  bool is_static = false;                             // module specialised for static_dims only
+  std::vector<int64_t> static_dims;
   // constraint recipes
   std::vector<std::pair<int, int>> eq_checks;         // symbolic dims that must be equal
   std::vector<std::pair<int, int64_t>> static_checks; // symbolic dim that must equal a static size
@@ -272,6 +274,11 @@ int make_plan(disc_ctx* c, const Pattern& p, const int64_t* dims, int n_dims, in
               void* const* outputs, FullPlan* fp) {
   (void)inputs;    // pointer values are available to the selection; nothing depends on alignment at present:
   (void)outputs;   // wide accesses need element alignment only
+  if (p.is_static) {
+    if (force >= 0) return set_err(c, DISC_ERR_INVALID_ARG, "a single-shape pattern has one kernel version");
+    if (n_dims != (int)p.static_dims.size() || !std::equal(dims, dims + n_dims, p.static_dims.begin()))
+      return set_err(c, DISC_ERR_SHAPE, "pattern was compiled for one shape and is launched with another");
+  }
   int rc = shape_calc(c, p, dims, n_dims, &fp->sv);
   if (rc) return rc;
   const Analysis& an = p.an;
@@ -617,8 +624,54 @@ void disc_destroy(disc_ctx* ctx) {
 
 const char* disc_last_error(const disc_ctx* ctx) { return ctx ? ctx->err.c_str() : "null context"; }
 
-int disc_register_pattern(disc_ctx* ctx, const disc_op* ops, int n_ops, const disc_constraint* cs, int n_cs,
-                          int32_t* pattern_id_out) {
+// Text of the DISC_STATIC_ARGS / DISC_STATIC_PLAN macros for one shape: every non-pointer member
+// of the argument block and of the launch-plan struct becomes an assignment of its constant.
+static std::string static_macros(const Pattern& p, const FullPlan& fp, const int64_t* dims) {
+  alignas(16) unsigned char buf[4096 + 32] = {0};
+  std::vector<const void*> in(std::max(1, p.an.n_inputs), nullptr);
+  std::vector<void*> outp(std::max(1, p.an.n_outputs), nullptr);
+  fill_args(p, fp, dims, in.data(), outp.data(), nullptr, buf);
+  std::ostringstream a;
+  a << "#define DISC_STATIC_ARGS(A)";
+  for (size_t i = 0; i < p.gen.args.fields.size(); ++i) {
+    const ArgField& f = p.gen.args.fields[i];
+    const std::string& n = p.gen.field_names[i];
+    const unsigned char* src = buf + f.offset;
+    switch (f.kind) {
+      case ArgField::IN_PTR: case ArgField::OUT_PTR: case ArgField::WS_PTR: break;
+      case ArgField::SPR_DIV: case ArgField::GROUP_DIV: {
+        uint32_t w[4];
+        memcpy(w, src, 16);
+        a << " A." << n << " = disc::FastDiv{" << w[0] << "u, " << w[1] << "u, " << w[2] << "u, 0u};";
+        break;
+      }
+      case ArgField::DIMF: {
+        uint32_t w;
+        memcpy(&w, src, 4);
+        a << " A." << n << " = __builtin_bit_cast(float, " << w << "u);";
+        break;
+      }
+      default: {
+        int64_t v;
+        memcpy(&v, src, 8);
+        a << " A." << n << " = " << v << "LL;";
+      }
+    }
+  }
+  a << "\n#define DISC_STATIC_PLAN(rp)";
+  const LaunchRec& L = fp.launches[0];
+  if (L.plan_kind == 1)
+    a << " rp.G = " << L.rp.G << "; rp.log2G = " << L.rp.log2G << "; rp.nv = " << L.rp.nv << "; rp.flags = " << L.rp.pad
+      << "; rp.rpb = " << L.rp.rpb << ";";
+  else if (L.plan_kind == 2)
+    a << " rp.GC = " << L.cp.GC << "; rp.log2GC = " << L.cp.log2GC << "; rp.nchunk = " << L.cp.nchunk << "; rp.chunk_rows = "
+      << L.cp.chunk_rows << "LL; rp.outer = " << L.cp.outer << "LL;";
+  a << "\n";
+  return a.str();
+}
+
+static int register_impl(disc_ctx* ctx, const disc_op* ops, int n_ops, const disc_constraint* cs, int n_cs,
+                         const int64_t* static_dims, int n_static_dims, int32_t* pattern_id_out) {
   if (!ctx) return DISC_ERR_INVALID_ARG;
   if (!pattern_id_out) return set_err(ctx, DISC_ERR_INVALID_ARG, "pattern_id_out is null");
   *pattern_id_out = -1;
@@ -644,6 +697,10 @@ int disc_register_pattern(disc_ctx* ctx, const disc_op* ops, int n_ops, const di
   }
   key.append("|");
   for (int i = 0; i < n_cs; ++i) key.append(reinterpret_cast<const char*>(&cs[i]), sizeof(disc_constraint));
+  if (static_dims) {   // a single-shape module is a pattern of its own, one per shape
+    key.append("|static");
+    key.append(reinterpret_cast<const char*>(static_dims), sizeof(int64_t) * (size_t)n_static_dims);
+  }
   auto hit = ctx->cache.find(key);
   if (hit != ctx->cache.end()) {
     *pattern_id_out = hit->second;
@@ -656,7 +713,8 @@ int disc_register_pattern(disc_ctx* ctx, const disc_op* ops, int n_ops, const di
   std::string err;
   int rc = analyze(ops, n_ops, cs, n_cs, &p->an, &err);
   if (rc) return set_err(ctx, rc, err);
-  rc = generate(p->an, "disc_p" + std::to_string(ctx->patterns.size()) + "_", &p->gen, &err);
+  const std::string prefix = "disc_p" + std::to_string(ctx->patterns.size()) + "_";
+  rc = generate(p->an, prefix, &p->gen, &err);
   if (rc) return set_err(ctx, rc, err);
   p->gen.source = std::string(kDeviceHeader) + "\n" + p->gen.source;
 
@@ -685,6 +743,24 @@ int disc_register_pattern(disc_ctx* ctx, const disc_op* ops, int n_ops, const di
     p->io_numel.push_back({prod, dtype_bytes(op.dtype)});
   }
 
+  if (static_dims) {
+    // plan the one shape with the generic rules, then regenerate the module with only the kernel
+    // versions that plan launches and with every extent and plan member as a constant
+    FullPlan fp;
+    rc = make_plan(ctx, *p, static_dims, n_static_dims, -1, nullptr, nullptr, &fp);
+    if (rc) return rc;
+    GenOptions opt;
+    for (int l = 0; l < fp.pub.n_launches; ++l) opt.only_kernels.push_back(fp.launches[l].kernel);
+    if (opt.only_kernels.empty()) return set_err(ctx, DISC_ERR_SHAPE, "a single-shape pattern needs a shape that launches something");
+    const std::string macros = static_macros(*p, fp, static_dims);
+    Generated g2;
+    rc = generate(p->an, prefix, &g2, &err, &opt);
+    if (rc) return set_err(ctx, rc, err);
+    g2.source = macros + std::string(kDeviceHeader) + "\n" + g2.source;
+    p->gen = g2;
+    p->is_static = true;
+    p->static_dims.assign(static_dims, static_dims + n_static_dims);
+  }
   std::vector<char> code;
   rc = compile_source(ctx, p->gen.source, &code, &p->compile_ms);
   p->compile_events = 1;
@@ -706,6 +782,18 @@ int disc_register_pattern(disc_ctx* ctx, const disc_op* ops, int n_ops, const di
   ctx->stats.patterns_registered++;
   *pattern_id_out = id;
   return DISC_OK;
+}
+
+int disc_register_pattern(disc_ctx* ctx, const disc_op* ops, int n_ops, const disc_constraint* cs, int n_cs,
+                          int32_t* pattern_id_out) {
+  return register_impl(ctx, ops, n_ops, cs, n_cs, nullptr, 0, pattern_id_out);
+}
+
+int disc_register_pattern_static(disc_ctx* ctx, const disc_op* ops, int n_ops, const disc_constraint* cs, int n_cs,
+                                 const int64_t* dims, int n_dims, int32_t* pattern_id_out) {
+  if (!ctx) return DISC_ERR_INVALID_ARG;
+  if (!dims || n_dims <= 0) return set_err(ctx, DISC_ERR_INVALID_ARG, "a single-shape pattern needs its dims");
+  return register_impl(ctx, ops, n_ops, cs, n_cs, dims, n_dims, pattern_id_out);
 }
 
 int disc_pattern_info(disc_ctx* ctx, int32_t id, disc_pattern_info_t* out) {

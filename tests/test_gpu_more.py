@@ -303,3 +303,27 @@ def test_util_kernels(ctx):
     ctx.util_empty_launch()
     torch.cuda.synchronize()
     assert torch.equal(src, dst)
+
+
+# ---------------------------------------------------------------- single-shape modules (gap-to-static comparison)
+@pytest.mark.parametrize("cfg_name,dims", [
+    ("C0", [37, 768]), ("C1", [2, 3, 77]), ("C2", [33, 1021]), ("C2", [700, 4096]), ("C3", [700, 1024]), ("C3", [5000, 300]),
+    ("C4", [41, 1000]), ("C4", [300, 5739]), ("C4", [5, 12289]), ("C4", [3, 30000]),
+])
+def test_single_shape_module_matches_oracle_and_generic(ctx, cfg_name, dims):
+    cfg = CONFIGS[cfg_name]
+    pat = cfg.pattern()
+    ins = cfg.inputs(dims, seed=9)
+    hs = ctx.register_static(pat, dims)
+    got = run_gpu(hs, pat, dims, ins)
+    want = oracle_run(pat, dims, [to_oracle_input(t) for t in ins])[0]
+    for k, (g, w) in enumerate(zip(got, want)):
+        assert_close(g, w, f"static {cfg_name} dims={dims} out{k}")
+    # (not compared bit for bit with the shape-generic module: the two may run with different grids,
+    # and rows of several wavefronts are summed in an order that depends on the block's row count)
+    from paper_2103_05288_amd import DiscError
+    with pytest.raises(DiscError) as e:
+        other = list(dims)
+        other[0] += 1
+        run_gpu(hs, pat, other, cfg.inputs(other, seed=9))
+    assert e.value.status == "SHAPE"

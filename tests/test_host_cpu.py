@@ -258,6 +258,42 @@ def test_row_schedule_capacity_steps(handles):
     assert p["slots_per_lane"] <= 2 and not p["kernels"][0].endswith("_s")
 
 
+def test_single_shape_registration(ctx, handles):
+    """The same op list compiled for one shape: a pattern of its own per shape, only that shape's kernel
+    versions in the module, its extents and launch plan as constants; other dims are refused."""
+    pat = CONFIGS["C4"].pattern()
+    before = ctx.stats()
+    a = ctx.register_static(pat, [300, 2048])
+    b = ctx.register_static(pat, [300, 2049])
+    again = ctx.register_static(pat, [300, 2048])
+    after = ctx.stats()
+    assert a.id != b.id and again.id == a.id and a.id != handles["C4"].id
+    assert after["compile_events"] == before["compile_events"] + 2 and after["pattern_cache_hits"] == before["pattern_cache_hits"] + 1
+    assert a.info["compile_events"] == 1 and a.info["n_variants"] == 1 and a.info["compile_ms"] > 0
+    generic = handles["C4"].plan([300, 2048])
+    pa = a.plan([300, 2048])
+    for k in ("variant_name", "lanes_per_row", "slots_per_lane", "vec_width", "block", "lds_bytes", "algorithmic_bytes"):
+        assert pa[k] == generic[k], k
+    assert pa["kernels"][0].split("_k_")[1] == generic["kernels"][0].split("_k_")[1]
+    src = a.source
+    assert "A.inner = 2048LL;" in src and "A.rows = 300LL;" in src and "rp.G = 128;" in src
+    assert src.count('extern "C" __global__') == 1
+    assert "A.inner = 2049LL;" in b.source
+    expect("SHAPE", a.plan, [300, 2049])
+    expect("SHAPE", a.plan, [301, 2048])
+    expect("INVALID_ARG", a.plan, [300, 2048], V["row_reg_scalar"])
+    # a column reduce keeps its three entry points; a small one its single strip kernel
+    c3 = CONFIGS["C3"].pattern()
+    big = ctx.register_static(c3, [5000, 1024])
+    small = ctx.register_static(c3, [100, 1024])
+    assert big.info["n_variants"] == 3 and small.info["n_variants"] == 1
+    assert "rp.nchunk = " in big.source and "A.mid = 5000LL;" in big.source
+    # nothing to launch, nothing to specialise
+    expect("SHAPE", ctx.register_static, pat, [0, 64])
+    expect("INVALID_ARG", ctx.register_static, pat, [])
+    expect("INVALID_ARG", ctx.register_static, pat, [1, 2, 3])
+
+
 def test_loop_and_index_width_selection(ctx, handles):
     h = handles["C0"]
     p = h.plan([300, 768])
