@@ -82,20 +82,18 @@ struct Vec<T, N, true> {
 };
 
 // The first n elements of a slot belong to the row (n = N everywhere but at the end of a row).
-// The per-element tests are evaluated once, where the span is made, so that every reduction
-// phase and the epilogue of a ragged slot reuse them instead of comparing again.
+// The per-element test e < n is made where it is used: keeping the 8 or 16 lane masks of every
+// slot alive across the phases was measured slower -- they do not fit the scalar registers next
+// to the kernel arguments and were spilled to vector-register lanes on every path.
 struct Span {
   int n;
-  bool ok[16];
   static DISC_DEV Span upto(int n) {
     Span s;
     s.n = n;
-#pragma unroll
-    for (int e = 0; e < 16; ++e) s.ok[e] = e < n;
     return s;
   }
   DISC_DEV bool full(int N) const { return n >= N; }
-  DISC_DEV bool has(int e) const { return ok[e]; }
+  DISC_DEV bool has(int e) const { return e < n; }
   DISC_DEV bool any() const { return n > 0; }
 };
 
@@ -487,8 +485,6 @@ DISC_DEV void row_reg_body(const typename Pat::Args& A, const RowPlan& rp) {
   if (PIPE && rg < ngroups) load_row();
   while (rg < ngroups) {
     if constexpr (!PIPE) load_row();
-    // the per-element tests of the spans are made here, once per row: carried around the loop
-    // they would stop being lane masks in scalar registers
     Span span[NV];
 #pragma unroll
     for (int j = 0; j < NV; ++j) span[j] = Span::upto(nvalid[j]);
