@@ -160,7 +160,8 @@ typedef struct {
   int32_t n_launches;       /* device launches this call makes (0 when an output is empty)     */
   int32_t index_bits;       /* 32 or 64                                                        */
   int32_t vec_width;        /* elements per access of the chosen version                       */
-  int32_t lanes_per_row;    /* row reduce: lanes that own one row (1..256), else 0             */
+  int32_t lanes_per_row;    /* row reduce: lanes that own one row (1..1024); column reduce:
+                               lanes along the columns per block; else 0                       */
   int32_t slots_per_lane;   /* row reduce: vector slots held per lane, else unroll factor      */
   int32_t reg_slots;        /* compile-time slot capacity of the chosen instantiation          */
   uint32_t grid[3][3];      /* per launch                                                      */

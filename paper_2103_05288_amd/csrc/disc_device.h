@@ -6,7 +6,8 @@
 // lanes, how data moves through registers / LDS, how reductions are combined.  The
 // schedules never see a shape as a compile-time constant; every extent arrives in the
 // kernel-argument block that the host fills at launch (the paper's host-side shape
-// calculation and launch-dimension selection, Sections 4.2.1 and 4.3).
+// calculation and launch-dimension selection, Sections 4.2.1 and 4.3).  (The one exception is
+// the single-shape module built for the gap-to-static comparison, see DISC_STATIC_ARGS.)
 //
 // The two templates of Section 4.3 ("classical loop fusion and input fusion with reduce
 // operation as the root") are kloop_kernel and the row_* / col_* kernels; each exists in
