@@ -381,9 +381,13 @@ struct Gen {
     std::ostringstream o;
     for (size_t i = 0; i < an.accesses.size(); ++i) {
       const Access& a = an.accesses[i];
-      if (a.has_inner && (a.kind == ACC_FULL || a.kind == ACC_PARTIAL)) o << "    disc::i64 b" << i << ";\n";
+      if (a.has_inner && a.kind == ACC_PARTIAL) o << "    disc::i64 b" << i << ";\n";
       if (!a.has_inner && a.is_output && a.kind == ACC_PARTIAL) o << "    disc::i64 b" << i << ";\n";
     }
+    // full-size operands: element offset of the row = sb + lb.  sb is the offset of the first row
+    // of the wavefront (uniform when the caller passes a uniform base row, so it lives in scalar
+    // registers and the accesses use scalar base + 32-bit lane offset), lb the lane's share.
+    o << "    disc::i64 sb;\n    int lb;\n    bool tail_ok;\n";
     for (size_t i = 0; i < an.nodes.size(); ++i) {
       const Node& n = an.nodes[i];
       const bool perrow_param = n.opcode == DISC_PARAM && !an.accesses[n.access].has_inner;
@@ -413,7 +417,16 @@ struct Gen {
   }
 
   void emit_row_begin() {
-    os << "  static DISC_DEV void row_begin(const Args& A, disc::i64 row, RowCtx& rc) {\n";
+    os << "  static DISC_DEV void row_begin(const Args& A, disc::i64 row, RowCtx& rc) { row_begin2(A, row, 0, rc); }\n";
+    os << "  static DISC_DEV void row_begin2(const Args& A, disc::i64 row_base, int row_delta, RowCtx& rc) {"
+          " row_begin3(A, row_base, row_delta, row_base * A.inner, rc); }\n";
+    // row = row_base + row_delta; base_off = row_base * inner, handed in by callers that keep it running
+    os << "  static DISC_DEV void row_begin3(const Args& A, disc::i64 row_base, int row_delta, disc::i64 base_off, RowCtx& rc) {\n";
+    os << "    const disc::i64 row = row_base + row_delta;\n";
+    // tail_ok: a ragged slot of this row may read its whole vector, because the rows after it hold
+    // the surplus elements (at most 15; one more row does when rows are that long, 16 rows always do)
+    os << "    rc.sb = base_off;\n    rc.lb = row_delta * (int)A.inner;\n"
+       << "    rc.tail_ok = A.rows - 1 - row >= (A.inner >= 15 ? 1 : 16);\n";
     const int n_outer = an.inner_group;
     const bool decomp = an.needs_decomp || (col_tmpl() && an.mid_group == 1);
     if (decomp) {
@@ -439,8 +452,6 @@ struct Gen {
         }
         if (a.has_inner || a.is_output) os << "    rc.b" << i << " = " << e << ";\n";
         else os << "    const disc::i64 pb" << i << " = " << e << ";\n";
-      } else if (a.kind == ACC_FULL && a.has_inner) {
-        os << "    rc.b" << i << " = row * A.inner;\n";
       }
     }
     Fn fn(*this, M_ROWLOCAL);
@@ -508,8 +519,13 @@ struct Gen {
     os << "    int unused_;\n  };\n";
   }
 
+  // pointer and element offset of slot `col` of an access that spans the inner group
+  std::string elem_ptr(const Access& a, const std::string& p) {
+    return a.kind == ACC_FULL ? "(" + p + " + rc.sb)" : p;
+  }
   std::string elem_base(const Access& a, size_t i) {
     if (a.kind == ACC_ROWVEC) return "col";
+    if (a.kind == ACC_FULL) return "disc::off(rc.lb, col)";
     return fmt("rc.b%zu + col", i);
   }
 
@@ -518,8 +534,8 @@ struct Gen {
     for (size_t i = 0; i < an.accesses.size(); ++i) {
       const Access& a = an.accesses[i];
       if (a.is_output || !a.has_inner || !need[i] || late(a)) continue;
-      os << "    disc::ld(s.a" << i << ", A.p" << a.slot << ", " << elem_base(a, i) << ", sp"
-         << (a.kind == ACC_FULL ? fmt(", rc.b%zu + col + V <= A.rows * A.inner", i) : std::string()) << ");\n";
+      os << "    disc::ld(s.a" << i << ", " << elem_ptr(a, fmt("A.p%d", a.slot)) << ", " << elem_base(a, i) << ", sp"
+         << (a.kind == ACC_FULL ? std::string(", rc.tail_ok") : std::string()) << ");\n";
     }
     if (with_red) {
       int k = 0;
@@ -535,7 +551,7 @@ struct Gen {
     for (size_t i = 0; i < an.accesses.size(); ++i) {
       const Access& a = an.accesses[i];
       if (!a.is_output || !elem_output(a)) continue;
-      os << "    disc::st(A.o" << a.slot << ", " << elem_base(a, i) << ", o.o" << a.slot << ", sp);\n";
+      os << "    disc::st(" << elem_ptr(a, fmt("A.o%d", a.slot)) << ", " << elem_base(a, i) << ", o.o" << a.slot << ", sp);\n";
     }
     os << "    (void)A; (void)rc; (void)col; (void)sp; (void)o;\n  }\n";
   }
@@ -677,9 +693,9 @@ struct Gen {
         // a compile-time choice: behind a run-time branch the wait for the operand would cover both
         // the LDS and the global counter, and so also the row loads that are in flight for later
         o << ind << "if constexpr (STAGED) disc::ld_lds(l" << ai << ", rc.sl, stage_offset<V>(A, " << st << "), (int)col);\n";
-        o << ind << "else disc::ld(l" << ai << ", A.p" << a.slot << ", " << elem_base(a, ai) << ", sp);\n";
+        o << ind << "else disc::ld(l" << ai << ", " << elem_ptr(a, fmt("A.p%d", a.slot)) << ", " << elem_base(a, ai) << ", sp);\n";
       } else {
-        o << ind << "disc::ld(l" << ai << ", A.p" << a.slot << ", " << elem_base(a, ai) << ", sp);\n";
+        o << ind << "disc::ld(l" << ai << ", " << elem_ptr(a, fmt("A.p%d", a.slot)) << ", " << elem_base(a, ai) << ", sp);\n";
       }
     }
   }

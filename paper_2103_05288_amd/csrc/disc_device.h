@@ -98,6 +98,12 @@ struct Span {
   DISC_DEV bool any() const { return n > 0; }
 };
 
+// Element offset of a slot inside the rows of one wavefront: 32-bit and unsigned when the column
+// index is (so the access can use a scalar base register plus a 32-bit lane offset), 64-bit when
+// the caller indexes columns with 64 bits.
+DISC_DEV unsigned off(int lane_base, int col) { return (unsigned)(lane_base + col); }
+DISC_DEV i64 off(int lane_base, i64 col) { return lane_base + col; }
+
 // A ragged slot (n < N elements) moves as the power-of-two pieces of n's binary expansion: the
 // piece of width W covers [(q-1)W, qW) when n / W == q is odd.  Every lane of a launch has the
 // same ragged length, so a wavefront issues at most log2(N) narrow accesses per ragged slot.
@@ -135,10 +141,24 @@ DISC_DEV void st_pieces(T* __restrict__ p, I off, const Vec<T, N>& s, int n) {
 // row (the rest are the tail of the previous / head of the next row).  Then the wide load is
 // still taken and the caller ignores the surplus elements; only a slot that would leave the
 // tensor is read element by element.  This keeps ragged rows on the wide-load path.
+// address of element `off` of p; a 32-bit unsigned offset is scaled in 32 bits, so that the
+// address is base + zero-extended byte offset -- the form that takes a scalar base register
+template <class T, class I>
+DISC_DEV const T* at(const T* p, I off) {
+  if constexpr (__is_same(I, unsigned))
+    return reinterpret_cast<const T*>(reinterpret_cast<const char*>(p) + (unsigned)(off * (unsigned)sizeof(T)));
+  else
+    return p + off;
+}
+template <class T, class I>
+DISC_DEV T* at(T* p, I off) {
+  return const_cast<T*>(at(const_cast<const T*>(p), off));
+}
+
 template <class T, int N, class I>
 DISC_DEV void ld(Vec<T, N>& d, const T* __restrict__ p, I off, Span sp, bool whole_ok = false) {
   if (sp.full(N) || whole_ok) {
-    d.v = *reinterpret_cast<const typename Vec<T, N>::unaligned_t*>(p + off);
+    d.v = *reinterpret_cast<const typename Vec<T, N>::unaligned_t*>(at(p, off));
   } else {
     d.clear();
     ld_pieces<N / 2>(d, p, off, sp.n);
@@ -153,7 +173,7 @@ DISC_DEV void ld(Vec<T, N>& d, const T* __restrict__ p, I off, Span sp, bool who
 template <class T, int N, class I>
 DISC_DEV void st(T* __restrict__ p, I off, const Vec<T, N>& s, Span sp) {
   if (sp.full(N)) {
-    *reinterpret_cast<typename Vec<T, N>::unaligned_t*>(p + off) = s.v;
+    *reinterpret_cast<typename Vec<T, N>::unaligned_t*>(at(p, off)) = s.v;
   } else {
     st_pieces<N / 2>(p, off, s, sp.n);
   }
@@ -475,9 +495,29 @@ DISC_DEV void row_reg_body(const typename Pat::Args& A, const RowPlan& rp) {
   typename Pat::RowCtx rc{};
   typename Pat::template Slot<V> slot[NV];
   i64 rg = blockIdx.x;
+  // Row bookkeeping in scalar registers: rw = row of the first lane group of this wavefront in
+  // the current row group, sbw = its element offset; both advance by a constant per iteration
+  // (no 64-bit products in the loop).  A lane's row is rw + dgrp.
+  const int grp_w = __builtin_amdgcn_readfirstlane(grp);
+  const int dgrp = grp - grp_w;
+  const i64 rstep = (i64)gridDim.x * rpb;
+  const i64 sbstep = rstep * A.inner;
+  i64 rw = rg * rpb + grp_w;
+  i64 sbw = rw * A.inner;
+  // rows past the end (last row group only) are replaced by the last row; their lanes compute
+  // along and store nothing
+  auto begin_row = [&](i64 rwv, i64 sbv, typename Pat::RowCtx& c) {
+    if (rwv + (rpb - grp_w) <= rows) {
+      Pat::row_begin3(A, rwv, dgrp, sbv, c);
+    } else {
+      const i64 last = rows - 1;
+      const i64 b = rwv < last ? rwv : last;
+      const i64 r = rwv + dgrp < last ? rwv + dgrp : last;
+      Pat::row_begin3(A, b, (int)(r - b), b * A.inner, c);
+    }
+  };
   auto load_row = [&]() {
-    const i64 row = rg * rpb + grp < rows ? rg * rpb + grp : rows - 1;
-    Pat::row_begin(A, row, rc);
+    begin_row(rw, sbw, rc);
     rc.sl = staged;
 #pragma unroll
     for (int j = 0; j < NV; ++j)
@@ -489,7 +529,7 @@ DISC_DEV void row_reg_body(const typename Pat::Args& A, const RowPlan& rp) {
     Span span[NV];
 #pragma unroll
     for (int j = 0; j < NV; ++j) span[j] = Span::upto(nvalid[j]);
-    const i64 row = rg * rpb + grp;
+    const i64 row = rw + dgrp;
     const bool active = row < rows;
     const i64 rgn = rg + gridDim.x;
     typename Pat::RowCtx rcn{};
@@ -504,8 +544,7 @@ DISC_DEV void row_reg_body(const typename Pat::Args& A, const RowPlan& rp) {
           rot = rot + 64 < rp.G ? rot + 64 : 0;
           place(rot, col0n, nvalidn);
         }
-        const i64 rown = rgn * rpb + grp < rows ? rgn * rpb + grp : rows - 1;
-        Pat::row_begin(A, rown, rcn);
+        begin_row(rw + rstep, sbw + sbstep, rcn);
         rcn.sl = staged;
 #pragma unroll
         for (int j = 0; j < NV; ++j)
@@ -532,6 +571,8 @@ DISC_DEV void row_reg_body(const typename Pat::Args& A, const RowPlan& rp) {
     }
     if (active && lane == 0) Pat::row_store(A, row, rc);
     rg = rgn;
+    rw += rstep;
+    sbw += sbstep;
     if constexpr (PIPE) {
       rc = rcn;
 #pragma unroll

@@ -385,13 +385,16 @@ int make_plan(disc_ctx* c, const Pattern& p, const int64_t* dims, int n_dims, in
         L.kernel = names[(((vec ? 0 : 1) * 3 + (inst - 1)) * 2 + (block > 256 ? 1 : 0)) * 2 + (stage ? 1 : 0)].c_str();
       }
       // grid-stride over row groups: a small whole number of rounds of the blocks the chip holds
-      // at once.  Measured: blocks of one wavefront-quad do best with three rounds (the hardware
-      // does not fill every CU to the computed residency in the first round; later blocks even
-      // that out), the wide blocks with one (each new block pays an unpipelined first row)
+      // at once.  Measured: with plenty of rows, blocks of one wavefront-quad do best with three
+      // rounds (the hardware does not fill every CU to the computed residency in the first round;
+      // later blocks even that out); the wide blocks, and any launch that would leave a block
+      // fewer than four row groups, with one (each new block pays an unpipelined first row and
+      // the staging of the row vectors)
       const int rpb = (int)L.block / G;
       const int64_t ngroups = (sv.rows + rpb - 1) / rpb;
       const int64_t held = (int64_t)c->n_cus * resident_blocks(c, p, L.kernel, L.block, L.dyn_lds);
-      const int rounds = c->row_rounds > 0 ? c->row_rounds : (L.block > 256 ? 1 : 3);
+      const int rounds = c->row_rounds > 0 ? c->row_rounds
+                         : (L.block > 256 ? 1 : (int)std::max<int64_t>(1, std::min<int64_t>(3, ngroups / (held * 4))));
       L.grid[0] = (uint32_t)std::min<int64_t>(ngroups, held * rounds);
       pub.lanes_per_row = G;
       pub.slots_per_lane = nv;
