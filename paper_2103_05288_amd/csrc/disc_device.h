@@ -278,9 +278,13 @@ DISC_DEV void group_step(typename Pat::template Acc<P>& acc) {
   Pat::template acc_xchg<P, S>(o);
   Pat::template acc_merge<P>(acc, o);
 }
-// nested on purpose: one scalar test per level, nothing re-derived after the branches rejoin
+// nested on purpose: one scalar test per level, nothing re-derived after the branches rejoin.
+// The empty asm makes G opaque at each call: the tests are then scalar compares at the point of
+// use; otherwise the compiler evaluates all six once per kernel and keeps them as lane masks in
+// twelve scalar registers across the row loop, which does not have them to spare.
 template <class Pat, int P>
 DISC_DEV void group_allreduce(typename Pat::template Acc<P>& acc, int G) {
+  asm volatile("" : "+s"(G));
   if (G > 1) {
     group_step<Pat, P, 1>(acc);
     if (G > 2) {
@@ -458,7 +462,6 @@ DISC_DEV void row_reg_body(const typename Pat::Args& A, const RowPlan& rp) {
   const i64 rows = A.rows;
   const int inner = (int)A.inner;
   int parity = 0;
-  const i64 ngroups = (rows + rpb - 1) / rpb;
   const char* staged = nullptr;
   if constexpr (Pat::STAGED) {
     Pat::template stage<V>(A, disc_stage_lds, threadIdx.x, blockDim.x);
@@ -494,7 +497,6 @@ DISC_DEV void row_reg_body(const typename Pat::Args& A, const RowPlan& rp) {
   // complete behind the lane reductions, the later phases, the epilogue and the stores.
   typename Pat::RowCtx rc{};
   typename Pat::template Slot<V> slot[NV];
-  i64 rg = blockIdx.x;
   // Row bookkeeping in scalar registers: rw = row of the first lane group of this wavefront in
   // the current row group, sbw = its element offset; both advance by a constant per iteration
   // (no 64-bit products in the loop).  A lane's row is rw + dgrp.
@@ -502,7 +504,7 @@ DISC_DEV void row_reg_body(const typename Pat::Args& A, const RowPlan& rp) {
   const int dgrp = grp - grp_w;
   const i64 rstep = (i64)gridDim.x * rpb;
   const i64 sbstep = rstep * A.inner;
-  i64 rw = rg * rpb + grp_w;
+  i64 rw = (i64)blockIdx.x * rpb + grp_w;
   i64 sbw = rw * A.inner;
   // rows past the end (last row group only) are replaced by the last row; their lanes compute
   // along and store nothing
@@ -523,15 +525,15 @@ DISC_DEV void row_reg_body(const typename Pat::Args& A, const RowPlan& rp) {
     for (int j = 0; j < NV; ++j)
       if (nvalid[j] > 0) Pat::template load<V>(A, rc, col0 + j * rp.G * V, Span::upto(nvalid[j]), slot[j]);
   };
-  if (PIPE && rg < ngroups) load_row();
-  while (rg < ngroups) {
+  // the row group of the block starts at row rw - grp_w; the block is done when that is past the end
+  if (PIPE && rw - grp_w < rows) load_row();
+  while (rw - grp_w < rows) {
     if constexpr (!PIPE) load_row();
     Span span[NV];
 #pragma unroll
     for (int j = 0; j < NV; ++j) span[j] = Span::upto(nvalid[j]);
     const i64 row = rw + dgrp;
     const bool active = row < rows;
-    const i64 rgn = rg + gridDim.x;
     typename Pat::RowCtx rcn{};
     typename Pat::template Slot<V> nxt[NV];
     int col0n = col0;
@@ -539,7 +541,7 @@ DISC_DEV void row_reg_body(const typename Pat::Args& A, const RowPlan& rp) {
 #pragma unroll
     for (int j = 0; j < NV; ++j) nvalidn[j] = nvalid[j];
     auto prefetch = [&]() {
-      if (PIPE && rgn < ngroups) {
+      if (PIPE && rw + rstep - grp_w < rows) {
         if (wpr > 1) {
           rot = rot + 64 < rp.G ? rot + 64 : 0;
           place(rot, col0n, nvalidn);
@@ -570,7 +572,6 @@ DISC_DEV void row_reg_body(const typename Pat::Args& A, const RowPlan& rp) {
       }
     }
     if (active && lane == 0) Pat::row_store(A, row, rc);
-    rg = rgn;
     rw += rstep;
     sbw += sbstep;
     if constexpr (PIPE) {
