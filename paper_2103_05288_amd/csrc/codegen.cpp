@@ -920,10 +920,9 @@ struct Gen {
       // rows get more lanes (blocks of up to 1024 threads) rather than more slots per lane.  The
       // three-slot versions exist for the row lengths that would leave a third of the lanes of the
       // next power of two without work
-      for (int nv : {1, 2}) {
-        krow(fmt("k_row_vec_nv%d", nv), V, nv);
-        krow(fmt("k_row_scalar_nv%d", nv), 1, nv);
-      }
+      // (a row of a single slot runs in the two-slot version: no version of its own)
+      krow("k_row_vec_nv2", V, 2);
+      krow("k_row_scalar_nv2", 1, 2);
       krow("k_row_vec_nv3", V, 3);
       max_threads = 1024;
       krow("k_row_vec_nv2w", V, 2);

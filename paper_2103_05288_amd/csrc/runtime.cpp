@@ -357,7 +357,7 @@ int make_plan(disc_ctx* c, const Pattern& p, const int64_t* dims, int n_dims, in
           if (cap >= spr && (best_cap < 0 || cap < best_cap)) { best_cap = cap; G = s.G; nv = k; block = s.block; }
         }
       nv = (int)((spr + G - 1) / G);
-      int inst = std::max(nv, block > 256 ? 2 : 1);   // instantiated slots per lane (blocks above 256: 2 or 3)
+      int inst = std::max(nv, 2);   // instantiated slots per lane: 2 or 3
       pub.variant = vec ? DISC_V_ROW_REG_VEC : DISC_V_ROW_REG_SCALAR;
       L.block = (uint32_t)block;
       L.plan_kind = 1;
