@@ -98,10 +98,12 @@ struct Span {
   DISC_DEV bool any() const { return n > 0; }
 };
 
-// Element offset of a slot inside the rows of one wavefront: 32-bit and unsigned when the column
-// index is (so the access can use a scalar base register plus a 32-bit lane offset), 64-bit when
-// the caller indexes columns with 64 bits.
-DISC_DEV unsigned off(int lane_base, int col) { return (unsigned)(lane_base + col); }
+// Element offset of a slot relative to the base row of the access.  A caller that passes the
+// column as `unsigned` promises that lane_base + col, scaled to bytes, fits 32 bits (the
+// register-resident row kernels: a wavefront's rows span at most 3 * 1024 slots); the access can
+// then use a scalar base register plus a 32-bit lane offset.  Any other column type: 64 bits.
+DISC_DEV unsigned off(int lane_base, unsigned col) { return (unsigned)lane_base + col; }
+DISC_DEV i64 off(int lane_base, int col) { return (i64)lane_base + col; }
 DISC_DEV i64 off(int lane_base, i64 col) { return lane_base + col; }
 
 // A ragged slot (n < N elements) moves as the power-of-two pieces of n's binary expansion: the
@@ -523,7 +525,7 @@ DISC_DEV void row_reg_body(const typename Pat::Args& A, const RowPlan& rp) {
     rc.sl = staged;
 #pragma unroll
     for (int j = 0; j < NV; ++j)
-      if (nvalid[j] > 0) Pat::template load<V>(A, rc, col0 + j * rp.G * V, Span::upto(nvalid[j]), slot[j]);
+      if (nvalid[j] > 0) Pat::template load<V>(A, rc, (unsigned)(col0 + j * rp.G * V), Span::upto(nvalid[j]), slot[j]);
   };
   // the row group of the block starts at row rw - grp_w; the block is done when that is past the end
   if (PIPE && rw - grp_w < rows) load_row();
@@ -553,7 +555,7 @@ DISC_DEV void row_reg_body(const typename Pat::Args& A, const RowPlan& rp) {
           if (nvalidn[j] > 0) {
             Span sn;            // the loads look at the element count only
             sn.n = nvalidn[j];
-            Pat::template load<V>(A, rcn, col0n + j * rp.G * V, sn, nxt[j]);
+            Pat::template load<V>(A, rcn, (unsigned)(col0n + j * rp.G * V), sn, nxt[j]);
           }
       }
       // keep the loads here: without a fence the compiler is free to sink them below the
@@ -568,7 +570,7 @@ DISC_DEV void row_reg_body(const typename Pat::Args& A, const RowPlan& rp) {
         const int col = col0 + j * rp.G * V;
         typename Pat::template OutSlot<V> o;
         Pat::template epilogue<V, true>(A, rc, slot[j], keep[j], col, span[j], o);
-        if (active) Pat::template store<V>(A, rc, col, span[j], o);
+        if (active) Pat::template store<V>(A, rc, (unsigned)col, span[j], o);
       }
     }
     if (active && lane == 0) Pat::row_store(A, row, rc);

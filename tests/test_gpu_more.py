@@ -327,3 +327,48 @@ def test_single_shape_module_matches_oracle_and_generic(ctx, cfg_name, dims):
         other[0] += 1
         run_gpu(hs, pat, other, cfg.inputs(other, seed=9))
     assert e.value.status == "SHAPE"
+
+
+def test_byte_offsets_beyond_32_bits(ctx):
+    """A 1-D tensor whose byte size exceeds 4 GiB while its slot count still fits the 32-bit slot
+    index, and a row-reduce whose single row is that long (streaming version): element offsets
+    inside a row must be scaled to bytes in 64 bits."""
+    n = (1 << 30) + 12345                      # 4 GiB + of fp32
+    pb = PatternBuilder()
+    d = pb.dim()
+    x = pb.param("f32", [d])
+    pb.output(pb.op("add", pb.op("mul", x, pb.const(2.0)), pb.const(1.0)))
+    pat = pb.build()
+    h = ctx.register(pat)
+    assert h.plan([n])["index_bits"] == 32
+    xs = torch.empty(n, dtype=torch.float32, device="cuda")
+    step = 1 << 20
+    for s in range(0, n, 1 << 26):             # value = index mod 2^20, exact in fp32
+        e = min(n, s + (1 << 26))
+        xs[s:e] = (torch.arange(s, e, device="cuda", dtype=torch.int64) % step).to(torch.float32)
+    out = torch.full((n,), float("nan"), dtype=torch.float32, device="cuda")
+    h.launch([n], [xs], [out])
+    torch.cuda.synchronize()
+    g = torch.Generator().manual_seed(3)
+    idx = torch.cat([torch.arange(0, 4096), torch.arange(n - 4096, n), torch.randint(0, n, (200000,), generator=g),
+                     torch.arange((1 << 30) - 2048, (1 << 30) + 2048)]).cuda()
+    want = (idx % step).to(torch.float32) * 2.0 + 1.0
+    assert torch.equal(out[idx], want)
+    assert not torch.isnan(out[:: 4099]).any()
+    del out
+    # one row of the same length: row max (streaming version, three passes would be needed for an
+    # epilogue; a reduce-only pattern keeps the test at two tensors)
+    pb = PatternBuilder()
+    t, hh = pb.dims(2)
+    x2 = pb.param("f32", [t, hh])
+    pb.output(pb.reduce("max", x2, 1))
+    pb.output(pb.reduce("min", x2, 1))
+    pat2 = pb.build()
+    h2 = ctx.register(pat2)
+    assert h2.plan([1, n])["variant_name"] == "row_stream_vec"
+    xs[n - 7] = 5.0e6                          # a maximum near the far end of the row
+    xs[(1 << 30) + 5] = -3.0                   # a minimum just past the 4 GiB byte offset
+    outs = [torch.empty(1, dtype=torch.float32, device="cuda") for _ in range(2)]
+    h2.launch([1, n], [xs.view(1, n)], outs)
+    torch.cuda.synchronize()
+    assert outs[0].item() == 5.0e6 and outs[1].item() == -3.0
