@@ -389,10 +389,11 @@ def main():
         "metric": "effective HBM GB/s over the dynamic-shape sweep (C0-C4), one compile per pattern",
         "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 3), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32 arithmetic (f32 / f16 / bf16 storage, f64 column sums)", "data": "synthetic",
+        "dtype": "f32", "data": "synthetic",
         "config": {"workload": "+".join(names) + " dynamic-shape sweeps: " +
                    ", ".join(f"{sw.name} {len(sw.calls)} calls" for sw in sweeps),
-                   "bytes_per_step": step_bytes, "calls_per_step": sum(len(sw.calls) for sw in sweeps)},
+                   "bytes_per_step": step_bytes, "calls_per_step": sum(len(sw.calls) for sw in sweeps),
+                   "storage": "f32 / f16 / bf16 / bool tensors, fp32 arithmetic, f64 accumulation of fp32 column sums"},
         "pct_of_peak": round(100 * value / PEAK_HBM_GBPS, 2),
         "roofline": roofline,
         "copy_ceiling_GBps": round(copy_gbps, 1),
