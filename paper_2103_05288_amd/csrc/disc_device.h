@@ -570,6 +570,13 @@ DISC_DEV void row_reg_body(const typename Pat::Args& A, const RowPlan& rp) {
         const int col = col0 + j * rp.G * V;
         typename Pat::template OutSlot<V> o;
         Pat::template epilogue<V, true>(A, rc, slot[j], keep[j], col, span[j], o);
+        // Loads and stores share one in-order counter, and with both kinds in flight the only
+        // wait the compiler can express is "all of them".  Waiting for the next row's loads HERE,
+        // before the first store of this row (they were issued a reduction phase ago and have
+        // landed), means the first use of those loads in the next iteration needs no wait at all
+        // -- otherwise that wait sits right behind these stores and exposes their full latency
+        // in every iteration.  The stores then have a whole iteration to drain.
+        if (PIPE && j == 0) __builtin_amdgcn_s_waitcnt(0x0F70);
         if (active) Pat::template store<V>(A, rc, (unsigned)col, span[j], o);
       }
     }
