@@ -477,7 +477,7 @@ DISC_DEV void row_reg_body(const typename Pat::Args& A, const RowPlan& rp) {
   // to twice the work of the others, and it would always be the first one -- on the same SIMD
   // of the CU for every row.  The slot grid is therefore turned by one wavefront from row to
   // row (lane l takes the columns of lane l + rot), which spreads the extra work evenly.
-  const int wpr = rp.G > 64 ? rp.G >> 6 : 1;
+  const int wpr = (rp.G > 64 && !(rp.flags & 2)) ? rp.G >> 6 : 1;   // flags bit 1: grid not turned (experiments)
   int rot = wpr > 1 ? (int)(blockIdx.x % (unsigned)wpr) * 64 : 0;
   int col0 = lane * V;
   int nvalid[NV];

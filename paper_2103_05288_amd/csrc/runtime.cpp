@@ -102,6 +102,7 @@ struct disc_ctx {
   hipFunction_t util_copy = nullptr, util_empty = nullptr;
   int row_target_nv = 3;     // tuning knobs, overridable from the environment for experiments
   int grid_mult = 8;
+  int row_turn = 1;          // rows of several wavefronts: slot grid turned by one wavefront per row
   int row_rounds = 0;        // row kernels: grid = this many rounds of resident blocks (0: by block size)
   int loop_unroll = 4;
   int row_stage = 1;
@@ -370,7 +371,7 @@ int make_plan(disc_ctx* c, const Pattern& p, const int64_t* dims, int n_dims, in
         int64_t bytes = 0;
         for (int eb : p.gen.staged_elem_bytes) bytes += ((sv.inner + v) * eb + 15) & ~15ll;
         const bool stage = vec && V > 1 && c->row_stage && bytes > 0 && bytes <= 48 * 1024;
-        L.rp.pad = stage ? 1 : 0;
+        L.rp.pad = (stage ? 1 : 0) | (c->row_turn ? 0 : 2);
         L.dyn_lds = stage ? (uint32_t)bytes : 0;
         // k_row_{vec|scalar}_nv{1|2|3}[w][_s]: w = block above 256 threads, _s = staged version
         static const std::vector<std::string> names = [] {
@@ -395,7 +396,14 @@ int make_plan(disc_ctx* c, const Pattern& p, const int64_t* dims, int n_dims, in
       const int64_t held = (int64_t)c->n_cus * resident_blocks(c, p, L.kernel, L.block, L.dyn_lds);
       const int rounds = c->row_rounds > 0 ? c->row_rounds
                          : (L.block > 256 ? 1 : (int)std::max<int64_t>(1, std::min<int64_t>(3, ngroups / (held * 4))));
-      L.grid[0] = (uint32_t)std::min<int64_t>(ngroups, held * rounds);
+      int64_t grid = std::min<int64_t>(ngroups, held * rounds);
+      // An odd grid: with an even one a block of one row per iteration would only ever see even or
+      // only odd rows, and when the row length is odd every other row starts two bytes off a
+      // dword -- half of the blocks would run ~20 % slower all the time and set the kernel's time
+      // (measured: +14-18 % on 4095- and 5739-wide rows).  With an odd grid every block walks
+      // through all alignments of its rows, whatever the rows per block.
+      if (grid > 2 && grid % 2 == 0 && grid < ngroups) grid -= 1;
+      L.grid[0] = (uint32_t)grid;
       pub.lanes_per_row = G;
       pub.slots_per_lane = nv;
       pub.reg_slots = inst;
@@ -608,6 +616,7 @@ int disc_create(disc_ctx** out, int hip_device) {
   }
   if (const char* e = getenv("DISC_ROW_TARGET_NV")) c->row_target_nv = std::max(1, std::min(8, atoi(e)));
   if (const char* e = getenv("DISC_ROW_STAGE")) c->row_stage = atoi(e) != 0;
+  if (const char* e = getenv("DISC_ROW_TURN")) c->row_turn = atoi(e) != 0;
   if (const char* e = getenv("DISC_ROW_ROUNDS")) c->row_rounds = std::max(0, atoi(e));
   if (const char* e = getenv("DISC_GRID_MULT")) c->grid_mult = std::max(1, std::min(64, atoi(e)));
   if (const char* e = getenv("DISC_LOOP_UNROLL")) (void)e;   // the unroll factor is a compile-time constant of the kernels
