@@ -102,6 +102,7 @@ struct disc_ctx {
   hipFunction_t util_copy = nullptr, util_empty = nullptr;
   int row_target_nv = 3;     // tuning knobs, overridable from the environment for experiments
   int grid_mult = 8;
+  int row_nopipe2 = 0;       // experiments: two-slot rows always in the unpipelined version
   int row_turn = 1;          // rows of several wavefronts: slot grid turned by one wavefront per row
   int row_rounds = 0;        // row kernels: grid = this many rounds of resident blocks (0: by block size)
   int loop_unroll = 4;
@@ -383,7 +384,9 @@ int make_plan(disc_ctx* c, const Pattern& p, const int64_t* dims, int n_dims, in
                   t.push_back(std::string("k_row_") + (vs ? "scalar" : "vec") + "_nv" + std::to_string(n) + (w ? "w" : "") + (s ? "_s" : ""));
           return t;
         }();
-        L.kernel = names[(((vec ? 0 : 1) * 3 + (inst - 1)) * 2 + (block > 256 ? 1 : 0)) * 2 + (stage ? 1 : 0)].c_str();
+        // (experiment knob: the two-slot version without the software pipeline also for small blocks)
+        const bool wide_version = block > 256 || (c->row_nopipe2 && inst == 2 && vec);
+        L.kernel = names[(((vec ? 0 : 1) * 3 + (inst - 1)) * 2 + (wide_version ? 1 : 0)) * 2 + (stage ? 1 : 0)].c_str();
       }
       // grid-stride over row groups: a small whole number of rounds of the blocks the chip holds
       // at once.  Measured: with plenty of rows, blocks of one wavefront-quad do best with three
@@ -616,6 +619,7 @@ int disc_create(disc_ctx** out, int hip_device) {
   }
   if (const char* e = getenv("DISC_ROW_TARGET_NV")) c->row_target_nv = std::max(1, std::min(8, atoi(e)));
   if (const char* e = getenv("DISC_ROW_STAGE")) c->row_stage = atoi(e) != 0;
+  if (const char* e = getenv("DISC_ROW_NOPIPE2")) c->row_nopipe2 = atoi(e) != 0;
   if (const char* e = getenv("DISC_ROW_TURN")) c->row_turn = atoi(e) != 0;
   if (const char* e = getenv("DISC_ROW_ROUNDS")) c->row_rounds = std::max(0, atoi(e));
   if (const char* e = getenv("DISC_GRID_MULT")) c->grid_mult = std::max(1, std::min(64, atoi(e)));
