@@ -345,3 +345,12 @@ def test_degenerate_shapes_and_errors(ctx, handles):
     expect("INVALID_ARG", ctx.force_variant, 99)
     # a host-only context cannot launch
     expect("INVALID_ARG", handles["C0"].launch, [1, 768], [1, 2, 3], [4], stream=0)
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py is a one-GPU program: any other --gpus value ends with a message, before touching a device."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert r.returncode != 0 and "ONE GPU" in r.stderr
