@@ -382,6 +382,7 @@ struct RowPlan {
   int log2G;    // meaningful for G <= 64
   int nv;       // slots per lane actually needed at this shape (<= NV of the instantiation)
   int flags;    // bit 0: the launched kernel is the version that stages row-vector operands in LDS
+                // bit 1: the slot grid is not turned from row to row (experiments)
   int rpb;      // rows per block = blockDim.x / G
 };
 

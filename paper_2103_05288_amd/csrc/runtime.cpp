@@ -23,7 +23,7 @@ extern const char* const kDeviceHeader;   // disc_device.h, embedded at build ti
 namespace {
 
 struct DeviceRowPlan {   // mirrors disc::RowPlan of the device header
-  int32_t G, log2G, nv, pad, rpb;
+  int32_t G, log2G, nv, flags, rpb;
 };
 struct DeviceColPlan {   // mirrors disc::ColPlan of the device header
   int32_t GC, log2GC, nchunk, pad;
@@ -372,7 +372,7 @@ int make_plan(disc_ctx* c, const Pattern& p, const int64_t* dims, int n_dims, in
         int64_t bytes = 0;
         for (int eb : p.gen.staged_elem_bytes) bytes += ((sv.inner + v) * eb + 15) & ~15ll;
         const bool stage = vec && V > 1 && c->row_stage && bytes > 0 && bytes <= 48 * 1024;
-        L.rp.pad = (stage ? 1 : 0) | (c->row_turn ? 0 : 2);
+        L.rp.flags = (stage ? 1 : 0) | (c->row_turn ? 0 : 2);
         L.dyn_lds = stage ? (uint32_t)bytes : 0;
         // k_row_{vec|scalar}_nv{1|2|3}[w][_s]: w = block above 256 threads, _s = staged version
         static const std::vector<std::string> names = [] {
@@ -677,7 +677,7 @@ static std::string static_macros(const Pattern& p, const FullPlan& fp, const int
   a << "\n#define DISC_STATIC_PLAN(rp)";
   const LaunchRec& L = fp.launches[0];
   if (L.plan_kind == 1)
-    a << " rp.G = " << L.rp.G << "; rp.log2G = " << L.rp.log2G << "; rp.nv = " << L.rp.nv << "; rp.flags = " << L.rp.pad
+    a << " rp.G = " << L.rp.G << "; rp.log2G = " << L.rp.log2G << "; rp.nv = " << L.rp.nv << "; rp.flags = " << L.rp.flags
       << "; rp.rpb = " << L.rp.rpb << ";";
   else if (L.plan_kind == 2)
     a << " rp.GC = " << L.cp.GC << "; rp.log2GC = " << L.cp.log2GC << "; rp.nchunk = " << L.cp.nchunk << "; rp.chunk_rows = "
