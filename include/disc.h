@@ -233,6 +233,50 @@ int disc_launch(disc_ctx* ctx, int32_t id, const int64_t* dims, int n_dims,
  * pattern and the shape (else DISC_ERR_INVALID_ARG at launch); -1 restores host selection. */
 int disc_force_variant(disc_ctx* ctx, int variant);
 
+/* ---- op graphs larger than one fusion pattern --------------------------------------------------
+ * The fusion decision over a graph (Section 4.3: whether ops may share a kernel follows from how
+ * shapes propagate through them and from the collected shape constraints) and the planning of the
+ * buffers between kernels (Section 4.2.2).  `ops` is an op list in the format above that need not
+ * be fusible as a whole.  The library cuts it, in list order, into consecutive fusion patterns: an
+ * op joins the current pattern as long as the pattern checker still accepts the result; an op
+ * that only feeds one later pattern moves there when that saves a buffer; each pattern is
+ * registered (and compiled once) through the pattern cache.  Values that cross a cut and are not
+ * graph outputs live in workspace buffers; a buffer is reused by a later value of the same element
+ * size and the same symbolic shape once its previous tenant has been read for the last time.
+ * Graph OUTPUTs must name computed values, each at most once (DISC_ERR_BAD_PATTERN otherwise).
+ * DISC_ERR_UNFUSIBLE when a single op is not a pattern by itself, DISC_ERR_BAD_PATTERN when the
+ * cut needs more than DISC_MAX_GRAPH_PATTERNS patterns.  All arrays are host memory, read during
+ * the call only.
+ *
+ * disc_graph_launch: `inputs` / `outputs` are host arrays of DEVICE pointers in the order of the
+ * graph's PARAM / OUTPUT ops; `workspace` is DEVICE memory of at least disc_graph_workspace_bytes
+ * (256-byte aligned), owned by the caller, free to reuse once the stream has passed the launch
+ * (DISC_ERR_WORKSPACE when missing or too small).  The patterns run in order on `hip_stream`; the
+ * call returns once they are enqueued.  A failure of one pattern's launch-time shape check returns
+ * that status with the earlier patterns already enqueued. */
+enum { DISC_MAX_GRAPH_PATTERNS = 64 };
+typedef struct {
+  int32_t n_dims, n_inputs, n_outputs;
+  int32_t n_patterns;                               /* kernels-worth of fused patterns         */
+  int32_t n_intermediates;                          /* values crossing a cut                   */
+  int32_t n_buffers;                                /* workspace buffers after reuse           */
+  int32_t pattern_id[DISC_MAX_GRAPH_PATTERNS];      /* ids usable with disc_pattern_info       */
+  int32_t pattern_ops[DISC_MAX_GRAPH_PATTERNS];     /* graph ops fused into each               */
+  int32_t group_of_op[DISC_MAX_OPS];                /* pattern index of each graph op, -1 for
+                                                       leaves, OUTPUT ops and dead code        */
+} disc_graph_info_t;
+int disc_register_graph(disc_ctx* ctx, const disc_op* ops, int n_ops, const disc_constraint* cs, int n_cs,
+                        int32_t* graph_id_out);
+int disc_graph_info(disc_ctx* ctx, int32_t graph_id, disc_graph_info_t* out);
+/* Bytes of DEVICE workspace disc_graph_launch needs at these dims: the planned buffers plus the
+ * largest workspace of any of its patterns. */
+int disc_graph_workspace_bytes(disc_ctx* ctx, int32_t graph_id, const int64_t* dims, int n_dims, size_t* out);
+/* Launches the patterns in order on `hip_stream`; same pointer conventions as disc_launch. */
+int disc_graph_launch(disc_ctx* ctx, int32_t graph_id, const int64_t* dims, int n_dims, const void* const* inputs,
+                      int n_in, void* const* outputs, int n_out, void* workspace, size_t workspace_bytes,
+                      void* hip_stream);
+
+
 int disc_get_stats(disc_ctx* ctx, disc_stats_t* out);
 
 /* Measurement helpers (not part of the method): a plain 16-byte-vector device copy used as the

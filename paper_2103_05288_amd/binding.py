@@ -44,6 +44,16 @@ class disc_pattern_info_t(C.Structure):
                 ("n_dim_classes", C.c_int32), ("dim_class", C.c_int32 * MAX_DIMS), ("compile_ms", C.c_double)]
 
 
+MAX_GRAPH_PATTERNS = 64
+MAX_OPS = 256
+
+
+class disc_graph_info_t(C.Structure):
+    _fields_ = [("n_dims", C.c_int32), ("n_inputs", C.c_int32), ("n_outputs", C.c_int32), ("n_patterns", C.c_int32),
+                ("n_intermediates", C.c_int32), ("n_buffers", C.c_int32), ("pattern_id", C.c_int32 * MAX_GRAPH_PATTERNS),
+                ("pattern_ops", C.c_int32 * MAX_GRAPH_PATTERNS), ("group_of_op", C.c_int32 * MAX_OPS)]
+
+
 class disc_plan_t(C.Structure):
     _fields_ = [("variant", C.c_int32), ("n_launches", C.c_int32), ("index_bits", C.c_int32),
                 ("vec_width", C.c_int32), ("lanes_per_row", C.c_int32), ("slots_per_lane", C.c_int32),
@@ -70,7 +80,8 @@ class DiscError(RuntimeError):
 EXPORTS = ("disc_create", "disc_destroy", "disc_last_error", "disc_register_pattern", "disc_register_pattern_static",
            "disc_pattern_info",
            "disc_pattern_source", "disc_workspace_bytes", "disc_plan", "disc_launch", "disc_force_variant",
-           "disc_get_stats", "disc_util_copy", "disc_util_empty_launch")
+           "disc_get_stats", "disc_util_copy", "disc_util_empty_launch", "disc_register_graph", "disc_graph_info",
+           "disc_graph_workspace_bytes", "disc_graph_launch")
 
 _lib = None
 
@@ -105,6 +116,11 @@ def load_library():
     lib.disc_plan.argtypes = [vp, C.c_int32, i64p, C.c_int, C.POINTER(vp), C.POINTER(vp), C.c_int, C.POINTER(disc_plan_t)]
     lib.disc_launch.argtypes = [vp, C.c_int32, i64p, C.c_int, C.POINTER(vp), C.c_int, C.POINTER(vp), C.c_int,
                                 vp, C.c_size_t, vp]
+    lib.disc_register_graph.argtypes = [vp, C.POINTER(disc_op), C.c_int, C.POINTER(disc_constraint), C.c_int, i32p]
+    lib.disc_graph_info.argtypes = [vp, C.c_int32, C.POINTER(disc_graph_info_t)]
+    lib.disc_graph_workspace_bytes.argtypes = [vp, C.c_int32, i64p, C.c_int, C.POINTER(C.c_size_t)]
+    lib.disc_graph_launch.argtypes = [vp, C.c_int32, i64p, C.c_int, C.POINTER(vp), C.c_int, C.POINTER(vp), C.c_int,
+                                      vp, C.c_size_t, vp]
     lib.disc_force_variant.argtypes = [vp, C.c_int]
     lib.disc_get_stats.argtypes = [vp, C.POINTER(disc_stats_t)]
     lib.disc_util_copy.argtypes = [vp, vp, vp, C.c_size_t, vp]
@@ -176,6 +192,43 @@ class PatternHandle:
         return self.ctx.pattern_source(self.id)
 
 
+class GraphHandle:
+    """An op graph cut into fusion patterns (disc_register_graph)."""
+
+    def __init__(self, ctx: "Context", gid: int, n_ops: int):
+        self.ctx, self.id, self.n_ops = ctx, gid, n_ops
+
+    @property
+    def info(self) -> dict:
+        g = disc_graph_info_t()
+        self.ctx._check(self.ctx.lib.disc_graph_info(self.ctx.h, self.id, C.byref(g)))
+        d = {k: getattr(g, k) for k in ("n_dims", "n_inputs", "n_outputs", "n_patterns", "n_intermediates", "n_buffers")}
+        d["pattern_id"] = list(g.pattern_id)[: g.n_patterns]
+        d["pattern_ops"] = list(g.pattern_ops)[: g.n_patterns]
+        d["group_of_op"] = list(g.group_of_op)[: self.n_ops]
+        return d
+
+    def workspace_bytes(self, dims) -> int:
+        arr, n = self.ctx._dims(dims)
+        out = C.c_size_t(0)
+        self.ctx._check(self.ctx.lib.disc_graph_workspace_bytes(self.ctx.h, self.id, arr, n, C.byref(out)))
+        return int(out.value)
+
+    def launch(self, dims, inputs: Sequence, outputs: Sequence, workspace=None, workspace_bytes: int = 0,
+               stream: Optional[int] = None):
+        arr, n = self.ctx._dims(dims)
+        ins = (C.c_void_p * max(1, len(inputs)))(*[_ptr(t) for t in inputs])
+        outs = (C.c_void_p * max(1, len(outputs)))(*[_ptr(t) for t in outputs])
+        ws = C.c_void_p(_ptr(workspace)) if workspace is not None else C.c_void_p()
+        if workspace is not None and not workspace_bytes and hasattr(workspace, "numel"):
+            workspace_bytes = workspace.numel() * workspace.element_size()
+        if stream is None:
+            import torch
+            stream = torch.cuda.current_stream().cuda_stream
+        self.ctx._check(self.ctx.lib.disc_graph_launch(self.ctx.h, self.id, arr, n, ins, len(inputs), outs, len(outputs),
+                                                       ws, C.c_size_t(workspace_bytes), C.c_void_p(stream)))
+
+
 def _ptr(t) -> int:
     return int(t.data_ptr()) if hasattr(t, "data_ptr") else int(t)
 
@@ -211,6 +264,13 @@ class Context:
         pid = C.c_int32(-1)
         self._check(self.lib.disc_register_pattern(self.h, ops, n_ops, cs, n_cs, C.byref(pid)))
         return PatternHandle(self, pid.value)
+
+    def register_graph(self, pattern) -> GraphHandle:
+        """An op list that need not be one fusible pattern: cut into patterns, buffers planned."""
+        ops, n_ops, cs, n_cs = marshal_pattern(pattern)
+        gid = C.c_int32(-1)
+        self._check(self.lib.disc_register_graph(self.h, ops, n_ops, cs, n_cs, C.byref(gid)))
+        return GraphHandle(self, gid.value, n_ops)
 
     def register_static(self, pattern, dims) -> PatternHandle:
         """The pattern compiled for this one shape only (single-shape module)."""

@@ -90,7 +90,33 @@ int64_t now_ns() {
 
 using namespace disc;
 
+// ---- op graphs larger than one fusion pattern (Section 4.3, fusion decision over a graph) -------
+struct GraphGroup {
+  std::vector<int> ops;          // graph op ids fused into this pattern, in graph order
+  int pattern_id = -1;
+  std::vector<int> in_values;    // graph value ids bound to the pattern's PARAMs, in order
+  std::vector<int> out_values;   // graph value ids produced by the pattern's OUTPUTs, in order
+};
+struct GraphIntermediate {
+  int value = -1;                // produced by group `first`, last read by group `last`
+  int first = 0, last = 0;
+  int buffer = -1;
+};
+struct Graph {
+  std::vector<disc_op> ops;
+  std::vector<disc_constraint> cs;
+  std::vector<int> group_of_op;  // -1 for leaves and OUTPUT ops
+  std::vector<GraphGroup> groups;
+  std::vector<GraphIntermediate> inter;
+  std::map<int, int> inter_of_value;
+  std::vector<int> buffer_value;         // a value whose size every tenant of the buffer shares
+  std::map<int, int> param_index;        // PARAM op id -> input index
+  std::map<int, int> output_index;       // value id -> output index (graph OUTPUT ops)
+  int n_sym = 0, n_inputs = 0, n_outputs = 0;
+};
+
 struct disc_ctx {
+  std::vector<std::unique_ptr<Graph>> graphs;
   int device = -1;
   int n_cus = 256;
   std::string err;
@@ -948,3 +974,385 @@ int disc_util_empty_launch(disc_ctx* ctx, void* hip_stream) {
 }
 
 }  // extern "C"
+
+// =================================================================================================
+// Op graphs (Section 4.3 "fusion decision", Section 4.2.2 buffer management): a list of ops that
+// need not be one fusible pattern is cut into consecutive fusion patterns with the SAME test the
+// single-pattern path uses (the checker's shape propagation + constraints), and the values that
+// cross pattern boundaries get buffers planned by lifetime, shared between values whose shapes
+// are the same symbolic expression.
+// =================================================================================================
+namespace {
+
+bool is_leaf(int opcode) { return opcode == DISC_PARAM || opcode == DISC_CONST || opcode == DISC_DIM_SIZE; }
+
+int op_arity(const disc_op& o) {
+  int n = 0;
+  for (int k = 0; k < 3; ++k)
+    if (o.in[k] >= 0) n = k + 1;
+  return n;
+}
+
+// The op list of the pattern that computes the graph ops `S` (ascending ids): operands produced
+// outside S become PARAMs (scalar leaves are copied instead), values of S read outside S (by ops
+// of other groups or by graph OUTPUTs) become OUTPUTs, constraints between values that both
+// appear are carried over.
+void build_sub_pattern(const Graph& g, const std::vector<int>& S, const std::vector<char>& in_S,
+                       std::vector<disc_op>* sub, std::vector<disc_constraint>* sub_cs, std::vector<int>* in_values,
+                       std::vector<int>* out_values) {
+  std::map<int, int> id_of;   // graph value -> sub-pattern value
+  sub->clear();
+  sub_cs->clear();
+  in_values->clear();
+  out_values->clear();
+  auto operand = [&](int v) {
+    auto it = id_of.find(v);
+    if (it != id_of.end()) return it->second;
+    const disc_op& src = g.ops[v];
+    disc_op o = src;
+    if (src.opcode == DISC_CONST || src.opcode == DISC_DIM_SIZE) {
+      for (int k = 0; k < 3; ++k) o.in[k] = -1;
+    } else {               // a graph input or a value of another group: a PARAM of its type and shape
+      o.opcode = DISC_PARAM;
+      for (int k = 0; k < 3; ++k) o.in[k] = -1;
+      for (int k = 0; k < DISC_MAX_RANK; ++k) o.axis_map[k] = 0;
+      o.fconst = 0;
+      in_values->push_back(v);
+    }
+    sub->push_back(o);
+    id_of[v] = (int)sub->size() - 1;
+    return id_of[v];
+  };
+  for (int v : S) {
+    disc_op o = g.ops[v];
+    const int n = op_arity(o);
+    for (int k = 0; k < n; ++k) o.in[k] = operand(g.ops[v].in[k]);
+    sub->push_back(o);
+    id_of[v] = (int)sub->size() - 1;
+  }
+  // consumers outside S
+  std::vector<char> read_outside(g.ops.size(), 0);
+  for (size_t i = 0; i < g.ops.size(); ++i) {
+    if (in_S[i]) continue;
+    const disc_op& o = g.ops[i];
+    if (is_leaf(o.opcode)) continue;
+    const int n = op_arity(o);
+    for (int k = 0; k < n; ++k)
+      if (o.in[k] >= 0 && in_S[o.in[k]]) read_outside[o.in[k]] = 1;
+  }
+  for (int v : S)
+    if (read_outside[v]) {
+      disc_op o = g.ops[v];
+      o.opcode = DISC_OUTPUT;
+      o.in[0] = id_of[v];
+      o.in[1] = o.in[2] = -1;
+      for (int k = 0; k < DISC_MAX_RANK; ++k) o.axis_map[k] = 0;
+      o.fconst = 0;
+      sub->push_back(o);
+      out_values->push_back(v);
+    }
+  for (const auto& c : g.cs) {
+    auto a = id_of.find(c.a_value), b = id_of.find(c.b_value);
+    if (a == id_of.end() || b == id_of.end()) continue;
+    disc_constraint t = c;
+    t.a_value = a->second;
+    t.b_value = b->second;
+    sub_cs->push_back(t);
+  }
+}
+
+int64_t value_bytes(const Graph& g, int v, const int64_t* dims) {
+  const disc_op& o = g.ops[v];
+  int64_t n = 1;
+  for (int k = 0; k < o.rank; ++k) n *= o.dim[k] >= 0 ? dims[o.dim[k]] : -(int64_t)o.dim[k];
+  return n * dtype_bytes(o.dtype);
+}
+
+Graph* get_graph(disc_ctx* ctx, int32_t id) {
+  if (!ctx || id < 0 || id >= (int)ctx->graphs.size()) return nullptr;
+  return ctx->graphs[id].get();
+}
+
+// byte offset of every buffer and of the shared pattern-workspace region for one set of dims
+int graph_layout(disc_ctx* ctx, const Graph& g, const int64_t* dims, int n_dims, std::vector<size_t>* buf_off,
+                 size_t* pattern_ws_off, size_t* total) {
+  if (!dims || n_dims != g.n_sym) return set_err(ctx, DISC_ERR_INVALID_ARG, "wrong number of dims for this graph");
+  for (int i = 0; i < n_dims; ++i)
+    if (dims[i] < 0) return set_err(ctx, DISC_ERR_SHAPE, "negative dim");
+  size_t off = 0;
+  buf_off->assign(g.buffer_value.size(), 0);
+  for (size_t b = 0; b < g.buffer_value.size(); ++b) {
+    (*buf_off)[b] = off;
+    off += ((size_t)value_bytes(g, g.buffer_value[b], dims) + 255) / 256 * 256;
+  }
+  *pattern_ws_off = off;
+  size_t need = 0;
+  for (const auto& gr : g.groups) {
+    size_t w = 0;
+    const int ns = ctx->patterns[gr.pattern_id]->an.n_sym;
+    int rc = disc_workspace_bytes(ctx, gr.pattern_id, dims, ns, &w);
+    if (rc) return rc;
+    need = std::max(need, w);
+  }
+  *total = off + need;
+  return DISC_OK;
+}
+
+}  // namespace
+
+int disc_register_graph(disc_ctx* ctx, const disc_op* ops, int n_ops, const disc_constraint* cs, int n_cs,
+                        int32_t* graph_id_out) {
+  if (!ctx) return DISC_ERR_INVALID_ARG;
+  if (!graph_id_out) return set_err(ctx, DISC_ERR_INVALID_ARG, "graph_id_out is null");
+  *graph_id_out = -1;
+  if (!ops || n_ops <= 0) return set_err(ctx, DISC_ERR_INVALID_ARG, "empty op list");
+  if (n_cs < 0 || (n_cs > 0 && !cs)) return set_err(ctx, DISC_ERR_INVALID_ARG, "bad constraint list");
+  if (n_ops > DISC_MAX_OPS) return set_err(ctx, DISC_ERR_BAD_PATTERN, "too many ops");
+  std::unique_ptr<Graph> g(new Graph);
+  g->ops.assign(ops, ops + n_ops);
+  if (n_cs) g->cs.assign(cs, cs + n_cs);
+  g->group_of_op.assign(n_ops, -1);
+  // structure checks the per-pattern checker cannot make on a cut-up list
+  std::vector<int> compute;
+  for (int i = 0; i < n_ops; ++i) {
+    const disc_op& o = g->ops[i];
+    if (o.opcode < 0 || o.opcode >= DISC_OPCODE_COUNT) return set_err(ctx, DISC_ERR_BAD_PATTERN, "unknown opcode");
+    if (o.rank < 0 || o.rank > DISC_MAX_RANK) return set_err(ctx, DISC_ERR_BAD_PATTERN, "rank out of range");
+    const int n = op_arity(o);
+    for (int k = 0; k < n; ++k)
+      if (o.in[k] < 0 || o.in[k] >= i || g->ops[o.in[k]].opcode == DISC_OUTPUT)
+        return set_err(ctx, DISC_ERR_BAD_PATTERN, "operand does not name an earlier value");
+    for (int k = 0; k < o.rank; ++k)
+      if (o.dim[k] >= 0) g->n_sym = std::max(g->n_sym, o.dim[k] + 1);
+    if (o.opcode == DISC_DIM_SIZE) g->n_sym = std::max(g->n_sym, o.axis_map[0] + 1);
+    if (o.opcode == DISC_PARAM) g->param_index[i] = g->n_inputs++;
+    else if (o.opcode == DISC_OUTPUT) {
+      if (n < 1 || is_leaf(g->ops[o.in[0]].opcode))
+        return set_err(ctx, DISC_ERR_BAD_PATTERN, "a graph output must be a computed value");
+      if (g->output_index.count(o.in[0])) return set_err(ctx, DISC_ERR_BAD_PATTERN, "a value is output twice");
+      g->output_index[o.in[0]] = g->n_outputs++;
+    } else if (!is_leaf(o.opcode)) compute.push_back(i);
+  }
+  if (g->n_sym > DISC_MAX_DIMS) return set_err(ctx, DISC_ERR_BAD_PATTERN, "too many symbolic dims");
+  if (compute.empty() || g->n_outputs == 0) return set_err(ctx, DISC_ERR_BAD_PATTERN, "nothing to compute");
+
+  // greedy cut in list order: an op joins the current pattern when the checker still accepts the
+  // pattern with it (one provable iteration space, one template); otherwise it opens the next one
+  std::vector<disc_op> sub;
+  std::vector<disc_constraint> sub_cs;
+  std::vector<int> ins, outs;
+  auto fusible = [&](const std::vector<int>& S, std::string* why) {
+    std::vector<char> in_S(n_ops, 0);
+    for (int v : S) in_S[v] = 1;
+    build_sub_pattern(*g, S, in_S, &sub, &sub_cs, &ins, &outs);
+    Analysis an;
+    return analyze(sub.data(), (int)sub.size(), sub_cs.empty() ? nullptr : sub_cs.data(), (int)sub_cs.size(), &an, why);
+  };
+  std::vector<std::vector<int>> cuts;
+  std::vector<int> cur;
+  std::string why;
+  for (int v : compute) {
+    cur.push_back(v);
+    if (fusible(cur, &why) == DISC_OK) continue;
+    cur.pop_back();
+    if (cur.empty()) return set_err(ctx, DISC_ERR_UNFUSIBLE, "op " + std::to_string(v) + " is not a pattern on its own: " + why);
+    cuts.push_back(cur);
+    cur.assign(1, v);
+    int rc = fusible(cur, &why);
+    if (rc) return set_err(ctx, rc, "op " + std::to_string(v) + " is not a pattern on its own: " + why);
+  }
+  cuts.push_back(cur);
+
+  // Sinking: the greedy cut also pulls in ops that only feed the NEXT pattern (say the |x| ahead of
+  // a reduction the current pattern cannot hold), which turns their result into one more buffer.
+  // Such an op moves to the pattern of its users when nothing of its own pattern and no graph
+  // output reads it, all its users sit in one later pattern, that pattern still passes the checker
+  // with it, and each of its computed operands crosses a pattern boundary anyway -- then the move
+  // saves one write and one read of the op's result and adds at most one read of an operand.
+  {
+    std::vector<int> grp(n_ops, -1);
+    for (size_t gi = 0; gi < cuts.size(); ++gi)
+      for (int v : cuts[gi]) grp[v] = (int)gi;
+    std::vector<std::vector<int>> users(n_ops);
+    for (int i = 0; i < n_ops; ++i) {
+      if (is_leaf(g->ops[i].opcode)) continue;
+      const int n = op_arity(g->ops[i]);
+      for (int k = 0; k < n; ++k) users[g->ops[i].in[k]].push_back(i);
+    }
+    auto read_elsewhere = [&](int v, int except) {       // graph output, or read outside its pattern by another op
+      for (int u : users[v]) {
+        if (u == except) continue;
+        if (g->ops[u].opcode == DISC_OUTPUT || grp[u] != grp[v]) return true;
+      }
+      return false;
+    };
+    bool moved = true;
+    while (moved) {
+      moved = false;
+      for (size_t gi = 0; gi + 1 < cuts.size(); ++gi) {
+        for (size_t pos = cuts[gi].size(); pos-- > 0;) {
+          const int x = cuts[gi][pos];
+          if (users[x].empty()) continue;
+          int to = -1;
+          bool ok = true;
+          for (int u : users[x]) {
+            if (g->ops[u].opcode == DISC_OUTPUT || grp[u] <= (int)gi) { ok = false; break; }
+            if (to >= 0 && grp[u] != to) { ok = false; break; }
+            to = grp[u];
+          }
+          if (!ok || to < 0) continue;
+          const int n = op_arity(g->ops[x]);
+          for (int k = 0; k < n && ok; ++k) {
+            const int a = g->ops[x].in[k];
+            if (!is_leaf(g->ops[a].opcode) && grp[a] == (int)gi && !read_elsewhere(a, x)) ok = false;
+          }
+          if (!ok) continue;
+          std::vector<int> bigger = cuts[to];
+          bigger.insert(std::lower_bound(bigger.begin(), bigger.end(), x), x);
+          if (fusible(bigger, &why) != DISC_OK) continue;
+          std::vector<int> smaller = cuts[gi];
+          smaller.erase(smaller.begin() + (long)pos);
+          if (!smaller.empty() && fusible(smaller, &why) != DISC_OK) continue;
+          cuts[to].swap(bigger);
+          cuts[gi].swap(smaller);
+          grp[x] = to;
+          moved = true;
+        }
+      }
+    }
+    std::vector<std::vector<int>> kept;
+    for (auto& c : cuts)
+      if (!c.empty()) kept.push_back(c);
+    cuts.swap(kept);
+  }
+  if (cuts.size() > (size_t)DISC_MAX_GRAPH_PATTERNS) return set_err(ctx, DISC_ERR_BAD_PATTERN, "the graph needs too many patterns");
+
+  for (size_t gi = 0; gi < cuts.size(); ++gi) {
+    GraphGroup gr;
+    gr.ops = cuts[gi];
+    std::vector<char> in_S(n_ops, 0);
+    for (int v : gr.ops) { in_S[v] = 1; g->group_of_op[v] = (int)gi; }
+    build_sub_pattern(*g, gr.ops, in_S, &sub, &sub_cs, &gr.in_values, &gr.out_values);
+    if (gr.out_values.empty()) { gr.pattern_id = -1; g->groups.push_back(gr); continue; }   // dead code: nothing reads it
+    int32_t pid = -1;
+    int rc = disc_register_pattern(ctx, sub.data(), (int)sub.size(), sub_cs.empty() ? nullptr : sub_cs.data(),
+                                   (int)sub_cs.size(), &pid);
+    if (rc) return rc;
+    gr.pattern_id = pid;
+    g->groups.push_back(gr);
+  }
+  // drop groups nothing reads
+  {
+    std::vector<GraphGroup> kept;
+    std::vector<int> renum(g->groups.size(), -1);
+    for (size_t gi = 0; gi < g->groups.size(); ++gi)
+      if (g->groups[gi].pattern_id >= 0) { renum[gi] = (int)kept.size(); kept.push_back(g->groups[gi]); }
+    for (int& x : g->group_of_op)
+      if (x >= 0) x = renum[x];
+    g->groups.swap(kept);
+  }
+  if (g->groups.empty()) return set_err(ctx, DISC_ERR_BAD_PATTERN, "no output depends on a computed value");
+
+  // values that cross pattern boundaries and are not graph outputs live in planned buffers
+  for (size_t gi = 0; gi < g->groups.size(); ++gi)
+    for (int v : g->groups[gi].out_values) {
+      if (g->output_index.count(v)) continue;
+      GraphIntermediate it;
+      it.value = v;
+      it.first = it.last = (int)gi;
+      g->inter_of_value[v] = (int)g->inter.size();
+      g->inter.push_back(it);
+    }
+  for (size_t gi = 0; gi < g->groups.size(); ++gi)
+    for (int v : g->groups[gi].in_values) {
+      auto it = g->inter_of_value.find(v);
+      if (it != g->inter_of_value.end()) g->inter[it->second].last = std::max(g->inter[it->second].last, (int)gi);
+    }
+  // a buffer is reused by a later value of the same dtype size and the same symbolic shape once
+  // its previous tenant has been read for the last time (Section 4.2.2: reuse by shape compatibility)
+  {
+    std::vector<int> free_after;          // per buffer: last group that reads its tenant
+    std::vector<std::string> key_of;      // per buffer
+    for (auto& it : g->inter) {
+      const disc_op& o = g->ops[it.value];
+      std::string key(1, (char)dtype_bytes(o.dtype));
+      key.append(reinterpret_cast<const char*>(o.dim), sizeof(int32_t) * (size_t)o.rank);
+      int pick = -1;
+      for (size_t b = 0; b < key_of.size() && pick < 0; ++b)
+        if (key_of[b] == key && free_after[b] < it.first) pick = (int)b;
+      if (pick < 0) {
+        pick = (int)key_of.size();
+        key_of.push_back(key);
+        free_after.push_back(it.last);
+        g->buffer_value.push_back(it.value);
+      } else {
+        free_after[pick] = it.last;
+      }
+      it.buffer = pick;
+    }
+  }
+  const int id = (int)ctx->graphs.size();
+  ctx->graphs.push_back(std::move(g));
+  *graph_id_out = id;
+  return DISC_OK;
+}
+
+int disc_graph_info(disc_ctx* ctx, int32_t id, disc_graph_info_t* out) {
+  Graph* g = get_graph(ctx, id);
+  if (!g || !out) return set_err(ctx, DISC_ERR_INVALID_ARG, "bad graph id or null output");
+  memset(out, 0, sizeof *out);
+  out->n_dims = g->n_sym;
+  out->n_inputs = g->n_inputs;
+  out->n_outputs = g->n_outputs;
+  out->n_patterns = (int)g->groups.size();
+  out->n_intermediates = (int)g->inter.size();
+  out->n_buffers = (int)g->buffer_value.size();
+  for (size_t i = 0; i < g->groups.size() && i < DISC_MAX_GRAPH_PATTERNS; ++i) {
+    out->pattern_id[i] = g->groups[i].pattern_id;
+    out->pattern_ops[i] = (int)g->groups[i].ops.size();
+  }
+  for (size_t i = 0; i < g->group_of_op.size() && i < DISC_MAX_OPS; ++i) out->group_of_op[i] = g->group_of_op[i];
+  return DISC_OK;
+}
+
+int disc_graph_workspace_bytes(disc_ctx* ctx, int32_t id, const int64_t* dims, int n_dims, size_t* out) {
+  Graph* g = get_graph(ctx, id);
+  if (!g || !out) return set_err(ctx, DISC_ERR_INVALID_ARG, "bad graph id or null output");
+  std::vector<size_t> off;
+  size_t pws = 0;
+  return graph_layout(ctx, *g, dims, n_dims, &off, &pws, out);
+}
+
+int disc_graph_launch(disc_ctx* ctx, int32_t id, const int64_t* dims, int n_dims, const void* const* inputs, int n_in,
+                      void* const* outputs, int n_out, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  Graph* g = get_graph(ctx, id);
+  if (!g) return set_err(ctx, DISC_ERR_INVALID_ARG, "bad graph id");
+  if (n_in != g->n_inputs || n_out != g->n_outputs) return set_err(ctx, DISC_ERR_INVALID_ARG, "wrong number of inputs or outputs");
+  if ((n_in > 0 && !inputs) || !outputs) return set_err(ctx, DISC_ERR_INVALID_ARG, "null pointer array");
+  std::vector<size_t> off;
+  size_t pws = 0, total = 0;
+  int rc = graph_layout(ctx, *g, dims, n_dims, &off, &pws, &total);
+  if (rc) return rc;
+  if (total > 0 && (!workspace || workspace_bytes < total)) return set_err(ctx, DISC_ERR_WORKSPACE, "workspace missing or too small");
+  char* ws = static_cast<char*>(workspace);
+  auto where = [&](int v) -> void* {
+    auto p = g->param_index.find(v);
+    if (p != g->param_index.end()) return const_cast<void*>(inputs[p->second]);
+    auto o = g->output_index.find(v);
+    if (o != g->output_index.end()) return outputs[o->second];
+    return ws + off[g->inter[g->inter_of_value.at(v)].buffer];
+  };
+  std::vector<const void*> in;
+  std::vector<void*> outp;
+  for (const auto& gr : g->groups) {
+    in.clear();
+    outp.clear();
+    for (int v : gr.in_values) in.push_back(where(v));
+    for (int v : gr.out_values) outp.push_back(where(v));
+    const int ns = ctx->patterns[gr.pattern_id]->an.n_sym;
+    rc = disc_launch(ctx, gr.pattern_id, dims, ns, in.data(), (int)in.size(), outp.data(), (int)outp.size(),
+                     ws ? ws + pws : nullptr, total - pws, hip_stream);
+    if (rc) return rc;
+  }
+  return DISC_OK;
+}

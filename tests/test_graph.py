@@ -1,0 +1,149 @@
+"""Op graphs larger than one fusion pattern: the cut into patterns and the buffer plan on the host
+(no GPU), and parity of the whole graph with the oracle on the GPU."""
+import numpy as np
+import pytest
+import torch
+
+from workloads import PatternBuilder
+from workloads.configs import TORCH_DTYPE
+
+
+def block_graph(p_is_output=True):
+    """bias + tanh -> residual -> LayerNorm * gamma -> row softmax -> column mean -> centred."""
+    pb = PatternBuilder("block")
+    T, H = pb.dims(2)
+    x = pb.param("bf16", [T, H]); b = pb.param("f32", [H]); r = pb.param("bf16", [T, H]); gam = pb.param("f32", [H])
+    row = lambda v: pb.broadcast(v, [T, H], [0])
+    col = lambda v: pb.broadcast(v, [T, H], [1])
+    h = pb.op("tanh", pb.op("add", pb.cast(x, "f32"), col(b)))
+    v = pb.op("add", h, pb.cast(r, "f32"))
+    mean = pb.op("div", pb.reduce("sum", v, 1), pb.dim_size(H))
+    d = pb.op("sub", v, row(mean))
+    var = pb.op("div", pb.reduce("sum", pb.op("mul", d, d), 1), pb.dim_size(H))
+    y = pb.op("mul", pb.op("mul", d, row(pb.op("rsqrt", pb.op("add", var, pb.const(1e-5))))), col(gam))
+    pb.output(pb.cast(y, "bf16"))
+    m = pb.reduce("max", y, 1)
+    e = pb.op("exp", pb.op("sub", y, row(m)))
+    p = pb.op("div", e, row(pb.reduce("sum", e, 1)))
+    if p_is_output:
+        pb.output(p)
+    cm = pb.op("div", pb.reduce("sum", p, 0), pb.dim_size(T))
+    pb.output(cm)
+    pb.output(pb.cast(pb.op("sub", p, col(cm)), "f16"))
+    return pb.build()
+
+
+def chain_graph(n_stages=4):
+    """Column-centre, row-normalise, column-centre, ...: every stage is a pattern of its own and
+    hands a [T, H] fp32 value to the next, so the buffers between them can be shared."""
+    pb = PatternBuilder("chain")
+    T, H = pb.dims(2)
+    v = pb.param("f32", [T, H])
+    for s in range(n_stages):
+        if s % 2 == 0:
+            cm = pb.op("div", pb.reduce("sum", v, 0), pb.dim_size(T))
+            v = pb.op("sub", v, pb.broadcast(cm, [T, H], [1]))
+        else:
+            m = pb.reduce("max", pb.op("abs", v), 1)
+            v = pb.op("div", v, pb.broadcast(pb.op("add", m, pb.const(1.0)), [T, H], [0]))
+    pb.output(v)
+    return pb.build()
+
+
+@pytest.fixture(scope="module")
+def hctx():
+    from paper_2103_05288_amd import Context
+    c = Context(device=-1)
+    yield c
+    c.close()
+
+
+def test_cut_into_patterns(hctx):
+    pat = block_graph()
+    g = hctx.register_graph(pat)
+    info = g.info
+    assert (info["n_inputs"], info["n_outputs"], info["n_dims"]) == (4, 4, 2)
+    # everything up to the row softmax is one row-reduce pattern with four dependent reductions;
+    # the column mean and what follows it is a second, column-reduce pattern
+    assert info["n_patterns"] == 2
+    t = [hctx.pattern_info(p) for p in info["pattern_id"]]
+    assert [x["template"] for x in t] == ["row_reduce", "col_reduce"] and t[0]["n_phases"] == 4
+    assert sum(info["pattern_ops"]) == sum(1 for o in pat.ops if o.opcode not in ("param", "const", "dim_size", "output"))
+    groups = [x for x in info["group_of_op"] if x >= 0]
+    assert groups == sorted(groups)                       # consecutive cuts in list order
+    for i, o in enumerate(pat.ops):
+        assert (info["group_of_op"][i] == -1) == (o.opcode in ("param", "const", "dim_size", "output"))
+    assert info["n_intermediates"] == 0 and g.workspace_bytes([100, 768]) == hctx.workspace_bytes(info["pattern_id"][1], [100, 768])
+    # the same graph with p no longer an output: p now lives in a planned buffer of T * H * 4 bytes
+    g2 = hctx.register_graph(block_graph(p_is_output=False))
+    i2 = g2.info
+    assert i2["n_patterns"] == 2 and i2["n_intermediates"] == 1 and i2["n_buffers"] == 1
+    assert g2.workspace_bytes([100, 768]) >= 100 * 768 * 4
+    # one compile per distinct pattern: registering the graph again compiles nothing
+    before = hctx.stats()["compile_events"]
+    hctx.register_graph(block_graph())
+    assert hctx.stats()["compile_events"] == before
+
+
+def test_buffers_are_shared_by_lifetime(hctx):
+    g = hctx.register_graph(chain_graph(5))
+    info = g.info
+    assert info["n_patterns"] == 5 and info["n_intermediates"] == 4
+    assert info["n_buffers"] == 2                         # ping-pong: a value dies when the next stage has read it
+    ws = g.workspace_bytes([1000, 300])
+    assert 2 * 1000 * 300 * 4 <= ws < 3 * 1000 * 300 * 4 + (1 << 20)
+    one = hctx.register_graph(chain_graph(1)).info
+    assert one["n_patterns"] == 1 and one["n_buffers"] == 0
+
+
+def test_graph_errors(hctx):
+    from paper_2103_05288_amd import DiscError
+    pb = PatternBuilder()
+    T, H = pb.dims(2)
+    x = pb.param("f32", [T, H])
+    pb.output(x)                                          # nothing computed
+    with pytest.raises(DiscError) as e:
+        hctx.register_graph(pb.build())
+    assert e.value.status == "BAD_PATTERN"
+    pb = PatternBuilder()
+    T, H = pb.dims(2)
+    x = pb.param("f32", [T, H])
+    y = pb.op("neg", x)
+    pb.output(y)
+    pb.output(y)
+    with pytest.raises(DiscError) as e:
+        hctx.register_graph(pb.build())
+    assert e.value.status == "BAD_PATTERN"
+    g = hctx.register_graph(chain_graph(2))
+    with pytest.raises(DiscError) as e:
+        g.workspace_bytes([1, 2, 3])
+    assert e.value.status == "INVALID_ARG"
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("which", ["block", "block_inter", "chain"])
+def test_graph_matches_oracle(which):
+    from oracle import run as oracle_run
+    from paper_2103_05288_amd import Context
+    from tests.util import assert_close, to_oracle_input
+    pat = {"block": block_graph(), "block_inter": block_graph(False), "chain": chain_graph(5)}[which]
+    ctx = Context(0)
+    try:
+        g = ctx.register_graph(pat)
+        gen = torch.Generator().manual_seed(11)
+        for dims in ([7, 33], [300, 768], [1500, 1021], [64, 4099]):
+            ins = []
+            for pi in pat.params:
+                shp = pat.shape_of(pi, dims)
+                ins.append(torch.randn(shp, generator=gen).to(TORCH_DTYPE[pat.ops[pi].dtype]))
+            dev_in = [t.cuda() for t in ins]
+            outs = [torch.full(pat.shape_of(o, dims), float("nan"), dtype=TORCH_DTYPE[pat.ops[o].dtype], device="cuda")
+                    for o in pat.outputs]
+            ws = torch.empty(max(16, g.workspace_bytes(dims)), dtype=torch.uint8, device="cuda")
+            g.launch(dims, dev_in, outs, workspace=ws)
+            torch.cuda.synchronize()
+            want = oracle_run(pat, dims, [to_oracle_input(t) for t in ins])[0]
+            for k, (o, w) in enumerate(zip(outs, want)):
+                assert_close(o.cpu(), w, f"graph {which} dims={dims} out{k}")
+    finally:
+        ctx.close()
