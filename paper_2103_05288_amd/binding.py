@@ -184,8 +184,8 @@ class PatternHandle:
     def launch(self, dims, inputs, outputs, **kw):
         return self.ctx.launch(self.id, dims, inputs, outputs, **kw)
 
-    def plan(self, dims, force_variant: int = -1):
-        return self.ctx.plan(self.id, dims, force_variant)
+    def plan(self, dims, force_variant: int = -1, inputs=None, outputs=None):
+        return self.ctx.plan(self.id, dims, force_variant, inputs, outputs)
 
     @property
     def source(self) -> str:
@@ -303,10 +303,14 @@ class Context:
         self._check(self.lib.disc_workspace_bytes(self.h, pid, arr, n, C.byref(out)))
         return out.value
 
-    def plan(self, pid: int, dims, force_variant: int = -1) -> dict:
+    def plan(self, pid: int, dims, force_variant: int = -1, inputs=None, outputs=None) -> dict:
+        """The launch plan for these dims; with inputs / outputs (tensors or device addresses) the
+        plan is the one a launch with exactly these operands takes."""
         arr, n = self._dims(dims)
         p = disc_plan_t()
-        self._check(self.lib.disc_plan(self.h, pid, arr, n, None, None, int(force_variant), C.byref(p)))
+        ins = (C.c_void_p * max(1, len(inputs)))(*[_ptr(t) for t in inputs]) if inputs is not None else None
+        outs = (C.c_void_p * max(1, len(outputs)))(*[_ptr(t) for t in outputs]) if outputs is not None else None
+        self._check(self.lib.disc_plan(self.h, pid, arr, n, ins, outs, int(force_variant), C.byref(p)))
         d = {k: getattr(p, k) for k, _ in p._fields_ if k not in ("grid", "block", "lds_bytes", "kernel")}
         d["kernels"] = [bytes(p.kernel[i]).split(b"\0")[0].decode() for i in range(p.n_launches)]
         d["grid"] = [list(g) for g in p.grid][: p.n_launches]

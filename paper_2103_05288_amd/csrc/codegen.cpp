@@ -530,12 +530,12 @@ struct Gen {
   }
 
   void emit_load_store(const std::vector<char>& need, bool with_red) {
-    os << "  template <int V, class C> static DISC_DEV void load(const Args& A, const RowCtx& rc, C col, disc::Span sp, Slot<V>& s) {\n";
+    os << "  template <int V, int NT = 0, class C> static DISC_DEV void load(const Args& A, const RowCtx& rc, C col, disc::Span sp, Slot<V>& s) {\n";
     for (size_t i = 0; i < an.accesses.size(); ++i) {
       const Access& a = an.accesses[i];
       if (a.is_output || !a.has_inner || !need[i] || late(a)) continue;
-      os << "    disc::ld(s.a" << i << ", " << elem_ptr(a, fmt("A.p%d", a.slot)) << ", " << elem_base(a, i) << ", sp"
-         << (a.kind == ACC_FULL ? std::string(", rc.tail_ok") : std::string()) << ");\n";
+      os << "    disc::ld" << (a.kind == ACC_FULL ? "<(NT & 1) != 0>" : "") << "(s.a" << i << ", " << elem_ptr(a, fmt("A.p%d", a.slot)) << ", "
+         << elem_base(a, i) << ", sp" << (a.kind == ACC_FULL ? std::string(", rc.tail_ok") : std::string()) << ");\n";
     }
     if (with_red) {
       int k = 0;
@@ -547,11 +547,12 @@ struct Gen {
       }
     }
     os << "    (void)A; (void)rc; (void)col; (void)sp; (void)s;\n  }\n";
-    os << "  template <int V, class C> static DISC_DEV void store(const Args& A, const RowCtx& rc, C col, disc::Span sp, const OutSlot<V>& o) {\n";
+    os << "  template <int V, int NT = 0, class C> static DISC_DEV void store(const Args& A, const RowCtx& rc, C col, disc::Span sp, const OutSlot<V>& o) {\n";
     for (size_t i = 0; i < an.accesses.size(); ++i) {
       const Access& a = an.accesses[i];
       if (!a.is_output || !elem_output(a)) continue;
-      os << "    disc::st(" << elem_ptr(a, fmt("A.o%d", a.slot)) << ", " << elem_base(a, i) << ", o.o" << a.slot << ", sp);\n";
+      os << "    disc::st" << (a.kind == ACC_FULL ? "<(NT & 2) != 0>" : "") << "(" << elem_ptr(a, fmt("A.o%d", a.slot)) << ", " << elem_base(a, i)
+         << ", o.o" << a.slot << ", sp);\n";
     }
     os << "    (void)A; (void)rc; (void)col; (void)sp; (void)o;\n  }\n";
   }
@@ -909,6 +910,13 @@ struct Gen {
       k(name, fmt("disc::row_reg_body<Pat, %d, %d, %s>(A, rp);", v, nv, pipe), "RowPlan");
       if (staged && v > 1)
         k(name + "_s", fmt("disc::row_reg_body<PatT<true>, %d, %d, %s>(A, rp);", v, nv, pipe), "RowPlan", "PatT<true>");
+      // blocks of one wavefront quad, vector width: a version with non-temporal accesses of the
+      // full-size operands, which the host picks for rows that start and end on 16-byte boundaries
+      if (v > 1 && max_threads <= 256) {
+        k(name + "_nt", fmt("disc::row_reg_body<Pat, %d, %d, %s, 3>(A, rp);", v, nv, pipe), "RowPlan");
+        if (staged)
+          k(name + "_s_nt", fmt("disc::row_reg_body<PatT<true>, %d, %d, %s, 3>(A, rp);", v, nv, pipe), "RowPlan", "PatT<true>");
+      }
     };
     if (an.tmpl == DISC_TEMPLATE_LOOP) {
       k("k_loop_vec", fmt("disc::kloop_body<Pat, %d, 4, false>(A);", V), nullptr);

@@ -157,10 +157,21 @@ DISC_DEV T* at(T* p, I off) {
   return const_cast<T*>(at(const_cast<const T*>(p), off));
 }
 
-template <class T, int N, class I>
+// NT: non-temporal access, a compile-time constant of the kernel version (a run-time choice
+// between the two accesses is merged into one plain access by the optimiser).  For operands
+// and results that are touched exactly once the hint keeps them from displacing each other in the
+// L2 and the memory-side cache; the host picks the version per launch (the hint hurts short or
+// misaligned rows, whose cache lines are shared by neighbouring rows and so ARE touched twice).
+template <bool NT = false, class T, int N, class I>
 DISC_DEV void ld(Vec<T, N>& d, const T* __restrict__ p, I off, Span sp, bool whole_ok = false) {
   if (sp.full(N) || whole_ok) {
-    d.v = *reinterpret_cast<const typename Vec<T, N>::unaligned_t*>(at(p, off));
+    const auto* q = reinterpret_cast<const typename Vec<T, N>::unaligned_t*>(at(p, off));
+#ifdef DISC_NT_LD
+    d.v = __builtin_nontemporal_load(q);
+#else
+    if constexpr (NT) d.v = __builtin_nontemporal_load(q);
+    else d.v = *q;
+#endif
   } else {
     d.clear();
     ld_pieces<N / 2>(d, p, off, sp.n);
@@ -172,10 +183,16 @@ DISC_DEV void ld(Vec<T, N>& d, const T* __restrict__ p, I off, Span sp, bool who
   }
 }
 
-template <class T, int N, class I>
+template <bool NT = false, class T, int N, class I>
 DISC_DEV void st(T* __restrict__ p, I off, const Vec<T, N>& s, Span sp) {
   if (sp.full(N)) {
-    *reinterpret_cast<typename Vec<T, N>::unaligned_t*>(at(p, off)) = s.v;
+    auto* q = reinterpret_cast<typename Vec<T, N>::unaligned_t*>(at(p, off));
+#ifdef DISC_NT_ST
+    __builtin_nontemporal_store(s.v, q);
+#else
+    if constexpr (NT) __builtin_nontemporal_store(s.v, q);
+    else *q = s.v;
+#endif
   } else {
     st_pieces<N / 2>(p, off, s, sp.n);
   }
@@ -455,7 +472,8 @@ DISC_DEV void row_phases(const typename Pat::Args& A, const RowPlan& rp, typenam
   }
 }
 
-template <class Pat, int V, int NV, bool PIPE = true>
+// NT: bit 0 = non-temporal loads of the full-size operands, bit 1 = non-temporal stores
+template <class Pat, int V, int NV, bool PIPE = true, int NT = 0>
 DISC_DEV void row_reg_body(const typename Pat::Args& A, const RowPlan& rp) {
   __shared__ __attribute__((aligned(16))) char lds[2 * 16 * Pat::MAX_ACC_BYTES];
   // G <= 64: a power of two; G > 64: a multiple of 64
@@ -526,7 +544,7 @@ DISC_DEV void row_reg_body(const typename Pat::Args& A, const RowPlan& rp) {
     rc.sl = staged;
 #pragma unroll
     for (int j = 0; j < NV; ++j)
-      if (nvalid[j] > 0) Pat::template load<V>(A, rc, (unsigned)(col0 + j * rp.G * V), Span::upto(nvalid[j]), slot[j]);
+      if (nvalid[j] > 0) Pat::template load<V, NT>(A, rc, (unsigned)(col0 + j * rp.G * V), Span::upto(nvalid[j]), slot[j]);
   };
   // the row group of the block starts at row rw - grp_w; the block is done when that is past the end
   if (PIPE && rw - grp_w < rows) load_row();
@@ -556,7 +574,7 @@ DISC_DEV void row_reg_body(const typename Pat::Args& A, const RowPlan& rp) {
           if (nvalidn[j] > 0) {
             Span sn;            // the loads look at the element count only
             sn.n = nvalidn[j];
-            Pat::template load<V>(A, rcn, (unsigned)(col0n + j * rp.G * V), sn, nxt[j]);
+            Pat::template load<V, NT>(A, rcn, (unsigned)(col0n + j * rp.G * V), sn, nxt[j]);
           }
       }
       // keep the loads here: without a fence the compiler is free to sink them below the
@@ -578,7 +596,7 @@ DISC_DEV void row_reg_body(const typename Pat::Args& A, const RowPlan& rp) {
         // -- otherwise that wait sits right behind these stores and exposes their full latency
         // in every iteration.  The stores then have a whole iteration to drain.
         if (PIPE && j == 0) __builtin_amdgcn_s_waitcnt(0x0F70);
-        if (active) Pat::template store<V>(A, rc, (unsigned)col, span[j], o);
+        if (active) Pat::template store<V, NT>(A, rc, (unsigned)col, span[j], o);
       }
     }
     if (active && lane == 0) Pat::row_store(A, row, rc);

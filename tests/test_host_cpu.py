@@ -248,8 +248,16 @@ def test_row_schedule_capacity_steps(handles):
         assert (p["lanes_per_row"], p["slots_per_lane"], p["block"][0][0]) == (G, nv, block), (H, p)
         assert G * nv * 8 >= H
         want = "k_row_vec_nv%d%s" % (max(nv, 2 if block > 256 else 1), "w" if block > 256 else "")
-        assert p["kernels"][0].endswith(want + "_s") or p["kernels"][0].endswith(want), (H, p["kernels"])
+        name = p["kernels"][0]
+        # the non-temporal version: rows that start and end on 16-byte boundaries, 128 elements or
+        # more, blocks of 256 threads
+        assert name.endswith("_nt") == (H % 8 == 0 and H >= 128 and block == 256), (H, name)
+        name = name[:-3] if name.endswith("_nt") else name
+        assert name.endswith(want + "_s") or name.endswith(want), (H, p["kernels"])
     assert h.plan([50, 24577])["variant_name"] == "row_stream_vec"
+    # below 512 elements the non-temporal version needs rows of whole 128-byte lines in every operand
+    assert [h.plan([50, H])["kernels"][0].endswith("_nt") for H in (128, 200, 360, 384, 504, 512, 520)] == \
+        [True, False, False, True, False, True, True]
     # C4 stages a float32 row vector: 4 bytes x H must fit 48 KiB
     assert h.plan([50, 8192])["kernels"][0].endswith("_s") and h.plan([50, 8192])["lds_bytes"][0] >= 4 * 8192
     assert not h.plan([50, 16385])["kernels"][0].endswith("_s") and h.plan([50, 16385])["lds_bytes"][0] == 0
@@ -269,7 +277,9 @@ def test_single_shape_registration(ctx, handles):
     after = ctx.stats()
     assert a.id != b.id and again.id == a.id and a.id != handles["C4"].id
     assert after["compile_events"] == before["compile_events"] + 2 and after["pattern_cache_hits"] == before["pattern_cache_hits"] + 1
-    assert a.info["compile_events"] == 1 and a.info["n_variants"] == 1 and a.info["compile_ms"] > 0
+    # 2048-wide rows plan the non-temporal version; its plain sibling stays for misaligned operands
+    assert a.info["compile_events"] == 1 and a.info["n_variants"] == 2 and a.info["compile_ms"] > 0
+    assert b.info["n_variants"] == 1
     generic = handles["C4"].plan([300, 2048])
     pa = a.plan([300, 2048])
     for k in ("variant_name", "lanes_per_row", "slots_per_lane", "vec_width", "block", "lds_bytes", "algorithmic_bytes"):
@@ -277,7 +287,7 @@ def test_single_shape_registration(ctx, handles):
     assert pa["kernels"][0].split("_k_")[1] == generic["kernels"][0].split("_k_")[1]
     src = a.source
     assert "A.inner = 2048LL;" in src and "A.rows = 300LL;" in src and "rp.G = 128;" in src
-    assert src.count('extern "C" __global__') == 1
+    assert src.count('extern "C" __global__') == 2 and b.source.count('extern "C" __global__') == 1
     assert "A.inner = 2049LL;" in b.source
     expect("SHAPE", a.plan, [300, 2049])
     expect("SHAPE", a.plan, [301, 2048])

@@ -17,9 +17,9 @@ pytestmark = pytest.mark.gpu
 
 # row lengths chosen around the capacity steps 2 * 2^k and 3 * 2^k slots of 8 elements, plus ragged
 # tails 1..7 past a slot boundary
-ROW_LENGTHS = [1, 3, 7, 8, 9, 15, 17, 31, 33, 47, 63, 65, 97, 100, 127, 129, 191, 200, 255, 257, 385, 511, 513, 770,
-               1023, 1025, 1100, 1537, 2047, 2049, 3000, 3073, 4097, 5739, 6145, 8191, 8193, 12289, 16386, 20003,
-               24576, 24577]
+ROW_LENGTHS = [1, 3, 7, 8, 9, 15, 17, 31, 33, 47, 63, 65, 97, 100, 127, 128, 129, 191, 200, 255, 256, 257, 385, 511, 513,
+               768, 770, 1023, 1024, 1025, 1100, 1537, 2047, 2048, 2049, 3000, 3073, 4096, 4097, 5739, 6144, 6145, 8191,
+               8193, 12289, 16386, 20003, 24576, 24577]
 
 
 @pytest.fixture(scope="module")
@@ -56,6 +56,9 @@ def test_every_capacity_class_and_tail(ctx, cfg_name):
     assert {4, 8, 16, 32, 64, 128, 256, 512, 1024} <= lanes
     assert {n for v, g, n in seen if v == "row_reg_vec"} >= {1, 2, 3}
     assert any(v == "row_stream_vec" for v, g, n in seen)
+    # rows that start and end on 16-byte boundaries run the non-temporal versions
+    assert all(h.plan([5, H])["kernels"][0].endswith("_nt") for H in (128, 768, 2048, 6144))
+    assert not any(h.plan([5, H])["kernels"][0].endswith("_nt") for H in (64, 127, 2047, 8192))
 
 
 @pytest.mark.parametrize("cfg_name", ["C2", "C4"])
@@ -72,6 +75,48 @@ def test_many_rows_per_block_and_turning_grid(monkeypatch, cfg_name):
             plan = check(c, cfg_name, [T, H], seed=H, handle=h)
             rows_per_block = plan["block"][0][0] // plan["lanes_per_row"]
             assert T > plan["grid"][0][0] * rows_per_block, (H, T, plan["grid"], rows_per_block)
+    finally:
+        c.close()
+
+
+def test_non_temporal_versions_any_alignment(monkeypatch):
+    """The non-temporal kernel versions forced for every row length (the host rule keeps them to
+    aligned rows for speed; their results do not depend on alignment), and the host rule with
+    operands that are not 16-byte aligned: it must fall back to the plain version."""
+    from paper_2103_05288_amd import Context
+    monkeypatch.setenv("DISC_ROW_NT", "1")
+    c = Context(0)
+    try:
+        for cfg_name in ("C2", "C4"):
+            h = c.register(CONFIGS[cfg_name].pattern())
+            for H, T in [(9, 40), (127, 300), (1000, 77), (2047, 500), (3001, 2003), (6144, 300)]:
+                plan = check(c, cfg_name, [T, H], seed=H + 2, handle=h)
+                assert plan["kernels"][0].endswith("_nt"), plan["kernels"]
+    finally:
+        c.close()
+    monkeypatch.delenv("DISC_ROW_NT")
+    c = Context(0)
+    try:
+        cfg = CONFIGS["C4"]
+        pat = cfg.pattern()
+        h = c.register(pat)
+        dims = [33, 1024]
+        ins = cfg.inputs(dims, seed=3)
+        want = oracle_run(pat, dims, [to_oracle_input(t) for t in ins])[0]
+        dev = []
+        for t in ins:                       # every operand 2 bytes (bf16) or 1 byte past a 16-byte boundary
+            flat = torch.empty(t.numel() + 16, dtype=t.dtype, device="cuda")
+            view = flat[1:1 + t.numel()].view(t.shape)
+            view.copy_(t)
+            dev.append(view)
+        out_flat = torch.zeros(dims[0] * dims[1] + 16, dtype=torch.bfloat16, device="cuda")
+        out = out_flat[1:1 + dims[0] * dims[1]].view(dims)
+        assert h.plan(dims)["kernels"][0].endswith("_nt")              # no pointers: assumed aligned
+        assert not h.plan(dims, inputs=dev, outputs=[out])["kernels"][0].endswith("_nt")
+        h.launch(dims, dev, [out])
+        torch.cuda.synchronize()
+        assert_close(out.cpu(), want[0], "misaligned bases")
+        assert float(out_flat[0]) == 0.0 and float(out_flat[-1]) == 0.0
     finally:
         c.close()
 
