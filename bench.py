@@ -352,6 +352,10 @@ def main():
     torch.cuda.synchronize()
     t_copy = min(time_events(lambda: [ctx.util_copy(dst, src, n_copy) for _ in range(10)]) for _ in range(3)) / 10
     copy_gbps = 2 * n_copy / t_copy / 1e9
+    ctx.util_copy(dst, src, n_copy, non_temporal=True)
+    torch.cuda.synchronize()
+    t_copy_nt = min(time_events(lambda: [ctx.util_copy(dst, src, n_copy, non_temporal=True) for _ in range(10)]) for _ in range(3)) / 10
+    copy_nt_gbps = 2 * n_copy / t_copy_nt / 1e9
     del src, dst
     ctx.util_empty_launch()
     torch.cuda.synchronize()
@@ -397,6 +401,7 @@ def main():
         "pct_of_peak": round(100 * value / PEAK_HBM_GBPS, 2),
         "roofline": roofline,
         "copy_ceiling_GBps": round(copy_gbps, 1),
+        "copy_nt_ceiling_GBps": round(copy_nt_gbps, 1),
         "empty_launch_us": round(t_empty * 1e6, 2),
         "host_launch_us_per_call": round(host_idle_us, 2), "host_plan_us_per_call": round(plan_us, 3),
         "host_launch_us_per_call_queue_full": round(host_us, 2),

@@ -283,6 +283,8 @@ int disc_get_stats(disc_ctx* ctx, disc_stats_t* out);
  * practical bandwidth ceiling, and an empty kernel used as the launch-latency floor.
  * dst / src are device pointers, 16-byte aligned; bytes a multiple of 16. */
 int disc_util_copy(disc_ctx* ctx, void* dst, const void* src, size_t bytes, void* hip_stream);
+/* The same copy with non-temporal loads and stores (the faster of the two on large buffers). */
+int disc_util_copy_nt(disc_ctx* ctx, void* dst, const void* src, size_t bytes, void* hip_stream);
 int disc_util_empty_launch(disc_ctx* ctx, void* hip_stream);
 
 #ifdef __cplusplus

@@ -80,7 +80,7 @@ class DiscError(RuntimeError):
 EXPORTS = ("disc_create", "disc_destroy", "disc_last_error", "disc_register_pattern", "disc_register_pattern_static",
            "disc_pattern_info",
            "disc_pattern_source", "disc_workspace_bytes", "disc_plan", "disc_launch", "disc_force_variant",
-           "disc_get_stats", "disc_util_copy", "disc_util_empty_launch", "disc_register_graph", "disc_graph_info",
+           "disc_get_stats", "disc_util_copy", "disc_util_copy_nt", "disc_util_empty_launch", "disc_register_graph", "disc_graph_info",
            "disc_graph_workspace_bytes", "disc_graph_launch")
 
 _lib = None
@@ -124,6 +124,7 @@ def load_library():
     lib.disc_force_variant.argtypes = [vp, C.c_int]
     lib.disc_get_stats.argtypes = [vp, C.POINTER(disc_stats_t)]
     lib.disc_util_copy.argtypes = [vp, vp, vp, C.c_size_t, vp]
+    lib.disc_util_copy_nt.argtypes = [vp, vp, vp, C.c_size_t, vp]
     lib.disc_util_empty_launch.argtypes = [vp, vp]
     _lib = lib
     return lib
@@ -344,11 +345,12 @@ class Context:
         d["variant_count"] = {VARIANTS[i]: s.variant_count[i] for i in range(len(VARIANTS)) if s.variant_count[i]}
         return d
 
-    def util_copy(self, dst, src, nbytes: int, stream: Optional[int] = None):
+    def util_copy(self, dst, src, nbytes: int, stream: Optional[int] = None, non_temporal: bool = False):
         if stream is None:
             import torch
             stream = torch.cuda.current_stream().cuda_stream
-        self._check(self.lib.disc_util_copy(self.h, C.c_void_p(_ptr(dst)), C.c_void_p(_ptr(src)),
+        fn = self.lib.disc_util_copy_nt if non_temporal else self.lib.disc_util_copy
+        self._check(fn(self.h, C.c_void_p(_ptr(dst)), C.c_void_p(_ptr(src)),
                                             C.c_size_t(nbytes), C.c_void_p(stream)))
 
     def util_empty_launch(self, stream: Optional[int] = None):

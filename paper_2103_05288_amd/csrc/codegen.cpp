@@ -920,6 +920,7 @@ struct Gen {
     };
     if (an.tmpl == DISC_TEMPLATE_LOOP) {
       k("k_loop_vec", fmt("disc::kloop_body<Pat, %d, 4, false>(A);", V), nullptr);
+      if (V > 1) k("k_loop_vec_nt", fmt("disc::kloop_body<Pat, %d, 4, false, 3>(A);", V), nullptr);
       k("k_loop_vec_i64", fmt("disc::kloop_body<Pat, %d, 1, true>(A);", V), nullptr);
       k("k_loop_scalar", "disc::kloop_body<Pat, 1, 4, false>(A);", nullptr);
       k("k_loop_scalar_i64", "disc::kloop_body<Pat, 1, 1, true>(A);", nullptr);
@@ -948,6 +949,7 @@ struct Gen {
       k("k_col_strip_scalar", fmt("disc::col_strip_body<Pat, %s, 1>(A, rp);", epi), "ColPlan");
       if (has_elem_outputs()) {
         k("k_col_epi_vec", fmt("disc::kloop_body<PatE, %d, 4, false>(A);", V), nullptr);
+        if (V > 1) k("k_col_epi_vec_nt", fmt("disc::kloop_body<PatE, %d, 4, false, 3>(A);", V), nullptr);
         k("k_col_epi_vec_i64", fmt("disc::kloop_body<PatE, %d, 1, true>(A);", V), nullptr);
         k("k_col_epi_scalar", "disc::kloop_body<PatE, 1, 4, false>(A);", nullptr);
         k("k_col_epi_scalar_i64", "disc::kloop_body<PatE, 1, 1, true>(A);", nullptr);

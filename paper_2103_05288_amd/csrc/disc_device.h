@@ -329,7 +329,8 @@ DISC_DEV void group_allreduce(typename Pat::template Acc<P>& acc, int G) {
 // slot list with a grid stride, U slots in flight per lane to keep enough bytes in flight
 // for HBM.  (row, col) of a slot come from one multiply-shift division per slot.
 // =======================================================================================
-template <class Pat, int V, int U, bool I64>
+// NT: bit 0 = non-temporal loads of the full-size operands, bit 1 = non-temporal stores
+template <class Pat, int V, int U, bool I64, int NT = 0>
 DISC_DEV void kloop_body(const typename Pat::Args& A) {
   if constexpr (!I64) {
     const u32 nslots = (u32)A.nslots;
@@ -348,7 +349,7 @@ DISC_DEV void kloop_body(const typename Pat::Args& A) {
           col[u] = (int)((s - row * A.spr_div.d) * V);
           nv[u] = min((int)V, (int)(inner - (u32)col[u]));
           Pat::row_begin(A, (i64)row, rc[u]);
-          Pat::template load<V>(A, rc[u], col[u], Span::upto(nv[u]), slot[u]);
+          Pat::template load<V, NT>(A, rc[u], col[u], Span::upto(nv[u]), slot[u]);
         }
       }
 #pragma unroll
@@ -357,7 +358,7 @@ DISC_DEV void kloop_body(const typename Pat::Args& A) {
           typename Pat::template OutSlot<V> o;
           typename Pat::template Keep<V> kp;
           Pat::template epilogue<V, false>(A, rc[u], slot[u], kp, col[u], Span::upto(nv[u]), o);
-          Pat::template store<V>(A, rc[u], col[u], Span::upto(nv[u]), o);
+          Pat::template store<V, NT>(A, rc[u], col[u], Span::upto(nv[u]), o);
         }
       }
     }
@@ -373,11 +374,11 @@ DISC_DEV void kloop_body(const typename Pat::Args& A) {
       typename Pat::template Slot<V> slot;
       typename Pat::RowCtx rc;
       Pat::row_begin(A, row, rc);
-      Pat::template load<V>(A, rc, col, Span::upto(nv), slot);
+      Pat::template load<V, NT>(A, rc, col, Span::upto(nv), slot);
       typename Pat::template OutSlot<V> o;
       typename Pat::template Keep<V> kp;
       Pat::template epilogue<V, false>(A, rc, slot, kp, col, Span::upto(nv), o);
-      Pat::template store<V>(A, rc, col, Span::upto(nv), o);
+      Pat::template store<V, NT>(A, rc, col, Span::upto(nv), o);
     }
   }
 }

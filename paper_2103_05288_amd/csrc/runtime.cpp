@@ -125,7 +125,7 @@ struct disc_ctx {
   disc_stats_t stats{};
   int force_variant = -1;
   hipModule_t util_module = nullptr;
-  hipFunction_t util_copy = nullptr, util_empty = nullptr;
+  hipFunction_t util_copy = nullptr, util_copy_nt = nullptr, util_empty = nullptr;
   int row_target_nv = 3;     // tuning knobs, overridable from the environment for experiments
   int grid_mult = 8;
   int row_nt = -1;           // non-temporal row versions: -1 = host rule, 0 = never, 1 = wherever the version exists
@@ -261,8 +261,11 @@ struct FullPlan {
 
 // Loop-fusion launch geometry for an iteration space [rows, inner]; shared by loop patterns and
 // by the epilogue stage of column reduces.  want_vec / want_i64: -1 = let the shape decide.
+// nt_name: the non-temporal sibling of names[0] (vector width, 32-bit index), taken for large
+// launches (8 Mi elements or more: nothing of them stays in a cache anyway) whose rows start on
+// 16-byte boundaries (`aligned`: the full-size operands are; inner a multiple of the width).
 int plan_loop(disc_ctx* c, int64_t rows, int64_t inner, int V, int want_vec, int want_i64, const char* const names[4],
-              FullPlan* fp, LaunchRec* L, bool* vec_out, bool* i64_out) {
+              const char* nt_name, bool aligned, FullPlan* fp, LaunchRec* L, bool* vec_out, bool* i64_out) {
   bool vec;
   {
     const int64_t spr_v = (inner + V - 1) / V;
@@ -281,6 +284,9 @@ int plan_loop(disc_ctx* c, int64_t rows, int64_t inner, int V, int want_vec, int
   int64_t blocks = (nslots + 256ll * U - 1) / (256ll * U);
   blocks = std::min(blocks, i64 ? max_grid * 4 : max_grid);
   L->kernel = names[(vec ? 0 : 2) + (i64 ? 1 : 0)];
+  if (nt_name && vec && v > 1 && !i64 && aligned && inner % v == 0 && c->row_nt != 0 &&
+      (c->row_nt > 0 || nslots >= (8ll << 20) / v))
+    L->kernel = nt_name;
   L->grid[0] = (uint32_t)blocks;
   L->block = 256;
   fp->nslots = nslots;
@@ -310,6 +316,15 @@ int make_plan(disc_ctx* c, const Pattern& p, const int64_t* dims, int n_dims, in
   }
   int rc = shape_calc(c, p, dims, n_dims, &fp->sv);
   if (rc) return rc;
+  // every full-size operand on a 16-byte boundary (null pointer arrays: assumed)
+  auto full_aligned = [&]() {
+    for (const Access& a : p.an.accesses) {
+      if (a.kind != ACC_FULL) continue;
+      const void* ptr = a.is_output ? (outputs ? outputs[a.slot] : nullptr) : (inputs ? inputs[a.slot] : nullptr);
+      if (reinterpret_cast<uintptr_t>(ptr) % 16 != 0) return false;
+    }
+    return true;
+  };
   const Analysis& an = p.an;
   const ShapeVals& sv = fp->sv;
   disc_plan_t& pub = fp->pub;
@@ -334,7 +349,7 @@ int make_plan(disc_ctx* c, const Pattern& p, const int64_t* dims, int n_dims, in
     }
     static const char* const names[] = {"k_loop_vec", "k_loop_vec_i64", "k_loop_scalar", "k_loop_scalar_i64"};
     bool vec, i64;
-    rc = plan_loop(c, sv.rows, sv.inner, V, want_vec, want_i64, names, fp, &fp->launches[0], &vec, &i64);
+    rc = plan_loop(c, sv.rows, sv.inner, V, want_vec, want_i64, names, "k_loop_vec_nt", full_aligned(), fp, &fp->launches[0], &vec, &i64);
     if (rc) return rc;
     pub.variant = vec ? (i64 ? DISC_V_LOOP_VEC_I64 : DISC_V_LOOP_VEC) : (i64 ? DISC_V_LOOP_SCALAR_I64 : DISC_V_LOOP_SCALAR);
     pub.n_launches = 1;
@@ -560,7 +575,7 @@ int make_plan(disc_ctx* c, const Pattern& p, const int64_t* dims, int n_dims, in
     if (p.gen.has_epilogue) {
       static const char* const names[] = {"k_col_epi_vec", "k_col_epi_vec_i64", "k_col_epi_scalar", "k_col_epi_scalar_i64"};
       bool v2, i64;
-      rc = plan_loop(c, sv.rows, inner, V, vec ? 1 : 0, -1, names, fp, &fp->launches[2], &v2, &i64);
+      rc = plan_loop(c, sv.rows, inner, V, vec ? 1 : 0, -1, names, "k_col_epi_vec_nt", full_aligned(), fp, &fp->launches[2], &v2, &i64);
       if (rc) return rc;
       pub.n_launches = 3;
     } else {
@@ -622,24 +637,29 @@ void fill_args(const Pattern& p, const FullPlan& fp, const int64_t* dims, const 
 
 const char* kUtilSource = R"SRC(
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
-extern "C" __global__ void __launch_bounds__(256) disc_util_copy_k(u32x4* __restrict__ dst, const u32x4* __restrict__ src, long long n) {
+template <bool NT>
+__device__ __forceinline__ void copy_body(u32x4* __restrict__ dst, const u32x4* __restrict__ src, long long n) {
   const long long stride = (long long)gridDim.x * blockDim.x;
   long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
   for (; i + 3 * stride < n; i += 4 * stride) {
-#ifdef DISC_NT_LD
-    u32x4 a = __builtin_nontemporal_load(src + i), b = __builtin_nontemporal_load(src + i + stride),
-          c = __builtin_nontemporal_load(src + i + 2 * stride), d = __builtin_nontemporal_load(src + i + 3 * stride);
-#else
-    u32x4 a = src[i], b = src[i + stride], c = src[i + 2 * stride], d = src[i + 3 * stride];
-#endif
-#ifdef DISC_NT_ST
-    __builtin_nontemporal_store(a, dst + i); __builtin_nontemporal_store(b, dst + i + stride);
-    __builtin_nontemporal_store(c, dst + i + 2 * stride); __builtin_nontemporal_store(d, dst + i + 3 * stride);
-#else
-    dst[i] = a; dst[i + stride] = b; dst[i + 2 * stride] = c; dst[i + 3 * stride] = d;
-#endif
+    u32x4 a, b, c, d;
+    if constexpr (NT) {
+      a = __builtin_nontemporal_load(src + i); b = __builtin_nontemporal_load(src + i + stride);
+      c = __builtin_nontemporal_load(src + i + 2 * stride); d = __builtin_nontemporal_load(src + i + 3 * stride);
+      __builtin_nontemporal_store(a, dst + i); __builtin_nontemporal_store(b, dst + i + stride);
+      __builtin_nontemporal_store(c, dst + i + 2 * stride); __builtin_nontemporal_store(d, dst + i + 3 * stride);
+    } else {
+      a = src[i]; b = src[i + stride]; c = src[i + 2 * stride]; d = src[i + 3 * stride];
+      dst[i] = a; dst[i + stride] = b; dst[i + 2 * stride] = c; dst[i + 3 * stride] = d;
+    }
   }
   for (; i < n; i += stride) dst[i] = src[i];
+}
+extern "C" __global__ void __launch_bounds__(256) disc_util_copy_k(u32x4* __restrict__ dst, const u32x4* __restrict__ src, long long n) {
+  copy_body<false>(dst, src, n);
+}
+extern "C" __global__ void __launch_bounds__(256) disc_util_copy_nt_k(u32x4* __restrict__ dst, const u32x4* __restrict__ src, long long n) {
+  copy_body<true>(dst, src, n);
 }
 extern "C" __global__ void disc_util_empty_k() {}
 )SRC";
@@ -654,6 +674,7 @@ int ensure_util(disc_ctx* c) {
   hipError_t e = hipModuleLoadData(&c->util_module, code.data());
   if (e != hipSuccess) return hip_fail(c, e, "hipModuleLoadData");
   if ((e = hipModuleGetFunction(&c->util_copy, c->util_module, "disc_util_copy_k")) != hipSuccess) return hip_fail(c, e, "hipModuleGetFunction");
+  if ((e = hipModuleGetFunction(&c->util_copy_nt, c->util_module, "disc_util_copy_nt_k")) != hipSuccess) return hip_fail(c, e, "hipModuleGetFunction");
   if ((e = hipModuleGetFunction(&c->util_empty, c->util_module, "disc_util_empty_k")) != hipSuccess) return hip_fail(c, e, "hipModuleGetFunction");
   return DISC_OK;
 }
@@ -995,7 +1016,7 @@ int disc_get_stats(disc_ctx* ctx, disc_stats_t* out) {
   return DISC_OK;
 }
 
-int disc_util_copy(disc_ctx* ctx, void* dst, const void* src, size_t bytes, void* hip_stream) {
+static int util_copy_impl(disc_ctx* ctx, void* dst, const void* src, size_t bytes, void* hip_stream, bool nt) {
   if (!ctx || !dst || !src || (bytes & 15) || ((uintptr_t)dst & 15) || ((uintptr_t)src & 15))
     return set_err(ctx, DISC_ERR_INVALID_ARG, "copy needs 16-byte aligned pointers and size");
   int rc = ensure_util(ctx);
@@ -1004,8 +1025,17 @@ int disc_util_copy(disc_ctx* ctx, void* dst, const void* src, size_t bytes, void
   if (n == 0) return DISC_OK;
   void* args[] = {&dst, &src, &n};
   long long blocks = std::min<long long>((n + 1023) / 1024, (long long)ctx->n_cus * 2);
-  hipError_t e = hipModuleLaunchKernel(ctx->util_copy, (uint32_t)blocks, 1, 1, 256, 1, 1, 0, (hipStream_t)hip_stream, args, nullptr);
+  hipError_t e = hipModuleLaunchKernel(nt ? ctx->util_copy_nt : ctx->util_copy, (uint32_t)blocks, 1, 1, 256, 1, 1, 0,
+                                       (hipStream_t)hip_stream, args, nullptr);
   return e == hipSuccess ? DISC_OK : hip_fail(ctx, e, "hipModuleLaunchKernel");
+}
+
+int disc_util_copy(disc_ctx* ctx, void* dst, const void* src, size_t bytes, void* hip_stream) {
+  return util_copy_impl(ctx, dst, src, bytes, hip_stream, false);
+}
+
+int disc_util_copy_nt(disc_ctx* ctx, void* dst, const void* src, size_t bytes, void* hip_stream) {
+  return util_copy_impl(ctx, dst, src, bytes, hip_stream, true);
 }
 
 int disc_util_empty_launch(disc_ctx* ctx, void* hip_stream) {

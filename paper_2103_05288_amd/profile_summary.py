@@ -76,8 +76,8 @@ def main():
         r = b["roofline"]
         lines.append("")
         lines.append("bench.py's own line from the same run (HIP events around every call):")
-        lines.append("  value %.1f GB/s (%.2f %% of 8 TB/s), copy ceiling %.1f GB/s"
-                     % (b["value"], b["pct_of_peak"], b["copy_ceiling_GBps"]))
+        lines.append("  value %.1f GB/s (%.2f %% of 8 TB/s), copy ceiling %.1f GB/s (non-temporal copy %.1f GB/s)"
+                     % (b["value"], b["pct_of_peak"], b["copy_ceiling_GBps"], b.get("copy_nt_ceiling_GBps", float("nan"))))
         lines.append("  roofline kernel %s: %d launches, avg %.2f us by HIP events, %.1f GB/s algorithmic"
                      % (r["kernel"], r["launches"], r["avg_launch_us"], r["achieved"]))
         for cfg, pc in b["per_config"].items():

@@ -92,11 +92,19 @@ def test_non_temporal_versions_any_alignment(monkeypatch):
             for H, T in [(9, 40), (127, 300), (1000, 77), (2047, 500), (3001, 2003), (6144, 300)]:
                 plan = check(c, cfg_name, [T, H], seed=H + 2, handle=h)
                 assert plan["kernels"][0].endswith("_nt"), plan["kernels"]
+        # the loop-fusion kernel and the epilogue of a column reduce have such versions too
+        plan = check(c, "C0", [300, 768], seed=9)
+        assert plan["kernels"][0].endswith("k_loop_vec_nt"), plan["kernels"]
+        plan = check(c, "C3", [3000, 1024], seed=10)
+        assert plan["kernels"][-1].endswith("k_col_epi_vec_nt"), plan["kernels"]
     finally:
         c.close()
     monkeypatch.delenv("DISC_ROW_NT")
     c = Context(0)
     try:
+        # host rule for the loop kernels: large launches only
+        h0 = c.register(CONFIGS["C0"].pattern())
+        assert h0.plan([20000, 768])["kernels"][0].endswith("_nt") and not h0.plan([300, 768])["kernels"][0].endswith("_nt")
         cfg = CONFIGS["C4"]
         pat = cfg.pattern()
         h = c.register(pat)
