@@ -11,7 +11,9 @@
 #include <chrono>
 #include <cstdlib>
 #include <cstring>
+#include <functional>
 #include <memory>
+#include <set>
 #include <sstream>
 
 #include "disc_internal.hpp"
@@ -106,6 +108,7 @@ struct Graph {
   std::vector<disc_op> ops;
   std::vector<disc_constraint> cs;
   std::vector<int> group_of_op;  // -1 for leaves and OUTPUT ops
+  std::vector<char> remat;       // value is recomputed by the patterns that read it instead of crossing a cut
   std::vector<GraphGroup> groups;
   std::vector<GraphIntermediate> inter;
   std::map<int, int> inter_of_value;
@@ -1070,21 +1073,28 @@ int op_arity(const disc_op& o) {
 // outside S become PARAMs (scalar leaves are copied instead), values of S read outside S (by ops
 // of other groups or by graph OUTPUTs) become OUTPUTs, constraints between values that both
 // appear are carried over.
+// `final_cut` false (while the cut is still growing): every value read outside S counts as an
+// output, also those that readers will recompute, so that a candidate always has an output.
 void build_sub_pattern(const Graph& g, const std::vector<int>& S, const std::vector<char>& in_S,
                        std::vector<disc_op>* sub, std::vector<disc_constraint>* sub_cs, std::vector<int>* in_values,
-                       std::vector<int>* out_values) {
+                       std::vector<int>* out_values, bool final_cut) {
   std::map<int, int> id_of;   // graph value -> sub-pattern value
   sub->clear();
   sub_cs->clear();
   in_values->clear();
   out_values->clear();
-  auto operand = [&](int v) {
+  std::function<int(int)> operand = [&](int v) -> int {
     auto it = id_of.find(v);
     if (it != id_of.end()) return it->second;
     const disc_op& src = g.ops[v];
     disc_op o = src;
     if (src.opcode == DISC_CONST || src.opcode == DISC_DIM_SIZE) {
       for (int k = 0; k < 3; ++k) o.in[k] = -1;
+    } else if (!is_leaf(src.opcode) && g.remat[v]) {
+      // a cheap element-wise function of graph inputs computed by another pattern: computed again
+      // here, from the inputs, instead of being written out and read back
+      const int n = op_arity(src);
+      for (int k = 0; k < n; ++k) o.in[k] = operand(src.in[k]);
     } else {               // a graph input or a value of another group: a PARAM of its type and shape
       o.opcode = DISC_PARAM;
       for (int k = 0; k < 3; ++k) o.in[k] = -1;
@@ -1096,13 +1106,6 @@ void build_sub_pattern(const Graph& g, const std::vector<int>& S, const std::vec
     id_of[v] = (int)sub->size() - 1;
     return id_of[v];
   };
-  for (int v : S) {
-    disc_op o = g.ops[v];
-    const int n = op_arity(o);
-    for (int k = 0; k < n; ++k) o.in[k] = operand(g.ops[v].in[k]);
-    sub->push_back(o);
-    id_of[v] = (int)sub->size() - 1;
-  }
   // consumers outside S
   std::vector<char> read_outside(g.ops.size(), 0);
   for (size_t i = 0; i < g.ops.size(); ++i) {
@@ -1111,7 +1114,26 @@ void build_sub_pattern(const Graph& g, const std::vector<int>& S, const std::vec
     if (is_leaf(o.opcode)) continue;
     const int n = op_arity(o);
     for (int k = 0; k < n; ++k)
-      if (o.in[k] >= 0 && in_S[o.in[k]]) read_outside[o.in[k]] = 1;
+      if (o.in[k] >= 0 && in_S[o.in[k]] && (!final_cut || o.opcode == DISC_OUTPUT || !g.remat[o.in[k]])) read_outside[o.in[k]] = 1;
+  }
+  // ops of S that only fed readers which now recompute them are left out of the final pattern
+  std::vector<char> live(g.ops.size(), final_cut ? 0 : 1);
+  if (final_cut)
+    for (size_t r = S.size(); r-- > 0;) {
+      const int v = S[r];
+      if (read_outside[v]) live[v] = 1;
+      if (!live[v]) continue;
+      const int n = op_arity(g.ops[v]);
+      for (int k = 0; k < n; ++k)
+        if (in_S[g.ops[v].in[k]]) live[g.ops[v].in[k]] = 1;
+    }
+  for (int v : S) {
+    if (!live[v]) continue;
+    disc_op o = g.ops[v];
+    const int n = op_arity(o);
+    for (int k = 0; k < n; ++k) o.in[k] = operand(g.ops[v].in[k]);
+    sub->push_back(o);
+    id_of[v] = (int)sub->size() - 1;
   }
   for (int v : S)
     if (read_outside[v]) {
@@ -1209,6 +1231,33 @@ int disc_register_graph(disc_ctx* ctx, const disc_op* ops, int n_ops, const disc
   if (g->n_sym > DISC_MAX_DIMS) return set_err(ctx, DISC_ERR_BAD_PATTERN, "too many symbolic dims");
   if (compute.empty() || g->n_outputs == 0) return set_err(ctx, DISC_ERR_BAD_PATTERN, "nothing to compute");
 
+  // Values that are cheap element-wise functions of at most two graph inputs (a cast of an input,
+  // an input plus a broadcast bias, ...) do not cross cuts: a pattern that reads one computes it
+  // again from the inputs, which costs no more traffic than reading the stored result and saves
+  // writing it.
+  g->remat.assign(n_ops, 0);
+  {
+    std::vector<std::set<int>> cone_params(n_ops);
+    std::vector<int> cone_ops(n_ops, 0);
+    for (int i = 0; i < n_ops; ++i) {
+      const disc_op& o = g->ops[i];
+      if (o.opcode == DISC_PARAM) { cone_params[i].insert(i); continue; }
+      if (is_leaf(o.opcode) || o.opcode == DISC_OUTPUT) continue;
+      if (o.opcode >= DISC_REDUCE_SUM && o.opcode <= DISC_REDUCE_ARGMAX) continue;
+      bool ok = true;
+      int nops = 1;
+      const int n = op_arity(o);
+      for (int k = 0; k < n && ok; ++k) {
+        const int a = o.in[k];
+        if (!is_leaf(g->ops[a].opcode) && !g->remat[a]) ok = false;
+        cone_params[i].insert(cone_params[a].begin(), cone_params[a].end());
+        nops += cone_ops[a];
+      }
+      cone_ops[i] = nops;
+      if (ok && cone_params[i].size() <= 2 && nops <= 8) g->remat[i] = 1;
+    }
+  }
+
   // greedy cut in list order: an op joins the current pattern when the checker still accepts the
   // pattern with it (one provable iteration space, one template); otherwise it opens the next one
   std::vector<disc_op> sub;
@@ -1217,7 +1266,7 @@ int disc_register_graph(disc_ctx* ctx, const disc_op* ops, int n_ops, const disc
   auto fusible = [&](const std::vector<int>& S, std::string* why) {
     std::vector<char> in_S(n_ops, 0);
     for (int v : S) in_S[v] = 1;
-    build_sub_pattern(*g, S, in_S, &sub, &sub_cs, &ins, &outs);
+    build_sub_pattern(*g, S, in_S, &sub, &sub_cs, &ins, &outs, false);
     Analysis an;
     return analyze(sub.data(), (int)sub.size(), sub_cs.empty() ? nullptr : sub_cs.data(), (int)sub_cs.size(), &an, why);
   };
@@ -1305,7 +1354,7 @@ int disc_register_graph(disc_ctx* ctx, const disc_op* ops, int n_ops, const disc
     gr.ops = cuts[gi];
     std::vector<char> in_S(n_ops, 0);
     for (int v : gr.ops) { in_S[v] = 1; g->group_of_op[v] = (int)gi; }
-    build_sub_pattern(*g, gr.ops, in_S, &sub, &sub_cs, &gr.in_values, &gr.out_values);
+    build_sub_pattern(*g, gr.ops, in_S, &sub, &sub_cs, &gr.in_values, &gr.out_values, true);
     if (gr.out_values.empty()) { gr.pattern_id = -1; g->groups.push_back(gr); continue; }   // dead code: nothing reads it
     int32_t pid = -1;
     int rc = disc_register_pattern(ctx, sub.data(), (int)sub.size(), sub_cs.empty() ? nullptr : sub_cs.data(),

@@ -50,6 +50,32 @@ def chain_graph(n_stages=4):
     return pb.build()
 
 
+def layernorm_backward_graph():
+    """dx, dgamma, dbeta of LayerNorm from x, dy, gamma: three dependent row reductions for dx and two
+    column reductions that need the normalised activations again -- row and column reductions in
+    one op list, which is never one pattern."""
+    pb = PatternBuilder("ln_bwd")
+    T, H = pb.dims(2)
+    x = pb.cast(pb.param("bf16", [T, H]), "f32")
+    dy = pb.cast(pb.param("bf16", [T, H]), "f32")
+    gam = pb.param("f32", [H])
+    row = lambda v: pb.broadcast(v, [T, H], [0])
+    col = lambda v: pb.broadcast(v, [T, H], [1])
+    mean = pb.op("div", pb.reduce("sum", x, 1), pb.dim_size(H))
+    xc = pb.op("sub", x, row(mean))
+    var = pb.op("div", pb.reduce("sum", pb.op("mul", xc, xc), 1), pb.dim_size(H))
+    rstd = pb.op("rsqrt", pb.op("add", var, pb.const(1e-5)))
+    xhat = pb.op("mul", xc, row(rstd))
+    g = pb.op("mul", dy, col(gam))
+    c1 = pb.op("div", pb.reduce("sum", g, 1), pb.dim_size(H))
+    c2 = pb.op("div", pb.reduce("sum", pb.op("mul", g, xhat), 1), pb.dim_size(H))
+    dx = pb.op("mul", pb.op("sub", pb.op("sub", g, row(c1)), pb.op("mul", xhat, row(c2))), row(rstd))
+    pb.output(pb.cast(dx, "bf16"))
+    pb.output(pb.reduce("sum", pb.op("mul", dy, xhat), 0))     # dgamma
+    pb.output(pb.reduce("sum", dy, 0))                          # dbeta
+    return pb.build()
+
+
 @pytest.fixture(scope="module")
 def hctx():
     from paper_2103_05288_amd import Context
@@ -96,6 +122,17 @@ def test_buffers_are_shared_by_lifetime(hctx):
     assert one["n_patterns"] == 1 and one["n_buffers"] == 0
 
 
+def test_row_and_column_reductions_in_one_graph(hctx):
+    g = hctx.register_graph(layernorm_backward_graph())
+    info = g.info
+    t = [hctx.pattern_info(p)["template"] for p in info["pattern_id"][:info["n_patterns"]]]
+    assert t == ["row_reduce", "col_reduce"], t
+    assert hctx.pattern_info(info["pattern_id"][0])["n_phases"] == 3
+    # the normalised activations cross the cut: one fp32 buffer of T * H elements
+    assert info["n_intermediates"] == 1 and info["n_buffers"] == 1
+    assert g.workspace_bytes([64, 100]) >= 64 * 100 * 4
+
+
 def test_graph_errors(hctx):
     from paper_2103_05288_amd import DiscError
     pb = PatternBuilder()
@@ -121,12 +158,13 @@ def test_graph_errors(hctx):
 
 
 @pytest.mark.gpu
-@pytest.mark.parametrize("which", ["block", "block_inter", "chain"])
+@pytest.mark.parametrize("which", ["block", "block_inter", "chain", "ln_bwd"])
 def test_graph_matches_oracle(which):
     from oracle import run as oracle_run
     from paper_2103_05288_amd import Context
     from tests.util import assert_close, to_oracle_input
-    pat = {"block": block_graph(), "block_inter": block_graph(False), "chain": chain_graph(5)}[which]
+    pat = {"block": block_graph(), "block_inter": block_graph(False), "chain": chain_graph(5),
+           "ln_bwd": layernorm_backward_graph()}[which]
     ctx = Context(0)
     try:
         g = ctx.register_graph(pat)
@@ -144,6 +182,19 @@ def test_graph_matches_oracle(which):
             torch.cuda.synchronize()
             want = oracle_run(pat, dims, [to_oracle_input(t) for t in ins])[0]
             for k, (o, w) in enumerate(zip(outs, want)):
+                if which == "ln_bwd" and k > 0:
+                    # Column sums of T terms of mixed sign: the element-wise bar relative to the
+                    # (cancelled) result does not apply.  Each term reaches the sum through at most 8
+                    # fp32 roundings (centring, rstd, two products, the stored intermediate), the sum
+                    # itself runs in fp64: |err| <= 8 * 2^-24 * sum_t |term_t| + 1e-6.
+                    x64, dy64 = ins[0].double().numpy(), ins[1].double().numpy()
+                    xc = x64 - x64.mean(1, keepdims=True)
+                    xhat = xc / np.sqrt((xc * xc).mean(1, keepdims=True) + 1e-5)
+                    terms = np.abs(dy64 * xhat) if k == 1 else np.abs(dy64)
+                    lim = 8 * 2.0 ** -24 * terms.sum(0) + 1e-6
+                    err = np.abs(o.cpu().double().numpy() - np.asarray(w, dtype=np.float64))
+                    assert (err <= lim).all(), (which, dims, k, float((err / lim).max()))
+                    continue
                 assert_close(o.cpu(), w, f"graph {which} dims={dims} out{k}")
     finally:
         ctx.close()
