@@ -31,6 +31,12 @@ with those standard meanings:
 * reduce_{sum,max,min}    : over exactly one axis, the axis is dropped
 * reduce_argmax           : lowest index among the maxima, int64
 * dim_size                : the runtime size of a symbolic dimension, as a scalar
+* slice                   : dynamic slice with stride 1 (Section 4.1 uses it as the example of an
+                            op whose former attributes -- the start indices -- are runtime
+                            values): result[i0, i1, ...] = x[s0 + i0, s1 + i1, ...]; the
+                            result sizes are the op's dims, the starts come from the
+                            runtime dims (or are static); a slice that leaves the operand
+                            is an error
 
 Inputs stored as f16 / bf16 are converted to float64 by the caller (every such
 value is exactly representable); the oracle itself only sees numpy arrays.
@@ -199,6 +205,15 @@ def _run(pattern, dims, inputs):
                 v = np.min(x, axis=ax)
             else:
                 v = np.argmax(x, axis=ax).astype(np.int64)  # first occurrence
+        elif oc == "slice":
+            x = vals[op.ins[0]]
+            if len(op.axis_map) != x.ndim or len(want) != x.ndim:
+                raise OracleError(f"op {idx}: slice needs one start and one size per axis")
+            starts = [dims[a] if a >= 0 else -1 - a for a in op.axis_map]
+            for k, (s0, n) in enumerate(zip(starts, want)):
+                if s0 < 0 or s0 + n > x.shape[k]:
+                    raise OracleError(f"op {idx}: slice [{s0}, {s0 + n}) leaves axis {k} of size {x.shape[k]}")
+            v = x[tuple(slice(s0, s0 + n) for s0, n in zip(starts, want))].copy()
         elif oc == "output":
             v = vals[op.ins[0]]
             outs.append(v)

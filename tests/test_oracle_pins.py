@@ -379,3 +379,72 @@ def test_c4_invariants():
     for h in range(H):
         qh = 0.0 if mask[t, h] else e[h] / ssum
         assert abs(y32[t, h] - (qh + x[t, h] / math.sqrt(ssum))) < 1e-14
+
+
+# ---------------------------------------------------------------- dynamic slice (Section 4.1)
+def _slice_pattern(rank, static_axes=()):
+    """out = slice(x): start and size of every axis are runtime values, except the axes in
+    ``static_axes``, which start at the static index 1 and have the static size 2."""
+    pb = PatternBuilder()
+    src = pb.dims(rank)
+    starts, sizes = [], []
+    for k in range(rank):
+        if k in static_axes:
+            starts.append(pb.static_start(1))
+            sizes.append(pb.static(2))
+        else:
+            starts.append(pb.dim())
+            sizes.append(pb.dim())
+    x = pb.param("f32", src)
+    pb.output(pb.slice(x, starts, sizes))
+    return pb.build(), starts, sizes
+
+
+def test_slice_matches_index_loops():
+    """Brute force: every element of the result by explicit index arithmetic."""
+    for rank, static_axes in ((1, ()), (2, ()), (3, (1,)), (2, (0, 1))):
+        pat, starts, sizes = _slice_pattern(rank, static_axes)
+        shape = (5, 4, 6)[:rank]
+        x = rng.normal(size=shape)
+        dims = [0] * pat.n_dims
+        for k in range(rank):
+            dims[k] = shape[k]
+        st = [1, 0, 2][:rank]
+        sz = [3, 4, 3][:rank]
+        for k in range(rank):
+            if k in static_axes:
+                st[k], sz[k] = 1, 2
+            else:
+                dims[starts[k]], dims[sizes[k]] = st[k], sz[k]
+        out = run(pat, dims, [x])[0][0]
+        assert out.shape == tuple(sz)
+        for idx in itertools.product(*[range(n) for n in sz]):
+            assert out[idx] == x[tuple(s + i for s, i in zip(st, idx))]
+
+
+def test_slice_identity_tiling_and_bounds():
+    pat, starts, sizes = _slice_pattern(2)
+    x = rng.normal(size=(7, 9))
+
+    def sl(s0, n0, s1, n1):
+        d = [0] * pat.n_dims
+        d[0], d[1] = 7, 9
+        d[starts[0]], d[sizes[0]], d[starts[1]], d[sizes[1]] = s0, n0, s1, n1
+        return run(pat, d, [x])[0][0]
+
+    assert np.array_equal(sl(0, 7, 0, 9), x)                                   # the whole operand
+    # adjacent slices tile the operand: gluing them back gives the operand (the Split case)
+    assert np.array_equal(np.concatenate([sl(0, 7, 0, 4), sl(0, 7, 4, 5)], axis=1), x)
+    assert np.array_equal(np.concatenate([sl(0, 2, 0, 9), sl(2, 5, 0, 9)], axis=0), x)
+    assert sl(3, 0, 0, 9).shape == (0, 9)                                      # an empty slice is legal
+    for bad in ((0, 8, 0, 9), (1, 7, 0, 9), (0, 7, 5, 5)):
+        with pytest.raises(OracleError):
+            sl(*bad)
+    # a slice is a producer like any other value: softmax over the second half of each row
+    pb = PatternBuilder()
+    T, H, s0, n = pb.dims(4)
+    xs = pb.slice(pb.param("f32", [T, H]), [pb.static_start(0), s0], [T, n])
+    e = pb.op("exp", pb.op("sub", xs, pb.broadcast(pb.reduce("max", xs, 1), [T, n], [0])))
+    pb.output(pb.op("div", e, pb.broadcast(pb.reduce("sum", e, 1), [T, n], [0])))
+    got = run(pb.build(), [7, 9, 4, 5], [x])[0][0]
+    np.testing.assert_allclose(got, scipy.special.softmax(x[:, 4:], axis=1), rtol=1e-13)

@@ -21,6 +21,11 @@ Conventions
 * rank-0 values (``const``, ``dim_size``) may be used directly as operands of
   element-wise ops (scalar operand).
 * ``output``        : marks value ``ins[0]`` as a result of the pattern.
+* ``slice``         : dynamic slice (the paper's DHLO example, Section 4.1: the start indices
+  of a slice are runtime values, not compile-time attributes).  ``dims`` are the
+  sizes of the result, ``axis_map[k]`` the start along axis ``k``: ``>= 0`` the
+  id of a symbolic dim whose runtime value is the start index, ``< 0`` the
+  static start ``-1 - axis_map[k]`` (so ``-1`` is start 0).  Stride 1.
 """
 from __future__ import annotations
 
@@ -34,7 +39,7 @@ UNARY = ("neg", "abs", "exp", "log", "tanh", "sqrt", "rsqrt", "rcp", "sigmoid", 
 BINARY = ("add", "sub", "mul", "div", "max", "min", "pow")
 COMPARE = ("lt", "le", "gt", "ge", "eq", "ne")
 REDUCE = ("reduce_sum", "reduce_max", "reduce_min", "reduce_argmax")
-OPCODES = LEAF + UNARY + BINARY + COMPARE + ("select", "cast", "broadcast") + REDUCE + ("output",)
+OPCODES = LEAF + UNARY + BINARY + COMPARE + ("select", "cast", "broadcast") + REDUCE + ("output", "slice")
 
 DIM_EQ = 0      # dimension-size equality constraint
 NUMEL_EQ = 1    # tensor-size equality constraint
@@ -146,6 +151,21 @@ class PatternBuilder:
             dtype = "i32" if kind == "argmax" else src.dtype
         dims = tuple(d for k, d in enumerate(src.dims) if k != axis)
         return self._push(Op(opcode, dtype, (v,), dims, (int(axis),)))
+
+    @staticmethod
+    def static_start(start: int) -> int:
+        """Encoding of a compile-time start index of ``slice``."""
+        assert start >= 0
+        return -1 - int(start)
+
+    def slice(self, v: int, starts: Sequence[int], sizes: Sequence[int]) -> int:
+        """result[i0, i1, ...] = v[start0 + i0, start1 + i1, ...]; ``sizes`` are the result dims."""
+        src = self.p.ops[v]
+        assert len(starts) == len(sizes) == len(src.dims)
+        for s_ in starts:
+            if s_ >= 0:
+                self.p.n_dims = max(self.p.n_dims, s_ + 1)
+        return self._push(Op("slice", src.dtype, (v,), tuple(sizes), tuple(int(x) for x in starts)))
 
     def output(self, v: int) -> int:
         src = self.p.ops[v]
