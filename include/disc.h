@@ -89,6 +89,13 @@ typedef enum {
   DISC_REDUCE_SUM, DISC_REDUCE_MAX, DISC_REDUCE_MIN,
   DISC_REDUCE_ARGMAX, /* lowest index among the maxima; dtype DISC_I32 or DISC_I64             */
   DISC_OUTPUT,     /* k-th OUTPUT = k-th output pointer; in[0] = the value, same dtype         */
+  DISC_SLICE,      /* dynamic slice of a PARAM, stride 1 (Section 4.1: start indices are runtime
+                      values, not attributes): result[i0,i1,..] = in[s0+i0, s1+i1, ..]; dim[] = sizes
+                      of the result; axis_map[k] = start along axis k: >= 0 the symbolic dim id whose
+                      runtime value is the start, < 0 the static start -1 - axis_map[k].  in[0] must
+                      be a PARAM (the slice is an indexing function on the input, never a copy; one
+                      PARAM may be sliced several times).  A launch whose slice leaves the operand
+                      fails with DISC_ERR_SHAPE.                                               */
   DISC_OPCODE_COUNT
 } disc_opcode;
 

@@ -43,7 +43,7 @@ const char* opcode_name(int oc) {
   static const char* names[] = {"param", "const", "dim_size", "neg", "abs", "exp", "log", "tanh",
     "sqrt", "rsqrt", "rcp", "sigmoid", "erf", "add", "sub", "mul", "div", "max", "min", "pow",
     "lt", "le", "gt", "ge", "eq", "ne", "select", "cast", "broadcast", "reduce_sum", "reduce_max",
-    "reduce_min", "reduce_argmax", "output"};
+    "reduce_min", "reduce_argmax", "output", "slice"};
   if (oc < 0 || oc >= DISC_OPCODE_COUNT) return "?";
   return names[oc];
 }
@@ -105,7 +105,7 @@ bool is_elementwise(int oc) {
 }
 int n_operands(int oc) {
   if (oc <= DISC_DIM_SIZE) return 0;
-  if (is_unary(oc) || oc == DISC_CAST || oc == DISC_BROADCAST || is_reduce(oc) || oc == DISC_OUTPUT)
+  if (is_unary(oc) || oc == DISC_CAST || oc == DISC_BROADCAST || is_reduce(oc) || oc == DISC_OUTPUT || oc == DISC_SLICE)
     return 1;
   if (oc == DISC_SELECT) return 3;
   return 2;
@@ -138,6 +138,11 @@ struct Builder {
       if (!an.classes.same(an.classes.atom(op.dim[k]), an.classes.atom(an.root_dims[k]))) return false;
     return true;
   }
+  // axis k of a SLICE op covers the whole axis of its operand: static start 0 and provably the same size
+  bool slice_axis_full(const disc_op& op, int k) {
+    const disc_op& src = an.ops[op.in[0]];
+    return op.axis_map[k] == -1 && an.classes.same(an.classes.atom(op.dim[k]), an.classes.atom(src.dim[k]));
+  }
   // drop axes of static size 1 from a context (they contribute offset 0)
   Ctx normalise(const disc_op& op, Ctx c) {
     for (int k = 0; k < op.rank; ++k)
@@ -167,6 +172,22 @@ struct Builder {
       a.ctx = c;
       int slot = 0;
       for (int i = 0; i < v; ++i)
+        if (an.ops[i].opcode == DISC_PARAM) ++slot;
+      a.slot = slot;
+      n.access = (int)an.accesses.size();
+      an.accesses.push_back(a);
+    } else if (oc == DISC_SLICE) {
+      // an indexing function on the sliced PARAM: the node is a PARAM node whose access carries
+      // the PARAM's own extents and the start offsets
+      n.opcode = DISC_PARAM;
+      Access a;
+      a.value = v;
+      a.src_value = op.in[0];
+      a.is_output = false;
+      a.dtype = op.dtype;
+      a.ctx = c;
+      int slot = 0;
+      for (int i = 0; i < op.in[0]; ++i)
         if (an.ops[i].opcode == DISC_PARAM) ++slot;
       a.slot = slot;
       n.access = (int)an.accesses.size();
@@ -301,6 +322,16 @@ int analyze(const disc_op* ops, int n_ops, const disc_constraint* cs, int n_cs, 
       }
       if (src.rank < 1 || op.rank != src.rank - 1) return bad("reduce result must drop exactly one axis");
       if (op.axis_map[0] < 0 || op.axis_map[0] >= src.rank) return bad("reduce axis out of range");
+    }
+    if (oc == DISC_SLICE) {
+      const disc_op& src = ops[op.in[0]];
+      if (src.opcode != DISC_PARAM) return bad("SLICE applies to a PARAM (slice the input, then compute)");
+      if (src.dtype != op.dtype) return bad("SLICE changes dtype");
+      if (src.rank != op.rank || op.rank < 1) return bad("SLICE keeps the rank of its operand (>= 1)");
+      for (int k = 0; k < op.rank; ++k) {
+        if (op.axis_map[k] >= DISC_MAX_DIMS) return bad("SLICE start names an unknown dim");
+        if (op.axis_map[k] >= 0) n_sym = std::max(n_sym, op.axis_map[k] + 1);
+      }
     }
     if (oc == DISC_BROADCAST) {
       const disc_op& src = ops[op.in[0]];
@@ -495,9 +526,9 @@ int analyze(const disc_op* ops, int n_ops, const disc_constraint* cs, int n_cs, 
     // (non-broadcast) tensor of the common element count or a scalar.
     for (int i = 0; i < n_ops; ++i) {
       const disc_op& op = ops[i];
-      if (op.opcode == DISC_BROADCAST) {
-        snprintf(buf, sizeof buf, "op %d (broadcast): outputs agree only in element count, so the pattern is "
-                 "fused over a flat index and cannot contain a broadcast", i);
+      if (op.opcode == DISC_BROADCAST || op.opcode == DISC_SLICE) {
+        snprintf(buf, sizeof buf, "op %d (%s): outputs agree only in element count, so the pattern is "
+                 "fused over a flat index and cannot contain a broadcast or a slice", i, opcode_name(op.opcode));
         err = buf;
         return DISC_ERR_UNFUSIBLE;
       }
@@ -592,6 +623,10 @@ int analyze(const disc_op* ops, int n_ops, const disc_constraint* cs, int n_cs, 
             if (pi < 0 || pj < 0) { join = false; break; }
             for (int k = pi + 1; k < pj; ++k)
               if (a.ctx[k] != -1) { join = false; break; }
+            // a sliced operand is contiguous across the two axes only if the inner one is whole
+            if (a.src_value >= 0)
+              for (int k = pi + 1; k <= pj; ++k)
+                if (!b.slice_axis_full(ops[a.value], k)) { join = false; break; }
             if (!join) break;
           }
         }
@@ -691,6 +726,45 @@ int analyze(const disc_op* ops, int n_ops, const disc_constraint* cs, int n_cs, 
     if (outer_cnt == n_outer) a.kind = a.has_inner ? ACC_FULL : (n_outer == 0 ? ACC_SCALAR : ACC_PERROW);
     else if (outer_cnt == 0) a.kind = a.has_inner ? ACC_ROWVEC : ACC_SCALAR;
     else a.kind = ACC_PARTIAL;
+    if (a.src_value >= 0) {
+      // sliced PARAM: strided like a partial access, with the PARAM's own extents as strides
+      const disc_op& sl = ops[a.value];
+      const disc_op& src = ops[a.src_value];
+      a.kind = ACC_PARTIAL;
+      an.needs_decomp = true;
+      auto tail_product = [&](int after) {       // product of the operand's extents of the axes behind `after`
+        DimProduct p;
+        for (int k = after + 1; k < src.rank; ++k) mul_into(p, dc, src.dim[k]);
+        return p;
+      };
+      for (size_t t = 0; t < a.groups.size(); ++t) {
+        if (a.groups[t] == an.inner_group) continue;
+        int last = -1;
+        for (int k = 0; k < (int)a.ctx.size(); ++k)
+          for (int ax : an.groups[a.groups[t]])
+            if (a.ctx[k] == ax) last = std::max(last, k);
+        a.stride_prod.push_back((int)an.products.size());
+        an.products.push_back(tail_product(last));
+      }
+      OffsetRecipe off;
+      for (int k = 0; k < sl.rank; ++k) {
+        if (sl.axis_map[k] != -1) off.terms.push_back({sl.axis_map[k], tail_product(k)});
+        if (!b.slice_axis_full(sl, k)) {
+          SliceCheck sc;
+          sc.start = sl.axis_map[k];
+          sc.size_dim = sl.dim[k];
+          sc.src_dim = src.dim[k];
+          sc.op = a.value;
+          sc.axis = k;
+          an.slice_checks.push_back(sc);
+        }
+      }
+      if (!off.terms.empty()) {
+        a.offset_index = (int)an.offsets.size();
+        an.offsets.push_back(off);
+      }
+      continue;
+    }
     if (a.kind == ACC_PARTIAL) {
       an.needs_decomp = true;
       // stride of spanned outer group g = product of the later groups this access spans

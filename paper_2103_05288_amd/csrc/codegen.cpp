@@ -97,7 +97,7 @@ struct Gen {
     for (int i = 0; i < an.n_outputs; ++i) add_field(ArgField::OUT_PTR, i, 8);
     for (int i = 0; i < 2; ++i) add_field(ArgField::WS_PTR, i, 8);
     for (int i = 0; i < 4; ++i) add_field(ArgField::AUX, i, 8);
-    for (size_t i = 0; i < an.products.size(); ++i) add_field(ArgField::STRIDE, (int)i, 8);
+    for (size_t i = 0; i < an.products.size() + an.offsets.size(); ++i) add_field(ArgField::STRIDE, (int)i, 8);   // strides, then base offsets of sliced operands
     for (size_t i = 0; i < an.dim_size_syms.size(); ++i) add_field(ArgField::DIMI, (int)i, 8);
     add_field(ArgField::SPR_DIV, 0, 16);
     for (int g = 0; g < 3; ++g) add_field(ArgField::GROUP_DIV, g, 16);
@@ -445,11 +445,13 @@ struct Gen {
       if (a.kind == ACC_PARTIAL) {
         std::string e;
         size_t sp = 0;
+        if (a.offset_index >= 0) e = fmt("A.st%d", (int)an.products.size() + a.offset_index);
         for (size_t t = 0; t < a.groups.size(); ++t) {
           if (a.groups[t] == an.inner_group) continue;
           if (!e.empty()) e += " + ";
           e += fmt("ig[%d] * A.st%d", a.groups[t], a.stride_prod[sp++]);
         }
+        if (e.empty()) e = "0";
         if (a.has_inner || a.is_output) os << "    rc.b" << i << " = " << e << ";\n";
         else os << "    const disc::i64 pb" << i << " = " << e << ";\n";
       }

@@ -80,6 +80,11 @@ struct Access {
   AccessKind kind = ACC_FULL;
   // ACC_PARTIAL: index (into Recipe::products) of the stride of each spanned outer group
   std::vector<int> stride_prod;
+  // SLICE of a PARAM: `value` is the SLICE op (its dims are what is read), `src_value` the PARAM;
+  // the strides are products of the PARAM's own dims and the base offset (index into
+  // Analysis::offsets, -1 = none) is the sum of start * stride over the sliced axes
+  int src_value = -1;
+  int offset_index = -1;
 };
 
 // Resolved graph: one node per (value, context) pair actually needed.
@@ -109,6 +114,17 @@ struct DimProduct {
   std::vector<int> sym;     // symbolic dim ids
   int64_t stat = 1;         // static factor
 };
+// Base offset of a sliced operand: sum of start * stride; a start is a symbolic dim id (>= 0) or
+// the static value -1 - start.
+struct OffsetRecipe {
+  std::vector<std::pair<int32_t, DimProduct>> terms;
+};
+// Launch-time check of one sliced axis: 0 <= start and start + size <= extent of the operand
+struct SliceCheck {
+  int32_t start, size_dim, src_dim;   // start: as above; the dims: symbolic id or -static
+  int op;
+  int axis;
+};
 
 struct Analysis {
   int tmpl = DISC_TEMPLATE_LOOP;
@@ -137,6 +153,8 @@ struct Analysis {
   // launch recipes
   std::vector<DimProduct> group_size;    // per collapsed group
   std::vector<DimProduct> products;      // strides of partial accesses
+  std::vector<OffsetRecipe> offsets;     // base offsets of sliced operands (kernel argument st<products.size() + i>)
+  std::vector<SliceCheck> slice_checks;
   std::vector<int> dim_size_syms;        // symbolic dims referenced by DIM_SIZE nodes
   int vec_width = 1;                     // elements per vector slot
 };

@@ -223,10 +223,31 @@ int shape_calc(disc_ctx* c, const Pattern& p, const int64_t* dims, int n_dims, S
   sv->rows = 1;
   for (int g = 0; g < an.inner_group; ++g) sv->rows *= sv->group[g];
   sv->mid = an.mid_group >= 0 ? sv->group[an.mid_group] : 0;
-  sv->products.resize(an.products.size());
+  sv->products.resize(an.products.size() + an.offsets.size());
   for (size_t i = 0; i < an.products.size(); ++i)
     if (!eval_product(an.products[i], dims, &sv->products[i]))
       return set_err(c, DISC_ERR_SHAPE, "stride overflows int64");
+  // sliced operands (Section 4.1: slice starts are runtime values): bounds, then base offsets
+  auto dim_val = [&](int32_t d) { return d >= 0 ? dims[d] : -(int64_t)d; };
+  auto start_val = [&](int32_t s) { return s >= 0 ? dims[s] : (int64_t)(-1 - s); };
+  for (const auto& sc : an.slice_checks) {
+    const int64_t st = start_val(sc.start), n = dim_val(sc.size_dim), ext = dim_val(sc.src_dim);
+    if (st < 0 || n > ext || st > ext - n) {
+      snprintf(buf, sizeof buf, "op %d (slice), axis %d: [%lld, %lld) leaves the operand's extent %lld", sc.op, sc.axis,
+               (long long)st, (long long)(st + n), (long long)ext);
+      return set_err(c, DISC_ERR_SHAPE, buf);
+    }
+  }
+  for (size_t i = 0; i < an.offsets.size(); ++i) {
+    int64_t sum = 0;
+    for (const auto& t : an.offsets[i].terms) {
+      int64_t stride = 0, term = 0;
+      if (!eval_product(t.second, dims, &stride) || mul_ovf(stride, start_val(t.first), &term) ||
+          __builtin_add_overflow(sum, term, &sum))
+        return set_err(c, DISC_ERR_SHAPE, "slice offset overflows int64");
+    }
+    sv->products[an.products.size() + i] = sum;
+  }
   sv->alg_bytes = 0;
   for (const auto& io : p.io_numel) {
     int64_t n = 0;
@@ -837,8 +858,20 @@ static int register_impl(disc_ctx* ctx, const disc_op* ops, int n_ops, const dis
     }
     p->n_classes = (int)rep_to_class.size();
   }
+  // algorithmic bytes: every operand and result once; an input that is only read through slices
+  // counts with the elements its slices read
+  std::vector<char> read_whole(p->an.ops.size(), 0);
   for (const auto& op : p->an.ops) {
-    if (op.opcode != DISC_PARAM && op.opcode != DISC_OUTPUT) continue;
+    if (op.opcode == DISC_SLICE || op.opcode <= DISC_DIM_SIZE) continue;
+    for (int k = 0; k < 3; ++k)
+      if (op.in[k] >= 0 && (k == 0 || op.opcode == DISC_SELECT || (op.opcode >= DISC_ADD && op.opcode <= DISC_NE)))
+        read_whole[op.in[k]] = 1;
+  }
+  for (size_t i = 0; i < p->an.ops.size(); ++i) {
+    const disc_op& op = p->an.ops[i];
+    if (op.opcode == DISC_PARAM && !read_whole[i]) continue;
+    if (op.opcode == DISC_SLICE && read_whole[op.in[0]]) continue;
+    if (op.opcode != DISC_PARAM && op.opcode != DISC_OUTPUT && op.opcode != DISC_SLICE) continue;
     DimProduct prod;
     for (int k = 0; k < op.rank; ++k) {
       if (op.dim[k] >= 0) prod.sym.push_back(op.dim[k]); else prod.stat *= -(int64_t)op.dim[k];
