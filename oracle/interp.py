@@ -37,6 +37,11 @@ with those standard meanings:
                             result sizes are the op's dims, the starts come from the
                             runtime dims (or are static); a slice that leaves the operand
                             is an error
+* pad                     : dynamic pad without interior padding (named beside slice in Section
+                            4.1): the operand sits at offset low_k along every axis of a result
+                            otherwise filled with the padding value; low_k are runtime values
+                            (or static), the result sizes are the op's dims; an operand that
+                            does not fit is an error
 
 Inputs stored as f16 / bf16 are converted to float64 by the caller (every such
 value is exactly representable); the oracle itself only sees numpy arrays.
@@ -214,6 +219,17 @@ def _run(pattern, dims, inputs):
                 if s0 < 0 or s0 + n > x.shape[k]:
                     raise OracleError(f"op {idx}: slice [{s0}, {s0 + n}) leaves axis {k} of size {x.shape[k]}")
             v = x[tuple(slice(s0, s0 + n) for s0, n in zip(starts, want))].copy()
+        elif oc == "pad":
+            x = vals[op.ins[0]]
+            if len(op.axis_map) != x.ndim or len(want) != x.ndim:
+                raise OracleError(f"op {idx}: pad needs one low padding and one size per axis")
+            low = [dims[a] if a >= 0 else -1 - a for a in op.axis_map]
+            for k, (l0, n) in enumerate(zip(low, want)):
+                if l0 < 0 or l0 + x.shape[k] > n:
+                    raise OracleError(f"op {idx}: operand [{l0}, {l0 + x.shape[k]}) does not fit axis {k} of size {n}")
+            fill = _as_dtype(np.asarray(op.fconst, dtype=np.float64), op.dtype)
+            v = np.full(want, fill, dtype=x.dtype)
+            v[tuple(slice(l0, l0 + m) for l0, m in zip(low, x.shape))] = x
         elif oc == "output":
             v = vals[op.ins[0]]
             outs.append(v)

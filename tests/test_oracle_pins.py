@@ -448,3 +448,51 @@ def test_slice_identity_tiling_and_bounds():
     pb.output(pb.op("div", e, pb.broadcast(pb.reduce("sum", e, 1), [T, n], [0])))
     got = run(pb.build(), [7, 9, 4, 5], [x])[0][0]
     np.testing.assert_allclose(got, scipy.special.softmax(x[:, 4:], axis=1), rtol=1e-13)
+
+
+# ---------------------------------------------------------------- dynamic pad (Section 4.1)
+def _pad_pattern(rank, value):
+    pb = PatternBuilder()
+    src = pb.dims(rank)
+    low = pb.dims(rank)
+    sizes = pb.dims(rank)
+    x = pb.param("f32", src)
+    pb.output(pb.pad(x, low, sizes, value))
+    return pb.build()
+
+
+def test_pad_matches_index_loops_and_inverts_slice():
+    for rank in (1, 2, 3):
+        pat = _pad_pattern(rank, -2.5)
+        shape = (3, 4, 2)[:rank]
+        low = (2, 0, 1)[:rank]
+        size = (7, 4, 5)[:rank]
+        x = rng.normal(size=shape)
+        out = run(pat, list(shape) + list(low) + list(size), [x])[0][0]
+        assert out.shape == tuple(size)
+        for idx in itertools.product(*[range(n) for n in size]):
+            src = tuple(i - l for i, l in zip(idx, low))
+            inside = all(0 <= s < d for s, d in zip(src, shape))
+            assert out[idx] == (x[src] if inside else -2.5)
+        # slicing the padded result at the same offsets gives the operand back
+        assert np.array_equal(out[tuple(slice(l, l + d) for l, d in zip(low, shape))], x)
+        # numpy's own pad agrees
+        ref = np.pad(x, [(l, n - l - d) for l, n, d in zip(low, size, shape)], constant_values=-2.5)
+        assert np.array_equal(out, ref)
+    pat = _pad_pattern(1, 0.0)
+    x = rng.normal(size=5)
+    assert np.array_equal(run(pat, [5, 0, 5], [x])[0][0], x)          # no padding at all
+    assert run(pat, [0, 0, 4], [np.zeros(0)])[0][0].tolist() == [0.0] * 4   # an empty operand: padding only
+    for bad in ([5, 1, 5], [5, 0, 4]):
+        with pytest.raises(OracleError):
+            run(pat, bad, [x])
+    # softmax with -inf padding behind each row equals softmax of the row, zeros in the padding
+    pb = PatternBuilder()
+    T, H, P = pb.dims(3)
+    xp = pb.pad(pb.param("f32", [T, H]), [pb.static_start(0), pb.static_start(0)], [T, P], float("-inf"))
+    e = pb.op("exp", pb.op("sub", xp, pb.broadcast(pb.reduce("max", xp, 1), [T, P], [0])))
+    pb.output(pb.op("div", e, pb.broadcast(pb.reduce("sum", e, 1), [T, P], [0])))
+    x2 = rng.normal(size=(4, 6))
+    got = run(pb.build(), [4, 6, 9], [x2])[0][0]
+    np.testing.assert_allclose(got[:, :6], scipy.special.softmax(x2, axis=1), rtol=1e-13)
+    assert np.all(got[:, 6:] == 0.0)

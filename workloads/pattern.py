@@ -26,6 +26,11 @@ Conventions
   sizes of the result, ``axis_map[k]`` the start along axis ``k``: ``>= 0`` the
   id of a symbolic dim whose runtime value is the start index, ``< 0`` the
   static start ``-1 - axis_map[k]`` (so ``-1`` is start 0).  Stride 1.
+* ``pad``           : dynamic pad (Section 4.1 names it beside slice): ``dims`` are the sizes
+  of the result, ``axis_map[k]`` the number of padding elements in front of
+  axis ``k`` (encoded like a slice start), ``fconst`` the padding value; the
+  padding behind an axis is whatever the result size leaves.  No interior
+  padding, no negative padding.
 """
 from __future__ import annotations
 
@@ -39,7 +44,7 @@ UNARY = ("neg", "abs", "exp", "log", "tanh", "sqrt", "rsqrt", "rcp", "sigmoid", 
 BINARY = ("add", "sub", "mul", "div", "max", "min", "pow")
 COMPARE = ("lt", "le", "gt", "ge", "eq", "ne")
 REDUCE = ("reduce_sum", "reduce_max", "reduce_min", "reduce_argmax")
-OPCODES = LEAF + UNARY + BINARY + COMPARE + ("select", "cast", "broadcast") + REDUCE + ("output", "slice")
+OPCODES = LEAF + UNARY + BINARY + COMPARE + ("select", "cast", "broadcast") + REDUCE + ("output", "slice", "pad")
 
 DIM_EQ = 0      # dimension-size equality constraint
 NUMEL_EQ = 1    # tensor-size equality constraint
@@ -166,6 +171,15 @@ class PatternBuilder:
             if s_ >= 0:
                 self.p.n_dims = max(self.p.n_dims, s_ + 1)
         return self._push(Op("slice", src.dtype, (v,), tuple(sizes), tuple(int(x) for x in starts)))
+
+    def pad(self, v: int, low: Sequence[int], sizes: Sequence[int], value: float = 0.0) -> int:
+        """result[i] = v[i - low] where that exists, ``value`` elsewhere; ``sizes`` are the result dims."""
+        src = self.p.ops[v]
+        assert len(low) == len(sizes) == len(src.dims)
+        for s_ in low:
+            if s_ >= 0:
+                self.p.n_dims = max(self.p.n_dims, s_ + 1)
+        return self._push(Op("pad", src.dtype, (v,), tuple(sizes), tuple(int(x) for x in low), float(value)))
 
     def output(self, v: int) -> int:
         src = self.p.ops[v]
