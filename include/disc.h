@@ -96,6 +96,12 @@ typedef enum {
                       be a PARAM (the slice is an indexing function on the input, never a copy; one
                       PARAM may be sliced several times).  A launch whose slice leaves the operand
                       fails with DISC_ERR_SHAPE.                                               */
+  DISC_PAD,        /* dynamic pad of a PARAM (named beside slice in Section 4.1), no interior padding:
+                      result[i] = in[i - low] where that exists, else `fconst`; dim[] = sizes of the
+                      result, axis_map[k] = padding in front of axis k, encoded like a SLICE start.
+                      in[0] must be a PARAM; the padding is produced in registers, never written to
+                      memory on its own.  A launch whose operand does not fit the result fails with
+                      DISC_ERR_SHAPE.                                                          */
   DISC_OPCODE_COUNT
 } disc_opcode;
 

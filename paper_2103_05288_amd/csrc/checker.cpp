@@ -43,7 +43,7 @@ const char* opcode_name(int oc) {
   static const char* names[] = {"param", "const", "dim_size", "neg", "abs", "exp", "log", "tanh",
     "sqrt", "rsqrt", "rcp", "sigmoid", "erf", "add", "sub", "mul", "div", "max", "min", "pow",
     "lt", "le", "gt", "ge", "eq", "ne", "select", "cast", "broadcast", "reduce_sum", "reduce_max",
-    "reduce_min", "reduce_argmax", "output", "slice"};
+    "reduce_min", "reduce_argmax", "output", "slice", "pad"};
   if (oc < 0 || oc >= DISC_OPCODE_COUNT) return "?";
   return names[oc];
 }
@@ -105,7 +105,7 @@ bool is_elementwise(int oc) {
 }
 int n_operands(int oc) {
   if (oc <= DISC_DIM_SIZE) return 0;
-  if (is_unary(oc) || oc == DISC_CAST || oc == DISC_BROADCAST || is_reduce(oc) || oc == DISC_OUTPUT || oc == DISC_SLICE)
+  if (is_unary(oc) || oc == DISC_CAST || oc == DISC_BROADCAST || is_reduce(oc) || oc == DISC_OUTPUT || oc == DISC_SLICE || oc == DISC_PAD)
     return 1;
   if (oc == DISC_SELECT) return 3;
   return 2;
@@ -176,13 +176,15 @@ struct Builder {
       a.slot = slot;
       n.access = (int)an.accesses.size();
       an.accesses.push_back(a);
-    } else if (oc == DISC_SLICE) {
-      // an indexing function on the sliced PARAM: the node is a PARAM node whose access carries
-      // the PARAM's own extents and the start offsets
+    } else if (oc == DISC_SLICE || oc == DISC_PAD) {
+      // an indexing function on the sliced / padded PARAM: the node is a PARAM node whose access
+      // carries the PARAM's own extents and the offsets
       n.opcode = DISC_PARAM;
       Access a;
       a.value = v;
       a.src_value = op.in[0];
+      a.padded = oc == DISC_PAD;
+      a.pad_value = op.fconst;
       a.is_output = false;
       a.dtype = op.dtype;
       a.ctx = c;
@@ -323,13 +325,13 @@ int analyze(const disc_op* ops, int n_ops, const disc_constraint* cs, int n_cs, 
       if (src.rank < 1 || op.rank != src.rank - 1) return bad("reduce result must drop exactly one axis");
       if (op.axis_map[0] < 0 || op.axis_map[0] >= src.rank) return bad("reduce axis out of range");
     }
-    if (oc == DISC_SLICE) {
+    if (oc == DISC_SLICE || oc == DISC_PAD) {
       const disc_op& src = ops[op.in[0]];
-      if (src.opcode != DISC_PARAM) return bad("SLICE applies to a PARAM (slice the input, then compute)");
-      if (src.dtype != op.dtype) return bad("SLICE changes dtype");
-      if (src.rank != op.rank || op.rank < 1) return bad("SLICE keeps the rank of its operand (>= 1)");
+      if (src.opcode != DISC_PARAM) return bad("SLICE / PAD apply to a PARAM (slice or pad the input, then compute)");
+      if (src.dtype != op.dtype) return bad("SLICE / PAD change dtype");
+      if (src.rank != op.rank || op.rank < 1) return bad("SLICE / PAD keep the rank of their operand (>= 1)");
       for (int k = 0; k < op.rank; ++k) {
-        if (op.axis_map[k] >= DISC_MAX_DIMS) return bad("SLICE start names an unknown dim");
+        if (op.axis_map[k] >= DISC_MAX_DIMS) return bad("SLICE start / PAD low names an unknown dim");
         if (op.axis_map[k] >= 0) n_sym = std::max(n_sym, op.axis_map[k] + 1);
       }
     }
@@ -526,9 +528,9 @@ int analyze(const disc_op* ops, int n_ops, const disc_constraint* cs, int n_cs, 
     // (non-broadcast) tensor of the common element count or a scalar.
     for (int i = 0; i < n_ops; ++i) {
       const disc_op& op = ops[i];
-      if (op.opcode == DISC_BROADCAST || op.opcode == DISC_SLICE) {
+      if (op.opcode == DISC_BROADCAST || op.opcode == DISC_SLICE || op.opcode == DISC_PAD) {
         snprintf(buf, sizeof buf, "op %d (%s): outputs agree only in element count, so the pattern is "
-                 "fused over a flat index and cannot contain a broadcast or a slice", i, opcode_name(op.opcode));
+                 "fused over a flat index and cannot contain a broadcast, a slice or a pad", i, opcode_name(op.opcode));
         err = buf;
         return DISC_ERR_UNFUSIBLE;
       }
@@ -727,33 +729,59 @@ int analyze(const disc_op* ops, int n_ops, const disc_constraint* cs, int n_cs, 
     else if (outer_cnt == 0) a.kind = a.has_inner ? ACC_ROWVEC : ACC_SCALAR;
     else a.kind = ACC_PARTIAL;
     if (a.src_value >= 0) {
-      // sliced PARAM: strided like a partial access, with the PARAM's own extents as strides
+      // sliced / padded PARAM: strided like a partial access, with the PARAM's own extents as strides
       const disc_op& sl = ops[a.value];
       const disc_op& src = ops[a.src_value];
+      a.all_outer = outer_cnt == n_outer && a.has_inner;
       a.kind = ACC_PARTIAL;
       an.needs_decomp = true;
+      if (a.padded && !a.has_inner) {
+        snprintf(buf, sizeof buf, "op %d (pad): a padded operand without the innermost axis is not supported", a.value);
+        err = buf;
+        return DISC_ERR_UNFUSIBLE;
+      }
       auto tail_product = [&](int after) {       // product of the operand's extents of the axes behind `after`
         DimProduct p;
         for (int k = after + 1; k < src.rank; ++k) mul_into(p, dc, src.dim[k]);
         return p;
       };
       for (size_t t = 0; t < a.groups.size(); ++t) {
-        if (a.groups[t] == an.inner_group) continue;
-        int last = -1;
+        int first = DISC_MAX_RANK, last = -1;
         for (int k = 0; k < (int)a.ctx.size(); ++k)
           for (int ax : an.groups[a.groups[t]])
-            if (a.ctx[k] == ax) last = std::max(last, k);
+            if (a.ctx[k] == ax) { last = std::max(last, k); first = std::min(first, k); }
+        // the operand is only present inside a window of this group's index when the group's
+        // outermost axis is padded (the axes behind it in the group are whole, or they would
+        // not have been merged with it)
+        int win = -1;
+        if (a.padded && last >= 0 && !b.slice_axis_full(sl, first)) {
+          WindowRecipe w;
+          w.low = sl.axis_map[first];
+          w.extent_dim = src.dim[first];
+          for (int k = first + 1; k <= last; ++k) mul_into(w.inner_sizes, dc, src.dim[k]);
+          win = (int)an.windows.size();
+          an.windows.push_back(w);
+        }
+        a.window.push_back(win);
+        if (a.groups[t] == an.inner_group) continue;
         a.stride_prod.push_back((int)an.products.size());
         an.products.push_back(tail_product(last));
       }
       OffsetRecipe off;
+      off.negative = a.padded;
       for (int k = 0; k < sl.rank; ++k) {
         if (sl.axis_map[k] != -1) off.terms.push_back({sl.axis_map[k], tail_product(k)});
         if (!b.slice_axis_full(sl, k)) {
+          if (a.padded && b.dim_is_one(sl.dim[k])) {
+            snprintf(buf, sizeof buf, "op %d (pad): axis %d has result size 1 and cannot be padded", a.value, k);
+            err = buf;
+            return DISC_ERR_BAD_PATTERN;
+          }
           SliceCheck sc;
           sc.start = sl.axis_map[k];
-          sc.size_dim = sl.dim[k];
-          sc.src_dim = src.dim[k];
+          // slice: start + result size <= operand extent; pad: low + operand extent <= result size
+          sc.size_dim = a.padded ? src.dim[k] : sl.dim[k];
+          sc.src_dim = a.padded ? sl.dim[k] : src.dim[k];
           sc.op = a.value;
           sc.axis = k;
           an.slice_checks.push_back(sc);

@@ -74,7 +74,7 @@ struct Gen {
   bool col_tmpl() const { return an.tmpl == DISC_TEMPLATE_COL_REDUCE; }
   bool row_tmpl() const { return an.tmpl == DISC_TEMPLATE_ROW_REDUCE; }
   // small cached operands of a row reduce are loaded at their point of use, not into the slot
-  bool late(const Access& a) const { return row_tmpl() && !a.is_output && a.has_inner && a.kind != ACC_FULL; }
+  bool late(const Access& a) const { return row_tmpl() && !a.is_output && a.has_inner && a.kind != ACC_FULL && !a.all_outer; }
 
   // ---- kernel-argument block ------------------------------------------------------------
   void add_field(ArgField::Kind k, int index, int size) {
@@ -97,7 +97,8 @@ struct Gen {
     for (int i = 0; i < an.n_outputs; ++i) add_field(ArgField::OUT_PTR, i, 8);
     for (int i = 0; i < 2; ++i) add_field(ArgField::WS_PTR, i, 8);
     for (int i = 0; i < 4; ++i) add_field(ArgField::AUX, i, 8);
-    for (size_t i = 0; i < an.products.size() + an.offsets.size(); ++i) add_field(ArgField::STRIDE, (int)i, 8);   // strides, then base offsets of sliced operands
+    // strides, then base offsets of sliced / padded operands, then [lo, hi) of every padding window
+    for (size_t i = 0; i < an.products.size() + an.offsets.size() + 2 * an.windows.size(); ++i) add_field(ArgField::STRIDE, (int)i, 8);
     for (size_t i = 0; i < an.dim_size_syms.size(); ++i) add_field(ArgField::DIMI, (int)i, 8);
     add_field(ArgField::SPR_DIV, 0, 16);
     for (int g = 0; g < 3; ++g) add_field(ArgField::GROUP_DIV, g, 16);
@@ -382,6 +383,7 @@ struct Gen {
     for (size_t i = 0; i < an.accesses.size(); ++i) {
       const Access& a = an.accesses[i];
       if (a.has_inner && a.kind == ACC_PARTIAL) o << "    disc::i64 b" << i << ";\n";
+      if (has_outer_window(a)) o << "    bool v" << i << ";\n";
       if (!a.has_inner && a.is_output && a.kind == ACC_PARTIAL) o << "    disc::i64 b" << i << ";\n";
     }
     // full-size operands: element offset of the row = sb + lb.  sb is the offset of the first row
@@ -405,6 +407,28 @@ struct Gen {
     if (need_rinv.count((int)i)) fn.body << "    rc.q" << i << " = 1.0f / rc.r" << i << ";\n";
     if (need_nl2e.count((int)i)) fn.body << "    rc.n" << i << " = -1.44269504088896341f * rc.r" << i << ";\n";
     fn.names[(int)i] = fmt("rc.r%zu", i);
+  }
+
+  bool has_outer_window(const Access& a) const {
+    if (!a.padded) return false;
+    for (size_t t = 0; t < a.groups.size(); ++t)
+      if (a.groups[t] != an.inner_group && a.window[t] >= 0) return true;
+    return false;
+  }
+  int window_arg(int w) const { return (int)(an.products.size() + an.offsets.size()) + 2 * w; }
+  // load of a slot of an operand; a padded one takes the padding value wherever the operand is not
+  std::string load_call(const Access& a, size_t i, const std::string& dst, const std::string& ld_tmpl, const std::string& extra) {
+    const std::string ptr = elem_ptr(a, fmt("A.p%d", a.slot));
+    if (!a.padded) return "disc::ld" + ld_tmpl + "(" + dst + ", " + ptr + ", " + elem_base(a, i) + ", sp" + extra + ");";
+    std::string lo = "0", hi = "0x7fffffffffffffffLL";
+    for (size_t t = 0; t < a.groups.size(); ++t)
+      if (a.groups[t] == an.inner_group && a.window[t] >= 0) {
+        lo = fmt("A.st%d", window_arg(a.window[t]));
+        hi = fmt("A.st%d", window_arg(a.window[t]) + 1);
+      }
+    const std::string ok = has_outer_window(a) ? fmt("rc.v%zu", i) : std::string("true");
+    return "disc::ld_win(" + dst + ", " + ptr + ", " + elem_base(a, i) + ", sp, (disc::i64)col, " + ok + ", " + lo + ", " + hi +
+           ", disc::pad_const<" + dtype_ctype(a.dtype) + ">(" + float_lit(a.pad_value) + "));";
   }
 
   // offset expression of an access without the inner group, for row `row`
@@ -445,7 +469,8 @@ struct Gen {
       if (a.kind == ACC_PARTIAL) {
         std::string e;
         size_t sp = 0;
-        if (a.offset_index >= 0) e = fmt("A.st%d", (int)an.products.size() + a.offset_index);
+        if (a.offset_index >= 0)
+          e = fmt("%sA.st%d", an.offsets[a.offset_index].negative ? "-" : "", (int)an.products.size() + a.offset_index);
         for (size_t t = 0; t < a.groups.size(); ++t) {
           if (a.groups[t] == an.inner_group) continue;
           if (!e.empty()) e += " + ";
@@ -454,6 +479,16 @@ struct Gen {
         if (e.empty()) e = "0";
         if (a.has_inner || a.is_output) os << "    rc.b" << i << " = " << e << ";\n";
         else os << "    const disc::i64 pb" << i << " = " << e << ";\n";
+        if (has_outer_window(a)) {
+          // the row lies inside the operand along every padded outer group
+          std::string v;
+          for (size_t t = 0; t < a.groups.size(); ++t) {
+            if (a.groups[t] == an.inner_group || a.window[t] < 0) continue;
+            if (!v.empty()) v += " && ";
+            v += fmt("ig[%d] >= A.st%d && ig[%d] < A.st%d", a.groups[t], window_arg(a.window[t]), a.groups[t], window_arg(a.window[t]) + 1);
+          }
+          os << "    rc.v" << i << " = " << v << ";\n";
+        }
       }
     }
     Fn fn(*this, M_ROWLOCAL);
@@ -536,8 +571,8 @@ struct Gen {
     for (size_t i = 0; i < an.accesses.size(); ++i) {
       const Access& a = an.accesses[i];
       if (a.is_output || !a.has_inner || !need[i] || late(a)) continue;
-      os << "    disc::ld" << (a.kind == ACC_FULL ? "<(NT & 1) != 0>" : "") << "(s.a" << i << ", " << elem_ptr(a, fmt("A.p%d", a.slot)) << ", "
-         << elem_base(a, i) << ", sp" << (a.kind == ACC_FULL ? std::string(", rc.tail_ok") : std::string()) << ");\n";
+      os << "    " << load_call(a, i, fmt("s.a%zu", i), a.kind == ACC_FULL ? "<(NT & 1) != 0>" : "",
+                            a.kind == ACC_FULL ? ", rc.tail_ok" : "") << "\n";
     }
     if (with_red) {
       int k = 0;
@@ -696,9 +731,9 @@ struct Gen {
         // a compile-time choice: behind a run-time branch the wait for the operand would cover both
         // the LDS and the global counter, and so also the row loads that are in flight for later
         o << ind << "if constexpr (STAGED) disc::ld_lds(l" << ai << ", rc.sl, stage_offset<V>(A, " << st << "), (int)col);\n";
-        o << ind << "else disc::ld(l" << ai << ", " << elem_ptr(a, fmt("A.p%d", a.slot)) << ", " << elem_base(a, ai) << ", sp);\n";
+        o << ind << "else " << load_call(a, ai, fmt("l%d", ai), "", "") << "\n";
       } else {
-        o << ind << "disc::ld(l" << ai << ", " << elem_ptr(a, fmt("A.p%d", a.slot)) << ", " << elem_base(a, ai) << ", sp);\n";
+        o << ind << load_call(a, ai, fmt("l%d", ai), "", "") << "\n";
       }
     }
   }

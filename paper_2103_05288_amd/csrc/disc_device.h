@@ -198,6 +198,32 @@ DISC_DEV void st(T* __restrict__ p, I off, const Vec<T, N>& s, Span sp) {
   }
 }
 
+// Slot of a padded operand: elements whose column lies in [wlo, whi) of a row that lies inside the
+// operand (row_ok) come from memory, the others are the padding value.  A slot wholly inside
+// takes the ordinary wide load; one that straddles an edge of the operand is read element by
+// element (two slots per row at most).
+template <class T>
+DISC_DEV T pad_const(float x) {
+  if constexpr (sizeof(T) == 1) return (T)(x != 0.0f);
+  else return (T)x;
+}
+template <class T, int N, class I>
+DISC_DEV void ld_win(Vec<T, N>& d, const T* __restrict__ p, I off, Span sp, i64 col, bool row_ok, i64 wlo, i64 whi, T padv) {
+  const i64 lo = wlo - col, hi = whi - col;        // the operand's columns in slot coordinates
+  if (row_ok && lo <= 0 && hi >= sp.n) {
+    ld(d, p, off, sp);
+  } else {
+    d.clear();
+#pragma unroll
+    for (int e = 0; e < N; ++e) {
+      T x = padv;
+      if (row_ok && sp.has(e) && e >= lo && e < hi) x = at(p, off)[e];
+      d.set(e, x);
+    }
+    __builtin_amdgcn_s_waitcnt(0x0F70);
+  }
+}
+
 // storage <-> register conversions (float values live in fp32 registers; one rounding,
 // to nearest even, at the store)
 DISC_DEV float to_f32(float x) { return x; }

@@ -85,6 +85,13 @@ struct Access {
   // Analysis::offsets, -1 = none) is the sum of start * stride over the sliced axes
   int src_value = -1;
   int offset_index = -1;
+  bool all_outer = false;  // spans every outer group: full-size data, loaded once per row like ACC_FULL
+  // PAD of a PARAM: as for SLICE, with the offset negative; `window[t]` (parallel to `groups`, -1 =
+  // none) names a pair of shape-calculation values [lo, hi): the operand exists where the index
+  // of that group lies inside, the rest of the result is `pad_value`
+  bool padded = false;
+  double pad_value = 0.0;
+  std::vector<int> window;
 };
 
 // Resolved graph: one node per (value, context) pair actually needed.
@@ -118,6 +125,14 @@ struct DimProduct {
 // the static value -1 - start.
 struct OffsetRecipe {
   std::vector<std::pair<int32_t, DimProduct>> terms;
+  bool negative = false;   // PAD: the operand starts `low` elements late, the offset is subtracted
+};
+// [lo, hi) of a padded operand in the index space of one collapsed group:
+// lo = low * inner_sizes, hi = (low + extent) * inner_sizes
+struct WindowRecipe {
+  int32_t low;             // encoded like a slice start
+  int32_t extent_dim;      // the operand's extent along the padded axis (symbolic id or -static)
+  DimProduct inner_sizes;  // product of the sizes of the group's axes behind the padded one
 };
 // Launch-time check of one sliced axis: 0 <= start and start + size <= extent of the operand
 struct SliceCheck {
@@ -155,6 +170,7 @@ struct Analysis {
   std::vector<DimProduct> products;      // strides of partial accesses
   std::vector<OffsetRecipe> offsets;     // base offsets of sliced operands (kernel argument st<products.size() + i>)
   std::vector<SliceCheck> slice_checks;
+  std::vector<WindowRecipe> windows;     // kernel arguments st<products + offsets + 2 i> (lo) and + 1 (hi)
   std::vector<int> dim_size_syms;        // symbolic dims referenced by DIM_SIZE nodes
   int vec_width = 1;                     // elements per vector slot
 };

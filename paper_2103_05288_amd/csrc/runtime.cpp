@@ -223,7 +223,7 @@ int shape_calc(disc_ctx* c, const Pattern& p, const int64_t* dims, int n_dims, S
   sv->rows = 1;
   for (int g = 0; g < an.inner_group; ++g) sv->rows *= sv->group[g];
   sv->mid = an.mid_group >= 0 ? sv->group[an.mid_group] : 0;
-  sv->products.resize(an.products.size() + an.offsets.size());
+  sv->products.resize(an.products.size() + an.offsets.size() + 2 * an.windows.size());
   for (size_t i = 0; i < an.products.size(); ++i)
     if (!eval_product(an.products[i], dims, &sv->products[i]))
       return set_err(c, DISC_ERR_SHAPE, "stride overflows int64");
@@ -233,8 +233,8 @@ int shape_calc(disc_ctx* c, const Pattern& p, const int64_t* dims, int n_dims, S
   for (const auto& sc : an.slice_checks) {
     const int64_t st = start_val(sc.start), n = dim_val(sc.size_dim), ext = dim_val(sc.src_dim);
     if (st < 0 || n > ext || st > ext - n) {
-      snprintf(buf, sizeof buf, "op %d (slice), axis %d: [%lld, %lld) leaves the operand's extent %lld", sc.op, sc.axis,
-               (long long)st, (long long)(st + n), (long long)ext);
+      snprintf(buf, sizeof buf, "op %d (%s), axis %d: [%lld, %lld) does not fit the extent %lld", sc.op,
+               an.ops[sc.op].opcode == DISC_PAD ? "pad" : "slice", sc.axis, (long long)st, (long long)(st + n), (long long)ext);
       return set_err(c, DISC_ERR_SHAPE, buf);
     }
   }
@@ -247,6 +247,15 @@ int shape_calc(disc_ctx* c, const Pattern& p, const int64_t* dims, int n_dims, S
         return set_err(c, DISC_ERR_SHAPE, "slice offset overflows int64");
     }
     sv->products[an.products.size() + i] = sum;
+  }
+  for (size_t i = 0; i < an.windows.size(); ++i) {
+    const WindowRecipe& w = an.windows[i];
+    int64_t inner = 0, lo = 0, hi = 0;
+    if (!eval_product(w.inner_sizes, dims, &inner) || mul_ovf(start_val(w.low), inner, &lo) ||
+        mul_ovf(start_val(w.low) + dim_val(w.extent_dim), inner, &hi))
+      return set_err(c, DISC_ERR_SHAPE, "padding window overflows int64");
+    sv->products[an.products.size() + an.offsets.size() + 2 * i] = lo;
+    sv->products[an.products.size() + an.offsets.size() + 2 * i + 1] = hi;
   }
   sv->alg_bytes = 0;
   for (const auto& io : p.io_numel) {
@@ -862,7 +871,7 @@ static int register_impl(disc_ctx* ctx, const disc_op* ops, int n_ops, const dis
   // counts with the elements its slices read
   std::vector<char> read_whole(p->an.ops.size(), 0);
   for (const auto& op : p->an.ops) {
-    if (op.opcode == DISC_SLICE || op.opcode <= DISC_DIM_SIZE) continue;
+    if (op.opcode == DISC_SLICE || op.opcode <= DISC_DIM_SIZE) continue;   // (a PAD reads its operand whole)
     for (int k = 0; k < 3; ++k)
       if (op.in[k] >= 0 && (k == 0 || op.opcode == DISC_SELECT || (op.opcode >= DISC_ADD && op.opcode <= DISC_NE)))
         read_whole[op.in[k]] = 1;
