@@ -97,7 +97,8 @@ typedef enum {
                       PARAM may be sliced several times).  A launch whose slice leaves the operand
                       fails with DISC_ERR_SHAPE.                                               */
   DISC_PAD,        /* dynamic pad of a PARAM (named beside slice in Section 4.1), no interior padding:
-                      result[i] = in[i - low] where that exists, else `fconst`; dim[] = sizes of the
+                      result[i] = in[i - low] where that exists, else `fconst` rounded to the operand's dtype
+                      (the padding value is a scalar of the operand's element type); dim[] = sizes of the
                       result, axis_map[k] = padding in front of axis k, encoded like a SLICE start.
                       in[0] must be a PARAM; the padding is produced in registers, never written to
                       memory on its own.  A launch whose operand does not fit the result fails with

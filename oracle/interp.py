@@ -41,7 +41,9 @@ with those standard meanings:
                             4.1): the operand sits at offset low_k along every axis of a result
                             otherwise filled with the padding value; low_k are runtime values
                             (or static), the result sizes are the op's dims; an operand that
-                            does not fit is an error
+                            does not fit is an error.  The padding value is a scalar of the
+                            operand's element type (HLO pad), so unlike computed values it IS
+                            rounded to that type (nearest even) when it is not representable
 
 Inputs stored as f16 / bf16 are converted to float64 by the caller (every such
 value is exactly representable); the oracle itself only sees numpy arrays.
@@ -71,6 +73,21 @@ def _as_dtype(x: np.ndarray, dtype: str) -> np.ndarray:
     if dtype == "bool":
         return x != 0
     raise OracleError(f"unknown dtype {dtype}")
+
+
+def _round_to_storage(value: float, dtype: str):
+    """A constant of a storage type: the nearest representable value, ties to even."""
+    if dtype == "f32":
+        return np.float64(np.float32(value))
+    if dtype == "f16":
+        return np.float64(np.float16(value))
+    if dtype == "bf16":
+        if not np.isfinite(value):
+            return np.float64(value)
+        bits = int(np.float32(value).view(np.uint32))
+        bits = (bits + 0x7FFF + ((bits >> 16) & 1)) & 0xFFFF0000     # keep 8 significant bits, ties to even
+        return np.float64(np.uint32(bits).view(np.float32))
+    return value
 
 
 def _broadcast_in_dim(x: np.ndarray, out_shape: Tuple[int, ...], axis_map: Sequence[int]) -> np.ndarray:
@@ -227,7 +244,7 @@ def _run(pattern, dims, inputs):
             for k, (l0, n) in enumerate(zip(low, want)):
                 if l0 < 0 or l0 + x.shape[k] > n:
                     raise OracleError(f"op {idx}: operand [{l0}, {l0 + x.shape[k]}) does not fit axis {k} of size {n}")
-            fill = _as_dtype(np.asarray(op.fconst, dtype=np.float64), op.dtype)
+            fill = _as_dtype(np.asarray(_round_to_storage(op.fconst, op.dtype), dtype=np.float64), op.dtype)
             v = np.full(want, fill, dtype=x.dtype)
             v[tuple(slice(l0, l0 + m) for l0, m in zip(low, x.shape))] = x
         elif oc == "output":

@@ -496,3 +496,15 @@ def test_pad_matches_index_loops_and_inverts_slice():
     got = run(pb.build(), [4, 6, 9], [x2])[0][0]
     np.testing.assert_allclose(got[:, :6], scipy.special.softmax(x2, axis=1), rtol=1e-13)
     assert np.all(got[:, 6:] == 0.0)
+
+
+def test_pad_value_has_the_operands_type():
+    """The padding value is a scalar of the operand's element type: 0.654... is not a bf16 / f16 /
+    f32 number and arrives as the nearest one (torch's conversion as the independent reference)."""
+    for dtype, tdt in (("bf16", torch.bfloat16), ("f16", torch.float16), ("f32", torch.float32)):
+        for value in (0.6540060516381072, -1.0e-3, 3.0, float("-inf"), 1.00390625, 1.01171875):   # the last two: bf16 ties
+            pb = PatternBuilder()
+            H, P = pb.dims(2)
+            pb.output(pb.pad(pb.param(dtype, [H]), [pb.static_start(0)], [P], value))
+            out = run(pb.build(), [2, 5], [np.zeros(2)])[0][0]
+            assert out[2] == out[3] == out[4] == float(torch.tensor(value, dtype=torch.float64).to(tdt).double())

@@ -1,5 +1,6 @@
 """Seeded random fusion patterns against the oracle: element-wise DAGs over rank-2 / rank-3 spaces
-with row vectors, per-row operands, scalars, masks and mixed storage types; no reduction (loop
+with row vectors, per-row operands, scalars, masks, windows (dynamic slices) of larger inputs,
+padded smaller inputs and mixed storage types; no reduction (loop
 fusion), one or two dependent row reductions with an epilogue, or a column reduction with an
 epilogue.  Every pattern is compiled once and launched at several shapes (ragged and aligned).
 
@@ -41,6 +42,7 @@ class Gen:
         self.dims = self.pb.dims(self.rank)
         self.full = list(self.dims)
         self.inputs = []          # (kind, dtype, dims)
+        self.extra = []           # windows / pads: the symbolic dims that need runtime values of their own
         self.kind = ["loop", "row", "row2", "col"][int(self.rng.integers(0, 4))]
 
     def pick(self, seq):
@@ -52,7 +54,7 @@ class Gen:
     def leaf(self):
         """A full-shaped fp32 value from a fresh or broadcast operand."""
         pb, full, rank = self.pb, self.full, self.rank
-        what = self.pick(["full", "full", "rowvec", "perrow", "const"])
+        what = self.pick(["full", "full", "rowvec", "perrow", "const", "window", "padded"])
         if what == "full":
             dt = self.pick(FLOATS)
             v = pb.param(dt, full)
@@ -67,6 +69,29 @@ class Gen:
             v = pb.param("f32", full[:-1])
             self.inputs.append(("normal", "f32", full[:-1]))
             return pb.broadcast(v, full, list(range(rank - 1)))
+        if what in ("window", "padded"):
+            # an input with extents of its own along the last two axes; the full shape is a window
+            # of it at a runtime offset (slice) or it sits inside the full shape at a runtime
+            # offset, the rest being a constant (pad)
+            dt = self.pick(FLOATS)
+            own = list(full)
+            starts = [pb.static_start(0)] * rank
+            spec = {"kind": what, "axes": []}
+            for ax in (rank - 2, rank - 1):
+                if self.rng.random() < 0.7:
+                    own[ax] = pb.dim()
+                    starts[ax] = pb.dim()
+                    spec["axes"].append((ax, own[ax], starts[ax]))
+            if not spec["axes"]:
+                own[rank - 1] = pb.dim()
+                starts[rank - 1] = pb.dim()
+                spec["axes"].append((rank - 1, own[rank - 1], starts[rank - 1]))
+            v = pb.param(dt, own)
+            self.inputs.append(("normal", dt, own))
+            self.extra.append(spec)
+            if what == "window":
+                return self.f32(pb.slice(v, starts, full))
+            return self.f32(pb.pad(v, starts, full, float(self.rng.uniform(-1.0, 1.0))))
         c = pb.const(float(self.rng.uniform(-1.5, 1.5)))
         return pb.op("add", self.leaf_full(), c)
 
@@ -136,6 +161,23 @@ class Gen:
         return out
 
 
+def complete_dims(gen, pat, base, rng):
+    """Runtime values for the extents and offsets of windowed / padded inputs, given the base shape."""
+    dims = list(base) + [0] * (pat.n_dims - len(base))
+    for spec in gen.extra:
+        for ax, own, start in spec["axes"]:
+            n = int(dims[gen.full[ax]])
+            if spec["kind"] == "window":          # the input is larger: own = start + n + slack
+                st = int(rng.integers(0, 9))
+                dims[start] = st
+                dims[own] = st + n + int(rng.integers(0, 9))
+            else:                                  # the input is smaller: start + own <= n
+                o = int(rng.integers(0, n + 1))
+                dims[own] = o
+                dims[start] = int(rng.integers(0, n - o + 1))
+    return dims
+
+
 def shapes_for(gen, rng):
     inner = [1, 7, 8, 33, 127, 200, 513, 1000, 1025, 2047, 3001, 4099]
     res = []
@@ -156,7 +198,8 @@ def test_random_pattern(ctx, seed):
     want_tmpl = {"loop": "loop", "row": "row_reduce", "row2": "row_reduce", "col": "col_reduce"}[gen.kind]
     assert h.info["template"] == want_tmpl, (seed, gen.kind, h.info["template"])
     rng = np.random.default_rng(1000 + seed)
-    for dims in shapes_for(gen, rng):
+    for base in shapes_for(gen, rng):
+        dims = complete_dims(gen, pat, base, rng)
         ins = gen.draw(dims, seed=seed * 7 + len(dims))
         got = run_gpu(h, pat, dims, ins)
         want = oracle_run(pat, dims, [to_oracle_input(t) for t in ins])[0]
