@@ -166,12 +166,8 @@ template <bool NT = false, class T, int N, class I>
 DISC_DEV void ld(Vec<T, N>& d, const T* __restrict__ p, I off, Span sp, bool whole_ok = false) {
   if (sp.full(N) || whole_ok) {
     const auto* q = reinterpret_cast<const typename Vec<T, N>::unaligned_t*>(at(p, off));
-#ifdef DISC_NT_LD
-    d.v = __builtin_nontemporal_load(q);
-#else
     if constexpr (NT) d.v = __builtin_nontemporal_load(q);
     else d.v = *q;
-#endif
   } else {
     d.clear();
     ld_pieces<N / 2>(d, p, off, sp.n);
@@ -187,12 +183,8 @@ template <bool NT = false, class T, int N, class I>
 DISC_DEV void st(T* __restrict__ p, I off, const Vec<T, N>& s, Span sp) {
   if (sp.full(N)) {
     auto* q = reinterpret_cast<typename Vec<T, N>::unaligned_t*>(at(p, off));
-#ifdef DISC_NT_ST
-    __builtin_nontemporal_store(s.v, q);
-#else
     if constexpr (NT) __builtin_nontemporal_store(s.v, q);
     else *q = s.v;
-#endif
   } else {
     st_pieces<N / 2>(p, off, s, sp.n);
   }

@@ -740,7 +740,6 @@ int disc_create(disc_ctx** out, int hip_device) {
   if (const char* e = getenv("DISC_ROW_TURN")) c->row_turn = atoi(e) != 0;
   if (const char* e = getenv("DISC_ROW_ROUNDS")) c->row_rounds = std::max(0, atoi(e));
   if (const char* e = getenv("DISC_GRID_MULT")) c->grid_mult = std::max(1, std::min(64, atoi(e)));
-  if (const char* e = getenv("DISC_LOOP_UNROLL")) (void)e;   // the unroll factor is a compile-time constant of the kernels
   *out = c.release();
   return DISC_OK;
 }
