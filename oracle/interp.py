@@ -37,6 +37,9 @@ with those standard meanings:
                             result sizes are the op's dims, the starts come from the
                             runtime dims (or are static); a slice that leaves the operand
                             is an error
+* transpose               : HLO transpose (the paper names Transpose among its examples of ops
+                            whose shapes propagate, Section 4.2.1): result axis k is operand
+                            axis perm[k], materialised as a real copy
 * pad                     : dynamic pad without interior padding (named beside slice in Section
                             4.1): the operand sits at offset low_k along every axis of a result
                             otherwise filled with the padding value; low_k are runtime values
@@ -236,6 +239,11 @@ def _run(pattern, dims, inputs):
                 if s0 < 0 or s0 + n > x.shape[k]:
                     raise OracleError(f"op {idx}: slice [{s0}, {s0 + n}) leaves axis {k} of size {x.shape[k]}")
             v = x[tuple(slice(s0, s0 + n) for s0, n in zip(starts, want))].copy()
+        elif oc == "transpose":
+            x = vals[op.ins[0]]
+            if sorted(op.axis_map) != list(range(x.ndim)):
+                raise OracleError(f"op {idx}: transpose needs a permutation of the operand's axes")
+            v = np.ascontiguousarray(np.transpose(x, op.axis_map))
         elif oc == "pad":
             x = vals[op.ins[0]]
             if len(op.axis_map) != x.ndim or len(want) != x.ndim:

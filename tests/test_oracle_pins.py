@@ -508,3 +508,31 @@ def test_pad_value_has_the_operands_type():
             pb.output(pb.pad(pb.param(dtype, [H]), [pb.static_start(0)], [P], value))
             out = run(pb.build(), [2, 5], [np.zeros(2)])[0][0]
             assert out[2] == out[3] == out[4] == float(torch.tensor(value, dtype=torch.float64).to(tdt).double())
+
+
+def test_transpose_matches_index_loops():
+    for perm in ((1, 0), (0, 2, 1), (2, 0, 1), (1, 0, 2, 3), (3, 2, 1, 0)):
+        rank = len(perm)
+        shape = (3, 4, 2, 5)[:rank]
+        pb = PatternBuilder()
+        x = pb.param("f32", pb.dims(rank))
+        t = pb.transpose(x, perm)
+        pb.output(t)
+        xa = rng.normal(size=shape)
+        out = run(pb.build(), list(shape), [xa])[0][0]
+        assert out.shape == tuple(shape[a] for a in perm)
+        for idx in itertools.product(*[range(n) for n in out.shape]):
+            src = [0] * rank
+            for k, a in enumerate(perm):
+                src[a] = idx[k]
+            assert out[idx] == xa[tuple(src)]
+        assert np.array_equal(out, torch.from_numpy(xa).permute(*perm).numpy())
+    # the inverse permutation undoes it
+    pb = PatternBuilder()
+    B, S, H = pb.dims(3)
+    x = pb.param("f32", [B, S, H])
+    t = pb.transpose(x, (2, 0, 1))               # [H, B, S]
+    pb.output(pb.op("neg", t))
+    xa = rng.normal(size=(2, 3, 4))
+    out = run(pb.build(), [2, 3, 4], [xa])[0][0]
+    assert np.array_equal(np.transpose(-out, (1, 2, 0)), xa)

@@ -31,6 +31,8 @@ Conventions
   axis ``k`` (encoded like a slice start), ``fconst`` the padding value; the
   padding behind an axis is whatever the result size leaves.  No interior
   padding, no negative padding.
+* ``transpose``     : HLO transpose: result axis ``k`` is operand axis ``axis_map[k]``
+  (``axis_map`` is a permutation).
 """
 from __future__ import annotations
 
@@ -44,7 +46,7 @@ UNARY = ("neg", "abs", "exp", "log", "tanh", "sqrt", "rsqrt", "rcp", "sigmoid", 
 BINARY = ("add", "sub", "mul", "div", "max", "min", "pow")
 COMPARE = ("lt", "le", "gt", "ge", "eq", "ne")
 REDUCE = ("reduce_sum", "reduce_max", "reduce_min", "reduce_argmax")
-OPCODES = LEAF + UNARY + BINARY + COMPARE + ("select", "cast", "broadcast") + REDUCE + ("output", "slice", "pad")
+OPCODES = LEAF + UNARY + BINARY + COMPARE + ("select", "cast", "broadcast") + REDUCE + ("output", "slice", "pad", "transpose")
 
 DIM_EQ = 0      # dimension-size equality constraint
 NUMEL_EQ = 1    # tensor-size equality constraint
@@ -171,6 +173,12 @@ class PatternBuilder:
             if s_ >= 0:
                 self.p.n_dims = max(self.p.n_dims, s_ + 1)
         return self._push(Op("slice", src.dtype, (v,), tuple(sizes), tuple(int(x) for x in starts)))
+
+    def transpose(self, v: int, perm: Sequence[int]) -> int:
+        """result axis k = operand axis perm[k]."""
+        src = self.p.ops[v]
+        assert sorted(perm) == list(range(len(src.dims)))
+        return self._push(Op("transpose", src.dtype, (v,), tuple(src.dims[a] for a in perm), tuple(int(a) for a in perm)))
 
     def pad(self, v: int, low: Sequence[int], sizes: Sequence[int], value: float = 0.0) -> int:
         """result[i] = v[i - low] where that exists, ``value`` elsewhere; ``sizes`` are the result dims."""
