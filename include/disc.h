@@ -103,6 +103,11 @@ typedef enum {
                       in[0] must be a PARAM; the padding is produced in registers, never written to
                       memory on its own.  A launch whose operand does not fit the result fails with
                       DISC_ERR_SHAPE.                                                          */
+  DISC_TRANSPOSE,  /* HLO transpose of a PARAM: result axis k = operand axis axis_map[k] (a permutation).
+                      in[0] must be a PARAM; an indexing function like SLICE, never a copy.  The
+                      operand's innermost axis must stay the innermost axis of the pattern's
+                      iteration space (accesses stay contiguous along rows); a transpose that moves
+                      it is refused with DISC_ERR_UNFUSIBLE.                                    */
   DISC_OPCODE_COUNT
 } disc_opcode;
 

@@ -17,7 +17,7 @@ DTYPE_IDS = {"f32": 0, "f16": 1, "bf16": 2, "i32": 3, "i64": 4, "bool": 5}
 _OPCODES = ("param", "const", "dim_size", "neg", "abs", "exp", "log", "tanh", "sqrt", "rsqrt", "rcp",
             "sigmoid", "erf", "add", "sub", "mul", "div", "max", "min", "pow", "lt", "le", "gt", "ge",
             "eq", "ne", "select", "cast", "broadcast", "reduce_sum", "reduce_max", "reduce_min",
-            "reduce_argmax", "output", "slice", "pad")
+            "reduce_argmax", "output", "slice", "pad", "transpose")
 OPCODE_IDS = {n: i for i, n in enumerate(_OPCODES)}
 VARIANTS = ("loop_vec", "loop_vec_i64", "loop_scalar", "loop_scalar_i64", "row_reg_vec", "row_reg_scalar",
             "row_stream_vec", "row_stream_scalar", "col_3stage_vec", "col_3stage_scalar", "col_strip_vec",

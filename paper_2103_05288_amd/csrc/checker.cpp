@@ -43,7 +43,7 @@ const char* opcode_name(int oc) {
   static const char* names[] = {"param", "const", "dim_size", "neg", "abs", "exp", "log", "tanh",
     "sqrt", "rsqrt", "rcp", "sigmoid", "erf", "add", "sub", "mul", "div", "max", "min", "pow",
     "lt", "le", "gt", "ge", "eq", "ne", "select", "cast", "broadcast", "reduce_sum", "reduce_max",
-    "reduce_min", "reduce_argmax", "output", "slice", "pad"};
+    "reduce_min", "reduce_argmax", "output", "slice", "pad", "transpose"};
   if (oc < 0 || oc >= DISC_OPCODE_COUNT) return "?";
   return names[oc];
 }
@@ -105,7 +105,7 @@ bool is_elementwise(int oc) {
 }
 int n_operands(int oc) {
   if (oc <= DISC_DIM_SIZE) return 0;
-  if (is_unary(oc) || oc == DISC_CAST || oc == DISC_BROADCAST || is_reduce(oc) || oc == DISC_OUTPUT || oc == DISC_SLICE || oc == DISC_PAD)
+  if (is_unary(oc) || oc == DISC_CAST || oc == DISC_BROADCAST || is_reduce(oc) || oc == DISC_OUTPUT || oc == DISC_SLICE || oc == DISC_PAD || oc == DISC_TRANSPOSE)
     return 1;
   if (oc == DISC_SELECT) return 3;
   return 2;
@@ -138,8 +138,10 @@ struct Builder {
       if (!an.classes.same(an.classes.atom(op.dim[k]), an.classes.atom(an.root_dims[k]))) return false;
     return true;
   }
-  // axis k of a SLICE op covers the whole axis of its operand: static start 0 and provably the same size
+  // axis k of a SLICE / PAD op covers the whole axis of its operand: static start 0 and provably
+  // the same size (a TRANSPOSE covers every axis)
   bool slice_axis_full(const disc_op& op, int k) {
+    if (op.opcode == DISC_TRANSPOSE) return true;
     const disc_op& src = an.ops[op.in[0]];
     return op.axis_map[k] == -1 && an.classes.same(an.classes.atom(op.dim[k]), an.classes.atom(src.dim[k]));
   }
@@ -176,15 +178,21 @@ struct Builder {
       a.slot = slot;
       n.access = (int)an.accesses.size();
       an.accesses.push_back(a);
-    } else if (oc == DISC_SLICE || oc == DISC_PAD) {
-      // an indexing function on the sliced / padded PARAM: the node is a PARAM node whose access
-      // carries the PARAM's own extents and the offsets
+    } else if (oc == DISC_SLICE || oc == DISC_PAD || oc == DISC_TRANSPOSE) {
+      // an indexing function on the sliced / padded / transposed PARAM: the node is a PARAM node
+      // whose access carries the PARAM's own extents and the offsets.  The context of the access
+      // is kept in the order of the PARAM's axes.
       n.opcode = DISC_PARAM;
       Access a;
       a.value = v;
       a.src_value = op.in[0];
       a.padded = oc == DISC_PAD;
       a.pad_value = op.fconst;
+      if (oc == DISC_TRANSPOSE) {
+        Ctx pc(c.size(), -1);
+        for (int k = 0; k < op.rank; ++k) pc[op.axis_map[k]] = c[k];
+        c = pc;
+      }
       a.is_output = false;
       a.dtype = op.dtype;
       a.ctx = c;
@@ -335,6 +343,17 @@ int analyze(const disc_op* ops, int n_ops, const disc_constraint* cs, int n_cs, 
         if (op.axis_map[k] >= 0) n_sym = std::max(n_sym, op.axis_map[k] + 1);
       }
     }
+    if (oc == DISC_TRANSPOSE) {
+      const disc_op& src = ops[op.in[0]];
+      if (src.opcode != DISC_PARAM) return bad("TRANSPOSE applies to a PARAM (transpose the input, then compute)");
+      if (src.dtype != op.dtype) return bad("TRANSPOSE changes dtype");
+      if (src.rank != op.rank || op.rank < 1) return bad("TRANSPOSE keeps the rank of its operand (>= 1)");
+      int seen = 0;
+      for (int k = 0; k < op.rank; ++k) {
+        if (op.axis_map[k] < 0 || op.axis_map[k] >= op.rank || (seen >> op.axis_map[k] & 1)) return bad("TRANSPOSE needs a permutation");
+        seen |= 1 << op.axis_map[k];
+      }
+    }
     if (oc == DISC_BROADCAST) {
       const disc_op& src = ops[op.in[0]];
       if (src.dtype != op.dtype) return bad("BROADCAST changes dtype");
@@ -379,6 +398,10 @@ int analyze(const disc_op* ops, int n_ops, const disc_constraint* cs, int n_cs, 
         for (int a = 0; a < op.rank; ++a)
           if (!unite(i, src.dim[a], op.dim[a])) return DISC_ERR_BAD_PATTERN;
       }
+    } else if (oc == DISC_TRANSPOSE) {
+      const disc_op& src = ops[op.in[0]];
+      for (int k = 0; k < op.rank; ++k)
+        if (!unite(i, src.dim[op.axis_map[k]], op.dim[k])) return DISC_ERR_BAD_PATTERN;
     } else if (oc == DISC_BROADCAST) {
       const disc_op& src = ops[op.in[0]];
       for (int k = 0; k < src.rank; ++k) {
@@ -528,9 +551,9 @@ int analyze(const disc_op* ops, int n_ops, const disc_constraint* cs, int n_cs, 
     // (non-broadcast) tensor of the common element count or a scalar.
     for (int i = 0; i < n_ops; ++i) {
       const disc_op& op = ops[i];
-      if (op.opcode == DISC_BROADCAST || op.opcode == DISC_SLICE || op.opcode == DISC_PAD) {
+      if (op.opcode == DISC_BROADCAST || op.opcode == DISC_SLICE || op.opcode == DISC_PAD || op.opcode == DISC_TRANSPOSE) {
         snprintf(buf, sizeof buf, "op %d (%s): outputs agree only in element count, so the pattern is "
-                 "fused over a flat index and cannot contain a broadcast, a slice or a pad", i, opcode_name(op.opcode));
+                 "fused over a flat index and cannot contain a broadcast, a slice, a pad or a transpose", i, opcode_name(op.opcode));
         err = buf;
         return DISC_ERR_UNFUSIBLE;
       }
@@ -622,7 +645,7 @@ int analyze(const disc_op* ops, int n_ops, const disc_constraint* cs, int n_cs, 
               if (a.ctx[k] == j) pj = k;
             }
             if (pi < 0 && pj < 0) continue;
-            if (pi < 0 || pj < 0) { join = false; break; }
+            if (pi < 0 || pj < 0 || pj < pi) { join = false; break; }   // (pj < pi: a transposed operand)
             for (int k = pi + 1; k < pj; ++k)
               if (a.ctx[k] != -1) { join = false; break; }
             // a sliced operand is contiguous across the two axes only if the inner one is whole
@@ -763,13 +786,24 @@ int analyze(const disc_op* ops, int n_ops, const disc_constraint* cs, int n_cs, 
           an.windows.push_back(w);
         }
         a.window.push_back(win);
-        if (a.groups[t] == an.inner_group) continue;
+        if (a.groups[t] == an.inner_group) {
+          // rows must stay contiguous in the operand: nothing but unit axes behind the inner group
+          for (int k = last + 1; k < src.rank; ++k)
+            if (!b.dim_is_one(src.dim[k])) {
+              snprintf(buf, sizeof buf, "op %d (%s): the operand's innermost axis is not the innermost axis of the "
+                       "iteration space; a transpose that moves it needs a tile transpose and is not fused", a.value,
+                       opcode_name(sl.opcode));
+              err = buf;
+              return DISC_ERR_UNFUSIBLE;
+            }
+          continue;
+        }
         a.stride_prod.push_back((int)an.products.size());
         an.products.push_back(tail_product(last));
       }
       OffsetRecipe off;
       off.negative = a.padded;
-      for (int k = 0; k < sl.rank; ++k) {
+      for (int k = 0; k < sl.rank && sl.opcode != DISC_TRANSPOSE; ++k) {
         if (sl.axis_map[k] != -1) off.terms.push_back({sl.axis_map[k], tail_product(k)});
         if (!b.slice_axis_full(sl, k)) {
           if (a.padded && b.dim_is_one(sl.dim[k])) {
