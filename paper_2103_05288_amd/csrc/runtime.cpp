@@ -294,11 +294,16 @@ struct FullPlan {
 
 // Loop-fusion launch geometry for an iteration space [rows, inner]; shared by loop patterns and
 // by the epilogue stage of column reduces.  want_vec / want_i64: -1 = let the shape decide.
+// Launches that move less than this may be read back from the memory-side cache (256 MB) by
+// whatever kernel consumes the result; the non-temporal versions are kept for larger ones, which
+// stream through the caches anyway.
+constexpr int64_t kNonTemporalMinBytes = 64ll << 20;
+
 // nt_name: the non-temporal sibling of names[0] (vector width, 32-bit index), taken for large
-// launches (8 Mi elements or more: nothing of them stays in a cache anyway) whose rows start on
-// 16-byte boundaries (`aligned`: the full-size operands are; inner a multiple of the width).
+// launches (`big`) whose rows start on 16-byte boundaries (`aligned`: the full-size operands are;
+// inner a multiple of the width).
 int plan_loop(disc_ctx* c, int64_t rows, int64_t inner, int V, int want_vec, int want_i64, const char* const names[4],
-              const char* nt_name, bool aligned, FullPlan* fp, LaunchRec* L, bool* vec_out, bool* i64_out) {
+              const char* nt_name, bool aligned, bool big, FullPlan* fp, LaunchRec* L, bool* vec_out, bool* i64_out) {
   bool vec;
   {
     const int64_t spr_v = (inner + V - 1) / V;
@@ -318,7 +323,7 @@ int plan_loop(disc_ctx* c, int64_t rows, int64_t inner, int V, int want_vec, int
   blocks = std::min(blocks, i64 ? max_grid * 4 : max_grid);
   L->kernel = names[(vec ? 0 : 2) + (i64 ? 1 : 0)];
   if (nt_name && vec && v > 1 && !i64 && aligned && inner % v == 0 && c->row_nt != 0 &&
-      (c->row_nt > 0 || nslots >= (8ll << 20) / v))
+      (c->row_nt > 0 || big))
     L->kernel = nt_name;
   L->grid[0] = (uint32_t)blocks;
   L->block = 256;
@@ -382,7 +387,7 @@ int make_plan(disc_ctx* c, const Pattern& p, const int64_t* dims, int n_dims, in
     }
     static const char* const names[] = {"k_loop_vec", "k_loop_vec_i64", "k_loop_scalar", "k_loop_scalar_i64"};
     bool vec, i64;
-    rc = plan_loop(c, sv.rows, sv.inner, V, want_vec, want_i64, names, "k_loop_vec_nt", full_aligned(), fp, &fp->launches[0], &vec, &i64);
+    rc = plan_loop(c, sv.rows, sv.inner, V, want_vec, want_i64, names, "k_loop_vec_nt", full_aligned(), sv.alg_bytes >= kNonTemporalMinBytes, fp, &fp->launches[0], &vec, &i64);
     if (rc) return rc;
     pub.variant = vec ? (i64 ? DISC_V_LOOP_VEC_I64 : DISC_V_LOOP_VEC) : (i64 ? DISC_V_LOOP_SCALAR_I64 : DISC_V_LOOP_SCALAR);
     pub.n_launches = 1;
@@ -470,11 +475,12 @@ int make_plan(disc_ctx* c, const Pattern& p, const int64_t* dims, int n_dims, in
         // every row is a whole number of 128-byte cache lines (from 128 elements on) or the row has
         // at least 512 elements.  Rows whose first and last cache lines are shared with their
         // neighbours lose with it (-25 % for 360- or 464-element rows, -30 % for short odd rows),
-        // as do operands that are read more than once, which never get the hint.
+        // as do operands that are read more than once, which never get the hint.  Small launches
+        // (kNonTemporalMinBytes) keep the plain version: their results may be consumed from cache.
         bool nt = false;
         if (vec && V > 1 && !wide_version && c->row_nt != 0) {
           nt = c->row_nt > 0;
-          if (c->row_nt < 0 && sv.inner % V == 0 && sv.inner >= 128) {
+          if (c->row_nt < 0 && sv.inner % V == 0 && sv.inner >= 128 && sv.alg_bytes >= kNonTemporalMinBytes) {
             nt = true;
             bool whole_lines = true;
             for (const Access& a : an.accesses) {
@@ -608,7 +614,7 @@ int make_plan(disc_ctx* c, const Pattern& p, const int64_t* dims, int n_dims, in
     if (p.gen.has_epilogue) {
       static const char* const names[] = {"k_col_epi_vec", "k_col_epi_vec_i64", "k_col_epi_scalar", "k_col_epi_scalar_i64"};
       bool v2, i64;
-      rc = plan_loop(c, sv.rows, inner, V, vec ? 1 : 0, -1, names, "k_col_epi_vec_nt", full_aligned(), fp, &fp->launches[2], &v2, &i64);
+      rc = plan_loop(c, sv.rows, inner, V, vec ? 1 : 0, -1, names, "k_col_epi_vec_nt", full_aligned(), sv.alg_bytes >= kNonTemporalMinBytes, fp, &fp->launches[2], &v2, &i64);
       if (rc) return rc;
       pub.n_launches = 3;
     } else {

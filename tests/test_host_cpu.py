@@ -249,14 +249,16 @@ def test_row_schedule_capacity_steps(handles):
         assert G * nv * 8 >= H
         want = "k_row_vec_nv%d%s" % (max(nv, 2 if block > 256 else 1), "w" if block > 256 else "")
         name = p["kernels"][0]
-        # the non-temporal version: rows that start and end on 16-byte boundaries, 128 elements or
-        # more, blocks of 256 threads
-        assert name.endswith("_nt") == (H % 8 == 0 and H >= 128 and block == 256), (H, name)
-        name = name[:-3] if name.endswith("_nt") else name
+        assert not name.endswith("_nt")                       # a small launch: its result may be wanted from cache
         assert name.endswith(want + "_s") or name.endswith(want), (H, p["kernels"])
+        # the non-temporal version: launches of 64 MiB or more whose rows start and end on 16-byte
+        # boundaries, 128 elements or more, blocks of 256 threads
+        big = h.plan([(80 << 20) // (5 * H) + 1, H])["kernels"][0]
+        assert big.endswith("_nt") == (H % 8 == 0 and H >= 128 and block == 256), (H, big)
+        assert (big[:-3] if big.endswith("_nt") else big) == name
     assert h.plan([50, 24577])["variant_name"] == "row_stream_vec"
     # below 512 elements the non-temporal version needs rows of whole 128-byte lines in every operand
-    assert [h.plan([50, H])["kernels"][0].endswith("_nt") for H in (128, 200, 360, 384, 504, 512, 520)] == \
+    assert [h.plan([200000, H])["kernels"][0].endswith("_nt") for H in (128, 200, 360, 384, 504, 512, 520)] == \
         [True, False, False, True, False, True, True]
     # C4 stages a float32 row vector: 4 bytes x H must fit 48 KiB
     assert h.plan([50, 8192])["kernels"][0].endswith("_s") and h.plan([50, 8192])["lds_bytes"][0] >= 4 * 8192
@@ -271,27 +273,27 @@ def test_single_shape_registration(ctx, handles):
     versions in the module, its extents and launch plan as constants; other dims are refused."""
     pat = CONFIGS["C4"].pattern()
     before = ctx.stats()
-    a = ctx.register_static(pat, [300, 2048])
+    a = ctx.register_static(pat, [30000, 2048])
     b = ctx.register_static(pat, [300, 2049])
-    again = ctx.register_static(pat, [300, 2048])
+    again = ctx.register_static(pat, [30000, 2048])
     after = ctx.stats()
     assert a.id != b.id and again.id == a.id and a.id != handles["C4"].id
     assert after["compile_events"] == before["compile_events"] + 2 and after["pattern_cache_hits"] == before["pattern_cache_hits"] + 1
     # 2048-wide rows plan the non-temporal version; its plain sibling stays for misaligned operands
     assert a.info["compile_events"] == 1 and a.info["n_variants"] == 2 and a.info["compile_ms"] > 0
     assert b.info["n_variants"] == 1
-    generic = handles["C4"].plan([300, 2048])
-    pa = a.plan([300, 2048])
+    generic = handles["C4"].plan([30000, 2048])
+    pa = a.plan([30000, 2048])
     for k in ("variant_name", "lanes_per_row", "slots_per_lane", "vec_width", "block", "lds_bytes", "algorithmic_bytes"):
         assert pa[k] == generic[k], k
     assert pa["kernels"][0].split("_k_")[1] == generic["kernels"][0].split("_k_")[1]
     src = a.source
-    assert "A.inner = 2048LL;" in src and "A.rows = 300LL;" in src and "rp.G = 128;" in src
+    assert "A.inner = 2048LL;" in src and "A.rows = 30000LL;" in src and "rp.G = 128;" in src
     assert src.count('extern "C" __global__') == 2 and b.source.count('extern "C" __global__') == 1
     assert "A.inner = 2049LL;" in b.source
-    expect("SHAPE", a.plan, [300, 2049])
-    expect("SHAPE", a.plan, [301, 2048])
-    expect("INVALID_ARG", a.plan, [300, 2048], V["row_reg_scalar"])
+    expect("SHAPE", a.plan, [30000, 2049])
+    expect("SHAPE", a.plan, [30001, 2048])
+    expect("INVALID_ARG", a.plan, [30000, 2048], V["row_reg_scalar"])
     # a column reduce keeps its three entry points; a small one its single strip kernel
     c3 = CONFIGS["C3"].pattern()
     big = ctx.register_static(c3, [5000, 1024])

@@ -56,9 +56,11 @@ def test_every_capacity_class_and_tail(ctx, cfg_name):
     assert {4, 8, 16, 32, 64, 128, 256, 512, 1024} <= lanes
     assert {n for v, g, n in seen if v == "row_reg_vec"} >= {1, 2, 3}
     assert any(v == "row_stream_vec" for v, g, n in seen)
-    # rows that start and end on 16-byte boundaries run the non-temporal versions
-    assert all(h.plan([5, H])["kernels"][0].endswith("_nt") for H in (128, 768, 2048, 6144))
-    assert not any(h.plan([5, H])["kernels"][0].endswith("_nt") for H in (64, 127, 2047, 8192))
+    # large launches of rows that start and end on 16-byte boundaries run the non-temporal versions
+    rows = lambda H: (100 << 20) // (4 * H)
+    assert all(h.plan([rows(H), H])["kernels"][0].endswith("_nt") for H in (128, 768, 2048, 6144))
+    assert not any(h.plan([rows(H), H])["kernels"][0].endswith("_nt") for H in (64, 127, 2047, 8192))
+    assert not any(h.plan([5, H])["kernels"][0].endswith("_nt") for H in (128, 768, 2048, 6144))
 
 
 @pytest.mark.parametrize("cfg_name", ["C2", "C4"])
@@ -105,6 +107,9 @@ def test_non_temporal_versions_any_alignment(monkeypatch):
         # host rule for the loop kernels: large launches only
         h0 = c.register(CONFIGS["C0"].pattern())
         assert h0.plan([20000, 768])["kernels"][0].endswith("_nt") and not h0.plan([300, 768])["kernels"][0].endswith("_nt")
+        # one real launch above the size threshold under the host rule (C2: 6 bytes per element)
+        plan = check(c, "C2", [14000, 1024], seed=21)
+        assert plan["kernels"][0].endswith("_nt"), plan["kernels"]
         cfg = CONFIGS["C4"]
         pat = cfg.pattern()
         h = c.register(pat)
@@ -119,8 +124,10 @@ def test_non_temporal_versions_any_alignment(monkeypatch):
             dev.append(view)
         out_flat = torch.zeros(dims[0] * dims[1] + 16, dtype=torch.bfloat16, device="cuda")
         out = out_flat[1:1 + dims[0] * dims[1]].view(dims)
-        assert h.plan(dims)["kernels"][0].endswith("_nt")              # no pointers: assumed aligned
-        assert not h.plan(dims, inputs=dev, outputs=[out])["kernels"][0].endswith("_nt")
+        # the rule at a size where it applies: aligned (or no) pointers take the version, these do not
+        big = [20000, 1024]
+        assert h.plan(big)["kernels"][0].endswith("_nt")
+        assert not h.plan(big, inputs=[t.data_ptr() for t in dev], outputs=[out.data_ptr()])["kernels"][0].endswith("_nt")
         h.launch(dims, dev, [out])
         torch.cuda.synchronize()
         assert_close(out.cpu(), want[0], "misaligned bases")
