@@ -244,6 +244,47 @@ def test_row_outputs_and_logsumexp(ctx):
         compare(ctx, pat, [T, H], [(torch.randn(T, H, generator=g) * 3).half()], "log-softmax", handle=hd)
 
 
+def test_softmax_backward_and_layernorm_with_second_output(ctx):
+    """Two adjacent variants of the benchmark patterns: the backward of a row softmax (one row
+    reduction over a product of two inputs, dx = y * (dy - sum(dy * y))) and add + bias + LayerNorm
+    that also emits the pre-normalisation sum as a second bf16 output."""
+    pb = PatternBuilder("softmax_bwd")
+    t, h = pb.dims(2)
+    y = pb.cast(pb.param("bf16", [t, h]), "f32")
+    dy = pb.cast(pb.param("bf16", [t, h]), "f32")
+    dot = pb.reduce("sum", pb.op("mul", dy, y), 1)
+    pb.output(pb.cast(pb.op("mul", y, pb.op("sub", dy, pb.broadcast(dot, [t, h], [0]))), "bf16"))
+    pat = pb.build()
+    hd = ctx.register(pat)
+    assert hd.info["template"] == "row_reduce" and hd.info["n_phases"] == 1
+    g = torch.Generator().manual_seed(4)
+    for T, H in ((3, 7), (50, 1000), (9, 5739), (2, 20000)):
+        probs = torch.softmax(torch.randn(T, H, generator=g), dim=1).bfloat16()
+        compare(ctx, pat, [T, H], [probs, torch.randn(T, H, generator=g).bfloat16()], "softmax backward", handle=hd)
+
+    pb = PatternBuilder("ln_two_outputs")
+    t, h = pb.dims(2)
+    x = pb.cast(pb.param("bf16", [t, h]), "f32")
+    r = pb.cast(pb.param("bf16", [t, h]), "f32")
+    b = pb.param("f32", [h]); gam = pb.param("f32", [h]); beta = pb.param("f32", [h])
+    col = lambda v: pb.broadcast(v, [t, h], [1])
+    row = lambda v: pb.broadcast(v, [t, h], [0])
+    v = pb.op("add", pb.op("add", x, r), col(b))
+    pb.output(pb.cast(v, "bf16"))
+    mean = pb.op("div", pb.reduce("sum", v, 1), pb.dim_size(h))
+    d = pb.op("sub", v, row(mean))
+    var = pb.op("div", pb.reduce("sum", pb.op("mul", d, d), 1), pb.dim_size(h))
+    n = pb.op("mul", d, row(pb.op("rsqrt", pb.op("add", var, pb.const(1e-5)))))
+    pb.output(pb.cast(pb.op("add", pb.op("mul", n, col(gam)), col(beta)), "bf16"))
+    pat = pb.build()
+    hd = ctx.register(pat)
+    assert hd.info["n_outputs"] == 2 and hd.info["n_phases"] == 2
+    for T, H in ((5, 8), (40, 768), (7, 4099)):
+        ins = [torch.randn(T, H, generator=g).bfloat16(), torch.randn(T, H, generator=g).bfloat16(),
+               torch.randn(H, generator=g), 1 + 0.1 * torch.randn(H, generator=g), 0.1 * torch.randn(H, generator=g)]
+        compare(ctx, pat, [T, H], ins, "LayerNorm with the sum as second output", handle=hd)
+
+
 def test_flat_fusion_by_tensor_size_equality(ctx):
     pb = PatternBuilder()
     a, b, c, d = pb.dims(4)
