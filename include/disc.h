@@ -107,7 +107,9 @@ typedef enum {
                       in[0] must be a PARAM; an indexing function like SLICE, never a copy.  The
                       operand's innermost axis must stay the innermost axis of the pattern's
                       iteration space (accesses stay contiguous along rows); a transpose that moves
-                      it is refused with DISC_ERR_UNFUSIBLE.                                    */
+                      it cannot be fused with anything (DISC_ERR_UNFUSIBLE), but is a pattern on its
+                      own (PARAM, TRANSPOSE, OUTPUT: DISC_TEMPLATE_TRANSPOSE) when it collapses to a
+                      batched 2-D transpose; disc_register_graph cuts it out that way.          */
   DISC_OPCODE_COUNT
 } disc_opcode;
 
@@ -140,7 +142,10 @@ typedef struct {
 typedef enum {
   DISC_TEMPLATE_LOOP = 0,       /* loop fusion: element-wise / broadcast chain                  */
   DISC_TEMPLATE_ROW_REDUCE = 1, /* input fusion, reduce over the innermost axis (+ epilogue)    */
-  DISC_TEMPLATE_COL_REDUCE = 2  /* input fusion, reduce over an outer axis (+ epilogue)         */
+  DISC_TEMPLATE_COL_REDUCE = 2, /* input fusion, reduce over an outer axis (+ epilogue)         */
+  DISC_TEMPLATE_TRANSPOSE = 3   /* not a fusion: PARAM -> TRANSPOSE -> OUTPUT alone, a permutation
+                                   that moves the innermost axis, run as a batched 2-D tile
+                                   transpose (what an op graph falls back to for such an op)    */
 } disc_template;
 
 typedef struct {
@@ -171,6 +176,7 @@ typedef enum {
   DISC_V_COL_3STAGE_SCALAR,
   DISC_V_COL_STRIP_VEC,     /* column reduce, one block per column strip, single launch        */
   DISC_V_COL_STRIP_SCALAR,
+  DISC_V_TRANSPOSE_TILE,    /* batched 2-D transpose through a 64 x 64 tile in LDS              */
   DISC_V_COUNT
 } disc_variant;
 

@@ -21,10 +21,10 @@ _OPCODES = ("param", "const", "dim_size", "neg", "abs", "exp", "log", "tanh", "s
 OPCODE_IDS = {n: i for i, n in enumerate(_OPCODES)}
 VARIANTS = ("loop_vec", "loop_vec_i64", "loop_scalar", "loop_scalar_i64", "row_reg_vec", "row_reg_scalar",
             "row_stream_vec", "row_stream_scalar", "col_3stage_vec", "col_3stage_scalar", "col_strip_vec",
-            "col_strip_scalar")
+            "col_strip_scalar", "transpose_tile")
 STATUS = {0: "OK", -1: "INVALID_ARG", -2: "BAD_PATTERN", -3: "UNFUSIBLE", -4: "CONSTRAINT", -5: "WORKSPACE",
           -6: "COMPILE", -7: "HIP", -8: "SHAPE", -9: "EMPTY_REDUCE"}
-TEMPLATES = ("loop", "row_reduce", "col_reduce")
+TEMPLATES = ("loop", "row_reduce", "col_reduce", "transpose")
 
 
 class disc_op(C.Structure):

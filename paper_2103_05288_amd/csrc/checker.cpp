@@ -440,6 +440,68 @@ int analyze(const disc_op* ops, int n_ops, const disc_constraint* cs, int n_cs, 
     }
   }
 
+  // ---- a transpose on its own -----------------------------------------------------------------
+  // PARAM -> TRANSPOSE -> OUTPUT with a permutation that moves the innermost axis is not a fusion
+  // pattern (every access of a fused kernel would be strided by a whole row); alone it is a
+  // batched 2-D transpose when its axes collapse to [batch,] P, Q <- [batch,] Q, P.
+  if (n_ops == 3 && ops[0].opcode == DISC_PARAM && ops[1].opcode == DISC_TRANSPOSE && ops[1].in[0] == 0 &&
+      ops[2].opcode == DISC_OUTPUT && ops[2].in[0] == 1) {
+    const disc_op& tr = ops[1];
+    // result axes that carry an index (size not statically 1), with the operand axis each comes from
+    std::vector<int> res_ax, src_ax;
+    for (int k = 0; k < tr.rank; ++k)
+      if (dc.static_of(dc.atom(tr.dim[k])) != 1) { res_ax.push_back(k); src_ax.push_back(tr.axis_map[k]); }
+    bool moves_inner = false;
+    if (!src_ax.empty()) {
+      int last_src = -1;
+      for (int a : src_ax) last_src = std::max(last_src, a);
+      moves_inner = src_ax.back() != last_src;
+    }
+    if (moves_inner) {
+      // merge result axes that are neighbours, in order, in the operand too
+      std::vector<std::vector<int>> grp;   // result axes per group
+      std::vector<int> first_src;          // operand axis of the first member
+      for (size_t t = 0; t < res_ax.size(); ++t) {
+        bool join = false;
+        if (!grp.empty()) {
+          const int prev = src_ax[t - 1], cur = src_ax[t];
+          join = cur > prev;
+          for (int a = prev + 1; a < cur && join; ++a)       // only unit axes may lie between them
+            if (dc.static_of(dc.atom(ops[0].dim[a])) != 1) join = false;
+        }
+        if (join) grp.back().push_back(res_ax[t]);
+        else { grp.push_back({res_ax[t]}); first_src.push_back(src_ax[t]); }
+      }
+      const size_t ng2 = grp.size();
+      const bool two = ng2 == 2 && first_src[0] > first_src[1];
+      const bool three = ng2 == 3 && first_src[0] < first_src[2] && first_src[2] < first_src[1];
+      if (!two && !three) {
+        err = "op 1 (transpose): the permutation does not collapse to a batched 2-D transpose";
+        return DISC_ERR_UNFUSIBLE;
+      }
+      an.tmpl = DISC_TEMPLATE_TRANSPOSE;
+      an.root_rank = tr.rank;
+      an.root_dims.assign(tr.dim, tr.dim + tr.rank);
+      an.reduce_axis = -1;
+      an.groups = grp;
+      an.inner_group = (int)ng2 - 1;
+      an.group_size.assign(ng2, DimProduct());
+      for (size_t g2 = 0; g2 < ng2; ++g2)
+        for (int ax : grp[g2]) mul_into(an.group_size[g2], dc, tr.dim[ax]);
+      Access in_a, out_a;
+      in_a.value = 0; in_a.slot = 0; in_a.dtype = ops[0].dtype; in_a.kind = ACC_FULL; in_a.has_inner = true;
+      out_a.value = 2; out_a.slot = 0; out_a.dtype = ops[2].dtype; out_a.kind = ACC_FULL; out_a.has_inner = true; out_a.is_output = true;
+      an.accesses = {in_a, out_a};
+      OutputRef o;
+      o.node = -1;
+      o.access = 1;
+      an.outputs = {o};
+      an.n_phases = 0;
+      an.vec_width = 1;
+      return DISC_OK;
+    }
+  }
+
   // ---- 3. fusion decision + template -----------------------------------------------------
   // tensor-size classes: two values have provably the same element count when the multisets of
   // their (non-unit) dimension classes agree, or when the caller says so

@@ -997,6 +997,29 @@ struct Gen {
   int run(Generated* out, std::string* err) {
     (void)err;
     build_layout();
+    if (an.tmpl == DISC_TEMPLATE_TRANSPOSE) {
+      // no fused expression: the argument block and one hand-written tile-transpose kernel
+      os << "// generated: a transpose on its own\nstruct Pat {\n";
+      emit_args();
+      os << "};\n";
+      const int ng = (int)an.groups.size();
+      const std::string batch = ng == 3 ? "A.gs0" : "1";
+      auto k = [&](const std::string& name, const std::string& body) {
+        if (opt && !opt->only_kernels.empty() &&
+            std::find(opt->only_kernels.begin(), opt->only_kernels.end(), name) == opt->only_kernels.end())
+          return;
+        os << "extern \"C\" __global__ void __launch_bounds__(256) " << out->prefix << name
+           << "(Pat::Args A) { DISC_STATIC_ARGS(A) " << body << " }\n";
+        out->kernels.push_back(name);
+      };
+      k("k_transpose_tile", fmt("disc::ktranspose_body(A.p0, A.o0, %s, A.gs%d, A.gs%d);", batch.c_str(), ng - 2, ng - 1));
+      out->source = os.str();
+      out->args = layout;
+      out->field_names.clear();
+      for (const auto& f : layout.fields) out->field_names.push_back(field_name(f));
+      out->has_epilogue = false;
+      return DISC_OK;
+    }
     plan_keeps();
     plan_rinv();
     os << "// generated: one fused pattern, every kernel version\n";

@@ -697,6 +697,43 @@ DISC_DEV void row_stream_body(const typename Pat::Args& A) {
 }
 
 // =======================================================================================
+// A transpose on its own (not a fusion): out[b][p][q] = in[b][q][p], any element type.  A block
+// moves 64 x 64 tiles through LDS so that both the reads (along p, the operand's innermost
+// axis) and the writes (along q) are contiguous; the padding of the LDS rows keeps the
+// column-wise reads off a single bank.
+// =======================================================================================
+template <class T>
+DISC_DEV void ktranspose_body(const T* __restrict__ in, T* __restrict__ out, i64 batch, i64 P, i64 Q) {
+  constexpr int TS = 64;
+  constexpr int PAD = sizeof(T) >= 4 ? 1 : 4 / (int)sizeof(T);
+  __shared__ T tile[TS][TS + PAD];
+  const i64 tiles_p = (P + TS - 1) / TS, tiles_q = (Q + TS - 1) / TS;
+  const i64 per_batch = tiles_p * tiles_q;
+  const i64 ntiles = batch * per_batch;
+  const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;     // 256 threads: 64 x 4
+  for (i64 t = blockIdx.x; t < ntiles; t += gridDim.x) {
+    const i64 b = t / per_batch;
+    const i64 r = t - b * per_batch;
+    const i64 tq = r / tiles_p;
+    const i64 p0 = (r - tq * tiles_p) * TS, q0 = tq * TS;
+    const T* src = in + b * P * Q;
+    T* dst = out + b * P * Q;
+#pragma unroll 4
+    for (int i = ty; i < TS; i += 4) {            // row q0 + i of the operand, elements p0 .. p0 + 63
+      const i64 q = q0 + i, p = p0 + tx;
+      if (q < Q && p < P) tile[i][tx] = src[q * P + p];
+    }
+    __syncthreads();
+#pragma unroll 4
+    for (int i = ty; i < TS; i += 4) {            // row p0 + i of the result, elements q0 .. q0 + 63
+      const i64 p = p0 + i, q = q0 + tx;
+      if (p < P && q < Q) dst[p * Q + q] = tile[tx][i];
+    }
+    __syncthreads();
+  }
+}
+
+// =======================================================================================
 // Input fusion with a column reduction as root (reduce over an outer axis).  Canonical
 // space [outer, mid, inner], `mid` reduced.  Three stages, no atomics, so results are
 // bit-identical from run to run:

@@ -376,7 +376,22 @@ int make_plan(disc_ctx* c, const Pattern& p, const int64_t* dims, int n_dims, in
   const int V = an.vec_width;
   const int64_t max_grid = (int64_t)c->n_cus * c->grid_mult;
 
-  if (an.tmpl == DISC_TEMPLATE_LOOP) {
+  if (an.tmpl == DISC_TEMPLATE_TRANSPOSE) {
+    if (sv.rows == 0 || sv.inner == 0) return DISC_OK;
+    if (force >= 0 && force != DISC_V_TRANSPOSE_TILE)
+      return set_err(c, DISC_ERR_INVALID_ARG, "forced version does not belong to a transpose pattern");
+    const int ng = (int)an.groups.size();
+    const int64_t P = sv.group[ng - 2], Q = sv.group[ng - 1], batch = ng == 3 ? sv.group[0] : 1;
+    const int64_t ntiles = batch * ((P + 63) / 64) * ((Q + 63) / 64);
+    LaunchRec& L = fp->launches[0];
+    L.kernel = "k_transpose_tile";
+    L.block = 256;
+    L.grid[0] = (uint32_t)std::min<int64_t>(ntiles, (int64_t)c->n_cus * 8);
+    pub.variant = DISC_V_TRANSPOSE_TILE;
+    pub.n_launches = 1;
+    pub.vec_width = 1;
+    pub.index_bits = 64;
+  } else if (an.tmpl == DISC_TEMPLATE_LOOP) {
     if (sv.rows == 0 || sv.inner == 0) return DISC_OK;
     int want_vec = -1, want_i64 = -1;
     if (force >= 0) {
@@ -1291,6 +1306,8 @@ int disc_register_graph(disc_ctx* ctx, const disc_op* ops, int n_ops, const disc
       if (o.opcode == DISC_PARAM) { cone_params[i].insert(i); continue; }
       if (is_leaf(o.opcode) || o.opcode == DISC_OUTPUT) continue;
       if (o.opcode >= DISC_REDUCE_SUM && o.opcode <= DISC_REDUCE_ARGMAX) continue;
+      // a transpose that moves the innermost axis fuses with nothing: it stays a kernel of its own
+      if (o.opcode == DISC_TRANSPOSE && o.rank > 0 && o.axis_map[o.rank - 1] != o.rank - 1) continue;
       bool ok = true;
       int nops = 1;
       const int n = op_arity(o);
