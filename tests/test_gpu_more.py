@@ -413,3 +413,45 @@ def test_byte_offsets_beyond_32_bits(ctx):
     h2.launch([1, n], [xs.view(1, n)], outs)
     torch.cuda.synchronize()
     assert outs[0].item() == 5.0e6 and outs[1].item() == -3.0
+
+
+def test_launches_can_be_captured_in_a_graph(ctx):
+    """disc_launch enqueues kernels and nothing else (no allocation, no synchronisation, no memset),
+    so a caller may record it into a HIP graph: row-reduce, three-launch column-reduce and loop
+    patterns captured once, replayed with new input contents, every replay checked against the
+    oracle (with the program's own eager work and synchronisations between the replays)."""
+    jobs = []
+    for name, dims in (("C2", [300, 1024]), ("C3", [3000, 1024]), ("C0", [77, 768]), ("C4", [50, 5739])):
+        cfg = CONFIGS[name]
+        pat = cfg.pattern()
+        h = ctx.register(pat)
+        ins = [t.cuda() for t in cfg.inputs(dims, seed=31)]
+        outs = alloc_outputs(pat, dims, "cuda")
+        ws = torch.empty(max(16, ctx.workspace_bytes(h.id, dims)), dtype=torch.uint8, device="cuda")
+        h.launch(dims, ins, outs, workspace=ws)          # warm: occupancy queries, module functions
+        jobs.append((name, cfg, pat, h, dims, ins, outs, ws))
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            for name, cfg, pat, h, dims, ins, outs, ws in jobs:
+                h.launch(dims, ins, outs, workspace=ws, stream=side.cuda_stream)
+    torch.cuda.current_stream().wait_stream(side)
+    for replay in range(3):
+        fresh = {}
+        for name, cfg, pat, h, dims, ins, outs, ws in jobs:
+            new = cfg.inputs(dims, seed=100 + replay)
+            for dst, src in zip(ins, new):
+                dst.copy_(src.cuda())                     # eager work between the replays
+            for o in outs:
+                o.fill_(float("nan")) if o.dtype.is_floating_point else o.zero_()
+            fresh[name] = new
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for name, cfg, pat, h, dims, ins, outs, ws in jobs:
+            want = oracle_run(pat, dims, [to_oracle_input(t) for t in fresh[name]])[0]
+            for k, (g, w) in enumerate(zip(outs, want)):
+                assert_close(g.cpu(), w, f"graph replay {replay} {name} out{k}")
