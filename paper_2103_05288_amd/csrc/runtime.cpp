@@ -109,6 +109,7 @@ struct Graph {
   std::vector<disc_constraint> cs;
   std::vector<int> group_of_op;  // -1 for leaves and OUTPUT ops
   std::vector<char> remat;       // value is recomputed by the patterns that read it instead of crossing a cut
+  std::vector<char> needed;      // some graph output depends on the op (the others are dead code)
   std::vector<GraphGroup> groups;
   std::vector<GraphIntermediate> inter;
   std::map<int, int> inter_of_value;
@@ -1171,7 +1172,7 @@ void build_sub_pattern(const Graph& g, const std::vector<int>& S, const std::vec
   // consumers outside S
   std::vector<char> read_outside(g.ops.size(), 0);
   for (size_t i = 0; i < g.ops.size(); ++i) {
-    if (in_S[i]) continue;
+    if (in_S[i] || !g.needed[i]) continue;
     const disc_op& o = g.ops[i];
     if (is_leaf(o.opcode)) continue;
     const int n = op_arity(o);
@@ -1291,6 +1292,22 @@ int disc_register_graph(disc_ctx* ctx, const disc_op* ops, int n_ops, const disc
     } else if (!is_leaf(o.opcode)) compute.push_back(i);
   }
   if (g->n_sym > DISC_MAX_DIMS) return set_err(ctx, DISC_ERR_BAD_PATTERN, "too many symbolic dims");
+  // dead code: ops that no graph output depends on belong to no pattern
+  {
+    std::vector<char>& needed = g->needed;
+    needed.assign(n_ops, 0);
+    for (int i = n_ops - 1; i >= 0; --i) {
+      const disc_op& o = g->ops[i];
+      if (o.opcode == DISC_OUTPUT) needed[i] = 1;
+      if (!needed[i]) continue;
+      const int n = op_arity(o);
+      for (int k = 0; k < n; ++k) needed[o.in[k]] = 1;
+    }
+    std::vector<int> kept;
+    for (int v : compute)
+      if (needed[v]) kept.push_back(v);
+    compute.swap(kept);
+  }
   if (compute.empty() || g->n_outputs == 0) return set_err(ctx, DISC_ERR_BAD_PATTERN, "nothing to compute");
 
   // Values that are cheap element-wise functions of at most two graph inputs (a cast of an input,
@@ -1361,7 +1378,7 @@ int disc_register_graph(disc_ctx* ctx, const disc_op* ops, int n_ops, const disc
       for (int v : cuts[gi]) grp[v] = (int)gi;
     std::vector<std::vector<int>> users(n_ops);
     for (int i = 0; i < n_ops; ++i) {
-      if (is_leaf(g->ops[i].opcode)) continue;
+      if (is_leaf(g->ops[i].opcode) || !g->needed[i]) continue;
       const int n = op_arity(g->ops[i]);
       for (int k = 0; k < n; ++k) users[g->ops[i].in[k]].push_back(i);
     }

@@ -133,6 +133,25 @@ def test_row_and_column_reductions_in_one_graph(hctx):
     assert g.workspace_bytes([64, 100]) >= 64 * 100 * 4
 
 
+def test_dead_code_belongs_to_no_pattern(hctx):
+    """Ops that no output depends on are left out: they neither form patterns nor turn the values
+    they read into buffers."""
+    pb = PatternBuilder("dead")
+    T, H = pb.dims(2)
+    x = pb.param("f32", [T, H])
+    y = pb.op("tanh", x)
+    dead_col = pb.reduce("sum", pb.op("mul", y, y), 0)            # a column reduction nothing reads
+    pb.op("neg", dead_col)
+    m = pb.reduce("max", y, 1)
+    pb.output(pb.op("sub", y, pb.broadcast(m, [T, H], [0])))
+    pb.op("exp", y)                                               # trailing dead element-wise op
+    g = hctx.register_graph(pb.build())
+    info = g.info
+    assert info["n_patterns"] == 1 and info["n_intermediates"] == 0 and g.workspace_bytes([10, 20]) == 0
+    assert hctx.pattern_info(info["pattern_id"][0])["template"] == "row_reduce"
+    assert sum(1 for x in info["group_of_op"][:10] if x == 0) == 4          # tanh, max, broadcast, sub
+
+
 def test_graph_errors(hctx):
     from paper_2103_05288_amd import DiscError
     pb = PatternBuilder()
