@@ -1283,6 +1283,8 @@ int disc_register_graph(disc_ctx* ctx, const disc_op* ops, int n_ops, const disc
     for (int k = 0; k < o.rank; ++k)
       if (o.dim[k] >= 0) g->n_sym = std::max(g->n_sym, o.dim[k] + 1);
     if (o.opcode == DISC_DIM_SIZE) g->n_sym = std::max(g->n_sym, o.axis_map[0] + 1);
+    if (o.opcode == DISC_SLICE || o.opcode == DISC_PAD)       // starts / low paddings that are runtime values
+      for (int k = 0; k < o.rank; ++k) g->n_sym = std::max(g->n_sym, o.axis_map[k] + 1);
     if (o.opcode == DISC_PARAM) g->param_index[i] = g->n_inputs++;
     else if (o.opcode == DISC_OUTPUT) {
       if (n < 1 || is_leaf(g->ops[o.in[0]].opcode))

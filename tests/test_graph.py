@@ -152,6 +152,20 @@ def test_dead_code_belongs_to_no_pattern(hctx):
     assert sum(1 for x in info["group_of_op"][:10] if x == 0) == 4          # tanh, max, broadcast, sub
 
 
+def test_graph_counts_runtime_starts_among_its_dims(hctx):
+    """The start of a slice is a runtime value of its own: the graph expects it in dims[] even
+    though no tensor has it as an extent."""
+    pb = PatternBuilder("sliced_graph")
+    T, H, W, s0 = pb.dims(4)
+    x = pb.slice(pb.param("f32", [T, W]), [pb.static_start(0), s0], [T, H])
+    m = pb.reduce("max", x, 1)
+    c = pb.reduce("sum", pb.op("sub", x, pb.broadcast(m, [T, H], [0])), 0)
+    pb.output(c)
+    g = hctx.register_graph(pb.build())
+    assert g.info["n_dims"] == 4 and g.info["n_patterns"] == 2
+    assert g.workspace_bytes([10, 20, 30, 5]) >= 10 * 20 * 4
+
+
 def test_graph_errors(hctx):
     from paper_2103_05288_amd import DiscError
     pb = PatternBuilder()

@@ -26,17 +26,30 @@ class GraphGen:
         self.T, self.H = self.pb.dims(2)
         self.full = [self.T, self.H]
         self.inputs = []            # (dtype, dims)
+        self.windows = []           # (extent dim, start dim) of windowed inputs
 
     def pick(self, seq):
         return seq[int(self.rng.integers(0, len(seq)))]
 
     def fresh(self):
         pb = self.pb
-        kind = self.pick(["full", "full", "row", "col"])
+        kind = self.pick(["full", "full", "row", "col", "transposed", "window"])
         dt = self.pick(["f32", "bf16", "f16"])
         if kind == "full":
             v = pb.param(dt, self.full)
             self.inputs.append((dt, self.full))
+            return pb.cast(v, "f32") if dt != "f32" else v
+        if kind == "transposed":    # stored as [H, T]: the transpose moves the innermost axis, a kernel of its own
+            v = pb.param(dt, [self.H, self.T])
+            self.inputs.append((dt, [self.H, self.T]))
+            v = pb.transpose(v, (1, 0))
+            return pb.cast(v, "f32") if dt != "f32" else v
+        if kind == "window":        # a window of a wider input at a runtime offset
+            W, s0 = pb.dim(), pb.dim()
+            self.windows.append((W, s0))
+            v = pb.param(dt, [self.T, W])
+            self.inputs.append((dt, [self.T, W]))
+            v = pb.slice(v, [pb.static_start(0), s0], self.full)
             return pb.cast(v, "f32") if dt != "f32" else v
         if kind == "col":           # a row vector: one value per column
             v = pb.param("f32", [self.H])
@@ -102,7 +115,11 @@ def test_random_graph(ctx, seed):
     info = g.info
     assert 1 <= info["n_patterns"] <= 64 and info["n_buffers"] <= info["n_intermediates"]
     rng = np.random.default_rng(500 + seed)
-    for dims in ([int(rng.integers(1, 40)), int(rng.integers(1, 200))], [int(rng.integers(100, 700)), 513], [37, 4099]):
+    for base in ([int(rng.integers(1, 40)), int(rng.integers(1, 200))], [int(rng.integers(100, 700)), 513], [37, 4099]):
+        dims = list(base) + [0] * (pat.n_dims - 2)
+        for W, s0 in gen.windows:
+            dims[s0] = int(rng.integers(0, 9))
+            dims[W] = dims[s0] + base[1] + int(rng.integers(0, 9))
         ins = gen.draw(dims, seed=seed * 11 + dims[1])
         outs = [torch.full(pat.shape_of(o, dims), float("nan"), dtype=TORCH_DTYPE[pat.ops[o].dtype], device="cuda") for o in pat.outputs]
         ws = torch.empty(max(16, g.workspace_bytes(dims)), dtype=torch.uint8, device="cuda")
