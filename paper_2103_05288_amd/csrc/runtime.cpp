@@ -541,6 +541,8 @@ int make_plan(disc_ctx* c, const Pattern& p, const int64_t* dims, int n_dims, in
     if (outer == 0 || inner == 0) return DISC_OK;
     if (mid == 0) return set_err(c, DISC_ERR_EMPTY_REDUCE, "reduction over an axis of size 0");
     if (mid >= (1ll << 31) - 1) return set_err(c, DISC_ERR_SHAPE, "reduced axis longer than 2^31");
+    // the column tiles are the x dimension of the grids (no grid stride across columns)
+    if (inner >= (1ll << 31) - 4096) return set_err(c, DISC_ERR_SHAPE, "column reduce: more than 2^31 columns");
     int want_vec = -1, want_strip = -1;
     if (force >= 0) {
       if (force < DISC_V_COL_3STAGE_VEC || force > DISC_V_COL_STRIP_SCALAR)
@@ -1219,11 +1221,14 @@ void build_sub_pattern(const Graph& g, const std::vector<int>& S, const std::vec
   }
 }
 
-int64_t value_bytes(const Graph& g, int v, const int64_t* dims) {
+// bytes of value v at these dims; false when the product does not fit 2^62
+bool value_bytes(const Graph& g, int v, const int64_t* dims, int64_t* out) {
   const disc_op& o = g.ops[v];
-  int64_t n = 1;
-  for (int k = 0; k < o.rank; ++k) n *= o.dim[k] >= 0 ? dims[o.dim[k]] : -(int64_t)o.dim[k];
-  return n * dtype_bytes(o.dtype);
+  int64_t n = dtype_bytes(o.dtype);
+  for (int k = 0; k < o.rank; ++k)
+    if (mul_ovf(n, o.dim[k] >= 0 ? dims[o.dim[k]] : -(int64_t)o.dim[k], &n)) return false;
+  *out = n;
+  return n < (1ll << 62);
 }
 
 Graph* get_graph(disc_ctx* ctx, int32_t id) {
@@ -1241,7 +1246,10 @@ int graph_layout(disc_ctx* ctx, const Graph& g, const int64_t* dims, int n_dims,
   buf_off->assign(g.buffer_value.size(), 0);
   for (size_t b = 0; b < g.buffer_value.size(); ++b) {
     (*buf_off)[b] = off;
-    off += ((size_t)value_bytes(g, g.buffer_value[b], dims) + 255) / 256 * 256;
+    int64_t bytes = 0;
+    if (!value_bytes(g, g.buffer_value[b], dims, &bytes) || off + (size_t)bytes + 256 < off)
+      return set_err(ctx, DISC_ERR_SHAPE, "buffer size overflows");
+    off += ((size_t)bytes + 255) / 256 * 256;
   }
   *pattern_ws_off = off;
   size_t need = 0;

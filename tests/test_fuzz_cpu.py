@@ -101,3 +101,54 @@ def test_single_field_mutations(hctx, name):
             except Exception as e:                       # DiscError only
                 assert type(e).__name__ == "DiscError"
     assert len(statuses) >= 2
+
+
+def test_plan_with_extreme_dims(hctx):
+    """The launch path without the enqueue, over sizes from 0 to 2^40 and negative ones: a plan or
+    a status, never a crash; a plan's grid and block stay within the device limits."""
+    from paper_2103_05288_amd import DiscError
+    from tests.test_slice import qkv_split, softmax_of_window
+    from tests.test_pad import padded_softmax, pad_scale
+    from tests.test_transpose import heads_softmax, pure_transpose
+    pats = [CONFIGS[n].pattern() for n in ("C0", "C1", "C3")] + [qkv_split(), softmax_of_window(), padded_softmax(), pad_scale(),
+                                                               heads_softmax(), pure_transpose("bf16", (0, 2, 1))]
+    values = [0, 1, 2, 3, 7, 8, 64, 1000, 4099, 1 << 16, 1 << 20, (1 << 31) - 1, 1 << 31, 1 << 33, 1 << 40, -1]
+    rng = np.random.default_rng(99)
+    planned = refused = 0
+    for pat in pats:
+        h = hctx.register(pat)
+        nd = h.info["n_dims"]
+        for _ in range(300):
+            dims = [values[int(rng.integers(0, len(values)))] for _ in range(nd)]
+            try:
+                p = h.plan(dims)
+            except DiscError as e:
+                assert e.status in ("SHAPE", "EMPTY_REDUCE", "CONSTRAINT", "INVALID_ARG"), (pat.name, dims, e)
+                refused += 1
+                continue
+            planned += 1
+            for l in range(p["n_launches"]):
+                gx, gy, gz = p["grid"][l]
+                assert 1 <= gx < (1 << 31) and 1 <= gy <= 65535 and 1 <= gz <= 65535, (pat.name, dims, p["grid"])
+                assert 64 <= p["block"][l][0] <= 1024 and p["lds_bytes"][l] <= 160 * 1024
+    assert planned > 200 and refused > 200
+
+
+def test_graph_workspace_with_extreme_dims(hctx):
+    from paper_2103_05288_amd import DiscError
+    from tests.test_graph import chain_graph, layernorm_backward_graph
+    values = [0, 1, 7, 1000, 1 << 20, (1 << 31) - 1, 1 << 33, 1 << 40, 1 << 62, -1]
+    rng = np.random.default_rng(5)
+    for make in (lambda: chain_graph(4), layernorm_backward_graph):
+        g = hctx.register_graph(make())
+        got = refused = 0
+        for _ in range(200):
+            dims = [values[int(rng.integers(0, len(values)))] for _ in range(2)]
+            try:
+                ws = g.workspace_bytes(dims)
+                assert 0 <= ws < (1 << 63)
+                got += 1
+            except DiscError as e:
+                assert e.status in ("SHAPE", "EMPTY_REDUCE", "INVALID_ARG"), (dims, e)
+                refused += 1
+        assert got > 20 and refused > 20
