@@ -4,19 +4,19 @@
  * The library implements the hot path that the DISC dynamic-shape compiler
  * (arXiv 2103.05288) speeds up: a fusion pattern of memory-bound ops is
  * registered ONCE, without shape values, and is then launched at any runtime
- * shape without recompiling (Section 2, "DISC generates fused kernels adaptive
- * to any coming shapes"; static rank only).
+ * shape without recompiling (Section 2: the fused kernels are generated for
+ * shapes that are not known yet; static rank only).
  *
  *   register:  op list + shape constraints  ->  constraint closure (Section
  *              4.2.1), fusion decision from shape propagation + constraints
- *              (Section 4.3 "Shape hints collection"), kernel template choice
- *              (loop fusion / input fusion with a reduce root, Section 4.3
- *              "Shape-adaptive fusion configuration"), ONE device compile that
+ *              (Section 4.3, the paragraph on shape hints), kernel template choice
+ *              (loop fusion / input fusion with a reduce root, Section 4.3,
+ *              the paragraph on fusion configuration), ONE device compile that
  *              holds every kernel version, and a launch plan with everything
  *              that does not depend on shape values precomputed.
- *   launch:    runtime dims -> host shape calculation (Section 4.2.1 "Shape
- *              calculation"), version + launch-dimension selection (Section
- *              4.3), kernel launch (Section 4.2.3 "Host-side control").
+ *   launch:    runtime dims -> host shape calculation (Section 4.2.1),
+ *              version + launch-dimension selection (Section 4.3), kernel
+ *              launch (Section 4.2.3, host-side control).
  *              No op of the pattern is walked at launch time.
  *
  * Conventions

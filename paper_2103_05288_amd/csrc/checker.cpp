@@ -8,8 +8,8 @@
 //  4. resolve every value to the root axes it is indexed by (implicit broadcast: a broadcast
 //     is an indexing function on the small operand, never materialised);
 //  5. merge root axes that play identical roles for every operand, so index arithmetic is
-//     done once per group instead of once per axis ("more aggressive index calculation
-//     simplification", Section 4.2.1);
+//     done once per group instead of once per axis (the index-calculation
+//     simplification of Section 4.2.1);
 //  6. write the shape-calculation recipes the launch path evaluates.
 #include <algorithm>
 #include <cstdio>

@@ -1117,7 +1117,7 @@ int disc_util_empty_launch(disc_ctx* ctx, void* hip_stream) {
 }  // extern "C"
 
 // =================================================================================================
-// Op graphs (Section 4.3 "fusion decision", Section 4.2.2 buffer management): a list of ops that
+// Op graphs (Section 4.3: fusion decision; Section 4.2.2: buffer management): a list of ops that
 // need not be one fusible pattern is cut into consecutive fusion patterns with the SAME test the
 // single-pattern path uses (the checker's shape propagation + constraints), and the values that
 // cross pattern boundaries get buffers planned by lifetime, shared between values whose shapes

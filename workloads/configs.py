@@ -2,7 +2,7 @@
 
 Each configuration stands in for a memory-bound sub-graph of the paper's
 workloads (Table 1: Transformer / BERT / Seq2seq / ASR / TTS with varying
-sequence length, Section 2 "Lack of Attention for Dynamic Shape"): bias+GELU,
+sequence length; Section 2 on the neglect of dynamic shapes): bias+GELU,
 masked attention softmax, residual+LayerNorm, a column reduction with a
 broadcast epilogue and a long mixed chain.  The paper's own models, weights and
 data are not public; everything here is synthetic and seeded.

@@ -1,8 +1,8 @@
 """Neutral description of a fusion pattern: an op sequence WITHOUT shape values.
 
-A fusion pattern in the paper's sense (Background, "DISC generates fused kernels
-adaptive to any coming shapes": the identity of a pattern does not include the
-shape values) is an ordered op list whose tensor dimensions are *symbolic*.
+A fusion pattern in the paper's sense (Section 2: kernels are generated for shapes
+that are not known yet, so the identity of a pattern does not include the shape
+values) is an ordered op list whose tensor dimensions are *symbolic*.
 Static rank only (same passage).  Shape constraints of the two kinds the paper
 names (Section 4.2.1: dimension-size equality, tensor-size equality) may be
 attached by the caller, which plays the role of the framework bridging layer.
