@@ -255,6 +255,8 @@ void mul_into(DimProduct& p, const DimClasses&, int32_t dim) {
 
 }  // namespace
 
+int operand_count(int opcode) { return n_operands(opcode); }
+
 int analyze(const disc_op* ops, int n_ops, const disc_constraint* cs, int n_cs, Analysis* out,
             std::string* errp) {
   Analysis& an = *out;

@@ -206,6 +206,9 @@ struct GenOptions {
 };
 
 // checker.cpp: validate, close constraints, decide fusion, resolve contexts, collapse.
+// number of operands (`in[]` entries that mean something) of an opcode
+int operand_count(int opcode);
+
 int analyze(const disc_op* ops, int n_ops, const disc_constraint* cs, int n_cs, Analysis* out,
             std::string* err);
 

@@ -1127,12 +1127,7 @@ namespace {
 
 bool is_leaf(int opcode) { return opcode == DISC_PARAM || opcode == DISC_CONST || opcode == DISC_DIM_SIZE; }
 
-int op_arity(const disc_op& o) {
-  int n = 0;
-  for (int k = 0; k < 3; ++k)
-    if (o.in[k] >= 0) n = k + 1;
-  return n;
-}
+int op_arity(const disc_op& o) { return operand_count(o.opcode); }
 
 // The op list of the pattern that computes the graph ops `S` (ascending ids): operands produced
 // outside S become PARAMs (scalar leaves are copied instead), values of S read outside S (by ops
