@@ -204,6 +204,50 @@ def gap_to_static(ctx, names, dev):
                     "shape-generic module used by the whole sweep"}
 
 
+def next_rows(ctx, dev):
+    """Secondary figures, outside the headline value: the op-graph path and the indexing functions
+    on inputs (slice, pad, transpose) at one large shape each; effective rate = bytes of the
+    graph's / pattern's inputs and outputs, each once, over the device time of one call."""
+    from workloads.configs import TORCH_DTYPE
+    from workloads.extras import (heads_softmax, layernorm_backward_graph, padded_softmax, pure_transpose, qkv_split)
+
+    def io_bytes(pat, dims):
+        n = 0
+        for v in list(pat.params) + list(pat.outputs):
+            n += int(np.prod(pat.shape_of(v, dims))) * torch.empty(0, dtype=TORCH_DTYPE[pat.ops[v].dtype]).element_size()
+        return n
+
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(5)
+    rows = {}
+    # ~1 GB of operands and results per call: nothing of a call survives in the 256 MB memory-side cache
+    cases = [("graph_layernorm_backward", layernorm_backward_graph(), [131072, 1024], True),
+             ("slice_qkv_split", qkv_split(), [131072, 1024, 3072, 1024, 2048], False),
+             ("pad_softmax_minus_inf", padded_softmax(), [131072, 2000, 24, 2048], False),
+             ("transpose_heads_softmax", heads_softmax(), [128, 1024, 16, 128], False),
+             ("transpose_tile_bf16", pure_transpose("bf16", (1, 0)), [16384, 16384], False)]
+    for name, pat, dims, is_graph in cases:
+        ins = [torch.randn(pat.shape_of(pi, dims), device=dev, generator=gen).to(TORCH_DTYPE[pat.ops[pi].dtype]) for pi in pat.params]
+        outs = [torch.empty(pat.shape_of(o, dims), dtype=TORCH_DTYPE[pat.ops[o].dtype], device=dev) for o in pat.outputs]
+        if is_graph:
+            h = ctx.register_graph(pat)
+            ws = torch.empty(max(16, h.workspace_bytes(dims)), dtype=torch.uint8, device=dev)
+            call = lambda: h.launch(dims, ins, outs, workspace=ws)
+            extra = {"patterns": h.info["n_patterns"], "planned_buffers": h.info["n_buffers"], "workspace_bytes": int(ws.numel())}
+        else:
+            h = ctx.register(pat)
+            ws = torch.empty(max(16, ctx.workspace_bytes(h.id, dims)), dtype=torch.uint8, device=dev)
+            call = h.bind(dims, ins, outs, workspace=ws)
+            extra = {"kernels": h.plan(dims)["kernels"], "template": h.info["template"]}
+        call()
+        torch.cuda.synchronize()
+        t = min(time_events(lambda: [call() for _ in range(10)]) for _ in range(3)) / 10
+        rows[name] = dict({"dims": dims, "io_bytes": io_bytes(pat, dims), "us": round(t * 1e6, 2),
+                           "GBps": round(io_bytes(pat, dims) / t / 1e9, 1)}, **extra)
+        del ins, outs, ws
+    return rows
+
+
 def cpu_baseline(sweeps, budget_s=20.0):
     """Oracle (as it stands) on a bounded sample of the sweep: calls in sweep order, smallest
     element counts first skipped none, until the time budget is used; row-independent patterns
@@ -266,6 +310,7 @@ def main():
     ap.add_argument("--configs", default="C0,C1,C2,C3,C4")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-gap-to-static", action="store_true")
+    ap.add_argument("--no-next-rows", action="store_true")
     ap.add_argument("--cpu-budget", type=float, default=20.0)
     ap.add_argument("--dump-calls", default="", help="write per-call dims / bytes / device time as JSON lines")
     args = ap.parse_args()
@@ -411,6 +456,8 @@ def main():
     }
     if not args.no_gap_to_static:
         out["gap_to_static"] = gap_to_static(ctx, names, dev)
+    if not args.no_next_rows:
+        out["next_rows"] = next_rows(ctx, dev)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(sweeps, args.cpu_budget)
     print(json.dumps(out))

@@ -714,8 +714,12 @@ DISC_DEV void ktranspose_body(const T* __restrict__ in, T* __restrict__ out, i64
   for (i64 t = blockIdx.x; t < ntiles; t += gridDim.x) {
     const i64 b = t / per_batch;
     const i64 r = t - b * per_batch;
+    // consecutive blocks walk a diagonal of the tile grid: with a power-of-two row pitch the tiles
+    // of one tile row (or column) would otherwise queue up on the same memory channels
     const i64 tq = r / tiles_p;
-    const i64 p0 = (r - tq * tiles_p) * TS, q0 = tq * TS;
+    i64 tp = r - tq * tiles_p + tq;
+    if (tp >= tiles_p) tp %= tiles_p;
+    const i64 p0 = tp * TS, q0 = tq * TS;
     const T* src = in + b * P * Q;
     T* dst = out + b * P * Q;
 #pragma unroll 4

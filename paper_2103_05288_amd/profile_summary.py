@@ -51,9 +51,9 @@ def main():
     ap.add_argument("--bench-json", default="")
     ap.add_argument("--out", default="profiles")
     ap.add_argument("--trace-cmd", default="rocprofv3 --kernel-trace --stats -d prof_out/trace -o trace -- "
-                                           "python3 bench.py --steps 3 --warmup 1 --no-cpu-baseline --no-gap-to-static")
+                                           "python3 bench.py --steps 3 --warmup 1 --no-cpu-baseline --no-gap-to-static --no-next-rows")
     ap.add_argument("--pmc-cmd", default="rocprofv3 --pmc {counter} -d prof_out/{dir} -o {dir} -- "
-                                         "python3 bench.py --steps 1 --warmup 0 --no-cpu-baseline --no-gap-to-static")
+                                         "python3 bench.py --steps 1 --warmup 0 --no-cpu-baseline --no-gap-to-static --no-next-rows")
     args = ap.parse_args()
     os.makedirs(args.out, exist_ok=True)
 

@@ -5,6 +5,7 @@ import pytest
 import torch
 
 from workloads import PatternBuilder
+from workloads.extras import layernorm_backward_graph
 from workloads.configs import TORCH_DTYPE
 
 
@@ -47,32 +48,6 @@ def chain_graph(n_stages=4):
             m = pb.reduce("max", pb.op("abs", v), 1)
             v = pb.op("div", v, pb.broadcast(pb.op("add", m, pb.const(1.0)), [T, H], [0]))
     pb.output(v)
-    return pb.build()
-
-
-def layernorm_backward_graph():
-    """dx, dgamma, dbeta of LayerNorm from x, dy, gamma: three dependent row reductions for dx and two
-    column reductions that need the normalised activations again -- row and column reductions in
-    one op list, which is never one pattern."""
-    pb = PatternBuilder("ln_bwd")
-    T, H = pb.dims(2)
-    x = pb.cast(pb.param("bf16", [T, H]), "f32")
-    dy = pb.cast(pb.param("bf16", [T, H]), "f32")
-    gam = pb.param("f32", [H])
-    row = lambda v: pb.broadcast(v, [T, H], [0])
-    col = lambda v: pb.broadcast(v, [T, H], [1])
-    mean = pb.op("div", pb.reduce("sum", x, 1), pb.dim_size(H))
-    xc = pb.op("sub", x, row(mean))
-    var = pb.op("div", pb.reduce("sum", pb.op("mul", xc, xc), 1), pb.dim_size(H))
-    rstd = pb.op("rsqrt", pb.op("add", var, pb.const(1e-5)))
-    xhat = pb.op("mul", xc, row(rstd))
-    g = pb.op("mul", dy, col(gam))
-    c1 = pb.op("div", pb.reduce("sum", g, 1), pb.dim_size(H))
-    c2 = pb.op("div", pb.reduce("sum", pb.op("mul", g, xhat), 1), pb.dim_size(H))
-    dx = pb.op("mul", pb.op("sub", pb.op("sub", g, row(c1)), pb.op("mul", xhat, row(c2))), row(rstd))
-    pb.output(pb.cast(dx, "bf16"))
-    pb.output(pb.reduce("sum", pb.op("mul", dy, xhat), 0))     # dgamma
-    pb.output(pb.reduce("sum", dy, 0))                          # dbeta
     return pb.build()
 
 

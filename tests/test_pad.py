@@ -5,6 +5,7 @@ import pytest
 import torch
 
 from workloads import PatternBuilder
+from workloads.extras import padded_softmax
 from workloads.configs import TORCH_DTYPE
 
 
@@ -14,17 +15,6 @@ def pad_scale():
     T, H, l0, l1, P0, P1 = pb.dims(6)
     xp = pb.pad(pb.param("f32", [T, H]), [l0, l1], [P0, P1], 1.5)
     pb.output(pb.op("mul", xp, pb.const(2.0)))
-    return pb.build()
-
-
-def padded_softmax():
-    """Rows padded with -inf behind (and in front of) the data, then a softmax: the padding gets
-    probability 0 and the data the softmax of the unpadded row."""
-    pb = PatternBuilder("padded_softmax")
-    T, H, l1, P = pb.dims(4)
-    xp = pb.cast(pb.pad(pb.param("bf16", [T, H]), [pb.static_start(0), l1], [T, P], float("-inf")), "f32")
-    e = pb.op("exp", pb.op("sub", xp, pb.broadcast(pb.reduce("max", xp, 1), [T, P], [0])))
-    pb.output(pb.cast(pb.op("div", e, pb.broadcast(pb.reduce("sum", e, 1), [T, P], [0])), "bf16"))
     return pb.build()
 
 

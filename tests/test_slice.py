@@ -5,6 +5,7 @@ import pytest
 import torch
 
 from workloads import PatternBuilder
+from workloads.extras import qkv_split, softmax_of_window
 from workloads.configs import TORCH_DTYPE
 
 
@@ -14,34 +15,6 @@ def loop_slice():
     xs = pb.slice(pb.param("f32", [T, H]), [pb.static_start(0), s0], [T, n])
     pb.output(pb.op("mul", xs, pb.const(2.0)))
     return pb.build(), lambda t, h, s, m: [t, h, s, m], lambda d: [(d[0], d[1])]
-
-
-def qkv_split():
-    """q, k, v are three slices of one [T, 3H] input; bias is a slice of a [3H] row vector."""
-    pb = PatternBuilder("qkv")
-    T, H, H3, s1, s2 = pb.dims(5)
-    qkv = pb.param("bf16", [T, H3])
-    bias = pb.param("f32", [H3])
-    z = pb.static_start(0)
-    f = lambda t: pb.cast(t, "f32")
-    q = f(pb.slice(qkv, [z, z], [T, H]))
-    k = f(pb.slice(qkv, [z, s1], [T, H]))
-    v = f(pb.slice(qkv, [z, s2], [T, H]))
-    bk = pb.broadcast(pb.slice(bias, [s1], [H]), [T, H], [1])
-    pb.output(pb.cast(pb.op("add", pb.op("mul", q, pb.op("add", k, bk)), v), "bf16"))
-    return pb.build()
-
-
-def softmax_of_window():
-    """Row softmax over a window [s0, s0 + n) of every row of a 3-D input, rows taken from a window
-    of the middle axis as well."""
-    pb = PatternBuilder("window_softmax")
-    B, S, H, r0, m, s0, n = pb.dims(7)
-    xs = pb.slice(pb.param("f16", [B, S, H]), [pb.static_start(0), r0, s0], [B, m, n])
-    x = pb.cast(xs, "f32")
-    e = pb.op("exp", pb.op("sub", x, pb.broadcast(pb.reduce("max", x, 2), [B, m, n], [0, 1])))
-    pb.output(pb.cast(pb.op("div", e, pb.broadcast(pb.reduce("sum", e, 2), [B, m, n], [0, 1])), "f16"))
-    return pb.build()
 
 
 def column_sum_of_rows_window():

@@ -5,18 +5,8 @@ import pytest
 import torch
 
 from workloads import PatternBuilder
+from workloads.extras import heads_softmax, pure_transpose
 from workloads.configs import TORCH_DTYPE
-
-
-def heads_softmax():
-    """[B, S, NH, D] read as [B, NH, S, D] (the attention-head transpose), softmax over D."""
-    pb = PatternBuilder("heads_softmax")
-    B, S, NH, D = pb.dims(4)
-    full = [B, NH, S, D]
-    t = pb.cast(pb.transpose(pb.param("bf16", [B, S, NH, D]), (0, 2, 1, 3)), "f32")
-    e = pb.op("exp", pb.op("sub", t, pb.broadcast(pb.reduce("max", t, 3), full, [0, 1, 2])))
-    pb.output(pb.cast(pb.op("div", e, pb.broadcast(pb.reduce("sum", e, 3), full, [0, 1, 2])), "bf16"))
-    return pb.build()
 
 
 def add_transposed():
@@ -37,12 +27,6 @@ def column_sum_of_transposed():
     B, S, H = pb.dims(3)
     t = pb.transpose(pb.param("f32", [B, S, H]), (1, 0, 2))
     pb.output(pb.reduce("sum", pb.op("sigmoid", t), 1))
-    return pb.build()
-
-
-def pure_transpose(dtype, perm):
-    pb = PatternBuilder("transpose" + "".join(str(a) for a in perm))
-    pb.output(pb.transpose(pb.param(dtype, pb.dims(len(perm))), perm))
     return pb.build()
 
 
