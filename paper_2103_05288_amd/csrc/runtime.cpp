@@ -1133,11 +1133,14 @@ int op_arity(const disc_op& o) { return operand_count(o.opcode); }
 // outside S become PARAMs (scalar leaves are copied instead), values of S read outside S (by ops
 // of other groups or by graph OUTPUTs) become OUTPUTs, constraints between values that both
 // appear are carried over.
-// `final_cut` false (while the cut is still growing): every value read outside S counts as an
-// output, also those that readers will recompute, so that a candidate always has an output.
+// `wanted` null (while the cut is still growing): every value read outside S counts as an output,
+// also those that readers will recompute, so that a candidate always has an output.  For the
+// patterns as registered, `wanted` marks the values other patterns really take in (their
+// in_values, which includes what their recomputed cones read) and the graph outputs.
 void build_sub_pattern(const Graph& g, const std::vector<int>& S, const std::vector<char>& in_S,
                        std::vector<disc_op>* sub, std::vector<disc_constraint>* sub_cs, std::vector<int>* in_values,
-                       std::vector<int>* out_values, bool final_cut) {
+                       std::vector<int>* out_values, const std::vector<char>* wanted) {
+  const bool final_cut = wanted != nullptr;
   std::map<int, int> id_of;   // graph value -> sub-pattern value
   sub->clear();
   sub_cs->clear();
@@ -1174,8 +1177,11 @@ void build_sub_pattern(const Graph& g, const std::vector<int>& S, const std::vec
     if (is_leaf(o.opcode)) continue;
     const int n = op_arity(o);
     for (int k = 0; k < n; ++k)
-      if (o.in[k] >= 0 && in_S[o.in[k]] && (!final_cut || o.opcode == DISC_OUTPUT || !g.remat[o.in[k]])) read_outside[o.in[k]] = 1;
+      if (o.in[k] >= 0 && in_S[o.in[k]] && !final_cut) read_outside[o.in[k]] = 1;
   }
+  if (final_cut)
+    for (int v : S)
+      if ((*wanted)[v]) read_outside[v] = 1;
   // ops of S that only fed readers which now recompute them are left out of the final pattern
   std::vector<char> live(g.ops.size(), final_cut ? 0 : 1);
   if (final_cut)
@@ -1315,19 +1321,28 @@ int disc_register_graph(disc_ctx* ctx, const disc_op* ops, int n_ops, const disc
   }
   if (compute.empty() || g->n_outputs == 0) return set_err(ctx, DISC_ERR_BAD_PATTERN, "nothing to compute");
 
-  // Values that are cheap element-wise functions of at most two graph inputs (a cast of an input,
-  // an input plus a broadcast bias, ...) do not cross cuts: a pattern that reads one computes it
-  // again from the inputs, which costs no more traffic than reading the stored result and saves
-  // writing it.
-  g->remat.assign(n_ops, 0);
-  {
-    std::vector<std::set<int>> cone_params(n_ops);
+  // Recomputing instead of buffering.  A value that is a cheap element-wise function of at most
+  // two graph inputs (a cast of an input, an input plus a broadcast bias, ...) does not cross
+  // cuts: a pattern that reads it computes it again from the inputs, which costs no more traffic
+  // than reading the stored result and saves writing it.  At level 2 the function may also use
+  // reduction results (per-row or per-column values: small), so that e.g. normalised activations
+  // are recomputed from the input and the row statistics instead of being stored in full; the
+  // reduction results themselves then cross the cut as small buffers.  Level 1: inputs only.
+  // Level 0: nothing is recomputed.  The highest level whose cut passes the checker is taken.
+  auto compute_remat = [&](int level) {
+    g->remat.assign(n_ops, 0);
+    if (level == 0) return;
+    std::vector<std::set<int>> cone_params(n_ops), cone_anchors(n_ops);
     std::vector<int> cone_ops(n_ops, 0);
+    const size_t max_ops = level == 2 ? 16 : 8;
     for (int i = 0; i < n_ops; ++i) {
       const disc_op& o = g->ops[i];
       if (o.opcode == DISC_PARAM) { cone_params[i].insert(i); continue; }
       if (is_leaf(o.opcode) || o.opcode == DISC_OUTPUT) continue;
-      if (o.opcode >= DISC_REDUCE_SUM && o.opcode <= DISC_REDUCE_ARGMAX) continue;
+      if (o.opcode >= DISC_REDUCE_SUM && o.opcode <= DISC_REDUCE_ARGMAX) {
+        if (level == 2) cone_anchors[i].insert(i);
+        continue;
+      }
       // a transpose that moves the innermost axis fuses with nothing: it stays a kernel of its own
       if (o.opcode == DISC_TRANSPOSE && o.rank > 0 && o.axis_map[o.rank - 1] != o.rank - 1) continue;
       bool ok = true;
@@ -1335,14 +1350,16 @@ int disc_register_graph(disc_ctx* ctx, const disc_op* ops, int n_ops, const disc
       const int n = op_arity(o);
       for (int k = 0; k < n && ok; ++k) {
         const int a = o.in[k];
-        if (!is_leaf(g->ops[a].opcode) && !g->remat[a]) ok = false;
+        const bool anchor = level == 2 && g->ops[a].opcode >= DISC_REDUCE_SUM && g->ops[a].opcode <= DISC_REDUCE_ARGMAX;
+        if (!is_leaf(g->ops[a].opcode) && !g->remat[a] && !anchor) ok = false;
         cone_params[i].insert(cone_params[a].begin(), cone_params[a].end());
+        cone_anchors[i].insert(cone_anchors[a].begin(), cone_anchors[a].end());
         nops += cone_ops[a];
       }
       cone_ops[i] = nops;
-      if (ok && cone_params[i].size() <= 2 && nops <= 8) g->remat[i] = 1;
+      if (ok && cone_params[i].size() <= 2 && cone_anchors[i].size() <= 4 && (size_t)nops <= max_ops) g->remat[i] = 1;
     }
-  }
+  };
 
   // greedy cut in list order: an op joins the current pattern when the checker still accepts the
   // pattern with it (one provable iteration space, one template); otherwise it opens the next one
@@ -1352,24 +1369,68 @@ int disc_register_graph(disc_ctx* ctx, const disc_op* ops, int n_ops, const disc
   auto fusible = [&](const std::vector<int>& S, std::string* why) {
     std::vector<char> in_S(n_ops, 0);
     for (int v : S) in_S[v] = 1;
-    build_sub_pattern(*g, S, in_S, &sub, &sub_cs, &ins, &outs, false);
+    build_sub_pattern(*g, S, in_S, &sub, &sub_cs, &ins, &outs, nullptr);
     Analysis an;
     return analyze(sub.data(), (int)sub.size(), sub_cs.empty() ? nullptr : sub_cs.data(), (int)sub_cs.size(), &an, why);
   };
+  // The patterns as they will be registered, last to first: a pattern's outputs are the graph
+  // outputs it computes and what later patterns take in -- directly or through the cones they
+  // recompute.  `each` gets every pattern that has an output; returns the first failure.
+  struct FinalPattern {
+    std::vector<disc_op> ops;
+    std::vector<disc_constraint> cs;
+    std::vector<int> in_values, out_values;
+  };
+  auto finalize = [&](const std::vector<std::vector<int>>& cs_, std::vector<FinalPattern>* each, std::string* why) {
+    std::vector<char> wanted(n_ops, 0);
+    for (const auto& kv : g->output_index) wanted[kv.first] = 1;
+    each->assign(cs_.size(), FinalPattern());
+    for (size_t gi = cs_.size(); gi-- > 0;) {
+      std::vector<char> in_S(n_ops, 0);
+      for (int v : cs_[gi]) in_S[v] = 1;
+      FinalPattern& fp = (*each)[gi];
+      build_sub_pattern(*g, cs_[gi], in_S, &fp.ops, &fp.cs, &fp.in_values, &fp.out_values, &wanted);
+      if (fp.out_values.empty()) { fp.in_values.clear(); continue; }      // nothing reads it: dropped
+      for (int v : fp.in_values) wanted[v] = 1;
+      Analysis an;
+      const int rc = analyze(fp.ops.data(), (int)fp.ops.size(), fp.cs.empty() ? nullptr : fp.cs.data(), (int)fp.cs.size(), &an, why);
+      if (rc) return rc;
+    }
+    return (int)DISC_OK;
+  };
   std::vector<std::vector<int>> cuts;
-  std::vector<int> cur;
   std::string why;
-  for (int v : compute) {
-    cur.push_back(v);
-    if (fusible(cur, &why) == DISC_OK) continue;
-    cur.pop_back();
-    if (cur.empty()) return set_err(ctx, DISC_ERR_UNFUSIBLE, "op " + std::to_string(v) + " is not a pattern on its own: " + why);
-    cuts.push_back(cur);
-    cur.assign(1, v);
-    int rc = fusible(cur, &why);
-    if (rc) return set_err(ctx, rc, "op " + std::to_string(v) + " is not a pattern on its own: " + why);
+  int cut_rc = DISC_OK;
+  for (int level = 2; level >= 0; --level) {
+    compute_remat(level);
+    cuts.clear();
+    cut_rc = DISC_OK;
+    std::vector<int> cur;
+    for (int v : compute) {
+      cur.push_back(v);
+      if (fusible(cur, &why) == DISC_OK) continue;
+      cur.pop_back();
+      if (cur.empty()) {
+        cut_rc = set_err(ctx, DISC_ERR_UNFUSIBLE, "op " + std::to_string(v) + " is not a pattern on its own: " + why);
+        break;
+      }
+      cuts.push_back(cur);
+      cur.assign(1, v);
+      const int rc = fusible(cur, &why);
+      if (rc) {
+        cut_rc = set_err(ctx, rc, "op " + std::to_string(v) + " is not a pattern on its own: " + why);
+        break;
+      }
+    }
+    if (cut_rc == DISC_OK) {
+      cuts.push_back(cur);
+      std::vector<FinalPattern> probe;
+      const int rc = finalize(cuts, &probe, &why);
+      if (rc) cut_rc = set_err(ctx, rc, "a cut of the graph is not a pattern: " + why);
+    }
+    if (cut_rc == DISC_OK) break;
   }
-  cuts.push_back(cur);
+  if (cut_rc != DISC_OK) return cut_rc;
 
   // Sinking: the greedy cut also pulls in ops that only feed the NEXT pattern (say the |x| ahead of
   // a reduction the current pattern cannot hold), which turns their result into one more buffer.
@@ -1435,16 +1496,21 @@ int disc_register_graph(disc_ctx* ctx, const disc_op* ops, int n_ops, const disc
   }
   if (cuts.size() > (size_t)DISC_MAX_GRAPH_PATTERNS) return set_err(ctx, DISC_ERR_BAD_PATTERN, "the graph needs too many patterns");
 
+  std::vector<FinalPattern> finals;
+  {
+    const int rc = finalize(cuts, &finals, &why);
+    if (rc) return set_err(ctx, rc, "a cut of the graph is not a pattern: " + why);
+  }
   for (size_t gi = 0; gi < cuts.size(); ++gi) {
     GraphGroup gr;
     gr.ops = cuts[gi];
-    std::vector<char> in_S(n_ops, 0);
-    for (int v : gr.ops) { in_S[v] = 1; g->group_of_op[v] = (int)gi; }
-    build_sub_pattern(*g, gr.ops, in_S, &sub, &sub_cs, &gr.in_values, &gr.out_values, true);
+    for (int v : gr.ops) g->group_of_op[v] = (int)gi;
+    gr.in_values = finals[gi].in_values;
+    gr.out_values = finals[gi].out_values;
     if (gr.out_values.empty()) { gr.pattern_id = -1; g->groups.push_back(gr); continue; }   // dead code: nothing reads it
     int32_t pid = -1;
-    int rc = disc_register_pattern(ctx, sub.data(), (int)sub.size(), sub_cs.empty() ? nullptr : sub_cs.data(),
-                                   (int)sub_cs.size(), &pid);
+    int rc = disc_register_pattern(ctx, finals[gi].ops.data(), (int)finals[gi].ops.size(),
+                                   finals[gi].cs.empty() ? nullptr : finals[gi].cs.data(), (int)finals[gi].cs.size(), &pid);
     if (rc) return rc;
     gr.pattern_id = pid;
     g->groups.push_back(gr);
