@@ -1614,7 +1614,9 @@ int disc_graph_launch(disc_ctx* ctx, int32_t id, const int64_t* dims, int n_dims
     if (p != g->param_index.end()) return const_cast<void*>(inputs[p->second]);
     auto o = g->output_index.find(v);
     if (o != g->output_index.end()) return outputs[o->second];
-    return ws + off[g->inter[g->inter_of_value.at(v)].buffer];
+    auto it = g->inter_of_value.find(v);
+    if (it == g->inter_of_value.end()) return nullptr;      // cannot happen for a registered graph
+    return ws + off[g->inter[it->second].buffer];
   };
   std::vector<const void*> in;
   std::vector<void*> outp;
@@ -1623,6 +1625,10 @@ int disc_graph_launch(disc_ctx* ctx, int32_t id, const int64_t* dims, int n_dims
     outp.clear();
     for (int v : gr.in_values) in.push_back(where(v));
     for (int v : gr.out_values) outp.push_back(where(v));
+    for (const void* q : in)
+      if (!q) return set_err(ctx, DISC_ERR_INVALID_ARG, "null input pointer (or a value of the graph without a place)");
+    for (void* q : outp)
+      if (!q) return set_err(ctx, DISC_ERR_INVALID_ARG, "null output pointer (or a value of the graph without a place)");
     const int ns = ctx->patterns[gr.pattern_id]->an.n_sym;
     rc = disc_launch(ctx, gr.pattern_id, dims, ns, in.data(), (int)in.size(), outp.data(), (int)outp.size(),
                      ws ? ws + pws : nullptr, total - pws, hip_stream);
