@@ -204,6 +204,31 @@ def gap_to_static(ctx, names, dev):
                     "shape-generic module used by the whole sweep"}
 
 
+def graph_replay(sweeps):
+    """The same launches recorded once into a HIP graph per configuration and replayed: what is left
+    when the host's per-call work (shape calculation, version selection, the launch call) and the
+    dispatch gaps between dependent launches are taken out.  Not the headline: a recorded graph has
+    its shapes fixed, which is what the method exists to avoid; the figure only shows how much of
+    the small-call configurations is launch latency."""
+    out = {}
+    side = torch.cuda.Stream()
+    for sw in sweeps:
+        calls = [sw.handle.bind(d, ins, outs, workspace=sw.workspace, stream=side.cuda_stream) for d, ins, outs in sw.bound]
+        side.wait_stream(torch.cuda.current_stream())
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(graph, stream=side):
+                for c in calls:
+                    c()
+        torch.cuda.current_stream().wait_stream(side)
+        graph.replay()
+        torch.cuda.synchronize()
+        t = min(time_events(graph.replay) for _ in range(3))
+        out[sw.name] = {"sweep_ms": round(t * 1e3, 4), "GBps_sweep": round(sum(sw.bytes) / t / 1e9, 1)}
+        del graph
+    return out
+
+
 def next_rows(ctx, dev):
     """Secondary figures, outside the headline value: the op-graph path and the indexing functions
     on inputs (slice, pad, transpose) at one large shape each; effective rate = bytes of the
@@ -458,6 +483,7 @@ def main():
         out["gap_to_static"] = gap_to_static(ctx, names, dev)
     if not args.no_next_rows:
         out["next_rows"] = next_rows(ctx, dev)
+        out["graph_replay"] = graph_replay(sweeps)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(sweeps, args.cpu_budget)
     print(json.dumps(out))
