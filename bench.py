@@ -128,6 +128,18 @@ class Sweep:
         # arguments marshalled once per call site; the timed loop is one C call per launch
         self.calls_bound = [self.handle.bind(d, ins, outs, workspace=self.workspace) for d, ins, outs in self.bound]
 
+    def bind_streams(self, streams):
+        """The same calls dealt out round-robin over several streams (independent requests may
+        overlap their ramp-up and drain); every stream gets a workspace of its own."""
+        ws = [torch.empty_like(self.workspace) for _ in streams]
+        self.calls_multi = [self.handle.bind(d, ins, outs, workspace=ws[i % len(streams)], stream=streams[i % len(streams)].cuda_stream)
+                            for i, (d, ins, outs) in enumerate(self.bound)]
+        self._multi_keep = ws
+
+    def run_all_multi(self):
+        for c in self.calls_multi:
+            c()
+
     def run_all(self):
         for c in self.calls_bound:
             c()
@@ -336,6 +348,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-gap-to-static", action="store_true")
     ap.add_argument("--no-next-rows", action="store_true")
+    ap.add_argument("--streams", type=int, default=1, help="streams the calls of the timed step are dealt out over")
     ap.add_argument("--cpu-budget", type=float, default=20.0)
     ap.add_argument("--dump-calls", default="", help="write per-call dims / bytes / device time as JSON lines")
     args = ap.parse_args()
@@ -356,9 +369,14 @@ def main():
     torch.cuda.synchronize()
     setup_s = time.perf_counter() - t_setup
 
+    streams = [torch.cuda.Stream() for _ in range(args.streams)] if args.streams > 1 else []
+    for sw in sweeps:
+        if streams:
+            sw.bind_streams(streams)
+
     def step():
         for sw in sweeps:
-            sw.run_all()
+            sw.run_all_multi() if streams else sw.run_all()
 
     for _ in range(args.warmup):
         step()
@@ -484,6 +502,23 @@ def main():
     if not args.no_next_rows:
         out["next_rows"] = next_rows(ctx, dev)
         out["graph_replay"] = graph_replay(sweeps)
+        if not streams:
+            # the same step with its (independent) calls dealt out over four streams: ramp-up and
+            # drain of consecutive kernels overlap.  A secondary figure; the headline, the roofline
+            # object and the profiles are all single-stream.
+            four = [torch.cuda.Stream() for _ in range(4)]
+            for sw in sweeps:
+                sw.bind_streams(four)
+            for sw in sweeps:
+                sw.run_all_multi()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(args.steps):
+                for sw in sweeps:
+                    sw.run_all_multi()
+            torch.cuda.synchronize()
+            w4 = (time.perf_counter() - t0) / args.steps
+            out["multi_stream"] = {"streams": 4, "value": round(step_bytes / w4 / 1e9, 1), "ms_per_step": round(w4 * 1e3, 3)}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(sweeps, args.cpu_budget)
     print(json.dumps(out))
