@@ -261,7 +261,7 @@ int analyze(const disc_op* ops, int n_ops, const disc_constraint* cs, int n_cs, 
             std::string* errp) {
   Analysis& an = *out;
   std::string& err = *errp;
-  char buf[256];
+  char buf[400];
   if (!ops || n_ops <= 0) { err = "empty op list"; return DISC_ERR_INVALID_ARG; }
   if (n_ops > DISC_MAX_OPS) { err = "too many ops"; return DISC_ERR_BAD_PATTERN; }
   if (n_cs < 0 || (n_cs > 0 && !cs)) { err = "bad constraint list"; return DISC_ERR_INVALID_ARG; }
@@ -536,6 +536,49 @@ int analyze(const disc_op* ops, int n_ops, const disc_constraint* cs, int n_cs, 
   int first_reduce = -1;
   for (int i = 0; i < n_ops; ++i)
     if (is_reduce(ops[i].opcode)) { first_reduce = i; break; }
+  // Sums over the rows next to reductions over the innermost axis (the weight gradients of a
+  // normalisation beside its input gradient): the row template carries them along as per-column
+  // partial sums that a second launch combines.  Accepted for a two-dimensional iteration space
+  // (other axes of size 1), floating-point sums, results that go straight to outputs.
+  std::vector<char> side(n_ops, 0);
+  if (first_reduce >= 0) {
+    auto unit = [&](int32_t d) { return dc.static_val[dc.find(dc.atom(d))] == 1; };
+    auto inner_axis = [&](const disc_op& t) {
+      for (int k = t.rank - 1; k >= 0; --k) if (!unit(t.dim[k])) return k;
+      return t.rank - 1;
+    };
+    bool mixed = false;
+    for (int i = 0; i < n_ops; ++i)
+      if (is_reduce(ops[i].opcode) && ops[i].axis_map[0] != ops[first_reduce].axis_map[0]) mixed = true;
+    int primary = -1;
+    if (mixed)
+      for (int i = 0; i < n_ops && primary < 0; ++i)
+        if (is_reduce(ops[i].opcode) && ops[i].axis_map[0] == inner_axis(ops[ops[i].in[0]])) primary = i;
+    if (primary >= 0) {
+      const int a1 = ops[primary].axis_map[0];
+      for (int i = 0; i < n_ops; ++i) {
+        if (!is_reduce(ops[i].opcode) || ops[i].axis_map[0] == a1) continue;
+        const disc_op& src = ops[ops[i].in[0]];
+        const int a2 = ops[i].axis_map[0];
+        bool ok = ops[i].opcode == DISC_REDUCE_SUM && a2 < a1 && reg_kind(src.dtype) == RK_F32;
+        for (int k = 0; k < src.rank; ++k)
+          if (k != a1 && k != a2 && !unit(src.dim[k])) ok = false;
+        for (int j = 0; j < n_ops; ++j)
+          for (int k = 0; k < operand_count(ops[j].opcode); ++k)
+            if (ops[j].in[k] == i && ops[j].opcode != DISC_OUTPUT) ok = false;
+        if (!ok) {
+          snprintf(buf, sizeof buf, "op %d (%s) reduces over axis %d while op %d reduces over the innermost axis: a "
+                   "reduction over the rows is fused with row reductions only as a floating-point sum over the "
+                   "outer axis of a two-dimensional iteration space that feeds outputs alone", i,
+                   opcode_name(ops[i].opcode), a2, primary);
+          err = buf;
+          return DISC_ERR_UNFUSIBLE;
+        }
+        side[i] = 1;
+      }
+      first_reduce = primary;
+    }
+  }
   int root_value;
   if (first_reduce >= 0) {
     root_value = ops[first_reduce].in[0];
@@ -560,7 +603,7 @@ int analyze(const disc_op* ops, int n_ops, const disc_constraint* cs, int n_cs, 
       err = buf;
       return DISC_ERR_UNFUSIBLE;
     }
-    if (ops[i].axis_map[0] != an.reduce_axis) {
+    if (ops[i].axis_map[0] != an.reduce_axis && !side[i]) {
       snprintf(buf, sizeof buf, "op %d and op %d reduce over different axes (%d vs %d)", first_reduce, i,
                an.reduce_axis, ops[i].axis_map[0]);
       err = buf;
@@ -577,7 +620,8 @@ int analyze(const disc_op* ops, int n_ops, const disc_constraint* cs, int n_cs, 
     const disc_op& op = ops[i];
     if (op.rank > 0 && b.shapes_match_root(op)) { nat[i] = ident; has_nat[i] = 1; continue; }
     if (is_reduce(op.opcode)) {
-      for (int k = 0; k < an.root_rank; ++k) if (k != an.reduce_axis) nat[i].push_back(k);
+      const int ax = side[i] ? op.axis_map[0] : an.reduce_axis;
+      for (int k = 0; k < an.root_rank; ++k) if (k != ax) nat[i].push_back(k);
       has_nat[i] = 1;
     } else if (is_elementwise(op.opcode) || op.opcode == DISC_OUTPUT) {
       for (int k = 0; k < n_operands(op.opcode); ++k) {
@@ -645,9 +689,16 @@ int analyze(const disc_op* ops, int n_ops, const disc_constraint* cs, int n_cs, 
       return DISC_ERR_UNFUSIBLE;
     }
     OutputRef o;
-    o.node = b.demand(i, c);
-    if (o.node < 0) return b.status;
     Access a;
+    if (side[ops[i].in[0]]) {
+      // a sum over the rows: the node is the value summed, seen over the whole iteration space
+      o.col_sum = a.col_sum = true;
+      o.node = b.demand(ops[ops[i].in[0]].in[0], ident);
+      ++an.n_col_sums;
+    } else {
+      o.node = b.demand(i, c);
+    }
+    if (o.node < 0) return b.status;
     a.value = i;
     a.is_output = true;
     a.dtype = ops[i].dtype;

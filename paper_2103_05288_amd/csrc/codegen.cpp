@@ -317,7 +317,7 @@ struct Gen {
       for (int id : an.reduces[P]) r.push_back(an.nodes[id].in[0]);
     } else {
       for (const auto& out : an.outputs)
-        if (elem_output(an.accesses[out.access])) r.push_back(out.node);
+        if (elem_output(an.accesses[out.access]) || out.col_sum) r.push_back(out.node);
     }
     return r;
   }
@@ -527,7 +527,7 @@ struct Gen {
 
   // outputs written per element by the epilogue (column reduce: only those that keep the reduced axis)
   bool elem_output(const Access& a) const {
-    if (!a.has_inner) return false;
+    if (!a.has_inner || a.col_sum) return false;
     if (!col_tmpl()) return true;
     for (int g : a.groups) if (g == an.mid_group) return true;
     return false;
@@ -860,6 +860,44 @@ struct Gen {
     os << "    (void)A; (void)row; (void)rc;\n  }\n";
   }
 
+  // ---- row reduce with sums over the rows: per-column partial sums next to the epilogue --------
+  // ColAcc holds one fp32 vector per summed output; col_sums adds one slot of one row to it;
+  // colsum_store rounds the finished sums of one column to the outputs' types.
+  void emit_col_sums() {
+    const int nq = an.n_col_sums;
+    os << "  static constexpr int NCOLSUM = " << nq << ";\n";
+    os << "  template <int V> struct ColAcc { typename disc::Vec<float, V>::vec_t c[" << std::max(nq, 1) << "]; };\n";
+    if (nq == 0) return;
+    os << "  template <int V, bool KEEP, class C> static DISC_DEV void col_sums(const Args& A, const RowCtx& rc, const Slot<V>& s, const Keep<V>& k, C col, disc::Span sp, ColAcc<V>& ca) {\n";
+    auto flavour = [&](bool keep) {
+      Fn fn(*this, M_ELEM);
+      fn.P = an.n_phases;
+      fn.keep = keep;
+      std::ostringstream tail;
+      int q = 0;
+      for (const auto& out : an.outputs) {
+        if (!out.col_sum) continue;
+        tail << "        ca.c[" << q++ << "][e] += " << convert(fn.val(out.node), an.nodes[out.node].rk, RK_F32) << ";\n";
+      }
+      emit_late_loads(os, fn, "      ");
+      os << "#pragma unroll\n      for (int e = 0; e < V; ++e) {\n" << fn.body.str() << tail.str() << "      }\n";
+    };
+    os << "    if constexpr (KEEP) {\n";
+    flavour(true);
+    os << "    } else {\n";
+    flavour(false);
+    os << "    }\n";
+    os << "    (void)A; (void)rc; (void)s; (void)k; (void)col; (void)sp; (void)ca;\n  }\n";
+    os << "  static DISC_DEV void colsum_store(const Args& A, disc::i64 col, const float (&v)[" << nq << "]) {\n";
+    int q = 0;
+    for (const auto& out : an.outputs) {
+      if (!out.col_sum) continue;
+      const Access& a = an.accesses[out.access];
+      os << "    A.o" << a.slot << "[col] = " << to_storage(fmt("v[%d]", q++), RK_F32, a.dtype) << ";\n";
+    }
+    os << "  }\n";
+  }
+
   // ---- column reduce: partial-accumulator planes and the finish step -------------------------
   // Workspace ws0 holds one 8-byte cell per (accumulator field, outer, chunk, column); ws1 holds
   // the final reduce results, one plane per reduction, typed as the reduce result's register kind.
@@ -977,6 +1015,7 @@ struct Gen {
       max_threads = 256;
       k("k_row_stream_vec", fmt("disc::row_stream_body<Pat, %d>(A);", V), nullptr);
       k("k_row_stream_scalar", "disc::row_stream_body<Pat, 1>(A);", nullptr);
+      if (an.n_col_sums > 0) k("k_colsum_finish", "disc::colsum_finish_body<Pat>(A);", nullptr);
     } else {
       k("k_col_partial_vec", fmt("disc::col_partial_body<Pat, %d>(A, rp);", V), "ColPlan");
       k("k_col_partial_scalar", "disc::col_partial_body<Pat, 1>(A, rp);", "ColPlan");
@@ -1043,6 +1082,7 @@ struct Gen {
         emit_row_phase_fns();
       }
       emit_epilogue(M_ELEM);
+      emit_col_sums();
       os << "};\n";
       if (staged_versions) os << "typedef PatT<false> Pat;\n";
     } else {
@@ -1086,6 +1126,7 @@ struct Gen {
     out->n_acc_cells = n_acc_cells;
     out->n_red_planes = col_tmpl() ? (int)an.reduces[0].size() : 0;
     out->has_epilogue = col_tmpl() ? has_elem_outputs() : true;
+    out->n_col_sums = row_tmpl() ? an.n_col_sums : 0;
     out->staged_elem_bytes.clear();
     for (int ai : staged_accesses()) out->staged_elem_bytes.push_back(dtype_bytes(an.accesses[ai].dtype));
     return DISC_OK;

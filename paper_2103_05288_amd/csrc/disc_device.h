@@ -445,6 +445,16 @@ DISC_DEV void ld_lds(Vec<T, N>& d, const char* base, int byte_off, int col) {
   d.v = *reinterpret_cast<const typename Vec<T, N>::vec_t*>(base + byte_off + col * (int)sizeof(T));
 }
 
+// Sums over the rows carried along by a row reduce (Pat::NCOLSUM of them): every lane adds the
+// values of its own columns, row after row, into fp32 registers; at the end of the kernel each
+// wavefront (rows of at most a wavefront) or lane group (longer rows) writes one row of partial
+// sums per summed output into the workspace, plane q at ws + q * n_partial_rows * inner, and a
+// second launch adds the partial rows up in a fixed order.
+DISC_DEV float lane_xor_f32(float v, int s) {
+  const int lane = (int)threadIdx.x & 63;
+  return __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute((lane ^ s) << 2, __builtin_bit_cast(int, v)));
+}
+
 // `after_first` runs once, after the slots have been folded into the accumulator of phase 0 and
 // before the lanes combine: the place where the caller issues the loads of the next row.
 template <class Pat, int P, int V, int NV, class Hook>
@@ -515,7 +525,8 @@ DISC_DEV void row_reg_body(const typename Pat::Args& A, const RowPlan& rp) {
   // to twice the work of the others, and it would always be the first one -- on the same SIMD
   // of the CU for every row.  The slot grid is therefore turned by one wavefront from row to
   // row (lane l takes the columns of lane l + rot), which spreads the extra work evenly.
-  const int wpr = (rp.G > 64 && !(rp.flags & 2)) ? rp.G >> 6 : 1;   // flags bit 1: grid not turned (experiments)
+  // (a lane that sums its columns over the rows keeps its columns: no turning then)
+  const int wpr = (Pat::NCOLSUM == 0 && rp.G > 64 && !(rp.flags & 2)) ? rp.G >> 6 : 1;   // flags bit 1: grid not turned (experiments)
   int rot = wpr > 1 ? (int)(blockIdx.x % (unsigned)wpr) * 64 : 0;
   int col0 = lane * V;
   int nvalid[NV];
@@ -537,6 +548,7 @@ DISC_DEV void row_reg_body(const typename Pat::Args& A, const RowPlan& rp) {
   // complete behind the lane reductions, the later phases, the epilogue and the stores.
   typename Pat::RowCtx rc{};
   typename Pat::template Slot<V> slot[NV];
+  typename Pat::template ColAcc<V> cacc[NV]{};
   // Row bookkeeping in scalar registers: rw = row of the first lane group of this wavefront in
   // the current row group, sbw = its element offset; both advance by a constant per iteration
   // (no 64-bit products in the loop).  A lane's row is rw + dgrp.
@@ -616,6 +628,9 @@ DISC_DEV void row_reg_body(const typename Pat::Args& A, const RowPlan& rp) {
         // in every iteration.  The stores then have a whole iteration to drain.
         if (PIPE && j == 0) __builtin_amdgcn_s_waitcnt(0x0F70);
         if (active) Pat::template store<V, NT>(A, rc, (unsigned)col, span[j], o);
+        if constexpr (Pat::NCOLSUM > 0) {
+          if (active) Pat::template col_sums<V, true>(A, rc, slot[j], keep[j], col, span[j], cacc[j]);
+        }
       }
     }
     if (active && lane == 0) Pat::row_store(A, row, rc);
@@ -633,6 +648,57 @@ DISC_DEV void row_reg_body(const typename Pat::Args& A, const RowPlan& rp) {
     } else if (wpr > 1) {
       rot = rot + 64 < rp.G ? rot + 64 : 0;
       place(rot, col0, nvalid);
+    }
+  }
+  if constexpr (Pat::NCOLSUM > 0) {
+    // lane groups of one wavefront hold the same columns: add them up across the groups
+    if (rp.G < 64) {
+#pragma unroll
+      for (int j = 0; j < NV; ++j)
+#pragma unroll
+        for (int q = 0; q < Pat::NCOLSUM; ++q)
+#pragma unroll
+          for (int e = 0; e < V; ++e) {
+            float x = cacc[j].c[q][e];
+            for (int sft = rp.G; sft < 64; sft <<= 1) x += lane_xor_f32(x, sft);
+            cacc[j].c[q][e] = x;
+          }
+    }
+    // lane sets of the block that hold the same columns (the wavefronts of short rows, the lane
+    // groups of rows of two wavefronts): in blocks of 256 threads they meet in LDS, one slot of
+    // one sum at a time, so that a block writes a single row of partial sums
+    const int period = rp.G > 64 ? rp.G : 64;
+    const int copies = (int)blockDim.x / period;
+    const int copy = (int)threadIdx.x / period;
+    const bool merge = copies > 1 && blockDim.x <= 256;
+    if (merge) {
+      __shared__ typename Vec<float, V>::vec_t cbuf[256];
+#pragma unroll
+      for (int j = 0; j < NV; ++j)
+#pragma unroll
+        for (int q = 0; q < Pat::NCOLSUM; ++q) {
+          if (copy > 0) cbuf[threadIdx.x] = cacc[j].c[q];
+          __syncthreads();
+          if (copy == 0)
+            for (int k = 1; k < copies; ++k) cacc[j].c[q] += cbuf[(int)threadIdx.x + k * period];
+          __syncthreads();
+        }
+    }
+    const int ppb = merge ? 1 : copies;                                 // rows of partial sums per block
+    const bool writer = (merge ? copy == 0 : true) && (rp.G >= 64 || ((int)threadIdx.x & 63) < rp.G);
+    float* ws = reinterpret_cast<float*>(A.ws0);
+    const i64 prow = (i64)blockIdx.x * ppb + (merge ? 0 : copy);
+    if (writer) {
+#pragma unroll
+      for (int j = 0; j < NV; ++j)
+        if (nvalid[j] > 0) {
+#pragma unroll
+          for (int q = 0; q < Pat::NCOLSUM; ++q) {
+            Vec<float, V> t;
+            t.v = cacc[j].c[q];
+            st(ws + ((i64)q * A.aux0 + prow) * A.inner, (i64)(col0 + j * rp.G * V), t, Span::upto(nvalid[j]));
+          }
+        }
     }
   }
 }
@@ -677,6 +743,7 @@ DISC_DEV void row_stream_body(const typename Pat::Args& A) {
   __shared__ __attribute__((aligned(16))) char lds[2 * 16 * Pat::MAX_ACC_BYTES];
   const int inner = (int)A.inner;
   int parity = 0;
+  bool first = true;
   for (i64 row = blockIdx.x; row < A.rows; row += gridDim.x) {
     typename Pat::RowCtx rc;
     Pat::row_begin(A, row, rc);
@@ -691,8 +758,73 @@ DISC_DEV void row_stream_body(const typename Pat::Args& A) {
       typename Pat::template Keep<V> kp;
       Pat::template epilogue<V, false>(A, rc, slot, kp, col, Span::upto(n), o);
       Pat::template store<V>(A, rc, col, Span::upto(n), o);
+      if constexpr (Pat::NCOLSUM > 0) {
+        // sums over the rows: the block's row of partial sums lives in the workspace (the rows are
+        // too long for registers); every lane owns its columns there, so no other lane touches them
+        typename Pat::template ColAcc<V> ca{};
+        Pat::template col_sums<V, false>(A, rc, slot, kp, col, Span::upto(n), ca);
+#pragma unroll
+        for (int q = 0; q < Pat::NCOLSUM; ++q) {
+          float* dst = reinterpret_cast<float*>(A.ws0) + ((i64)q * A.aux0 + blockIdx.x) * A.inner;
+          Vec<float, V> t;
+          t.v = ca.c[q];
+          if (!first) {
+            Vec<float, V> old;
+            ld(old, dst, (i64)col, Span::upto(n));
+            t.v += old.v;
+          }
+          st(dst, (i64)col, t, Span::upto(n));
+        }
+      }
     }
     if (threadIdx.x == 0) Pat::row_store(A, row, rc);
+    first = false;
+  }
+}
+
+// Second launch of a row reduce with sums over the rows: adds up the P rows of partial sums of
+// every summed output, in a fixed order (the result does not depend on timing) and in fp64 (the
+// fp32 partial sums each cover the rows of one block only).  A block takes 16 columns; its 256
+// lanes are 16 columns x 16 lanes that each walk every 16th partial row, four loads in flight; the
+// 16 lane totals of a column meet in LDS.
+template <class Pat>
+DISC_DEV void colsum_finish_body(const typename Pat::Args& A) {
+  constexpr int NQ = Pat::NCOLSUM;
+  __shared__ double red[NQ][16][17];
+  const int cl = (int)threadIdx.x & 15, pl = (int)threadIdx.x >> 4;
+  const i64 inner = A.inner, P = A.aux0;
+  const float* ws = reinterpret_cast<const float*>(A.ws0);
+  for (i64 c0 = (i64)blockIdx.x * 16; c0 < inner; c0 += (i64)gridDim.x * 16) {
+    const i64 col = c0 + cl;
+#pragma unroll
+    for (int q = 0; q < NQ; ++q) {
+      double a0 = 0.0, a1 = 0.0, a2 = 0.0, a3 = 0.0;
+      if (col < inner) {
+        const float* src = ws + (i64)q * P * inner + col;
+        i64 p = pl;
+        for (; p + 48 < P; p += 64) {
+          a0 += src[p * inner];
+          a1 += src[(p + 16) * inner];
+          a2 += src[(p + 32) * inner];
+          a3 += src[(p + 48) * inner];
+        }
+        for (; p < P; p += 16) a0 += src[p * inner];
+      }
+      red[q][pl][cl] = (a0 + a1) + (a2 + a3);
+    }
+    __syncthreads();
+    if (pl == 0 && col < inner) {
+      float v[NQ];
+#pragma unroll
+      for (int q = 0; q < NQ; ++q) {
+        double t = 0.0;
+#pragma unroll
+        for (int k = 0; k < 16; ++k) t += red[q][k][cl];
+        v[q] = (float)t;
+      }
+      Pat::colsum_store(A, col, v);
+    }
+    __syncthreads();
   }
 }
 

@@ -92,6 +92,9 @@ struct Access {
   bool padded = false;
   double pad_value = 0.0;
   std::vector<int> window;
+  // output of a row-reduce pattern that is a sum over the rows (a column sum beside the row
+  // reductions): one element per column, accumulated next to the epilogue
+  bool col_sum = false;
 };
 
 // Resolved graph: one node per (value, context) pair actually needed.
@@ -112,8 +115,9 @@ struct Node {
 };
 
 struct OutputRef {
-  int node = -1;
+  int node = -1;      // the value stored; for a column sum beside row reductions, the value summed
   int access = -1;
+  bool col_sum = false;
 };
 
 // A product of runtime dims the host evaluates at launch (shape calculation).
@@ -162,6 +166,7 @@ struct Analysis {
   std::vector<OutputRef> outputs;        // in OUTPUT-op order
   std::vector<int> reduces[8];           // reduce nodes per phase
   int n_phases = 0;
+  int n_col_sums = 0;                    // row reduce: outputs that are sums over the rows
   int n_inputs = 0, n_outputs = 0;
   bool needs_decomp = false;             // some access is ACC_PARTIAL
 
@@ -196,6 +201,7 @@ struct Generated {
   int n_acc_cells = 0;                // column reduce: 8-byte cells per partial accumulator
   int n_red_planes = 0;               // column reduce: reduce-result planes in the workspace
   bool has_epilogue = true;           // column reduce: some output keeps the reduced axis
+  int n_col_sums = 0;                 // row reduce: outputs summed over the rows (second launch combines the partial sums)
   std::vector<int> staged_elem_bytes; // row reduce: element size of each row vector that can be staged in LDS
   std::vector<std::string> field_names;   // member name of each args.fields entry in Pat::Args
 };

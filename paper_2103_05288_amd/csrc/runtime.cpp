@@ -408,6 +408,9 @@ int make_plan(disc_ctx* c, const Pattern& p, const int64_t* dims, int n_dims, in
     pub.variant = vec ? (i64 ? DISC_V_LOOP_VEC_I64 : DISC_V_LOOP_VEC) : (i64 ? DISC_V_LOOP_SCALAR_I64 : DISC_V_LOOP_SCALAR);
     pub.n_launches = 1;
   } else if (an.tmpl == DISC_TEMPLATE_ROW_REDUCE) {
+    const int n_col_sums = p.gen.n_col_sums;   // outputs summed over the rows, carried along by the row kernels
+    if (sv.rows == 0 && n_col_sums > 0 && sv.inner > 0)
+      return set_err(c, DISC_ERR_EMPTY_REDUCE, "reduction over an axis of size 0");
     if (sv.rows == 0) return DISC_OK;
     if (sv.inner == 0) return set_err(c, DISC_ERR_EMPTY_REDUCE, "reduction over an axis of size 0");
     if (sv.inner >= (1ll << 31) - 4096) return set_err(c, DISC_ERR_SHAPE, "row longer than 2^31 elements");
@@ -432,7 +435,9 @@ int make_plan(disc_ctx* c, const Pattern& p, const int64_t* dims, int n_dims, in
     if (stream) {
       pub.variant = vec ? DISC_V_ROW_STREAM_VEC : DISC_V_ROW_STREAM_SCALAR;
       L.kernel = vec ? "k_row_stream_vec" : "k_row_stream_scalar";
-      L.grid[0] = (uint32_t)std::min<int64_t>(sv.rows, max_grid * 2);
+      // (sums over the rows: a row of partial sums per block in the workspace, so fewer blocks)
+      L.grid[0] = (uint32_t)std::min<int64_t>(sv.rows, n_col_sums > 0 ? (int64_t)c->n_cus * 2 : max_grid * 2);
+      fp->aux[0] = L.grid[0];   // rows of partial sums: one per block
       pub.lanes_per_row = 256;
       pub.slots_per_lane = (int)((spr + 255) / 256);
       pub.reg_slots = 1;
@@ -468,7 +473,7 @@ int make_plan(disc_ctx* c, const Pattern& p, const int64_t* dims, int n_dims, in
         int64_t bytes = 0;
         for (int eb : p.gen.staged_elem_bytes) bytes += ((sv.inner + v) * eb + 15) & ~15ll;
         const bool stage = vec && V > 1 && c->row_stage && bytes > 0 && bytes <= 48 * 1024;
-        L.rp.flags = (stage ? 1 : 0) | (c->row_turn ? 0 : 2);
+        L.rp.flags = (stage ? 1 : 0) | (c->row_turn && n_col_sums == 0 ? 0 : 2);
         L.dyn_lds = stage ? (uint32_t)bytes : 0;
         // k_row_{vec|scalar}_nv{1|2|3}[w][_s][_nt]: w = block above 256 threads, _s = staged version,
         // _nt = non-temporal accesses of the full-size operands
@@ -519,8 +524,9 @@ int make_plan(disc_ctx* c, const Pattern& p, const int64_t* dims, int n_dims, in
       const int rpb = (int)L.block / G;
       const int64_t ngroups = (sv.rows + rpb - 1) / rpb;
       const int64_t held = (int64_t)c->n_cus * resident_blocks(c, p, L.kernel, L.block, L.dyn_lds);
+      // (with sums over the rows every block writes a row of partial sums per wavefront: one round)
       const int rounds = c->row_rounds > 0 ? c->row_rounds
-                         : (L.block > 256 ? 1 : (int)std::max<int64_t>(1, std::min<int64_t>(3, ngroups / (held * 4))));
+                         : (L.block > 256 || n_col_sums > 0 ? 1 : (int)std::max<int64_t>(1, std::min<int64_t>(3, ngroups / (held * 4))));
       int64_t grid = std::min<int64_t>(ngroups, held * rounds);
       // An odd grid: with an even one a block of one row per iteration would only ever see even or
       // only odd rows, and when the row length is odd every other row starts two bytes off a
@@ -529,11 +535,28 @@ int make_plan(disc_ctx* c, const Pattern& p, const int64_t* dims, int n_dims, in
       // through all alignments of its rows, whatever the rows per block.
       if (grid > 2 && grid % 2 == 0 && grid < ngroups) grid -= 1;
       L.grid[0] = (uint32_t)grid;
+      // rows of partial sums: one per block of 256 threads, one per lane group of a wider block
+      fp->aux[0] = grid * (L.block <= 256 ? 1 : (int64_t)L.block / std::max(G, 64));
       pub.lanes_per_row = G;
       pub.slots_per_lane = nv;
       pub.reg_slots = inst;
     }
     pub.n_launches = 1;
+    if (n_col_sums > 0) {
+      // workspace: n_col_sums planes of [partial rows, inner] fp32; the second launch adds the rows up
+      int64_t cells, bytes;
+      if (mul_ovf(fp->aux[0], sv.inner, &cells) || mul_ovf(cells, 4ll * n_col_sums, &bytes))
+        return set_err(c, DISC_ERR_SHAPE, "workspace size overflows int64");
+      pub.workspace_bytes = (size_t)bytes;
+      fp->ws_off[0] = 0;
+      LaunchRec& L1 = fp->launches[1];
+      L1.kernel = "k_colsum_finish";
+      L1.block = 256;
+      L1.grid[0] = (uint32_t)std::min<int64_t>((sv.inner + 15) / 16, max_grid * 4);
+      pub.n_launches = 2;
+    } else {
+      fp->aux[0] = 0;
+    }
   } else {
     // column reduce: canonical [outer, mid, inner], rows = outer * mid
     const int64_t outer = an.mid_group == 1 ? sv.group[0] : 1;
@@ -1462,6 +1485,8 @@ int disc_register_graph(disc_ctx* ctx, const disc_op* ops, int n_ops, const disc
         for (size_t pos = cuts[gi].size(); pos-- > 0;) {
           const int x = cuts[gi][pos];
           if (users[x].empty()) continue;
+          // a reduction stays where its operand is computed: moved, it would read the operand again
+          if (g->ops[x].opcode >= DISC_REDUCE_SUM && g->ops[x].opcode <= DISC_REDUCE_ARGMAX) continue;
           int to = -1;
           bool ok = true;
           for (int u : users[x]) {

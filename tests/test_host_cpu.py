@@ -137,6 +137,13 @@ def test_unfusible_patterns(ctx):
     pb = PatternBuilder()
     t, h = pb.dims(2)
     x = pb.param("f32", [t, h])
+    pb.output(pb.reduce("max", x, 0))
+    pb.output(pb.reduce("sum", x, 1))
+    assert "floating-point sum" in expect("UNFUSIBLE", ctx.register, pb.build())
+    # (a SUM over the rows next to row reductions is fused: tests/test_row_col_sums.py)
+    pb = PatternBuilder()
+    b, t, h = pb.dims(3)
+    x = pb.param("f32", [b, t, h])
     pb.output(pb.reduce("sum", x, 0))
     pb.output(pb.reduce("sum", x, 1))
     assert "different axes" in expect("UNFUSIBLE", ctx.register, pb.build())

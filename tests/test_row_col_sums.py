@@ -1,0 +1,187 @@
+"""Sums over the rows fused into a row-reduce pattern (the weight gradients of a normalisation next
+to its input gradient, Section 4.3's input fusion with both reduction kinds in one kernel): the
+checker's acceptance rule, the launch plan, and parity with the oracle through the C ABI."""
+import numpy as np
+import pytest
+import torch
+
+from workloads.configs import TORCH_DTYPE
+from workloads.extras import layernorm_backward_graph
+from workloads.pattern import PatternBuilder
+
+
+@pytest.fixture(scope="module")
+def hctx():
+    from paper_2103_05288_amd import Context
+    c = Context(device=-1)
+    yield c
+    c.close()
+
+
+def softmax_backward_with_bias_gradient():
+    """dx of a row softmax (one row reduction) and the column sum of dx's upstream gradient."""
+    pb = PatternBuilder("softmax_bwd_bias")
+    t, h = pb.dims(2)
+    y = pb.cast(pb.param("bf16", [t, h]), "f32")
+    dy = pb.cast(pb.param("bf16", [t, h]), "f32")
+    dot = pb.reduce("sum", pb.op("mul", dy, y), 1)
+    dx = pb.op("mul", y, pb.op("sub", dy, pb.broadcast(dot, [t, h], [0])))
+    pb.output(pb.cast(dx, "bf16"))
+    pb.output(pb.reduce("sum", dx, 0))
+    return pb.build()
+
+
+def test_one_pattern_two_launches(hctx):
+    pat = layernorm_backward_graph()
+    h = hctx.register(pat)
+    assert h.info["template"] == "row_reduce" and h.info["n_phases"] == 3 and h.info["n_outputs"] == 3
+    pl = h.plan([4096, 1024])
+    assert pl["n_launches"] == 2 and pl["kernels"][0].split("k_row_")[1].startswith("vec_nv2") and pl["kernels"][1].endswith("k_colsum_finish")
+    # one row of fp32 partial sums per block and summed output
+    assert pl["workspace_bytes"] == pl["grid"][0][0] * 1024 * 4 * 2
+    assert pl["grid"][1][0] == 1024 // 16
+    # rows too long for registers: the streaming version keeps the partial sums in the workspace
+    pl = h.plan([100, 30000])
+    assert pl["kernels"][0].endswith("k_row_stream_vec") and pl["workspace_bytes"] == 100 * 30000 * 4 * 2
+    # wide blocks (one lane group per block): still one row of partial sums per block
+    pl = h.plan([3000, 8192])
+    assert pl["block"][0][0] == 512 and pl["workspace_bytes"] == pl["grid"][0][0] * 8192 * 4 * 2
+    # the graph front end now keeps the whole backward pass in this one pattern
+    g = hctx.register_graph(pat)
+    assert g.info["n_patterns"] == 1 and g.info["n_intermediates"] == 0
+    # a sum over zero rows has no value
+    from paper_2103_05288_amd import DiscError
+    with pytest.raises(DiscError) as e:
+        h.plan([0, 64])
+    assert "size 0" in str(e.value)
+
+
+def test_acceptance_rule(hctx):
+    from paper_2103_05288_amd import DiscError
+
+    def build(kind="sum", consume=False, rank3=False, integer=False):
+        pb = PatternBuilder("rule")
+        if rank3:
+            b, t, h = pb.dims(3)
+            shape, rows_axes = [b, t, h], [0, 1]
+        else:
+            t, h = pb.dims(2)
+            shape, rows_axes = [t, h], [0]
+        x = pb.param("i32" if integer else "f32", shape)
+        m = pb.reduce("max", x, len(shape) - 1)
+        d = pb.op("sub", x, pb.broadcast(m, shape, rows_axes))
+        pb.output(d)
+        s = pb.reduce(kind, d, 0)
+        if consume:
+            s = pb.op("neg", s)
+        pb.output(s)
+        return pb.build()
+
+    assert hctx.register(build()).info["template"] == "row_reduce"
+    for kw, word in ((dict(kind="max"), "floating-point sum"), (dict(consume=True), "outputs alone"),
+                     (dict(rank3=True), "two-dimensional"), (dict(integer=True), "floating-point sum")):
+        with pytest.raises(DiscError) as e:
+            hctx.register(build(**kw))
+        assert e.value.status == "UNFUSIBLE" and word in str(e.value), (kw, str(e.value))
+
+
+def _inputs(pat, dims, gen):
+    ins = []
+    for pi in pat.params:
+        shp = pat.shape_of(pi, dims)
+        ins.append(torch.randn(shp, generator=gen).to(TORCH_DTYPE[pat.ops[pi].dtype]))
+    return ins
+
+
+def _check_sum(got, want, terms_abs, rows_per_block, what):
+    """A sum of T terms of mixed sign cannot meet a bar relative to the (cancelled) result.  Each
+    term carries at most 8 fp32 roundings from the element-wise arithmetic; a lane then adds the
+    terms of its block's rows in fp32 (rows_per_block additions), the lane groups of a block meet in
+    at most 8 more fp32 additions, and the partial rows are added in fp64:
+    |err| <= (16 + rows_per_block) * 2^-24 * sum_t |term_t| + 1e-6."""
+    lim = (16 + rows_per_block) * 2.0 ** -24 * terms_abs.sum(0) + 1e-6
+    err = np.abs(got.double().numpy() - np.asarray(want, dtype=np.float64))
+    assert (err <= lim).all(), (what, float((err / lim).max()))
+
+
+LN_SHAPES = [[7, 5], [300, 1], [1000, 77], [20000, 16], [4096, 1024], [513, 2050], [1500, 1021], [300, 4100],
+             [65, 8200], [40, 30000], [3, 40000]]
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("dims", LN_SHAPES, ids=lambda d: f"{d[0]}x{d[1]}")
+def test_layernorm_backward_single_pattern_matches_oracle(dims):
+    from oracle import run as oracle_run
+    from paper_2103_05288_amd import Context
+    from tests.util import assert_close, run_gpu, to_oracle_input
+    pat = layernorm_backward_graph()
+    ctx = Context(0)
+    try:
+        h = ctx.register(pat)
+        gen = torch.Generator().manual_seed(dims[0] * 7919 + dims[1])
+        ins = _inputs(pat, dims, gen)
+        pl = h.plan(dims)
+        assert pl["n_launches"] == 2
+        got = run_gpu(h, pat, dims, ins)
+        want = oracle_run(pat, dims, [to_oracle_input(t) for t in ins])[0]
+        assert_close(got[0], want[0], f"dx dims={dims}")
+        x64, dy64 = ins[0].double().numpy(), ins[1].double().numpy()
+        xc = x64 - x64.mean(1, keepdims=True)
+        xhat = xc / np.sqrt((xc * xc).mean(1, keepdims=True) + 1e-5)
+        rpb = -(-dims[0] // pl["grid"][0][0])
+        _check_sum(got[1], want[1], np.abs(dy64 * xhat), rpb, f"dgamma dims={dims} {pl['kernels'][0]}")
+        _check_sum(got[2], want[2], np.abs(dy64), rpb, f"dbeta dims={dims} {pl['kernels'][0]}")
+        # the same call again on the same workspace gives the same bits (fixed summation order)
+        again = run_gpu(h, pat, dims, ins)
+        for a, b in zip(got, again):
+            assert torch.equal(a, b)
+    finally:
+        ctx.close()
+
+
+@pytest.mark.gpu
+def test_forced_versions_and_one_phase_pattern():
+    """Every row-kernel version carries the sums (scalar and streaming versions forced on shapes the
+    host would give to the vector version), and a one-phase pattern (softmax backward) with a single
+    summed output."""
+    from oracle import run as oracle_run
+    from paper_2103_05288_amd import Context
+    from paper_2103_05288_amd.binding import VARIANTS
+    from tests.util import assert_close, run_gpu, to_oracle_input
+    ctx = Context(0)
+    try:
+        pat = layernorm_backward_graph()
+        h = ctx.register(pat)
+        gen = torch.Generator().manual_seed(5)
+        for force in ("row_reg_vec", "row_reg_scalar", "row_stream_vec", "row_stream_scalar"):
+            for dims in ([33, 768], [600, 100]):
+                ins = _inputs(pat, dims, gen)
+                ctx.force_variant(VARIANTS.index(force))
+                try:
+                    pl = h.plan(dims, force_variant=VARIANTS.index(force))
+                    got = run_gpu(h, pat, dims, ins)
+                finally:
+                    ctx.force_variant(-1)
+                want = oracle_run(pat, dims, [to_oracle_input(t) for t in ins])[0]
+                assert_close(got[0], want[0], f"dx {force} {dims}")
+                x64, dy64 = ins[0].double().numpy(), ins[1].double().numpy()
+                xc = x64 - x64.mean(1, keepdims=True)
+                xhat = xc / np.sqrt((xc * xc).mean(1, keepdims=True) + 1e-5)
+                rpb = -(-dims[0] // pl["grid"][0][0])
+                _check_sum(got[1], want[1], np.abs(dy64 * xhat), rpb, f"dgamma {force} {dims}")
+                _check_sum(got[2], want[2], np.abs(dy64), rpb, f"dbeta {force} {dims}")
+        pat = softmax_backward_with_bias_gradient()
+        h = ctx.register(pat)
+        assert h.info["template"] == "row_reduce" and h.info["n_phases"] == 1
+        for dims in ([3, 7], [2000, 1000], [9, 5739], [5000, 48]):
+            probs = torch.softmax(torch.randn(*dims, generator=gen), dim=1).bfloat16()
+            ins = [probs, torch.randn(*dims, generator=gen).bfloat16()]
+            pl = h.plan(dims)
+            got = run_gpu(h, pat, dims, ins)
+            want = oracle_run(pat, dims, [to_oracle_input(t) for t in ins])[0]
+            assert_close(got[0], want[0], f"softmax backward dx {dims}")
+            y64, dy64 = ins[0].double().numpy(), ins[1].double().numpy()
+            dx = y64 * (dy64 - (dy64 * y64).sum(1, keepdims=True))
+            _check_sum(got[1], want[1], np.abs(dx) + np.abs(y64 * dy64), -(-dims[0] // pl["grid"][0][0]), f"sum of dx {dims}")
+    finally:
+        ctx.close()
