@@ -141,7 +141,13 @@ typedef struct {
 
 typedef enum {
   DISC_TEMPLATE_LOOP = 0,       /* loop fusion: element-wise / broadcast chain                  */
-  DISC_TEMPLATE_ROW_REDUCE = 1, /* input fusion, reduce over the innermost axis (+ epilogue)    */
+  DISC_TEMPLATE_ROW_REDUCE = 1, /* input fusion, reduce over the innermost axis (+ epilogue).  One
+                                   extension beyond Section 4.3's one reduction kind per kernel:
+                                   REDUCE_SUM of a float value over the outer axis of a
+                                   two-dimensional iteration space whose result feeds OUTPUTs only
+                                   (weight gradients next to an input gradient) is carried along
+                                   by the row kernels as per-block partial sums in the workspace
+                                   and finished by a second launch, in a fixed order           */
   DISC_TEMPLATE_COL_REDUCE = 2, /* input fusion, reduce over an outer axis (+ epilogue)         */
   DISC_TEMPLATE_TRANSPOSE = 3   /* not a fusion: PARAM -> TRANSPOSE -> OUTPUT alone, a permutation
                                    that moves the innermost axis, run as a batched 2-D tile
@@ -237,7 +243,8 @@ int disc_pattern_info(disc_ctx* ctx, int32_t id, disc_pattern_info_t* out);
 /* Generated device source of the pattern (context-owned, valid until disc_destroy). */
 const char* disc_pattern_source(disc_ctx* ctx, int32_t id);
 
-/* Bytes of device workspace disc_launch needs at these dims (0 for loop / row patterns). */
+/* Bytes of device workspace disc_launch needs at these dims (0 for loop patterns and for row
+ * patterns without sums over the rows). */
 int disc_workspace_bytes(disc_ctx* ctx, int32_t id, const int64_t* dims, int n_dims, size_t* out);
 
 /* Pure host: the runtime flow of one launch without enqueueing anything (shape calculation,
