@@ -246,7 +246,8 @@ def next_rows(ctx, dev):
     on inputs (slice, pad, transpose) at one large shape each; effective rate = bytes of the
     graph's / pattern's inputs and outputs, each once, over the device time of one call."""
     from workloads.configs import TORCH_DTYPE
-    from workloads.extras import (heads_softmax, layernorm_backward_graph, padded_softmax, pure_transpose, qkv_split)
+    from workloads.extras import (gelu_backward_bias_gradient, heads_softmax, layernorm_backward_graph, padded_softmax,
+                                  pure_transpose, qkv_split)
 
     def io_bytes(pat, dims):
         n = 0
@@ -259,6 +260,7 @@ def next_rows(ctx, dev):
     rows = {}
     # ~1 GB of operands and results per call: nothing of a call survives in the 256 MB memory-side cache
     cases = [("graph_layernorm_backward", layernorm_backward_graph(), [131072, 1024], True),
+             ("gelu_backward_bias_gradient", gelu_backward_bias_gradient(), [131072, 1024], False),
              ("slice_qkv_split", qkv_split(), [131072, 1024, 3072, 1024, 2048], False),
              ("pad_softmax_minus_inf", padded_softmax(), [131072, 2000, 24, 2048], False),
              ("transpose_heads_softmax", heads_softmax(), [128, 1024, 16, 128], False),
@@ -270,7 +272,8 @@ def next_rows(ctx, dev):
             h = ctx.register_graph(pat)
             ws = torch.empty(max(16, h.workspace_bytes(dims)), dtype=torch.uint8, device=dev)
             call = lambda: h.launch(dims, ins, outs, workspace=ws)
-            extra = {"patterns": h.info["n_patterns"], "planned_buffers": h.info["n_buffers"], "workspace_bytes": int(ws.numel())}
+            extra = {"patterns": h.info["n_patterns"], "planned_buffers": h.info["n_buffers"], "workspace_bytes": int(ws.numel()),
+                     "kernel_prefixes": ["disc_p%d_" % p for p in h.info["pattern_id"][:h.info["n_patterns"]]]}
         else:
             h = ctx.register(pat)
             ws = torch.empty(max(16, ctx.workspace_bytes(h.id, dims)), dtype=torch.uint8, device=dev)
@@ -348,6 +351,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-gap-to-static", action="store_true")
     ap.add_argument("--no-next-rows", action="store_true")
+    ap.add_argument("--next-rows-only", action="store_true",
+                    help="time the secondary workloads alone (plus the plain copy the traffic counters are scaled by) "
+                         "and print them as one JSON line; what the profiles of those kernels are taken from")
     ap.add_argument("--streams", type=int, default=1, help="streams the calls of the timed step are dealt out over")
     ap.add_argument("--cpu-budget", type=float, default=20.0)
     ap.add_argument("--dump-calls", default="", help="write per-call dims / bytes / device time as JSON lines")
@@ -363,6 +369,17 @@ def main():
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     ctx = Context(0)
+    if args.next_rows_only:
+        n_copy = 1 << 30
+        src = torch.zeros(n_copy, dtype=torch.uint8, device=dev)
+        dst = torch.empty(n_copy, dtype=torch.uint8, device=dev)
+        ctx.util_copy(dst, src, n_copy)
+        torch.cuda.synchronize()
+        t_copy = min(time_events(lambda: [ctx.util_copy(dst, src, n_copy) for _ in range(10)]) for _ in range(3)) / 10
+        del src, dst
+        print(json.dumps({"mode": "next_rows_only", "copy_ceiling_GBps": round(2 * n_copy / t_copy / 1e9, 1),
+                          "next_rows": next_rows(ctx, dev)}))
+        return
     names = [n for n in args.configs.split(",") if n]
     t_setup = time.perf_counter()
     sweeps = [Sweep(n, ctx, dev) for n in names]

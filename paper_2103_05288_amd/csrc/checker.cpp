@@ -257,8 +257,10 @@ void mul_into(DimProduct& p, const DimClasses&, int32_t dim) {
 
 int operand_count(int opcode) { return n_operands(opcode); }
 
-int analyze(const disc_op* ops, int n_ops, const disc_constraint* cs, int n_cs, Analysis* out,
-            std::string* errp) {
+// loop_sides: sums over the rows next to a loop fusion may ride along in a row template without
+// reduction phases; *used_loop_sides tells whether that rule decided the template
+static int analyze_impl(const disc_op* ops, int n_ops, const disc_constraint* cs, int n_cs, Analysis* out,
+                        std::string* errp, bool loop_sides, bool* used_loop_sides) {
   Analysis& an = *out;
   std::string& err = *errp;
   char buf[400];
@@ -541,6 +543,7 @@ int analyze(const disc_op* ops, int n_ops, const disc_constraint* cs, int n_cs, 
   // partial sums that a second launch combines.  Accepted for a two-dimensional iteration space
   // (other axes of size 1), floating-point sums, results that go straight to outputs.
   std::vector<char> side(n_ops, 0);
+  int rows_axis_override = -1;
   if (first_reduce >= 0) {
     auto unit = [&](int32_t d) { return dc.static_val[dc.find(dc.atom(d))] == 1; };
     auto inner_axis = [&](const disc_op& t) {
@@ -550,22 +553,47 @@ int analyze(const disc_op* ops, int n_ops, const disc_constraint* cs, int n_cs, 
     bool mixed = false;
     for (int i = 0; i < n_ops; ++i)
       if (is_reduce(ops[i].opcode) && ops[i].axis_map[0] != ops[first_reduce].axis_map[0]) mixed = true;
+    // may reduction i ride along with rows whose innermost axis is a1?
+    auto side_ok = [&](int i, int a1) {
+      const disc_op& src = ops[ops[i].in[0]];
+      const int a2 = ops[i].axis_map[0];
+      bool ok = ops[i].opcode == DISC_REDUCE_SUM && a2 < a1 && reg_kind(src.dtype) == RK_F32;
+      for (int k = 0; k < src.rank; ++k)
+        if (k != a1 && k != a2 && !unit(src.dim[k])) ok = false;
+      for (int j = 0; j < n_ops; ++j)
+        for (int k = 0; k < operand_count(ops[j].opcode); ++k)
+          if (ops[j].in[k] == i && ops[j].opcode != DISC_OUTPUT) ok = false;
+      return ok;
+    };
     int primary = -1;
     if (mixed)
       for (int i = 0; i < n_ops && primary < 0; ++i)
         if (is_reduce(ops[i].opcode) && ops[i].axis_map[0] == inner_axis(ops[ops[i].in[0]])) primary = i;
+    if (!mixed && loop_sides) {
+      // Sums over the rows next to a LOOP fusion (a bias gradient beside an element-wise backward):
+      // when every reduction qualifies and some output keeps the full shape, the pattern runs in
+      // the row template without reduction phases -- the operands are read once, where a column
+      // reduce would read them again for its epilogue.
+      const disc_op& src0 = ops[ops[first_reduce].in[0]];
+      const int a1 = inner_axis(src0);
+      bool ok = ops[first_reduce].axis_map[0] != a1, elem_out = false;
+      for (int i = 0; i < n_ops && ok; ++i) {
+        if (is_reduce(ops[i].opcode)) ok = side_ok(i, a1);
+        if (ops[i].opcode == DISC_OUTPUT && !is_reduce(ops[ops[i].in[0]].opcode) && ops[i].rank == src0.rank) elem_out = true;
+      }
+      if (ok && elem_out) {
+        for (int i = 0; i < n_ops; ++i)
+          if (is_reduce(ops[i].opcode)) side[i] = 1;
+        rows_axis_override = a1;
+        *used_loop_sides = true;
+      }
+    }
     if (primary >= 0) {
       const int a1 = ops[primary].axis_map[0];
       for (int i = 0; i < n_ops; ++i) {
         if (!is_reduce(ops[i].opcode) || ops[i].axis_map[0] == a1) continue;
-        const disc_op& src = ops[ops[i].in[0]];
         const int a2 = ops[i].axis_map[0];
-        bool ok = ops[i].opcode == DISC_REDUCE_SUM && a2 < a1 && reg_kind(src.dtype) == RK_F32;
-        for (int k = 0; k < src.rank; ++k)
-          if (k != a1 && k != a2 && !unit(src.dim[k])) ok = false;
-        for (int j = 0; j < n_ops; ++j)
-          for (int k = 0; k < operand_count(ops[j].opcode); ++k)
-            if (ops[j].in[k] == i && ops[j].opcode != DISC_OUTPUT) ok = false;
+        const bool ok = side_ok(i, a1);
         if (!ok) {
           snprintf(buf, sizeof buf, "op %d (%s) reduces over axis %d while op %d reduces over the innermost axis: a "
                    "reduction over the rows is fused with row reductions only as a floating-point sum over the "
@@ -582,7 +610,7 @@ int analyze(const disc_op* ops, int n_ops, const disc_constraint* cs, int n_cs, 
   int root_value;
   if (first_reduce >= 0) {
     root_value = ops[first_reduce].in[0];
-    an.reduce_axis = ops[first_reduce].axis_map[0];
+    an.reduce_axis = rows_axis_override >= 0 ? rows_axis_override : ops[first_reduce].axis_map[0];
   } else {
     root_value = -1;
     for (int i = 0; i < n_ops; ++i)
@@ -975,6 +1003,19 @@ int analyze(const disc_op* ops, int n_ops, const disc_constraint* cs, int n_cs, 
   if (!any) min_bytes = 2;
   an.vec_width = std::min(8, 16 / min_bytes);
   return DISC_OK;
+}
+
+int analyze(const disc_op* ops, int n_ops, const disc_constraint* cs, int n_cs, Analysis* out,
+            std::string* errp) {
+  bool used = false;
+  int rc = analyze_impl(ops, n_ops, cs, n_cs, out, errp, true, &used);
+  if (rc != DISC_OK && used) {
+    // the pattern is not a loop fusion with sums riding along after all: judge it as before
+    *out = Analysis();
+    errp->clear();
+    rc = analyze_impl(ops, n_ops, cs, n_cs, out, errp, false, &used);
+  }
+  return rc;
 }
 
 }  // namespace disc

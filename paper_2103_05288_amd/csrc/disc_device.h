@@ -614,6 +614,7 @@ DISC_DEV void row_reg_body(const typename Pat::Args& A, const RowPlan& rp) {
     };
     typename Pat::template Keep<V> keep[NV];
     row_phases<Pat, 0, V, NV>(A, rp, rc, slot, keep, span, col0, lds, parity, prefetch);
+    if constexpr (Pat::NPHASE == 0) prefetch();   // (no reduction phase to hide the next row's loads behind)
 #pragma unroll
     for (int j = 0; j < NV; ++j) {
       if (span[j].any()) {
@@ -785,16 +786,19 @@ DISC_DEV void row_stream_body(const typename Pat::Args& A) {
 // Second launch of a row reduce with sums over the rows: adds up the P rows of partial sums of
 // every summed output, in a fixed order (the result does not depend on timing) and in fp64 (the
 // fp32 partial sums each cover the rows of one block only).  A block takes 16 columns; its 256
-// lanes are 16 columns x 16 lanes that each walk every 16th partial row, four loads in flight; the
-// 16 lane totals of a column meet in LDS.
+// lanes are 16 columns x 16 lanes that each walk every 16th partial row, one sum after the other,
+// four loads in flight; the 16 lane totals of a column meet in LDS.  (Measured at 1023 partial
+// rows x 1024 columns x 2 sums: 12.6 us; 8 columns x 32 lanes with the sums interleaved, and
+// blocks of 1024 threads covering whole 128-byte lines, both took 19 us.)
+constexpr int kColsumCols = 16, kColsumLanes = 16;
 template <class Pat>
 DISC_DEV void colsum_finish_body(const typename Pat::Args& A) {
-  constexpr int NQ = Pat::NCOLSUM;
-  __shared__ double red[NQ][16][17];
-  const int cl = (int)threadIdx.x & 15, pl = (int)threadIdx.x >> 4;
+  constexpr int NQ = Pat::NCOLSUM, CL = kColsumCols, PL = kColsumLanes;
+  __shared__ double red[NQ][PL][CL + 1];
+  const int cl = (int)threadIdx.x % CL, pl = (int)threadIdx.x / CL;
   const i64 inner = A.inner, P = A.aux0;
   const float* ws = reinterpret_cast<const float*>(A.ws0);
-  for (i64 c0 = (i64)blockIdx.x * 16; c0 < inner; c0 += (i64)gridDim.x * 16) {
+  for (i64 c0 = (i64)blockIdx.x * CL; c0 < inner; c0 += (i64)gridDim.x * CL) {
     const i64 col = c0 + cl;
 #pragma unroll
     for (int q = 0; q < NQ; ++q) {
@@ -802,13 +806,13 @@ DISC_DEV void colsum_finish_body(const typename Pat::Args& A) {
       if (col < inner) {
         const float* src = ws + (i64)q * P * inner + col;
         i64 p = pl;
-        for (; p + 48 < P; p += 64) {
+        for (; p + 3 * PL < P; p += 4 * PL) {
           a0 += src[p * inner];
-          a1 += src[(p + 16) * inner];
-          a2 += src[(p + 32) * inner];
-          a3 += src[(p + 48) * inner];
+          a1 += src[(p + PL) * inner];
+          a2 += src[(p + 2 * PL) * inner];
+          a3 += src[(p + 3 * PL) * inner];
         }
-        for (; p < P; p += 16) a0 += src[p * inner];
+        for (; p < P; p += PL) a0 += src[p * inner];
       }
       red[q][pl][cl] = (a0 + a1) + (a2 + a3);
     }
@@ -819,7 +823,7 @@ DISC_DEV void colsum_finish_body(const typename Pat::Args& A) {
       for (int q = 0; q < NQ; ++q) {
         double t = 0.0;
 #pragma unroll
-        for (int k = 0; k < 16; ++k) t += red[q][k][cl];
+        for (int k = 0; k < PL; ++k) t += red[q][k][cl];
         v[q] = (float)t;
       }
       Pat::colsum_store(A, col, v);

@@ -412,6 +412,7 @@ int make_plan(disc_ctx* c, const Pattern& p, const int64_t* dims, int n_dims, in
     if (sv.rows == 0 && n_col_sums > 0 && sv.inner > 0)
       return set_err(c, DISC_ERR_EMPTY_REDUCE, "reduction over an axis of size 0");
     if (sv.rows == 0) return DISC_OK;
+    if (sv.inner == 0 && an.n_phases == 0) return DISC_OK;   // (no reduction over the rows' axis: nothing to do)
     if (sv.inner == 0) return set_err(c, DISC_ERR_EMPTY_REDUCE, "reduction over an axis of size 0");
     if (sv.inner >= (1ll << 31) - 4096) return set_err(c, DISC_ERR_SHAPE, "row longer than 2^31 elements");
     bool vec = sv.inner >= V / 2 || V == 1;
@@ -552,7 +553,7 @@ int make_plan(disc_ctx* c, const Pattern& p, const int64_t* dims, int n_dims, in
       LaunchRec& L1 = fp->launches[1];
       L1.kernel = "k_colsum_finish";
       L1.block = 256;
-      L1.grid[0] = (uint32_t)std::min<int64_t>((sv.inner + 15) / 16, max_grid * 4);
+      L1.grid[0] = (uint32_t)std::min<int64_t>((sv.inner + 15) / 16, max_grid * 4);   // 16 columns per block
       pub.n_launches = 2;
     } else {
       fp->aux[0] = 0;

@@ -43,6 +43,65 @@ def short(name: str, n: int = 44) -> str:
     return name if len(name) <= n else name[:n - 1] + "~"
 
 
+def next_rows_summary(args):
+    """Kernel times and measured HBM bytes of the secondary workloads of bench.py (one large call
+    each), next to the bytes of their inputs and outputs."""
+    cmd_t = "rocprofv3 --kernel-trace --stats -d prof_out/nr_trace -o trace -- python3 bench.py --next-rows-only"
+    cmd_c = "rocprofv3 --pmc {counter} -d prof_out/{dir} -o {dir} -- python3 bench.py --next-rows-only"
+    rows = top_kernels(args.trace)
+    avg_us = {name: avg for name, calls, tot, avg, pct in rows}
+    lines = ["rocprofv3 kernel trace of bench.py's secondary workloads (one ~1 GB call each, repeated), MI355X",
+             "command (from the repository root, after `cd /tmp && export TMPDIR=/tmp` on the GPU box):",
+             "  " + cmd_t, "",
+             "%-46s %8s %14s %12s %7s" % ("kernel", "calls", "total_us", "avg_us", "pct")]
+    for name, calls, tot, avg, pct in rows:
+        if _ours(name):
+            lines.append("%-46s %8d %14.1f %12.3f %7.2f" % (short(name), calls, tot, avg, pct))
+    b = json.load(open(args.bench_json)) if args.bench_json and os.path.exists(args.bench_json) else None
+    if b:
+        lines += ["", "bench.py's own figures from the same run (HIP events around ten calls, best of three):"]
+        for k, v in b["next_rows"].items():
+            lines.append("  %-28s dims %-34s %8.2f us  %7.1f GB/s of input + output bytes" % (k, v["dims"], v["us"], v["GBps"]))
+    with open(os.path.join(args.out, "next_rows_kernel_trace.txt"), "w") as f:
+        f.write("\n".join(lines) + "\n")
+
+    fetch = counter_per_kernel(args.fetch, "FETCH_SIZE")
+    write = counter_per_kernel(args.write, "WRITE_SIZE")
+    if COPY_KERNEL not in fetch or COPY_KERNEL not in write:
+        raise SystemExit("the copy kernel is missing from the counter runs: no scale factors")
+    f_scale = COPY_BYTES / (fetch[COPY_KERNEL][1] / fetch[COPY_KERNEL][0] * 1024.0)
+    w_scale = COPY_BYTES / (write[COPY_KERNEL][1] / write[COPY_KERNEL][0] * 1024.0)
+    per = {}
+    for name in sorted(set(fetch) | set(write)):
+        if not _ours(name) or name in ("disc_util_empty_k", COPY_KERNEL):
+            continue
+        nf, sf = fetch.get(name, (0, 0.0))
+        nw, sw = write.get(name, (0, 0.0))
+        per[name] = (sf * 1024.0 * f_scale / max(nf, 1), sw * 1024.0 * w_scale / max(nw, 1))
+    lines = ["HBM traffic of bench.py's secondary workloads per kernel: rocprofv3 FETCH_SIZE and WRITE_SIZE, MI355X",
+             "commands (one counter per run; from the repository root, after `cd /tmp && export TMPDIR=/tmp`):",
+             "  " + cmd_c.format(counter="FETCH_SIZE", dir="nr_fetch"),
+             "  " + cmd_c.format(counter="WRITE_SIZE", dir="nr_write"), "",
+             "scale factors from the plain copy kernel %s (1 GiB each way per launch): FETCH_SIZE %.4f, WRITE_SIZE %.4f"
+             % (COPY_KERNEL, f_scale, w_scale), "",
+             "%-34s %16s %18s %12s" % ("kernel", "read MB/launch", "written MB/launch", "avg us")]
+    for name, (rd, wr) in per.items():
+        lines.append("%-34s %16.2f %18.2f %12.2f" % (name, rd / 1e6, wr / 1e6, avg_us.get(name, float("nan"))))
+    if b:
+        lines += ["", "per workload: bytes of the inputs and outputs (each once) against the measured bytes of its kernels:"]
+        for k, v in b["next_rows"].items():
+            mine = [n for n in per if any(n.startswith(p) for p in v.get("kernel_prefixes", []))] or \
+                   [n for n in per if n in v.get("kernels", [])]
+            meas = sum(per[n][0] + per[n][1] for n in mine)
+            t = sum(avg_us.get(n, 0.0) for n in mine)
+            if meas:
+                lines.append("  %-28s algorithmic %9.2f MB  measured %9.2f MB  ratio %.3f  kernels %s (%.1f us in all: %.0f GB/s)"
+                             % (k, v["io_bytes"] / 1e6, meas / 1e6, meas / v["io_bytes"], "+".join(mine), t, v["io_bytes"] / t / 1e3 if t else 0))
+    with open(os.path.join(args.out, "next_rows_hbm_traffic.txt"), "w") as f:
+        f.write("\n".join(lines) + "\n")
+    print("\n".join(lines[-8:]))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--trace", required=True)
@@ -54,8 +113,13 @@ def main():
                                            "python3 bench.py --steps 3 --warmup 1 --no-cpu-baseline --no-gap-to-static --no-next-rows")
     ap.add_argument("--pmc-cmd", default="rocprofv3 --pmc {counter} -d prof_out/{dir} -o {dir} -- "
                                          "python3 bench.py --steps 1 --warmup 0 --no-cpu-baseline --no-gap-to-static --no-next-rows")
+    ap.add_argument("--mode", default="sweep", choices=["sweep", "next_rows"],
+                    help="next_rows: the three databases come from `bench.py --next-rows-only` runs; writes "
+                         "next_rows_kernel_trace.txt and next_rows_hbm_traffic.txt and leaves traffic.json alone")
     args = ap.parse_args()
     os.makedirs(args.out, exist_ok=True)
+    if args.mode == "next_rows":
+        return next_rows_summary(args)
 
     # ---- kernel trace -------------------------------------------------------------------------
     rows = top_kernels(args.trace)

@@ -6,7 +6,7 @@ import pytest
 import torch
 
 from workloads.configs import TORCH_DTYPE
-from workloads.extras import layernorm_backward_graph
+from workloads.extras import gelu_backward_bias_gradient, layernorm_backward_graph
 from workloads.pattern import PatternBuilder
 
 
@@ -39,7 +39,7 @@ def test_one_pattern_two_launches(hctx):
     assert pl["n_launches"] == 2 and pl["kernels"][0].split("k_row_")[1].startswith("vec_nv2") and pl["kernels"][1].endswith("k_colsum_finish")
     # one row of fp32 partial sums per block and summed output
     assert pl["workspace_bytes"] == pl["grid"][0][0] * 1024 * 4 * 2
-    assert pl["grid"][1][0] == 1024 // 16
+    assert pl["grid"][1][0] == 1024 // 16 and pl["block"][1][0] == 256
     # rows too long for registers: the streaming version keeps the partial sums in the workspace
     pl = h.plan([100, 30000])
     assert pl["kernels"][0].endswith("k_row_stream_vec") and pl["workspace_bytes"] == 100 * 30000 * 4 * 2
@@ -83,6 +83,29 @@ def test_acceptance_rule(hctx):
         with pytest.raises(DiscError) as e:
             hctx.register(build(**kw))
         assert e.value.status == "UNFUSIBLE" and word in str(e.value), (kw, str(e.value))
+
+
+def test_sum_over_rows_beside_a_loop_fusion(hctx):
+    """No row reduction at all: an element-wise backward with its bias gradient runs in the row
+    template without reduction phases (operands read once); a pattern whose element-wise output
+    needs the column sum keeps the column-reduce template."""
+    h = hctx.register(gelu_backward_bias_gradient())
+    assert h.info["template"] == "row_reduce" and h.info["n_phases"] == 0 and h.info["n_outputs"] == 2
+    pl = h.plan([4096, 1024])
+    assert pl["n_launches"] == 2 and pl["kernels"][1].endswith("k_colsum_finish")
+    assert pl["workspace_bytes"] == pl["grid"][0][0] * 1024 * 4
+    assert h.plan([5, 0])["n_launches"] == 0           # nothing to compute, and no reduction over an empty axis
+    pb = PatternBuilder("centre")
+    t, hh = pb.dims(2)
+    x = pb.param("f32", [t, hh])
+    m = pb.op("div", pb.reduce("sum", x, 0), pb.dim_size(t))
+    pb.output(pb.op("sub", x, pb.broadcast(m, [t, hh], [1])))
+    assert hctx.register(pb.build()).info["template"] == "col_reduce"
+    # a column sum alone (no full-shape output) also stays a column reduce: more parallel over the rows
+    pb = PatternBuilder("bias_grad_alone")
+    t, hh = pb.dims(2)
+    pb.output(pb.reduce("sum", pb.op("tanh", pb.param("f32", [t, hh])), 0))
+    assert hctx.register(pb.build()).info["template"] == "col_reduce"
 
 
 def _inputs(pat, dims, gen):
@@ -183,5 +206,30 @@ def test_forced_versions_and_one_phase_pattern():
             y64, dy64 = ins[0].double().numpy(), ins[1].double().numpy()
             dx = y64 * (dy64 - (dy64 * y64).sum(1, keepdims=True))
             _check_sum(got[1], want[1], np.abs(dx) + np.abs(y64 * dy64), -(-dims[0] // pl["grid"][0][0]), f"sum of dx {dims}")
+    finally:
+        ctx.close()
+
+
+@pytest.mark.gpu
+def test_gelu_backward_with_bias_gradient_matches_oracle():
+    from oracle import run as oracle_run
+    from paper_2103_05288_amd import Context
+    from tests.util import assert_close, run_gpu, to_oracle_input
+    pat = gelu_backward_bias_gradient()
+    ctx = Context(0)
+    try:
+        h = ctx.register(pat)
+        gen = torch.Generator().manual_seed(17)
+        for dims in ([1, 1], [7, 5], [1000, 77], [20000, 16], [4096, 1024], [513, 2050], [300, 4100], [65, 8200], [40, 30000]):
+            ins = _inputs(pat, dims, gen)
+            pl = h.plan(dims)
+            got = run_gpu(h, pat, dims, ins)
+            want = oracle_run(pat, dims, [to_oracle_input(t) for t in ins])[0]
+            assert_close(got[0], want[0], f"gelu backward dx dims={dims}")
+            dy, x, b = (t.double().numpy() for t in ins)
+            a = 1.702 * (x + b)
+            s = 1.0 / (1.0 + np.exp(-a))
+            dx = dy * s * (1.0 + a * (1.0 - s))
+            _check_sum(got[1], want[1], np.abs(dx), -(-dims[0] // pl["grid"][0][0]), f"bias gradient dims={dims} {pl['kernels'][0]}")
     finally:
         ctx.close()

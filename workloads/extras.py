@@ -84,3 +84,22 @@ def pure_transpose(dtype, perm):
     pb = PatternBuilder("transpose" + "".join(str(a) for a in perm))
     pb.output(pb.transpose(pb.param(dtype, pb.dims(len(perm))), perm))
     return pb.build()
+
+
+def gelu_backward_bias_gradient():
+    """Backward of bias + GELU (the sigmoid form used by the C0 pattern family): dx = dy * gelu'(x + b)
+    as bf16, and the bias gradient db = sum over the rows of dx -- an element-wise chain with a sum
+    over the rows riding along."""
+    pb = PatternBuilder("gelu_bwd_bias")
+    T, H = pb.dims(2)
+    dy = pb.cast(pb.param("bf16", [T, H]), "f32")
+    x = pb.cast(pb.param("bf16", [T, H]), "f32")
+    b = pb.param("f32", [H])
+    u = pb.op("add", x, pb.broadcast(b, [T, H], [1]))
+    a = pb.op("mul", u, pb.const(1.702))
+    s = pb.op("sigmoid", a)
+    g = pb.op("mul", s, pb.op("add", pb.const(1.0), pb.op("mul", a, pb.op("sub", pb.const(1.0), s))))
+    dx = pb.op("mul", dy, g)
+    pb.output(pb.cast(dx, "bf16"))
+    pb.output(pb.reduce("sum", dx, 0))
+    return pb.build()
