@@ -2,7 +2,9 @@
 with row vectors, per-row operands, scalars, masks, windows (dynamic slices) of larger inputs,
 padded smaller inputs and mixed storage types; no reduction (loop
 fusion), one or two dependent row reductions with an epilogue, or a column reduction with an
-epilogue.  Every pattern is compiled once and launched at several shapes (ragged and aligned).
+epilogue; half of the rank-2 loop and row patterns also emit a sum over the rows, which rides
+along in the row kernels.  Every pattern is compiled once and launched at several shapes (ragged
+and aligned).
 
 The generator keeps the arithmetic well conditioned, so the element-wise parity bar applies:
 reduced terms are non-negative (sums) or the reduction is exact (max / min), values stay O(1), and
@@ -44,6 +46,9 @@ class Gen:
         self.inputs = []          # (kind, dtype, dims)
         self.extra = []           # windows / pads: the symbolic dims that need runtime values of their own
         self.kind = ["loop", "row", "row2", "col"][int(self.rng.integers(0, 4))]
+        # a sum over the rows beside the loop fusion / the row reductions (drawn from a generator of
+        # its own, so that the rest of the pattern does not depend on it)
+        self.side_sum = self.rank == 2 and self.kind != "col" and np.random.default_rng(5000 + seed).random() < 0.7
 
     def pick(self, seq):
         return seq[int(self.rng.integers(0, len(seq)))]
@@ -122,6 +127,8 @@ class Gen:
             pb.output(pb.cast(v, self.pick(FLOATS)))
             if self.rng.random() < 0.4:
                 pb.output(pb.op("gt", v, pb.const(0.25), dims=full))
+            if self.side_sum:
+                pb.output(pb.reduce("sum", pb.op("sigmoid", v), 0))
         elif self.kind in ("row", "row2"):
             axis = rank - 1
             back = list(range(rank - 1))
@@ -137,6 +144,8 @@ class Gen:
             pb.output(pb.cast(y, self.pick(FLOATS)))
             if self.rng.random() < 0.5:
                 pb.output(s)
+            if self.side_sum:
+                pb.output(pb.reduce("sum", pb.op("sigmoid", y), 0))      # non-negative terms
         else:
             axis = rank - 2
             keep = [k for k in range(rank) if k != axis]
@@ -187,6 +196,8 @@ def shapes_for(gen, rng):
         res.append([t, h] if gen.rank == 2 else [int(rng.integers(1, 5)), t, h])
     if gen.kind == "col":                      # one tall shape: chunks of the reduced axis, three launches
         res.append([3000, 520] if gen.rank == 2 else [2, 2500, 130])
+    if gen.side_sum:                           # many rows per block, several blocks
+        res.append([2500, 130])
     return res
 
 
@@ -196,6 +207,8 @@ def test_random_pattern(ctx, seed):
     pat = gen.build()
     h = ctx.register(pat)
     want_tmpl = {"loop": "loop", "row": "row_reduce", "row2": "row_reduce", "col": "col_reduce"}[gen.kind]
+    if gen.side_sum:
+        want_tmpl = "row_reduce"               # also for a loop fusion: the row template without reduction phases
     assert h.info["template"] == want_tmpl, (seed, gen.kind, h.info["template"])
     rng = np.random.default_rng(1000 + seed)
     for base in shapes_for(gen, rng):
