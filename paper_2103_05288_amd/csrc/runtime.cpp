@@ -819,6 +819,17 @@ static std::string static_macros(const Pattern& p, const FullPlan& fp, const int
     const unsigned char* src = buf + f.offset;
     switch (f.kind) {
       case ArgField::IN_PTR: case ArgField::OUT_PTR: case ArgField::WS_PTR: break;
+      case ArgField::AUX:
+        // the number of partial-sum rows follows the grid, which is chosen again at every launch
+        // from the loaded kernel's residency: it stays a run-time argument
+        if (p.gen.n_col_sums > 0) break;
+        [[fallthrough]];
+      default: {
+        int64_t v;
+        memcpy(&v, src, 8);
+        a << " A." << n << " = " << v << "LL;";
+        break;
+      }
       case ArgField::SPR_DIV: case ArgField::GROUP_DIV: {
         uint32_t w[4];
         memcpy(w, src, 16);
@@ -830,11 +841,6 @@ static std::string static_macros(const Pattern& p, const FullPlan& fp, const int
         memcpy(&w, src, 4);
         a << " A." << n << " = __builtin_bit_cast(float, " << w << "u);";
         break;
-      }
-      default: {
-        int64_t v;
-        memcpy(&v, src, 8);
-        a << " A." << n << " = " << v << "LL;";
       }
     }
   }

@@ -233,3 +233,32 @@ def test_gelu_backward_with_bias_gradient_matches_oracle():
             _check_sum(got[1], want[1], np.abs(dx), -(-dims[0] // pl["grid"][0][0]), f"bias gradient dims={dims} {pl['kernels'][0]}")
     finally:
         ctx.close()
+
+
+@pytest.mark.gpu
+def test_single_shape_build_of_a_pattern_with_sums_over_rows():
+    """The shape-specialised build (every extent and plan member a constant, Section 5.3's static
+    counterpart) of LayerNorm backward: the number of partial-sum rows follows the grid of the
+    launch, not the one planned at registration."""
+    from oracle import run as oracle_run
+    from paper_2103_05288_amd import Context
+    from tests.util import assert_close, run_gpu, to_oracle_input
+    pat = layernorm_backward_graph()
+    ctx = Context(0)
+    try:
+        gen = torch.Generator().manual_seed(23)
+        for dims in ([20000, 768], [3000, 2050]):
+            ins = _inputs(pat, dims, gen)
+            hs = ctx.register_static(pat, dims)
+            pl = hs.plan(dims)
+            got = run_gpu(hs, pat, dims, ins)
+            want = oracle_run(pat, dims, [to_oracle_input(t) for t in ins])[0]
+            assert_close(got[0], want[0], f"static dx dims={dims}")
+            x64, dy64 = ins[0].double().numpy(), ins[1].double().numpy()
+            xc = x64 - x64.mean(1, keepdims=True)
+            xhat = xc / np.sqrt((xc * xc).mean(1, keepdims=True) + 1e-5)
+            rpb = -(-dims[0] // pl["grid"][0][0])
+            _check_sum(got[1], want[1], np.abs(dy64 * xhat), rpb, f"static dgamma dims={dims}")
+            _check_sum(got[2], want[2], np.abs(dy64), rpb, f"static dbeta dims={dims}")
+    finally:
+        ctx.close()
