@@ -834,19 +834,26 @@ DISC_DEV void colsum_finish_body(const typename Pat::Args& A) {
 
 // =======================================================================================
 // A transpose on its own (not a fusion): out[b][p][q] = in[b][q][p], any element type.  A block
-// moves 64 x 64 tiles through LDS so that both the reads (along p, the operand's innermost
-// axis) and the writes (along q) are contiguous; the padding of the LDS rows keeps the
-// column-wise reads off a single bank.
+// moves square tiles through LDS so that both the reads (along p, the operand's innermost axis)
+// and the writes (along q) are contiguous.  Every global access is 16 bytes wide (8 two-byte
+// elements), and a tile row is 256 bytes of the operand -- two whole cache lines per row on both
+// sides: 128 x 128 tiles for one- and two-byte elements, 64 x 64 for wider ones (with 64 x 64
+// tiles and one element per lane, two-byte elements moved 128 bytes per row and reached 2.5 TB/s
+// where four-byte elements reached 4.3).  A lane issues all its loads of a tile before the first
+// LDS write.  The LDS row pitch is an odd number of dwords, so the column-wise element reads of
+// the second half spread over the banks.
 // =======================================================================================
 template <class T>
 DISC_DEV void ktranspose_body(const T* __restrict__ in, T* __restrict__ out, i64 batch, i64 P, i64 Q) {
-  constexpr int TS = 64;
+  constexpr int VE = 16 / (int)sizeof(T);                    // elements per 16-byte access
+  constexpr int TS = sizeof(T) <= 2 ? 128 : 64;
   constexpr int PAD = sizeof(T) >= 4 ? 1 : 4 / (int)sizeof(T);
-  __shared__ T tile[TS][TS + PAD];
+  constexpr int VPR = TS / VE;                               // 16-byte pieces per tile row
+  constexpr int NVEC = TS * VPR / 256;                       // pieces per lane and tile
+  __shared__ __attribute__((aligned(16))) T tile[TS][TS + PAD];
   const i64 tiles_p = (P + TS - 1) / TS, tiles_q = (Q + TS - 1) / TS;
   const i64 per_batch = tiles_p * tiles_q;
   const i64 ntiles = batch * per_batch;
-  const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;     // 256 threads: 64 x 4
   for (i64 t = blockIdx.x; t < ntiles; t += gridDim.x) {
     const i64 b = t / per_batch;
     const i64 r = t - b * per_batch;
@@ -858,16 +865,49 @@ DISC_DEV void ktranspose_body(const T* __restrict__ in, T* __restrict__ out, i64
     const i64 p0 = tp * TS, q0 = tq * TS;
     const T* src = in + b * P * Q;
     T* dst = out + b * P * Q;
-#pragma unroll 4
-    for (int i = ty; i < TS; i += 4) {            // row q0 + i of the operand, elements p0 .. p0 + 63
-      const i64 q = q0 + i, p = p0 + tx;
-      if (q < Q && p < P) tile[i][tx] = src[q * P + p];
+    Vec<T, VE> piece[NVEC];
+#pragma unroll
+    for (int k = 0; k < NVEC; ++k) {              // row q0 + row of the operand, elements p0 + v * VE ...
+      const int idx = (int)threadIdx.x + k * 256;
+      const int row = idx / VPR, v = idx % VPR;
+      const i64 q = q0 + row, p = p0 + v * VE;
+      piece[k].clear();
+      if (q < Q) {
+        if (p + VE <= P) {
+          piece[k].v = *reinterpret_cast<const typename Vec<T, VE>::unaligned_t*>(src + q * P + p);
+        } else {
+#pragma unroll
+          for (int e = 0; e < VE; ++e)
+            if (p + e < P) piece[k].set(e, src[q * P + p + e]);
+        }
+      }
+    }
+#pragma unroll
+    for (int k = 0; k < NVEC; ++k) {
+      const int idx = (int)threadIdx.x + k * 256;
+      const int row = idx / VPR, v = idx % VPR;
+#pragma unroll
+      for (int e = 0; e < VE; ++e) tile[row][v * VE + e] = piece[k].get(e);
     }
     __syncthreads();
-#pragma unroll 4
-    for (int i = ty; i < TS; i += 4) {            // row p0 + i of the result, elements q0 .. q0 + 63
-      const i64 p = p0 + i, q = q0 + tx;
-      if (p < P && q < Q) dst[p * Q + q] = tile[tx][i];
+#pragma unroll
+    for (int k = 0; k < NVEC; ++k) {              // row p0 + row of the result, elements q0 + v * VE ...
+      const int idx = (int)threadIdx.x + k * 256;
+      const int row = idx / VPR, v = idx % VPR;
+      const i64 p = p0 + row, q = q0 + v * VE;
+      Vec<T, VE> o;
+      o.clear();
+#pragma unroll
+      for (int e = 0; e < VE; ++e) o.set(e, tile[v * VE + e][row]);
+      if (p < P) {
+        if (q + VE <= Q) {
+          *reinterpret_cast<typename Vec<T, VE>::unaligned_t*>(dst + p * Q + q) = o.v;
+        } else {
+#pragma unroll
+          for (int e = 0; e < VE; ++e)
+            if (q + e < Q) dst[p * Q + q + e] = o.get(e);
+        }
+      }
     }
     __syncthreads();
   }

@@ -383,7 +383,9 @@ int make_plan(disc_ctx* c, const Pattern& p, const int64_t* dims, int n_dims, in
       return set_err(c, DISC_ERR_INVALID_ARG, "forced version does not belong to a transpose pattern");
     const int ng = (int)an.groups.size();
     const int64_t P = sv.group[ng - 2], Q = sv.group[ng - 1], batch = ng == 3 ? sv.group[0] : 1;
-    const int64_t ntiles = batch * ((P + 63) / 64) * ((Q + 63) / 64);
+    // tiles of 256 bytes per row: 128 x 128 elements of one or two bytes, 64 x 64 wider ones
+    const int64_t ts = dtype_bytes(an.accesses[0].dtype) <= 2 ? 128 : 64;
+    const int64_t ntiles = batch * ((P + ts - 1) / ts) * ((Q + ts - 1) / ts);
     LaunchRec& L = fp->launches[0];
     L.kernel = "k_transpose_tile";
     L.block = 256;
