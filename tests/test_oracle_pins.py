@@ -536,3 +536,37 @@ def test_transpose_matches_index_loops():
     xa = rng.normal(size=(2, 3, 4))
     out = run(pb.build(), [2, 3, 4], [xa])[0][0]
     assert np.array_equal(np.transpose(-out, (1, 2, 0)), xa)
+
+
+def test_backward_workloads_equal_autograd():
+    """The two backward workloads of workloads/extras.py, run by the oracle over their op lists,
+    against reverse-mode differentiation of the forward functions in fp64 (torch.autograd): pins
+    the op lists themselves (a dropped term or a swapped operand in the hand-written gradient
+    formulas fails here) and the oracle's handling of row and column reductions in one list."""
+    from workloads.extras import gelu_backward_bias_gradient, layernorm_backward_graph
+    g = torch.Generator().manual_seed(31)
+    T, H = 9, 13
+    # inputs that are exact in their storage types, so the oracle and autograd see the same values
+    x = torch.randn(T, H, generator=g).bfloat16().double()
+    dy = torch.randn(T, H, generator=g).bfloat16().double()
+    gam = torch.randn(H, generator=g).float().double()
+
+    xr = x.clone().requires_grad_(True)
+    gr = gam.clone().requires_grad_(True)
+    beta = torch.zeros(H, dtype=torch.float64, requires_grad=True)
+    y = torch.nn.functional.layer_norm(xr, (H,), gr, beta, eps=1e-5)
+    y.backward(dy)
+    out = run(layernorm_backward_graph(), [T, H], [x.numpy(), dy.numpy(), gam.numpy()])[0]
+    # dx is stored as bf16 (8 significant bits); dgamma and dbeta are fp32 sums
+    np.testing.assert_allclose(np.asarray(out[0], dtype=np.float64), xr.grad.numpy(), rtol=2.0 ** -8, atol=1e-6)
+    np.testing.assert_allclose(np.asarray(out[1], dtype=np.float64), gr.grad.numpy(), rtol=1e-6, atol=1e-6)
+    np.testing.assert_allclose(np.asarray(out[2], dtype=np.float64), beta.grad.numpy(), rtol=1e-6, atol=1e-6)
+
+    b = torch.randn(H, generator=g).float().double()
+    xr = x.clone().requires_grad_(True)
+    br = b.clone().requires_grad_(True)
+    u = xr + br
+    (u * torch.sigmoid(1.702 * u)).backward(dy)
+    out = run(gelu_backward_bias_gradient(), [T, H], [dy.numpy(), x.numpy(), b.numpy()])[0]
+    np.testing.assert_allclose(np.asarray(out[0], dtype=np.float64), xr.grad.numpy(), rtol=2.0 ** -8, atol=1e-6)
+    np.testing.assert_allclose(np.asarray(out[1], dtype=np.float64), br.grad.numpy(), rtol=1e-6, atol=1e-6)
