@@ -305,7 +305,8 @@ static int analyze_impl(const disc_op* ops, int n_ops, const disc_constraint* cs
       ++n_out;
       if (op.dtype != ops[op.in[0]].dtype) return bad("OUTPUT dtype differs from its value");
       if (op.rank != ops[op.in[0]].rank) return bad("OUTPUT rank differs from its value");
-      if (op.rank == 0) return bad("rank-0 outputs are not supported");
+      if (op.rank == 0 && !is_reduce(ops[op.in[0]].opcode))
+        return bad("rank-0 outputs are supported only for reductions of per-row values over the rows");
     }
     if (is_unary(oc) && oc != DISC_NEG && oc != DISC_ABS && !is_float_dtype(op.dtype))
       return bad("transcendental op needs a float dtype");
@@ -565,10 +566,40 @@ static int analyze_impl(const disc_op* ops, int n_ops, const disc_constraint* cs
           if (ops[j].in[k] == i && ops[j].opcode != DISC_OUTPUT) ok = false;
       return ok;
     };
+    auto non_unit = [&](const disc_op& t) {
+      int n = 0;
+      for (int k = 0; k < t.rank; ++k) n += unit(t.dim[k]) ? 0 : 1;
+      return n;
+    };
     int primary = -1;
     if (mixed)
       for (int i = 0; i < n_ops && primary < 0; ++i)
-        if (is_reduce(ops[i].opcode) && ops[i].axis_map[0] == inner_axis(ops[ops[i].in[0]])) primary = i;
+        if (is_reduce(ops[i].opcode) && non_unit(ops[ops[i].in[0]]) >= 2 &&
+            ops[i].axis_map[0] == inner_axis(ops[ops[i].in[0]])) primary = i;
+    // A reduction of PER-ROW values over the rows, down to one number (the sum of per-row losses,
+    // the maximum of per-row maxima): rides along too, one partial result per block.  The source
+    // has the rows' axis alone; sum, maximum or minimum of float values; result to outputs only.
+    auto scalar_side_ok = [&](int i, int primary_op) {
+      const disc_op& src = ops[ops[i].in[0]];
+      const disc_op& root = ops[ops[primary_op].in[0]];
+      const int a1 = ops[primary_op].axis_map[0];
+      if (non_unit(src) != 1 || non_unit(ops[i]) != 0 || non_unit(root) != 2) return false;
+      if (ops[i].opcode != DISC_REDUCE_SUM && ops[i].opcode != DISC_REDUCE_MAX && ops[i].opcode != DISC_REDUCE_MIN) return false;
+      if (reg_kind(src.dtype) != RK_F32) return false;
+      int rows_class = -1, inner_class = dc.find(dc.atom(root.dim[a1])), src_class = -1;
+      for (int k = 0; k < root.rank; ++k)
+        if (k != a1 && !unit(root.dim[k])) rows_class = dc.find(dc.atom(root.dim[k]));
+      for (int k = 0; k < src.rank; ++k)
+        if (!unit(src.dim[k])) {
+          src_class = dc.find(dc.atom(src.dim[k]));
+          if (ops[i].axis_map[0] != k) return false;       // it must be the rows' axis that is reduced
+        }
+      if (src_class != rows_class || src_class == inner_class) return false;
+      for (int j = 0; j < n_ops; ++j)
+        for (int k = 0; k < operand_count(ops[j].opcode); ++k)
+          if (ops[j].in[k] == i && ops[j].opcode != DISC_OUTPUT) return false;
+      return true;
+    };
     if (!mixed && loop_sides) {
       // Sums over the rows next to a LOOP fusion (a bias gradient beside an element-wise backward):
       // when every reduction qualifies and some output keeps the full shape, the pattern runs in
@@ -591,7 +622,9 @@ static int analyze_impl(const disc_op* ops, int n_ops, const disc_constraint* cs
     if (primary >= 0) {
       const int a1 = ops[primary].axis_map[0];
       for (int i = 0; i < n_ops; ++i) {
-        if (!is_reduce(ops[i].opcode) || ops[i].axis_map[0] == a1) continue;
+        if (!is_reduce(ops[i].opcode) || i == primary) continue;
+        if (non_unit(ops[ops[i].in[0]]) == 1 && scalar_side_ok(i, primary)) { side[i] = 2; continue; }
+        if (ops[i].axis_map[0] == a1) continue;
         const int a2 = ops[i].axis_map[0];
         const bool ok = side_ok(i, a1);
         if (!ok) {
@@ -607,6 +640,13 @@ static int analyze_impl(const disc_op* ops, int n_ops, const disc_constraint* cs
       first_reduce = primary;
     }
   }
+  for (int i = 0; i < n_ops; ++i)
+    if (ops[i].opcode == DISC_OUTPUT && ops[i].rank == 0 && side[ops[i].in[0]] != 2) {
+      snprintf(buf, sizeof buf, "op %d (output): a rank-0 result is fused only as a sum, maximum or minimum of "
+               "per-row float values over the rows of a two-dimensional row-reduce pattern", i);
+      err = buf;
+      return DISC_ERR_UNFUSIBLE;
+    }
   int root_value;
   if (first_reduce >= 0) {
     root_value = ops[first_reduce].in[0];
@@ -623,7 +663,7 @@ static int analyze_impl(const disc_op* ops, int n_ops, const disc_constraint* cs
   Builder b(an, err);
   // every reduction must run over the same axis of the same iteration space
   for (int i = 0; i < n_ops; ++i) {
-    if (!is_reduce(ops[i].opcode)) continue;
+    if (!is_reduce(ops[i].opcode) || side[i] == 2) continue;
     const disc_op& src = ops[ops[i].in[0]];
     if (!b.shapes_match_root(src)) {
       snprintf(buf, sizeof buf, "op %d (%s) and op %d (%s): the reduced tensors cannot be proved to have "
@@ -649,7 +689,8 @@ static int analyze_impl(const disc_op* ops, int n_ops, const disc_constraint* cs
     if (op.rank > 0 && b.shapes_match_root(op)) { nat[i] = ident; has_nat[i] = 1; continue; }
     if (is_reduce(op.opcode)) {
       const int ax = side[i] ? op.axis_map[0] : an.reduce_axis;
-      for (int k = 0; k < an.root_rank; ++k) if (k != ax) nat[i].push_back(k);
+      if (side[i] != 2)
+        for (int k = 0; k < an.root_rank; ++k) if (k != ax) nat[i].push_back(k);
       has_nat[i] = 1;
     } else if (is_elementwise(op.opcode) || op.opcode == DISC_OUTPUT) {
       for (int k = 0; k < n_operands(op.opcode); ++k) {
@@ -718,7 +759,20 @@ static int analyze_impl(const disc_op* ops, int n_ops, const disc_constraint* cs
     }
     OutputRef o;
     Access a;
-    if (side[ops[i].in[0]]) {
+    if (side[ops[i].in[0]] == 2) {
+      // a reduction of per-row values over the rows: the node is the per-row value
+      const disc_op& src = ops[ops[ops[i].in[0]].in[0]];
+      int rows_axis = -1;
+      for (int k = 0; k < an.root_rank; ++k)
+        if (k != an.reduce_axis && !b.dim_is_one(an.root_dims[k])) rows_axis = k;
+      Ctx sc(src.rank, -1);
+      for (int k = 0; k < src.rank; ++k)
+        if (!b.dim_is_one(src.dim[k])) sc[k] = rows_axis;
+      o.row_red = a.row_red = true;
+      o.red_opcode = ops[ops[i].in[0]].opcode;
+      o.node = b.demand(ops[ops[i].in[0]].in[0], sc);
+      ++an.n_row_reds;
+    } else if (side[ops[i].in[0]]) {
       // a sum over the rows: the node is the value summed, seen over the whole iteration space
       o.col_sum = a.col_sum = true;
       o.node = b.demand(ops[ops[i].in[0]].in[0], ident);

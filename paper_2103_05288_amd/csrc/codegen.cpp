@@ -850,7 +850,7 @@ struct Gen {
     if (!col_tmpl()) {
       for (const auto& out : an.outputs) {
         const Access& a = an.accesses[out.access];
-        if (a.has_inner) continue;
+        if (a.has_inner || a.row_red) continue;
         const Node& n = an.nodes[out.node];
         std::string off = a.kind == ACC_PERROW ? "row" : a.kind == ACC_SCALAR ? "0" : fmt("rc.b%d", out.access);
         Fn fn2(*this, M_ELEM);
@@ -894,6 +894,42 @@ struct Gen {
       if (!out.col_sum) continue;
       const Access& a = an.accesses[out.access];
       os << "    A.o" << a.slot << "[col] = " << to_storage(fmt("v[%d]", q++), RK_F32, a.dtype) << ";\n";
+    }
+    os << "  }\n";
+  }
+
+  // ---- row reduce with reductions of per-row values over the rows (to one number each) ----------
+  // rr_identity / rr_merge: the reduction of output q; row_reds folds one finished row into a
+  // lane's running values; rowred_store rounds the results to the outputs' types.
+  void emit_row_reds() {
+    const int nq = an.n_row_reds;
+    os << "  static constexpr int NROWRED = " << nq << ";\n";
+    if (nq == 0) return;
+    std::vector<const OutputRef*> outs;
+    for (const auto& out : an.outputs) if (out.row_red) outs.push_back(&out);
+    os << "  static DISC_DEV float rr_identity(int q) {\n    switch (q) {\n";
+    for (int q = 0; q < nq; ++q)
+      os << "      case " << q << ": return " << (outs[q]->red_opcode == DISC_REDUCE_SUM ? "0.0f" : outs[q]->red_opcode == DISC_REDUCE_MAX ? "-__builtin_inff()" : "__builtin_inff()") << ";\n";
+    os << "    }\n    return 0.0f;\n  }\n";
+    for (const char* ty : {"float", "double"}) {
+      os << "  static DISC_DEV " << ty << " rr_merge(int q, " << ty << " a, " << ty << " b) {\n    switch (q) {\n";
+      for (int q = 0; q < nq; ++q) {
+        const int oc = outs[q]->red_opcode;
+        const std::string f = std::string(oc == DISC_REDUCE_MAX ? "fmax" : "fmin") + (ty[0] == 'f' ? "f" : "");
+        os << "      case " << q << ": return " << (oc == DISC_REDUCE_SUM ? std::string("a + b") : f + "(a, b)") << ";\n";
+      }
+      os << "    }\n    return a;\n  }\n";
+    }
+    os << "  static DISC_DEV void row_reds(const Args& A, const RowCtx& rc, float (&r)[" << nq << "]) {\n";
+    for (int q = 0; q < nq; ++q) {
+      const Node& n = an.nodes[outs[q]->node];
+      os << "    r[" << q << "] = rr_merge(" << q << ", r[" << q << "], " << convert(fmt("rc.r%d", outs[q]->node), n.rk, RK_F32) << ");\n";
+    }
+    os << "    (void)A;\n  }\n";
+    os << "  static DISC_DEV void rowred_store(const Args& A, const float (&v)[" << nq << "]) {\n";
+    for (int q = 0; q < nq; ++q) {
+      const Access& a = an.accesses[outs[q]->access];
+      os << "    A.o" << a.slot << "[0] = " << to_storage(fmt("v[%d]", q), RK_F32, a.dtype) << ";\n";
     }
     os << "  }\n";
   }
@@ -1016,6 +1052,7 @@ struct Gen {
       k("k_row_stream_vec", fmt("disc::row_stream_body<Pat, %d>(A);", V), nullptr);
       k("k_row_stream_scalar", "disc::row_stream_body<Pat, 1>(A);", nullptr);
       if (an.n_col_sums > 0) k("k_colsum_finish", "disc::colsum_finish_body<Pat>(A);", nullptr);
+      if (an.n_row_reds > 0) k("k_rowred_finish", "disc::rowred_finish_body<Pat>(A);", nullptr);
     } else {
       k("k_col_partial_vec", fmt("disc::col_partial_body<Pat, %d>(A, rp);", V), "ColPlan");
       k("k_col_partial_scalar", "disc::col_partial_body<Pat, 1>(A, rp);", "ColPlan");
@@ -1083,6 +1120,7 @@ struct Gen {
       }
       emit_epilogue(M_ELEM);
       emit_col_sums();
+      emit_row_reds();
       os << "};\n";
       if (staged_versions) os << "typedef PatT<false> Pat;\n";
     } else {
@@ -1127,6 +1165,7 @@ struct Gen {
     out->n_red_planes = col_tmpl() ? (int)an.reduces[0].size() : 0;
     out->has_epilogue = col_tmpl() ? has_elem_outputs() : true;
     out->n_col_sums = row_tmpl() ? an.n_col_sums : 0;
+    out->n_row_reds = row_tmpl() ? an.n_row_reds : 0;
     out->staged_elem_bytes.clear();
     for (int ai : staged_accesses()) out->staged_elem_bytes.push_back(dtype_bytes(an.accesses[ai].dtype));
     return DISC_OK;

@@ -549,6 +549,13 @@ DISC_DEV void row_reg_body(const typename Pat::Args& A, const RowPlan& rp) {
   typename Pat::RowCtx rc{};
   typename Pat::template Slot<V> slot[NV];
   typename Pat::template ColAcc<V> cacc[NV]{};
+  // reductions of per-row values over the rows: every lane of a lane group keeps the running values
+  // of the group's rows
+  float racc[Pat::NROWRED > 0 ? Pat::NROWRED : 1];
+  if constexpr (Pat::NROWRED > 0) {
+#pragma unroll
+    for (int q = 0; q < Pat::NROWRED; ++q) racc[q] = Pat::rr_identity(q);
+  }
   // Row bookkeeping in scalar registers: rw = row of the first lane group of this wavefront in
   // the current row group, sbw = its element offset; both advance by a constant per iteration
   // (no 64-bit products in the loop).  A lane's row is rw + dgrp.
@@ -615,6 +622,9 @@ DISC_DEV void row_reg_body(const typename Pat::Args& A, const RowPlan& rp) {
     typename Pat::template Keep<V> keep[NV];
     row_phases<Pat, 0, V, NV>(A, rp, rc, slot, keep, span, col0, lds, parity, prefetch);
     if constexpr (Pat::NPHASE == 0) prefetch();   // (no reduction phase to hide the next row's loads behind)
+    if constexpr (Pat::NROWRED > 0) {
+      if (active) Pat::row_reds(A, rc, racc);
+    }
 #pragma unroll
     for (int j = 0; j < NV; ++j) {
       if (span[j].any()) {
@@ -702,6 +712,34 @@ DISC_DEV void row_reg_body(const typename Pat::Args& A, const RowPlan& rp) {
         }
     }
   }
+  if constexpr (Pat::NROWRED > 0) {
+    // The lanes of a lane group hold the same values, the groups of a wavefront different rows:
+    // combine across the groups, then across the wavefronts of the block through LDS (the
+    // wavefronts of one lane group of a long row hold the same rows: one of them counts), and
+    // write one partial result per block and reduction: ws1[q * blocks + block].
+    if (rp.G < 64) {
+#pragma unroll
+      for (int q = 0; q < Pat::NROWRED; ++q)
+        for (int sft = rp.G; sft < 64; sft <<= 1) racc[q] = Pat::rr_merge(q, racc[q], lane_xor_f32(racc[q], sft));
+    }
+    __shared__ float rbuf[16][Pat::NROWRED];
+    const int wave = (int)threadIdx.x >> 6, nw = (int)blockDim.x >> 6;
+    const int wpg = rp.G > 64 ? rp.G >> 6 : 1;
+    if (((int)threadIdx.x & 63) == 0) {
+#pragma unroll
+      for (int q = 0; q < Pat::NROWRED; ++q) rbuf[wave][q] = racc[q];
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      float* ws = reinterpret_cast<float*>(A.ws1);
+#pragma unroll
+      for (int q = 0; q < Pat::NROWRED; ++q) {
+        float t = rbuf[0][q];
+        for (int w = wpg; w < nw; w += wpg) t = Pat::rr_merge(q, t, rbuf[w][q]);
+        ws[(i64)q * A.aux1 + blockIdx.x] = t;
+      }
+    }
+  }
 }
 
 // Streaming version for rows that do not fit the register budget: one block per row, the
@@ -745,11 +783,17 @@ DISC_DEV void row_stream_body(const typename Pat::Args& A) {
   const int inner = (int)A.inner;
   int parity = 0;
   bool first = true;
+  float racc[Pat::NROWRED > 0 ? Pat::NROWRED : 1];
+  if constexpr (Pat::NROWRED > 0) {
+#pragma unroll
+    for (int q = 0; q < Pat::NROWRED; ++q) racc[q] = Pat::rr_identity(q);
+  }
   for (i64 row = blockIdx.x; row < A.rows; row += gridDim.x) {
     typename Pat::RowCtx rc;
     Pat::row_begin(A, row, rc);
     rc.sl = nullptr;
     row_stream_phases<Pat, 0, V>(A, rc, inner, lds, parity);
+    if constexpr (Pat::NROWRED > 0) Pat::row_reds(A, rc, racc);   // (every lane holds the row's values)
     for (int col = threadIdx.x * V; col < inner; col += blockDim.x * V) {
       int n = inner - col;
       n = n > V ? V : n;
@@ -780,6 +824,42 @@ DISC_DEV void row_stream_body(const typename Pat::Args& A) {
     }
     if (threadIdx.x == 0) Pat::row_store(A, row, rc);
     first = false;
+  }
+  if constexpr (Pat::NROWRED > 0) {
+    if (threadIdx.x == 0) {
+#pragma unroll
+      for (int q = 0; q < Pat::NROWRED; ++q) reinterpret_cast<float*>(A.ws1)[(i64)q * A.aux1 + blockIdx.x] = racc[q];
+    }
+  }
+}
+
+// Last launch of a row reduce with reductions of per-row values over the rows: one block folds the
+// per-block partial results of every reduction in a fixed order (sums in fp64) and stores them.
+template <class Pat>
+DISC_DEV void rowred_finish_body(const typename Pat::Args& A) {
+  constexpr int NQ = Pat::NROWRED;
+  __shared__ double red[NQ][256];
+  const float* ws = reinterpret_cast<const float*>(A.ws1);
+  const i64 P = A.aux1;
+#pragma unroll
+  for (int q = 0; q < NQ; ++q) {
+    double t = (double)Pat::rr_identity(q);
+    for (i64 i = threadIdx.x; i < P; i += 256) t = Pat::rr_merge(q, t, (double)ws[(i64)q * P + i]);
+    red[q][threadIdx.x] = t;
+  }
+  __syncthreads();
+  for (int s = 128; s > 0; s >>= 1) {
+    if ((int)threadIdx.x < s) {
+#pragma unroll
+      for (int q = 0; q < NQ; ++q) red[q][threadIdx.x] = Pat::rr_merge(q, red[q][threadIdx.x], red[q][threadIdx.x + s]);
+    }
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) {
+    float v[NQ];
+#pragma unroll
+    for (int q = 0; q < NQ; ++q) v[q] = (float)red[q][0];
+    Pat::rowred_store(A, v);
   }
 }
 

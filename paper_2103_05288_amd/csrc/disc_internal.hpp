@@ -95,6 +95,8 @@ struct Access {
   // output of a row-reduce pattern that is a sum over the rows (a column sum beside the row
   // reductions): one element per column, accumulated next to the epilogue
   bool col_sum = false;
+  // output of a row-reduce pattern that reduces per-row values over the rows to one number
+  bool row_red = false;
 };
 
 // Resolved graph: one node per (value, context) pair actually needed.
@@ -118,6 +120,8 @@ struct OutputRef {
   int node = -1;      // the value stored; for a column sum beside row reductions, the value summed
   int access = -1;
   bool col_sum = false;
+  bool row_red = false;   // a reduction (red_opcode) of the per-row value `node` over the rows
+  int red_opcode = 0;
 };
 
 // A product of runtime dims the host evaluates at launch (shape calculation).
@@ -167,6 +171,7 @@ struct Analysis {
   std::vector<int> reduces[8];           // reduce nodes per phase
   int n_phases = 0;
   int n_col_sums = 0;                    // row reduce: outputs that are sums over the rows
+  int n_row_reds = 0;                    // row reduce: outputs that reduce per-row values over the rows to one number
   int n_inputs = 0, n_outputs = 0;
   bool needs_decomp = false;             // some access is ACC_PARTIAL
 
@@ -202,6 +207,7 @@ struct Generated {
   int n_red_planes = 0;               // column reduce: reduce-result planes in the workspace
   bool has_epilogue = true;           // column reduce: some output keeps the reduced axis
   int n_col_sums = 0;                 // row reduce: outputs summed over the rows (second launch combines the partial sums)
+  int n_row_reds = 0;                 // row reduce: per-row values reduced over the rows to one number (last launch)
   std::vector<int> staged_elem_bytes; // row reduce: element size of each row vector that can be staged in LDS
   std::vector<std::string> field_names;   // member name of each args.fields entry in Pat::Args
 };

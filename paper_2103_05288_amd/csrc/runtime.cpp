@@ -411,6 +411,8 @@ int make_plan(disc_ctx* c, const Pattern& p, const int64_t* dims, int n_dims, in
     pub.n_launches = 1;
   } else if (an.tmpl == DISC_TEMPLATE_ROW_REDUCE) {
     const int n_col_sums = p.gen.n_col_sums;   // outputs summed over the rows, carried along by the row kernels
+    const int n_row_reds = p.gen.n_row_reds;   // per-row values reduced over the rows to one number each
+    if (sv.rows == 0 && n_row_reds > 0) return set_err(c, DISC_ERR_EMPTY_REDUCE, "reduction over an axis of size 0");
     if (sv.rows == 0 && n_col_sums > 0 && sv.inner > 0)
       return set_err(c, DISC_ERR_EMPTY_REDUCE, "reduction over an axis of size 0");
     if (sv.rows == 0) return DISC_OK;
@@ -559,6 +561,17 @@ int make_plan(disc_ctx* c, const Pattern& p, const int64_t* dims, int n_dims, in
       pub.n_launches = 2;
     } else {
       fp->aux[0] = 0;
+    }
+    if (n_row_reds > 0) {
+      // one partial result per block and reduction behind the column-sum planes; a last launch of
+      // one block folds them
+      fp->aux[1] = L.grid[0];
+      fp->ws_off[1] = (pub.workspace_bytes + 255) / 256 * 256;
+      pub.workspace_bytes = fp->ws_off[1] + (size_t)n_row_reds * (size_t)L.grid[0] * 4;
+      LaunchRec& Lr = fp->launches[pub.n_launches++];
+      Lr.kernel = "k_rowred_finish";
+      Lr.block = 256;
+      Lr.grid[0] = 1;
     }
   } else {
     // column reduce: canonical [outer, mid, inner], rows = outer * mid
@@ -824,7 +837,7 @@ static std::string static_macros(const Pattern& p, const FullPlan& fp, const int
       case ArgField::AUX:
         // the number of partial-sum rows follows the grid, which is chosen again at every launch
         // from the loaded kernel's residency: it stays a run-time argument
-        if (p.gen.n_col_sums > 0) break;
+        if (p.gen.n_col_sums > 0 || p.gen.n_row_reds > 0) break;
         [[fallthrough]];
       default: {
         int64_t v;

@@ -6,7 +6,7 @@ import pytest
 import torch
 
 from workloads.configs import TORCH_DTYPE
-from workloads.extras import gelu_backward_bias_gradient, layernorm_backward_graph
+from workloads.extras import gelu_backward_bias_gradient, layernorm_backward_graph, logsumexp_with_total_and_amax
 from workloads.pattern import PatternBuilder
 
 
@@ -106,6 +106,57 @@ def test_sum_over_rows_beside_a_loop_fusion(hctx):
     t, hh = pb.dims(2)
     pb.output(pb.reduce("sum", pb.op("tanh", pb.param("f32", [t, hh])), 0))
     assert hctx.register(pb.build()).info["template"] == "col_reduce"
+
+
+def test_per_row_values_reduced_over_the_rows(hctx):
+    """Rank-0 outputs: a sum / maximum / minimum of per-row values over the rows rides along in the
+    row kernels (one partial result per block, a last one-block launch)."""
+    from paper_2103_05288_amd import DiscError
+    pat = logsumexp_with_total_and_amax()
+    h = hctx.register(pat)
+    assert h.info["template"] == "row_reduce" and h.info["n_phases"] == 2 and h.info["n_outputs"] == 3
+    pl = h.plan([4096, 1024])
+    assert pl["n_launches"] == 2 and pl["kernels"][1].endswith("k_rowred_finish") and pl["grid"][1] == [1, 1, 1]
+    assert pl["workspace_bytes"] == 2 * pl["grid"][0][0] * 4
+    assert h.plan([100, 30000])["kernels"][0].endswith("k_row_stream_vec")
+    with pytest.raises(DiscError) as e:
+        h.plan([0, 64])
+    assert e.value.status == "EMPTY_REDUCE"
+    assert pat.shape_of(pat.outputs[1], [7, 5]) == ()
+    # with sums over the rows of full-size values in the same pattern: three launches
+    pb = PatternBuilder("both")
+    t, hh = pb.dims(2)
+    x = pb.param("f32", [t, hh])
+    m = pb.reduce("max", x, 1)
+    d = pb.op("sub", x, pb.broadcast(m, [t, hh], [0]))
+    pb.output(d)
+    pb.output(pb.reduce("sum", d, 0))
+    pb.output(pb.reduce("min", m, 0))
+    hb = hctx.register(pb.build())
+    pl = hb.plan([4096, 1024])
+    assert [k.split("_k_")[1] for k in pl["kernels"]][1:] == ["colsum_finish", "rowred_finish"]
+    assert pl["workspace_bytes"] == (pl["grid"][0][0] * 1024 * 4 + 255) // 256 * 256 + pl["grid"][0][0] * 4
+    # what is not fused: a rank-0 result of anything else
+    for build in ("prod_like_argmax", "consumed", "column_vector", "no_row_reduce"):
+        pb = PatternBuilder(build)
+        t, hh = pb.dims(2)
+        x = pb.param("f32", [t, hh])
+        m = pb.reduce("max", x, 1)
+        pb.output(pb.op("sub", x, pb.broadcast(m, [t, hh], [0])))
+        if build == "prod_like_argmax":
+            pb.output(pb.reduce("argmax", m, 0))
+        elif build == "consumed":
+            s = pb.reduce("sum", m, 0)
+            pb.output(pb.op("sub", m, pb.broadcast(s, [t], [])))
+        elif build == "column_vector":
+            pb.output(pb.reduce("sum", pb.reduce("sum", x, 0), 0))
+        else:
+            pb = PatternBuilder(build)
+            t = pb.dim()
+            pb.output(pb.reduce("sum", pb.param("f32", [t]), 0))
+        with pytest.raises(DiscError) as e:
+            hctx.register(pb.build())
+        assert e.value.status in ("UNFUSIBLE", "BAD_PATTERN"), (build, str(e.value))
 
 
 def _inputs(pat, dims, gen):
@@ -260,5 +311,73 @@ def test_single_shape_build_of_a_pattern_with_sums_over_rows():
             rpb = -(-dims[0] // pl["grid"][0][0])
             _check_sum(got[1], want[1], np.abs(dy64 * xhat), rpb, f"static dgamma dims={dims}")
             _check_sum(got[2], want[2], np.abs(dy64), rpb, f"static dbeta dims={dims}")
+    finally:
+        ctx.close()
+
+
+@pytest.mark.gpu
+def test_logsumexp_total_and_amax_match_oracle():
+    from oracle import run as oracle_run
+    from paper_2103_05288_amd import Context
+    from paper_2103_05288_amd.binding import VARIANTS
+    from tests.util import assert_close, run_gpu, to_oracle_input
+    pat = logsumexp_with_total_and_amax()
+    ctx = Context(0)
+    try:
+        h = ctx.register(pat)
+        gen = torch.Generator().manual_seed(29)
+        cases = [([1, 1], None), ([7, 5], None), ([1000, 77], None), ([20000, 16], None), ([4096, 1024], None), ([513, 2050], None),
+                 ([300, 4100], None), ([65, 8200], None), ([40, 30000], None),
+                 ([33, 768], "row_reg_scalar"), ([600, 100], "row_stream_vec"), ([600, 100], "row_stream_scalar")]
+        for dims, force in cases:
+            ins = [(3 * torch.randn(*dims, generator=gen)).bfloat16()]
+            fv = VARIANTS.index(force) if force else -1
+            ctx.force_variant(fv)
+            try:
+                pl = h.plan(dims, force_variant=fv)
+                got = run_gpu(h, pat, dims, ins)
+            finally:
+                ctx.force_variant(-1)
+            want = oracle_run(pat, dims, [to_oracle_input(t) for t in ins])[0]
+            assert_close(got[0], want[0], f"lse dims={dims} {force}")
+            # the total: terms of either sign, each with fp32 roundings of its own; a lane adds the
+            # rows of its block in fp32, the blocks are added in fp64
+            lse = np.asarray(want[0], dtype=np.float64)
+            rpb = -(-dims[0] // pl["grid"][0][0])
+            lim = (16 + rpb) * 2.0 ** -24 * np.abs(lse).sum() + 1e-6
+            assert abs(float(got[1]) - float(want[1])) <= lim, (dims, force, float(got[1]), float(want[1]), lim)
+            # the amax of bf16 inputs is exact
+            assert float(got[2]) == float(want[2]) == float(ins[0].float().abs().max()), (dims, force)
+    finally:
+        ctx.close()
+
+
+@pytest.mark.gpu
+def test_column_sums_and_scalar_reductions_together():
+    from oracle import run as oracle_run
+    from paper_2103_05288_amd import Context
+    from tests.util import assert_close, run_gpu, to_oracle_input
+    pb = PatternBuilder("both")
+    t, hh = pb.dims(2)
+    x = pb.param("f32", [t, hh])
+    m = pb.reduce("max", x, 1)
+    e = pb.op("exp", pb.op("sub", x, pb.broadcast(m, [t, hh], [0])))        # in (0, 1]
+    pb.output(pb.cast(e, "bf16"))
+    pb.output(pb.reduce("sum", e, 0))                                      # non-negative terms: the element-wise bar applies
+    pb.output(pb.reduce("min", m, 0))
+    pb.output(pb.reduce("sum", pb.reduce("sum", e, 1), 0))
+    pat = pb.build()
+    ctx = Context(0)
+    try:
+        h = ctx.register(pat)
+        assert h.info["n_phases"] == 2
+        gen = torch.Generator().manual_seed(37)
+        for dims in ([5, 3], [3000, 130], [700, 1024], [129, 5000], [50, 26000]):
+            ins = [torch.randn(*dims, generator=gen)]
+            assert h.plan(dims)["n_launches"] == 3
+            got = run_gpu(h, pat, dims, ins)
+            want = oracle_run(pat, dims, [to_oracle_input(t) for t in ins])[0]
+            for k, (g, w) in enumerate(zip(got, want)):
+                assert_close(g, w, f"dims={dims} out{k}")
     finally:
         ctx.close()

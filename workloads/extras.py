@@ -103,3 +103,19 @@ def gelu_backward_bias_gradient():
     pb.output(pb.cast(dx, "bf16"))
     pb.output(pb.reduce("sum", dx, 0))
     return pb.build()
+
+
+def logsumexp_with_total_and_amax():
+    """Per-row log-sum-exp of bf16 logits (two dependent row reductions), its sum over all rows (the
+    normaliser part of a summed cross-entropy loss) and the largest |logit| of the whole tensor (the
+    amax a scaling recipe tracks): two rank-0 outputs that reduce per-row values over the rows."""
+    pb = PatternBuilder("lse_total_amax")
+    T, H = pb.dims(2)
+    x = pb.cast(pb.param("bf16", [T, H]), "f32")
+    m = pb.reduce("max", x, 1)
+    e = pb.op("exp", pb.op("sub", x, pb.broadcast(m, [T, H], [0])))
+    lse = pb.op("add", pb.op("log", pb.reduce("sum", e, 1)), m)
+    pb.output(lse)
+    pb.output(pb.reduce("sum", lse, 0))
+    pb.output(pb.reduce("max", pb.reduce("max", pb.op("abs", x), 1), 0))
+    return pb.build()
