@@ -88,7 +88,9 @@ typedef enum {
                       strictly increasing; an operand axis of static size 1 may expand         */
   DISC_REDUCE_SUM, DISC_REDUCE_MAX, DISC_REDUCE_MIN,
   DISC_REDUCE_ARGMAX, /* lowest index among the maxima; dtype DISC_I32 or DISC_I64             */
-  DISC_OUTPUT,     /* k-th OUTPUT = k-th output pointer; in[0] = the value, same dtype         */
+  DISC_OUTPUT,     /* k-th OUTPUT = k-th output pointer; in[0] = the value, same dtype.  Rank 0
+                      (one element) only for a reduction of per-row values over the rows, see
+                      DISC_TEMPLATE_ROW_REDUCE                                                  */
   DISC_SLICE,      /* dynamic slice of a PARAM, stride 1 (Section 4.1: start indices are runtime
                       values, not attributes): result[i0,i1,..] = in[s0+i0, s1+i1, ..]; dim[] = sizes
                       of the result; axis_map[k] = start along axis k: >= 0 the symbolic dim id whose
@@ -147,7 +149,11 @@ typedef enum {
                                    two-dimensional iteration space whose result feeds OUTPUTs only
                                    (weight gradients next to an input gradient) is carried along
                                    by the row kernels as per-block partial sums in the workspace
-                                   and finished by a second launch, in a fixed order           */
+                                   and finished by a second launch, in a fixed order.  Likewise
+                                   REDUCE_SUM / MAX / MIN of a per-row float value over the rows,
+                                   down to one number (a rank-0 OUTPUT: the total of per-row
+                                   losses, the amax of a tensor): one partial result per block,
+                                   folded by a last launch of one block                         */
   DISC_TEMPLATE_COL_REDUCE = 2, /* input fusion, reduce over an outer axis (+ epilogue)         */
   DISC_TEMPLATE_TRANSPOSE = 3   /* not a fusion: PARAM -> TRANSPOSE -> OUTPUT alone, a permutation
                                    that moves the innermost axis, run as a batched 2-D tile
