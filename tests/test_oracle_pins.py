@@ -570,3 +570,21 @@ def test_backward_workloads_equal_autograd():
     out = run(gelu_backward_bias_gradient(), [T, H], [dy.numpy(), x.numpy(), b.numpy()])[0]
     np.testing.assert_allclose(np.asarray(out[0], dtype=np.float64), xr.grad.numpy(), rtol=2.0 ** -8, atol=1e-6)
     np.testing.assert_allclose(np.asarray(out[1], dtype=np.float64), br.grad.numpy(), rtol=1e-6, atol=1e-6)
+
+
+def test_reduction_of_per_row_values_to_one_number():
+    """A rank-1 value reduced over its only axis gives a rank-0 result: against Python's own sum /
+    max / min over a list, for a chain of two reductions of a matrix."""
+    rng = np.random.default_rng(3)
+    x = rng.standard_normal((6, 5))
+    for inner, outer, py_in, py_out in (("sum", "sum", sum, sum), ("max", "min", max, min), ("min", "max", min, max), ("max", "sum", max, sum)):
+        pb = PatternBuilder()
+        t, h = pb.dims(2)
+        v = pb.param("f32", [t, h])
+        r = pb.reduce(inner, v, 1)
+        pb.output(r)
+        pb.output(pb.reduce(outer, r, 0))
+        out = run(pb.build(), [6, 5], [x])[0]
+        rows = [py_in(float(a) for a in x[i]) for i in range(6)]
+        assert np.asarray(out[1]).shape == ()
+        assert float(out[1]) == pytest.approx(py_out(rows), rel=1e-6, abs=1e-6)
