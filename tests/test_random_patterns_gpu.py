@@ -2,8 +2,8 @@
 with row vectors, per-row operands, scalars, masks, windows (dynamic slices) of larger inputs,
 padded smaller inputs and mixed storage types; no reduction (loop
 fusion), one or two dependent row reductions with an epilogue, or a column reduction with an
-epilogue; half of the rank-2 loop and row patterns also emit a sum over the rows, which rides
-along in the row kernels.  Every pattern is compiled once and launched at several shapes (ragged
+epilogue; most of the rank-2 loop and row patterns also emit a sum over the rows, and row
+patterns rank-0 reductions of their per-row results, which ride along in the row kernels.  Every pattern is compiled once and launched at several shapes (ragged
 and aligned).
 
 The generator keeps the arithmetic well conditioned, so the element-wise parity bar applies:
@@ -49,6 +49,8 @@ class Gen:
         # a sum over the rows beside the loop fusion / the row reductions (drawn from a generator of
         # its own, so that the rest of the pattern does not depend on it)
         self.side_sum = self.rank == 2 and self.kind != "col" and np.random.default_rng(5000 + seed).random() < 0.7
+        # rank-0 outputs: per-row reduction results reduced once more over the rows
+        self.scalar_out = self.rank == 2 and self.kind in ("row", "row2") and np.random.default_rng(7000 + seed).random() < 0.7
 
     def pick(self, seq):
         return seq[int(self.rng.integers(0, len(seq)))]
@@ -146,6 +148,9 @@ class Gen:
                 pb.output(s)
             if self.side_sum:
                 pb.output(pb.reduce("sum", pb.op("sigmoid", y), 0))      # non-negative terms
+            if self.scalar_out:
+                pb.output(pb.reduce("sum", s, 0))                        # positive terms
+                pb.output(pb.reduce("min", m, 0))
         else:
             axis = rank - 2
             keep = [k for k in range(rank) if k != axis]
@@ -196,7 +201,7 @@ def shapes_for(gen, rng):
         res.append([t, h] if gen.rank == 2 else [int(rng.integers(1, 5)), t, h])
     if gen.kind == "col":                      # one tall shape: chunks of the reduced axis, three launches
         res.append([3000, 520] if gen.rank == 2 else [2, 2500, 130])
-    if gen.side_sum:                           # many rows per block, several blocks
+    if gen.side_sum or gen.scalar_out:         # many rows per block, several blocks
         res.append([2500, 130])
     return res
 
