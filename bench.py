@@ -246,8 +246,8 @@ def next_rows(ctx, dev):
     on inputs (slice, pad, transpose) at one large shape each; effective rate = bytes of the
     graph's / pattern's inputs and outputs, each once, over the device time of one call."""
     from workloads.configs import TORCH_DTYPE
-    from workloads.extras import (gelu_backward_bias_gradient, heads_softmax, layernorm_backward_graph, padded_softmax,
-                                  pure_transpose, qkv_split)
+    from workloads.extras import (gelu_backward_bias_gradient, heads_softmax, layernorm_backward_graph,
+                                  logsumexp_with_total_and_amax, padded_softmax, pure_transpose, qkv_split)
 
     def io_bytes(pat, dims):
         n = 0
@@ -261,6 +261,7 @@ def next_rows(ctx, dev):
     # ~1 GB of operands and results per call: nothing of a call survives in the 256 MB memory-side cache
     cases = [("graph_layernorm_backward", layernorm_backward_graph(), [131072, 1024], True),
              ("gelu_backward_bias_gradient", gelu_backward_bias_gradient(), [131072, 1024], False),
+             ("logsumexp_total_amax", logsumexp_with_total_and_amax(), [262144, 2048], False),
              ("slice_qkv_split", qkv_split(), [131072, 1024, 3072, 1024, 2048], False),
              ("pad_softmax_minus_inf", padded_softmax(), [131072, 2000, 24, 2048], False),
              ("transpose_heads_softmax", heads_softmax(), [128, 1024, 16, 128], False),

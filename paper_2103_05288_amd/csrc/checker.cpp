@@ -791,6 +791,11 @@ static int analyze_impl(const disc_op* ops, int n_ops, const disc_constraint* cs
     an.outputs.push_back(o);
   }
   if (b.status != DISC_OK) return b.status;
+  if (an.n_col_sums > 4 || an.n_row_reds > 4) {
+    // (registers per lane for the column sums, LDS of the last launch for the rank-0 results)
+    err = "more than four reductions over the rows of one kind in a row-reduce pattern";
+    return DISC_ERR_UNFUSIBLE;
+  }
 
   // ---- 5. collapse root axes with identical roles ------------------------------------------
   an.groups.clear();

@@ -1052,7 +1052,11 @@ struct Gen {
       k("k_row_stream_vec", fmt("disc::row_stream_body<Pat, %d>(A);", V), nullptr);
       k("k_row_stream_scalar", "disc::row_stream_body<Pat, 1>(A);", nullptr);
       if (an.n_col_sums > 0) k("k_colsum_finish", "disc::colsum_finish_body<Pat>(A);", nullptr);
-      if (an.n_row_reds > 0) k("k_rowred_finish", "disc::rowred_finish_body<Pat>(A);", nullptr);
+      if (an.n_row_reds > 0) {
+        max_threads = 1024;
+        k("k_rowred_finish", "disc::rowred_finish_body<Pat>(A);", nullptr);
+        max_threads = 256;
+      }
     } else {
       k("k_col_partial_vec", fmt("disc::col_partial_body<Pat, %d>(A, rp);", V), "ColPlan");
       k("k_col_partial_scalar", "disc::col_partial_body<Pat, 1>(A, rp);", "ColPlan");

@@ -833,29 +833,45 @@ DISC_DEV void row_stream_body(const typename Pat::Args& A) {
   }
 }
 
-// Last launch of a row reduce with reductions of per-row values over the rows: one block folds the
-// per-block partial results of every reduction in a fixed order (sums in fp64) and stores them.
+// Last launch of a row reduce with reductions of per-row values over the rows: one block of 1024
+// threads folds the per-block partial results of every reduction in a fixed order (sums in fp64)
+// and stores them.  All reductions advance together and two strides are in flight per lane, so a
+// lane makes one or two dependent trips to memory for the couple of thousand partial results of a
+// large launch (a 256-thread block that took the reductions one after the other needed 14 us).
 template <class Pat>
 DISC_DEV void rowred_finish_body(const typename Pat::Args& A) {
   constexpr int NQ = Pat::NROWRED;
-  __shared__ double red[NQ][256];
+  __shared__ double red[NQ][1024];
   const float* ws = reinterpret_cast<const float*>(A.ws1);
   const i64 P = A.aux1;
+  const int nt = (int)blockDim.x, tid = (int)threadIdx.x;      // nt: a power of two <= 1024
+  double t0[NQ], t1[NQ];
 #pragma unroll
-  for (int q = 0; q < NQ; ++q) {
-    double t = (double)Pat::rr_identity(q);
-    for (i64 i = threadIdx.x; i < P; i += 256) t = Pat::rr_merge(q, t, (double)ws[(i64)q * P + i]);
-    red[q][threadIdx.x] = t;
+  for (int q = 0; q < NQ; ++q) t0[q] = t1[q] = (double)Pat::rr_identity(q);
+  i64 i = tid;
+  for (; i + nt < P; i += 2 * nt) {
+#pragma unroll
+    for (int q = 0; q < NQ; ++q) {
+      const float a = ws[(i64)q * P + i], b = ws[(i64)q * P + i + nt];
+      t0[q] = Pat::rr_merge(q, t0[q], (double)a);
+      t1[q] = Pat::rr_merge(q, t1[q], (double)b);
+    }
   }
-  __syncthreads();
-  for (int s = 128; s > 0; s >>= 1) {
-    if ((int)threadIdx.x < s) {
+  for (; i < P; i += nt) {
 #pragma unroll
-      for (int q = 0; q < NQ; ++q) red[q][threadIdx.x] = Pat::rr_merge(q, red[q][threadIdx.x], red[q][threadIdx.x + s]);
+    for (int q = 0; q < NQ; ++q) t0[q] = Pat::rr_merge(q, t0[q], (double)ws[(i64)q * P + i]);
+  }
+#pragma unroll
+  for (int q = 0; q < NQ; ++q) red[q][tid] = Pat::rr_merge(q, t0[q], t1[q]);
+  __syncthreads();
+  for (int s = nt >> 1; s > 0; s >>= 1) {
+    if (tid < s) {
+#pragma unroll
+      for (int q = 0; q < NQ; ++q) red[q][tid] = Pat::rr_merge(q, red[q][tid], red[q][tid + s]);
     }
     __syncthreads();
   }
-  if (threadIdx.x == 0) {
+  if (tid == 0) {
     float v[NQ];
 #pragma unroll
     for (int q = 0; q < NQ; ++q) v[q] = (float)red[q][0];
@@ -866,10 +882,10 @@ DISC_DEV void rowred_finish_body(const typename Pat::Args& A) {
 // Second launch of a row reduce with sums over the rows: adds up the P rows of partial sums of
 // every summed output, in a fixed order (the result does not depend on timing) and in fp64 (the
 // fp32 partial sums each cover the rows of one block only).  A block takes 16 columns; its 256
-// lanes are 16 columns x 16 lanes that each walk every 16th partial row, one sum after the other,
-// four loads in flight; the 16 lane totals of a column meet in LDS.  (Measured at 1023 partial
-// rows x 1024 columns x 2 sums: 12.6 us; 8 columns x 32 lanes with the sums interleaved, and
-// blocks of 1024 threads covering whole 128-byte lines, both took 19 us.)
+// lanes are 16 columns x 16 lanes that each walk every 16th partial row of all sums together,
+// eight loads in flight; the 16 lane totals of a column meet in LDS.  (Measured at 1023 partial
+// rows x 1024 columns x 2 sums: 8.7 us, 12.6 with one sum after the other; 8 columns x 32 lanes,
+// and blocks of 1024 threads covering whole 128-byte lines, both took 19 us.)
 constexpr int kColsumCols = 16, kColsumLanes = 16;
 template <class Pat>
 DISC_DEV void colsum_finish_body(const typename Pat::Args& A) {
@@ -880,21 +896,38 @@ DISC_DEV void colsum_finish_body(const typename Pat::Args& A) {
   const float* ws = reinterpret_cast<const float*>(A.ws0);
   for (i64 c0 = (i64)blockIdx.x * CL; c0 < inner; c0 += (i64)gridDim.x * CL) {
     const i64 col = c0 + cl;
+    constexpr int U = NQ >= 2 ? 4 : 8;            // partial rows in flight per lane and sum
+    double acc[NQ][U];
+#pragma unroll
+    for (int q = 0; q < NQ; ++q)
+#pragma unroll
+      for (int u = 0; u < U; ++u) acc[q][u] = 0.0;
+    if (col < inner) {
+      const float* src = ws + col;
+      const i64 plane = P * inner;
+      i64 p = pl;
+      for (; p + (U - 1) * PL < P; p += U * PL) {
+        float x[NQ][U];
+#pragma unroll
+        for (int q = 0; q < NQ; ++q)
+#pragma unroll
+          for (int u = 0; u < U; ++u) x[q][u] = src[q * plane + (p + u * PL) * inner];
+#pragma unroll
+        for (int q = 0; q < NQ; ++q)
+#pragma unroll
+          for (int u = 0; u < U; ++u) acc[q][u] += x[q][u];
+      }
+      for (; p < P; p += PL) {
+#pragma unroll
+        for (int q = 0; q < NQ; ++q) acc[q][0] += src[q * plane + p * inner];
+      }
+    }
 #pragma unroll
     for (int q = 0; q < NQ; ++q) {
-      double a0 = 0.0, a1 = 0.0, a2 = 0.0, a3 = 0.0;
-      if (col < inner) {
-        const float* src = ws + (i64)q * P * inner + col;
-        i64 p = pl;
-        for (; p + 3 * PL < P; p += 4 * PL) {
-          a0 += src[p * inner];
-          a1 += src[(p + PL) * inner];
-          a2 += src[(p + 2 * PL) * inner];
-          a3 += src[(p + 3 * PL) * inner];
-        }
-        for (; p < P; p += PL) a0 += src[p * inner];
-      }
-      red[q][pl][cl] = (a0 + a1) + (a2 + a3);
+      double t = 0.0;
+#pragma unroll
+      for (int u = 0; u < U; ++u) t += acc[q][u];
+      red[q][pl][cl] = t;
     }
     __syncthreads();
     if (pl == 0 && col < inner) {

@@ -570,7 +570,7 @@ int make_plan(disc_ctx* c, const Pattern& p, const int64_t* dims, int n_dims, in
       pub.workspace_bytes = fp->ws_off[1] + (size_t)n_row_reds * (size_t)L.grid[0] * 4;
       LaunchRec& Lr = fp->launches[pub.n_launches++];
       Lr.kernel = "k_rowred_finish";
-      Lr.block = 256;
+      Lr.block = 1024;
       Lr.grid[0] = 1;
     }
   } else {
