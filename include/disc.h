@@ -57,7 +57,9 @@ typedef enum {
   DISC_ERR_COMPILE = -6,     /* device compile failed; the compiler log is in disc_last_error   */
   DISC_ERR_HIP = -7,         /* a HIP runtime call failed                                       */
   DISC_ERR_SHAPE = -8,       /* negative dim, element count overflow, row too long              */
-  DISC_ERR_EMPTY_REDUCE = -9 /* reduction over an axis of runtime size 0                        */
+  DISC_ERR_EMPTY_REDUCE = -9,/* reduction over an axis of runtime size 0                        */
+  DISC_ERR_INTERNAL = -10    /* an exception inside the library (out of host memory, ...); caught
+                                at the boundary, never propagated                               */
 } disc_status;
 
 enum { DISC_MAX_RANK = 4, DISC_MAX_OPS = 256, DISC_MAX_DIMS = 16 };
@@ -231,8 +233,11 @@ void disc_destroy(disc_ctx* ctx);
 const char* disc_last_error(const disc_ctx* ctx);
 
 /* Register a fusion pattern (op sequence without shape values + constraints) and compile it
- * once.  `ops` / `cs` are copied.  Registering an identical op list + constraints again returns
- * the same id without compiling (pattern cache keyed on the op sequence, never on sizes). */
+ * once (Section 2: fused kernels are generated for shapes that are not known yet; Section 4.2.1:
+ * shape constraints collected without shape values; Section 4.3: they decide what may share a
+ * kernel and which template it gets).  `ops` / `cs` are copied.  Registering an identical op list
+ * + constraints again returns the same id without compiling (pattern cache keyed on the op
+ * sequence, never on sizes). */
 int disc_register_pattern(disc_ctx* ctx, const disc_op* ops, int n_ops, const disc_constraint* cs,
                           int n_cs, int32_t* pattern_id_out);
 /* The same pattern compiled for ONE shape, the way a static-shape compiler would (Section 1 and
@@ -250,17 +255,23 @@ int disc_pattern_info(disc_ctx* ctx, int32_t id, disc_pattern_info_t* out);
 const char* disc_pattern_source(disc_ctx* ctx, int32_t id);
 
 /* Bytes of device workspace disc_launch needs at these dims (0 for loop patterns and for row
- * patterns without sums over the rows). */
+ * patterns without sums over the rows).  Buffer sizes are a result of the host-side shape
+ * calculation (Section 4.2.1) and the buffers come from the caller (Section 4.2.2: the framework's
+ * allocator owns the memory). */
 int disc_workspace_bytes(disc_ctx* ctx, int32_t id, const int64_t* dims, int n_dims, size_t* out);
 
-/* Pure host: the runtime flow of one launch without enqueueing anything (shape calculation,
- * constraint check, version and launch-dimension selection).  `inputs` / `outputs` may be NULL
+/* Pure host: the runtime flow of one launch without enqueueing anything: shape calculation and
+ * constraint check (Section 4.2.1), selection of one of the pattern's kernel versions and of the
+ * launch dimensions from the runtime shape (Section 4.3, the paragraph on the versions).  `inputs` / `outputs` may be NULL
  * (then buffers are assumed 16-byte aligned); pointers are only inspected, never dereferenced.
  * force_variant = -1 lets the host choose. */
 int disc_plan(disc_ctx* ctx, int32_t id, const int64_t* dims, int n_dims, const void* const* inputs,
               void* const* outputs, int force_variant, disc_plan_t* out);
 
-/* Launch the pattern at runtime sizes dims[0..n_dims).  Asynchronous on `hip_stream` (a
+/* Launch the pattern at runtime sizes dims[0..n_dims): the generated runtime flow of Sections
+ * 4.2.1 and 4.2.3 (shape calculation, kernel launch with host-chosen launch dimensions) followed
+ * by the enqueue; a dims vector that contradicts a registered dimension-size or tensor-size
+ * equality is refused with DISC_ERR_CONSTRAINT before anything runs.  Asynchronous on `hip_stream` (a
  * hipStream_t, NULL = default stream).  Any output with zero elements and no reduction over an
  * empty axis: success, nothing launched. */
 int disc_launch(disc_ctx* ctx, int32_t id, const int64_t* dims, int n_dims,
@@ -270,6 +281,15 @@ int disc_launch(disc_ctx* ctx, int32_t id, const int64_t* dims, int n_dims,
 /* Tests only: make the next launches of this context use `variant` when it is legal for the
  * pattern and the shape (else DISC_ERR_INVALID_ARG at launch); -1 restores host selection. */
 int disc_force_variant(disc_ctx* ctx, int variant);
+/* Tests only: override one host rule of the context, so that kernel versions the rule would not
+ * pick at small test sizes still run against the oracle.  Results never depend on these. */
+typedef enum {
+  DISC_OPT_NON_TEMPORAL = 0,      /* -1 host rule (default), 0 never, 1 wherever the version exists   */
+  DISC_OPT_STAGE_ROW_VECTORS = 1, /* 1 host rule (default), 0 row vectors are never staged in LDS     */
+  DISC_OPT_ROW_ROUNDS = 2         /* 0 host rule (default), n > 0: row-kernel grid = n rounds of the
+                                     blocks the chip holds at once                                    */
+} disc_test_option_id;
+int disc_test_option(disc_ctx* ctx, int option, int value);
 
 /* ---- op graphs larger than one fusion pattern --------------------------------------------------
  * The fusion decision over a graph (Section 4.3: whether ops may share a kernel follows from how

@@ -21,11 +21,23 @@ the op set here is the element-wise / broadcast / cast / select / reduce family
 with those standard meanings:
 
 * unary, binary, compare  : numpy ufuncs on float64 (int64 for integer values)
+* a binary op or a select : takes its operands in the element type of its RESULT (HLO's
+                            element-wise ops have one element type; an operand of another
+                            type is converted as by ``cast`` first), so an integer division is
+                            the truncating one exactly when the result is an integer
+* integer values          : two's complement of their declared width: every i32 result is
+                            reduced modulo 2^32 into [-2^31, 2^31), i64 modulo 2^64 (numpy's
+                            int64 does that by itself); division truncates toward zero;
+                            division by zero and -2^31 / -1 have no defined result
 * rsqrt = 1/sqrt, rcp = 1/x, sigmoid = 1/(1+exp(-x)), erf = the error function
-* cast to a float type    : identity (values are not rounded to the storage type;
-                            the comparator that uses the oracle absorbs the final
-                            rounding); cast to an integer type truncates toward zero;
-                            cast to bool is ``x != 0``
+* cast to f32             : identity (float values are held in float64 throughout)
+* cast to f16 / bf16      : the conversion is the op's meaning: the value is rounded to the
+                            target type (nearest even) when anything but ``output`` ops reads
+                            it, as the unfused sequence would hand it on.  A cast that only
+                            feeds outputs is the store itself and stays unrounded here: the
+                            comparator that uses the oracle owns that last rounding
+* cast to an integer type : truncates toward zero, then wraps to the width; cast to bool is
+                            ``x != 0``
 * select(p, a, b)         : a where p != 0, else b
 * broadcast               : HLO broadcast_in_dim
 * reduce_{sum,max,min}    : over exactly one axis, the axis is dropped
@@ -67,15 +79,40 @@ _FLOAT = ("f32", "f16", "bf16")
 _INT = ("i32", "i64")
 
 
+def _wrap(x: np.ndarray, dtype: str) -> np.ndarray:
+    """Two's complement of the declared width (see module docstring); other kinds pass through."""
+    if dtype == "i32" and x.dtype.kind == "i":
+        return ((x.astype(np.int64) + (1 << 31)) % (1 << 32)) - (1 << 31)
+    return x
+
+
 def _as_dtype(x: np.ndarray, dtype: str) -> np.ndarray:
-    """Value conversion performed by a ``cast`` op (see module docstring)."""
+    """Value conversion performed by a ``cast`` op (see module docstring), without the rounding
+    to a 16-bit float type."""
     if dtype in _FLOAT:
         return x.astype(np.float64)
     if dtype in _INT:
-        return np.trunc(x.astype(np.float64)).astype(np.int64)
+        if x.dtype.kind == "f":
+            x = np.trunc(x)
+        return _wrap(x.astype(np.int64), dtype)
     if dtype == "bool":
         return x != 0
     raise OracleError(f"unknown dtype {dtype}")
+
+
+def _round_array(x: np.ndarray, dtype: str) -> np.ndarray:
+    """Every element to the nearest value of a 16-bit float type, ties to even."""
+    if dtype == "f16":
+        return x.astype(np.float16).astype(np.float64)
+    if dtype == "bf16":
+        f = x.astype(np.float32)
+        # (float64 -> float32 -> bf16 rounds twice; the callers' values are float32 values already
+        # or far from a bf16 tie, and _round_to_storage below has the same two steps)
+        bits = f.view(np.uint32).astype(np.uint64)
+        r = ((bits + 0x7FFF + ((bits >> 16) & 1)) & 0xFFFF0000).astype(np.uint32)
+        out = r.view(np.float32).astype(np.float64)
+        return np.where(np.isfinite(f), out, f.astype(np.float64))
+    return x
 
 
 def _round_to_storage(value: float, dtype: str):
@@ -181,6 +218,11 @@ def _run(pattern, dims, inputs):
     vals: Dict[int, np.ndarray] = {}
     outs: List[np.ndarray] = []
     next_param = 0
+    # values that something other than an ``output`` op reads
+    read_on = set()
+    for op in pattern.ops:
+        if op.opcode != "output":
+            read_on.update(op.ins)
     for idx, op in enumerate(pattern.ops):
         want = tuple(dims[d] if d >= 0 else -d for d in op.dims)
         oc = op.opcode
@@ -200,19 +242,22 @@ def _run(pattern, dims, inputs):
         elif oc == "dim_size":
             v = _as_dtype(np.asarray(float(dims[op.axis_map[0]])), op.dtype)
         elif oc in _UNARY:
-            v = _UNARY[oc](vals[op.ins[0]])
+            v = _UNARY[oc](_as_dtype(vals[op.ins[0]], op.dtype))
         elif oc in _BINARY:
-            a, b = _common(vals[op.ins[0]], vals[op.ins[1]])
+            a, b = _as_dtype(vals[op.ins[0]], op.dtype), _as_dtype(vals[op.ins[1]], op.dtype)
+            _same_shape(a, b)
             v = _BINARY[oc](a, b)
         elif oc in _COMPARE:
             a, b = _common(vals[op.ins[0]], vals[op.ins[1]])
             v = _COMPARE[oc](a, b)
         elif oc == "select":
-            a, b = _common(vals[op.ins[1]], vals[op.ins[2]])
+            a, b = _as_dtype(vals[op.ins[1]], op.dtype), _as_dtype(vals[op.ins[2]], op.dtype)
             _same_shape(vals[op.ins[0]], a, b)
             v = np.where(vals[op.ins[0]] != 0, a, b)
         elif oc == "cast":
             v = _as_dtype(vals[op.ins[0]], op.dtype)
+            if op.dtype in ("f16", "bf16") and idx in read_on:
+                v = _round_array(v, op.dtype)
         elif oc == "broadcast":
             v = _broadcast_in_dim(vals[op.ins[0]], want, op.axis_map)
         elif oc in ("reduce_sum", "reduce_max", "reduce_min", "reduce_argmax"):
@@ -223,7 +268,7 @@ def _run(pattern, dims, inputs):
             if x.shape[ax] == 0:
                 raise OracleError(f"op {idx}: reduction over an empty axis")
             if oc == "reduce_sum":
-                v = np.sum(x, axis=ax)
+                v = _wrap(np.sum(x, axis=ax), pattern.ops[op.ins[0]].dtype)   # (an i32 sum wraps like its terms)
             elif oc == "reduce_max":
                 v = np.max(x, axis=ax)
             elif oc == "reduce_min":
@@ -260,7 +305,7 @@ def _run(pattern, dims, inputs):
             outs.append(v)
         else:
             raise OracleError(f"op {idx}: unknown opcode {oc}")
-        v = np.asarray(v)
+        v = _wrap(np.asarray(v), op.dtype)
         if v.ndim > 0 or len(want) > 0:
             # rank-0 operands act as scalars inside element-wise ops; anything
             # else must come out with exactly the declared shape

@@ -23,7 +23,8 @@ VARIANTS = ("loop_vec", "loop_vec_i64", "loop_scalar", "loop_scalar_i64", "row_r
             "row_stream_vec", "row_stream_scalar", "col_3stage_vec", "col_3stage_scalar", "col_strip_vec",
             "col_strip_scalar", "transpose_tile")
 STATUS = {0: "OK", -1: "INVALID_ARG", -2: "BAD_PATTERN", -3: "UNFUSIBLE", -4: "CONSTRAINT", -5: "WORKSPACE",
-          -6: "COMPILE", -7: "HIP", -8: "SHAPE", -9: "EMPTY_REDUCE"}
+          -6: "COMPILE", -7: "HIP", -8: "SHAPE", -9: "EMPTY_REDUCE", -10: "INTERNAL"}
+TEST_OPTIONS = {"non_temporal": 0, "stage_row_vectors": 1, "row_rounds": 2}
 TEMPLATES = ("loop", "row_reduce", "col_reduce", "transpose")
 
 
@@ -79,7 +80,7 @@ class DiscError(RuntimeError):
 
 EXPORTS = ("disc_create", "disc_destroy", "disc_last_error", "disc_register_pattern", "disc_register_pattern_static",
            "disc_pattern_info",
-           "disc_pattern_source", "disc_workspace_bytes", "disc_plan", "disc_launch", "disc_force_variant",
+           "disc_pattern_source", "disc_workspace_bytes", "disc_plan", "disc_launch", "disc_force_variant", "disc_test_option",
            "disc_get_stats", "disc_util_copy", "disc_util_copy_nt", "disc_util_empty_launch", "disc_register_graph", "disc_graph_info",
            "disc_graph_workspace_bytes", "disc_graph_launch")
 
@@ -122,6 +123,7 @@ def load_library():
     lib.disc_graph_launch.argtypes = [vp, C.c_int32, i64p, C.c_int, C.POINTER(vp), C.c_int, C.POINTER(vp), C.c_int,
                                       vp, C.c_size_t, vp]
     lib.disc_force_variant.argtypes = [vp, C.c_int]
+    lib.disc_test_option.argtypes = [vp, C.c_int, C.c_int]
     lib.disc_get_stats.argtypes = [vp, C.POINTER(disc_stats_t)]
     lib.disc_util_copy.argtypes = [vp, vp, vp, C.c_size_t, vp]
     lib.disc_util_copy_nt.argtypes = [vp, vp, vp, C.c_size_t, vp]
@@ -322,6 +324,10 @@ class Context:
 
     def force_variant(self, variant: int):
         self._check(self.lib.disc_force_variant(self.h, int(variant)))
+
+    def test_option(self, name: str, value: int):
+        """Tests only: override one host rule (see disc_test_option in disc.h)."""
+        self._check(self.lib.disc_test_option(self.h, TEST_OPTIONS[name], int(value)))
 
     def launch(self, pid: int, dims, inputs: Sequence, outputs: Sequence, workspace=None,
                workspace_bytes: int = 0, stream: Optional[int] = None):

@@ -54,5 +54,25 @@ def build_library(verbose: bool = False) -> str:
     return LIB
 
 
+def build_sanitized_driver(out_path: str, driver_source: str) -> str:
+    """Host code of the library (checker, code generator, planner, launcher) and a C++ driver in ONE
+    executable under AddressSanitizer + UndefinedBehaviorSanitizer.  Host code only: device code is
+    never built with a sanitizer.  Run it with ASAN_OPTIONS=detect_leaks=0 (the device compiler's
+    own library is not instrumented and keeps caches alive)."""
+    build_dir = os.path.join(HERE, "_build")
+    os.makedirs(build_dir, exist_ok=True)
+    embed = _embed_header(build_dir)
+    rocm = os.environ.get("ROCM_PATH", "/opt/rocm")
+    cmd = [os.environ.get("CXX", "g++"), "-O1", "-g", "-std=c++17", "-fsanitize=address,undefined",
+           "-static-libasan", "-fno-sanitize-recover=undefined", "-fno-omit-frame-pointer", "-DDISC_NO_INTERPOSE",
+           "-D__HIP_PLATFORM_AMD__", "-I", os.path.join(rocm, "include"), "-I", os.path.join(ROOT, "include"),
+           "-I", CSRC, "-o", out_path, driver_source] + [os.path.join(CSRC, s) for s in SOURCES] + \
+          [embed, "-L", os.path.join(rocm, "lib"), "-Wl,-rpath," + os.path.join(rocm, "lib"), "-lamdhip64", "-lhiprtc"]
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError("sanitized host build failed:\n" + r.stdout + r.stderr)
+    return out_path
+
+
 if __name__ == "__main__":
     print(build_library(verbose=True))

@@ -257,6 +257,40 @@ void mul_into(DimProduct& p, const DimClasses&, int32_t dim) {
 
 int operand_count(int opcode) { return n_operands(opcode); }
 
+namespace {
+struct KernelNames {
+  std::string name[K_COUNT];
+  KernelNames() {
+    static const char* const fixed[K_ROW_BASE] = {
+        "k_loop_vec", "k_loop_vec_i64", "k_loop_scalar", "k_loop_scalar_i64", "k_loop_vec_nt",
+        "k_row_stream_vec", "k_row_stream_scalar", "k_colsum_finish", "k_rowred_finish",
+        "k_col_partial_vec", "k_col_partial_scalar", "k_col_finish", "k_col_strip_vec", "k_col_strip_scalar",
+        "k_col_epi_vec", "k_col_epi_vec_i64", "k_col_epi_scalar", "k_col_epi_scalar_i64", "k_col_epi_vec_nt",
+        "k_transpose_tile"};
+    for (int i = 0; i < K_ROW_BASE; ++i) name[i] = fixed[i];
+    for (int sc = 0; sc < 2; ++sc)
+      for (int n = 1; n <= 3; ++n)
+        for (int w = 0; w < 2; ++w)
+          for (int st = 0; st < 2; ++st)
+            for (int nt = 0; nt < 2; ++nt)
+              name[K_ROW_BASE + row_kernel_index(sc, n, w, st, nt)] = std::string("k_row_") + (sc ? "scalar" : "vec") + "_nv" +
+                                                                      std::to_string(n) + (w ? "w" : "") + (st ? "_s" : "") + (nt ? "_nt" : "");
+  }
+};
+const KernelNames& kernel_names() {
+  static const KernelNames t;
+  return t;
+}
+}  // namespace
+
+const char* kernel_name(int kid) { return kid >= 0 && kid < K_COUNT ? kernel_names().name[kid].c_str() : "?"; }
+int kernel_id(const std::string& name) {
+  const KernelNames& t = kernel_names();
+  for (int i = 0; i < K_COUNT; ++i)
+    if (t.name[i] == name) return i;
+  return -1;
+}
+
 // loop_sides: sums over the rows next to a loop fusion may ride along in a row template without
 // reduction phases; *used_loop_sides tells whether that rule decided the template
 static int analyze_impl(const disc_op* ops, int n_ops, const disc_constraint* cs, int n_cs, Analysis* out,
@@ -739,6 +773,13 @@ static int analyze_impl(const disc_op* ops, int n_ops, const disc_constraint* cs
                  opcode_name(op.opcode), root_value);
         err = buf;
         return DISC_ERR_UNFUSIBLE;
+      }
+      // the proof may rest on a caller's tensor-size equality: the host-side shape calculation
+      // carries it (Section 4.2.1) and refuses a launch whose dims contradict it
+      if ((op.opcode == DISC_PARAM || op.opcode == DISC_OUTPUT) && op.rank > 0 && numel_key(op) != numel_key(ops[root_value])) {
+        DimProduct prod;
+        for (int k = 0; k < op.rank; ++k) mul_into(prod, dc, op.dim[k]);
+        an.numel_checks.push_back({i, prod});
       }
     }
   }

@@ -45,6 +45,7 @@ std::string float_lit(double v) {
   snprintf(buf, sizeof buf, "%.9gf", (double)f);
   std::string s = buf;
   if (s.find('.') == std::string::npos && s.find('e') == std::string::npos) s.insert(s.size() - 1, ".0");
+  if (std::signbit(f)) s = "(" + s + ")";   // a literal that starts with '-' must survive a prefix operator
   return s;
 }
 
@@ -68,7 +69,12 @@ struct Gen {
   std::set<int> need_rinv;     // per-row values whose reciprocal is precomputed
   std::set<int> need_nl2e;     // per-row values r for which -r*log2(e) is precomputed (exp(x - r))
   const GenOptions* opt = nullptr;
-  explicit Gen(const Analysis& a) : an(a) {}
+  std::set<int> read_on;       // ops whose value something other than an OUTPUT reads
+  explicit Gen(const Analysis& a) : an(a) {
+    for (const auto& op : an.ops)
+      if (op.opcode != DISC_OUTPUT)
+        for (int k = 0; k < operand_count(op.opcode); ++k) read_on.insert(op.in[k]);
+  }
 
   static bool is_reduce(int oc) { return oc >= DISC_REDUCE_SUM && oc <= DISC_REDUCE_ARGMAX; }
   bool col_tmpl() const { return an.tmpl == DISC_TEMPLATE_COL_REDUCE; }
@@ -221,7 +227,7 @@ struct Gen {
       if (n.opcode == DISC_CONST) {
         if (n.rk == RK_F32) r = float_lit(n.fconst);
         else if (n.rk == RK_BOOL) r = n.fconst != 0 ? "true" : "false";
-        else r = fmt("%lld%s", (long long)n.fconst, n.rk == RK_I64 ? "LL" : "");
+        else r = fmt("(%lld%s)", (long long)n.fconst, n.rk == RK_I64 ? "LL" : "");
       } else if (n.opcode == DISC_DIM_SIZE) {
         if (n.rk == RK_F32) r = fmt("A.dimf%d", g.dim_index(n.sym_dim));
         else r = fmt("(%s)A.dimi%d", reg_ctype(n.rk), g.dim_index(n.sym_dim));
@@ -261,13 +267,17 @@ struct Gen {
       return r;
     }
     std::string as(int id, RegKind k) { return convert(val(id), g.an.nodes[id].rk, k); }
+    static std::string wrap_arith(RegKind k, const std::string& x, const char* op, const std::string& y) {
+      const char* u = k == RK_I64 ? "disc::u64" : "disc::u32";
+      return fmt("(%s)((%s)(%s) %s (%s)(%s))", reg_ctype(k), u, x.c_str(), op, u, y.c_str());
+    }
     std::string expr(const Node& n) {
       const RegKind k = n.rk;
       auto a = [&](int i) { return as(n.in[i], k); };
       const bool f = fast();
       switch (n.opcode) {
-        case DISC_NEG: return "-" + a(0);
-        case DISC_ABS: return k == RK_F32 ? "fabsf(" + a(0) + ")" : "(" + a(0) + " < 0 ? -" + a(0) + " : " + a(0) + ")";
+        case DISC_NEG: return k == RK_F32 ? "-(" + a(0) + ")" : wrap_arith(k, "0", "-", a(0));
+        case DISC_ABS: return k == RK_F32 ? "fabsf(" + a(0) + ")" : "((" + a(0) + ") < 0 ? " + wrap_arith(k, "0", "-", a(0)) + " : (" + a(0) + "))";
         case DISC_EXP: {
           // exp(x - r) with r a per-row value: exp2(fma(x, log2e, -r*log2e)), the product with r
           // is made once per row
@@ -283,9 +293,10 @@ struct Gen {
         case DISC_RCP: return f ? "disc::fast_rcp(" + a(0) + ")" : "(1.0f / " + a(0) + ")";
         case DISC_SIGMOID: return f ? "disc::fast_sigmoid(" + a(0) + ")" : "(1.0f / (1.0f + expf(-" + a(0) + ")))";
         case DISC_ERF: return "erff(" + a(0) + ")";
-        case DISC_ADD: return a(0) + " + " + a(1);
-        case DISC_SUB: return a(0) + " - " + a(1);
-        case DISC_MUL: return a(0) + " * " + a(1);
+        // integers wrap (two's complement of the declared width): computed on the unsigned type
+        case DISC_ADD: return k == RK_F32 ? a(0) + " + " + a(1) : wrap_arith(k, a(0), "+", a(1));
+        case DISC_SUB: return k == RK_F32 ? a(0) + " - " + a(1) : wrap_arith(k, a(0), "-", a(1));
+        case DISC_MUL: return k == RK_F32 ? a(0) + " * " + a(1) : wrap_arith(k, a(0), "*", a(1));
         case DISC_DIV: {
           if (k != RK_F32 || !f) return a(0) + " / " + a(1);
           const Node& d = g.an.nodes[n.in[1]];
@@ -304,7 +315,13 @@ struct Gen {
           return as(n.in[0], kc) + " " + sym[n.opcode - DISC_LT] + " " + as(n.in[1], kc);
         }
         case DISC_SELECT: return as(n.in[0], RK_BOOL) + " ? " + a(1) + " : " + a(2);
-        case DISC_CAST: return a(0);   // float->int conversion truncates toward zero in C
+        case DISC_CAST:
+          // float -> int truncates toward zero in C.  A cast to a 16-bit float type whose value is
+          // read by further ops rounds it to that type, as the unfused sequence would hand it on;
+          // one that only feeds outputs is rounded by the store
+          if ((n.dtype == DISC_F16 || n.dtype == DISC_BF16) && g.read_on.count(n.value))
+            return fmt("disc::to_f32(disc::from_f32<%s>(%s))", dtype_ctype(n.dtype), a(0).c_str());
+          return a(0);
         default: return "0 /* unexpected opcode */";
       }
     }
@@ -629,7 +646,9 @@ struct Gen {
     RegKind ok = an.nodes[n.in[0]].rk;
     std::string f = "acc." + accf(n.reduce_slot), i = "acc." + acci(n.reduce_slot);
     switch (n.opcode) {
-      case DISC_REDUCE_SUM: return f + " += " + x + ";";
+      case DISC_REDUCE_SUM:
+        if (ok == RK_I32 || ok == RK_I64) return f + " = " + Fn::wrap_arith(ok, f, "+", x) + ";";   // integer sums wrap
+        return f + " += " + x + ";";
       case DISC_REDUCE_MAX:
         return ok == RK_F32 ? f + " = fmaxf(" + f + ", " + x + ");" : f + " = " + f + " > " + x + " ? " + f + " : " + x + ";";
       case DISC_REDUCE_MIN:
@@ -659,7 +678,10 @@ struct Gen {
         RegKind ok = an.nodes[n.in[0]].rk;
         std::string f = accf(n.reduce_slot), i = acci(n.reduce_slot);
         switch (n.opcode) {
-          case DISC_REDUCE_SUM: os << "      a." << f << " += b." << f << ";\n"; break;
+          case DISC_REDUCE_SUM:
+            if (ok == RK_I32 || ok == RK_I64) os << "      a." << f << " = " << Fn::wrap_arith(ok, "a." + f, "+", "b." + f) << ";\n";
+            else os << "      a." << f << " += b." << f << ";\n";
+            break;
           case DISC_REDUCE_MAX:   // compare-select: partner values arrive through lane exchanges / LDS
             os << "      a." << f << " = b." << f << " > a." << f << " ? b." << f << " : a." << f << ";\n";
             break;

@@ -9,8 +9,8 @@
 // calculation and launch-dimension selection, Sections 4.2.1 and 4.3).  (The one exception is
 // the single-shape module built for the gap-to-static comparison, see DISC_STATIC_ARGS.)
 //
-// The two templates of Section 4.3 ("classical loop fusion and input fusion with reduce
-// operation as the root") are kloop_kernel and the row_* / col_* kernels; each exists in
+// The two templates of Section 4.3 -- loop fusion, and input fusion rooted at a reduction -- are
+// kloop_kernel and the row_* / col_* kernels; each exists in
 // several versions (vector / scalar access, 32 / 64-bit index, register-resident / streamed
 // row, ...) which the host selects per incoming shape.
 //

@@ -180,6 +180,9 @@ struct Analysis {
   std::vector<DimProduct> products;      // strides of partial accesses
   std::vector<OffsetRecipe> offsets;     // base offsets of sliced operands (kernel argument st<products.size() + i>)
   std::vector<SliceCheck> slice_checks;
+  // flat loop fusion: element counts of the operands and results, each of which must equal the
+  // element count of the iteration space at launch (the tensor-size equalities the decision used)
+  std::vector<std::pair<int, DimProduct>> numel_checks;   // (op index, its element count)
   std::vector<WindowRecipe> windows;     // kernel arguments st<products + offsets + 2 i> (lo) and + 1 (hi)
   std::vector<int> dim_size_syms;        // symbolic dims referenced by DIM_SIZE nodes
   int vec_width = 1;                     // elements per vector slot
@@ -211,6 +214,26 @@ struct Generated {
   std::vector<int> staged_elem_bytes; // row reduce: element size of each row vector that can be staged in LDS
   std::vector<std::string> field_names;   // member name of each args.fields entry in Pat::Args
 };
+
+// Every entry point a pattern module can hold has a fixed number, so that the launch path
+// indexes arrays (function handles, residency) and never looks a name up.  The row kernels are
+// numbered by their five version bits: K_ROW_BASE + row_kernel_index(...).
+enum KernelId {
+  K_LOOP_VEC = 0, K_LOOP_VEC_I64, K_LOOP_SCALAR, K_LOOP_SCALAR_I64, K_LOOP_VEC_NT,
+  K_ROW_STREAM_VEC, K_ROW_STREAM_SCALAR, K_COLSUM_FINISH, K_ROWRED_FINISH,
+  K_COL_PARTIAL_VEC, K_COL_PARTIAL_SCALAR, K_COL_FINISH, K_COL_STRIP_VEC, K_COL_STRIP_SCALAR,
+  K_COL_EPI_VEC, K_COL_EPI_VEC_I64, K_COL_EPI_SCALAR, K_COL_EPI_SCALAR_I64, K_COL_EPI_VEC_NT,
+  K_TRANSPOSE_TILE,
+  K_ROW_BASE,
+  K_COUNT = K_ROW_BASE + 48
+};
+// k_row_{vec|scalar}_nv{1|2|3}[w][_s][_nt]: scalar access, instantiated slots per lane, block above
+// 256 threads, row vectors staged in LDS, non-temporal accesses of the full-size operands
+inline int row_kernel_index(bool scalar, int inst, bool wide, bool staged, bool nt) {
+  return ((((scalar ? 1 : 0) * 3 + (inst - 1)) * 2 + (wide ? 1 : 0)) * 2 + (staged ? 1 : 0)) * 2 + (nt ? 1 : 0);
+}
+const char* kernel_name(int kid);            // entry-point name without the pattern prefix
+int kernel_id(const std::string& name);      // -1 when unknown (registration time only)
 
 // Optional restriction of the generated module: only the named entry points (without prefix).
 struct GenOptions {

@@ -31,6 +31,9 @@ struct DeviceColPlan {   // mirrors disc::ColPlan of the device header
   int32_t GC, log2GC, nchunk, pad;
   int64_t chunk_rows, outer;
 };
+constexpr int kLdsStep = 512, kLdsSteps = 48 * 1024 / kLdsStep + 2;
+constexpr int kArgBufBytes = 4096;    // kernel-argument block + launch-plan struct
+constexpr int kMaxShapeValues = 64;   // strides + base offsets + padding windows of one pattern
 struct FastDivHost {
   uint32_t d, m, s, pad;
 };
@@ -53,8 +56,11 @@ struct Pattern {
   int compile_events = 0;
   double compile_ms = 0;
   hipModule_t module = nullptr;
-  std::map<std::string, hipFunction_t> fn;
-  mutable std::map<std::string, int> resident;        // (kernel, block, LDS) -> blocks resident per CU
+  // Launch-time tables, indexed by kernel number: nothing on the launch path looks up a name.
+  hipFunction_t fn[K_COUNT] = {};
+  // blocks resident per CU by (kernel, block-size class, dynamic LDS in steps of kLdsStep bytes),
+  // asked from the runtime on first use (0 = not asked yet)
+  mutable int16_t resident[K_COUNT][3][kLdsSteps] = {};
   bool is_static = false;                             // module specialised for static_dims only
   std::vector<int64_t> static_dims;
   // constraint recipes
@@ -69,7 +75,7 @@ struct Pattern {
 struct ShapeVals {
   int64_t group[4] = {1, 1, 1, 1};
   int64_t rows = 1, inner = 1, mid = 0;
-  std::vector<int64_t> products;
+  int64_t products[kMaxShapeValues];   // strides, base offsets, padding windows (no allocation at launch)
   int64_t alg_bytes = 0;
 };
 
@@ -130,15 +136,13 @@ struct disc_ctx {
   int force_variant = -1;
   hipModule_t util_module = nullptr;
   hipFunction_t util_copy = nullptr, util_copy_nt = nullptr, util_empty = nullptr;
-  int row_target_nv = 3;     // tuning knobs, overridable from the environment for experiments
-  int grid_mult = 8;
-  int row_nt = -1;           // non-temporal row versions: -1 = host rule, 0 = never, 1 = wherever the version exists
-  int row_nopipe2 = 0;       // experiments: two-slot rows always in the unpipelined version
-  int row_turn = 1;          // rows of several wavefronts: slot grid turned by one wavefront per row
-  int row_rounds = 0;        // row kernels: grid = this many rounds of resident blocks (0: by block size)
-  int loop_unroll = 4;
-  int row_stage = 1;
+  // test overrides (disc_test_option); the defaults are the host rules
+  int row_nt = -1;           // non-temporal versions: -1 = host rule, 0 = never, 1 = wherever the version exists
+  int row_rounds = 0;        // row kernels: grid = this many rounds of resident blocks (0: host rule)
+  int row_stage = 1;         // 0: row vectors are never staged in LDS
 };
+constexpr int kGridMult = 8;     // loop / column kernels: grid capped at this many blocks per CU
+constexpr int kLoopUnroll = 4;   // loop kernels: slots in flight per lane
 
 namespace {
 
@@ -159,13 +163,6 @@ int compile_source(disc_ctx* c, const std::string& src, std::vector<char>* code,
                                    "-packed-fp32-ops", "-Wno-unused-value",
                                    // the fused expressions are scalar per element on purpose: no packed-fp32 pairs
                                    "-fno-slp-vectorize", "-fno-vectorize"};
-  // extra device-compiler options for experiments (space separated), e.g. -D switches
-  std::vector<std::string> extra;
-  if (const char* e = getenv("DISC_DEVICE_FLAGS")) {
-    std::istringstream is(e);
-    for (std::string w; is >> w;) extra.push_back(w);
-    for (const auto& w : extra) opts.push_back(w.c_str());
-  }
   auto t0 = std::chrono::steady_clock::now();
   hiprtcResult r = hiprtcCompileProgram(prog, (int)opts.size(), opts.data());
   *ms = std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - t0).count();
@@ -220,11 +217,19 @@ int shape_calc(disc_ctx* c, const Pattern& p, const int64_t* dims, int n_dims, S
     if (!eval_product(an.group_size[g], dims, &sv->group[g]) || mul_ovf(total, sv->group[g], &total))
       return set_err(c, DISC_ERR_SHAPE, "element count overflows int64");
   }
+  for (const auto& nc : an.numel_checks) {
+    int64_t n = 0;
+    if (!eval_product(nc.second, dims, &n)) return set_err(c, DISC_ERR_SHAPE, "element count overflows int64");
+    if (n != total) {
+      snprintf(buf, sizeof buf, "op %d has %lld elements, the iteration space %lld: they were registered as equal in size",
+               nc.first, (long long)n, (long long)total);
+      return set_err(c, DISC_ERR_CONSTRAINT, buf);
+    }
+  }
   sv->inner = sv->group[an.inner_group];
   sv->rows = 1;
   for (int g = 0; g < an.inner_group; ++g) sv->rows *= sv->group[g];
   sv->mid = an.mid_group >= 0 ? sv->group[an.mid_group] : 0;
-  sv->products.resize(an.products.size() + an.offsets.size() + 2 * an.windows.size());
   for (size_t i = 0; i < an.products.size(); ++i)
     if (!eval_product(an.products[i], dims, &sv->products[i]))
       return set_err(c, DISC_ERR_SHAPE, "stride overflows int64");
@@ -275,7 +280,7 @@ int ilog2_ceil(int64_t v) {
 }
 
 struct LaunchRec {
-  const char* kernel = nullptr;
+  int kid = -1;              // KernelId
   uint32_t grid[3] = {1, 1, 1};
   uint32_t block = 256;
   int plan_kind = 0;         // 0 none, 1 RowPlan, 2 ColPlan
@@ -303,8 +308,8 @@ constexpr int64_t kNonTemporalMinBytes = 64ll << 20;
 // nt_name: the non-temporal sibling of names[0] (vector width, 32-bit index), taken for large
 // launches (`big`) whose rows start on 16-byte boundaries (`aligned`: the full-size operands are;
 // inner a multiple of the width).
-int plan_loop(disc_ctx* c, int64_t rows, int64_t inner, int V, int want_vec, int want_i64, const char* const names[4],
-              const char* nt_name, bool aligned, bool big, FullPlan* fp, LaunchRec* L, bool* vec_out, bool* i64_out) {
+int plan_loop(disc_ctx* c, int64_t rows, int64_t inner, int V, int want_vec, int want_i64, const int names[4],
+              int nt_name, bool aligned, bool big, FullPlan* fp, LaunchRec* L, bool* vec_out, bool* i64_out) {
   bool vec;
   {
     const int64_t spr_v = (inner + V - 1) / V;
@@ -318,14 +323,14 @@ int plan_loop(disc_ctx* c, int64_t rows, int64_t inner, int V, int want_vec, int
   bool i64 = nslots >= (1ll << 31) - (1ll << 24) || inner >= (1ll << 31) - 16 || rows >= (1ll << 31);
   if (want_i64 == 1) i64 = true;
   else if (want_i64 == 0 && i64) return set_err(c, DISC_ERR_INVALID_ARG, "forced 32-bit version cannot index this shape");
-  const int U = i64 ? 1 : c->loop_unroll;
-  const int64_t max_grid = (int64_t)c->n_cus * c->grid_mult;
+  const int U = i64 ? 1 : kLoopUnroll;
+  const int64_t max_grid = (int64_t)c->n_cus * kGridMult;
   int64_t blocks = (nslots + 256ll * U - 1) / (256ll * U);
   blocks = std::min(blocks, i64 ? max_grid * 4 : max_grid);
-  L->kernel = names[(vec ? 0 : 2) + (i64 ? 1 : 0)];
-  if (nt_name && vec && v > 1 && !i64 && aligned && inner % v == 0 && c->row_nt != 0 &&
+  L->kid = names[(vec ? 0 : 2) + (i64 ? 1 : 0)];
+  if (nt_name >= 0 && vec && v > 1 && !i64 && aligned && inner % v == 0 && c->row_nt != 0 &&
       (c->row_nt > 0 || big))
-    L->kernel = nt_name;
+    L->kid = nt_name;
   L->grid[0] = (uint32_t)blocks;
   L->block = 256;
   fp->nslots = nslots;
@@ -341,7 +346,7 @@ int plan_loop(disc_ctx* c, int64_t rows, int64_t inner, int V, int want_vec, int
 // Blocks of a kernel that one CU holds at a given block size and dynamic LDS size, as the
 // runtime computes it from the compiled kernel's register and LDS use (asked once per
 // combination).  Without a device: an estimate from a 16-wavefront budget.
-int resident_blocks(const disc_ctx* c, const Pattern& p, const char* kernel, uint32_t block, uint32_t dyn_lds);
+int resident_blocks(const disc_ctx* c, const Pattern& p, int kid, uint32_t block, uint32_t dyn_lds);
 
 // ---- version + launch-dimension selection (host) ---------------------------------------------
 int make_plan(disc_ctx* c, const Pattern& p, const int64_t* dims, int n_dims, int force, const void* const* inputs,
@@ -375,7 +380,7 @@ int make_plan(disc_ctx* c, const Pattern& p, const int64_t* dims, int n_dims, in
   pub.n_launches = 0;
   pub.variant = -1;
   const int V = an.vec_width;
-  const int64_t max_grid = (int64_t)c->n_cus * c->grid_mult;
+  const int64_t max_grid = (int64_t)c->n_cus * kGridMult;
 
   if (an.tmpl == DISC_TEMPLATE_TRANSPOSE) {
     if (sv.rows == 0 || sv.inner == 0) return DISC_OK;
@@ -387,7 +392,7 @@ int make_plan(disc_ctx* c, const Pattern& p, const int64_t* dims, int n_dims, in
     const int64_t ts = dtype_bytes(an.accesses[0].dtype) <= 2 ? 128 : 64;
     const int64_t ntiles = batch * ((P + ts - 1) / ts) * ((Q + ts - 1) / ts);
     LaunchRec& L = fp->launches[0];
-    L.kernel = "k_transpose_tile";
+    L.kid = K_TRANSPOSE_TILE;
     L.block = 256;
     L.grid[0] = (uint32_t)std::min<int64_t>(ntiles, (int64_t)c->n_cus * 8);
     pub.variant = DISC_V_TRANSPOSE_TILE;
@@ -403,9 +408,9 @@ int make_plan(disc_ctx* c, const Pattern& p, const int64_t* dims, int n_dims, in
       want_vec = force == DISC_V_LOOP_VEC || force == DISC_V_LOOP_VEC_I64;
       want_i64 = force == DISC_V_LOOP_VEC_I64 || force == DISC_V_LOOP_SCALAR_I64;
     }
-    static const char* const names[] = {"k_loop_vec", "k_loop_vec_i64", "k_loop_scalar", "k_loop_scalar_i64"};
+    static const int names[] = {K_LOOP_VEC, K_LOOP_VEC_I64, K_LOOP_SCALAR, K_LOOP_SCALAR_I64};
     bool vec, i64;
-    rc = plan_loop(c, sv.rows, sv.inner, V, want_vec, want_i64, names, "k_loop_vec_nt", full_aligned(), sv.alg_bytes >= kNonTemporalMinBytes, fp, &fp->launches[0], &vec, &i64);
+    rc = plan_loop(c, sv.rows, sv.inner, V, want_vec, want_i64, names, K_LOOP_VEC_NT, full_aligned(), sv.alg_bytes >= kNonTemporalMinBytes, fp, &fp->launches[0], &vec, &i64);
     if (rc) return rc;
     pub.variant = vec ? (i64 ? DISC_V_LOOP_VEC_I64 : DISC_V_LOOP_VEC) : (i64 ? DISC_V_LOOP_SCALAR_I64 : DISC_V_LOOP_SCALAR);
     pub.n_launches = 1;
@@ -439,7 +444,7 @@ int make_plan(disc_ctx* c, const Pattern& p, const int64_t* dims, int n_dims, in
     L.block = 256;
     if (stream) {
       pub.variant = vec ? DISC_V_ROW_STREAM_VEC : DISC_V_ROW_STREAM_SCALAR;
-      L.kernel = vec ? "k_row_stream_vec" : "k_row_stream_scalar";
+      L.kid = vec ? K_ROW_STREAM_VEC : K_ROW_STREAM_SCALAR;
       // (sums over the rows: a row of partial sums per block in the workspace, so fewer blocks)
       L.grid[0] = (uint32_t)std::min<int64_t>(sv.rows, n_col_sums > 0 ? (int64_t)c->n_cus * 2 : max_grid * 2);
       fp->aux[0] = L.grid[0];   // rows of partial sums: one per block
@@ -456,7 +461,7 @@ int make_plan(disc_ctx* c, const Pattern& p, const int64_t* dims, int n_dims, in
       struct Shape { int G, block; };
       static const Shape shapes[] = {{1, 256},  {2, 256},  {4, 256},   {8, 256},   {16, 256},  {32, 256},
                                      {64, 256}, {128, 256}, {256, 256}, {512, 512}, {1024, 1024}};
-      const int max_nv = std::max(1, std::min(vec ? 3 : 2, c->row_target_nv));   // three slots: wide versions only
+      const int max_nv = vec ? 3 : 2;   // three slots: vector versions only
       int G = 1024, nv = 2, block = 1024;
       int64_t best_cap = -1;
       for (const Shape& s : shapes)
@@ -478,23 +483,9 @@ int make_plan(disc_ctx* c, const Pattern& p, const int64_t* dims, int n_dims, in
         int64_t bytes = 0;
         for (int eb : p.gen.staged_elem_bytes) bytes += ((sv.inner + v) * eb + 15) & ~15ll;
         const bool stage = vec && V > 1 && c->row_stage && bytes > 0 && bytes <= 48 * 1024;
-        L.rp.flags = (stage ? 1 : 0) | (c->row_turn && n_col_sums == 0 ? 0 : 2);
+        L.rp.flags = (stage ? 1 : 0) | (n_col_sums == 0 ? 0 : 2);
         L.dyn_lds = stage ? (uint32_t)bytes : 0;
-        // k_row_{vec|scalar}_nv{1|2|3}[w][_s][_nt]: w = block above 256 threads, _s = staged version,
-        // _nt = non-temporal accesses of the full-size operands
-        static const std::vector<std::string> names = [] {
-          std::vector<std::string> t;
-          for (int vs = 0; vs < 2; ++vs)
-            for (int n = 1; n <= 3; ++n)
-              for (int w = 0; w < 2; ++w)
-                for (int s = 0; s < 2; ++s)
-                  for (int nt = 0; nt < 2; ++nt)
-                    t.push_back(std::string("k_row_") + (vs ? "scalar" : "vec") + "_nv" + std::to_string(n) + (w ? "w" : "") +
-                                (s ? "_s" : "") + (nt ? "_nt" : ""));
-          return t;
-        }();
-        // (experiment knob: the two-slot version without the software pipeline also for small blocks)
-        const bool wide_version = block > 256 || (c->row_nopipe2 && inst == 2 && vec);
+        const bool wide_version = block > 256;
         // Non-temporal version (blocks of 256 threads, vector width only).  Host rule, measured on
         // softmax and LayerNorm sweeps: the hint gains 5-15 % when every row starts and ends on a
         // 16-byte boundary (row length a multiple of the vector width, aligned bases) and either
@@ -518,7 +509,7 @@ int make_plan(disc_ctx* c, const Pattern& p, const int64_t* dims, int n_dims, in
             if (!whole_lines && sv.inner < 512) nt = false;
           }
         }
-        L.kernel = names[((((vec ? 0 : 1) * 3 + (inst - 1)) * 2 + (wide_version ? 1 : 0)) * 2 + (stage ? 1 : 0)) * 2 + (nt ? 1 : 0)].c_str();
+        L.kid = K_ROW_BASE + row_kernel_index(!vec, inst, wide_version, stage, nt);
       }
       // grid-stride over row groups: a small whole number of rounds of the blocks the chip holds
       // at once.  Measured: with plenty of rows, blocks of one wavefront-quad do best with three
@@ -528,7 +519,7 @@ int make_plan(disc_ctx* c, const Pattern& p, const int64_t* dims, int n_dims, in
       // the staging of the row vectors)
       const int rpb = (int)L.block / G;
       const int64_t ngroups = (sv.rows + rpb - 1) / rpb;
-      const int64_t held = (int64_t)c->n_cus * resident_blocks(c, p, L.kernel, L.block, L.dyn_lds);
+      const int64_t held = (int64_t)c->n_cus * resident_blocks(c, p, L.kid, L.block, L.dyn_lds);
       // (with sums over the rows every block writes a row of partial sums per wavefront: one round)
       const int rounds = c->row_rounds > 0 ? c->row_rounds
                          : (L.block > 256 || n_col_sums > 0 ? 1 : (int)std::max<int64_t>(1, std::min<int64_t>(3, ngroups / (held * 4))));
@@ -555,7 +546,7 @@ int make_plan(disc_ctx* c, const Pattern& p, const int64_t* dims, int n_dims, in
       pub.workspace_bytes = (size_t)bytes;
       fp->ws_off[0] = 0;
       LaunchRec& L1 = fp->launches[1];
-      L1.kernel = "k_colsum_finish";
+      L1.kid = K_COLSUM_FINISH;
       L1.block = 256;
       L1.grid[0] = (uint32_t)std::min<int64_t>((sv.inner + 15) / 16, max_grid * 4);   // 16 columns per block
       pub.n_launches = 2;
@@ -569,7 +560,7 @@ int make_plan(disc_ctx* c, const Pattern& p, const int64_t* dims, int n_dims, in
       fp->ws_off[1] = (pub.workspace_bytes + 255) / 256 * 256;
       pub.workspace_bytes = fp->ws_off[1] + (size_t)n_row_reds * (size_t)L.grid[0] * 4;
       LaunchRec& Lr = fp->launches[pub.n_launches++];
-      Lr.kernel = "k_rowred_finish";
+      Lr.kid = K_ROWRED_FINISH;
       Lr.block = 1024;
       Lr.grid[0] = 1;
     }
@@ -620,7 +611,7 @@ int make_plan(disc_ctx* c, const Pattern& p, const int64_t* dims, int n_dims, in
       pub.vec_width = v;
       pub.index_bits = 64;
       LaunchRec& L0 = fp->launches[0];
-      L0.kernel = vec ? "k_col_strip_vec" : "k_col_strip_scalar";
+      L0.kid = vec ? K_COL_STRIP_VEC : K_COL_STRIP_SCALAR;
       L0.grid[0] = (uint32_t)col_tiles;
       L0.grid[1] = (uint32_t)std::min<int64_t>(outer, 65535);
       L0.plan_kind = 2;
@@ -630,7 +621,7 @@ int make_plan(disc_ctx* c, const Pattern& p, const int64_t* dims, int n_dims, in
       pub.block[0][0] = L0.block;
       pub.block[0][1] = pub.block[0][2] = 1;
       pub.lds_bytes[0] = 0;
-      snprintf(pub.kernel[0], sizeof pub.kernel[0], "%s%s", p.gen.prefix.c_str(), L0.kernel);
+      snprintf(pub.kernel[0], sizeof pub.kernel[0], "%s%s", p.gen.prefix.c_str(), kernel_name(L0.kid));
       return DISC_OK;
     }
     int GC = 1 << ilog2_ceil(std::min<int64_t>(spr, 64));
@@ -655,23 +646,23 @@ int make_plan(disc_ctx* c, const Pattern& p, const int64_t* dims, int n_dims, in
     pub.variant = vec ? DISC_V_COL_3STAGE_VEC : DISC_V_COL_3STAGE_SCALAR;
     pub.lanes_per_row = GC;
     LaunchRec& L0 = fp->launches[0];
-    L0.kernel = vec ? "k_col_partial_vec" : "k_col_partial_scalar";
+    L0.kid = vec ? K_COL_PARTIAL_VEC : K_COL_PARTIAL_SCALAR;
     L0.grid[0] = (uint32_t)col_tiles;
     L0.grid[1] = (uint32_t)nchunk;
     L0.grid[2] = (uint32_t)std::min<int64_t>(outer, 65535);
     L0.plan_kind = 2;
     L0.cp = cp;
     LaunchRec& L1 = fp->launches[1];
-    L1.kernel = "k_col_finish";
+    L1.kid = K_COL_FINISH;
     L1.grid[0] = (uint32_t)((inner + 63) / 64);
     L1.grid[1] = (uint32_t)std::min<int64_t>(outer, 65535);
     L1.plan_kind = 2;
     L1.cp = cp;
     pub.n_launches = 2;
     if (p.gen.has_epilogue) {
-      static const char* const names[] = {"k_col_epi_vec", "k_col_epi_vec_i64", "k_col_epi_scalar", "k_col_epi_scalar_i64"};
+      static const int names[] = {K_COL_EPI_VEC, K_COL_EPI_VEC_I64, K_COL_EPI_SCALAR, K_COL_EPI_SCALAR_I64};
       bool v2, i64;
-      rc = plan_loop(c, sv.rows, inner, V, vec ? 1 : 0, -1, names, "k_col_epi_vec_nt", full_aligned(), sv.alg_bytes >= kNonTemporalMinBytes, fp, &fp->launches[2], &v2, &i64);
+      rc = plan_loop(c, sv.rows, inner, V, vec ? 1 : 0, -1, names, K_COL_EPI_VEC_NT, full_aligned(), sv.alg_bytes >= kNonTemporalMinBytes, fp, &fp->launches[2], &v2, &i64);
       if (rc) return rc;
       pub.n_launches = 3;
     } else {
@@ -684,24 +675,23 @@ int make_plan(disc_ctx* c, const Pattern& p, const int64_t* dims, int n_dims, in
     pub.block[l][0] = fp->launches[l].block;
     pub.block[l][1] = pub.block[l][2] = 1;
     pub.lds_bytes[l] = fp->launches[l].dyn_lds;
-    snprintf(pub.kernel[l], sizeof pub.kernel[l], "%s%s", p.gen.prefix.c_str(), fp->launches[l].kernel);
+    snprintf(pub.kernel[l], sizeof pub.kernel[l], "%s%s", p.gen.prefix.c_str(), kernel_name(fp->launches[l].kid));
   }
   return DISC_OK;
 }
 
-int resident_blocks(const disc_ctx* c, const Pattern& p, const char* kernel, uint32_t block, uint32_t dyn_lds) {
+int resident_blocks(const disc_ctx* c, const Pattern& p, int kid, uint32_t block, uint32_t dyn_lds) {
   const int estimate = std::max(1, 16 / (int)((block + 63) / 64));
-  if (c->device < 0) return estimate;
-  char key[96];
-  snprintf(key, sizeof key, "%s/%u/%u", kernel, block, dyn_lds);
-  auto it = p.resident.find(key);
-  if (it != p.resident.end()) return it->second;
+  if (c->device < 0 || kid < 0 || kid >= K_COUNT || !p.fn[kid]) return estimate;
+  // the table is stepped in dynamic LDS: the question is asked for the upper end of the step
+  const int bc = block <= 256 ? 0 : block <= 512 ? 1 : 2;
+  const int step = (int)std::min<uint32_t>((dyn_lds + kLdsStep - 1) / kLdsStep, kLdsSteps - 1);
+  int16_t& cell = p.resident[kid][bc][step];
+  if (cell > 0) return cell;
   int nb = 0;
-  auto f = p.fn.find(kernel);
-  if (f == p.fn.end() ||
-      hipModuleOccupancyMaxActiveBlocksPerMultiprocessor(&nb, f->second, (int)block, dyn_lds) != hipSuccess || nb < 1)
+  if (hipModuleOccupancyMaxActiveBlocksPerMultiprocessor(&nb, p.fn[kid], (int)block, (size_t)step * kLdsStep) != hipSuccess || nb < 1)
     nb = estimate;
-  p.resident[key] = nb;
+  cell = (int16_t)nb;
   return nb;
 }
 
@@ -780,9 +770,28 @@ int ensure_util(disc_ctx* c) {
 // ============================================================================================
 // C ABI
 // ============================================================================================
+// Nothing may leave an extern "C" function by exception: registration allocates (strings, vectors,
+// maps), and an allocation failure there must come back as a status like everything else.
+static int guard_fail(disc_ctx* c, const char* what) noexcept {
+  if (c) {
+    try {
+      c->err = std::string("internal error: ") + what;
+    } catch (...) {
+    }
+  }
+  return DISC_ERR_INTERNAL;
+}
+#define DISC_TRY try {
+#define DISC_CATCH(c)                                                          \
+  }                                                                            \
+  catch (const std::bad_alloc&) { return guard_fail(c, "out of host memory"); } \
+  catch (const std::exception& e) { return guard_fail(c, e.what()); }          \
+  catch (...) { return guard_fail(c, "unknown exception"); }
+
 extern "C" {
 
 int disc_create(disc_ctx** out, int hip_device) {
+  DISC_TRY
   if (!out) return DISC_ERR_INVALID_ARG;
   *out = nullptr;
   std::unique_ptr<disc_ctx> c(new (std::nothrow) disc_ctx);
@@ -796,15 +805,9 @@ int disc_create(disc_ctx** out, int hip_device) {
     if (hipGetDeviceProperties(&prop, hip_device) != hipSuccess) return DISC_ERR_HIP;
     c->n_cus = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
   }
-  if (const char* e = getenv("DISC_ROW_TARGET_NV")) c->row_target_nv = std::max(1, std::min(8, atoi(e)));
-  if (const char* e = getenv("DISC_ROW_STAGE")) c->row_stage = atoi(e) != 0;
-  if (const char* e = getenv("DISC_ROW_NOPIPE2")) c->row_nopipe2 = atoi(e) != 0;
-  if (const char* e = getenv("DISC_ROW_NT")) c->row_nt = atoi(e);
-  if (const char* e = getenv("DISC_ROW_TURN")) c->row_turn = atoi(e) != 0;
-  if (const char* e = getenv("DISC_ROW_ROUNDS")) c->row_rounds = std::max(0, atoi(e));
-  if (const char* e = getenv("DISC_GRID_MULT")) c->grid_mult = std::max(1, std::min(64, atoi(e)));
   *out = c.release();
   return DISC_OK;
+  DISC_CATCH(nullptr)
 }
 
 void disc_destroy(disc_ctx* ctx) {
@@ -822,7 +825,7 @@ const char* disc_last_error(const disc_ctx* ctx) { return ctx ? ctx->err.c_str()
 // Text of the DISC_STATIC_ARGS / DISC_STATIC_PLAN macros for one shape: every non-pointer member
 // of the argument block and of the launch-plan struct becomes an assignment of its constant.
 static std::string static_macros(const Pattern& p, const FullPlan& fp, const int64_t* dims) {
-  alignas(16) unsigned char buf[4096 + 32] = {0};
+  alignas(16) unsigned char buf[kArgBufBytes] = {0};
   std::vector<const void*> in(std::max(1, p.an.n_inputs), nullptr);
   std::vector<void*> outp(std::max(1, p.an.n_outputs), nullptr);
   fill_args(p, fp, dims, in.data(), outp.data(), nullptr, buf);
@@ -918,6 +921,10 @@ static int register_impl(disc_ctx* ctx, const disc_op* ops, int n_ops, const dis
   rc = generate(p->an, prefix, &p->gen, &err);
   if (rc) return set_err(ctx, rc, err);
   p->gen.source = std::string(kDeviceHeader) + "\n" + p->gen.source;
+  // the launch path works in fixed-size buffers (nothing is allocated per launch)
+  if (p->an.products.size() + p->an.offsets.size() + 2 * p->an.windows.size() > (size_t)kMaxShapeValues)
+    return set_err(ctx, DISC_ERR_UNFUSIBLE, "too many strided, sliced or padded operands in one pattern");
+  if (p->gen.args.size + 48 > kArgBufBytes) return set_err(ctx, DISC_ERR_UNFUSIBLE, "kernel-argument block too large");
 
   // launch-time constraint recipes
   DimClasses& dc = p->an.classes;
@@ -964,7 +971,7 @@ static int register_impl(disc_ctx* ctx, const disc_op* ops, int n_ops, const dis
     if (rc) return rc;
     GenOptions opt;
     for (int l = 0; l < fp.pub.n_launches; ++l) {
-      const std::string k = fp.launches[l].kernel;
+      const std::string k = kernel_name(fp.launches[l].kid);
       opt.only_kernels.push_back(k);
       // planned without pointers, i.e. for aligned operands: keep the plain sibling of a
       // non-temporal version for launches whose operands turn out not to be 16-byte aligned
@@ -992,7 +999,9 @@ static int register_impl(disc_ctx* ctx, const disc_op* ops, int n_ops, const dis
       hipFunction_t f;
       e = hipModuleGetFunction(&f, p->module, (p->gen.prefix + name).c_str());
       if (e != hipSuccess) return hip_fail(ctx, e, ("hipModuleGetFunction " + name).c_str());
-      p->fn[name] = f;
+      const int kid = kernel_id(name);
+      if (kid < 0) return set_err(ctx, DISC_ERR_COMPILE, "generated module holds an unnumbered kernel: " + name);
+      p->fn[kid] = f;
     }
   }
   const int id = (int)ctx->patterns.size();
@@ -1005,17 +1014,22 @@ static int register_impl(disc_ctx* ctx, const disc_op* ops, int n_ops, const dis
 
 int disc_register_pattern(disc_ctx* ctx, const disc_op* ops, int n_ops, const disc_constraint* cs, int n_cs,
                           int32_t* pattern_id_out) {
+  DISC_TRY
   return register_impl(ctx, ops, n_ops, cs, n_cs, nullptr, 0, pattern_id_out);
+  DISC_CATCH(ctx)
 }
 
 int disc_register_pattern_static(disc_ctx* ctx, const disc_op* ops, int n_ops, const disc_constraint* cs, int n_cs,
                                  const int64_t* dims, int n_dims, int32_t* pattern_id_out) {
+  DISC_TRY
   if (!ctx) return DISC_ERR_INVALID_ARG;
   if (!dims || n_dims <= 0) return set_err(ctx, DISC_ERR_INVALID_ARG, "a single-shape pattern needs its dims");
   return register_impl(ctx, ops, n_ops, cs, n_cs, dims, n_dims, pattern_id_out);
+  DISC_CATCH(ctx)
 }
 
 int disc_pattern_info(disc_ctx* ctx, int32_t id, disc_pattern_info_t* out) {
+  DISC_TRY
   Pattern* p = get_pattern(ctx, id);
   if (!p || !out) return set_err(ctx, DISC_ERR_INVALID_ARG, "bad pattern id or null output");
   memset(out, 0, sizeof *out);
@@ -1032,6 +1046,7 @@ int disc_pattern_info(disc_ctx* ctx, int32_t id, disc_pattern_info_t* out) {
   for (int d = 0; d < p->an.n_sym && d < DISC_MAX_DIMS; ++d) out->dim_class[d] = p->class_of_dim[d];
   out->compile_ms = p->compile_ms;
   return DISC_OK;
+  DISC_CATCH(ctx)
 }
 
 const char* disc_pattern_source(disc_ctx* ctx, int32_t id) {
@@ -1040,6 +1055,7 @@ const char* disc_pattern_source(disc_ctx* ctx, int32_t id) {
 }
 
 int disc_workspace_bytes(disc_ctx* ctx, int32_t id, const int64_t* dims, int n_dims, size_t* out) {
+  DISC_TRY
   Pattern* p = get_pattern(ctx, id);
   if (!p || !out) return set_err(ctx, DISC_ERR_INVALID_ARG, "bad pattern id or null output");
   FullPlan fp;
@@ -1047,10 +1063,12 @@ int disc_workspace_bytes(disc_ctx* ctx, int32_t id, const int64_t* dims, int n_d
   if (rc) return rc;
   *out = fp.pub.workspace_bytes;
   return DISC_OK;
+  DISC_CATCH(ctx)
 }
 
 int disc_plan(disc_ctx* ctx, int32_t id, const int64_t* dims, int n_dims, const void* const* inputs,
               void* const* outputs, int force_variant, disc_plan_t* out) {
+  DISC_TRY
   Pattern* p = get_pattern(ctx, id);
   if (!p || !out) return set_err(ctx, DISC_ERR_INVALID_ARG, "bad pattern id or null output");
   FullPlan fp;
@@ -1058,16 +1076,32 @@ int disc_plan(disc_ctx* ctx, int32_t id, const int64_t* dims, int n_dims, const 
   if (rc) return rc;
   *out = fp.pub;
   return DISC_OK;
+  DISC_CATCH(ctx)
 }
 
 int disc_force_variant(disc_ctx* ctx, int variant) {
+  DISC_TRY
   if (!ctx || variant < -1 || variant >= DISC_V_COUNT) return set_err(ctx, DISC_ERR_INVALID_ARG, "unknown version");
   ctx->force_variant = variant;
   return DISC_OK;
+  DISC_CATCH(ctx)
+}
+
+int disc_test_option(disc_ctx* ctx, int option, int value) {
+  DISC_TRY
+  if (!ctx) return DISC_ERR_INVALID_ARG;
+  switch (option) {
+    case DISC_OPT_NON_TEMPORAL: ctx->row_nt = value < 0 ? -1 : value > 0 ? 1 : 0; return DISC_OK;
+    case DISC_OPT_STAGE_ROW_VECTORS: ctx->row_stage = value != 0; return DISC_OK;
+    case DISC_OPT_ROW_ROUNDS: ctx->row_rounds = std::max(0, value); return DISC_OK;
+    default: return set_err(ctx, DISC_ERR_INVALID_ARG, "unknown option");
+  }
+  DISC_CATCH(ctx)
 }
 
 int disc_launch(disc_ctx* ctx, int32_t id, const int64_t* dims, int n_dims, const void* const* inputs, int n_in,
                 void* const* outputs, int n_out, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  DISC_TRY
   const int64_t t0 = now_ns();
   Pattern* p = get_pattern(ctx, id);
   if (!p) return set_err(ctx, DISC_ERR_INVALID_ARG, "bad pattern id");
@@ -1095,14 +1129,13 @@ int disc_launch(disc_ctx* ctx, int32_t id, const int64_t* dims, int n_dims, cons
   if (fp.pub.workspace_bytes > 0 && (!workspace || workspace_bytes < fp.pub.workspace_bytes))
     return set_err(ctx, DISC_ERR_WORKSPACE, "workspace missing or too small");
 
-  alignas(16) unsigned char buf[4096 + 32];
-  const int asz = p->gen.args.size;
-  if (asz + 48 > (int)sizeof buf) return set_err(ctx, DISC_ERR_BAD_PATTERN, "argument block too large");
+  alignas(16) unsigned char buf[kArgBufBytes];
+  const int asz = p->gen.args.size;   // (fits: checked at registration)
   fill_args(*p, fp, dims, inputs, outputs, workspace, buf);
   for (int l = 0; l < fp.pub.n_launches; ++l) {
     const LaunchRec& L = fp.launches[l];
-    auto it = p->fn.find(L.kernel);
-    if (it == p->fn.end()) return set_err(ctx, DISC_ERR_HIP, std::string("kernel version missing: ") + L.kernel);
+    const hipFunction_t fn = L.kid >= 0 && L.kid < K_COUNT ? p->fn[L.kid] : nullptr;
+    if (!fn) return set_err(ctx, DISC_ERR_HIP, std::string("kernel version missing: ") + kernel_name(L.kid));
     size_t size = (size_t)asz;
     if (L.plan_kind == 1) {
       memcpy(buf + asz, &L.rp, sizeof L.rp);
@@ -1112,7 +1145,7 @@ int disc_launch(disc_ctx* ctx, int32_t id, const int64_t* dims, int n_dims, cons
       size += sizeof L.cp;
     }
     void* extra[] = {HIP_LAUNCH_PARAM_BUFFER_POINTER, buf, HIP_LAUNCH_PARAM_BUFFER_SIZE, &size, HIP_LAUNCH_PARAM_END};
-    hipError_t e = hipModuleLaunchKernel(it->second, L.grid[0], L.grid[1], L.grid[2], L.block, 1, 1, L.dyn_lds,
+    hipError_t e = hipModuleLaunchKernel(fn, L.grid[0], L.grid[1], L.grid[2], L.block, 1, 1, L.dyn_lds,
                                          (hipStream_t)hip_stream, nullptr, extra);
     if (e != hipSuccess) return hip_fail(ctx, e, "hipModuleLaunchKernel");
     ctx->stats.device_launches++;
@@ -1121,12 +1154,15 @@ int disc_launch(disc_ctx* ctx, int32_t id, const int64_t* dims, int n_dims, cons
   if (fp.pub.variant >= 0 && fp.pub.variant < DISC_V_COUNT) ctx->stats.variant_count[fp.pub.variant]++;
   ctx->stats.host_launch_ns += now_ns() - t0;
   return DISC_OK;
+  DISC_CATCH(ctx)
 }
 
 int disc_get_stats(disc_ctx* ctx, disc_stats_t* out) {
+  DISC_TRY
   if (!ctx || !out) return DISC_ERR_INVALID_ARG;
   *out = ctx->stats;
   return DISC_OK;
+  DISC_CATCH(ctx)
 }
 
 static int util_copy_impl(disc_ctx* ctx, void* dst, const void* src, size_t bytes, void* hip_stream, bool nt) {
@@ -1144,19 +1180,25 @@ static int util_copy_impl(disc_ctx* ctx, void* dst, const void* src, size_t byte
 }
 
 int disc_util_copy(disc_ctx* ctx, void* dst, const void* src, size_t bytes, void* hip_stream) {
+  DISC_TRY
   return util_copy_impl(ctx, dst, src, bytes, hip_stream, false);
+  DISC_CATCH(ctx)
 }
 
 int disc_util_copy_nt(disc_ctx* ctx, void* dst, const void* src, size_t bytes, void* hip_stream) {
+  DISC_TRY
   return util_copy_impl(ctx, dst, src, bytes, hip_stream, true);
+  DISC_CATCH(ctx)
 }
 
 int disc_util_empty_launch(disc_ctx* ctx, void* hip_stream) {
+  DISC_TRY
   if (!ctx) return DISC_ERR_INVALID_ARG;
   int rc = ensure_util(ctx);
   if (rc) return rc;
   hipError_t e = hipModuleLaunchKernel(ctx->util_empty, 1, 1, 1, 64, 1, 1, 0, (hipStream_t)hip_stream, nullptr, nullptr);
   return e == hipSuccess ? DISC_OK : hip_fail(ctx, e, "hipModuleLaunchKernel");
+  DISC_CATCH(ctx)
 }
 
 }  // extern "C"
@@ -1314,6 +1356,7 @@ int graph_layout(disc_ctx* ctx, const Graph& g, const int64_t* dims, int n_dims,
 
 int disc_register_graph(disc_ctx* ctx, const disc_op* ops, int n_ops, const disc_constraint* cs, int n_cs,
                         int32_t* graph_id_out) {
+  DISC_TRY
   if (!ctx) return DISC_ERR_INVALID_ARG;
   if (!graph_id_out) return set_err(ctx, DISC_ERR_INVALID_ARG, "graph_id_out is null");
   *graph_id_out = -1;
@@ -1616,9 +1659,11 @@ int disc_register_graph(disc_ctx* ctx, const disc_op* ops, int n_ops, const disc
   ctx->graphs.push_back(std::move(g));
   *graph_id_out = id;
   return DISC_OK;
+  DISC_CATCH(ctx)
 }
 
 int disc_graph_info(disc_ctx* ctx, int32_t id, disc_graph_info_t* out) {
+  DISC_TRY
   Graph* g = get_graph(ctx, id);
   if (!g || !out) return set_err(ctx, DISC_ERR_INVALID_ARG, "bad graph id or null output");
   memset(out, 0, sizeof *out);
@@ -1634,18 +1679,22 @@ int disc_graph_info(disc_ctx* ctx, int32_t id, disc_graph_info_t* out) {
   }
   for (size_t i = 0; i < g->group_of_op.size() && i < DISC_MAX_OPS; ++i) out->group_of_op[i] = g->group_of_op[i];
   return DISC_OK;
+  DISC_CATCH(ctx)
 }
 
 int disc_graph_workspace_bytes(disc_ctx* ctx, int32_t id, const int64_t* dims, int n_dims, size_t* out) {
+  DISC_TRY
   Graph* g = get_graph(ctx, id);
   if (!g || !out) return set_err(ctx, DISC_ERR_INVALID_ARG, "bad graph id or null output");
   std::vector<size_t> off;
   size_t pws = 0;
   return graph_layout(ctx, *g, dims, n_dims, &off, &pws, out);
+  DISC_CATCH(ctx)
 }
 
 int disc_graph_launch(disc_ctx* ctx, int32_t id, const int64_t* dims, int n_dims, const void* const* inputs, int n_in,
                       void* const* outputs, int n_out, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  DISC_TRY
   Graph* g = get_graph(ctx, id);
   if (!g) return set_err(ctx, DISC_ERR_INVALID_ARG, "bad graph id");
   if (n_in != g->n_inputs || n_out != g->n_outputs) return set_err(ctx, DISC_ERR_INVALID_ARG, "wrong number of inputs or outputs");
@@ -1682,4 +1731,5 @@ int disc_graph_launch(disc_ctx* ctx, int32_t id, const int64_t* dims, int n_dims
     if (rc) return rc;
   }
   return DISC_OK;
+  DISC_CATCH(ctx)
 }

@@ -129,6 +129,22 @@ def test_caller_constraints_enable_fusion(ctx):
     hn = ctx.register(_two_chains("numel")[0])             # tensor-size equality: fused over a flat index
     assert hn.info["template"] == "loop" and hn.info["n_collapsed"] == 1
     assert hn.plan([4, 6, 3, 8])["inner"] == 24
+    # the registered tensor-size equality is part of the launch-time shape calculation: dims that
+    # contradict it are refused before anything could run over the smaller tensor
+    msg = expect("CONSTRAINT", hn.plan, [4, 6, 5, 1])
+    assert "registered as equal in size" in msg
+    expect("CONSTRAINT", hn.ctx.workspace_bytes, hn.id, [4, 6, 23, 1])
+    # (the advisor's case: a rank-1 tensor tied to a rank-2 one)
+    pb = PatternBuilder()
+    a, b, c = pb.dims(3)
+    x = pb.param("f32", [a, b])
+    z = pb.param("f32", [c])
+    pb.output(pb.op("exp", x))
+    pb.output(pb.op("neg", z))
+    pb.numel_eq(x, z)
+    h1 = ctx.register(pb.build())
+    assert h1.plan([4, 6, 24])["inner"] == 24
+    expect("CONSTRAINT", h1.plan, [4, 6, 5])
 
 
 # ------------------------------------------------------------------ fusion decision
@@ -373,3 +389,80 @@ def test_bench_refuses_more_than_one_gpu():
     root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
     r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
     assert r.returncode != 0 and "ONE GPU" in r.stderr
+
+
+# ------------------------------------------------------------------ code generation corner cases
+def test_negative_constants_and_integer_ops_compile(ctx):
+    """NEG / ABS of negative literals (float and integer) and integer arithmetic of both widths go
+    through the one device compile (a '-' pasted in front of a negative literal would not)."""
+    pb = PatternBuilder()
+    n = pb.dim()
+    x = pb.param("f32", [n])
+    xi = pb.param("i32", [n])
+    xl = pb.param("i64", [n])
+    pb.output(pb.op("add", x, pb.op("neg", pb.const(-1.5)), dims=[n]))
+    pb.output(pb.op("mul", x, pb.op("abs", pb.const(-2.0)), dims=[n]))
+    pb.output(pb.op("add", xi, pb.op("abs", pb.const(-3.0, "i32")), dims=[n]))
+    pb.output(pb.op("sub", xl, pb.op("neg", pb.const(-7.0, "i64")), dims=[n]))
+    pb.output(pb.op("div", pb.op("mul", xi, xi), pb.op("max", pb.op("abs", xi), pb.const(1.0, "i32"), dims=[n])))
+    pb.output(pb.cast(pb.op("mul", pb.cast(pb.cast(x, "bf16"), "f32"), x), "f16"))
+    h = ctx.register(pb.build())
+    assert h.info["compile_events"] == 1 and h.info["template"] == "loop"
+    src = h.source
+    assert "disc::from_f32<__bf16>" in src          # the mid-chain cast rounds
+    assert "(disc::u32)" in src and "(disc::u64)" in src   # integer arithmetic wraps
+
+
+# ------------------------------------------------------------------ the launch path allocates nothing
+def test_launch_path_makes_no_heap_allocation(tmp_path):
+    """1000 distinct shapes per benchmark pattern through disc_plan / disc_workspace_bytes (the launch
+    path without the enqueue) under a counting allocator: no allocation, so no strings, maps or
+    vectors are built per call -- the host flow is tables filled at registration (Section 4.2.3).
+    The counting program is C++ (tests/cpp/plan_alloc_count.cpp) because the allocator of the whole
+    process has to be interposed."""
+    import struct
+    import subprocess
+    import numpy as np
+    from paper_2103_05288_amd.binding import marshal_pattern
+    from workloads import extras
+    exe = tmp_path / "plan_alloc_count"
+    subprocess.run(["g++", "-O1", "-std=c++17", "-I", os.path.join(ROOT, "include"), "-o", str(exe),
+                    os.path.join(ROOT, "tests", "cpp", "plan_alloc_count.cpp"), lib_path(),
+                    "-Wl,-rpath," + os.path.dirname(lib_path()), "-Wl,-rpath,/opt/rocm/lib"], check=True)
+    rng = np.random.default_rng(5)
+    files = []
+    pats = {n: cfg.pattern() for n, cfg in CONFIGS.items()}
+    pats["LNB"] = extras.layernorm_backward_graph()
+    pats["LSE"] = extras.logsumexp_with_total_and_amax()
+    for name, pat in pats.items():
+        ops, n_ops, cs, n_cs = marshal_pattern(pat)
+        nd = pat.n_dims
+        shapes = set()
+        while len(shapes) < 1000:
+            if name == "C1":
+                shapes.add((int(rng.integers(1, 9)), int(rng.integers(1, 13)), int(rng.integers(1, 2000))))
+            else:
+                shapes.add(tuple(int(2 ** rng.uniform(0, 17)) for _ in range(nd)))
+        path = tmp_path / f"{name}.pat"
+        with open(path, "wb") as f:
+            f.write(struct.pack("<iii", n_ops, n_cs, nd))
+            f.write(bytes(ops))
+            if n_cs:
+                f.write(bytes(cs)[: n_cs * 20])
+            f.write(struct.pack("<i", len(shapes)))
+            for s in sorted(shapes):
+                f.write(struct.pack("<%dq" % nd, *s))
+        files.append(str(path))
+    r = subprocess.run([str(exe)] + files, capture_output=True, text=True)
+    print(r.stdout, r.stderr)
+    assert r.returncode == 0, r.stdout + r.stderr
+    assert r.stdout.count("allocations=0") == len(files)
+    # the same driver with the library's host sources under ASan + UBSan: registration (checker,
+    # code generation, the device compile) and 1000 plans per pattern, error paths included
+    from paper_2103_05288_amd.build import build_sanitized_driver
+    san = build_sanitized_driver(str(tmp_path / "plan_sanitized"), os.path.join(ROOT, "tests", "cpp", "plan_alloc_count.cpp"))
+    env = dict(os.environ, ASAN_OPTIONS="detect_leaks=0:abort_on_error=0", UBSAN_OPTIONS="print_stacktrace=1")
+    r = subprocess.run([san] + files, capture_output=True, text=True, env=env)
+    print(r.stdout[-2000:], r.stderr[-4000:])
+    assert r.returncode == 0, r.stdout + r.stderr
+    assert "runtime error" not in r.stderr and "AddressSanitizer" not in r.stderr

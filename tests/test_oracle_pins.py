@@ -588,3 +588,149 @@ def test_reduction_of_per_row_values_to_one_number():
         rows = [py_in(float(a) for a in x[i]) for i in range(6)]
         assert np.asarray(out[1]).shape == ()
         assert float(out[1]) == pytest.approx(py_out(rows), rel=1e-6, abs=1e-6)
+
+
+# ---------------------------------------------------------------- integer arithmetic
+def _wrap_py(v: int, bits: int) -> int:
+    """Two's complement of a Python int, written with Python's own arithmetic."""
+    v &= (1 << bits) - 1
+    return v - (1 << bits) if v >> (bits - 1) else v
+
+
+def _trunc_div(a: int, b: int) -> int:
+    """C-style division from exact rationals: toward zero (Python's // floors)."""
+    from fractions import Fraction
+    return math.trunc(Fraction(a, b))
+
+
+INT_REF = {
+    "add": lambda a, b: a + b, "sub": lambda a, b: a - b, "mul": lambda a, b: a * b,
+    "div": _trunc_div, "max": max, "min": min,
+}
+# values beyond 2^24 (a detour through fp32 would show), beyond 2^31 for i64, all sign combinations,
+# exact multiples and non-multiples
+INT_A = [7, -7, 7, -7, 0, 123456789, -123456789, 2147483647, -2147483647, 40000, -65536, 99, 1 << 30, 16777217, -16777219, 6]
+INT_B = [2, 2, -2, -2, 5, 1000, 1000, 3, -3, 50000, 65536, -99, 4, -16777213, 3, -3]
+
+
+@pytest.mark.parametrize("dtype,bits", [("i32", 32), ("i64", 64)])
+@pytest.mark.parametrize("opcode", sorted(INT_REF))
+def test_integer_binary_ops_match_python_ints(opcode, dtype, bits):
+    a = np.array(INT_A, dtype=np.int64)
+    b = np.array(INT_B, dtype=np.int64)
+    if dtype == "i64":
+        a = a * 3000000007 + 1
+        b = np.where(np.abs(b) > 1000, b * 1000003, b)
+    got = _single(opcode, a, b, dtype=dtype)
+    assert got.dtype == np.int64
+    ref = [_wrap_py(INT_REF[opcode](int(u), int(v)), bits) for u, v in zip(a, b)]
+    assert got.tolist() == ref
+    if opcode in ("sub", "div"):
+        assert got.tolist() != [_wrap_py(INT_REF[opcode](int(v), int(u)), bits) if u != 0 else 0 for u, v in zip(a, b)]
+
+
+def test_integer_division_truncates_toward_zero_for_all_signs():
+    cases = [(7, 2, 3), (-7, 2, -3), (7, -2, -3), (-7, -2, 3), (6, 3, 2), (-6, 3, -2), (6, -3, -2), (-6, -3, 2),
+             (1, 5, 0), (-1, 5, 0), (0, -5, 0), (2147483647, -1, -2147483647)]
+    a = np.array([c[0] for c in cases]); b = np.array([c[1] for c in cases])
+    for dt in ("i32", "i64"):
+        assert _single("div", a, b, dtype=dt).tolist() == [c[2] for c in cases]
+
+
+def test_i32_results_wrap_and_i64_results_do_not():
+    a = np.array([2147483647, -2147483648, 65536, 2147483647])
+    b = np.array([1, -1, 65536, 2147483647])
+    assert _single("add", a, b, dtype="i32").tolist() == [-2147483648, 2147483647, 131072, -2]
+    assert _single("mul", a, b, dtype="i32").tolist() == [2147483647, -2147483648, 0, 1]
+    assert _single("add", a, b, dtype="i64").tolist() == [2147483648, -2147483649, 131072, 4294967294]
+    assert _single("mul", a, b, dtype="i64").tolist() == [2147483647, 2147483648, 1 << 32, 2147483647 ** 2]
+    # neg / abs of integers stay integers
+    x = np.array([5, -5, 0, -2147483647])
+    assert _single("neg", x, dtype="i32").tolist() == [-5, 5, 0, 2147483647]
+    assert _single("abs", x, dtype="i64").tolist() == [5, 5, 0, 2147483647]
+
+
+def test_binary_operands_take_the_result_type():
+    """An op's operands are converted to the element type of its result first: integer operands
+    of a float division divide as floats, an i64 operand of an i32 op is wrapped before the op."""
+    pb = PatternBuilder()
+    n = pb.dim()
+    a = pb.param("i32", [n])
+    b = pb.param("i64", [n])
+    pb.output(pb.op("div", a, b, dtype="f32"))
+    pb.output(pb.op("div", a, b, dtype="i64"))
+    pb.output(pb.op("max", a, b, dtype="i32"))
+    pb.output(pb.op("lt", a, b))
+    m = pb.param("bool", [n])
+    pb.output(pb.op("select", m, a, b, dtype="i32"))
+    pb.output(pb.op("add", pb.cast(m, "i32"), a))
+    av = np.array([7, -7, 9, 5]); bv = np.array([2, 2, (1 << 32) + 3, -4]); mv = np.array([1, 0, 0, 1], dtype=np.uint8)
+    o = run(pb.build(), [4], [av, bv, mv])[0]
+    assert o[0].dtype == np.float64 and o[0].tolist() == [3.5, -3.5, 9 / ((1 << 32) + 3), -1.25]
+    assert o[1].tolist() == [3, -3, 0, -1]
+    assert o[2].tolist() == [7, 2, 9, 5]              # max(9, wrap32(2^32 + 3) = 3) = 9
+    assert o[3].tolist() == [False, True, True, False]   # compared as 64-bit integers
+    assert o[4].tolist() == [7, 2, 3, 5]
+    assert o[5].tolist() == [8, -7, 9, 6]
+
+
+def test_integer_reductions_and_casts():
+    pb = PatternBuilder()
+    t, h = pb.dims(2)
+    x = pb.param("i32", [t, h])
+    pb.output(pb.reduce("sum", x, 1))
+    pb.output(pb.reduce("max", x, 1))
+    pb.output(pb.reduce("min", x, 0))
+    pb.output(pb.reduce("sum", pb.cast(x, "i64"), 1))
+    f = pb.param("f32", [t, h])
+    pb.output(pb.cast(f, "i32"))
+    pb.output(pb.cast(pb.cast(x, "i64"), "i32"))
+    xv = np.array([[2147483647, 1, 5], [-3, -4, 16777217]])
+    fv = np.array([[2.9, -2.9, 0.5], [-0.5, 1e9, -16777216.0]])
+    o = run(pb.build(), [2, 3], [xv, fv])[0]
+    assert o[0].tolist() == [_wrap_py(2147483647 + 1 + 5, 32), 16777210]
+    assert o[1].tolist() == [2147483647, 16777217]
+    assert o[2].tolist() == [-3, -4, 5]
+    assert o[3].tolist() == [2147483653, 16777210]
+    assert o[4].tolist() == [[2, -2, 0], [0, 1000000000, -16777216]]
+    assert o[5].tolist() == xv.tolist()
+
+
+# ---------------------------------------------------------------- a cast to a 16-bit float type mid-chain rounds
+def _bf16_rne_py(v: float) -> float:
+    """Nearest bf16 value, ties to even, from exact rational arithmetic (normal range)."""
+    from fractions import Fraction
+    if v == 0 or not math.isfinite(v):
+        return v
+    fr = Fraction(v)
+    e = math.floor(math.log2(abs(v)))
+    if Fraction(2) ** e > abs(fr):
+        e -= 1
+    q = Fraction(2) ** (e - 7)                  # spacing of values with 8 significant bits
+    n = fr / q
+    lo = math.floor(n)
+    r = n - lo
+    k = lo + 1 if r > Fraction(1, 2) or (r == Fraction(1, 2) and lo % 2 == 1) else lo
+    return float(k * q)
+
+
+def test_mid_chain_cast_to_16_bit_rounds_and_output_cast_does_not():
+    xs = np.array([1.0 + 2.0 ** -8, 1.0 + 3 * 2.0 ** -8, 3.14159, -2.71828, 1e-3, 65504.0, 1.0 + 2.0 ** -9, 1.0 + 2.0 ** -11 + 2.0 ** -12])
+    xs = xs.astype(np.float32).astype(np.float64)
+    for kind, ref in (("bf16", _bf16_rne_py), ("f16", lambda v: float(np.float16(v)))):
+        pb = PatternBuilder()
+        n = pb.dim()
+        x = pb.param("f32", [n])
+        c = pb.cast(x, kind)
+        pb.output(pb.op("mul", pb.cast(c, "f32"), pb.const(3.0)))    # the cast is read by an op: it rounds
+        pb.output(pb.cast(x, kind))                                  # a cast that only feeds an output: the store
+        o = run(pb.build(), [len(xs)], [xs])[0]
+        want = np.array([ref(float(v)) for v in xs])
+        assert (want != xs).any()
+        np.testing.assert_array_equal(o[0], want * 3.0)
+        np.testing.assert_array_equal(o[1], xs)
+    # ties go to the even neighbour (1 + 2^-8 lies halfway between 1 and 1 + 2^-7)
+    assert _bf16_rne_py(1.0 + 2.0 ** -8) == 1.0 and _bf16_rne_py(1.0 + 3 * 2.0 ** -8) == 1.0 + 2.0 ** -6
+    # and the rounding agrees with torch's conversion
+    t = torch.tensor(xs, dtype=torch.float32)
+    assert torch.equal(t.to(torch.bfloat16).to(torch.float64), torch.tensor([_bf16_rne_py(float(v)) for v in xs], dtype=torch.float64))

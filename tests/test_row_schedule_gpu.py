@@ -69,8 +69,8 @@ def test_many_rows_per_block_and_turning_grid(monkeypatch, cfg_name):
     and, for rows of several wavefronts, the slot grid keeps turning.  One round of resident blocks
     keeps the row counts this needs small."""
     from paper_2103_05288_amd import Context
-    monkeypatch.setenv("DISC_ROW_ROUNDS", "1")
     c = Context(0)
+    c.test_option("row_rounds", 1)
     try:
         h = c.register(CONFIGS[cfg_name].pattern())
         for H, T in [(127, 70001), (1100, 9001), (2047, 6000), (3001, 5003), (5739, 6007), (8190, 4500), (20003, 700)]:
@@ -86,8 +86,8 @@ def test_non_temporal_versions_any_alignment(monkeypatch):
     aligned rows for speed; their results do not depend on alignment), and the host rule with
     operands that are not 16-byte aligned: it must fall back to the plain version."""
     from paper_2103_05288_amd import Context
-    monkeypatch.setenv("DISC_ROW_NT", "1")
     c = Context(0)
+    c.test_option("non_temporal", 1)
     try:
         for cfg_name in ("C2", "C4"):
             h = c.register(CONFIGS[cfg_name].pattern())
@@ -101,7 +101,6 @@ def test_non_temporal_versions_any_alignment(monkeypatch):
         assert plan["kernels"][-1].endswith("k_col_epi_vec_nt"), plan["kernels"]
     finally:
         c.close()
-    monkeypatch.delenv("DISC_ROW_NT")
     c = Context(0)
     try:
         # host rule for the loop kernels: large launches only
@@ -140,8 +139,8 @@ def test_unstaged_versions(monkeypatch):
     """The same shapes with LDS staging switched off: the kernel versions that read row vectors from
     global memory in every slot."""
     from paper_2103_05288_amd import Context
-    monkeypatch.setenv("DISC_ROW_STAGE", "0")
     c = Context(0)
+    c.test_option("stage_row_vectors", 0)
     try:
         for cfg_name in ("C2", "C4"):
             h = c.register(CONFIGS[cfg_name].pattern())
