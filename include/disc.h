@@ -278,6 +278,26 @@ int disc_launch(disc_ctx* ctx, int32_t id, const int64_t* dims, int n_dims,
                 const void* const* inputs, int n_in, void* const* outputs, int n_out,
                 void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* For callers that cannot allocate (code under HIP graph capture, tight serving loops, harnesses
+ * that forbid hipMalloc): disc_launch without a workspace argument.  The kernels that exchange
+ * partial results through device memory (column reduces; row reduces that carry sums over the
+ * rows) use a fixed array of DISC_STATIC_SCRATCH_BYTES that is part of the library's code object
+ * -- one copy per GPU, held until the process ends -- instead of a caller's workspace.  The call
+ * allocates nothing and frees nothing, on the device or through any library.  A shape whose
+ * partial results need more than the array holds is refused with DISC_ERR_WORKSPACE before
+ * anything runs (use disc_launch with a workspace then).  Same kernels, same launch plan and same
+ * results, bit for bit, as disc_launch.  Every call on one GPU shares that GPU's array: calls
+ * that overlap in time on one GPU (two streams, two contexts, two threads) race on it -- keep
+ * them on one stream, or give all but one of them a workspace through disc_launch.  Nothing in the
+ * array has to be cleared between calls (each call writes every cell it later reads).
+ * disc_create asks the array's device address once per device; disc_static_scratch_init repeats
+ * that (idempotent) for a caller that wants the failure, if any, up front. */
+enum { DISC_STATIC_SCRATCH_BYTES = 16 << 20 };
+int disc_static_scratch_init(disc_ctx* ctx);
+int disc_launch_static_scratch(disc_ctx* ctx, int32_t id, const int64_t* dims, int n_dims,
+                               const void* const* inputs, int n_in, void* const* outputs, int n_out,
+                               void* hip_stream);
+
 /* Tests only: make the next launches of this context use `variant` when it is legal for the
  * pattern and the shape (else DISC_ERR_INVALID_ARG at launch); -1 restores host selection. */
 int disc_force_variant(disc_ctx* ctx, int variant);

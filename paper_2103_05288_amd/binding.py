@@ -81,6 +81,7 @@ class DiscError(RuntimeError):
 EXPORTS = ("disc_create", "disc_destroy", "disc_last_error", "disc_register_pattern", "disc_register_pattern_static",
            "disc_pattern_info",
            "disc_pattern_source", "disc_workspace_bytes", "disc_plan", "disc_launch", "disc_force_variant", "disc_test_option",
+           "disc_static_scratch_init", "disc_launch_static_scratch",
            "disc_get_stats", "disc_util_copy", "disc_util_copy_nt", "disc_util_empty_launch", "disc_register_graph", "disc_graph_info",
            "disc_graph_workspace_bytes", "disc_graph_launch")
 
@@ -123,6 +124,8 @@ def load_library():
     lib.disc_graph_launch.argtypes = [vp, C.c_int32, i64p, C.c_int, C.POINTER(vp), C.c_int, C.POINTER(vp), C.c_int,
                                       vp, C.c_size_t, vp]
     lib.disc_force_variant.argtypes = [vp, C.c_int]
+    lib.disc_static_scratch_init.argtypes = [vp]
+    lib.disc_launch_static_scratch.argtypes = [vp, C.c_int32, i64p, C.c_int, C.POINTER(vp), C.c_int, C.POINTER(vp), C.c_int, vp]
     lib.disc_test_option.argtypes = [vp, C.c_int, C.c_int]
     lib.disc_get_stats.argtypes = [vp, C.POINTER(disc_stats_t)]
     lib.disc_util_copy.argtypes = [vp, vp, vp, C.c_size_t, vp]
@@ -343,6 +346,18 @@ class Context:
             stream = torch.cuda.current_stream().cuda_stream
         self._check(self.lib.disc_launch(self.h, pid, arr, n, ins, len(inputs), outs, len(outputs), ws,
                                          C.c_size_t(workspace_bytes), C.c_void_p(stream)))
+
+    def launch_static_scratch(self, pid: int, dims, inputs: Sequence, outputs: Sequence, stream: Optional[int] = None):
+        """disc_launch_static_scratch: no workspace argument, nothing allocated (the library's own
+        fixed device array serves as scratch memory)."""
+        arr, n = self._dims(dims)
+        ins = (C.c_void_p * max(1, len(inputs)))(*[_ptr(t) for t in inputs])
+        outs = (C.c_void_p * max(1, len(outputs)))(*[_ptr(t) for t in outputs])
+        if stream is None:
+            import torch
+            stream = torch.cuda.current_stream().cuda_stream
+        self._check(self.lib.disc_launch_static_scratch(self.h, pid, arr, n, ins, len(inputs), outs, len(outputs),
+                                                        C.c_void_p(stream)))
 
     def stats(self) -> dict:
         s = disc_stats_t()

@@ -40,11 +40,23 @@ def build_library(verbose: bool = False) -> str:
     # hipRTC with --offload-arch=gfx950, so the host compiler is used here.
     rocm = os.environ.get("ROCM_PATH", "/opt/rocm")
     cxx = os.environ.get("CXX", "g++")
+    # The one exception: scratch.hip owns a static __device__ array (the scratch memory of
+    # disc_launch_static_scratch), so it is compiled as HIP for gfx950 and linked in as an object.
+    scratch_obj = os.path.join(build_dir, "scratch.o")
+    hipcc = os.path.join(rocm, "bin", "hipcc")
+    hcmd = [hipcc, "--offload-arch=gfx950", "-O2", "-std=c++17", "-fPIC", "-Xclang", "-target-feature", "-Xclang",
+            "-packed-fp32-ops", "-I", os.path.join(ROOT, "include"), "-I", CSRC, "-c",
+            os.path.join(CSRC, "scratch.hip"), "-o", scratch_obj]
+    if verbose:
+        print(" ".join(hcmd))
+    r = subprocess.run(hcmd, capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError("hipcc compile of scratch.hip failed:\n" + r.stdout + r.stderr)
     cmd = [cxx, "-O2", "-std=c++17", "-fPIC", "-shared", "-Wall", "-Wno-unused-result",
            "-D__HIP_PLATFORM_AMD__", "-I", os.path.join(rocm, "include"),
            "-I", os.path.join(ROOT, "include"), "-I", CSRC,
            "-o", LIB] + [os.path.join(CSRC, s) for s in SOURCES] + \
-          [embed, "-L", os.path.join(rocm, "lib"), "-Wl,-rpath," + os.path.join(rocm, "lib"),
+          [embed, scratch_obj, "-L", os.path.join(rocm, "lib"), "-Wl,-rpath," + os.path.join(rocm, "lib"),
            "-lamdhip64", "-lhiprtc"]
     if verbose:
         print(" ".join(cmd))
@@ -59,15 +71,16 @@ def build_sanitized_driver(out_path: str, driver_source: str) -> str:
     executable under AddressSanitizer + UndefinedBehaviorSanitizer.  Host code only: device code is
     never built with a sanitizer.  Run it with ASAN_OPTIONS=detect_leaks=0 (the device compiler's
     own library is not instrumented and keeps caches alive)."""
+    build_library()                       # (leaves the HIP object of scratch.hip, linked in unsanitized)
     build_dir = os.path.join(HERE, "_build")
-    os.makedirs(build_dir, exist_ok=True)
     embed = _embed_header(build_dir)
     rocm = os.environ.get("ROCM_PATH", "/opt/rocm")
     cmd = [os.environ.get("CXX", "g++"), "-O1", "-g", "-std=c++17", "-fsanitize=address,undefined",
            "-static-libasan", "-fno-sanitize-recover=undefined", "-fno-omit-frame-pointer", "-DDISC_NO_INTERPOSE",
            "-D__HIP_PLATFORM_AMD__", "-I", os.path.join(rocm, "include"), "-I", os.path.join(ROOT, "include"),
            "-I", CSRC, "-o", out_path, driver_source] + [os.path.join(CSRC, s) for s in SOURCES] + \
-          [embed, "-L", os.path.join(rocm, "lib"), "-Wl,-rpath," + os.path.join(rocm, "lib"), "-lamdhip64", "-lhiprtc"]
+          [embed, os.path.join(build_dir, "scratch.o"), "-L", os.path.join(rocm, "lib"),
+           "-Wl,-rpath," + os.path.join(rocm, "lib"), "-lamdhip64", "-lhiprtc"]
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError("sanitized host build failed:\n" + r.stdout + r.stderr)

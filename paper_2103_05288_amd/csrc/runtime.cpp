@@ -767,6 +767,19 @@ int ensure_util(disc_ctx* c) {
 
 }  // namespace
 
+// accessors for scratch.hip (the one source file compiled as HIP: it owns the static device array)
+namespace disc {
+int context_device(const disc_ctx* ctx) { return ctx ? ctx->device : -1; }
+int context_fail(disc_ctx* ctx, int code, const char* msg) {
+  try {
+    return set_err(ctx, code, msg);
+  } catch (...) {
+    return code;
+  }
+}
+}  // namespace disc
+extern "C" int disc_static_scratch_init(disc_ctx* ctx);
+
 // ============================================================================================
 // C ABI
 // ============================================================================================
@@ -804,6 +817,8 @@ int disc_create(disc_ctx** out, int hip_device) {
     hipDeviceProp_t prop;
     if (hipGetDeviceProperties(&prop, hip_device) != hipSuccess) return DISC_ERR_HIP;
     c->n_cus = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+    // the device address of the static scratch array (disc_launch_static_scratch), once per device
+    if (disc_static_scratch_init(c.get()) != DISC_OK) return DISC_ERR_HIP;
   }
   *out = c.release();
   return DISC_OK;
