@@ -191,6 +191,8 @@ typedef enum {
   DISC_V_COL_STRIP_VEC,     /* column reduce, one block per column strip, single launch        */
   DISC_V_COL_STRIP_SCALAR,
   DISC_V_TRANSPOSE_TILE,    /* batched 2-D transpose through a 64 x 64 tile in LDS              */
+  DISC_V_COL_2STAGE_VEC,    /* column reduce: partial -> finish + epilogue in one kernel (2 launches) */
+  DISC_V_COL_2STAGE_SCALAR,
   DISC_V_COUNT
 } disc_variant;
 

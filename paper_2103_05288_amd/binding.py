@@ -21,7 +21,7 @@ _OPCODES = ("param", "const", "dim_size", "neg", "abs", "exp", "log", "tanh", "s
 OPCODE_IDS = {n: i for i, n in enumerate(_OPCODES)}
 VARIANTS = ("loop_vec", "loop_vec_i64", "loop_scalar", "loop_scalar_i64", "row_reg_vec", "row_reg_scalar",
             "row_stream_vec", "row_stream_scalar", "col_3stage_vec", "col_3stage_scalar", "col_strip_vec",
-            "col_strip_scalar", "transpose_tile")
+            "col_strip_scalar", "transpose_tile", "col_2stage_vec", "col_2stage_scalar")
 STATUS = {0: "OK", -1: "INVALID_ARG", -2: "BAD_PATTERN", -3: "UNFUSIBLE", -4: "CONSTRAINT", -5: "WORKSPACE",
           -6: "COMPILE", -7: "HIP", -8: "SHAPE", -9: "EMPTY_REDUCE", -10: "INTERNAL"}
 TEST_OPTIONS = {"non_temporal": 0, "stage_row_vectors": 1, "row_rounds": 2}

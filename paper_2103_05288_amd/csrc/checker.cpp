@@ -266,7 +266,7 @@ struct KernelNames {
         "k_row_stream_vec", "k_row_stream_scalar", "k_colsum_finish", "k_rowred_finish",
         "k_col_partial_vec", "k_col_partial_scalar", "k_col_finish", "k_col_strip_vec", "k_col_strip_scalar",
         "k_col_epi_vec", "k_col_epi_vec_i64", "k_col_epi_scalar", "k_col_epi_scalar_i64", "k_col_epi_vec_nt",
-        "k_transpose_tile"};
+        "k_transpose_tile", "k_col_epi2_vec", "k_col_epi2_vec_nt", "k_col_epi2_scalar"};
     for (int i = 0; i < K_ROW_BASE; ++i) name[i] = fixed[i];
     for (int sc = 0; sc < 2; ++sc)
       for (int n = 1; n <= 3; ++n)

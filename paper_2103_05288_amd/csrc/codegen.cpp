@@ -584,7 +584,12 @@ struct Gen {
   }
 
   void emit_load_store(const std::vector<char>& need, bool with_red) {
-    os << "  template <int V, int NT = 0, class C> static DISC_DEV void load(const Args& A, const RowCtx& rc, C col, disc::Span sp, Slot<V>& s) {\n";
+    if (with_red) emit_load(need, false, "load_x");   // operands only: the caller holds the reduce results
+    emit_load(need, with_red, "load");
+    emit_store();
+  }
+  void emit_load(const std::vector<char>& need, bool with_red, const char* name) {
+    os << "  template <int V, int NT = 0, class C> static DISC_DEV void " << name << "(const Args& A, const RowCtx& rc, C col, disc::Span sp, Slot<V>& s) {\n";
     for (size_t i = 0; i < an.accesses.size(); ++i) {
       const Access& a = an.accesses[i];
       if (a.is_output || !a.has_inner || !need[i] || late(a)) continue;
@@ -601,6 +606,8 @@ struct Gen {
       }
     }
     os << "    (void)A; (void)rc; (void)col; (void)sp; (void)s;\n  }\n";
+  }
+  void emit_store() {
     os << "  template <int V, int NT = 0, class C> static DISC_DEV void store(const Args& A, const RowCtx& rc, C col, disc::Span sp, const OutSlot<V>& o) {\n";
     for (size_t i = 0; i < an.accesses.size(); ++i) {
       const Access& a = an.accesses[i];
@@ -1006,6 +1013,33 @@ struct Gen {
     os << "    (void)A; (void)o; (void)c; (void)acc;\n  }\n";
   }
 
+  // column reduce, two-launch version: the finish step of one (outer index o, column c) with the
+  // reduce results delivered into element e of a slot (registers) instead of the workspace planes;
+  // `write` (one block per column tile) also stores the outputs that lost the reduced axis
+  void emit_finish_elem() {
+    os << "  template <int V> static DISC_DEV void clear_red(Slot<V>& s) {\n";
+    for (int id : an.reduces[0]) os << "    s.red" << an.nodes[id].reduce_slot << ".clear();\n";
+    os << "    (void)s;\n  }\n";
+    os << "  template <int V> static DISC_DEV void finish_elem(const Args& A, disc::i64 o, disc::i64 c, const Pat::Acc<0>& acc, Slot<V>& s, int e, bool write) {\n";
+    Fn fn(*this, M_COL_FINISH);
+    std::ostringstream tail;
+    for (int id : an.reduces[0]) {
+      const Node& n = an.nodes[id];
+      tail << "    s.red" << n.reduce_slot << ".set(e, " << fn.val(id) << ");\n";
+    }
+    tail << "    if (write) {\n";
+    for (const auto& out : an.outputs) {
+      const Access& a = an.accesses[out.access];
+      if (elem_output(a)) continue;
+      const Node& n = an.nodes[out.node];
+      std::string off = a.groups.size() > 1 ? "o * A.inner + c" : "c";
+      tail << "      A.o" << a.slot << "[" << off << "] = " << to_storage(fn.val(out.node), n.rk, a.dtype) << ";\n";
+    }
+    tail << "    }\n";
+    os << fn.body.str() << tail.str();
+    os << "    (void)A; (void)o; (void)c; (void)acc; (void)s; (void)e; (void)write;\n  }\n";
+  }
+
   void emit_args() {
     os << "  struct Args {\n";
     for (const auto& f : layout.fields) os << "    " << field_decl(f) << "\n";
@@ -1092,6 +1126,10 @@ struct Gen {
         k("k_col_epi_vec_i64", fmt("disc::kloop_body<PatE, %d, 1, true>(A);", V), nullptr);
         k("k_col_epi_scalar", "disc::kloop_body<PatE, 1, 4, false>(A);", nullptr);
         k("k_col_epi_scalar_i64", "disc::kloop_body<PatE, 1, 1, true>(A);", nullptr);
+        // two-launch version: finish + epilogue in one kernel (plain; non-temporal stores)
+        k("k_col_epi2_vec", fmt("disc::col_epi2_body<Pat, PatE, %d, 0>(A, rp);", V), "ColPlan");
+        if (V > 1) k("k_col_epi2_vec_nt", fmt("disc::col_epi2_body<Pat, PatE, %d, 2>(A, rp);", V), "ColPlan");
+        k("k_col_epi2_scalar", "disc::col_epi2_body<Pat, PatE, 1, 0>(A, rp);", "ColPlan");
       }
     }
   }
@@ -1176,6 +1214,7 @@ struct Gen {
         os << "  static DISC_DEV void row_begin(const Args& A, disc::i64 row, RowCtx& rc) { Pat::row_begin(A, row, rc); }\n";
         emit_load_store(need3, true);
         emit_epilogue(M_COL_EPI);
+        emit_finish_elem();
         os << "};\n";
       }
     }

@@ -1047,6 +1047,7 @@ struct ColPlan {
   int pad;
   i64 chunk_rows;  // rows per chunk
   i64 outer;
+  i64 epi_rows;    // two-launch version: rows of the reduced axis per block of the second launch
 };
 
 // V column accumulators of one lane over rows [m0 + ty, m1) with stride TY of outer slice o,
@@ -1083,6 +1084,66 @@ DISC_DEV void col_accumulate(const typename Pat::Args& A, i64 o, i64 col, int nv
   }
 }
 
+// Exchange with the lane whose number differs in bit S (a true xor exchange, unlike lane_xchg whose
+// middle steps assume that earlier steps have run): DPP quad permutes, the swizzle unit for 4 and 8,
+// the permlane swaps for 16 and 32.
+template <int S>
+DISC_DEV u32 lane_xor_u32(u32 v) {
+  if constexpr (S == 1 || S == 2 || S == 16 || S == 32) return lane_xchg_u32<S>(v);
+  else return (u32)__builtin_amdgcn_ds_swizzle((int)v, (S << 10) | 0x1f);   // bit mode: and 0x1f, or 0, xor S
+}
+template <int S, class T>
+DISC_DEV T lane_xor_pod(const T& v) {
+  static_assert(sizeof(T) % 4 == 0, "accumulators are made of 4- and 8-byte fields");
+  u32 w[sizeof(T) / 4];
+  __builtin_memcpy(w, &v, sizeof(T));
+#pragma unroll
+  for (int i = 0; i < (int)(sizeof(T) / 4); ++i) w[i] = lane_xor_u32<S>(w[i]);
+  T r;
+  __builtin_memcpy(&r, w, sizeof(T));
+  return r;
+}
+template <class Pat, int S, int V>
+DISC_DEV void col_lane_step(typename Pat::template Acc<0> (&acc)[V]) {
+#pragma unroll
+  for (int e = 0; e < V; ++e) {
+    const typename Pat::template Acc<0> o = lane_xor_pod<S>(acc[e]);
+    Pat::template acc_merge<0>(acc[e], o);
+  }
+}
+
+// The row-lanes of a block each hold accumulators of the same GC * V columns (thread = ty * GC + tx).
+// Combines them column by column in a fixed order and leaves the block's result in EVERY lane:
+// the lanes of a wavefront that hold the same columns meet through xor exchanges over the lane
+// distances GC .. 32 (both partners compute the same commutative merge, so they agree bit for bit),
+// then the wavefronts meet through one LDS cell per wavefront and column.  (One lane per column
+// walking all row-lanes' cells in LDS, as before, cost up to 2 us per block with 128 row-lanes.)
+// `lds` holds 4 * 64 * V accumulators; ends with a barrier, so the caller may reuse it at once.
+template <class Pat, int V>
+DISC_DEV void col_block_merge(typename Pat::template Acc<0> (&acc)[V], typename Pat::template Acc<0>* lds, int GC, int tx) {
+  int g = GC;
+  asm volatile("" : "+s"(g));
+  if (g <= 1) col_lane_step<Pat, 1, V>(acc);
+  if (g <= 2) col_lane_step<Pat, 2, V>(acc);
+  if (g <= 4) col_lane_step<Pat, 4, V>(acc);
+  if (g <= 8) col_lane_step<Pat, 8, V>(acc);
+  if (g <= 16) col_lane_step<Pat, 16, V>(acc);
+  if (g <= 32) col_lane_step<Pat, 32, V>(acc);
+  const int wave = (int)threadIdx.x >> 6, lane = (int)threadIdx.x & 63, nw = (int)blockDim.x >> 6;
+  const int gw = GC < 64 ? GC : 64;          // columns-lanes per wavefront
+  if (lane < gw) {
+#pragma unroll
+    for (int e = 0; e < V; ++e) lds[(wave * gw + lane) * V + e] = acc[e];
+  }
+  __syncthreads();
+#pragma unroll
+  for (int e = 0; e < V; ++e) {
+    acc[e] = lds[tx * V + e];
+    for (int w = 1; w < nw; ++w) Pat::template acc_merge<0>(acc[e], lds[(w * gw + tx) * V + e]);
+  }
+  __syncthreads();
+}
+
 template <class Pat, int V>
 DISC_DEV void col_partial_body(const typename Pat::Args& A, const ColPlan& cp) {
   typedef typename Pat::template Acc<0> AccT;
@@ -1099,27 +1160,59 @@ DISC_DEV void col_partial_body(const typename Pat::Args& A, const ColPlan& cp) {
   for (i64 o = blockIdx.z; o < cp.outer; o += gridDim.z) {
     AccT acc[V];
     col_accumulate<Pat, V>(A, o, col, nvalid, m0, m1, ty, TY, acc);
-#pragma unroll
-    for (int e = 0; e < V; ++e) lds[(ty * cp.GC + tx) * V + e] = acc[e];
-    __syncthreads();
-    if (ty == 0 && nvalid > 0) {
-      for (int t = 1; t < TY; ++t)
-#pragma unroll
-        for (int e = 0; e < V; ++e) Pat::template acc_merge<0>(acc[e], lds[(t * cp.GC + tx) * V + e]);
+    col_block_merge<Pat, V>(acc, lds, cp.GC, tx);
+    if (ty == 0) {
 #pragma unroll
       for (int e = 0; e < V; ++e)
         if (e < nvalid) Pat::acc_st(A, (o * cp.nchunk + chunk) * A.inner + col + e, acc[e]);
     }
-    __syncthreads();
   }
 }
 
-// Single-launch version for small problems, where three launches cost more than the work: a
-// block owns a strip of GC * V columns and ALL rows of it.  It reduces the strip (same lane
-// layout and fixed merge order as above), finishes its columns itself, and then -- when the
-// pattern has per-element outputs -- walks the strip a second time for the epilogue, reading the
-// tensor from cache and the reduce results it has just written (fence + barrier in between;
-// no other block reads them).  PatE = void: no epilogue.
+// The rows [m0, m1) of outer slice o, a block's share of them, through the epilogue: `base` holds
+// the reduce results of the lane's columns (the same for every row), the operands are loaded into
+// copies of it, four rows in flight per lane.
+template <class Pat, class PatE, int V, int NT>
+DISC_DEV void col_rows_epilogue(const typename Pat::Args& A, const typename PatE::template Slot<V>& base, i64 o, i64 col,
+                                Span sp, i64 m0, i64 m1, int ty, int TY) {
+  i64 m = m0 + ty;
+  for (; m + 3 * TY < m1; m += 4 * TY) {
+    typename PatE::template Slot<V> s[4];
+    typename PatE::RowCtx rc[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      s[u] = base;
+      PatE::row_begin(A, o * A.mid + m + u * TY, rc[u]);
+      PatE::template load_x<V, NT>(A, rc[u], col, sp, s[u]);
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      typename PatE::template OutSlot<V> out;
+      typename PatE::template Keep<V> kp;
+      PatE::template epilogue<V, false>(A, rc[u], s[u], kp, col, sp, out);
+      PatE::template store<V, NT>(A, rc[u], col, sp, out);
+    }
+  }
+  for (; m < m1; m += TY) {
+    typename PatE::template Slot<V> s1 = base;
+    typename PatE::RowCtx rc;
+    PatE::row_begin(A, o * A.mid + m, rc);
+    PatE::template load_x<V, NT>(A, rc, col, sp, s1);
+    typename PatE::template OutSlot<V> out;
+    typename PatE::template Keep<V> kp;
+    PatE::template epilogue<V, false>(A, rc, s1, kp, col, sp, out);
+    PatE::template store<V, NT>(A, rc, col, sp, out);
+  }
+}
+
+// Single-launch version for small problems, where every further launch costs more than the work
+// (a kernel that makes one round trip to memory takes 5-6 us on this part whatever it moves): a
+// block owns a strip of GC * V columns and ALL rows of it.  It reduces the strip, every lane ends up
+// with the results of its own columns in registers (col_block_merge), the lanes of the first row
+// write the outputs that lost the reduced axis, and -- when the pattern has per-element outputs --
+// the block walks its strip a second time for the epilogue, reading the tensor from cache.  Nothing
+// goes through memory between the two passes.  PatE = void: no epilogue; the reduce results go to
+// the workspace planes as in the three-launch version.
 template <class Pat, class PatE, int V>
 DISC_DEV void col_strip_body(const typename Pat::Args& A, const ColPlan& cp) {
   typedef typename Pat::template Acc<0> AccT;
@@ -1133,62 +1226,118 @@ DISC_DEV void col_strip_body(const typename Pat::Args& A, const ColPlan& cp) {
   for (i64 o = blockIdx.y; o < cp.outer; o += gridDim.y) {
     AccT acc[V];
     col_accumulate<Pat, V>(A, o, col, nvalid, 0, A.mid, ty, TY, acc);
+    col_block_merge<Pat, V>(acc, lds, cp.GC, tx);
+    if constexpr (__is_same(PatE, void)) {
+      if (ty == 0) {
 #pragma unroll
-    for (int e = 0; e < V; ++e) lds[(ty * cp.GC + tx) * V + e] = acc[e];
-    __syncthreads();
-    if (ty == 0 && nvalid > 0) {
-      for (int t = 1; t < TY; ++t)
-#pragma unroll
-        for (int e = 0; e < V; ++e) Pat::template acc_merge<0>(acc[e], lds[(t * cp.GC + tx) * V + e]);
-#pragma unroll
-      for (int e = 0; e < V; ++e)
-        if (e < nvalid) Pat::col_finish(A, o, col + e, acc[e]);
-    }
-    if constexpr (!__is_same(PatE, void)) {
-      __threadfence();
-      __syncthreads();
-      if (nvalid > 0) {
-        const Span sp = Span::upto(nvalid);
-        for (i64 m = ty; m < A.mid; m += TY) {
-          typename PatE::RowCtx rc;
-          PatE::row_begin(A, o * A.mid + m, rc);
-          typename PatE::template Slot<V> slot;
-          PatE::template load<V>(A, rc, col, sp, slot);
-          typename PatE::template OutSlot<V> out;
-          typename PatE::template Keep<V> kp;
-          PatE::template epilogue<V, false>(A, rc, slot, kp, col, sp, out);
-          PatE::template store<V>(A, rc, col, sp, out);
-        }
+        for (int e = 0; e < V; ++e)
+          if (e < nvalid) Pat::col_finish(A, o, col + e, acc[e]);
       }
+    } else {
+      if (nvalid > 0) {
+        typename PatE::template Slot<V> base;
+        PatE::template clear_red<V>(base);
+#pragma unroll
+        for (int e = 0; e < V; ++e)
+          if (e < nvalid) PatE::template finish_elem<V>(A, o, col + e, acc[e], base, e, ty == 0);
+        col_rows_epilogue<Pat, PatE, V, 0>(A, base, o, col, Span::upto(nvalid), 0, A.mid, ty, TY);
+      }
+    }
+  }
+}
+
+// Second of three launches: per column, the partials of all chunks merged in a fixed order.  A
+// block takes 16 columns; its 256 lanes are 16 columns x 16 lanes that each walk every 16th chunk
+// with four loads in flight, and the 16 lane results of a column meet in LDS.  (One lane per
+// column walking the chunks one dependent load at a time, on inner / 64 blocks, took 18 us for
+// 256 chunks x 1024 columns.)
+template <class Pat>
+DISC_DEV void col_finish_body(const typename Pat::Args& A, const ColPlan& cp) {
+  typedef typename Pat::template Acc<0> AccT;
+  constexpr int CL = 16, PL = 16;
+  __shared__ AccT lds[PL][CL + 1];
+  const int cl = (int)threadIdx.x % CL, pl = (int)threadIdx.x / CL;
+  const i64 c = (i64)blockIdx.x * CL + cl;
+  for (i64 o = blockIdx.y; o < cp.outer; o += gridDim.y) {
+    AccT acc[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) Pat::template acc_init<0>(acc[u]);
+    if (c < A.inner) {
+      const i64 base = o * cp.nchunk * A.inner + c;
+      int j = pl;
+      for (; j + 3 * PL < cp.nchunk; j += 4 * PL) {
+        AccT t[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) Pat::acc_ld(A, base + (i64)(j + u * PL) * A.inner, t[u]);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) Pat::template acc_merge<0>(acc[u], t[u]);
+      }
+      for (; j < cp.nchunk; j += PL) {
+        AccT t;
+        Pat::acc_ld(A, base + (i64)j * A.inner, t);
+        Pat::template acc_merge<0>(acc[0], t);
+      }
+    }
+#pragma unroll
+    for (int u = 1; u < 4; ++u) Pat::template acc_merge<0>(acc[0], acc[u]);
+    lds[pl][cl] = acc[0];
+    __syncthreads();
+    if (pl == 0 && c < A.inner) {
+      AccT tot = lds[0][cl];
+      for (int k = 1; k < PL; ++k) Pat::template acc_merge<0>(tot, lds[k][cl]);
+      Pat::col_finish(A, o, c, tot);
     }
     __syncthreads();
   }
 }
 
-template <class Pat>
-DISC_DEV void col_finish_body(const typename Pat::Args& A, const ColPlan& cp) {
+// Two-launch version: the second launch both finishes and applies the epilogue.  A block owns a
+// column tile (the same GC * V columns as in the partial pass) and a range of rows.  It first merges
+// the few chunk partials of its own columns (every block of a column tile repeats this small piece
+// of work, in the same fixed order, so all of them hold the same results; the block of the first
+// row range also writes the outputs that lost the reduced axis), keeps the reduce results in
+// registers -- they are the same for every row -- and then streams its rows through the epilogue.
+// No finish launch, no reduce-result planes in memory, no per-slot loads of them.
+// The row ranges are handed out in reverse: the first blocks to start take the rows that the
+// partial pass read last and that are most likely still in the memory-side cache.
+// NT: bit 0 = non-temporal loads of the full-size operands, bit 1 = non-temporal stores.
+template <class Pat, class PatE, int V, int NT>
+DISC_DEV void col_epi2_body(const typename Pat::Args& A, const ColPlan& cp) {
   typedef typename Pat::template Acc<0> AccT;
-  __shared__ AccT lds[256];
-  const int tx = threadIdx.x & 63;
-  const int g = threadIdx.x >> 6;
-  const i64 c = (i64)blockIdx.x * 64 + tx;
-  for (i64 o = blockIdx.y; o < cp.outer; o += gridDim.y) {
-    AccT acc;
-    Pat::template acc_init<0>(acc);
-    if (c < A.inner) {
-      for (int j = g; j < cp.nchunk; j += 4) {
-        AccT t;
-        Pat::acc_ld(A, (o * cp.nchunk + j) * A.inner + c, t);
-        Pat::template acc_merge<0>(acc, t);
+  __shared__ AccT lds[256 * V];
+  const int tx = threadIdx.x & (cp.GC - 1);
+  const int ty = threadIdx.x >> cp.log2GC;
+  const int TY = blockDim.x >> cp.log2GC;
+  const i64 col = ((i64)blockIdx.x * cp.GC + tx) * V;
+  const i64 rem = A.inner - col;
+  const int nvalid = rem <= 0 ? 0 : (rem < (i64)V ? (int)rem : V);
+  const i64 rb = (i64)gridDim.y - 1 - blockIdx.y;
+  const i64 m0 = rb * cp.epi_rows;
+  const i64 m1 = m0 + cp.epi_rows < A.mid ? m0 + cp.epi_rows : A.mid;
+  for (i64 o = blockIdx.z; o < cp.outer; o += gridDim.z) {
+    AccT acc[V];
+#pragma unroll
+    for (int e = 0; e < V; ++e) Pat::template acc_init<0>(acc[e]);
+    if (nvalid > 0) {
+      for (int j = ty; j < cp.nchunk; j += TY) {
+        AccT t[V];
+#pragma unroll
+        for (int e = 0; e < V; ++e)
+          if (e < nvalid) Pat::acc_ld(A, (o * cp.nchunk + j) * A.inner + col + e, t[e]);
+#pragma unroll
+        for (int e = 0; e < V; ++e)
+          if (e < nvalid) Pat::template acc_merge<0>(acc[e], t[e]);
       }
     }
-    lds[g * 64 + tx] = acc;
-    __syncthreads();
-    if (g == 0 && c < A.inner) {
-      for (int t = 1; t < 4; ++t) Pat::template acc_merge<0>(acc, lds[t * 64 + tx]);
-      Pat::col_finish(A, o, c, acc);
+    col_block_merge<Pat, V>(acc, lds, cp.GC, tx);
+    if (nvalid > 0) {
+      typename PatE::template Slot<V> base;
+      PatE::template clear_red<V>(base);
+#pragma unroll
+      for (int e = 0; e < V; ++e)
+        if (e < nvalid) PatE::template finish_elem<V>(A, o, col + e, acc[e], base, e, rb == 0 && ty == 0);
+      col_rows_epilogue<Pat, PatE, V, NT>(A, base, o, col, Span::upto(nvalid), m0, m1, ty, TY);
     }
-    __syncthreads();
   }
 }
 

@@ -224,6 +224,7 @@ enum KernelId {
   K_COL_PARTIAL_VEC, K_COL_PARTIAL_SCALAR, K_COL_FINISH, K_COL_STRIP_VEC, K_COL_STRIP_SCALAR,
   K_COL_EPI_VEC, K_COL_EPI_VEC_I64, K_COL_EPI_SCALAR, K_COL_EPI_SCALAR_I64, K_COL_EPI_VEC_NT,
   K_TRANSPOSE_TILE,
+  K_COL_EPI2_VEC, K_COL_EPI2_VEC_NT, K_COL_EPI2_SCALAR,
   K_ROW_BASE,
   K_COUNT = K_ROW_BASE + 48
 };

@@ -29,7 +29,7 @@ struct DeviceRowPlan {   // mirrors disc::RowPlan of the device header
 };
 struct DeviceColPlan {   // mirrors disc::ColPlan of the device header
   int32_t GC, log2GC, nchunk, pad;
-  int64_t chunk_rows, outer;
+  int64_t chunk_rows, outer, epi_rows;
 };
 constexpr int kLdsStep = 512, kLdsSteps = 48 * 1024 / kLdsStep + 2;
 constexpr int kArgBufBytes = 4096;    // kernel-argument block + launch-plan struct
@@ -573,12 +573,16 @@ int make_plan(disc_ctx* c, const Pattern& p, const int64_t* dims, int n_dims, in
     if (mid >= (1ll << 31) - 1) return set_err(c, DISC_ERR_SHAPE, "reduced axis longer than 2^31");
     // the column tiles are the x dimension of the grids (no grid stride across columns)
     if (inner >= (1ll << 31) - 4096) return set_err(c, DISC_ERR_SHAPE, "column reduce: more than 2^31 columns");
-    int want_vec = -1, want_strip = -1;
+    int want_vec = -1, want_strip = -1, want_two = -1;
     if (force >= 0) {
-      if (force < DISC_V_COL_3STAGE_VEC || force > DISC_V_COL_STRIP_SCALAR)
+      const bool two = force == DISC_V_COL_2STAGE_VEC || force == DISC_V_COL_2STAGE_SCALAR;
+      if ((force < DISC_V_COL_3STAGE_VEC || force > DISC_V_COL_STRIP_SCALAR) && !two)
         return set_err(c, DISC_ERR_INVALID_ARG, "forced version does not belong to a column-reduce pattern");
-      want_vec = force == DISC_V_COL_3STAGE_VEC || force == DISC_V_COL_STRIP_VEC;
+      if (two && !p.gen.has_epilogue)
+        return set_err(c, DISC_ERR_INVALID_ARG, "the two-launch version needs an output that keeps the reduced axis");
+      want_vec = force == DISC_V_COL_3STAGE_VEC || force == DISC_V_COL_STRIP_VEC || force == DISC_V_COL_2STAGE_VEC;
       want_strip = force == DISC_V_COL_STRIP_VEC || force == DISC_V_COL_STRIP_SCALAR;
+      want_two = two;
     }
     bool vec;
     {
@@ -589,8 +593,10 @@ int make_plan(disc_ctx* c, const Pattern& p, const int64_t* dims, int n_dims, in
     const int v = vec ? V : 1;
     const int64_t spr = (inner + v - 1) / v;
     // Small problems: one launch, a block per strip of columns (reduce, finish and epilogue in the
-    // same kernel).  Three launches cost ~12 us whatever the size; below about a million elements
-    // that is more than the work.
+    // same kernel).  A launch that makes a round trip to memory costs 5-6 us whatever it moves; up
+    // to about a million elements one such launch (4.5-10 us measured on 1024 fp32 columns) beats
+    // two (12 us).  Measured alternatives: the strip version up to two million elements (17 us at
+    // 1500 rows: too few blocks) and 128 narrower strips instead of 64 (no gain).
     int64_t total;
     const bool small = !mul_ovf(outer * mid, inner, &total) && total <= (1ll << 20);
     const bool strip = want_strip >= 0 ? want_strip != 0 : small;
@@ -600,12 +606,13 @@ int make_plan(disc_ctx* c, const Pattern& p, const int64_t* dims, int n_dims, in
       while (GC < 64 && (GC * (vec ? 16 : 4) < 32 || spr / (GC * 2) >= 64)) GC *= 2;
       GC = std::min<int>(GC, 1 << ilog2_ceil(std::min<int64_t>(spr, 64)));
       const int64_t col_tiles = (spr + GC - 1) / GC;
-      DeviceColPlan cp{GC, ilog2_ceil(GC), 1, 0, mid, outer};
+      DeviceColPlan cp{GC, ilog2_ceil(GC), 1, 0, mid, outer, 0};
       fp->aux[0] = 0;
       fp->aux[1] = outer * inner * 8;
       fp->ws_off[0] = 0;
       fp->ws_off[1] = 0;
-      pub.workspace_bytes = (size_t)p.gen.n_red_planes * (size_t)fp->aux[1];
+      // (with an epilogue the reduce results stay in registers; without, they go to the planes)
+      pub.workspace_bytes = p.gen.has_epilogue ? 0 : (size_t)p.gen.n_red_planes * (size_t)fp->aux[1];
       pub.variant = vec ? DISC_V_COL_STRIP_VEC : DISC_V_COL_STRIP_SCALAR;
       pub.lanes_per_row = GC;
       pub.vec_width = v;
@@ -624,17 +631,42 @@ int make_plan(disc_ctx* c, const Pattern& p, const int64_t* dims, int n_dims, in
       snprintf(pub.kernel[0], sizeof pub.kernel[0], "%s%s", p.gen.prefix.c_str(), kernel_name(L0.kid));
       return DISC_OK;
     }
-    int GC = 1 << ilog2_ceil(std::min<int64_t>(spr, 64));
+    // Lanes along the columns per block: 16 lanes of one vector each (256 bytes of a row: two
+    // whole cache lines) unless the rows are narrower; the other lanes of the block run down the
+    // rows.  Narrow column tiles give the grid its width: with 64 lanes across, 1024 fp32 columns
+    // are only 4 tiles, and the chunks of the reduced axis would have to supply all the parallelism.
+    constexpr int64_t kTwoLaunchChunks = 32;
+    // (narrow tensors: 8 or 4 lanes across when that yields more blocks, down to 64-byte row pieces)
+    int GC = 1 << ilog2_ceil(std::min<int64_t>(spr, 16));
+    {
+      auto blocks_at = [&](int gc) {
+        const int64_t t = (spr + gc - 1) / gc * std::min<int64_t>(outer, 65535);
+        const int64_t maxc = std::max<int64_t>(1, mid / (4ll * (256 / gc)));
+        return std::min<int64_t>(t * std::min<int64_t>(kTwoLaunchChunks, maxc), (int64_t)c->n_cus * 2);
+      };
+      int best = GC;
+      for (int gc = GC >> 1; gc >= 4; gc >>= 1)
+        if (blocks_at(gc) > blocks_at(best)) best = gc;
+      GC = best;
+    }
     const int TY = 256 / GC;
     const int64_t col_tiles = (spr + GC - 1) / GC;
-    // chunks of the reduced axis: enough blocks to fill the chip, at least 4 rows per row-lane
-    int64_t target_blocks = (int64_t)c->n_cus * 4;
-    int64_t nchunk = (target_blocks + col_tiles * outer - 1) / (col_tiles * outer);
+    const int64_t tiles = col_tiles * std::min<int64_t>(outer, 65535);
+    // Chunks of the reduced axis: enough blocks for two per CU, at least four rows per row-lane.
+    // Up to kTwoLaunchChunks chunks the second launch can afford to merge the partials of its own
+    // columns in every block (a few loads per lane), which saves the finish launch and the round
+    // trip of the reduce results through memory: the two-launch version.  A reduced axis so long
+    // and narrow that it needs more chunks than that keeps the separate finish launch.
     const int64_t max_chunks = std::max<int64_t>(1, mid / (4ll * TY));
-    nchunk = std::max<int64_t>(1, std::min<int64_t>(std::min<int64_t>(nchunk, max_chunks), 1024));
+    int64_t nchunk = ((int64_t)c->n_cus * 2 + tiles - 1) / tiles;
+    nchunk = std::max<int64_t>(1, std::min<int64_t>(nchunk, max_chunks));
+    bool two = p.gen.has_epilogue && nchunk <= kTwoLaunchChunks;
+    if (want_two >= 0) two = want_two != 0;
+    if (two) nchunk = std::min<int64_t>(nchunk, kTwoLaunchChunks);
+    else nchunk = std::min<int64_t>(std::max<int64_t>(1, std::min<int64_t>(((int64_t)c->n_cus * 4 + tiles - 1) / tiles, max_chunks)), 1024);
     const int64_t chunk_rows = (mid + nchunk - 1) / nchunk;
     nchunk = (mid + chunk_rows - 1) / chunk_rows;
-    DeviceColPlan cp{GC, ilog2_ceil(GC), (int32_t)nchunk, 0, chunk_rows, outer};
+    DeviceColPlan cp{GC, ilog2_ceil(GC), (int32_t)nchunk, 0, chunk_rows, outer, 0};
     int64_t cells, red_bytes;
     if (mul_ovf(outer * nchunk, inner, &cells) || mul_ovf(cells, (int64_t)p.gen.n_acc_cells * 8, &red_bytes))
       return set_err(c, DISC_ERR_SHAPE, "workspace size overflows int64");
@@ -642,8 +674,6 @@ int make_plan(disc_ctx* c, const Pattern& p, const int64_t* dims, int n_dims, in
     fp->aux[1] = outer * inner * 8;     // bytes per reduce-result plane
     fp->ws_off[0] = 0;
     fp->ws_off[1] = ((size_t)red_bytes + 255) / 256 * 256;
-    pub.workspace_bytes = fp->ws_off[1] + (size_t)p.gen.n_red_planes * (size_t)fp->aux[1];
-    pub.variant = vec ? DISC_V_COL_3STAGE_VEC : DISC_V_COL_3STAGE_SCALAR;
     pub.lanes_per_row = GC;
     LaunchRec& L0 = fp->launches[0];
     L0.kid = vec ? K_COL_PARTIAL_VEC : K_COL_PARTIAL_SCALAR;
@@ -651,23 +681,51 @@ int make_plan(disc_ctx* c, const Pattern& p, const int64_t* dims, int n_dims, in
     L0.grid[1] = (uint32_t)nchunk;
     L0.grid[2] = (uint32_t)std::min<int64_t>(outer, 65535);
     L0.plan_kind = 2;
-    L0.cp = cp;
-    LaunchRec& L1 = fp->launches[1];
-    L1.kid = K_COL_FINISH;
-    L1.grid[0] = (uint32_t)((inner + 63) / 64);
-    L1.grid[1] = (uint32_t)std::min<int64_t>(outer, 65535);
-    L1.plan_kind = 2;
-    L1.cp = cp;
-    pub.n_launches = 2;
-    if (p.gen.has_epilogue) {
-      static const int names[] = {K_COL_EPI_VEC, K_COL_EPI_VEC_I64, K_COL_EPI_SCALAR, K_COL_EPI_SCALAR_I64};
-      bool v2, i64;
-      rc = plan_loop(c, sv.rows, inner, V, vec ? 1 : 0, -1, names, K_COL_EPI_VEC_NT, full_aligned(), sv.alg_bytes >= kNonTemporalMinBytes, fp, &fp->launches[2], &v2, &i64);
-      if (rc) return rc;
-      pub.n_launches = 3;
-    } else {
+    if (two) {
+      // second launch: column tiles x row ranges, about eight blocks per CU; every lane gets at
+      // least four rows so that the merge of the partials stays a small part of the block's work
+      int64_t row_blocks = std::max<int64_t>(1, ((int64_t)c->n_cus * 8 + tiles - 1) / tiles);
+      row_blocks = std::min<int64_t>(std::min<int64_t>(row_blocks, max_chunks), 65535);
+      cp.epi_rows = (mid + row_blocks - 1) / row_blocks;
+      row_blocks = (mid + cp.epi_rows - 1) / cp.epi_rows;
+      pub.workspace_bytes = (size_t)red_bytes;   // partials only: the reduce results stay in registers
+      pub.variant = vec ? DISC_V_COL_2STAGE_VEC : DISC_V_COL_2STAGE_SCALAR;
       pub.vec_width = v;
       pub.index_bits = 64;
+      L0.cp = cp;
+      LaunchRec& L1 = fp->launches[1];
+      // non-temporal stores for large launches with aligned rows: the results then do not push the
+      // operand, which the second launch reads again, out of the memory-side cache
+      const bool nt = vec && v > 1 && inner % v == 0 && c->row_nt != 0 &&
+                      (c->row_nt > 0 || (sv.alg_bytes >= kNonTemporalMinBytes && full_aligned()));
+      L1.kid = vec ? (nt ? K_COL_EPI2_VEC_NT : K_COL_EPI2_VEC) : K_COL_EPI2_SCALAR;
+      L1.grid[0] = (uint32_t)col_tiles;
+      L1.grid[1] = (uint32_t)row_blocks;
+      L1.grid[2] = (uint32_t)std::min<int64_t>(outer, 65535);
+      L1.plan_kind = 2;
+      L1.cp = cp;
+      pub.n_launches = 2;
+    } else {
+      pub.workspace_bytes = fp->ws_off[1] + (size_t)p.gen.n_red_planes * (size_t)fp->aux[1];
+      pub.variant = vec ? DISC_V_COL_3STAGE_VEC : DISC_V_COL_3STAGE_SCALAR;
+      L0.cp = cp;
+      LaunchRec& L1 = fp->launches[1];
+      L1.kid = K_COL_FINISH;
+      L1.grid[0] = (uint32_t)((inner + 15) / 16);   // 16 columns per block
+      L1.grid[1] = (uint32_t)std::min<int64_t>(outer, 65535);
+      L1.plan_kind = 2;
+      L1.cp = cp;
+      pub.n_launches = 2;
+      if (p.gen.has_epilogue) {
+        static const int names[] = {K_COL_EPI_VEC, K_COL_EPI_VEC_I64, K_COL_EPI_SCALAR, K_COL_EPI_SCALAR_I64};
+        bool v2, i64;
+        rc = plan_loop(c, sv.rows, inner, V, vec ? 1 : 0, -1, names, K_COL_EPI_VEC_NT, full_aligned(), sv.alg_bytes >= kNonTemporalMinBytes, fp, &fp->launches[2], &v2, &i64);
+        if (rc) return rc;
+        pub.n_launches = 3;
+      } else {
+        pub.vec_width = v;
+        pub.index_bits = 64;
+      }
     }
   }
   for (int l = 0; l < pub.n_launches; ++l) {
@@ -884,7 +942,7 @@ static std::string static_macros(const Pattern& p, const FullPlan& fp, const int
       << "; rp.rpb = " << L.rp.rpb << ";";
   else if (L.plan_kind == 2)
     a << " rp.GC = " << L.cp.GC << "; rp.log2GC = " << L.cp.log2GC << "; rp.nchunk = " << L.cp.nchunk << "; rp.chunk_rows = "
-      << L.cp.chunk_rows << "LL; rp.outer = " << L.cp.outer << "LL;";
+      << L.cp.chunk_rows << "LL; rp.outer = " << L.cp.outer << "LL; rp.epi_rows = " << L.cp.epi_rows << "LL;";
   a << "\n";
   return a.str();
 }

@@ -45,7 +45,8 @@ FORCED = {
     "C0": (["loop_vec", "loop_vec_i64", "loop_scalar", "loop_scalar_i64"], [[37, 768], [5, 13]]),
     "C1": (["row_reg_vec", "row_reg_scalar", "row_stream_vec", "row_stream_scalar"], [[2, 3, 77], [1, 2, 256]]),
     "C2": (["row_reg_vec", "row_reg_scalar", "row_stream_vec", "row_stream_scalar"], [[33, 768], [9, 1021]]),
-    "C3": (["col_3stage_vec", "col_3stage_scalar", "col_strip_vec", "col_strip_scalar"], [[700, 1024], [129, 37], [3, 1024]]),
+    "C3": (["col_3stage_vec", "col_3stage_scalar", "col_strip_vec", "col_strip_scalar", "col_2stage_vec", "col_2stage_scalar"],
+           [[700, 1024], [129, 37], [3, 1024], [4099, 519]]),
     "C4": (["row_reg_vec", "row_reg_scalar", "row_stream_vec", "row_stream_scalar"], [[41, 1000], [7, 2040]]),
 }
 
@@ -221,7 +222,7 @@ def test_outer_sum_and_rank3_column_reduce(ctx):
     assert hd.info["template"] == "col_reduce"
     for B, T, C in ((1, 1, 1), (3, 50, 17), (2, 700, 256), (70, 9, 8)):
         ins = [torch.randn(B, T, C, generator=g), torch.randn(C, generator=g)]
-        for v in (None, "col_3stage_vec", "col_3stage_scalar", "col_strip_vec", "col_strip_scalar"):
+        for v in (None, "col_3stage_vec", "col_3stage_scalar", "col_strip_vec", "col_strip_scalar", "col_2stage_vec", "col_2stage_scalar"):
             compare(ctx, pat, [B, T, C], ins, "rank3 col", force=v, handle=hd)
 
 
@@ -307,8 +308,10 @@ def test_launch_errors_and_stats(ctx):
     dims = [100, 64]
     ins = [t.cuda() for t in cfg.inputs(dims, seed=1)]
     outs = alloc_outputs(pat, dims, "cuda")
+    big = [20000, 300]                   # partials of the chunks go through the workspace
+    ins_b = [t.cuda() for t in cfg.inputs(big, seed=2)]
     with pytest.raises(DiscError) as e:
-        h.launch(dims, ins, outs, workspace=torch.empty(16, dtype=torch.uint8, device="cuda"))
+        h.launch(big, ins_b, alloc_outputs(pat, big, "cuda"), workspace=torch.empty(16, dtype=torch.uint8, device="cuda"))
     assert e.value.status == "WORKSPACE"
     with pytest.raises(DiscError) as e:
         h.launch(dims, ins[:0], outs)
@@ -321,12 +324,18 @@ def test_launch_errors_and_stats(ctx):
     assert after["launch_calls"] == before["launch_calls"] + 1
     assert after["device_launches"] == before["device_launches"] + 1      # small: the single-launch version
     assert after["compile_events"] == before["compile_events"]
-    big = [5000, 300]
-    ins_b = [t.cuda() for t in cfg.inputs(big, seed=2)]
     h.launch(big, ins_b, alloc_outputs(pat, big, "cuda"),
              workspace=torch.empty(ctx.workspace_bytes(h.id, big), dtype=torch.uint8, device="cuda"))
     torch.cuda.synchronize()
-    assert ctx.stats()["device_launches"] == after["device_launches"] + 3   # partial, finish, epilogue
+    assert ctx.stats()["device_launches"] == after["device_launches"] + 2   # partial, finish + epilogue
+    ctx.force_variant(V("col_3stage_vec"))
+    try:
+        h.launch(big, ins_b, alloc_outputs(pat, big, "cuda"),
+                 workspace=torch.empty(ctx.workspace_bytes(h.id, big), dtype=torch.uint8, device="cuda"))
+    finally:
+        ctx.force_variant(-1)
+    torch.cuda.synchronize()
+    assert ctx.stats()["device_launches"] == after["device_launches"] + 5   # partial, finish, epilogue
     # zero rows: success, nothing launched
     c0 = CONFIGS["C0"]
     p0 = c0.pattern()

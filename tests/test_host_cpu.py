@@ -321,7 +321,7 @@ def test_single_shape_registration(ctx, handles):
     c3 = CONFIGS["C3"].pattern()
     big = ctx.register_static(c3, [5000, 1024])
     small = ctx.register_static(c3, [100, 1024])
-    assert big.info["n_variants"] == 3 and small.info["n_variants"] == 1
+    assert big.info["n_variants"] == 2 and small.info["n_variants"] == 1      # partial + finish-and-epilogue; one strip kernel
     assert "rp.nchunk = " in big.source and "A.mid = 5000LL;" in big.source
     # nothing to launch, nothing to specialise
     expect("SHAPE", ctx.register_static, pat, [0, 64])
@@ -347,19 +347,31 @@ def test_loop_and_index_width_selection(ctx, handles):
 
 def test_col_reduce_plan_and_workspace(ctx, handles):
     h = handles["C3"]
+    # the usual case: two launches, the second finishes and applies the epilogue
     p = h.plan([65536, 1024])
-    assert p["variant_name"] == "col_3stage_vec" and p["n_launches"] == 3 and p["mid"] == 65536
+    assert p["variant_name"] == "col_2stage_vec" and p["n_launches"] == 2 and p["mid"] == 65536
+    assert p["kernels"][0].endswith("k_col_partial_vec") and p["kernels"][1].endswith("k_col_epi2_vec_nt")
     assert p["workspace_bytes"] > 0 and ctx.workspace_bytes(h.id, [65536, 1024]) == p["workspace_bytes"]
-    assert p["grid"][0][1] > 1                                    # the reduced axis is cut into chunks
+    assert 1 < p["grid"][0][1] <= 32                              # the reduced axis is cut into a few chunks
+    assert p["grid"][0][0] * p["grid"][0][1] >= 512               # ... on narrow column tiles: the chip is filled
+    assert p["grid"][1][0] == p["grid"][0][0] and p["grid"][1][1] > p["grid"][0][1]
+    assert h.plan([3000, 1024])["kernels"][1].endswith("k_col_epi2_vec")      # small launches keep plain stores
+    # a long and narrow reduced axis needs more chunks than the second launch can merge per block:
+    # the separate finish launch stays
+    q = h.plan([2000000, 8])
+    assert q["variant_name"] == "col_3stage_vec" and q["n_launches"] == 3 and q["grid"][0][1] > 32
+    assert q["kernels"][1].endswith("k_col_finish")
+    f3 = h.plan([65536, 1024], V["col_3stage_vec"])
+    assert f3["n_launches"] == 3 and f3["workspace_bytes"] > p["workspace_bytes"]
     assert h.plan([1, 1024], V["col_3stage_vec"])["grid"][0][1] == 1
+    assert h.plan([1, 1024], V["col_2stage_vec"])["grid"][0][1] == 1
     assert ctx.workspace_bytes(handles["C4"].id, [10, 10]) == 0
-    # up to about a million elements: one launch, a block per strip of columns; the workspace then
-    # holds the reduce results only
+    # up to about a million elements: one launch, a block per strip of columns, no workspace
     s = h.plan([512, 1024])
     assert s["variant_name"] == "col_strip_vec" and s["n_launches"] == 1 and s["kernels"][0].endswith("k_col_strip_vec")
     assert s["grid"][0][0] * s["lanes_per_row"] * s["vec_width"] >= 1024 and s["grid"][0][0] >= 32
-    assert 0 < s["workspace_bytes"] < p["workspace_bytes"]
-    assert h.plan([1025, 1024])["variant_name"] == "col_3stage_vec"
+    assert s["workspace_bytes"] == 0                       # reduce results stay in registers
+    assert h.plan([1025, 1024])["variant_name"] == "col_2stage_vec"
     assert h.plan([7, 5])["variant_name"] == "col_strip_scalar"
     forced = h.plan([300, 1024], V["col_3stage_scalar"])
     assert forced["variant_name"] == "col_3stage_scalar" and forced["n_launches"] == 3

@@ -119,7 +119,8 @@ def test_integer_row_and_column_reductions_are_bit_exact(ctx, dtype, bits):
     pb.output(m)
     pb.output(pb.op("sub", a, pb.broadcast(m, [t, h], [1])))
     col_pat = pb.build()
-    for dims, force in (([300, 64], None), ([5000, 257], None), ([2100, 600], "col_3stage_vec"), ([77, 33], "col_strip_scalar")):
+    for dims, force in (([300, 64], None), ([5000, 257], None), ([2100, 600], "col_3stage_vec"), ([77, 33], "col_strip_scalar"),
+                        ([3000, 130], "col_2stage_scalar")):
         av = _ints((dims[0], dims[1]), tdt, 21 + dims[1], bits)
         print(f"[int col] {dtype} dims={dims} force={force}", flush=True)
         check(ctx, col_pat, dims, [av], f"int col {dtype}", force=force)

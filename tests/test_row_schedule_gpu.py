@@ -12,6 +12,7 @@ from oracle import run as oracle_run
 from workloads import PatternBuilder
 from workloads.configs import CONFIGS
 from tests.util import assert_close, run_gpu, to_oracle_input
+from paper_2103_05288_amd import VARIANTS
 
 pytestmark = pytest.mark.gpu
 
@@ -98,6 +99,11 @@ def test_non_temporal_versions_any_alignment(monkeypatch):
         plan = check(c, "C0", [300, 768], seed=9)
         assert plan["kernels"][0].endswith("k_loop_vec_nt"), plan["kernels"]
         plan = check(c, "C3", [3000, 1024], seed=10)
+        assert plan["kernels"][-1].endswith("k_col_epi2_vec_nt"), plan["kernels"]
+        c.force_variant(VARIANTS.index("col_3stage_vec"))
+        check(c, "C3", [3000, 1024], seed=10)
+        c.force_variant(-1)
+        plan = c.register(CONFIGS["C3"].pattern()).plan([3000, 1024], VARIANTS.index("col_3stage_vec"))
         assert plan["kernels"][-1].endswith("k_col_epi_vec_nt"), plan["kernels"]
     finally:
         c.close()

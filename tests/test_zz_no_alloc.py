@@ -44,7 +44,7 @@ def test_static_scratch_matches_disc_launch_twice_second_smaller(ctx):
     cfg = CONFIGS["C3"]
     pat = cfg.pattern()
     h = ctx.register(pat)
-    for dims in ([5000, 1024], [1100, 1024], [4097, 333]):
+    for dims in ([5000, 1024], [2500, 1024], [4097, 1333]):
         assert h.plan(dims)["workspace_bytes"] > 0 and h.plan(dims)["n_launches"] >= 2
         print(f"[static scratch] C3 dims={dims}", flush=True)
         _both_ways(ctx, h, pat, dims, cfg.inputs(dims, seed=dims[0]), "C3")
