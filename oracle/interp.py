@@ -60,6 +60,16 @@ with those standard meanings:
                             operand's element type (HLO pad), so unlike computed values it IS
                             rounded to that type (nearest even) when it is not representable
 
+* ne_prev / compact / compact_count / compact_rank : outputs whose size depends on the input
+                            values (Section 2 gives Unique as the example of such an op).  Over
+                            rank-1 values of one length N: ne_prev(x)[i] = (i == 0) or x[i] != x[i-1];
+                            compact(value, keep) = the elements of value at the positions where
+                            keep is nonzero, in order -- an array of the data-dependent length
+                            n = compact_count(keep), NOT padded to the declared upper bound N;
+                            compact_rank(keep)[i] = (number of kept positions <= i) - 1.
+                            compact(x, ne_prev(x)) is Unique of a sorted x, compact_rank its
+                            second result (the index of every element in the output)
+
 Inputs stored as f16 / bf16 are converted to float64 by the caller (every such
 value is exactly representable); the oracle itself only sees numpy arrays.
 """
@@ -300,9 +310,32 @@ def _run(pattern, dims, inputs):
             fill = _as_dtype(np.asarray(_round_to_storage(op.fconst, op.dtype), dtype=np.float64), op.dtype)
             v = np.full(want, fill, dtype=x.dtype)
             v[tuple(slice(l0, l0 + m) for l0, m in zip(low, x.shape))] = x
+        elif oc == "ne_prev":
+            x = vals[op.ins[0]]
+            if x.ndim != 1:
+                raise OracleError(f"op {idx}: ne_prev takes a rank-1 operand")
+            v = np.ones(x.shape, dtype=bool)          # the first element opens the first run
+            v[1:] = x[1:] != x[:-1]
+        elif oc == "compact":
+            x, keep = vals[op.ins[0]], vals[op.ins[1]]
+            if x.ndim != 1 or keep.shape != x.shape:
+                raise OracleError(f"op {idx}: compact takes two rank-1 operands of one length")
+            v = x[keep != 0].copy()                   # data-dependent length, order kept
+            vals[idx] = v
+            continue                                  # (its length is the result, not the declared bound)
+        elif oc == "compact_count":
+            v = _wrap(np.asarray(np.count_nonzero(vals[op.ins[0]] != 0), dtype=np.int64), op.dtype)
+        elif oc == "compact_rank":
+            keep = vals[op.ins[0]]
+            if keep.ndim != 1:
+                raise OracleError(f"op {idx}: compact_rank takes a rank-1 operand")
+            v = np.cumsum((keep != 0).astype(np.int64)) - 1
         elif oc == "output":
             v = vals[op.ins[0]]
             outs.append(v)
+            if pattern.ops[op.ins[0]].opcode == "compact":
+                vals[idx] = v
+                continue
         else:
             raise OracleError(f"op {idx}: unknown opcode {oc}")
         v = _wrap(np.asarray(v), op.dtype)

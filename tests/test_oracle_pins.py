@@ -734,3 +734,73 @@ def test_mid_chain_cast_to_16_bit_rounds_and_output_cast_does_not():
     # and the rounding agrees with torch's conversion
     t = torch.tensor(xs, dtype=torch.float32)
     assert torch.equal(t.to(torch.bfloat16).to(torch.float64), torch.tensor([_bf16_rne_py(float(v)) for v in xs], dtype=torch.float64))
+
+
+# ---------------------------------------------------------------- data-dependent output sizes (Unique-style)
+def _unique_sorted_pattern(dtype="i32"):
+    pb = PatternBuilder()
+    n = pb.dim()
+    x = pb.param(dtype, [n])
+    keep = pb.ne_prev(x)
+    pb.output(pb.compact(x, keep))
+    pb.output(pb.compact_rank(keep))
+    pb.output(pb.compact_count(keep))
+    return pb.build()
+
+
+def test_unique_of_sorted_input_matches_python_sets():
+    pat = _unique_sorted_pattern()
+    r = np.random.default_rng(3)
+    for n, hi in ((1, 3), (2, 1), (17, 4), (300, 7), (300, 100000), (1000, 2)):
+        x = np.sort(r.integers(-hi, hi + 1, size=n))
+        y, idx, cnt = run(pat, [n], [x])[0]
+        want = sorted(set(int(v) for v in x))                 # distinct values, ascending = order of first occurrence
+        assert y.tolist() == want and int(cnt) == len(want)
+        assert y.shape == (len(want),)                        # the output HAS the data-dependent length
+        assert [want[i] for i in idx.tolist()] == x.tolist()  # idx maps every element to its slot in y
+        assert idx.tolist() == [want.index(int(v)) for v in x]
+    # all equal: one value; all distinct: everything kept
+    y, idx, cnt = run(pat, [5], [np.array([4, 4, 4, 4, 4])])[0]
+    assert y.tolist() == [4] and idx.tolist() == [0] * 5 and int(cnt) == 1
+    y, idx, cnt = run(pat, [4], [np.array([-2, 0, 1, 9])])[0]
+    assert y.tolist() == [-2, 0, 1, 9] and idx.tolist() == [0, 1, 2, 3] and int(cnt) == 4
+
+
+def test_ne_prev_marks_run_starts_also_in_unsorted_input():
+    pb = PatternBuilder()
+    n = pb.dim()
+    x = pb.param("f32", [n])
+    pb.output(pb.cast(pb.ne_prev(x), "i32"))
+    x = np.array([1.5, 1.5, -2.0, -2.0, -2.0, 1.5, 0.0, -0.0, 7.0])
+    got = run(pb.build(), [len(x)], [x])[0][0].tolist()
+    assert got == [1] + [int(x[i] != x[i - 1]) for i in range(1, len(x))] == [1, 0, 1, 0, 0, 1, 1, 0, 1]
+
+
+def test_compaction_by_a_computed_predicate_matches_list_comprehension():
+    """keep = (x * w > c): the kept values of another expression, in order; none kept and all kept."""
+    pb = PatternBuilder()
+    n = pb.dim()
+    x = pb.param("f32", [n])
+    w = pb.param("f32", [n])
+    thr = pb.param("f32", [])            # a rank-0 input decides how much survives
+    keep = pb.op("gt", pb.op("mul", x, w), thr, dims=[n])
+    pb.output(pb.compact(pb.op("add", x, pb.const(1.0), dims=[n]), keep))
+    pb.output(pb.compact(pb.cast(w, "i32"), keep))
+    pb.output(pb.compact_count(keep, "i64"))
+    pb.output(pb.compact_rank(keep, "i64"))
+    pat = pb.build()
+    r = np.random.default_rng(8)
+    xv = r.normal(size=200)
+    wv = np.round(r.normal(size=200) * 4)
+    for c in (0.0, -1e9, 1e9, 2.5):
+        y, wi, cnt, rank = run(pat, [200], [xv, wv, np.asarray(c)])[0]
+        kept = [i for i in range(200) if float(xv[i]) * float(wv[i]) > c]
+        assert y.tolist() == [float(xv[i]) + 1.0 for i in kept]
+        assert wi.tolist() == [int(wv[i]) for i in kept]
+        assert int(cnt) == len(kept) == y.shape[0]
+        seen, want_rank = 0, []
+        for i in range(200):
+            seen += i in kept
+            want_rank.append(seen - 1)
+        assert rank.tolist() == want_rank
+    assert run(pat, [200], [xv, wv, np.asarray(1e9)])[0][0].shape == (0,)      # nothing kept: an empty result

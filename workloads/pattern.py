@@ -33,6 +33,12 @@ Conventions
   padding, no negative padding.
 * ``transpose``     : HLO transpose: result axis ``k`` is operand axis ``axis_map[k]``
   (``axis_map`` is a permutation).
+* ``ne_prev`` / ``compact`` / ``compact_count`` / ``compact_rank`` : outputs whose size depends
+  on the input values (Section 2 names Unique as that kind of op), over rank-1 values of one
+  length N.  ``ne_prev(x)[i] = (i == 0) or x[i] != x[i-1]``; ``compact(value, keep)`` keeps the
+  elements of ``value`` where ``keep`` is nonzero, in order (its declared dim is the upper bound
+  N; ``compact_count(keep)`` of them are defined); ``compact_rank(keep)[i]`` = number of kept
+  positions ``<= i``, minus one.  ``compact(x, ne_prev(x))`` with the rank is Unique of a sorted x.
 """
 from __future__ import annotations
 
@@ -46,7 +52,9 @@ UNARY = ("neg", "abs", "exp", "log", "tanh", "sqrt", "rsqrt", "rcp", "sigmoid", 
 BINARY = ("add", "sub", "mul", "div", "max", "min", "pow")
 COMPARE = ("lt", "le", "gt", "ge", "eq", "ne")
 REDUCE = ("reduce_sum", "reduce_max", "reduce_min", "reduce_argmax")
-OPCODES = LEAF + UNARY + BINARY + COMPARE + ("select", "cast", "broadcast") + REDUCE + ("output", "slice", "pad", "transpose")
+COMPACTION = ("ne_prev", "compact", "compact_count", "compact_rank")
+OPCODES = (LEAF + UNARY + BINARY + COMPARE + ("select", "cast", "broadcast") + REDUCE + ("output", "slice", "pad", "transpose")
+           + COMPACTION)
 
 DIM_EQ = 0      # dimension-size equality constraint
 NUMEL_EQ = 1    # tensor-size equality constraint
@@ -188,6 +196,20 @@ class PatternBuilder:
             if s_ >= 0:
                 self.p.n_dims = max(self.p.n_dims, s_ + 1)
         return self._push(Op("pad", src.dtype, (v,), tuple(sizes), tuple(int(x) for x in low), float(value)))
+
+    def ne_prev(self, v: int) -> int:
+        src = self.p.ops[v]
+        return self._push(Op("ne_prev", "bool", (v,), src.dims))
+
+    def compact(self, value: int, keep: int) -> int:
+        src = self.p.ops[value]
+        return self._push(Op("compact", src.dtype, (value, keep), src.dims))
+
+    def compact_count(self, keep: int, dtype: str = "i32") -> int:
+        return self._push(Op("compact_count", dtype, (keep,), ()))
+
+    def compact_rank(self, keep: int, dtype: str = "i32") -> int:
+        return self._push(Op("compact_rank", dtype, (keep,), self.p.ops[keep].dims))
 
     def output(self, v: int) -> int:
         src = self.p.ops[v]
