@@ -66,12 +66,13 @@ class Arena:
                 b = min(numel, a + chunk)
                 self.buf[a:b] = (torch.rand(b - a, device=device, generator=g) < 0.1).to(dtype)
 
-    def take(self, shape):
+    def take(self, shape, shift=0):
+        """`shift` elements past the 256-byte aligned position: deliberately misaligned operands."""
         n = int(np.prod(shape))
-        if self.pos + n > self.buf.numel():
+        if self.pos + n + shift > self.buf.numel():
             self.pos = 0
-        v = self.buf[self.pos:self.pos + n].view(*shape)
-        self.pos += (n + self.align - 1) // self.align * self.align
+        v = self.buf[self.pos + shift:self.pos + shift + n].view(*shape)
+        self.pos += (n + shift + self.align - 1) // self.align * self.align
         return v
 
 
@@ -109,24 +110,31 @@ class Sweep:
                       for k, oi in enumerate(pat.outputs)]
         ws_need = max(ctx.workspace_bytes(self.handle.id, d) for d in self.calls)
         self.workspace = torch.empty(max(ws_need, 256), dtype=torch.uint8, device=dev)
-        rng = np.random.default_rng(4242)
-        for d in self.calls:
-            ins = [arenas_in[k].take(s) for k, s in enumerate(in_shapes(d))]
-            if self.name == "C1":
-                # real key-padding mask (0 / -1e4) from per-batch valid lengths
-                B, NH, S = d
-                lens = torch.from_numpy(rng.integers(1, S + 1, size=B)).to(dev)
-                keys = torch.arange(S, device=dev).view(1, 1, 1, S)
-                ins[1] = torch.where(keys < lens.view(B, 1, 1, 1), 0.0, -1.0e4).to(torch.float16).contiguous()
-            if self.name == "C0":
-                ins[1] = ins[1] * 0.02
-            if self.name == "C2":
-                ins[3] = (ins[3].float() * 0.1 + 1.0).to(ins[3].dtype)
-                ins[4] = (ins[4].float() * 0.1).to(ins[4].dtype)
-            outs = [arenas_out[k].take(s) for k, s in enumerate(out_shapes(d))]
-            self.bound.append((d, ins, outs))
+        self.bound_shifted = []
+        # second pass over the same arenas: every operand and result one element past its 256-byte
+        # aligned position (the labelled misaligned-bases sweep)
+        for shift in (0, 1):
+            rng = np.random.default_rng(4242)
+            for a in arenas_in + arenas_out:
+                a.pos = 0
+            for d in self.calls:
+                ins = [arenas_in[k].take(s, shift) for k, s in enumerate(in_shapes(d))]
+                if self.name == "C1":
+                    # real key-padding mask (0 / -1e4) from per-batch valid lengths
+                    B, NH, S = d
+                    lens = torch.from_numpy(rng.integers(1, S + 1, size=B)).to(dev)
+                    keys = torch.arange(S, device=dev).view(1, 1, 1, S)
+                    ins[1] = torch.where(keys < lens.view(B, 1, 1, 1), 0.0, -1.0e4).to(torch.float16).contiguous()
+                if self.name == "C0":
+                    ins[1] = ins[1] * 0.02
+                if self.name == "C2":
+                    ins[3] = (ins[3].float() * 0.1 + 1.0).to(ins[3].dtype)
+                    ins[4] = (ins[4].float() * 0.1).to(ins[4].dtype)
+                outs = [arenas_out[k].take(s, shift) for k, s in enumerate(out_shapes(d))]
+                (self.bound if shift == 0 else self.bound_shifted).append((d, ins, outs))
         # arguments marshalled once per call site; the timed loop is one C call per launch
         self.calls_bound = [self.handle.bind(d, ins, outs, workspace=self.workspace) for d, ins, outs in self.bound]
+        self.calls_shifted = [self.handle.bind(d, ins, outs, workspace=self.workspace) for d, ins, outs in self.bound_shifted]
 
     def bind_streams(self, streams):
         """The same calls dealt out round-robin over several streams (independent requests may
@@ -142,6 +150,10 @@ class Sweep:
 
     def run_all(self):
         for c in self.calls_bound:
+            c()
+
+    def run_all_shifted(self):
+        for c in self.calls_shifted:
             c()
 
     def run_one(self, i):
@@ -247,7 +259,7 @@ def next_rows(ctx, dev):
     graph's / pattern's inputs and outputs, each once, over the device time of one call."""
     from workloads.configs import TORCH_DTYPE
     from workloads.extras import (gelu_backward_bias_gradient, heads_softmax, layernorm_backward_graph,
-                                  logsumexp_with_total_and_amax, padded_softmax, pure_transpose, qkv_split)
+                                  logsumexp_with_total_and_amax, padded_softmax, pure_transpose, qkv_split, unique_of_sorted)
 
     def io_bytes(pat, dims):
         n = 0
@@ -286,13 +298,113 @@ def next_rows(ctx, dev):
         rows[name] = dict({"dims": dims, "io_bytes": io_bytes(pat, dims), "us": round(t * 1e6, 2),
                            "GBps": round(io_bytes(pat, dims) / t / 1e9, 1)}, **extra)
         del ins, outs, ws
+    # an output whose size depends on the data: Unique of a sorted tensor (about one value in sixteen
+    # is new).  Bytes = the input, the index of every element, and what was actually kept.
+    pat = unique_of_sorted("i32")
+    n = 1 << 27
+    x = torch.sort(torch.randint(0, n // 16, (n,), device=dev, generator=gen, dtype=torch.int32)).values
+    outs = [torch.empty(n, dtype=torch.int32, device=dev), torch.empty(n, dtype=torch.int32, device=dev),
+            torch.zeros(1, dtype=torch.int64, device=dev)]
+    h = ctx.register(pat)
+    ws = torch.empty(max(16, ctx.workspace_bytes(h.id, [n])), dtype=torch.uint8, device=dev)
+    call = h.bind([n], [x], outs, workspace=ws)
+    call()
+    torch.cuda.synchronize()
+    kept = int(outs[2][0])
+    t = min(time_events(lambda: [call() for _ in range(10)]) for _ in range(3)) / 10
+    moved = 4 * n + 4 * n + 4 * kept + 8
+    rows["unique_of_sorted_i32"] = {"dims": [n], "kept": kept, "io_bytes": moved, "us": round(t * 1e6, 2),
+                                    "GBps": round(moved / t / 1e9, 1), "kernels": h.plan([n])["kernels"], "template": h.info["template"],
+                                    "expected_traffic_over_io_bytes": round((8 * n + 4 * n + 4 * kept) / moved, 3),
+                                    "note": "three launches; the input is read twice (count pass, scatter pass)"}
+    del x, outs, ws
     return rows
 
 
+def mix_ceiling(ctx, dev):
+    """The practical ceiling for the row kernels' traffic mix: streaming probes that move 3 bytes read :
+    2 written per element with one 1-byte stream (the 12-op pattern) and 4 : 2 (residual + LayerNorm)
+    and do next to no arithmetic, plain and non-temporal, swept over the grid size and the bytes in
+    flight per lane.  The best rate of each mix is what the fused kernels are compared with."""
+    n = 1 << 27                                   # elements of 2 bytes: 256 MB per 2-byte stream
+    a = torch.zeros(n, dtype=torch.int16, device=dev)
+    b = torch.zeros(n, dtype=torch.int16, device=dev)
+    m = torch.zeros(n, dtype=torch.uint8, device=dev)
+    out = torch.empty(n, dtype=torch.int16, device=dev)
+    res = {}
+    for kind, name, bytes_per_elem in ((0, "read3_write2_with_byte_stream", 5), (1, "read4_write2", 6)):
+        rows = []
+        for nt in (0, 1):
+            for u in (1, 2, 4, 8):
+                for bpc in (2, 4, 8, 16, 32):
+                    call = lambda: ctx.util_mix(kind, nt, u, bpc, out, a, m if kind == 0 else b, n)
+                    call()
+                    torch.cuda.synchronize()
+                    t = min(time_events(call) for _ in range(3))
+                    rows.append({"non_temporal": nt, "slots_in_flight": u, "blocks_per_cu": bpc,
+                                 "GBps": round(bytes_per_elem * n / t / 1e9, 1)})
+        best = max(rows, key=lambda r: r["GBps"])
+        best_plain = max((r for r in rows if not r["non_temporal"]), key=lambda r: r["GBps"])
+        res[name] = {"best": best, "best_plain": best_plain, "configs_tried": len(rows),
+                     "worst_GBps": min(r["GBps"] for r in rows)}
+    del a, b, m, out
+    return res
+
+
+def accuracy_report(sweeps, rows_per_call=48, calls_per_cfg=4):
+    """16-bit outputs against the oracle on sampled rows, outside the timed region: the largest
+    relative error with no absolute term (over |oracle| > 1e-3) and the fraction of those elements
+    beyond 2e-3 -- the literal bar of the benchmark spec, which a correctly rounded bf16 value can
+    miss by itself (half a unit in the last place of bf16 is up to 2^-8 = 3.9e-3 of the value)."""
+    from oracle import run as oracle_run
+    out = {}
+    for sw in sweeps:
+        pat = sw.pattern
+        kinds = {pat.ops[o].dtype for o in pat.outputs}
+        if not (kinds & {"f16", "bf16"}):
+            continue
+        order = np.argsort(sw.bytes)
+        picks = [int(order[int(q * (len(order) - 1))]) for q in np.linspace(0.35, 1.0, calls_per_cfg)]
+        worst, n_all, n_bad, worst_ulp = 0.0, 0, 0, 0.0
+        for i in picks:
+            d, ins, outs = sw.bound[i]
+            sw.run_one(i)
+            torch.cuda.synchronize()
+            lead = d[0]
+            lo = max(0, lead // 2 - rows_per_call // 2)
+            hi = min(lead, lo + rows_per_call) if sw.name != "C1" else min(lead, lo + 1)
+            sub, dims = [], list(d)
+            dims[0] = hi - lo
+            for t, pi in zip(ins, pat.params):
+                op = pat.ops[pi]
+                t = t[lo:hi] if (len(op.dims) >= 1 and op.dims[0] == 0) else t
+                t = t.cpu()
+                sub.append(t.to(torch.float64).numpy() if t.dtype.is_floating_point else t.numpy())
+            want = oracle_run(pat, dims, sub)[0]
+            for o_t, w, oi in zip(outs, want, pat.outputs):
+                if pat.ops[oi].dtype not in ("f16", "bf16"):
+                    continue
+                g = o_t[lo:hi].cpu().to(torch.float64).numpy()
+                sel = np.abs(w) > 1e-3
+                rel = np.abs(g - w)[sel] / np.abs(w)[sel]
+                if rel.size:
+                    worst = max(worst, float(rel.max()))
+                    n_all += int(rel.size)
+                    n_bad += int((rel > 2e-3).sum())
+                    bits = 7 if pat.ops[oi].dtype == "bf16" else 10
+                    ulp = np.exp2(np.floor(np.log2(np.abs(w)[sel])) - bits)
+                    worst_ulp = max(worst_ulp, float((np.abs(g - w)[sel] / ulp).max()))
+        out[sw.name] = {"storage": sorted(kinds & {"f16", "bf16"})[0], "calls_checked": len(picks), "elements": n_all,
+                        "max_rel_err_atol0": float("%.3e" % worst), "fraction_beyond_2e-3": float("%.3e" % (n_bad / max(1, n_all))),
+                        "max_err_in_ulps_of_storage": round(worst_ulp, 3)}
+    return out
+
+
 def cpu_baseline(sweeps, budget_s=20.0):
-    """Oracle (as it stands) on a bounded sample of the sweep: calls in sweep order, smallest
-    element counts first skipped none, until the time budget is used; row-independent patterns
-    are evaluated in row chunks on a thread pool (numpy releases the GIL inside ufuncs)."""
+    """Oracle (as it stands) on a bounded sample of the sweep: per configuration the calls in order of
+    element count, smallest first, none above 256 MiB, until that configuration's share of the time
+    budget is used; row-independent patterns are evaluated in row chunks on a thread pool (numpy
+    releases the GIL inside ufuncs)."""
     from oracle import run as oracle_run
     cores = min(os.cpu_count() or 1, 16)
     pool = ThreadPoolExecutor(max_workers=cores)
@@ -337,7 +449,8 @@ def cpu_baseline(sweeps, budget_s=20.0):
         total_s += used
         n_calls += n
     pool.shutdown()
-    return {"value": round(total_bytes / total_s / 1e9, 4), "unit": "GB/s", "cores": cores, "kind": "oracle",
+    return {"value": round(total_bytes / total_s / 1e9, 4), "unit": "GB/s", "cores": cores, "host_cpu_count": os.cpu_count(),
+            "kind": "oracle",
             "sample": f"{n_calls} smallest-first calls of the C0-C4 sweeps (<= 256 MiB each), ~{budget_s:.0f} s of CPU work; "
                       "C0/C2/C4 row-chunked over a thread pool, C1/C3 one numpy call",
             "per_config": detail}
@@ -433,8 +546,14 @@ def main():
         long_rows = [i for i, pl in enumerate(plans) if pl["inner"] >= 1024]
         big = [i for i in range(len(sw.calls)) if sw.bytes[i] >= (32 << 20)]
         gb = lambda idx: (sum(sw.bytes[i] for i in idx) / max(1e-12, sum(per_call[i] for i in idx)) / 1e9) if idx else None
+        sw.run_all_shifted()
+        torch.cuda.synchronize()
+        t_shift = min(time_events(sw.run_all_shifted) for _ in range(3))
+        n_launch = [pl["n_launches"] for pl in plans]
         per_cfg[sw.name] = {
             "calls": len(sw.calls), "bytes": sum(sw.bytes), "sweep_ms": round(t_cfg * 1e3, 4),
+            "device_launches": int(sum(n_launch)),
+            "GBps_sweep_misaligned_bases": round(sum(sw.bytes) / t_shift / 1e9, 1),
             "GBps_sweep": round(sum(sw.bytes) / t_cfg / 1e9, 1),
             "GBps_sum_of_calls": round(gb(list(range(len(sw.calls)))), 1),
             "GBps_rows_ge_1024": None if gb(long_rows) is None else round(gb(long_rows), 1),
@@ -480,20 +599,37 @@ def main():
     s1 = ctx.stats()
     host_idle_us = (s1["host_launch_ns"] - s0["host_launch_ns"]) / 2048 / 1e3
 
+    # latency-adjusted bound: a call cannot finish faster than its launches' fixed cost t0 plus its
+    # bytes at the peak rate; t0 = the measured back-to-back cost of an empty launch
+    for sw in sweeps:
+        pc = per_cfg[sw.name]
+        plans = [sw.handle.plan(d) for d in sw.calls]
+        bound_s = sum(pl["n_launches"] * t_empty + b / (PEAK_HBM_GBPS * 1e9) for pl, b in zip(plans, sw.bytes))
+        pc["latency_adjusted_bound_GBps"] = round(sum(sw.bytes) / bound_s / 1e9, 1)
+        pc["frac_of_latency_adjusted_bound"] = round(pc["GBps_sweep"] / pc["latency_adjusted_bound_GBps"], 4)
+    mix = mix_ceiling(ctx, dev)
+    mix_best = {"C4": mix["read3_write2_with_byte_stream"]["best"]["GBps"], "C2": mix["read4_write2"]["best"]["GBps"]}
+
     dom_name, dom_kernel, dom = dominant
     achieved = dom["bytes"] / dom["seconds"] / 1e9
     # measured HBM traffic per launch of that kernel over the same sweep (rocprofv3 FETCH_SIZE / WRITE_SIZE,
     # scaled by what the counters read for the plain copy kernel): recorded under profiles/
-    traffic = None
+    traffic, traffic_commit = None, None
     tpath = os.path.join(ROOT, "profiles", "traffic.json")
     if os.path.exists(tpath):
-        rec = json.load(open(tpath)).get(dom_kernel)
+        tj = json.load(open(tpath))
+        rec = tj.get(dom_kernel)
         traffic = rec["bytes_per_launch"] if rec else None
+        traffic_commit = tj.get("_commit")
     roofline = {"bound": "hbm", "kernel": f"{dom_name}:{dom_kernel}", "achieved": round(achieved, 1), "peak": PEAK_HBM_GBPS,
                 "unit": "GB/s", "frac": round(achieved / PEAK_HBM_GBPS, 4), "traffic": traffic,
                 "launches": dom["launches"], "avg_launch_us": round(dom["seconds"] / dom["launches"] * 1e6, 2),
                 "bytes_per_launch": int(dom["bytes"] / dom["launches"]),
-                "frac_of_copy_ceiling": round(achieved / copy_gbps, 4)}
+                "traffic_source": "profiles/traffic.json (rocprofv3 FETCH_SIZE / WRITE_SIZE passes over this command)"
+                                  + (f" at commit {traffic_commit}" if traffic_commit else ""),
+                "frac_of_copy_ceiling": round(achieved / copy_gbps, 4),
+                "mix_ceiling_GBps": mix_best.get(dom_name),
+                "frac_of_mix_ceiling": round(achieved / mix_best[dom_name], 4) if dom_name in mix_best else None}
 
     out = {
         "metric": "effective HBM GB/s over the dynamic-shape sweep (C0-C4), one compile per pattern",
@@ -508,6 +644,10 @@ def main():
         "roofline": roofline,
         "copy_ceiling_GBps": round(copy_gbps, 1),
         "copy_nt_ceiling_GBps": round(copy_nt_gbps, 1),
+        "mix_ceiling": mix,
+        "rows_ge_1024_vs_mix_ceiling": {n: round(per_cfg[n]["GBps_rows_ge_1024"] / mix_best[n], 4)
+                                        for n in mix_best if n in per_cfg and per_cfg[n]["GBps_rows_ge_1024"]},
+        "accuracy_16bit_outputs": accuracy_report(sweeps),
         "empty_launch_us": round(t_empty * 1e6, 2),
         "host_launch_us_per_call": round(host_idle_us, 2), "host_plan_us_per_call": round(plan_us, 3),
         "host_launch_us_per_call_queue_full": round(host_us, 2),

@@ -114,6 +114,22 @@ typedef enum {
                       it cannot be fused with anything (DISC_ERR_UNFUSIBLE), but is a pattern on its
                       own (PARAM, TRANSPOSE, OUTPUT: DISC_TEMPLATE_TRANSPOSE) when it collapses to a
                       batched 2-D transpose; disc_register_graph cuts it out that way.          */
+  /* ---- outputs whose size depends on the input VALUES (Section 2 names Unique as the op whose
+   * output shape is only known once the data is: the other source of dynamic shapes besides varying
+   * input shapes).  All four live in a pattern of rank-1 values of one length N
+   * (DISC_TEMPLATE_COMPACT); the results of the last three may only feed OUTPUTs. */
+  DISC_NE_PREV,       /* in[0] = a PARAM x of rank 1; DISC_BOOL result[i] = (i == 0) || x[i] != x[i-1]: marks
+                         the first element of every run of equal values                              */
+  DISC_COMPACT,       /* in = (value, keep); rank 1, dim = N (the upper bound), dtype of value:
+                         result[k] = value[i_k], where i_0 < i_1 < ... are the positions with keep != 0.
+                         Only the first n = COMPACT_COUNT(keep) elements of the OUTPUT buffer are written;
+                         the caller sizes it for N.  COMPACT(x, NE_PREV(x)) is Unique of a sorted x
+                         (distinct values in order of first occurrence)                              */
+  DISC_COMPACT_COUNT, /* in[0] = keep; rank 0, DISC_I32 or DISC_I64: the number n of positions kept -- the
+                         data-dependent size, delivered in device memory (nothing is synchronised)   */
+  DISC_COMPACT_RANK,  /* in[0] = keep; rank 1, dim = N, DISC_I32 or DISC_I64: result[i] = (number of kept
+                         positions <= i) - 1.  For keep = NE_PREV(x) this is Unique's second result: the
+                         index in the compacted output of the value at position i                    */
   DISC_OPCODE_COUNT
 } disc_opcode;
 
@@ -157,9 +173,14 @@ typedef enum {
                                    losses, the amax of a tensor): one partial result per block,
                                    folded by a last launch of one block                         */
   DISC_TEMPLATE_COL_REDUCE = 2, /* input fusion, reduce over an outer axis (+ epilogue)         */
-  DISC_TEMPLATE_TRANSPOSE = 3   /* not a fusion: PARAM -> TRANSPOSE -> OUTPUT alone, a permutation
+  DISC_TEMPLATE_TRANSPOSE = 3,  /* not a fusion: PARAM -> TRANSPOSE -> OUTPUT alone, a permutation
                                    that moves the innermost axis, run as a batched 2-D tile
                                    transpose (what an op graph falls back to for such an op)    */
+  DISC_TEMPLATE_COMPACT = 4     /* loop fusion over rank-1 values whose outputs are compacted by a
+                                   predicate computed in the same pattern (DISC_COMPACT and
+                                   friends): per-block counts, a fixed-order scan of the counts, a
+                                   scatter -- three launches, no atomics, the element count written
+                                   to device memory                                              */
 } disc_template;
 
 typedef struct {
@@ -193,6 +214,8 @@ typedef enum {
   DISC_V_TRANSPOSE_TILE,    /* batched 2-D transpose through a 64 x 64 tile in LDS              */
   DISC_V_COL_2STAGE_VEC,    /* column reduce: partial -> finish + epilogue in one kernel (2 launches) */
   DISC_V_COL_2STAGE_SCALAR,
+  DISC_V_COMPACT_VEC,       /* compaction: count -> scan -> scatter, vector loads               */
+  DISC_V_COMPACT_SCALAR,
   DISC_V_COUNT
 } disc_variant;
 
@@ -366,6 +389,14 @@ int disc_util_copy(disc_ctx* ctx, void* dst, const void* src, size_t bytes, void
 /* The same copy with non-temporal loads and stores (the faster of the two on large buffers). */
 int disc_util_copy_nt(disc_ctx* ctx, void* dst, const void* src, size_t bytes, void* hip_stream);
 int disc_util_empty_launch(disc_ctx* ctx, void* hip_stream);
+/* A streaming probe with the traffic mix of the row kernels and next to no arithmetic: the practical
+ * ceiling those kernels are measured against.  Per element of 2 bytes: kind 0 reads 2 bytes of `a` and
+ * 1 byte of `b_or_mask` and writes 2 bytes of `out` (3 read : 2 written, the 12-op pattern's mix);
+ * kind 1 reads 2 bytes each of `a` and `b_or_mask` and writes 2 (4 : 2, residual + LayerNorm).  Device
+ * pointers, 16-byte aligned; n_elems a multiple of 8; slots_in_flight in {1, 2, 4, 8} (16-byte slots
+ * per lane in flight); blocks_per_cu 1..64 (grid = that x CUs, grid-stride). */
+int disc_util_mix(disc_ctx* ctx, int kind, int non_temporal, int slots_in_flight, int blocks_per_cu, void* out, const void* a,
+                  const void* b_or_mask, size_t n_elems, void* hip_stream);
 
 #ifdef __cplusplus
 }

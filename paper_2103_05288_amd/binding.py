@@ -17,15 +17,16 @@ DTYPE_IDS = {"f32": 0, "f16": 1, "bf16": 2, "i32": 3, "i64": 4, "bool": 5}
 _OPCODES = ("param", "const", "dim_size", "neg", "abs", "exp", "log", "tanh", "sqrt", "rsqrt", "rcp",
             "sigmoid", "erf", "add", "sub", "mul", "div", "max", "min", "pow", "lt", "le", "gt", "ge",
             "eq", "ne", "select", "cast", "broadcast", "reduce_sum", "reduce_max", "reduce_min",
-            "reduce_argmax", "output", "slice", "pad", "transpose")
+            "reduce_argmax", "output", "slice", "pad", "transpose", "ne_prev", "compact", "compact_count", "compact_rank")
 OPCODE_IDS = {n: i for i, n in enumerate(_OPCODES)}
 VARIANTS = ("loop_vec", "loop_vec_i64", "loop_scalar", "loop_scalar_i64", "row_reg_vec", "row_reg_scalar",
             "row_stream_vec", "row_stream_scalar", "col_3stage_vec", "col_3stage_scalar", "col_strip_vec",
-            "col_strip_scalar", "transpose_tile", "col_2stage_vec", "col_2stage_scalar")
+            "col_strip_scalar", "transpose_tile", "col_2stage_vec", "col_2stage_scalar",
+            "compact_vec", "compact_scalar")
 STATUS = {0: "OK", -1: "INVALID_ARG", -2: "BAD_PATTERN", -3: "UNFUSIBLE", -4: "CONSTRAINT", -5: "WORKSPACE",
           -6: "COMPILE", -7: "HIP", -8: "SHAPE", -9: "EMPTY_REDUCE", -10: "INTERNAL"}
 TEST_OPTIONS = {"non_temporal": 0, "stage_row_vectors": 1, "row_rounds": 2}
-TEMPLATES = ("loop", "row_reduce", "col_reduce", "transpose")
+TEMPLATES = ("loop", "row_reduce", "col_reduce", "transpose", "compact")
 
 
 class disc_op(C.Structure):
@@ -82,7 +83,7 @@ EXPORTS = ("disc_create", "disc_destroy", "disc_last_error", "disc_register_patt
            "disc_pattern_info",
            "disc_pattern_source", "disc_workspace_bytes", "disc_plan", "disc_launch", "disc_force_variant", "disc_test_option",
            "disc_static_scratch_init", "disc_launch_static_scratch",
-           "disc_get_stats", "disc_util_copy", "disc_util_copy_nt", "disc_util_empty_launch", "disc_register_graph", "disc_graph_info",
+           "disc_get_stats", "disc_util_copy", "disc_util_copy_nt", "disc_util_empty_launch", "disc_util_mix", "disc_register_graph", "disc_graph_info",
            "disc_graph_workspace_bytes", "disc_graph_launch")
 
 _lib = None
@@ -131,6 +132,7 @@ def load_library():
     lib.disc_util_copy.argtypes = [vp, vp, vp, C.c_size_t, vp]
     lib.disc_util_copy_nt.argtypes = [vp, vp, vp, C.c_size_t, vp]
     lib.disc_util_empty_launch.argtypes = [vp, vp]
+    lib.disc_util_mix.argtypes = [vp, C.c_int, C.c_int, C.c_int, C.c_int, vp, vp, vp, C.c_size_t, vp]
     _lib = lib
     return lib
 
@@ -373,6 +375,15 @@ class Context:
         fn = self.lib.disc_util_copy_nt if non_temporal else self.lib.disc_util_copy
         self._check(fn(self.h, C.c_void_p(_ptr(dst)), C.c_void_p(_ptr(src)),
                                             C.c_size_t(nbytes), C.c_void_p(stream)))
+
+    def util_mix(self, kind: int, non_temporal: bool, slots_in_flight: int, blocks_per_cu: int, out, a, b_or_mask, n_elems: int,
+                 stream: Optional[int] = None):
+        if stream is None:
+            import torch
+            stream = torch.cuda.current_stream().cuda_stream
+        self._check(self.lib.disc_util_mix(self.h, int(kind), int(bool(non_temporal)), int(slots_in_flight), int(blocks_per_cu),
+                                           C.c_void_p(_ptr(out)), C.c_void_p(_ptr(a)), C.c_void_p(_ptr(b_or_mask)),
+                                           C.c_size_t(n_elems), C.c_void_p(stream)))
 
     def util_empty_launch(self, stream: Optional[int] = None):
         if stream is None:

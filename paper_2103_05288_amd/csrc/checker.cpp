@@ -43,7 +43,8 @@ const char* opcode_name(int oc) {
   static const char* names[] = {"param", "const", "dim_size", "neg", "abs", "exp", "log", "tanh",
     "sqrt", "rsqrt", "rcp", "sigmoid", "erf", "add", "sub", "mul", "div", "max", "min", "pow",
     "lt", "le", "gt", "ge", "eq", "ne", "select", "cast", "broadcast", "reduce_sum", "reduce_max",
-    "reduce_min", "reduce_argmax", "output", "slice", "pad", "transpose"};
+    "reduce_min", "reduce_argmax", "output", "slice", "pad", "transpose", "ne_prev", "compact", "compact_count",
+    "compact_rank"};
   if (oc < 0 || oc >= DISC_OPCODE_COUNT) return "?";
   return names[oc];
 }
@@ -105,8 +106,10 @@ bool is_elementwise(int oc) {
 }
 int n_operands(int oc) {
   if (oc <= DISC_DIM_SIZE) return 0;
-  if (is_unary(oc) || oc == DISC_CAST || oc == DISC_BROADCAST || is_reduce(oc) || oc == DISC_OUTPUT || oc == DISC_SLICE || oc == DISC_PAD || oc == DISC_TRANSPOSE)
+  if (is_unary(oc) || oc == DISC_CAST || oc == DISC_BROADCAST || is_reduce(oc) || oc == DISC_OUTPUT || oc == DISC_SLICE || oc == DISC_PAD || oc == DISC_TRANSPOSE ||
+      oc == DISC_NE_PREV || oc == DISC_COMPACT_COUNT || oc == DISC_COMPACT_RANK)
     return 1;
+  if (oc == DISC_COMPACT) return 2;
   if (oc == DISC_SELECT) return 3;
   return 2;
 }
@@ -202,6 +205,30 @@ struct Builder {
       a.slot = slot;
       n.access = (int)an.accesses.size();
       an.accesses.push_back(a);
+    } else if (oc == DISC_NE_PREV) {
+      // two reads of the same PARAM: the element itself and its predecessor (an access of its own,
+      // one element earlier)
+      n.in[0] = demand(op.in[0], c);
+      if (n.in[0] < 0) return -1;
+      Node pn;
+      const disc_op& src = an.ops[op.in[0]];
+      pn.opcode = DISC_PARAM;
+      pn.dtype = src.dtype;
+      pn.rk = reg_kind(src.dtype);
+      pn.value = op.in[0];
+      pn.ctx = c;
+      Access a = an.accesses[an.nodes[n.in[0]].access];
+      a.prev = true;
+      pn.access = (int)an.accesses.size();
+      an.accesses.push_back(a);
+      n.in[1] = (int)an.nodes.size();
+      an.nodes.push_back(pn);
+      n.n_in = 2;
+    } else if (oc == DISC_COMPACT) {
+      // the kept values are the value itself; where they go is decided by the kernel
+      int id = demand(op.in[0], c);
+      memo[key] = id;
+      return id;
     } else if (oc == DISC_CONST) {
       n.fconst = op.fconst;
     } else if (oc == DISC_DIM_SIZE) {
@@ -266,7 +293,8 @@ struct KernelNames {
         "k_row_stream_vec", "k_row_stream_scalar", "k_colsum_finish", "k_rowred_finish",
         "k_col_partial_vec", "k_col_partial_scalar", "k_col_finish", "k_col_strip_vec", "k_col_strip_scalar",
         "k_col_epi_vec", "k_col_epi_vec_i64", "k_col_epi_scalar", "k_col_epi_scalar_i64", "k_col_epi_vec_nt",
-        "k_transpose_tile", "k_col_epi2_vec", "k_col_epi2_vec_nt", "k_col_epi2_scalar"};
+        "k_transpose_tile", "k_col_epi2_vec", "k_col_epi2_vec_nt", "k_col_epi2_scalar",
+        "k_compact_count_vec", "k_compact_count_scalar", "k_compact_scan", "k_compact_scatter_vec", "k_compact_scatter_scalar"};
     for (int i = 0; i < K_ROW_BASE; ++i) name[i] = fixed[i];
     for (int sc = 0; sc < 2; ++sc)
       for (int n = 1; n <= 3; ++n)
@@ -289,6 +317,106 @@ int kernel_id(const std::string& name) {
   for (int i = 0; i < K_COUNT; ++i)
     if (t.name[i] == name) return i;
   return -1;
+}
+
+// A pattern with DISC_COMPACT / COMPACT_COUNT / COMPACT_RANK outputs (Section 2: Unique-style ops,
+// whose output size depends on the input values): a loop fusion over rank-1 values of one length N
+// that computes the values and ONE predicate; what is kept goes to the outputs in order.
+// Called after validation and constraint closure.
+static int analyze_compact(Analysis& an, std::string& err) {
+  const std::vector<disc_op>& ops = an.ops;
+  const int n_ops = (int)ops.size();
+  char buf[256];
+  auto fail = [&](int code, int i, const char* what) {
+    snprintf(buf, sizeof buf, "op %d (%s): %s", i, opcode_name(ops[i].opcode), what);
+    err = buf;
+    return code;
+  };
+  int keep = -1, root = -1;
+  for (int i = 0; i < n_ops; ++i) {
+    const disc_op& op = ops[i];
+    const int oc = op.opcode;
+    if (oc == DISC_BROADCAST || is_reduce(oc) || oc == DISC_SLICE || oc == DISC_PAD || oc == DISC_TRANSPOSE)
+      return fail(DISC_ERR_UNFUSIBLE, i, "a pattern with compacted outputs is a loop fusion over rank-1 values of one length: "
+                                         "no broadcast, reduction, slice, pad or transpose");
+    if (op.rank > 1) return fail(DISC_ERR_UNFUSIBLE, i, "a pattern with compacted outputs works on rank-1 values");
+    if (oc == DISC_COMPACT || oc == DISC_COMPACT_COUNT || oc == DISC_COMPACT_RANK) {
+      const int k = oc == DISC_COMPACT ? op.in[1] : op.in[0];
+      if (keep >= 0 && k != keep) return fail(DISC_ERR_UNFUSIBLE, i, "all compactions of one pattern share one predicate");
+      keep = k;
+      if (oc == DISC_COMPACT && ops[op.in[0]].opcode >= DISC_COMPACT && ops[op.in[0]].opcode <= DISC_COMPACT_RANK)
+        return fail(DISC_ERR_UNFUSIBLE, i, "a compaction result cannot be compacted again in the same pattern");
+    } else if (oc != DISC_OUTPUT) {
+      for (int k = 0; k < n_operands(oc); ++k)
+        if (ops[op.in[k]].opcode >= DISC_COMPACT && ops[op.in[k]].opcode <= DISC_COMPACT_RANK)
+          return fail(DISC_ERR_UNFUSIBLE, i, "a compaction result may only feed OUTPUTs (its size is not known to the host)");
+    } else if (ops[op.in[0]].opcode < DISC_COMPACT || ops[op.in[0]].opcode > DISC_COMPACT_RANK) {
+      return fail(DISC_ERR_UNFUSIBLE, i, "every OUTPUT of a pattern with compacted outputs is a COMPACT, COMPACT_COUNT or COMPACT_RANK result");
+    }
+    if (op.rank == 1 && root < 0) root = i;
+  }
+  if (keep < 0) { err = "NE_PREV is supported in patterns whose outputs are compacted (COMPACT / COMPACT_COUNT / COMPACT_RANK)"; return DISC_ERR_UNFUSIBLE; }
+  DimClasses& dc = an.classes;
+  for (int i = 0; i < n_ops; ++i)
+    if (ops[i].rank == 1 && !dc.same(dc.atom(ops[i].dim[0]), dc.atom(ops[root].dim[0])))
+      return fail(DISC_ERR_UNFUSIBLE, i, "its length cannot be proved equal to that of the other values; add a DIM_EQ constraint");
+  an.tmpl = DISC_TEMPLATE_COMPACT;
+  an.root_rank = 1;
+  an.root_dims.assign(1, ops[root].dim[0]);
+  an.reduce_axis = -1;
+  an.groups.assign(1, std::vector<int>(1, 0));
+  an.inner_group = 0;
+  Builder b(an, err);
+  const Ctx ident(1, 0);
+  an.compact_keep = b.demand(keep, ident);
+  if (an.compact_keep < 0) return b.status;
+  for (int i = 0; i < n_ops; ++i) {
+    if (ops[i].opcode != DISC_OUTPUT) continue;
+    const disc_op& src = ops[ops[i].in[0]];
+    OutputRef o;
+    Access a;
+    a.value = i;
+    a.is_output = true;
+    a.dtype = ops[i].dtype;
+    a.slot = (int)an.outputs.size();
+    if (src.opcode == DISC_COMPACT) {
+      o.node = b.demand(src.in[0], ident);
+      if (o.node < 0) return b.status;
+      a.compact = true;
+      a.ctx = ident;
+    } else {
+      o.node = an.compact_keep;
+      a.compact_rank = src.opcode == DISC_COMPACT_RANK;
+      a.compact_count = src.opcode == DISC_COMPACT_COUNT;
+      if (a.compact_rank) a.ctx = ident;
+    }
+    o.access = (int)an.accesses.size();
+    an.accesses.push_back(a);
+    an.outputs.push_back(o);
+  }
+  if (b.status != DISC_OK) return b.status;
+  for (auto& a : an.accesses) {
+    a.groups.clear();
+    if (!a.ctx.empty()) a.groups.push_back(0);
+    a.has_inner = !a.ctx.empty();
+    a.kind = a.has_inner ? ACC_FULL : ACC_SCALAR;
+  }
+  for (auto& n : an.nodes) {
+    n.dom = (n.opcode == DISC_CONST || n.opcode == DISC_DIM_SIZE || n.ctx.empty()) ? DOM_SCALAR : DOM_ELEM;
+    n.phase = 0;
+  }
+  an.n_phases = 0;
+  an.group_size.assign(1, DimProduct());
+  mul_into(an.group_size[0], dc, ops[root].dim[0]);
+  for (auto& n : an.nodes)
+    if (n.opcode == DISC_DIM_SIZE &&
+        std::find(an.dim_size_syms.begin(), an.dim_size_syms.end(), n.sym_dim) == an.dim_size_syms.end())
+      an.dim_size_syms.push_back(n.sym_dim);
+  int min_bytes = 8;
+  for (const auto& a : an.accesses)
+    if (a.has_inner && a.dtype != DISC_BOOL && !a.compact_rank) min_bytes = std::min(min_bytes, dtype_bytes(a.dtype));
+  an.vec_width = std::min(8, 16 / min_bytes);
+  return DISC_OK;
 }
 
 // loop_sides: sums over the rows next to a loop fusion may ride along in a row template without
@@ -339,8 +467,8 @@ static int analyze_impl(const disc_op* ops, int n_ops, const disc_constraint* cs
       ++n_out;
       if (op.dtype != ops[op.in[0]].dtype) return bad("OUTPUT dtype differs from its value");
       if (op.rank != ops[op.in[0]].rank) return bad("OUTPUT rank differs from its value");
-      if (op.rank == 0 && !is_reduce(ops[op.in[0]].opcode))
-        return bad("rank-0 outputs are supported only for reductions of per-row values over the rows");
+      if (op.rank == 0 && !is_reduce(ops[op.in[0]].opcode) && ops[op.in[0]].opcode != DISC_COMPACT_COUNT)
+        return bad("rank-0 outputs are supported only for reductions of per-row values over the rows and for COMPACT_COUNT");
     }
     if (is_unary(oc) && oc != DISC_NEG && oc != DISC_ABS && !is_float_dtype(op.dtype))
       return bad("transcendental op needs a float dtype");
@@ -392,6 +520,21 @@ static int analyze_impl(const disc_op* ops, int n_ops, const disc_constraint* cs
         if (op.axis_map[k] < 0 || op.axis_map[k] >= op.rank || (seen >> op.axis_map[k] & 1)) return bad("TRANSPOSE needs a permutation");
         seen |= 1 << op.axis_map[k];
       }
+    }
+    if (oc == DISC_NE_PREV) {
+      const disc_op& src = ops[op.in[0]];
+      if (src.opcode != DISC_PARAM || src.rank != 1) return bad("NE_PREV applies to a PARAM of rank 1");
+      if (op.dtype != DISC_BOOL || op.rank != 1) return bad("NE_PREV gives a DISC_BOOL value of rank 1");
+    }
+    if (oc == DISC_COMPACT) {
+      if (op.rank != 1 || ops[op.in[0]].rank != 1 || ops[op.in[1]].rank != 1) return bad("COMPACT takes and gives rank-1 values");
+      if (ops[op.in[1]].dtype != DISC_BOOL) return bad("COMPACT's second operand is the DISC_BOOL predicate");
+      if (ops[op.in[0]].dtype != op.dtype) return bad("COMPACT changes dtype");
+    }
+    if (oc == DISC_COMPACT_COUNT || oc == DISC_COMPACT_RANK) {
+      if (ops[op.in[0]].dtype != DISC_BOOL || ops[op.in[0]].rank != 1) return bad("operand must be a DISC_BOOL predicate of rank 1");
+      if (op.dtype != DISC_I32 && op.dtype != DISC_I64) return bad("result must be DISC_I32 or DISC_I64");
+      if (op.rank != (oc == DISC_COMPACT_RANK ? 1 : 0)) return bad("COMPACT_COUNT has rank 0, COMPACT_RANK rank 1");
     }
     if (oc == DISC_BROADCAST) {
       const disc_op& src = ops[op.in[0]];
@@ -454,6 +597,11 @@ static int analyze_impl(const disc_op* ops, int n_ops, const disc_constraint* cs
         if (!unite(i, src.dim[k], op.dim[r])) return DISC_ERR_BAD_PATTERN;
         ++r;
       }
+    } else if (oc == DISC_NE_PREV || oc == DISC_COMPACT || oc == DISC_COMPACT_RANK) {
+      // shape propagation: one length N for operands and result (a COMPACT result's dim is the
+      // upper bound of its data-dependent length)
+      for (int k = 0; k < n_operands(oc); ++k)
+        if (!unite(i, ops[op.in[k]].dim[0], op.dim[0])) return DISC_ERR_BAD_PATTERN;
     }
   }
   // caller-supplied constraints (what the framework bridging would inject)
@@ -478,6 +626,10 @@ static int analyze_impl(const disc_op* ops, int n_ops, const disc_constraint* cs
       return badc("unknown kind");
     }
   }
+
+  // ---- outputs whose size depends on the data ---------------------------------------------------
+  for (int i = 0; i < n_ops; ++i)
+    if (ops[i].opcode >= DISC_NE_PREV && ops[i].opcode <= DISC_COMPACT_RANK) return analyze_compact(an, err);
 
   // ---- a transpose on its own -----------------------------------------------------------------
   // PARAM -> TRANSPOSE -> OUTPUT with a permutation that moves the innermost axis is not a fusion

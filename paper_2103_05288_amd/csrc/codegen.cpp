@@ -79,6 +79,7 @@ struct Gen {
   static bool is_reduce(int oc) { return oc >= DISC_REDUCE_SUM && oc <= DISC_REDUCE_ARGMAX; }
   bool col_tmpl() const { return an.tmpl == DISC_TEMPLATE_COL_REDUCE; }
   bool row_tmpl() const { return an.tmpl == DISC_TEMPLATE_ROW_REDUCE; }
+  bool compact_tmpl() const { return an.tmpl == DISC_TEMPLATE_COMPACT; }
   // small cached operands of a row reduce are loaded at their point of use, not into the slot
   bool late(const Access& a) const { return row_tmpl() && !a.is_output && a.has_inner && a.kind != ACC_FULL && !a.all_outer; }
 
@@ -314,6 +315,12 @@ struct Gen {
           static const char* sym[] = {"<", "<=", ">", ">=", "==", "!="};
           return as(n.in[0], kc) + " " + sym[n.opcode - DISC_LT] + " " + as(n.in[1], kc);
         }
+        case DISC_NE_PREV: {
+          // the first element of the tensor opens the first run; in[1] is the same operand read one
+          // element earlier
+          const RegKind kc = g.an.nodes[n.in[0]].rk;
+          return "((disc::i64)col + e == 0) || (" + as(n.in[0], kc) + " != " + as(n.in[1], kc) + ")";
+        }
         case DISC_SELECT: return as(n.in[0], RK_BOOL) + " ? " + a(1) + " : " + a(2);
         case DISC_CAST:
           // float -> int truncates toward zero in C.  A cast to a 16-bit float type whose value is
@@ -436,6 +443,7 @@ struct Gen {
   // load of a slot of an operand; a padded one takes the padding value wherever the operand is not
   std::string load_call(const Access& a, size_t i, const std::string& dst, const std::string& ld_tmpl, const std::string& extra) {
     const std::string ptr = elem_ptr(a, fmt("A.p%d", a.slot));
+    if (a.prev) return "disc::ld_prev(" + dst + ", " + ptr + ", (disc::i64)" + elem_base(a, i) + ", sp);";
     if (!a.padded) return "disc::ld" + ld_tmpl + "(" + dst + ", " + ptr + ", " + elem_base(a, i) + ", sp" + extra + ");";
     std::string lo = "0", hi = "0x7fffffffffffffffLL";
     for (size_t t = 0; t < a.groups.size(); ++t)
@@ -544,7 +552,7 @@ struct Gen {
 
   // outputs written per element by the epilogue (column reduce: only those that keep the reduced axis)
   bool elem_output(const Access& a) const {
-    if (!a.has_inner || a.col_sum) return false;
+    if (!a.has_inner || a.col_sum || a.compact_rank) return false;
     if (!col_tmpl()) return true;
     for (int g : a.groups) if (g == an.mid_group) return true;
     return false;
@@ -570,6 +578,7 @@ struct Gen {
       const Access& a = an.accesses[i];
       if (a.is_output && elem_output(a)) os << "    disc::Vec<" << dtype_ctype(a.dtype) << ", V> o" << a.slot << ";\n";
     }
+    if (compact_tmpl()) os << "    bool keep[V];\n";   // the predicate of every element of the slot
     os << "    int unused_;\n  };\n";
   }
 
@@ -859,6 +868,7 @@ struct Gen {
           tail << "        o.o" << a.slot << ".set(e, " << to_storage(fn.val(out.node), n.rk, a.dtype) << ");\n";
         }
       }
+      if (compact_tmpl()) tail << "        o.keep[e] = " << convert(fn.val(an.compact_keep), an.nodes[an.compact_keep].rk, RK_BOOL) << ";\n";
       emit_late_loads(os, fn, "      ");
       os << decl.str();
       os << "#pragma unroll\n      for (int e = 0; e < V; ++e) {\n" << fn.body.str() << tail.str() << "      }\n" << pack.str();
@@ -879,7 +889,7 @@ struct Gen {
     if (!col_tmpl()) {
       for (const auto& out : an.outputs) {
         const Access& a = an.accesses[out.access];
-        if (a.has_inner || a.row_red) continue;
+        if (a.has_inner || a.row_red || a.compact_count) continue;
         const Node& n = an.nodes[out.node];
         std::string off = a.kind == ACC_PERROW ? "row" : a.kind == ACC_SCALAR ? "0" : fmt("rc.b%d", out.access);
         Fn fn2(*this, M_ELEM);
@@ -1040,6 +1050,31 @@ struct Gen {
     os << "    (void)A; (void)o; (void)c; (void)acc; (void)s; (void)e; (void)write;\n  }\n";
   }
 
+  // compaction pattern: where the kept values, the slots and the count go
+  void emit_compact_fns() {
+    os << "  template <int V> static DISC_DEV void compact_store(const Args& A, const OutSlot<V>& o, int e, disc::i64 pos) {\n";
+    for (const auto& out : an.outputs) {
+      const Access& a = an.accesses[out.access];
+      if (a.compact) os << "    A.o" << a.slot << "[pos] = o.o" << a.slot << ".get(e);\n";
+    }
+    os << "    (void)A; (void)o; (void)e; (void)pos;\n  }\n";
+    os << "  static DISC_DEV void rank_store(const Args& A, disc::i64 idx, disc::i64 rank) {\n";
+    for (const auto& out : an.outputs) {
+      const Access& a = an.accesses[out.access];
+      if (a.compact_rank) os << "    A.o" << a.slot << "[idx] = (" << dtype_ctype(a.dtype) << ")rank;\n";
+    }
+    os << "    (void)A; (void)idx; (void)rank;\n  }\n";
+    bool has_rank = false;
+    for (const auto& out : an.outputs) has_rank = has_rank || an.accesses[out.access].compact_rank;
+    os << "  static constexpr bool HAS_RANK = " << (has_rank ? "true" : "false") << ";\n";
+    os << "  static DISC_DEV void count_store(const Args& A, disc::i64 total) {\n";
+    for (const auto& out : an.outputs) {
+      const Access& a = an.accesses[out.access];
+      if (a.compact_count) os << "    A.o" << a.slot << "[0] = (" << dtype_ctype(a.dtype) << ")total;\n";
+    }
+    os << "    (void)A; (void)total;\n  }\n";
+  }
+
   void emit_args() {
     os << "  struct Args {\n";
     for (const auto& f : layout.fields) os << "    " << field_decl(f) << "\n";
@@ -1085,7 +1120,15 @@ struct Gen {
           k(name + "_s_nt", fmt("disc::row_reg_body<PatT<true>, %d, %d, %s, 3>(A, rp);", v, nv, pipe), "RowPlan", "PatT<true>");
       }
     };
-    if (an.tmpl == DISC_TEMPLATE_LOOP) {
+    if (an.tmpl == DISC_TEMPLATE_COMPACT) {
+      k("k_compact_count_vec", fmt("disc::compact_count_body<Pat, %d>(A);", V), nullptr);
+      k("k_compact_count_scalar", "disc::compact_count_body<Pat, 1>(A);", nullptr);
+      k("k_compact_scatter_vec", fmt("disc::compact_scatter_body<Pat, %d>(A);", V), nullptr);
+      k("k_compact_scatter_scalar", "disc::compact_scatter_body<Pat, 1>(A);", nullptr);
+      max_threads = 1024;
+      k("k_compact_scan", "disc::compact_scan_body<Pat>(A);", nullptr);
+      max_threads = 256;
+    } else if (an.tmpl == DISC_TEMPLATE_LOOP) {
       k("k_loop_vec", fmt("disc::kloop_body<Pat, %d, 4, false>(A);", V), nullptr);
       if (V > 1) k("k_loop_vec_nt", fmt("disc::kloop_body<Pat, %d, 4, false, 3>(A);", V), nullptr);
       k("k_loop_vec_i64", fmt("disc::kloop_body<Pat, %d, 1, true>(A);", V), nullptr);
@@ -1185,6 +1228,7 @@ struct Gen {
       emit_epilogue(M_ELEM);
       emit_col_sums();
       emit_row_reds();
+      if (compact_tmpl()) emit_compact_fns();
       os << "};\n";
       if (staged_versions) os << "typedef PatT<false> Pat;\n";
     } else {

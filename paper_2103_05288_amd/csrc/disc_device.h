@@ -216,6 +216,22 @@ DISC_DEV void ld_win(Vec<T, N>& d, const T* __restrict__ p, I off, Span sp, i64 
   }
 }
 
+// Slot of an operand read one element earlier: d[e] = p[off + e - 1].  The very first slot of the
+// tensor (off == 0) has no element in front of it: its element 0 stays zero (the caller never looks
+// at it) and the rest is read one by one.
+template <class T, int N>
+DISC_DEV void ld_prev(Vec<T, N>& d, const T* __restrict__ p, i64 off, Span sp) {
+  if (off > 0) {
+    ld(d, p, off - 1, sp);
+  } else {
+    d.clear();
+#pragma unroll
+    for (int e = 1; e < N; ++e)
+      if (sp.has(e)) d.set(e, p[e - 1]);
+    __builtin_amdgcn_s_waitcnt(0x0F70);
+  }
+}
+
 // storage <-> register conversions (float values live in fp32 registers; one rounding,
 // to nearest even, at the store)
 DISC_DEV float to_f32(float x) { return x; }
@@ -1338,6 +1354,135 @@ DISC_DEV void col_epi2_body(const typename Pat::Args& A, const ColPlan& cp) {
         if (e < nvalid) PatE::template finish_elem<V>(A, o, col + e, acc[e], base, e, rb == 0 && ty == 0);
       col_rows_epilogue<Pat, PatE, V, NT>(A, base, o, col, Span::upto(nvalid), m0, m1, ty, TY);
     }
+  }
+}
+
+// =======================================================================================
+// Outputs whose size depends on the data (compaction by a predicate computed in the pattern; Unique
+// of a sorted tensor is the case keep[i] = x[i] != x[i-1]).  Rank-1 values of length N = A.inner.
+// Three launches, no atomics, nothing read back by the host:
+//   1. compact_count:   a block owns a tile of 256 * kCompactSlots * V consecutive elements (a lane
+//                       owns kCompactSlots consecutive slots), evaluates the fused chain and counts
+//                       what is kept; one count per block to the workspace.
+//   2. compact_scan:    one block turns the counts into exclusive offsets, in a fixed order, and
+//                       stores the total -- the data-dependent size -- in the COMPACT_COUNT outputs.
+//   3. compact_scatter: the blocks evaluate their tiles again (the inputs are read twice; nothing
+//                       but the counts is kept between the launches), rank what they keep with a
+//                       scan over the lanes, and store the kept values at offset + rank, in order;
+//                       COMPACT_RANK outputs get the slot of every element.
+// =======================================================================================
+constexpr int kCompactSlots = 2;
+
+// inclusive scan over the 64 lanes of a wavefront
+DISC_DEV int wave_inclusive_scan(int x) {
+  const int lane = (int)threadIdx.x & 63;
+#pragma unroll
+  for (int d = 1; d < 64; d <<= 1) {
+    const int t = __builtin_amdgcn_ds_bpermute(((lane - d) & 63) << 2, x);
+    if (lane >= d) x += t;
+  }
+  return x;
+}
+
+// evaluates the tile of the calling lane: kept flags and values of its kCompactSlots slots
+template <class Pat, int V>
+DISC_DEV int compact_eval(const typename Pat::Args& A, i64 first, typename Pat::template OutSlot<V> (&o)[kCompactSlots],
+                          int (&nvalid)[kCompactSlots]) {
+  int cnt = 0;
+  typename Pat::RowCtx rc;
+  Pat::row_begin(A, 0, rc);
+#pragma unroll
+  for (int u = 0; u < kCompactSlots; ++u) {
+    const i64 col = first + (i64)u * V;
+    const i64 rem = A.inner - col;
+    nvalid[u] = rem <= 0 ? 0 : (rem < (i64)V ? (int)rem : V);
+    if (nvalid[u] > 0) {
+      typename Pat::template Slot<V> slot;
+      typename Pat::template Keep<V> kp;
+      Pat::template load<V>(A, rc, col, Span::upto(nvalid[u]), slot);
+      Pat::template epilogue<V, false>(A, rc, slot, kp, col, Span::upto(nvalid[u]), o[u]);
+#pragma unroll
+      for (int e = 0; e < V; ++e) cnt += (e < nvalid[u] && o[u].keep[e]) ? 1 : 0;
+    }
+  }
+  return cnt;
+}
+
+template <class Pat, int V>
+DISC_DEV void compact_count_body(const typename Pat::Args& A) {
+  __shared__ int wsum[4];
+  const i64 tile = (i64)blockDim.x * kCompactSlots * V;
+  i64* counts = reinterpret_cast<i64*>(A.ws0);
+  for (i64 b = blockIdx.x; b < A.aux0; b += gridDim.x) {
+    typename Pat::template OutSlot<V> o[kCompactSlots];
+    int nvalid[kCompactSlots];
+    const int cnt = compact_eval<Pat, V>(A, b * tile + (i64)threadIdx.x * kCompactSlots * V, o, nvalid);
+    const int incl = wave_inclusive_scan(cnt);
+    if (((int)threadIdx.x & 63) == 63) wsum[threadIdx.x >> 6] = incl;
+    __syncthreads();
+    if (threadIdx.x == 0) counts[b] = (i64)wsum[0] + wsum[1] + wsum[2] + wsum[3];
+    __syncthreads();
+  }
+}
+
+// one block of 1024 threads: exclusive scan of the A.aux0 block counts, in place
+template <class Pat>
+DISC_DEV void compact_scan_body(const typename Pat::Args& A) {
+  __shared__ i64 part[1024];
+  i64* counts = reinterpret_cast<i64*>(A.ws0);
+  const i64 nb = A.aux0;
+  const int nt = (int)blockDim.x, tid = (int)threadIdx.x;
+  const i64 per = (nb + nt - 1) / nt;
+  const i64 lo = (i64)tid * per, hi = lo + per < nb ? lo + per : nb;
+  i64 sum = 0;
+  for (i64 i = lo; i < hi; ++i) sum += counts[i];
+  part[tid] = sum;
+  __syncthreads();
+  for (int d = 1; d < nt; d <<= 1) {          // inclusive scan of the per-thread sums
+    const i64 t = tid >= d ? part[tid - d] : 0;
+    __syncthreads();
+    part[tid] += t;
+    __syncthreads();
+  }
+  i64 run = part[tid] - sum;                   // exclusive prefix of this thread's stretch
+  for (i64 i = lo; i < hi; ++i) {
+    const i64 c = counts[i];
+    counts[i] = run;
+    run += c;
+  }
+  if (tid == nt - 1) Pat::count_store(A, part[nt - 1]);
+}
+
+template <class Pat, int V>
+DISC_DEV void compact_scatter_body(const typename Pat::Args& A) {
+  __shared__ int wsum[4];
+  const i64 tile = (i64)blockDim.x * kCompactSlots * V;
+  const i64* offsets = reinterpret_cast<const i64*>(A.ws0);
+  for (i64 b = blockIdx.x; b < A.aux0; b += gridDim.x) {
+    typename Pat::template OutSlot<V> o[kCompactSlots];
+    int nvalid[kCompactSlots];
+    const i64 first = b * tile + (i64)threadIdx.x * kCompactSlots * V;
+    const int cnt = compact_eval<Pat, V>(A, first, o, nvalid);
+    const int incl = wave_inclusive_scan(cnt);
+    const int wave = (int)threadIdx.x >> 6;
+    if (((int)threadIdx.x & 63) == 63) wsum[wave] = incl;
+    __syncthreads();
+    i64 pos = offsets[b] + (incl - cnt);
+    for (int w = 0; w < wave; ++w) pos += wsum[w];
+#pragma unroll
+    for (int u = 0; u < kCompactSlots; ++u) {
+#pragma unroll
+      for (int e = 0; e < V; ++e) {
+        if (e < nvalid[u]) {
+          if (o[u].keep[e]) {
+            Pat::template compact_store<V>(A, o[u], e, pos);
+            ++pos;
+          }
+          if constexpr (Pat::HAS_RANK) Pat::rank_store(A, first + (i64)u * V + e, pos - 1);
+        }
+      }
+    }
+    __syncthreads();
   }
 }
 

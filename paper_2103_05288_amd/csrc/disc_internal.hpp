@@ -97,6 +97,10 @@ struct Access {
   bool col_sum = false;
   // output of a row-reduce pattern that reduces per-row values over the rows to one number
   bool row_red = false;
+  // compaction pattern: an input read one element earlier (NE_PREV); outputs that are the kept
+  // values (compact), the slot of every element (compact_rank), the number kept (compact_count)
+  bool prev = false;
+  bool compact = false, compact_rank = false, compact_count = false;
 };
 
 // Resolved graph: one node per (value, context) pair actually needed.
@@ -172,6 +176,7 @@ struct Analysis {
   int n_phases = 0;
   int n_col_sums = 0;                    // row reduce: outputs that are sums over the rows
   int n_row_reds = 0;                    // row reduce: outputs that reduce per-row values over the rows to one number
+  int compact_keep = -1;                 // compaction pattern: node of the predicate
   int n_inputs = 0, n_outputs = 0;
   bool needs_decomp = false;             // some access is ACC_PARTIAL
 
@@ -225,6 +230,7 @@ enum KernelId {
   K_COL_EPI_VEC, K_COL_EPI_VEC_I64, K_COL_EPI_SCALAR, K_COL_EPI_SCALAR_I64, K_COL_EPI_VEC_NT,
   K_TRANSPOSE_TILE,
   K_COL_EPI2_VEC, K_COL_EPI2_VEC_NT, K_COL_EPI2_SCALAR,
+  K_COMPACT_COUNT_VEC, K_COMPACT_COUNT_SCALAR, K_COMPACT_SCAN, K_COMPACT_SCATTER_VEC, K_COMPACT_SCATTER_SCALAR,
   K_ROW_BASE,
   K_COUNT = K_ROW_BASE + 48
 };

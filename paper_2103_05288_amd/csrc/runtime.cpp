@@ -136,6 +136,7 @@ struct disc_ctx {
   int force_variant = -1;
   hipModule_t util_module = nullptr;
   hipFunction_t util_copy = nullptr, util_copy_nt = nullptr, util_empty = nullptr;
+  hipFunction_t util_mix[2][2][4] = {};   // [kind][non-temporal][log2 slots in flight]
   // test overrides (disc_test_option); the defaults are the host rules
   int row_nt = -1;           // non-temporal versions: -1 = host rule, 0 = never, 1 = wherever the version exists
   int row_rounds = 0;        // row kernels: grid = this many rounds of resident blocks (0: host rule)
@@ -399,6 +400,42 @@ int make_plan(disc_ctx* c, const Pattern& p, const int64_t* dims, int n_dims, in
     pub.n_launches = 1;
     pub.vec_width = 1;
     pub.index_bits = 64;
+  } else if (an.tmpl == DISC_TEMPLATE_COMPACT) {
+    // count -> scan -> scatter over tiles of 256 lanes x kCompactSlots slots; the workspace holds one
+    // 8-byte count / offset per tile.  An empty input still runs the scan launch: it stores the
+    // count (zero) that the caller reads from device memory.
+    if (force >= 0 && force != DISC_V_COMPACT_VEC && force != DISC_V_COMPACT_SCALAR)
+      return set_err(c, DISC_ERR_INVALID_ARG, "forced version does not belong to a compaction pattern");
+    constexpr int kCompactSlots = 2;   // (mirrors the device header)
+    bool vec = V > 1;
+    if (force >= 0) vec = force == DISC_V_COMPACT_VEC;
+    const int v = vec ? V : 1;
+    const int64_t tile = 256ll * kCompactSlots * v;
+    const int64_t nb = (sv.inner + tile - 1) / tile;
+    fp->aux[0] = nb;
+    fp->ws_off[0] = 0;
+    pub.workspace_bytes = (size_t)std::max<int64_t>(nb, 1) * 8;
+    pub.variant = vec ? DISC_V_COMPACT_VEC : DISC_V_COMPACT_SCALAR;
+    pub.vec_width = v;
+    pub.index_bits = 64;
+    pub.slots_per_lane = kCompactSlots;
+    const uint32_t grid = (uint32_t)std::min<int64_t>(nb, max_grid * 4);
+    int l = 0;
+    if (nb > 0) {
+      fp->launches[l].kid = vec ? K_COMPACT_COUNT_VEC : K_COMPACT_COUNT_SCALAR;
+      fp->launches[l].grid[0] = grid;
+      ++l;
+    }
+    fp->launches[l].kid = K_COMPACT_SCAN;
+    fp->launches[l].block = 1024;
+    fp->launches[l].grid[0] = 1;
+    ++l;
+    if (nb > 0) {
+      fp->launches[l].kid = vec ? K_COMPACT_SCATTER_VEC : K_COMPACT_SCATTER_SCALAR;
+      fp->launches[l].grid[0] = grid;
+      ++l;
+    }
+    pub.n_launches = l;
   } else if (an.tmpl == DISC_TEMPLATE_LOOP) {
     if (sv.rows == 0 || sv.inner == 0) return DISC_OK;
     int want_vec = -1, want_i64 = -1;
@@ -806,6 +843,49 @@ extern "C" __global__ void __launch_bounds__(256) disc_util_copy_nt_k(u32x4* __r
   copy_body<true>(dst, src, n);
 }
 extern "C" __global__ void disc_util_empty_k() {}
+
+// Streaming probes with the traffic mix of the row kernels and no arithmetic to speak of: per slot of
+// eight 2-byte elements, KIND 0 reads 16 bytes + 8 bytes of a 1-byte stream and writes 16 bytes (3 bytes
+// read : 2 written per element, the mix of the 12-op pattern), KIND 1 reads 16 + 16 bytes and writes 16
+// (4 : 2, residual + LayerNorm).  NT = non-temporal accesses, U = slots in flight per lane.
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+template <int KIND, bool NT, int U>
+__device__ __forceinline__ void mix_body(u32x4* __restrict__ out, const u32x4* __restrict__ a, const u32x4* __restrict__ b,
+                                         const u32x2* __restrict__ m, long long n) {
+  const long long stride = (long long)gridDim.x * blockDim.x;
+  for (long long i0 = (long long)blockIdx.x * blockDim.x + threadIdx.x; i0 < n; i0 += stride * U) {
+    u32x4 x[U], y[U];
+    u32x2 k[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const long long i = i0 + u * stride;
+      if (i < n) {
+        if constexpr (NT) x[u] = __builtin_nontemporal_load(a + i); else x[u] = a[i];
+        if constexpr (KIND == 0) { if constexpr (NT) k[u] = __builtin_nontemporal_load(m + i); else k[u] = m[i]; }
+        else { if constexpr (NT) y[u] = __builtin_nontemporal_load(b + i); else y[u] = b[i]; }
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const long long i = i0 + u * stride;
+      if (i < n) {
+        u32x4 r = x[u];
+        if constexpr (KIND == 0) { r.x ^= k[u].x; r.z ^= k[u].y; } else { r ^= y[u]; }
+        if constexpr (NT) __builtin_nontemporal_store(r, out + i); else out[i] = r;
+      }
+    }
+  }
+}
+#define DISC_MIX(KIND, NT, U)                                                                                        \
+  extern "C" __global__ void __launch_bounds__(256) disc_util_mix_##KIND##_##NT##_##U(                               \
+      u32x4* __restrict__ out, const u32x4* __restrict__ a, const u32x4* __restrict__ b, const u32x2* __restrict__ m, \
+      long long n) {                                                                                                 \
+    mix_body<KIND, NT != 0, U>(out, a, b, m, n);                                                                     \
+  }
+DISC_MIX(0, 0, 1) DISC_MIX(0, 0, 2) DISC_MIX(0, 0, 4) DISC_MIX(0, 0, 8)
+DISC_MIX(0, 1, 1) DISC_MIX(0, 1, 2) DISC_MIX(0, 1, 4) DISC_MIX(0, 1, 8)
+DISC_MIX(1, 0, 1) DISC_MIX(1, 0, 2) DISC_MIX(1, 0, 4) DISC_MIX(1, 0, 8)
+DISC_MIX(1, 1, 1) DISC_MIX(1, 1, 2) DISC_MIX(1, 1, 4) DISC_MIX(1, 1, 8)
 )SRC";
 
 int ensure_util(disc_ctx* c) {
@@ -820,6 +900,13 @@ int ensure_util(disc_ctx* c) {
   if ((e = hipModuleGetFunction(&c->util_copy, c->util_module, "disc_util_copy_k")) != hipSuccess) return hip_fail(c, e, "hipModuleGetFunction");
   if ((e = hipModuleGetFunction(&c->util_copy_nt, c->util_module, "disc_util_copy_nt_k")) != hipSuccess) return hip_fail(c, e, "hipModuleGetFunction");
   if ((e = hipModuleGetFunction(&c->util_empty, c->util_module, "disc_util_empty_k")) != hipSuccess) return hip_fail(c, e, "hipModuleGetFunction");
+  for (int kind = 0; kind < 2; ++kind)
+    for (int nt = 0; nt < 2; ++nt)
+      for (int lu = 0; lu < 4; ++lu) {
+        char name[48];
+        snprintf(name, sizeof name, "disc_util_mix_%d_%d_%d", kind, nt, 1 << lu);
+        if ((e = hipModuleGetFunction(&c->util_mix[kind][nt][lu], c->util_module, name)) != hipSuccess) return hip_fail(c, e, "hipModuleGetFunction");
+      }
   return DISC_OK;
 }
 
@@ -1261,6 +1348,29 @@ int disc_util_copy(disc_ctx* ctx, void* dst, const void* src, size_t bytes, void
 int disc_util_copy_nt(disc_ctx* ctx, void* dst, const void* src, size_t bytes, void* hip_stream) {
   DISC_TRY
   return util_copy_impl(ctx, dst, src, bytes, hip_stream, true);
+  DISC_CATCH(ctx)
+}
+
+int disc_util_mix(disc_ctx* ctx, int kind, int non_temporal, int slots_in_flight, int blocks_per_cu, void* out, const void* a,
+                  const void* b_or_mask, size_t n_elems, void* hip_stream) {
+  DISC_TRY
+  if (!ctx || !out || !a || !b_or_mask || (n_elems & 7) || kind < 0 || kind > 1 || blocks_per_cu < 1 || blocks_per_cu > 64 ||
+      (((uintptr_t)out | (uintptr_t)a | (uintptr_t)b_or_mask) & 15))
+    return set_err(ctx, DISC_ERR_INVALID_ARG, "mix probe: 16-byte aligned pointers, n_elems a multiple of 8, kind 0 or 1");
+  int lu = 0;
+  while (lu < 4 && (1 << lu) != slots_in_flight) ++lu;
+  if (lu == 4) return set_err(ctx, DISC_ERR_INVALID_ARG, "mix probe: slots in flight must be 1, 2, 4 or 8");
+  int rc = ensure_util(ctx);
+  if (rc) return rc;
+  long long n = (long long)(n_elems / 8);
+  if (n == 0) return DISC_OK;
+  const void* bp = kind == 1 ? b_or_mask : nullptr;
+  const void* mp = kind == 0 ? b_or_mask : nullptr;
+  void* args[] = {&out, &a, &bp, &mp, &n};
+  const long long blocks = std::min<long long>((n + 255) / 256, (long long)ctx->n_cus * blocks_per_cu);
+  hipError_t e = hipModuleLaunchKernel(ctx->util_mix[kind][non_temporal ? 1 : 0][lu], (uint32_t)blocks, 1, 1, 256, 1, 1, 0,
+                                       (hipStream_t)hip_stream, args, nullptr);
+  return e == hipSuccess ? DISC_OK : hip_fail(ctx, e, "hipModuleLaunchKernel");
   DISC_CATCH(ctx)
 }
 

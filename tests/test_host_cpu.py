@@ -478,3 +478,56 @@ def test_launch_path_makes_no_heap_allocation(tmp_path):
     print(r.stdout[-2000:], r.stderr[-4000:])
     assert r.returncode == 0, r.stdout + r.stderr
     assert "runtime error" not in r.stderr and "AddressSanitizer" not in r.stderr
+
+
+# ------------------------------------------------------------------ outputs whose size depends on the data
+def test_compaction_patterns_checker_and_plan(ctx):
+    pb = PatternBuilder()
+    n = pb.dim()
+    x = pb.param("i32", [n])
+    keep = pb.ne_prev(x)
+    pb.output(pb.compact(x, keep))
+    pb.output(pb.compact_rank(keep))
+    pb.output(pb.compact_count(keep))
+    h = ctx.register(pb.build())
+    assert h.info["template"] == "compact" and h.info["compile_events"] == 1 and h.info["n_outputs"] == 3
+    p = h.plan([100000])
+    assert p["variant_name"] == "compact_vec" and p["n_launches"] == 3
+    assert [k.split("k_compact_")[1] for k in p["kernels"]] == ["count_vec", "scan", "scatter_vec"]
+    assert p["grid"][1] == [1, 1, 1] and p["block"][1][0] == 1024
+    tile = 256 * 2 * p["vec_width"]
+    assert p["grid"][0][0] == -(-100000 // tile) and p["workspace_bytes"] == 8 * p["grid"][0][0]
+    assert h.plan([0])["n_launches"] == 1 and h.plan([0])["kernels"][0].endswith("k_compact_scan")   # the count is still delivered
+    assert h.plan([5], V["compact_scalar"])["vec_width"] == 1
+    expect("INVALID_ARG", h.plan, [5], V["loop_vec"])
+    # value and predicate share one length by the op's shape propagation: checked at launch
+    pb = PatternBuilder()
+    a, b = pb.dims(2)
+    x = pb.param("f32", [a])
+    k = pb.op("gt", pb.param("f32", [b]), pb.const(0.0), dims=[b])
+    pb.output(pb.compact(x, k))
+    h2 = ctx.register(pb.build())
+    assert h2.info["n_dim_classes"] == 1 and h2.plan([7, 7])["n_launches"] == 3
+    expect("CONSTRAINT", h2.plan, [7, 8])
+    # a second predicate; a compaction result used further; a reduction beside it
+    pb = PatternBuilder()
+    n = pb.dim()
+    x = pb.param("f32", [n])
+    k1 = pb.op("gt", x, pb.const(0.0), dims=[n])
+    k2 = pb.op("lt", x, pb.const(0.0), dims=[n])
+    pb.output(pb.compact(x, k1))
+    pb.output(pb.compact(x, k2))
+    assert "share one predicate" in expect("UNFUSIBLE", ctx.register, pb.build())
+    pb = PatternBuilder()
+    n = pb.dim()
+    x = pb.param("f32", [n])
+    y = pb.compact(x, pb.op("gt", x, pb.const(0.0), dims=[n]))
+    pb.output(pb.op("exp", y))
+    assert "only feed OUTPUTs" in expect("UNFUSIBLE", ctx.register, pb.build())
+    pb = PatternBuilder()
+    t, hh = pb.dims(2)
+    x = pb.param("f32", [t, hh])
+    pb.output(pb.reduce("sum", x, 1))
+    xx = pb.param("f32", [t])
+    pb.output(pb.compact(xx, pb.op("gt", xx, pb.const(0.0), dims=[t])))
+    expect("UNFUSIBLE", ctx.register, pb.build())

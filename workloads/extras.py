@@ -119,3 +119,16 @@ def logsumexp_with_total_and_amax():
     pb.output(pb.reduce("sum", lse, 0))
     pb.output(pb.reduce("max", pb.reduce("max", pb.op("abs", x), 1), 0))
     return pb.build()
+
+
+def unique_of_sorted(dtype="i32"):
+    """Unique of a sorted rank-1 tensor (Section 2 names Unique as the op whose output size depends on
+    the input values): the distinct values in order, the index of every element in them, the count."""
+    pb = PatternBuilder("unique_sorted")
+    n = pb.dim()
+    x = pb.param(dtype, [n])
+    keep = pb.ne_prev(x)
+    pb.output(pb.compact(x, keep))
+    pb.output(pb.compact_rank(keep, "i32"))
+    pb.output(pb.compact_count(keep, "i64"))
+    return pb.build()
