@@ -1058,12 +1058,15 @@ struct Gen {
       if (a.compact) os << "    A.o" << a.slot << "[pos] = o.o" << a.slot << ".get(e);\n";
     }
     os << "    (void)A; (void)o; (void)e; (void)pos;\n  }\n";
-    os << "  static DISC_DEV void rank_store(const Args& A, disc::i64 idx, disc::i64 rank) {\n";
+    // the slots of the V elements of one slot of the tile, stored as one vector
+    os << "  template <int V> static DISC_DEV void rank_store(const Args& A, disc::i64 col, const disc::i64 (&rank)[V], disc::Span sp) {\n";
     for (const auto& out : an.outputs) {
       const Access& a = an.accesses[out.access];
-      if (a.compact_rank) os << "    A.o" << a.slot << "[idx] = (" << dtype_ctype(a.dtype) << ")rank;\n";
+      if (!a.compact_rank) continue;
+      os << "    {\n      disc::Vec<" << dtype_ctype(a.dtype) << ", V> t;\n#pragma unroll\n      for (int e = 0; e < V; ++e) t.v[e] = ("
+         << dtype_ctype(a.dtype) << ")rank[e];\n      disc::st(A.o" << a.slot << ", col, t, sp);\n    }\n";
     }
-    os << "    (void)A; (void)idx; (void)rank;\n  }\n";
+    os << "    (void)A; (void)col; (void)rank; (void)sp;\n  }\n";
     bool has_rank = false;
     for (const auto& out : an.outputs) has_rank = has_rank || an.accesses[out.access].compact_rank;
     os << "  static constexpr bool HAS_RANK = " << (has_rank ? "true" : "false") << ";\n";

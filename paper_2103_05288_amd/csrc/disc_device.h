@@ -1371,7 +1371,7 @@ DISC_DEV void col_epi2_body(const typename Pat::Args& A, const ColPlan& cp) {
 //                       scan over the lanes, and store the kept values at offset + rank, in order;
 //                       COMPACT_RANK outputs get the slot of every element.
 // =======================================================================================
-constexpr int kCompactSlots = 2;
+constexpr int kCompactSlots = 4;
 
 // inclusive scan over the 64 lanes of a wavefront
 DISC_DEV int wave_inclusive_scan(int x) {
@@ -1471,15 +1471,17 @@ DISC_DEV void compact_scatter_body(const typename Pat::Args& A) {
     for (int w = 0; w < wave; ++w) pos += wsum[w];
 #pragma unroll
     for (int u = 0; u < kCompactSlots; ++u) {
+      i64 rank[V];
 #pragma unroll
       for (int e = 0; e < V; ++e) {
-        if (e < nvalid[u]) {
-          if (o[u].keep[e]) {
-            Pat::template compact_store<V>(A, o[u], e, pos);
-            ++pos;
-          }
-          if constexpr (Pat::HAS_RANK) Pat::rank_store(A, first + (i64)u * V + e, pos - 1);
+        if (e < nvalid[u] && o[u].keep[e]) {
+          Pat::template compact_store<V>(A, o[u], e, pos);
+          ++pos;
         }
+        rank[e] = pos - 1;
+      }
+      if constexpr (Pat::HAS_RANK) {
+        if (nvalid[u] > 0) Pat::template rank_store<V>(A, first + (i64)u * V, rank, Span::upto(nvalid[u]));
       }
     }
     __syncthreads();

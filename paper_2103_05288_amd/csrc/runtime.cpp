@@ -406,7 +406,7 @@ int make_plan(disc_ctx* c, const Pattern& p, const int64_t* dims, int n_dims, in
     // count (zero) that the caller reads from device memory.
     if (force >= 0 && force != DISC_V_COMPACT_VEC && force != DISC_V_COMPACT_SCALAR)
       return set_err(c, DISC_ERR_INVALID_ARG, "forced version does not belong to a compaction pattern");
-    constexpr int kCompactSlots = 2;   // (mirrors the device header)
+    constexpr int kCompactSlots = 4;   // (mirrors the device header)
     bool vec = V > 1;
     if (force >= 0) vec = force == DISC_V_COMPACT_VEC;
     const int v = vec ? V : 1;

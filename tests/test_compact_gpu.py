@@ -82,8 +82,9 @@ def test_unique_of_sorted_tensor(ctx, dtype):
     pat = unique_sorted(dtype)
     tdt = {"i32": torch.int32, "i64": torch.int64, "f32": torch.float32}[dtype]
     g = torch.Generator().manual_seed(11)
-    # ragged sizes around the tile size (256 lanes x 2 slots x V), one element, long runs, no repeats
-    for n, spread in ((1, 3), (2, 1), (7, 2), (2047, 50), (2048, 5), (2049, 100000), (5000, 1), (100003, 300), (1 << 20, 40000)):
+    # ragged sizes around the tile sizes (256 lanes x 4 slots x 2 or 4 elements), one element, long runs, no repeats
+    for n, spread in ((1, 3), (2, 1), (7, 2), (2047, 50), (2048, 5), (2049, 100000), (4095, 7), (4096, 900), (4097, 3), (5000, 1),
+                      (100003, 300), (1 << 20, 40000)):
         x = torch.sort(torch.randint(-spread, spread + 1, (n,), generator=g, dtype=torch.int64)).values
         if dtype == "i64":
             x = x * 3000000007            # beyond 32 bits

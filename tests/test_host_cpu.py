@@ -495,7 +495,7 @@ def test_compaction_patterns_checker_and_plan(ctx):
     assert p["variant_name"] == "compact_vec" and p["n_launches"] == 3
     assert [k.split("k_compact_")[1] for k in p["kernels"]] == ["count_vec", "scan", "scatter_vec"]
     assert p["grid"][1] == [1, 1, 1] and p["block"][1][0] == 1024
-    tile = 256 * 2 * p["vec_width"]
+    tile = 256 * 4 * p["vec_width"]
     assert p["grid"][0][0] == -(-100000 // tile) and p["workspace_bytes"] == 8 * p["grid"][0][0]
     assert h.plan([0])["n_launches"] == 1 and h.plan([0])["kernels"][0].endswith("k_compact_scan")   # the count is still delivered
     assert h.plan([5], V["compact_scalar"])["vec_width"] == 1
