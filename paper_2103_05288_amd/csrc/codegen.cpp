@@ -598,7 +598,7 @@ struct Gen {
     emit_store();
   }
   void emit_load(const std::vector<char>& need, bool with_red, const char* name) {
-    os << "  template <int V, int NT = 0, class C> static DISC_DEV void " << name << "(const Args& A, const RowCtx& rc, C col, disc::Span sp, Slot<V>& s) {\n";
+    os << "  template <int V, int NT = 0, class C, class SP> static DISC_DEV void " << name << "(const Args& A, const RowCtx& rc, C col, SP sp, Slot<V>& s) {\n";
     for (size_t i = 0; i < an.accesses.size(); ++i) {
       const Access& a = an.accesses[i];
       if (a.is_output || !a.has_inner || !need[i] || late(a)) continue;
@@ -617,7 +617,7 @@ struct Gen {
     os << "    (void)A; (void)rc; (void)col; (void)sp; (void)s;\n  }\n";
   }
   void emit_store() {
-    os << "  template <int V, int NT = 0, class C> static DISC_DEV void store(const Args& A, const RowCtx& rc, C col, disc::Span sp, const OutSlot<V>& o) {\n";
+    os << "  template <int V, int NT = 0, class C, class SP> static DISC_DEV void store(const Args& A, const RowCtx& rc, C col, SP sp, const OutSlot<V>& o) {\n";
     for (size_t i = 0; i < an.accesses.size(); ++i) {
       const Access& a = an.accesses[i];
       if (!a.is_output || !elem_output(a)) continue;
@@ -801,7 +801,7 @@ struct Gen {
   }
 
   void emit_row_phase_fns() {
-    os << "  template <int P, int V, bool KEEP> static DISC_DEV void phase(const Args& A, Acc<P>& acc, const Slot<V>& s, Keep<V>& k, disc::Span sp, int col, const RowCtx& rc) {\n";
+    os << "  template <int P, int V, bool KEEP, class SP> static DISC_DEV void phase(const Args& A, Acc<P>& acc, const Slot<V>& s, Keep<V>& k, SP sp, int col, const RowCtx& rc) {\n";
     for (int p = 0; p < an.n_phases; ++p) {
       os << "    if constexpr (P == " << p << ") {\n";
       os << "      if constexpr (KEEP) {\n";
@@ -848,7 +848,7 @@ struct Gen {
   }
 
   void emit_epilogue(Mode mode) {
-    os << "  template <int V, bool KEEP, class C> static DISC_DEV void epilogue(const Args& A, const RowCtx& rc, const Slot<V>& s, const Keep<V>& k, C col, disc::Span sp, OutSlot<V>& o) {\n";
+    os << "  template <int V, bool KEEP, class C, class SP> static DISC_DEV void epilogue(const Args& A, const RowCtx& rc, const Slot<V>& s, const Keep<V>& k, C col, SP sp, OutSlot<V>& o) {\n";
     auto flavour = [&](bool keep) {
       Fn fn(*this, mode);
       fn.P = an.n_phases;
@@ -907,7 +907,7 @@ struct Gen {
     os << "  static constexpr int NCOLSUM = " << nq << ";\n";
     os << "  template <int V> struct ColAcc { typename disc::Vec<float, V>::vec_t c[" << std::max(nq, 1) << "]; };\n";
     if (nq == 0) return;
-    os << "  template <int V, bool KEEP, class C> static DISC_DEV void col_sums(const Args& A, const RowCtx& rc, const Slot<V>& s, const Keep<V>& k, C col, disc::Span sp, ColAcc<V>& ca) {\n";
+    os << "  template <int V, bool KEEP, class C, class SP> static DISC_DEV void col_sums(const Args& A, const RowCtx& rc, const Slot<V>& s, const Keep<V>& k, C col, SP sp, ColAcc<V>& ca) {\n";
     auto flavour = [&](bool keep) {
       Fn fn(*this, M_ELEM);
       fn.P = an.n_phases;
@@ -1115,12 +1115,17 @@ struct Gen {
       k(name, fmt("disc::row_reg_body<Pat, %d, %d, %s>(A, rp);", v, nv, pipe), "RowPlan");
       if (staged && v > 1)
         k(name + "_s", fmt("disc::row_reg_body<PatT<true>, %d, %d, %s>(A, rp);", v, nv, pipe), "RowPlan", "PatT<true>");
-      // blocks of one wavefront quad, vector width: a version with non-temporal accesses of the
-      // full-size operands, which the host picks for rows that start and end on 16-byte boundaries
+      // blocks of one wavefront quad, vector width: versions for rows that are a whole number of
+      // slots (no ragged-tail path anywhere in them), with plain accesses (_e) and with non-temporal
+      // accesses of the full-size operands (_nt), which the host picks for large launches of rows
+      // that start and end on 16-byte boundaries
       if (v > 1 && max_threads <= 256) {
-        k(name + "_nt", fmt("disc::row_reg_body<Pat, %d, %d, %s, 3>(A, rp);", v, nv, pipe), "RowPlan");
-        if (staged)
-          k(name + "_s_nt", fmt("disc::row_reg_body<PatT<true>, %d, %d, %s, 3>(A, rp);", v, nv, pipe), "RowPlan", "PatT<true>");
+        k(name + "_e", fmt("disc::row_reg_body<Pat, %d, %d, %s, 0, true>(A, rp);", v, nv, pipe), "RowPlan");
+        k(name + "_nt", fmt("disc::row_reg_body<Pat, %d, %d, %s, 3, true>(A, rp);", v, nv, pipe), "RowPlan");
+        if (staged) {
+          k(name + "_s_e", fmt("disc::row_reg_body<PatT<true>, %d, %d, %s, 0, true>(A, rp);", v, nv, pipe), "RowPlan", "PatT<true>");
+          k(name + "_s_nt", fmt("disc::row_reg_body<PatT<true>, %d, %d, %s, 3, true>(A, rp);", v, nv, pipe), "RowPlan", "PatT<true>");
+        }
       }
     };
     if (an.tmpl == DISC_TEMPLATE_COMPACT) {

@@ -97,6 +97,21 @@ struct Span {
   DISC_DEV bool has(int e) const { return e < n; }
   DISC_DEV bool any() const { return n > 0; }
 };
+// The span of a slot in a launch whose rows are a whole number of slots (row length a multiple of
+// the vector width): a slot is either all inside the row or not there at all, which the compiler
+// knows -- every ragged-tail path (predicated bodies, piecewise loads and stores, the wave-wide
+// "all full?" vote) drops out of the kernel versions built on it.
+struct EvenSpan {
+  int n;
+  static DISC_DEV EvenSpan upto(int n) {
+    EvenSpan s;
+    s.n = n;
+    return s;
+  }
+  DISC_DEV bool full(int) const { return true; }
+  DISC_DEV bool has(int) const { return true; }
+  DISC_DEV bool any() const { return n > 0; }
+};
 
 // Element offset of a slot relative to the base row of the access.  A caller that passes the
 // column as `unsigned` promises that lane_base + col, scaled to bytes, fits 32 bits (the
@@ -162,8 +177,8 @@ DISC_DEV T* at(T* p, I off) {
 // and results that are touched exactly once the hint keeps them from displacing each other in the
 // L2 and the memory-side cache; the host picks the version per launch (the hint hurts short or
 // misaligned rows, whose cache lines are shared by neighbouring rows and so ARE touched twice).
-template <bool NT = false, class T, int N, class I>
-DISC_DEV void ld(Vec<T, N>& d, const T* __restrict__ p, I off, Span sp, bool whole_ok = false) {
+template <bool NT = false, class T, int N, class I, class SP>
+DISC_DEV void ld(Vec<T, N>& d, const T* __restrict__ p, I off, SP sp, bool whole_ok = false) {
   if (sp.full(N) || whole_ok) {
     const auto* q = reinterpret_cast<const typename Vec<T, N>::unaligned_t*>(at(p, off));
     if constexpr (NT) d.v = __builtin_nontemporal_load(q);
@@ -179,8 +194,8 @@ DISC_DEV void ld(Vec<T, N>& d, const T* __restrict__ p, I off, Span sp, bool who
   }
 }
 
-template <bool NT = false, class T, int N, class I>
-DISC_DEV void st(T* __restrict__ p, I off, const Vec<T, N>& s, Span sp) {
+template <bool NT = false, class T, int N, class I, class SP>
+DISC_DEV void st(T* __restrict__ p, I off, const Vec<T, N>& s, SP sp) {
   if (sp.full(N)) {
     auto* q = reinterpret_cast<typename Vec<T, N>::unaligned_t*>(at(p, off));
     if constexpr (NT) __builtin_nontemporal_store(s.v, q);
@@ -199,8 +214,8 @@ DISC_DEV T pad_const(float x) {
   if constexpr (sizeof(T) == 1) return (T)(x != 0.0f);
   else return (T)x;
 }
-template <class T, int N, class I>
-DISC_DEV void ld_win(Vec<T, N>& d, const T* __restrict__ p, I off, Span sp, i64 col, bool row_ok, i64 wlo, i64 whi, T padv) {
+template <class T, int N, class I, class SP>
+DISC_DEV void ld_win(Vec<T, N>& d, const T* __restrict__ p, I off, SP sp, i64 col, bool row_ok, i64 wlo, i64 whi, T padv) {
   const i64 lo = wlo - col, hi = whi - col;        // the operand's columns in slot coordinates
   if (row_ok && lo <= 0 && hi >= sp.n) {
     ld(d, p, off, sp);
@@ -219,8 +234,8 @@ DISC_DEV void ld_win(Vec<T, N>& d, const T* __restrict__ p, I off, Span sp, i64 
 // Slot of an operand read one element earlier: d[e] = p[off + e - 1].  The very first slot of the
 // tensor (off == 0) has no element in front of it: its element 0 stays zero (the caller never looks
 // at it) and the rest is read one by one.
-template <class T, int N>
-DISC_DEV void ld_prev(Vec<T, N>& d, const T* __restrict__ p, i64 off, Span sp) {
+template <class T, int N, class SP>
+DISC_DEV void ld_prev(Vec<T, N>& d, const T* __restrict__ p, i64 off, SP sp) {
   if (off > 0) {
     ld(d, p, off - 1, sp);
   } else {
@@ -429,6 +444,8 @@ DISC_DEV void kloop_body(const typename Pat::Args& A) {
 // back.  Within a wavefront partial results are combined with xor-shuffles; across the
 // wavefronts of a row through a double-buffered LDS exchange (one barrier per phase).
 // =======================================================================================
+template <bool EVEN> struct SpanSel { typedef Span type; };
+template <> struct SpanSel<true> { typedef EvenSpan type; };
 struct RowPlan {
   int G;        // lanes per row: a power of two <= 64, or a multiple of 64 (whole wavefronts)
   int log2G;    // meaningful for G <= 64
@@ -473,10 +490,10 @@ DISC_DEV float lane_xor_f32(float v, int s) {
 
 // `after_first` runs once, after the slots have been folded into the accumulator of phase 0 and
 // before the lanes combine: the place where the caller issues the loads of the next row.
-template <class Pat, int P, int V, int NV, class Hook>
+template <class Pat, int P, int V, int NV, class Hook, class SP>
 DISC_DEV void row_phases(const typename Pat::Args& A, const RowPlan& rp, typename Pat::RowCtx& rc,
                          const typename Pat::template Slot<V> (&slot)[NV],
-                         typename Pat::template Keep<V> (&keep)[NV], const Span (&span)[NV],
+                         typename Pat::template Keep<V> (&keep)[NV], const SP (&span)[NV],
                          int col0, char* lds, int& parity, Hook& after_first) {
   if constexpr (P < Pat::NPHASE) {
     typename Pat::template Acc<P> acc;
@@ -518,8 +535,10 @@ DISC_DEV void row_phases(const typename Pat::Args& A, const RowPlan& rp, typenam
 }
 
 // NT: bit 0 = non-temporal loads of the full-size operands, bit 1 = non-temporal stores
-template <class Pat, int V, int NV, bool PIPE = true, int NT = 0>
+// EVEN: the host promises that the row length is a multiple of V (no ragged slot anywhere)
+template <class Pat, int V, int NV, bool PIPE = true, int NT = 0, bool EVEN = false>
 DISC_DEV void row_reg_body(const typename Pat::Args& A, const RowPlan& rp) {
+  typedef typename SpanSel<EVEN>::type SP;
   __shared__ __attribute__((aligned(16))) char lds[2 * 16 * Pat::MAX_ACC_BYTES];
   // G <= 64: a power of two; G > 64: a multiple of 64
   const int grp = rp.G <= 64 ? (int)threadIdx.x >> rp.log2G : ((int)threadIdx.x >> 6) / (rp.G >> 6);
@@ -598,15 +617,15 @@ DISC_DEV void row_reg_body(const typename Pat::Args& A, const RowPlan& rp) {
     rc.sl = staged;
 #pragma unroll
     for (int j = 0; j < NV; ++j)
-      if (nvalid[j] > 0) Pat::template load<V, NT>(A, rc, (unsigned)(col0 + j * rp.G * V), Span::upto(nvalid[j]), slot[j]);
+      if (nvalid[j] > 0) Pat::template load<V, NT>(A, rc, (unsigned)(col0 + j * rp.G * V), SP::upto(nvalid[j]), slot[j]);
   };
   // the row group of the block starts at row rw - grp_w; the block is done when that is past the end
   if (PIPE && rw - grp_w < rows) load_row();
   while (rw - grp_w < rows) {
     if constexpr (!PIPE) load_row();
-    Span span[NV];
+    SP span[NV];
 #pragma unroll
-    for (int j = 0; j < NV; ++j) span[j] = Span::upto(nvalid[j]);
+    for (int j = 0; j < NV; ++j) span[j] = SP::upto(nvalid[j]);
     const i64 row = rw + dgrp;
     const bool active = row < rows;
     typename Pat::RowCtx rcn{};
@@ -626,7 +645,7 @@ DISC_DEV void row_reg_body(const typename Pat::Args& A, const RowPlan& rp) {
 #pragma unroll
         for (int j = 0; j < NV; ++j)
           if (nvalidn[j] > 0) {
-            Span sn;            // the loads look at the element count only
+            SP sn;              // the loads look at the element count only
             sn.n = nvalidn[j];
             Pat::template load<V, NT>(A, rcn, (unsigned)(col0n + j * rp.G * V), sn, nxt[j]);
           }
@@ -723,7 +742,7 @@ DISC_DEV void row_reg_body(const typename Pat::Args& A, const RowPlan& rp) {
           for (int q = 0; q < Pat::NCOLSUM; ++q) {
             Vec<float, V> t;
             t.v = cacc[j].c[q];
-            st(ws + ((i64)q * A.aux0 + prow) * A.inner, (i64)(col0 + j * rp.G * V), t, Span::upto(nvalid[j]));
+            st(ws + ((i64)q * A.aux0 + prow) * A.inner, (i64)(col0 + j * rp.G * V), t, SP::upto(nvalid[j]));
           }
         }
     }

@@ -232,12 +232,13 @@ enum KernelId {
   K_COL_EPI2_VEC, K_COL_EPI2_VEC_NT, K_COL_EPI2_SCALAR,
   K_COMPACT_COUNT_VEC, K_COMPACT_COUNT_SCALAR, K_COMPACT_SCAN, K_COMPACT_SCATTER_VEC, K_COMPACT_SCATTER_SCALAR,
   K_ROW_BASE,
-  K_COUNT = K_ROW_BASE + 48
+  K_COUNT = K_ROW_BASE + 72
 };
-// k_row_{vec|scalar}_nv{1|2|3}[w][_s][_nt]: scalar access, instantiated slots per lane, block above
-// 256 threads, row vectors staged in LDS, non-temporal accesses of the full-size operands
-inline int row_kernel_index(bool scalar, int inst, bool wide, bool staged, bool nt) {
-  return ((((scalar ? 1 : 0) * 3 + (inst - 1)) * 2 + (wide ? 1 : 0)) * 2 + (staged ? 1 : 0)) * 2 + (nt ? 1 : 0);
+// k_row_{vec|scalar}_nv{1|2|3}[w][_s][_nt|_e]: scalar access, instantiated slots per lane, block above
+// 256 threads, row vectors staged in LDS, then the access flavour: 0 = any row length, 1 (_nt) = rows
+// of whole slots with non-temporal accesses of the full-size operands, 2 (_e) = rows of whole slots
+inline int row_kernel_index(bool scalar, int inst, bool wide, bool staged, int flavour) {
+  return ((((scalar ? 1 : 0) * 3 + (inst - 1)) * 2 + (wide ? 1 : 0)) * 2 + (staged ? 1 : 0)) * 3 + flavour;
 }
 const char* kernel_name(int kid);            // entry-point name without the pattern prefix
 int kernel_id(const std::string& name);      // -1 when unknown (registration time only)

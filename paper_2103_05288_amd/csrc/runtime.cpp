@@ -531,10 +531,13 @@ int make_plan(disc_ctx* c, const Pattern& p, const int64_t* dims, int n_dims, in
         // neighbours lose with it (-25 % for 360- or 464-element rows, -30 % for short odd rows),
         // as do operands that are read more than once, which never get the hint.  Small launches
         // (kNonTemporalMinBytes) keep the plain version: their results may be consumed from cache.
+        // rows of whole slots (row length a multiple of the vector width) take the versions without
+        // any ragged-tail path: _e, or _nt under the rule above
+        const bool even = vec && V > 1 && !wide_version && sv.inner % V == 0;
         bool nt = false;
-        if (vec && V > 1 && !wide_version && c->row_nt != 0) {
+        if (even && c->row_nt != 0) {
           nt = c->row_nt > 0;
-          if (c->row_nt < 0 && sv.inner % V == 0 && sv.inner >= 128 && sv.alg_bytes >= kNonTemporalMinBytes) {
+          if (c->row_nt < 0 && sv.inner >= 128 && sv.alg_bytes >= kNonTemporalMinBytes) {
             nt = true;
             bool whole_lines = true;
             for (const Access& a : an.accesses) {
@@ -546,7 +549,7 @@ int make_plan(disc_ctx* c, const Pattern& p, const int64_t* dims, int n_dims, in
             if (!whole_lines && sv.inner < 512) nt = false;
           }
         }
-        L.kid = K_ROW_BASE + row_kernel_index(!vec, inst, wide_version, stage, nt);
+        L.kid = K_ROW_BASE + row_kernel_index(!vec, inst, wide_version, stage, nt ? 1 : even ? 2 : 0);
       }
       // grid-stride over row groups: a small whole number of rounds of the blocks the chip holds
       // at once.  Measured: with plenty of rows, blocks of one wavefront-quad do best with three
@@ -1135,7 +1138,9 @@ static int register_impl(disc_ctx* ctx, const disc_op* ops, int n_ops, const dis
       opt.only_kernels.push_back(k);
       // planned without pointers, i.e. for aligned operands: keep the plain sibling of a
       // non-temporal version for launches whose operands turn out not to be 16-byte aligned
-      if (k.size() > 3 && k.compare(k.size() - 3, 3, "_nt") == 0) opt.only_kernels.push_back(k.substr(0, k.size() - 3));
+      // (for a row kernel that sibling is the version for rows of whole slots, _e)
+      if (k.size() > 3 && k.compare(k.size() - 3, 3, "_nt") == 0)
+        opt.only_kernels.push_back(k.substr(0, k.size() - 3) + (k.compare(0, 6, "k_row_") == 0 ? "_e" : ""));
     }
     if (opt.only_kernels.empty()) return set_err(ctx, DISC_ERR_SHAPE, "a single-shape pattern needs a shape that launches something");
     const std::string macros = static_macros(*p, fp, static_dims);

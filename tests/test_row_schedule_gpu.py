@@ -83,18 +83,19 @@ def test_many_rows_per_block_and_turning_grid(monkeypatch, cfg_name):
 
 
 def test_non_temporal_versions_any_alignment(monkeypatch):
-    """The non-temporal kernel versions forced for every row length (the host rule keeps them to
-    aligned rows for speed; their results do not depend on alignment), and the host rule with
-    operands that are not 16-byte aligned: it must fall back to the plain version."""
+    """The non-temporal kernel versions forced wherever they exist (rows of whole slots, also small
+    launches and short rows that the host rule would leave to the plain versions), and the host rule
+    with operands that are not 16-byte aligned: it must fall back to a plain version."""
     from paper_2103_05288_amd import Context
     c = Context(0)
     c.test_option("non_temporal", 1)
     try:
         for cfg_name in ("C2", "C4"):
             h = c.register(CONFIGS[cfg_name].pattern())
-            for H, T in [(9, 40), (127, 300), (1000, 77), (2047, 500), (3001, 2003), (6144, 300)]:
+            for H, T in [(8, 40), (127, 300), (1000, 77), (2047, 500), (3000, 2003), (6144, 300), (72, 5000)]:
                 plan = check(c, cfg_name, [T, H], seed=H + 2, handle=h)
-                assert plan["kernels"][0].endswith("_nt"), plan["kernels"]
+                # (the non-temporal versions are built for rows of whole slots: 8 elements here)
+                assert plan["kernels"][0].endswith("_nt") == (H % 8 == 0), plan["kernels"]
         # the loop-fusion kernel and the epilogue of a column reduce have such versions too
         plan = check(c, "C0", [300, 768], seed=9)
         assert plan["kernels"][0].endswith("k_loop_vec_nt"), plan["kernels"]
