@@ -12,7 +12,8 @@
 //    and which are recomputed from the raw slot (a cast or one add is cheaper than 8 registers);
 //  * division by a per-row value becomes a multiplication by a reciprocal computed once per row;
 //    per-element transcendental ops use the hardware approximations (1 ulp exp2 / log2 / rcp /
-//    rsq), per-row and per-column scalar math stays IEEE-correct.
+//    rsq); so do per-row reciprocals and roots; per-row exp / log / tanh and per-column math stay
+//    IEEE-correct.
 #include <algorithm>
 #include <cmath>
 #include <cstdarg>
@@ -289,9 +290,12 @@ struct Gen {
         }
         case DISC_LOG: return (f ? "disc::fast_log(" : "logf(") + a(0) + ")";
         case DISC_TANH: return (f ? "disc::fast_tanh(" : "tanhf(") + a(0) + ")";
-        case DISC_SQRT: return (f ? "disc::fast_sqrt(" : "sqrtf(") + a(0) + ")";
-        case DISC_RSQRT: return (f ? "disc::fast_rsqrt(" : "rsqrtf(") + a(0) + ")";
-        case DISC_RCP: return f ? "disc::fast_rcp(" + a(0) + ")" : "(1.0f / " + a(0) + ")";
+        // square roots and reciprocals use the approximation units per row as well (1 ulp: far inside
+        // the fp32 bar): the IEEE expansions cost 6-10 instructions each, per row and lane, and a
+        // lane of a long row only has 16-24 elements to spread them over
+        case DISC_SQRT: return (f || mode == M_ROWLOCAL ? "disc::fast_sqrt(" : "sqrtf(") + a(0) + ")";
+        case DISC_RSQRT: return (f || mode == M_ROWLOCAL ? "disc::fast_rsqrt(" : "rsqrtf(") + a(0) + ")";
+        case DISC_RCP: return f || mode == M_ROWLOCAL ? "disc::fast_rcp(" + a(0) + ")" : "(1.0f / " + a(0) + ")";
         case DISC_SIGMOID: return f ? "disc::fast_sigmoid(" + a(0) + ")" : "(1.0f / (1.0f + expf(-" + a(0) + ")))";
         case DISC_ERF: return "erff(" + a(0) + ")";
         // integers wrap (two's complement of the declared width): computed on the unsigned type
@@ -299,6 +303,14 @@ struct Gen {
         case DISC_SUB: return k == RK_F32 ? a(0) + " - " + a(1) : wrap_arith(k, a(0), "-", a(1));
         case DISC_MUL: return k == RK_F32 ? a(0) + " * " + a(1) : wrap_arith(k, a(0), "*", a(1));
         case DISC_DIV: {
+          if (k == RK_F32 && mode == M_ROWLOCAL) {
+            // per-row quotients: by a launch-wide scalar (a dimension size) it is a product with the
+            // reciprocal, which the compiler computes once per kernel; by a per-row value a product
+            // with its approximate reciprocal
+            const Node& dr = g.an.nodes[n.in[1]];
+            if (dr.dom == DOM_SCALAR) return a(0) + " * (1.0f / " + a(1) + ")";
+            return a(0) + " * disc::fast_rcp(" + a(1) + ")";
+          }
           if (k != RK_F32 || !f) return a(0) + " / " + a(1);
           const Node& d = g.an.nodes[n.in[1]];
           if (mode == M_ELEM && g.need_rinv.count(n.in[1])) return a(0) + " * " + fmt("rc.q%d", n.in[1]);
@@ -428,7 +440,7 @@ struct Gen {
   }
   void assign_row(Fn& fn, size_t i, const std::string& v) {
     fn.body << "    rc.r" << i << " = " << v << ";\n";
-    if (need_rinv.count((int)i)) fn.body << "    rc.q" << i << " = 1.0f / rc.r" << i << ";\n";
+    if (need_rinv.count((int)i)) fn.body << "    rc.q" << i << " = disc::fast_rcp(rc.r" << i << ");\n";
     if (need_nl2e.count((int)i)) fn.body << "    rc.n" << i << " = -1.44269504088896341f * rc.r" << i << ";\n";
     fn.names[(int)i] = fmt("rc.r%zu", i);
   }
