@@ -189,3 +189,88 @@ def test_ragged_pieces_every_storage_width(ctx):
             assert_close(got[0], want[0], f"widths f32 dims={[T_, H_]}")
             assert_close(got[1], want[1], f"widths f16 dims={[T_, H_]}")
             assert np.array_equal(got[2].numpy()[safe] != 0, np.asarray(want[2])[safe] != 0), [T_, H_]
+
+
+def test_odd_rows_of_two_byte_elements_any_base_alignment():
+    """Rows of an odd number of 2-byte elements start alternately on and two bytes off a dword
+    boundary.  A pattern with 2-byte and 1-byte full-size operands and results, an fp32 row vector
+    (staged in LDS or not), a sum, a max and an argmax per row; guard cells around every result show
+    that nothing is written outside, with bases on a 16-byte boundary and one element past it."""
+    from paper_2103_05288_amd import Context
+    pb = PatternBuilder("odd_rows")
+    T, H = pb.dims(2)
+    x = pb.param("bf16", [T, H])
+    m = pb.param("bool", [T, H])
+    g = pb.param("f32", [H])
+    x32 = pb.cast(x, "f32")
+    v = pb.op("mul", x32, pb.broadcast(g, [T, H], [1]))
+    mx = pb.reduce("max", v, 1)
+    am = pb.reduce("argmax", v, 1)
+    e = pb.op("exp", pb.op("sub", v, pb.broadcast(mx, [T, H], [0])))
+    s = pb.reduce("sum", e, 1)
+    y = pb.op("select", m, x32, pb.op("div", e, pb.broadcast(s, [T, H], [0])), dims=[T, H])
+    pb.output(pb.cast(y, "bf16"))
+    pb.output(pb.cast(pb.op("add", y, v), "f16"))
+    pb.output(pb.op("gt", v, pb.const(0.25), dims=[T, H]))
+    pb.output(am)
+    pb.output(s)
+    pat = pb.build()
+    rng = np.random.default_rng(11)
+    out_dt = [torch.bfloat16, torch.float16, torch.bool, torch.int32, torch.float32]
+
+    def run(c, h, dims, ins, skew):
+        """Launch with every full-size tensor `skew` elements past a 16-byte boundary and guards around the results."""
+        T_, H_ = dims
+        dev = []
+        for t in ins:
+            if t.dim() == 2:
+                flat = torch.zeros(t.numel() + 32, dtype=t.dtype, device="cuda")
+                view = flat[16 + skew:16 + skew + t.numel()].view(t.shape)
+                view.copy_(t)
+                dev.append(view)
+            else:
+                dev.append(t.cuda())
+        flats, outs = [], []
+        for dt, full in zip(out_dt, (True, True, True, False, False)):
+            n = T_ * H_ if full else T_
+            flat = torch.full((n + 32,), 1, dtype=dt, device="cuda")
+            flats.append(flat)
+            outs.append(flat[16 + skew:16 + skew + n].view((T_, H_) if full else (T_,)))
+        h.launch(dims, dev, outs)
+        torch.cuda.synchronize()
+        for f, o in zip(flats, outs):
+            fc = f.cpu()
+            assert bool((fc[:16 + skew] == 1).all()) and bool((fc[16 + skew + o.numel():] == 1).all()), f"guard cells dims={dims} skew={skew}"
+        return [o.cpu() for o in outs]
+
+    for stage in (1, 0):
+        c = Context(0)
+        c.test_option("stage_row_vectors", stage)
+        c.test_option("row_rounds", 1)
+        try:
+            h = c.register(pat)
+            shapes = [(2, 5), (3, 9), (5, 33), (64, 127), (1001, 129), (7, 511), (300, 1023), (33, 1025), (4100, 3001),
+                      (6000, 4095), (9, 6143), (2500, 8191), (5, 24575), (70001, 127)]
+            for T_, H_ in shapes:
+                ins = [torch.from_numpy(rng.standard_normal((T_, H_)).astype(np.float32)).to(torch.bfloat16),
+                       torch.from_numpy((rng.random((T_, H_)) < 0.3)),
+                       torch.from_numpy((0.5 + rng.random(H_)).astype(np.float32))]
+                print(f"[odd rows] stage={stage} dims={[T_, H_]}", flush=True)
+                want = oracle_run(pat, [T_, H_], [to_oracle_input(t) for t in ins])[0]
+                v64 = np.asarray(ins[0].float().numpy(), dtype=np.float64) * np.asarray(ins[2].numpy(), dtype=np.float64)[None, :]
+                for skew in (0, 1):          # bf16 / f16 tensors: dword aligned, then two bytes off
+                    got = run(c, h, [T_, H_], ins, skew)
+                    what = f"odd rows dims={[T_, H_]} stage={stage} skew={skew}"
+                    assert_close(got[0], want[0], what + " out0")
+                    assert_close(got[1], want[1], what + " out1")
+                    safe = np.abs(v64 - 0.25) > 1e-5
+                    assert np.array_equal(got[2].numpy()[safe], np.asarray(want[2])[safe] != 0), what + " out2"
+                    # argmax: the position may differ only where two products tie to fp32 rounding
+                    ga = got[3].numpy().astype(np.int64)
+                    wa = np.asarray(want[3]).astype(np.int64)
+                    rows_ = np.arange(T_)
+                    assert np.all((ga >= 0) & (ga < H_)), what
+                    assert np.all(np.abs(v64[rows_, ga] - v64[rows_, wa]) <= 1e-6 * np.abs(v64[rows_, wa])), what + " argmax"
+                    assert_close(got[4], want[4], what + " out4")
+        finally:
+            c.close()
