@@ -471,6 +471,9 @@ def main():
     ap.add_argument("--streams", type=int, default=1, help="streams the calls of the timed step are dealt out over")
     ap.add_argument("--cpu-budget", type=float, default=20.0)
     ap.add_argument("--dump-calls", default="", help="write per-call dims / bytes / device time as JSON lines")
+    ap.add_argument("--one-call", default="", metavar="CFG:DIMS",
+                    help="launch ONE call of one configuration a few times (e.g. C4:65536,4096) and print its plan and "
+                         "rate as one JSON line; what the per-kernel counter passes under profiles/ are taken from")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -483,6 +486,26 @@ def main():
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     ctx = Context(0)
+    if args.one_call:
+        name, dims_s = args.one_call.split(":")
+        dims = [int(x) for x in dims_s.split(",")]
+        cfg = CONFIGS[name]
+        pat = cfg.pattern()
+        h = ctx.register(pat)
+        ins = cfg.inputs(dims, seed=3, device="cuda")
+        outs = [torch.empty(pat.shape_of(o, dims), dtype=TORCH_DTYPE[pat.ops[o].dtype], device=dev) for o in pat.outputs]
+        ws = torch.empty(max(16, ctx.workspace_bytes(h.id, dims)), dtype=torch.uint8, device=dev)
+        call = h.bind(dims, ins, outs, workspace=ws)
+        call()
+        torch.cuda.synchronize()
+        t = min(time_events(call) for _ in range(3))
+        plan = h.plan(dims)
+        print(json.dumps({"mode": "one_call", "config": name, "dims": dims, "kernels": plan["kernels"],
+                          "grid": plan["grid"][:plan["n_launches"]], "block": plan["block"][:plan["n_launches"]],
+                          "lanes_per_row": plan["lanes_per_row"], "slots_per_lane": plan["slots_per_lane"],
+                          "launches": 4, "us": round(t * 1e6, 2),
+                          "GBps": round(algorithmic_bytes(pat, dims) / t / 1e9, 1)}))
+        return
     if args.next_rows_only:
         n_copy = 1 << 30
         src = torch.zeros(n_copy, dtype=torch.uint8, device=dev)
