@@ -300,10 +300,10 @@ struct KernelNames {
       for (int n = 1; n <= 3; ++n)
         for (int w = 0; w < 2; ++w)
           for (int st = 0; st < 2; ++st)
-            for (int fl = 0; fl < 3; ++fl)
+            for (int fl = 0; fl < 4; ++fl)
               name[K_ROW_BASE + row_kernel_index(sc, n, w, st, fl)] = std::string("k_row_") + (sc ? "scalar" : "vec") + "_nv" +
                                                                       std::to_string(n) + (w ? "w" : "") + (st ? "_s" : "") +
-                                                                      (fl == 1 ? "_nt" : fl == 2 ? "_e" : "");
+                                                                      (fl == 1 ? "_nt" : fl == 2 ? "_e" : fl == 3 ? "_t" : "");
   }
 };
 const KernelNames& kernel_names() {

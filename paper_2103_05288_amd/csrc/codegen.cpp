@@ -753,21 +753,24 @@ struct Gen {
     return -1;
   }
   // byte offset of staged operand k: operands are laid out one after the other, each
-  // (inner + V) elements long (zero padding behind), rounded up to 16 bytes
+  // (inner + vector width) elements long (zero padding behind), rounded up to 16 bytes.  The
+  // padding is that of the pattern's vector width whatever the width of the slot that reads the
+  // copy (the single elements at the end of a row read it too).
   void emit_stage_fns() {
     std::vector<int> st = staged_accesses();
+    const int pad = an.vec_width;
     os << "  static constexpr int N_STAGED = " << st.size() << ";\n";
-    os << "  template <int V> static DISC_DEV int stage_offset(const Args& A, int k) {\n    int off = 0;\n";
+    os << "  static DISC_DEV int stage_offset(const Args& A, int k) {\n    int off = 0;\n";
     for (size_t k = 0; k < st.size(); ++k)
-      os << "    if (k > " << k << ") off += (((int)A.inner + V) * " << dtype_bytes(an.accesses[st[k]].dtype) << " + 15) & ~15;\n";
+      os << "    if (k > " << k << ") off += (((int)A.inner + " << pad << ") * " << dtype_bytes(an.accesses[st[k]].dtype) << " + 15) & ~15;\n";
     os << "    (void)A; (void)k;\n    return off;\n  }\n";
     os << "  template <int V> static DISC_DEV void stage(const Args& A, char* lds, int tid, int nthreads) {\n";
     for (size_t k = 0; k < st.size(); ++k) {
       const Access& a = an.accesses[st[k]];
       os << "    {\n      " << dtype_ctype(a.dtype) << "* dst = reinterpret_cast<" << dtype_ctype(a.dtype)
-         << "*>(lds + stage_offset<V>(A, " << k << "));\n";
+         << "*>(lds + stage_offset(A, " << k << "));\n";
       os << "      const int n = (int)A.inner;\n";
-      os << "      disc::stage_copy<V>(dst, A.p" << a.slot << ", n, tid, nthreads);\n    }\n";
+      os << "      disc::stage_copy<" << pad << ">(dst, A.p" << a.slot << ", n, tid, nthreads);\n    }\n";
     }
     os << "    (void)A; (void)lds; (void)tid; (void)nthreads;\n  }\n";
   }
@@ -780,7 +783,7 @@ struct Gen {
       if (st >= 0) {
         // a compile-time choice: behind a run-time branch the wait for the operand would cover both
         // the LDS and the global counter, and so also the row loads that are in flight for later
-        o << ind << "if constexpr (STAGED) disc::ld_lds(l" << ai << ", rc.sl, stage_offset<V>(A, " << st << "), (int)col);\n";
+        o << ind << "if constexpr (STAGED) disc::ld_lds(l" << ai << ", rc.sl, stage_offset(A, " << st << "), (int)col);\n";
         o << ind << "else " << load_call(a, ai, fmt("l%d", ai), "", "") << "\n";
       } else {
         o << ind << load_call(a, ai, fmt("l%d", ai), "", "") << "\n";
@@ -1127,15 +1130,20 @@ struct Gen {
       k(name, fmt("disc::row_reg_body<Pat, %d, %d, %s>(A, rp);", v, nv, pipe), "RowPlan");
       if (staged && v > 1)
         k(name + "_s", fmt("disc::row_reg_body<PatT<true>, %d, %d, %s>(A, rp);", v, nv, pipe), "RowPlan", "PatT<true>");
-      // blocks of one wavefront quad, vector width: versions for rows that are a whole number of
-      // slots (no ragged-tail path anywhere in them), with plain accesses (_e) and with non-temporal
-      // accesses of the full-size operands (_nt), which the host picks for large launches of rows
-      // that start and end on 16-byte boundaries
+      // blocks of one wavefront quad, vector width: versions whose vector slots are all whole (no
+      // ragged-tail path anywhere in them).  _e: rows that are a whole number of slots; _nt: the
+      // same with non-temporal accesses of the full-size operands, for large launches of rows that
+      // start and end on 16-byte boundaries; _t: the elements behind the last whole slot of a row
+      // are taken one per lane as slots of ONE element (not with sums over the rows: there a
+      // lane's columns are laid out by slot).
+      const bool tail = an.n_col_sums == 0;
       if (v > 1 && max_threads <= 256) {
         k(name + "_e", fmt("disc::row_reg_body<Pat, %d, %d, %s, 0, true>(A, rp);", v, nv, pipe), "RowPlan");
+        if (tail) k(name + "_t", fmt("disc::row_reg_body<Pat, %d, %d, %s, 0, true, true>(A, rp);", v, nv, pipe), "RowPlan");
         k(name + "_nt", fmt("disc::row_reg_body<Pat, %d, %d, %s, 3, true>(A, rp);", v, nv, pipe), "RowPlan");
         if (staged) {
           k(name + "_s_e", fmt("disc::row_reg_body<PatT<true>, %d, %d, %s, 0, true>(A, rp);", v, nv, pipe), "RowPlan", "PatT<true>");
+          if (tail) k(name + "_s_t", fmt("disc::row_reg_body<PatT<true>, %d, %d, %s, 0, true, true>(A, rp);", v, nv, pipe), "RowPlan", "PatT<true>");
           k(name + "_s_nt", fmt("disc::row_reg_body<PatT<true>, %d, %d, %s, 3, true>(A, rp);", v, nv, pipe), "RowPlan", "PatT<true>");
         }
       }
@@ -1295,6 +1303,7 @@ struct Gen {
     out->has_epilogue = col_tmpl() ? has_elem_outputs() : true;
     out->n_col_sums = row_tmpl() ? an.n_col_sums : 0;
     out->n_row_reds = row_tmpl() ? an.n_row_reds : 0;
+    out->row_tail_ok = an.n_col_sums == 0;
     out->staged_elem_bytes.clear();
     for (int ai : staged_accesses()) out->staged_elem_bytes.push_back(dtype_bytes(an.accesses[ai].dtype));
     return DISC_OK;

@@ -488,13 +488,34 @@ DISC_DEV float lane_xor_f32(float v, int s) {
   return __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute((lane ^ s) << 2, __builtin_bit_cast(int, v)));
 }
 
+// The end of a row behind its last whole slot, taken as slots of ONE element by the first lanes of
+// the row (TAIL versions of the row kernels): the lane's element, what it keeps between the
+// phases, and its column (-1: this lane has none).
+template <class Pat>
+struct TailSlot {
+  typename Pat::template Slot<1> s;
+  typename Pat::template Keep<1> k;
+  int col;
+};
+struct NoTail {
+  int col;
+};
+template <class Pat, bool TAIL>
+struct TailSel {
+  typedef NoTail type;
+};
+template <class Pat>
+struct TailSel<Pat, true> {
+  typedef TailSlot<Pat> type;
+};
+
 // `after_first` runs once, after the slots have been folded into the accumulator of phase 0 and
 // before the lanes combine: the place where the caller issues the loads of the next row.
-template <class Pat, int P, int V, int NV, class Hook, class SP>
+template <class Pat, int P, int V, int NV, class Hook, class SP, class TS>
 DISC_DEV void row_phases(const typename Pat::Args& A, const RowPlan& rp, typename Pat::RowCtx& rc,
                          const typename Pat::template Slot<V> (&slot)[NV],
                          typename Pat::template Keep<V> (&keep)[NV], const SP (&span)[NV],
-                         int col0, char* lds, int& parity, Hook& after_first) {
+                         int col0, char* lds, int& parity, Hook& after_first, TS& ts) {
   if constexpr (P < Pat::NPHASE) {
     typename Pat::template Acc<P> acc;
     Pat::template acc_init<P>(acc);
@@ -502,6 +523,9 @@ DISC_DEV void row_phases(const typename Pat::Args& A, const RowPlan& rp, typenam
     for (int j = 0; j < NV; ++j) {
       const int col = col0 + j * rp.G * V;
       if (span[j].any()) Pat::template phase<P, V, true>(A, acc, slot[j], keep[j], span[j], col, rc);
+    }
+    if constexpr (!__is_same(TS, NoTail)) {
+      if (ts.col >= 0) Pat::template phase<P, 1, true>(A, acc, ts.s, ts.k, EvenSpan::upto(1), ts.col, rc);
     }
     if constexpr (P == 0) after_first();
     // lanes of one wavefront
@@ -530,14 +554,21 @@ DISC_DEV void row_phases(const typename Pat::Args& A, const RowPlan& rp, typenam
       }
     }
     Pat::template row_after<P>(A, rc, acc);
-    row_phases<Pat, P + 1, V, NV>(A, rp, rc, slot, keep, span, col0, lds, parity, after_first);
+    row_phases<Pat, P + 1, V, NV>(A, rp, rc, slot, keep, span, col0, lds, parity, after_first, ts);
   }
 }
 
 // NT: bit 0 = non-temporal loads of the full-size operands, bit 1 = non-temporal stores
-// EVEN: the host promises that the row length is a multiple of V (no ragged slot anywhere)
-template <class Pat, int V, int NV, bool PIPE = true, int NT = 0, bool EVEN = false>
+// EVEN: every vector slot is whole -- the host promises that the row length is a multiple of V, or
+// TAIL: (with EVEN) the elements behind the last whole slot of a row, inner % V of them, are taken
+//       one per lane by the lanes that hold the row's first columns, as slots of ONE element that
+//       go through the same phases, the same accumulators and the same epilogue.  Against a
+//       ragged last slot this costs one element's work in one wavefront of the row instead of a
+//       predicated pass over a whole slot in every lane of that wavefront, no access moves in
+//       pieces, and the row needs capacity for its whole slots only.  Needs G >= V lanes per row.
+template <class Pat, int V, int NV, bool PIPE = true, int NT = 0, bool EVEN = false, bool TAIL = false>
 DISC_DEV void row_reg_body(const typename Pat::Args& A, const RowPlan& rp) {
+  static_assert(!TAIL || (EVEN && Pat::NCOLSUM == 0), "single-element tails: whole vector slots, no sums over the rows");
   typedef typename SpanSel<EVEN>::type SP;
   __shared__ __attribute__((aligned(16))) char lds[2 * 16 * Pat::MAX_ACC_BYTES];
   // G <= 64: a power of two; G > 64: a multiple of 64
@@ -545,7 +576,9 @@ DISC_DEV void row_reg_body(const typename Pat::Args& A, const RowPlan& rp) {
   const int lane = (int)threadIdx.x - grp * rp.G;
   const int rpb = rp.rpb;
   const i64 rows = A.rows;
-  const int inner = (int)A.inner;
+  // the part of the row that the vector slots cover, and the number of single elements behind it
+  const int ntail = TAIL ? (int)A.inner & (V - 1) : 0;
+  const int inner = (int)A.inner - ntail;
   int parity = 0;
   const char* staged = nullptr;
   if constexpr (Pat::STAGED) {
@@ -565,10 +598,12 @@ DISC_DEV void row_reg_body(const typename Pat::Args& A, const RowPlan& rp) {
   int rot = wpr > 1 ? (int)(blockIdx.x % (unsigned)wpr) * 64 : 0;
   int col0 = lane * V;
   int nvalid[NV];
-  auto place = [&](int r, int& c0, int (&n)[NV]) {
+  int tcol = -1;                        // column of this lane's single element behind the whole slots
+  auto place = [&](int r, int& c0, int (&n)[NV], int& tc) {
     int l = lane + r;
     if (l >= rp.G) l -= rp.G;
     c0 = l * V;
+    tc = l < ntail ? inner + l : -1;
 #pragma unroll
     for (int j = 0; j < NV; ++j) {
       const int col = c0 + j * rp.G * V;
@@ -576,13 +611,15 @@ DISC_DEV void row_reg_body(const typename Pat::Args& A, const RowPlan& rp) {
       n[j] = (j < rp.nv && hi > 0) ? hi : 0;
     }
   };
-  place(rot, col0, nvalid);
+  place(rot, col0, nvalid, tcol);
   // Software pipeline over the rows of a block: the loads of the next row are issued as soon as
   // the first reduction phase has consumed the current row's slots (every load issued so far
   // has landed by then, so no wait in the rest of the iteration touches the new loads); they
   // complete behind the lane reductions, the later phases, the epilogue and the stores.
   typename Pat::RowCtx rc{};
   typename Pat::template Slot<V> slot[NV];
+  typedef typename TailSel<Pat, TAIL>::type TS;
+  TS ts, tsn;
   typename Pat::template ColAcc<V> cacc[NV]{};
   // reductions of per-row values over the rows: every lane of a lane group keeps the running values
   // of the group's rows
@@ -618,6 +655,10 @@ DISC_DEV void row_reg_body(const typename Pat::Args& A, const RowPlan& rp) {
 #pragma unroll
     for (int j = 0; j < NV; ++j)
       if (nvalid[j] > 0) Pat::template load<V, NT>(A, rc, (unsigned)(col0 + j * rp.G * V), SP::upto(nvalid[j]), slot[j]);
+    if constexpr (TAIL) {
+      ts.col = tcol;
+      if (tcol >= 0) Pat::template load<1, 0>(A, rc, (unsigned)tcol, EvenSpan::upto(1), ts.s);
+    }
   };
   // the row group of the block starts at row rw - grp_w; the block is done when that is past the end
   if (PIPE && rw - grp_w < rows) load_row();
@@ -630,7 +671,7 @@ DISC_DEV void row_reg_body(const typename Pat::Args& A, const RowPlan& rp) {
     const bool active = row < rows;
     typename Pat::RowCtx rcn{};
     typename Pat::template Slot<V> nxt[NV];
-    int col0n = col0;
+    int col0n = col0, tcoln = tcol;
     int nvalidn[NV];
 #pragma unroll
     for (int j = 0; j < NV; ++j) nvalidn[j] = nvalid[j];
@@ -638,7 +679,7 @@ DISC_DEV void row_reg_body(const typename Pat::Args& A, const RowPlan& rp) {
       if (PIPE && rw + rstep - grp_w < rows) {
         if (wpr > 1) {
           rot = rot + 64 < rp.G ? rot + 64 : 0;
-          place(rot, col0n, nvalidn);
+          place(rot, col0n, nvalidn, tcoln);
         }
         begin_row(rw + rstep, sbw + sbstep, rcn);
         rcn.sl = staged;
@@ -649,13 +690,17 @@ DISC_DEV void row_reg_body(const typename Pat::Args& A, const RowPlan& rp) {
             sn.n = nvalidn[j];
             Pat::template load<V, NT>(A, rcn, (unsigned)(col0n + j * rp.G * V), sn, nxt[j]);
           }
+        if constexpr (TAIL) {
+          tsn.col = tcoln;
+          if (tcoln >= 0) Pat::template load<1, 0>(A, rcn, (unsigned)tcoln, EvenSpan::upto(1), tsn.s);
+        }
       }
       // keep the loads here: without a fence the compiler is free to sink them below the
       // stores of this row (to save registers), which undoes the pipeline
       asm volatile("" ::: "memory");
     };
     typename Pat::template Keep<V> keep[NV];
-    row_phases<Pat, 0, V, NV>(A, rp, rc, slot, keep, span, col0, lds, parity, prefetch);
+    row_phases<Pat, 0, V, NV>(A, rp, rc, slot, keep, span, col0, lds, parity, prefetch, ts);
     if constexpr (Pat::NPHASE == 0) prefetch();   // (no reduction phase to hide the next row's loads behind)
     if constexpr (Pat::NROWRED > 0) {
       if (active) Pat::row_reds(A, rc, racc);
@@ -679,6 +724,13 @@ DISC_DEV void row_reg_body(const typename Pat::Args& A, const RowPlan& rp) {
         }
       }
     }
+    if constexpr (TAIL) {
+      if (ts.col >= 0) {
+        typename Pat::template OutSlot<1> o;
+        Pat::template epilogue<1, true>(A, rc, ts.s, ts.k, ts.col, EvenSpan::upto(1), o);
+        if (active) Pat::template store<1, 0>(A, rc, (unsigned)ts.col, EvenSpan::upto(1), o);
+      }
+    }
     if (active && lane == 0) Pat::row_store(A, row, rc);
     rw += rstep;
     sbw += sbstep;
@@ -686,14 +738,16 @@ DISC_DEV void row_reg_body(const typename Pat::Args& A, const RowPlan& rp) {
       rc = rcn;
 #pragma unroll
       for (int j = 0; j < NV; ++j) slot[j] = nxt[j];
+      if constexpr (TAIL) ts = tsn;
       if (wpr > 1) {
         col0 = col0n;
+        tcol = tcoln;
 #pragma unroll
         for (int j = 0; j < NV; ++j) nvalid[j] = nvalidn[j];
       }
     } else if (wpr > 1) {
       rot = rot + 64 < rp.G ? rot + 64 : 0;
-      place(rot, col0, nvalid);
+      place(rot, col0, nvalid, tcol);
     }
   }
   if constexpr (Pat::NCOLSUM > 0) {

@@ -217,6 +217,7 @@ struct Generated {
   int n_col_sums = 0;                 // row reduce: outputs summed over the rows (second launch combines the partial sums)
   int n_row_reds = 0;                 // row reduce: per-row values reduced over the rows to one number (last launch)
   std::vector<int> staged_elem_bytes; // row reduce: element size of each row vector that can be staged in LDS
+  bool row_tail_ok = false;           // row reduce: the versions for rows of whole slots also take a ragged end, one element per lane
   std::vector<std::string> field_names;   // member name of each args.fields entry in Pat::Args
 };
 
@@ -232,13 +233,14 @@ enum KernelId {
   K_COL_EPI2_VEC, K_COL_EPI2_VEC_NT, K_COL_EPI2_SCALAR,
   K_COMPACT_COUNT_VEC, K_COMPACT_COUNT_SCALAR, K_COMPACT_SCAN, K_COMPACT_SCATTER_VEC, K_COMPACT_SCATTER_SCALAR,
   K_ROW_BASE,
-  K_COUNT = K_ROW_BASE + 72
+  K_COUNT = K_ROW_BASE + 96
 };
-// k_row_{vec|scalar}_nv{1|2|3}[w][_s][_nt|_e]: scalar access, instantiated slots per lane, block above
+// k_row_{vec|scalar}_nv{1|2|3}[w][_s][_nt|_e|_t]: scalar access, instantiated slots per lane, block above
 // 256 threads, row vectors staged in LDS, then the access flavour: 0 = any row length, 1 (_nt) = rows
-// of whole slots with non-temporal accesses of the full-size operands, 2 (_e) = rows of whole slots
+// of whole slots with non-temporal accesses of the full-size operands, 2 (_e) = rows of whole slots,
+// 3 (_t) = whole slots + the ragged end of the row as single elements
 inline int row_kernel_index(bool scalar, int inst, bool wide, bool staged, int flavour) {
-  return ((((scalar ? 1 : 0) * 3 + (inst - 1)) * 2 + (wide ? 1 : 0)) * 2 + (staged ? 1 : 0)) * 3 + flavour;
+  return ((((scalar ? 1 : 0) * 3 + (inst - 1)) * 2 + (wide ? 1 : 0)) * 2 + (staged ? 1 : 0)) * 4 + flavour;
 }
 const char* kernel_name(int kid);            // entry-point name without the pattern prefix
 int kernel_id(const std::string& name);      // -1 when unknown (registration time only)

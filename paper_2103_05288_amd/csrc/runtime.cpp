@@ -469,7 +469,7 @@ int make_plan(disc_ctx* c, const Pattern& p, const int64_t* dims, int n_dims, in
       vec = force == DISC_V_ROW_REG_VEC || force == DISC_V_ROW_STREAM_VEC;
     }
     const int v = vec ? V : 1;
-    const int64_t spr = (sv.inner + v - 1) / v;
+    int64_t spr = (sv.inner + v - 1) / v;
     stream = spr > 1024 * (vec ? 3 : 2);
     if (force == DISC_V_ROW_STREAM_VEC || force == DISC_V_ROW_STREAM_SCALAR) stream = true;
     else if (force >= 0 && stream) return set_err(c, DISC_ERR_INVALID_ARG, "row too long for the forced register-resident version");
@@ -500,12 +500,30 @@ int make_plan(disc_ctx* c, const Pattern& p, const int64_t* dims, int n_dims, in
                                      {64, 256}, {128, 256}, {256, 256}, {512, 512}, {1024, 1024}};
       const int max_nv = vec ? 3 : 2;   // three slots: vector versions only
       int G = 1024, nv = 2, block = 1024;
-      int64_t best_cap = -1;
-      for (const Shape& s : shapes)
-        for (int k = max_nv; k >= 1; --k) {
-          const int64_t cap = (int64_t)s.G * k;
-          if (cap >= spr && (best_cap < 0 || cap < best_cap)) { best_cap = cap; G = s.G; nv = k; block = s.block; }
-        }
+      auto choose = [&](int64_t slots) {
+        int64_t best_cap = -1;
+        for (const Shape& s : shapes)
+          for (int k = max_nv; k >= 1; --k) {
+            const int64_t cap = (int64_t)s.G * k;
+            if (cap >= slots && (best_cap < 0 || cap < best_cap)) { best_cap = cap; G = s.G; nv = k; block = s.block; }
+          }
+      };
+      // A ragged end (row length not a multiple of the vector width) as single elements: the row
+      // then needs lanes for its WHOLE slots only, and the elements behind them go one each to the
+      // first lanes of the row -- in the versions for rows of whole slots, when the pattern has
+      // them for this case (no sums over the rows), the row has at least as many lanes as a slot
+      // has elements, and the block is a wavefront quad.  Otherwise the ragged end is a slot.
+      const bool tail_ok = vec && v > 1 && p.gen.row_tail_ok && sv.inner % v != 0 && sv.inner / v >= 1;
+      bool tail = false;
+      if (tail_ok) {
+        choose(sv.inner / v);
+        tail = G >= v && block <= 256;
+      }
+      if (!tail) {
+        choose(spr);
+        tail = tail_ok && G >= v && block <= 256;   // (the whole slots alone would have fitted fewer lanes than a slot has elements)
+      }
+      if (tail) spr = sv.inner / v;
       nv = (int)((spr + G - 1) / G);
       int inst = std::max(nv, 2);   // instantiated slots per lane: 2 or 3
       pub.variant = vec ? DISC_V_ROW_REG_VEC : DISC_V_ROW_REG_SCALAR;
@@ -533,9 +551,9 @@ int make_plan(disc_ctx* c, const Pattern& p, const int64_t* dims, int n_dims, in
         // (kNonTemporalMinBytes) keep the plain version: their results may be consumed from cache.
         // rows of whole slots (row length a multiple of the vector width) take the versions without
         // any ragged-tail path: _e, or _nt under the rule above
-        const bool even = vec && V > 1 && !wide_version && sv.inner % V == 0;
+        const bool even = vec && V > 1 && !wide_version && (sv.inner % V == 0 || tail);
         bool nt = false;
-        if (even && c->row_nt != 0) {
+        if (even && !tail && c->row_nt != 0) {
           nt = c->row_nt > 0;
           if (c->row_nt < 0 && sv.inner >= 128 && sv.alg_bytes >= kNonTemporalMinBytes) {
             nt = true;
@@ -549,7 +567,7 @@ int make_plan(disc_ctx* c, const Pattern& p, const int64_t* dims, int n_dims, in
             if (!whole_lines && sv.inner < 512) nt = false;
           }
         }
-        L.kid = K_ROW_BASE + row_kernel_index(!vec, inst, wide_version, stage, nt ? 1 : even ? 2 : 0);
+        L.kid = K_ROW_BASE + row_kernel_index(!vec, inst, wide_version, stage, nt ? 1 : tail ? 3 : even ? 2 : 0);
       }
       // grid-stride over row groups: a small whole number of rounds of the blocks the chip holds
       // at once.  Measured: with plenty of rows, blocks of one wavefront-quad do best with three

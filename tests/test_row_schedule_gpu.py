@@ -49,10 +49,17 @@ def check(ctx, cfg_name, dims, seed, handle=None):
 def test_every_capacity_class_and_tail(ctx, cfg_name):
     h = ctx.register(CONFIGS[cfg_name].pattern())
     seen = set()
+    suffixes = set()
     for i, H in enumerate(ROW_LENGTHS):
         T = 1 + (i * 5) % 23            # 1 .. 23 rows: every residue of rows per block shows up
         plan = check(ctx, cfg_name, [T, H], seed=100 + i, handle=h)
         seen.add((plan["variant_name"], plan["lanes_per_row"], plan["slots_per_lane"]))
+        name = plan["kernels"][0]
+        suffixes.add(name.rsplit("_", 1)[1] if name.rsplit("_", 1)[1] in ("e", "t", "nt") else "")
+        # a ragged end on at least 8 lanes in a block of 256 threads is taken as single elements (_t)
+        if plan["variant_name"] == "row_reg_vec" and plan["block"][0][0] == 256:
+            assert name.endswith("_t") == (H % 8 != 0 and plan["lanes_per_row"] >= 8), (H, name)
+    assert {"", "e", "t"} <= suffixes
     lanes = {g for v, g, n in seen if v == "row_reg_vec"}
     assert {4, 8, 16, 32, 64, 128, 256, 512, 1024} <= lanes
     assert {n for v, g, n in seen if v == "row_reg_vec"} >= {1, 2, 3}
