@@ -331,8 +331,10 @@ int disc_force_variant(disc_ctx* ctx, int variant);
 typedef enum {
   DISC_OPT_NON_TEMPORAL = 0,      /* -1 host rule (default), 0 never, 1 wherever the version exists   */
   DISC_OPT_STAGE_ROW_VECTORS = 1, /* 1 host rule (default), 0 row vectors are never staged in LDS     */
-  DISC_OPT_ROW_ROUNDS = 2         /* 0 host rule (default), n > 0: row-kernel grid = n rounds of the
+  DISC_OPT_ROW_ROUNDS = 2,        /* 0 host rule (default), n > 0: row-kernel grid = n rounds of the
                                      blocks the chip holds at once                                    */
+  DISC_OPT_ALIGN_ROW_SLOTS = 3    /* 1 host rule (default), 0: the vector slots of ragged rows are never
+                                     shifted to the 16-byte boundaries of the tensor                  */
 } disc_test_option_id;
 int disc_test_option(disc_ctx* ctx, int option, int value);
 

@@ -25,7 +25,7 @@ VARIANTS = ("loop_vec", "loop_vec_i64", "loop_scalar", "loop_scalar_i64", "row_r
             "compact_vec", "compact_scalar")
 STATUS = {0: "OK", -1: "INVALID_ARG", -2: "BAD_PATTERN", -3: "UNFUSIBLE", -4: "CONSTRAINT", -5: "WORKSPACE",
           -6: "COMPILE", -7: "HIP", -8: "SHAPE", -9: "EMPTY_REDUCE", -10: "INTERNAL"}
-TEST_OPTIONS = {"non_temporal": 0, "stage_row_vectors": 1, "row_rounds": 2}
+TEST_OPTIONS = {"non_temporal": 0, "stage_row_vectors": 1, "row_rounds": 2, "align_row_slots": 3}
 TEMPLATES = ("loop", "row_reduce", "col_reduce", "transpose", "compact")
 
 

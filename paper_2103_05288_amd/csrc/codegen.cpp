@@ -738,6 +738,15 @@ struct Gen {
     os << "    (void)a;\n  }\n";
   }
 
+  // May the vector slots of a row start at any column (the _t versions shift them to the 16-byte
+  // boundaries of the tensor)?  The copies of row vectors in LDS are then read with element
+  // alignment, which is only as fast as an aligned read for elements of 4 bytes and more.
+  bool row_shift_ok() const {
+    if (!row_tmpl() || an.n_col_sums > 0) return false;
+    for (int ai : staged_accesses())
+      if (dtype_bytes(an.accesses[ai].dtype) < 4) return false;
+    return true;
+  }
   // row-vector operands of a row reduce that can be staged in LDS, in access order
   std::vector<int> staged_accesses() const {
     std::vector<int> r;
@@ -783,7 +792,7 @@ struct Gen {
       if (st >= 0) {
         // a compile-time choice: behind a run-time branch the wait for the operand would cover both
         // the LDS and the global counter, and so also the row loads that are in flight for later
-        o << ind << "if constexpr (STAGED) disc::ld_lds(l" << ai << ", rc.sl, stage_offset(A, " << st << "), (int)col);\n";
+        o << ind << "if constexpr (STAGED) disc::ld_lds<SP::kAnyColumn && " << (row_shift_ok() ? "true" : "false") << ">(l" << ai << ", rc.sl, stage_offset(A, " << st << "), (int)col);\n";
         o << ind << "else " << load_call(a, ai, fmt("l%d", ai), "", "") << "\n";
       } else {
         o << ind << load_call(a, ai, fmt("l%d", ai), "", "") << "\n";
@@ -1304,6 +1313,7 @@ struct Gen {
     out->n_col_sums = row_tmpl() ? an.n_col_sums : 0;
     out->n_row_reds = row_tmpl() ? an.n_row_reds : 0;
     out->row_tail_ok = an.n_col_sums == 0;
+    out->row_shift_ok = row_shift_ok();
     out->staged_elem_bytes.clear();
     for (int ai : staged_accesses()) out->staged_elem_bytes.push_back(dtype_bytes(an.accesses[ai].dtype));
     return DISC_OK;

@@ -87,6 +87,7 @@ struct Vec<T, N, true> {
 // slot alive across the phases was measured slower -- they do not fit the scalar registers next
 // to the kernel arguments and were spilled to vector-register lanes on every path.
 struct Span {
+  static constexpr bool kAnyColumn = false;
   int n;
   static DISC_DEV Span upto(int n) {
     Span s;
@@ -102,6 +103,7 @@ struct Span {
 // knows -- every ragged-tail path (predicated bodies, piecewise loads and stores, the wave-wide
 // "all full?" vote) drops out of the kernel versions built on it.
 struct EvenSpan {
+  static constexpr bool kAnyColumn = false;
   int n;
   static DISC_DEV EvenSpan upto(int n) {
     EvenSpan s;
@@ -444,14 +446,28 @@ DISC_DEV void kloop_body(const typename Pat::Args& A) {
 // back.  Within a wavefront partial results are combined with xor-shuffles; across the
 // wavefronts of a row through a double-buffered LDS exchange (one barrier per phase).
 // =======================================================================================
-template <bool EVEN> struct SpanSel { typedef Span type; };
-template <> struct SpanSel<true> { typedef EvenSpan type; };
+// The span of a slot in the kernel versions that take the ragged ends of a row as single elements:
+// whole like EvenSpan, but the slot may start at ANY column (the vector slots of a row may be
+// shifted to 16-byte boundaries of memory, and single elements sit anywhere), so copies of row
+// vectors in LDS are read with element alignment only.
+struct TailSpan : EvenSpan {
+  static constexpr bool kAnyColumn = true;
+  static DISC_DEV TailSpan upto(int n) {
+    TailSpan s;
+    s.n = n;
+    return s;
+  }
+};
+template <bool EVEN, bool TAIL = false> struct SpanSel { typedef Span type; };
+template <> struct SpanSel<true, false> { typedef EvenSpan type; };
+template <> struct SpanSel<true, true> { typedef TailSpan type; };
 struct RowPlan {
   int G;        // lanes per row: a power of two <= 64, or a multiple of 64 (whole wavefronts)
   int log2G;    // meaningful for G <= 64
   int nv;       // slots per lane actually needed at this shape (<= NV of the instantiation)
   int flags;    // bit 0: the launched kernel is the version that stages row-vector operands in LDS
-                // bit 1: the slot grid is not turned from row to row (experiments)
+                // bit 1: the slot grid is not turned from row to row
+                // bit 2: (_t versions) vector slots on the V-element boundaries of the tensor
   int rpb;      // rows per block = blockDim.x / G
 };
 
@@ -472,10 +488,13 @@ DISC_DEV void stage_copy(T* dst, const T* __restrict__ src, int n, int tid, int 
   for (int i = nvec * E + tid; i < n + PAD; i += nthreads) dst[i] = i < n ? src[i] : T(0);
 }
 
-// each staged operand is stored as [inner elements | N zeros]; col is a multiple of N
-template <class T, int N>
+// each staged operand is stored as [inner elements | zeros]; col is a multiple of N, or (ANY) any
+// column, read with element alignment
+template <bool ANY = false, class T, int N>
 DISC_DEV void ld_lds(Vec<T, N>& d, const char* base, int byte_off, int col) {
-  d.v = *reinterpret_cast<const typename Vec<T, N>::vec_t*>(base + byte_off + col * (int)sizeof(T));
+  const char* q = base + byte_off + col * (int)sizeof(T);
+  if constexpr (ANY) d.v = *reinterpret_cast<const typename Vec<T, N>::unaligned_t*>(q);
+  else d.v = *reinterpret_cast<const typename Vec<T, N>::vec_t*>(q);
 }
 
 // Sums over the rows carried along by a row reduce (Pat::NCOLSUM of them): every lane adds the
@@ -525,7 +544,7 @@ DISC_DEV void row_phases(const typename Pat::Args& A, const RowPlan& rp, typenam
       if (span[j].any()) Pat::template phase<P, V, true>(A, acc, slot[j], keep[j], span[j], col, rc);
     }
     if constexpr (!__is_same(TS, NoTail)) {
-      if (ts.col >= 0) Pat::template phase<P, 1, true>(A, acc, ts.s, ts.k, EvenSpan::upto(1), ts.col, rc);
+      if (ts.col >= 0) Pat::template phase<P, 1, true>(A, acc, ts.s, ts.k, TailSpan::upto(1), ts.col, rc);
     }
     if constexpr (P == 0) after_first();
     // lanes of one wavefront
@@ -569,16 +588,14 @@ DISC_DEV void row_phases(const typename Pat::Args& A, const RowPlan& rp, typenam
 template <class Pat, int V, int NV, bool PIPE = true, int NT = 0, bool EVEN = false, bool TAIL = false>
 DISC_DEV void row_reg_body(const typename Pat::Args& A, const RowPlan& rp) {
   static_assert(!TAIL || (EVEN && Pat::NCOLSUM == 0), "single-element tails: whole vector slots, no sums over the rows");
-  typedef typename SpanSel<EVEN>::type SP;
+  typedef typename SpanSel<EVEN, TAIL>::type SP;
   __shared__ __attribute__((aligned(16))) char lds[2 * 16 * Pat::MAX_ACC_BYTES];
   // G <= 64: a power of two; G > 64: a multiple of 64
   const int grp = rp.G <= 64 ? (int)threadIdx.x >> rp.log2G : ((int)threadIdx.x >> 6) / (rp.G >> 6);
   const int lane = (int)threadIdx.x - grp * rp.G;
   const int rpb = rp.rpb;
   const i64 rows = A.rows;
-  // the part of the row that the vector slots cover, and the number of single elements behind it
-  const int ntail = TAIL ? (int)A.inner & (V - 1) : 0;
-  const int inner = (int)A.inner - ntail;
+  const int inner = (int)A.inner;
   int parity = 0;
   const char* staged = nullptr;
   if constexpr (Pat::STAGED) {
@@ -596,19 +613,53 @@ DISC_DEV void row_reg_body(const typename Pat::Args& A, const RowPlan& rp) {
   // (a lane that sums its columns over the rows keeps its columns: no turning then)
   const int wpr = (Pat::NCOLSUM == 0 && rp.G > 64 && !(rp.flags & 2)) ? rp.G >> 6 : 1;   // flags bit 1: grid not turned (experiments)
   int rot = wpr > 1 ? (int)(blockIdx.x % (unsigned)wpr) * 64 : 0;
+  // Row bookkeeping in scalar registers: rw = row of the first lane group of this wavefront in
+  // the current row group, sbw = its element offset; both advance by a constant per iteration
+  // (no 64-bit products in the loop).  A lane's row is rw + dgrp.
+  const int grp_w = __builtin_amdgcn_readfirstlane(grp);
+  const int dgrp = grp - grp_w;
+  const i64 rstep = (i64)gridDim.x * rpb;
+  const i64 sbstep = rstep * A.inner;
+  i64 rw = (i64)blockIdx.x * rpb + grp_w;
+  i64 sbw = rw * A.inner;
+  // TAIL versions, flags bit 2: the vector slots of a row are shifted to the V-element boundaries
+  // of the TENSOR (row * inner + column a multiple of V), so that every wide access of a full-size
+  // operand whose base is aligned is aligned itself, whatever the row length: the `head` elements
+  // in front of the first boundary are single elements like those behind the last whole slot.
+  // The host launches a grid that puts rows of equal alignment on a lane group (the distance
+  // between its rows times the row length is a multiple of V), so `head` is worked out once.  It is
+  // an alignment matter only: any value 0 .. V-1 addresses the row correctly.
+  int head = 0;
+  if constexpr (TAIL) {
+    if (rp.flags & 4) {
+      const i64 r = rw + dgrp < rows ? rw + dgrp : rows - 1;
+      const int e0 = (int)(((r & (V - 1)) * (i64)(inner & (V - 1))) & (V - 1));   // (row * inner) mod V
+      head = (V - e0) & (V - 1);
+    }
+  }
   int col0 = lane * V;
   int nvalid[NV];
-  int tcol = -1;                        // column of this lane's single element behind the whole slots
+  int tcol = -1;                        // column of this lane's single element (TAIL versions), -1: none
   auto place = [&](int r, int& c0, int (&n)[NV], int& tc) {
     int l = lane + r;
     if (l >= rp.G) l -= rp.G;
-    c0 = l * V;
-    tc = l < ntail ? inner + l : -1;
+    if constexpr (TAIL) {
+      // [head single elements | whole slots | single elements behind them]
+      const int whole = (inner - head) / V;
+      const int behind = head + whole * V;         // first column behind the whole slots
+      c0 = head + l * V;
 #pragma unroll
-    for (int j = 0; j < NV; ++j) {
-      const int col = c0 + j * rp.G * V;
-      const int hi = inner - col > V ? V : inner - col;
-      n[j] = (j < rp.nv && hi > 0) ? hi : 0;
+      for (int j = 0; j < NV; ++j) n[j] = (j < rp.nv && l + j * rp.G < whole) ? V : 0;
+      tc = l < head ? (l < inner ? l : -1) : (behind + (l - head) < inner ? behind + (l - head) : -1);
+    } else {
+      c0 = l * V;
+      tc = -1;
+#pragma unroll
+      for (int j = 0; j < NV; ++j) {
+        const int col = c0 + j * rp.G * V;
+        const int hi = inner - col > V ? V : inner - col;
+        n[j] = (j < rp.nv && hi > 0) ? hi : 0;
+      }
     }
   };
   place(rot, col0, nvalid, tcol);
@@ -628,15 +679,6 @@ DISC_DEV void row_reg_body(const typename Pat::Args& A, const RowPlan& rp) {
 #pragma unroll
     for (int q = 0; q < Pat::NROWRED; ++q) racc[q] = Pat::rr_identity(q);
   }
-  // Row bookkeeping in scalar registers: rw = row of the first lane group of this wavefront in
-  // the current row group, sbw = its element offset; both advance by a constant per iteration
-  // (no 64-bit products in the loop).  A lane's row is rw + dgrp.
-  const int grp_w = __builtin_amdgcn_readfirstlane(grp);
-  const int dgrp = grp - grp_w;
-  const i64 rstep = (i64)gridDim.x * rpb;
-  const i64 sbstep = rstep * A.inner;
-  i64 rw = (i64)blockIdx.x * rpb + grp_w;
-  i64 sbw = rw * A.inner;
   // rows past the end (last row group only) are replaced by the last row; their lanes compute
   // along and store nothing
   auto begin_row = [&](i64 rwv, i64 sbv, typename Pat::RowCtx& c) {
@@ -657,7 +699,7 @@ DISC_DEV void row_reg_body(const typename Pat::Args& A, const RowPlan& rp) {
       if (nvalid[j] > 0) Pat::template load<V, NT>(A, rc, (unsigned)(col0 + j * rp.G * V), SP::upto(nvalid[j]), slot[j]);
     if constexpr (TAIL) {
       ts.col = tcol;
-      if (tcol >= 0) Pat::template load<1, 0>(A, rc, (unsigned)tcol, EvenSpan::upto(1), ts.s);
+      if (tcol >= 0) Pat::template load<1, 0>(A, rc, (unsigned)tcol, TailSpan::upto(1), ts.s);
     }
   };
   // the row group of the block starts at row rw - grp_w; the block is done when that is past the end
@@ -692,7 +734,7 @@ DISC_DEV void row_reg_body(const typename Pat::Args& A, const RowPlan& rp) {
           }
         if constexpr (TAIL) {
           tsn.col = tcoln;
-          if (tcoln >= 0) Pat::template load<1, 0>(A, rcn, (unsigned)tcoln, EvenSpan::upto(1), tsn.s);
+          if (tcoln >= 0) Pat::template load<1, 0>(A, rcn, (unsigned)tcoln, TailSpan::upto(1), tsn.s);
         }
       }
       // keep the loads here: without a fence the compiler is free to sink them below the
@@ -727,8 +769,8 @@ DISC_DEV void row_reg_body(const typename Pat::Args& A, const RowPlan& rp) {
     if constexpr (TAIL) {
       if (ts.col >= 0) {
         typename Pat::template OutSlot<1> o;
-        Pat::template epilogue<1, true>(A, rc, ts.s, ts.k, ts.col, EvenSpan::upto(1), o);
-        if (active) Pat::template store<1, 0>(A, rc, (unsigned)ts.col, EvenSpan::upto(1), o);
+        Pat::template epilogue<1, true>(A, rc, ts.s, ts.k, ts.col, TailSpan::upto(1), o);
+        if (active) Pat::template store<1, 0>(A, rc, (unsigned)ts.col, TailSpan::upto(1), o);
       }
     }
     if (active && lane == 0) Pat::row_store(A, row, rc);

@@ -217,7 +217,8 @@ struct Generated {
   int n_col_sums = 0;                 // row reduce: outputs summed over the rows (second launch combines the partial sums)
   int n_row_reds = 0;                 // row reduce: per-row values reduced over the rows to one number (last launch)
   std::vector<int> staged_elem_bytes; // row reduce: element size of each row vector that can be staged in LDS
-  bool row_tail_ok = false;           // row reduce: the versions for rows of whole slots also take a ragged end, one element per lane
+  bool row_tail_ok = false;           // row reduce: there are versions that take a ragged end of a row as single elements (_t)
+  bool row_shift_ok = false;          // ... and their vector slots may be shifted to the 16-byte boundaries of the tensor
   std::vector<std::string> field_names;   // member name of each args.fields entry in Pat::Args
 };
 

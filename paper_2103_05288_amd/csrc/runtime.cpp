@@ -13,6 +13,7 @@
 #include <cstring>
 #include <functional>
 #include <memory>
+#include <numeric>
 #include <set>
 #include <sstream>
 
@@ -141,6 +142,7 @@ struct disc_ctx {
   int row_nt = -1;           // non-temporal versions: -1 = host rule, 0 = never, 1 = wherever the version exists
   int row_rounds = 0;        // row kernels: grid = this many rounds of resident blocks (0: host rule)
   int row_stage = 1;         // 0: row vectors are never staged in LDS
+  int row_shift = 1;         // 0: vector slots of ragged rows are never shifted to the tensor's 16-byte boundaries
 };
 constexpr int kGridMult = 8;     // loop / column kernels: grid capped at this many blocks per CU
 constexpr int kLoopUnroll = 4;   // loop kernels: slots in flight per lane
@@ -525,6 +527,26 @@ int make_plan(disc_ctx* c, const Pattern& p, const int64_t* dims, int n_dims, in
       }
       if (tail) spr = sv.inner / v;
       nv = (int)((spr + G - 1) / G);
+      // Vector slots on the 16-byte boundaries of the tensor (the elements of a row in front of the
+      // first boundary become single elements too): when the bases of the full-size operands are
+      // aligned to a slot, the row has lanes for up to 2 (V - 1) single elements, and the grid can
+      // be cut so that a lane group only meets rows of one alignment (see below).
+      // Measured (rows of 2047 .. 4104 bf16 elements, plain accesses): rows that start on dword
+      // boundaries run as fast unshifted as rows of whole 16-byte slots (5.14-5.20 against 5.15
+      // TB/s) and lose 1-6 % when shifted (more single elements); rows that start off a dword
+      // boundary (odd lengths of 2-byte elements) run at 4.90 unshifted and 4.95-5.01 shifted.
+      // So the shift is for rows that start off dword boundaries only.
+      bool shift = tail && p.gen.row_shift_ok && G >= 2 * v - 2 && c->row_shift != 0;
+      if (shift) {
+        bool off_dword = false;
+        for (const Access& a : an.accesses) {
+          if (a.kind != ACC_FULL || a.src_value >= 0) continue;
+          const void* ptr = a.is_output ? (outputs ? outputs[a.slot] : nullptr) : (inputs ? inputs[a.slot] : nullptr);
+          if (reinterpret_cast<uintptr_t>(ptr) % (uintptr_t)(v * dtype_bytes(a.dtype)) != 0) shift = false;
+          if (dtype_bytes(a.dtype) >= 2 && (sv.inner * dtype_bytes(a.dtype)) % 4 != 0) off_dword = true;
+        }
+        shift = shift && off_dword;
+      }
       int inst = std::max(nv, 2);   // instantiated slots per lane: 2 or 3
       pub.variant = vec ? DISC_V_ROW_REG_VEC : DISC_V_ROW_REG_SCALAR;
       L.block = (uint32_t)block;
@@ -587,7 +609,16 @@ int make_plan(disc_ctx* c, const Pattern& p, const int64_t* dims, int n_dims, in
       // dword -- half of the blocks would run ~20 % slower all the time and set the kernel's time
       // (measured: +14-18 % on 4095- and 5739-wide rows).  With an odd grid every block walks
       // through all alignments of its rows, whatever the rows per block.
-      if (grid > 2 && grid % 2 == 0 && grid < ngroups) grid -= 1;
+      if (shift) {
+        // rows of one alignment per lane group: (distance between its rows) x (row length) must be a
+        // multiple of the vector width
+        int64_t m = v / std::gcd<int64_t>(sv.inner % v, v);
+        m /= std::gcd<int64_t>(m, rpb);
+        if (grid >= m) grid -= grid % m;
+        else shift = false;
+      }
+      if (shift) L.rp.flags |= 4;
+      else if (grid > 2 && grid % 2 == 0 && grid < ngroups) grid -= 1;
       L.grid[0] = (uint32_t)grid;
       // rows of partial sums: one per block of 256 threads, one per lane group of a wider block
       fp->aux[0] = grid * (L.block <= 256 ? 1 : (int64_t)L.block / std::max(G, 64));
@@ -1277,6 +1308,7 @@ int disc_test_option(disc_ctx* ctx, int option, int value) {
     case DISC_OPT_NON_TEMPORAL: ctx->row_nt = value < 0 ? -1 : value > 0 ? 1 : 0; return DISC_OK;
     case DISC_OPT_STAGE_ROW_VECTORS: ctx->row_stage = value != 0; return DISC_OK;
     case DISC_OPT_ROW_ROUNDS: ctx->row_rounds = std::max(0, value); return DISC_OK;
+    case DISC_OPT_ALIGN_ROW_SLOTS: ctx->row_shift = value != 0; return DISC_OK;
     default: return set_err(ctx, DISC_ERR_INVALID_ARG, "unknown option");
   }
   DISC_CATCH(ctx)

@@ -298,6 +298,30 @@ def test_row_schedule_capacity_steps(handles):
     assert p["slots_per_lane"] <= 2 and not p["kernels"][0].endswith("_s")
 
 
+def test_aligned_slots_of_ragged_rows_plan(handles):
+    """Ragged rows in the versions that take the row's ends as single elements (_t): when the rows
+    start off dword boundaries (odd lengths of 2-byte elements), with aligned bases and at least 14
+    lanes per row, the vector slots are put on the tensor's 16-byte boundaries,
+    which needs a grid that gives a lane group rows of one alignment only -- (grid x rows per block x
+    row length) a multiple of the vector width.  Otherwise the grid stays odd, so that every block
+    meets all alignments."""
+    h4 = handles["C4"]
+    for H in (513, 1023, 1026, 1100, 2047, 4095, 5739, 6145):
+        T = (200 << 20) // H
+        p = h4.plan([T, H])
+        assert p["kernels"][0].endswith("_t"), (H, p["kernels"])
+        rpb = p["block"][0][0] // p["lanes_per_row"]
+        if H % 2 == 1:        # rows of bf16 elements that start off dword boundaries: shifted
+            assert (p["grid"][0][0] * rpb * H) % 8 == 0, (H, p["grid"])
+        else:                 # dword-aligned rows run at full rate as they are
+            assert p["grid"][0][0] % 2 == 1, (H, p["grid"])
+        q = h4.plan([T, H], inputs=[4098, 4096, 4096, 4096], outputs=[4096])      # one base off a slot boundary
+        assert q["kernels"][0].endswith("_t") and q["grid"][0][0] % 2 == 1, (H, q["grid"])
+    # too few rows for such a grid: the plain _t launch
+    p = h4.plan([5, 5739])
+    assert p["kernels"][0].endswith("_t") and p["grid"][0][0] == 5
+
+
 def test_single_shape_registration(ctx, handles):
     """The same op list compiled for one shape: a pattern of its own per shape, only that shape's kernel
     versions in the module, its extents and launch plan as constants; other dims are refused."""
