@@ -281,3 +281,38 @@ def test_odd_rows_of_two_byte_elements_any_base_alignment():
                     assert_close(got[4], want[4], what + " out4")
         finally:
             c.close()
+
+
+def test_single_element_ends_in_fp32_and_f16_patterns(ctx):
+    """The versions that take the ragged ends of a row as single elements, at other vector widths
+    than the benchmark patterns': an fp32 softmax (4 elements per slot, up to 3 single elements at
+    either end -- fp32 rows always start on dword boundaries, so they are never shifted) and an f16
+    one with a row-group mask (8 per slot; odd rows are shifted), at seeded random row lengths."""
+    rng = np.random.default_rng(23)
+    for dt, tdt in (("f32", torch.float32), ("f16", torch.float16)):
+        pb = PatternBuilder("softmax_" + dt)
+        B, S, H = pb.dims(3)
+        x = pb.param(dt, [B, S, H])
+        m = pb.param(dt, [B, pb.static(1), H])
+        v = pb.op("add", pb.cast(x, "f32"), pb.cast(pb.broadcast(m, [B, S, H], [0, 1, 2]), "f32"))
+        mx = pb.reduce("max", v, 2)
+        e = pb.op("exp", pb.op("sub", v, pb.broadcast(mx, [B, S, H], [0, 1])))
+        s = pb.reduce("sum", e, 2)
+        pb.output(pb.cast(pb.op("div", e, pb.broadcast(s, [B, S, H], [0, 1])), dt))
+        pb.output(mx)
+        pat = pb.build()
+        h = ctx.register(pat)
+        seen_t = 0
+        for _ in range(14):
+            Hh = int(rng.integers(33, 3000))
+            Bb, Ss = int(rng.integers(1, 4)), int(rng.integers(1, 300))
+            dims = [Bb, Ss, Hh]
+            xs = torch.from_numpy(rng.standard_normal((Bb, Ss, Hh)).astype(np.float32)).to(tdt)
+            ms = torch.from_numpy((rng.random((Bb, 1, Hh)) < 0.2).astype(np.float32) * -50.0).to(tdt)
+            got = run_gpu(h, pat, dims, [xs, ms])
+            want = oracle_run(pat, dims, [to_oracle_input(xs), to_oracle_input(ms)])[0]
+            plan = h.plan(dims)
+            seen_t += plan["kernels"][0].endswith("_t")
+            for k, (g, w) in enumerate(zip(got, want)):
+                assert_close(g, w, f"softmax {dt} dims={dims} out{k} kernel={plan['kernels'][0]}")
+        assert seen_t >= 5
