@@ -105,6 +105,9 @@ struct GraphGroup {
   int pattern_id = -1;
   std::vector<int> in_values;    // graph value ids bound to the pattern's PARAMs, in order
   std::vector<int> out_values;   // graph value ids produced by the pattern's OUTPUTs, in order
+  // where each of those values lives at launch, resolved at registration: (kind, index) with kind
+  // 0 = graph input, 1 = graph output, 2 = planned buffer
+  std::vector<std::pair<int, int>> in_place, out_place;
 };
 struct GraphIntermediate {
   int value = -1;                // produced by group `first`, last read by group `last`
@@ -1563,15 +1566,15 @@ Graph* get_graph(disc_ctx* ctx, int32_t id) {
 }
 
 // byte offset of every buffer and of the shared pattern-workspace region for one set of dims
-int graph_layout(disc_ctx* ctx, const Graph& g, const int64_t* dims, int n_dims, std::vector<size_t>* buf_off,
+// buf_off: room for one offset per buffer (at most DISC_MAX_OPS)
+int graph_layout(disc_ctx* ctx, const Graph& g, const int64_t* dims, int n_dims, size_t* buf_off,
                  size_t* pattern_ws_off, size_t* total) {
   if (!dims || n_dims != g.n_sym) return set_err(ctx, DISC_ERR_INVALID_ARG, "wrong number of dims for this graph");
   for (int i = 0; i < n_dims; ++i)
     if (dims[i] < 0) return set_err(ctx, DISC_ERR_SHAPE, "negative dim");
   size_t off = 0;
-  buf_off->assign(g.buffer_value.size(), 0);
   for (size_t b = 0; b < g.buffer_value.size(); ++b) {
-    (*buf_off)[b] = off;
+    buf_off[b] = off;
     int64_t bytes = 0;
     if (!value_bytes(g, g.buffer_value[b], dims, &bytes) || off + (size_t)bytes + 256 < off)
       return set_err(ctx, DISC_ERR_SHAPE, "buffer size overflows");
@@ -1893,6 +1896,27 @@ int disc_register_graph(disc_ctx* ctx, const disc_op* ops, int n_ops, const disc
       it.buffer = pick;
     }
   }
+  // the launch path looks nothing up: every operand of every pattern gets its place now
+  for (auto& gr : g->groups) {
+    auto place_of = [&](int v) -> std::pair<int, int> {
+      auto pi = g->param_index.find(v);
+      if (pi != g->param_index.end()) return {0, pi->second};
+      auto oi = g->output_index.find(v);
+      if (oi != g->output_index.end()) return {1, oi->second};
+      auto it = g->inter_of_value.find(v);
+      if (it != g->inter_of_value.end()) return {2, g->inter[it->second].buffer};
+      return {-1, 0};
+    };
+    for (int v : gr.in_values) gr.in_place.push_back(place_of(v));
+    for (int v : gr.out_values) gr.out_place.push_back(place_of(v));
+    for (const auto& pl : gr.in_place)
+      if (pl.first < 0) return set_err(ctx, DISC_ERR_INTERNAL, "a value of the graph has no place");
+    for (const auto& pl : gr.out_place)
+      if (pl.first < 0) return set_err(ctx, DISC_ERR_INTERNAL, "a value of the graph has no place");
+    if (gr.in_place.size() > (size_t)DISC_MAX_OPS || gr.out_place.size() > (size_t)DISC_MAX_OPS)
+      return set_err(ctx, DISC_ERR_BAD_PATTERN, "too many operands in one pattern of the graph");
+  }
+  if (g->buffer_value.size() > (size_t)DISC_MAX_OPS) return set_err(ctx, DISC_ERR_BAD_PATTERN, "too many buffers");
   const int id = (int)ctx->graphs.size();
   ctx->graphs.push_back(std::move(g));
   *graph_id_out = id;
@@ -1924,9 +1948,9 @@ int disc_graph_workspace_bytes(disc_ctx* ctx, int32_t id, const int64_t* dims, i
   DISC_TRY
   Graph* g = get_graph(ctx, id);
   if (!g || !out) return set_err(ctx, DISC_ERR_INVALID_ARG, "bad graph id or null output");
-  std::vector<size_t> off;
+  size_t off[DISC_MAX_OPS];
   size_t pws = 0;
-  return graph_layout(ctx, *g, dims, n_dims, &off, &pws, out);
+  return graph_layout(ctx, *g, dims, n_dims, off, &pws, out);
   DISC_CATCH(ctx)
 }
 
@@ -1937,35 +1961,31 @@ int disc_graph_launch(disc_ctx* ctx, int32_t id, const int64_t* dims, int n_dims
   if (!g) return set_err(ctx, DISC_ERR_INVALID_ARG, "bad graph id");
   if (n_in != g->n_inputs || n_out != g->n_outputs) return set_err(ctx, DISC_ERR_INVALID_ARG, "wrong number of inputs or outputs");
   if ((n_in > 0 && !inputs) || !outputs) return set_err(ctx, DISC_ERR_INVALID_ARG, "null pointer array");
-  std::vector<size_t> off;
+  // nothing is allocated and nothing looked up here: offsets and pointer arrays live on the stack,
+  // the place of every operand was resolved at registration
+  size_t off[DISC_MAX_OPS];
   size_t pws = 0, total = 0;
-  int rc = graph_layout(ctx, *g, dims, n_dims, &off, &pws, &total);
+  int rc = graph_layout(ctx, *g, dims, n_dims, off, &pws, &total);
   if (rc) return rc;
   if (total > 0 && (!workspace || workspace_bytes < total)) return set_err(ctx, DISC_ERR_WORKSPACE, "workspace missing or too small");
   char* ws = static_cast<char*>(workspace);
-  auto where = [&](int v) -> void* {
-    auto p = g->param_index.find(v);
-    if (p != g->param_index.end()) return const_cast<void*>(inputs[p->second]);
-    auto o = g->output_index.find(v);
-    if (o != g->output_index.end()) return outputs[o->second];
-    auto it = g->inter_of_value.find(v);
-    if (it == g->inter_of_value.end()) return nullptr;      // cannot happen for a registered graph
-    return ws + off[g->inter[it->second].buffer];
+  const void* in[DISC_MAX_OPS];
+  void* outp[DISC_MAX_OPS];
+  auto where = [&](const std::pair<int, int>& pl) -> void* {
+    return pl.first == 0 ? const_cast<void*>(inputs[pl.second]) : pl.first == 1 ? outputs[pl.second] : ws + off[pl.second];
   };
-  std::vector<const void*> in;
-  std::vector<void*> outp;
   for (const auto& gr : g->groups) {
-    in.clear();
-    outp.clear();
-    for (int v : gr.in_values) in.push_back(where(v));
-    for (int v : gr.out_values) outp.push_back(where(v));
-    for (const void* q : in)
-      if (!q) return set_err(ctx, DISC_ERR_INVALID_ARG, "null input pointer (or a value of the graph without a place)");
-    for (void* q : outp)
-      if (!q) return set_err(ctx, DISC_ERR_INVALID_ARG, "null output pointer (or a value of the graph without a place)");
+    const int ni = (int)gr.in_place.size(), no = (int)gr.out_place.size();
+    for (int k = 0; k < ni; ++k) {
+      in[k] = where(gr.in_place[k]);
+      if (!in[k]) return set_err(ctx, DISC_ERR_INVALID_ARG, "null input pointer");
+    }
+    for (int k = 0; k < no; ++k) {
+      outp[k] = where(gr.out_place[k]);
+      if (!outp[k]) return set_err(ctx, DISC_ERR_INVALID_ARG, "null output pointer");
+    }
     const int ns = ctx->patterns[gr.pattern_id]->an.n_sym;
-    rc = disc_launch(ctx, gr.pattern_id, dims, ns, in.data(), (int)in.size(), outp.data(), (int)outp.size(),
-                     ws ? ws + pws : nullptr, total - pws, hip_stream);
+    rc = disc_launch(ctx, gr.pattern_id, dims, ns, in, ni, outp, no, ws ? ws + pws : nullptr, total - pws, hip_stream);
     if (rc) return rc;
   }
   return DISC_OK;
