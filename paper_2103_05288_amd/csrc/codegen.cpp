@@ -1156,6 +1156,12 @@ struct Gen {
           k(name + "_s_nt", fmt("disc::row_reg_body<PatT<true>, %d, %d, %s, 3, true>(A, rp);", v, nv, pipe), "RowPlan", "PatT<true>");
         }
       }
+      // blocks above 256 threads: the _t version of the two-slot kernel only (the three-slot one
+      // has no registers to spare under its 128-register cap)
+      if (v > 1 && max_threads > 256 && nv == 2 && tail) {
+        k(name + "_t", fmt("disc::row_reg_body<Pat, %d, %d, %s, 0, true, true>(A, rp);", v, nv, pipe), "RowPlan");
+        if (staged) k(name + "_s_t", fmt("disc::row_reg_body<PatT<true>, %d, %d, %s, 0, true, true>(A, rp);", v, nv, pipe), "RowPlan", "PatT<true>");
+      }
     };
     if (an.tmpl == DISC_TEMPLATE_COMPACT) {
       k("k_compact_count_vec", fmt("disc::compact_count_body<Pat, %d>(A);", V), nullptr);

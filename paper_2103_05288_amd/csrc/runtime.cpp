@@ -520,13 +520,15 @@ int make_plan(disc_ctx* c, const Pattern& p, const int64_t* dims, int n_dims, in
       // has elements, and the block is a wavefront quad.  Otherwise the ragged end is a slot.
       const bool tail_ok = vec && v > 1 && p.gen.row_tail_ok && sv.inner % v != 0 && sv.inner / v >= 1;
       bool tail = false;
+      // (blocks above 256 threads have such a version for two slots per lane only)
+      auto tail_fits = [&](int64_t slots) { return G >= v && (block <= 256 || (slots + G - 1) / G <= 2); };
       if (tail_ok) {
         choose(sv.inner / v);
-        tail = G >= v && block <= 256;
+        tail = tail_fits(sv.inner / v);
       }
       if (!tail) {
         choose(spr);
-        tail = tail_ok && G >= v && block <= 256;   // (the whole slots alone would have fitted fewer lanes than a slot has elements)
+        tail = tail_ok && tail_fits(sv.inner / v);   // (the whole slots alone would have fitted fewer lanes than a slot has elements)
       }
       if (tail) spr = sv.inner / v;
       nv = (int)((spr + G - 1) / G);

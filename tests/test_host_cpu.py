@@ -267,19 +267,20 @@ def test_row_schedule_capacity_steps(handles):
         1024: (64, 2, 256), 1100: (64, 3, 256), 1537: (64, 3, 256), 1543: (64, 3, 256), 1545: (128, 2, 256),
         3000: (128, 3, 256), 4096: (256, 2, 256), 5739: (256, 3, 256), 6145: (256, 3, 256), 6151: (256, 3, 256),
         6153: (512, 2, 512), 8192: (512, 2, 512),
-        8200: (512, 3, 512), 12289: (1024, 2, 1024), 16385: (1024, 3, 1024), 24576: (1024, 3, 1024),
+        8200: (512, 3, 512), 12289: (1024, 2, 1024), 16385: (1024, 2, 1024), 16393: (1024, 3, 1024), 24576: (1024, 3, 1024),
     }
     for H, (G, nv, block) in cases.items():
         p = h.plan([50, H])
         assert (p["lanes_per_row"], p["slots_per_lane"], p["block"][0][0]) == (G, nv, block), (H, p)
-        tail = H % 8 != 0 and G >= 8 and block == 256 and G * nv * 8 >= H - H % 8 and p["kernels"][0].endswith("_t")
+        tail = H % 8 != 0 and G >= 8 and (block == 256 or nv <= 2) and G * nv * 8 >= H - H % 8 and p["kernels"][0].endswith("_t")
         assert G * nv * 8 >= (H - H % 8 if tail else H)
         want = "k_row_vec_nv%d%s" % (max(nv, 2 if block > 256 else 1), "w" if block > 256 else "")
         name = p["kernels"][0]
         assert not name.endswith("_nt")                       # a small launch: its result may be wanted from cache
         # rows in blocks of 256 threads take a version without ragged-tail paths: _e when they are
         # whole slots, _t (whole slots + single elements) when they have at least 8 lanes
-        even = "" if block != 256 else "_e" if H % 8 == 0 else "_t" if G >= 8 else ""
+        # (blocks above 256 threads: a _t version of the two-slot kernel only)
+        even = ("_t" if H % 8 != 0 and nv <= 2 else "") if block != 256 else "_e" if H % 8 == 0 else "_t" if G >= 8 else ""
         assert name.endswith(want + "_s" + even) or name.endswith(want + even), (H, p["kernels"])
         # the non-temporal version: launches of 64 MiB or more whose rows start and end on 16-byte
         # boundaries, 128 elements or more, blocks of 256 threads
